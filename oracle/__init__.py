@@ -1,0 +1,202 @@
+"""ctypes front-end of the CPU oracle (``kge_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the benchmark's
+``cpu_baseline`` leg.  The product package never imports this module, and this module never
+imports the product package.  All arithmetic lives in the C file; this wrapper only marshals
+numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kge_oracle.c")
+_LIB = os.path.join(_HERE, "libkge_oracle.so")
+
+SCORERS = {"transe": 0, "transh": 1, "rotate": 2, "distmult": 3, "complex": 4}
+LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, no fast-math, no contraction, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_score_one.restype = C.c_double
+        _lib.orc_loss_one.restype = C.c_double
+        _lib.orc_loss_bwd.restype = C.c_double
+        _lib.orc_bf16_rne.restype = C.c_uint16
+    return _lib
+
+
+def _p(a, ctype):
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _f32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _sid(scorer):
+    return SCORERS[scorer] if isinstance(scorer, str) else int(scorer)
+
+
+def _lid(loss):
+    return LOSSES[loss] if isinstance(loss, str) else int(loss)
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops of the oracle will use."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        try:
+            return max(1, int(env.split(",")[0]))
+        except ValueError:
+            pass
+    return os.cpu_count() or 1
+
+
+# ---------------------------------------------------------------------------------------------
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_p(c, C.c_uint32), _p(k, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def philox_single_round(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox_single_round(_p(c, C.c_uint32), _p(k, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def sample_negatives(seed, step, tag, lo, hi, n):
+    out = np.zeros(int(n), dtype=np.int32)
+    lib().orc_sample_negatives(C.c_uint64(seed), C.c_uint64(step), C.c_uint32(tag),
+                               C.c_int64(lo), C.c_int64(hi), C.c_int64(n), _p(out, C.c_int32))
+    return out
+
+
+def score_one(scorer, h, r, w, t):
+    h, r, w, t = _f32(h), _f32(r), _f32(w), _f32(t)
+    return float(lib().orc_score_one(_sid(scorer), C.c_int(h.shape[0]), _p(h, C.c_float),
+                                     _p(r, C.c_float), _p(w, C.c_float), _p(t, C.c_float)))
+
+
+def score_batch(scorer, ent, rel, relw, h, r, t, neg, want_neg=True):
+    ent, rel, relw = _f32(ent), _f32(rel), _f32(relw)
+    h, r, t, neg = _i32(h), _i32(r), _i32(t), _i32(neg)
+    B, N, d = h.shape[0], neg.shape[0], ent.shape[1]
+    pos = np.zeros(B, dtype=np.float64)
+    ngs = np.zeros((B, N), dtype=np.float64) if want_neg else None
+    lib().orc_score_batch(_sid(scorer), C.c_int(d), _p(ent, C.c_float), _p(rel, C.c_float),
+                          _p(relw, C.c_float), _p(h, C.c_int32), _p(r, C.c_int32),
+                          _p(t, C.c_int32), C.c_int64(B), _p(neg, C.c_int32), C.c_int64(N),
+                          _p(pos, C.c_double), _p(ngs, C.c_double))
+    return pos, ngs
+
+
+def loss_one(loss, gamma, adv_temp, n_ent_for_c, fp, s):
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    ds = np.zeros_like(s)
+    dfp = C.c_double(0.0)
+    L = lib().orc_loss_one(_lid(loss), C.c_double(gamma), C.c_double(adv_temp),
+                           C.c_int64(n_ent_for_c), C.c_double(fp), _p(s, C.c_double),
+                           C.c_int64(s.shape[0]), C.byref(dfp), _p(ds, C.c_double))
+    return float(L), float(dfp.value), ds
+
+
+def loss_bwd(scorer, loss, ent, rel, relw, h, r, t, neg, gamma=0.0, adv_temp=0.0,
+             loss_scale=None, n_ent_for_c=0, want_grads=True):
+    ent, rel, relw = _f32(ent), _f32(rel), _f32(relw)
+    h, r, t, neg = _i32(h), _i32(r), _i32(t), _i32(neg)
+    B, N, d = h.shape[0], neg.shape[0], ent.shape[1]
+    k = rel.shape[1]
+    if loss_scale is None:
+        loss_scale = 1.0 / max(B, 1)
+    g_ent = np.zeros((2 * B + N, d), dtype=np.float64) if want_grads else None
+    g_rel = np.zeros((B, k), dtype=np.float64) if want_grads else None
+    g_relw = np.zeros((B, d), dtype=np.float64) if (want_grads and relw is not None) else None
+    per = np.zeros(B, dtype=np.float64)
+    L = lib().orc_loss_bwd(_sid(scorer), _lid(loss), C.c_int(d), _p(ent, C.c_float),
+                           _p(rel, C.c_float), _p(relw, C.c_float), _p(h, C.c_int32),
+                           _p(r, C.c_int32), _p(t, C.c_int32), C.c_int64(B), _p(neg, C.c_int32),
+                           C.c_int64(N), C.c_double(gamma), C.c_double(adv_temp),
+                           C.c_double(loss_scale), C.c_int64(n_ent_for_c), _p(g_ent, C.c_double),
+                           _p(g_rel, C.c_double), _p(g_relw, C.c_double), _p(per, C.c_double))
+    return {"loss": float(L), "g_ent": g_ent, "g_rel": g_rel, "g_relw": g_relw,
+            "g_ent_idx": np.concatenate([h, t, neg]).astype(np.int32), "g_rel_idx": r.copy(),
+            "per_triple": per}
+
+
+def sparse_adam(theta, m, v, idx, grads, lr, beta1=0.9, beta2=0.999, eps=1e-8, step=1):
+    """Returns (theta', m', v', touched) as fp64 arrays; inputs are not modified."""
+    th = np.array(theta, dtype=np.float64, order="C")
+    mm = np.array(m, dtype=np.float64, order="C")
+    vv = np.array(v, dtype=np.float64, order="C")
+    idx, grads = _i32(idx), _f32(grads)
+    n_rows, d = th.shape
+    touched = np.zeros(n_rows, dtype=np.uint8)
+    lib().orc_sparse_adam(_p(th, C.c_double), _p(mm, C.c_double), _p(vv, C.c_double),
+                          C.c_int64(n_rows), C.c_int(d), _p(idx, C.c_int32), _p(grads, C.c_float),
+                          C.c_int64(idx.shape[0]), C.c_double(lr), C.c_double(beta1),
+                          C.c_double(beta2), C.c_double(eps), C.c_int64(step),
+                          _p(touched, C.c_uint8))
+    return th, mm, vv, touched.astype(bool)
+
+
+def bf16_rne(x):
+    x = _f32(x)
+    out = np.zeros(x.shape, dtype=np.uint16)
+    lib().orc_bf16_rne_array(_p(x, C.c_float), C.c_int64(x.size), _p(out, C.c_uint16))
+    return out
+
+
+def topk(scorer, ent, rel, relw, h, r, cand_lo, cand_hi, K, true_t=None):
+    ent, rel, relw = _f32(ent), _f32(rel), _f32(relw)
+    h, r, true_t = _i32(h), _i32(r), _i32(true_t)
+    Q, d = h.shape[0], ent.shape[1]
+    out_idx = np.zeros((Q, K), dtype=np.int32)
+    out_score = np.zeros((Q, K), dtype=np.float64)
+    rank = np.zeros(Q, dtype=np.int64) if true_t is not None else None
+    lib().orc_topk(_sid(scorer), C.c_int(d), _p(ent, C.c_float), _p(rel, C.c_float),
+                   _p(relw, C.c_float), _p(h, C.c_int32), _p(r, C.c_int32), C.c_int64(Q),
+                   C.c_int64(cand_lo), C.c_int64(cand_hi), C.c_int32(K), _p(out_idx, C.c_int32),
+                   _p(out_score, C.c_double), _p(true_t, C.c_int32), _p(rank, C.c_int64))
+    return out_idx, out_score, rank
+
+
+def bucket_triples(h, t, part_size, D, want_order=True):
+    h, t = _i32(h), _i32(t)
+    n = h.shape[0]
+    counts = np.zeros(D * D, dtype=np.int64)
+    offsets = np.zeros(D * D + 1, dtype=np.int64)
+    order = np.zeros(n, dtype=np.int64) if want_order else None
+    lib().orc_bucket_triples(_p(h, C.c_int32), _p(t, C.c_int32), C.c_int64(n),
+                             C.c_int64(part_size), C.c_int(D), _p(counts, C.c_int64),
+                             _p(offsets, C.c_int64), _p(order, C.c_int64))
+    return counts, offsets, order
