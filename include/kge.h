@@ -1,0 +1,196 @@
+/*
+ * kge.h -- C ABI of the MI355X (gfx950) knowledge-graph-embedding hot path.
+ *
+ * One GPU plays one BESS worker (arXiv 2211.12281, Section 4): it gathers the (h, r, t) embedding
+ * rows of a micro-batch, scores every query against its positive tail and against ONE block of
+ * negative tails shared by the whole micro-batch, evaluates the loss and its backward pass, and
+ * applies a duplicate-aware sparse Adam update to the touched rows; for link prediction it scores
+ * queries against a range of entity rows and returns the top-K.
+ *
+ * Conventions for every entry point
+ *  - Structs (kge_model_t, kge_loss_cfg_t, kge_adam_cfg_t) are read on the HOST during the call.
+ *    Every other pointer is a DEVICE pointer into memory owned by the caller; the library neither
+ *    allocates nor frees device memory and keeps no state between calls.  Scratch space comes
+ *    from the caller's workspace `ws` (size from kge_workspace_bytes(); 256-byte aligned).
+ *  - Work is enqueued on `hip_stream` (a hipStream_t, may be NULL for the default stream) and the
+ *    call returns without waiting for it.  Calls that share a workspace must be ordered on one
+ *    stream.
+ *  - Return value: KGE_OK (0) or a negative KGE_E_* code.  Arguments are validated on the host
+ *    before anything is launched; on error nothing has been enqueued.
+ *  - Index VALUES are not range-checked on the device: ids outside [0, n_ent) / [0, n_rel) are
+ *    undefined behaviour.  n_ent, n_rel < 2^31.
+ *  - Table layout: row-major, row i of a table starts at element i*ld; dtype KGE_F32 (float) or
+ *    KGE_BF16 (bfloat16 bit patterns).  `dim` (d) must be a multiple of 8 (fp32) or 16 (bf16);
+ *    d*sizeof(element) <= 1024 bytes.  Complex-valued scorers (RotatE, ComplEx) store a row as
+ *    [d/2 real parts | d/2 imaginary parts].  The relation row has rel_dim = d elements, except
+ *    RotatE where it holds d/2 phases (Section 3.1, "Encoder": k = d/2 for RotatE, else d).
+ *  - Scores follow Table 2 with p = 2:
+ *      TransE   -||h + r - t||            TransH  -||(h - (w.h)w) + r - (t - (w.t)w)||, w = relw/||relw||
+ *      RotatE   -||h o e^{ir} - t||       DistMult <r, h, t>       ComplEx  Re<r, h, conj t>
+ */
+#ifndef KGE_H_
+#define KGE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { KGE_TRANSE = 0, KGE_TRANSH = 1, KGE_ROTATE = 2, KGE_DISTMULT = 3, KGE_COMPLEX = 4 } kge_scorer_t;
+typedef enum { KGE_LOGSIGMOID = 0, KGE_SAMPLED_SOFTMAX = 1 } kge_loss_t;
+typedef enum { KGE_F32 = 0, KGE_BF16 = 1 } kge_dtype_t;
+typedef enum { KGE_OP_SCORE = 0, KGE_OP_LOSS_BWD = 1, KGE_OP_SPARSE_ADAM = 2, KGE_OP_TOPK = 3,
+               KGE_OP_PARTITION = 4 } kge_op_t;
+
+enum {
+    KGE_OK = 0,
+    KGE_E_INVALID_ARG = -1,         /* NULL where data is required, negative size, bad enum, bad dim */
+    KGE_E_UNSUPPORTED = -2,         /* valid request this build has no kernel for (e.g. p_norm = 1) */
+    KGE_E_WORKSPACE_TOO_SMALL = -3,
+    KGE_E_HIP = -4                  /* a HIP runtime call failed (launch error) */
+};
+
+/* A model = scorer + tables (Section 3.1: shallow entity / relation embeddings; TransH adds w_r). */
+typedef struct {
+    int32_t scorer;      /* kge_scorer_t */
+    int32_t p_norm;      /* distance scorers: 2 (1 is not implemented -> KGE_E_UNSUPPORTED) */
+    int32_t dtype;       /* kge_dtype_t of ent, rel, relw as the kernels read them */
+    int32_t dim;         /* d */
+    int32_t rel_dim;     /* d, or d/2 for RotatE */
+    int32_t reserved;
+    int64_t n_ent, n_rel;
+    const void *ent;     /* [n_ent, ent_ld] */
+    const void *rel;     /* [n_rel, rel_ld] */
+    const void *relw;    /* [n_rel, relw_ld], TransH only (else NULL) */
+    int64_t ent_ld, rel_ld, relw_ld;   /* row strides in elements */
+} kge_model_t;
+
+/* Loss of Section 3.1 ("Loss Functions"). */
+typedef struct {
+    int32_t loss;          /* kge_loss_t */
+    float gamma;           /* margin of the log-sigmoid loss */
+    float adv_temp;        /* a >= 0, temperature of the self-adversarial weights (StopGrad) */
+    float loss_scale;      /* the micro-batch loss is loss_scale * sum_b L_b; <= 0 selects 1/B */
+    int64_t n_ent_for_c;   /* |E| in the sampled-softmax correction c = log((|E|-1)/N) */
+} kge_loss_cfg_t;
+
+typedef struct {
+    float lr, beta1, beta2, eps;
+    int64_t step;          /* global 1-based step used in the bias corrections */
+} kge_adam_cfg_t;
+
+/*
+ * Shared negative ids (Section 4, "Training", eq. (negsamples): one set of corrupted tails per
+ * micro-batch): out_idx[i], i < n, i.i.d. uniform in [lo, hi), with replacement, no filtering.
+ * Counter-based Philox4x32-10: key = (seed_lo, seed_hi); block k = i/2 has counter
+ * (k_lo, k_hi, step, stream_tag) and yields two ids from its words (w1:w0) and (w3:w2);
+ * id = lo + floor(x * (hi - lo) / 2^64).  Bit-exact, no hidden state.  step < 2^32.
+ * out_idx: device int32[n].  Per-partition draws (N/D ids from each shard E_j) are D calls with
+ * the shard's [lo, hi).
+ */
+int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int64_t lo, int64_t hi,
+                         int64_t n, int32_t *out_idx, void *hip_stream);
+
+/*
+ * Scores of a micro-batch (Table 2; negative sharing per eq. (negsamples)):
+ *   pos_out[b]       = f(h_b, r_b, t_b)           b < B          (float[B], or NULL)
+ *   neg_out[b*N + n] = f(h_b, r_b, neg_n)         n < N          (float[B*N] row-major, or NULL)
+ * h, r, t: int32[B]; neg: int32[N] (may be NULL when N = 0).  B = 0 or N = 0 are valid.
+ * Arithmetic: fp32 tables -> fp32 matrix cores; bf16 tables -> bf16 matrix cores with fp32
+ * accumulation (queries are rounded to bf16 after the query build).
+ */
+int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, const int32_t *t,
+              int64_t B, const int32_t *neg, int64_t N, float *pos_out, float *neg_out, void *ws,
+              size_t ws_bytes, void *hip_stream);
+
+/*
+ * Forward + backward of one micro-batch (losses of Section 3.1; the shared negative block is
+ * never written to memory):
+ *   loss_out      float[1]           loss_scale * sum_b L_b
+ *   g_ent         float[(2B+N) * d]  gradient rows, one per gathered entity slot, in the order
+ *                                    heads (B), positive tails (B), shared negatives (N);
+ *                                    duplicates are NOT merged (kge_sparse_adam does that)
+ *   g_ent_idx     int32[2B+N]        the table row each slot targets (= h, t, neg concatenated)
+ *   g_rel         float[B * rel_dim] gradient of each triple's relation row
+ *   g_relw        float[B * d]       TransH only (NULL otherwise)
+ *   g_rel_idx     int32[B]           = r
+ * The sub-gradient of a distance score at distance 0 is 0.  TransH requires d*sizeof(element)
+ * <= 512 bytes in this call.
+ */
+int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h,
+                 const int32_t *r, const int32_t *t, int64_t B, const int32_t *neg, int64_t N,
+                 float *loss_out, float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw,
+                 int32_t *g_rel_idx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Duplicate-aware scatter-add + lazy sparse Adam on the touched rows only (Section 1: only the
+ * rows of the mini-batch are accessed and updated; optimiser state lives beside the rows,
+ * Section 4.1).  grads[i*dim .. ] (float, i < M) targets table row idx[i]; rows with equal idx
+ * are summed first (sort by row, then a fixed-order segmented reduction: results do not depend
+ * on scheduling), then each touched row takes ONE Adam step with the global step:
+ *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+ *   theta <- theta - lr * (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps)
+ * Untouched rows and their moments are not read or written.
+ *   param_f32   float[n_rows, ld]   master weights (updated in place)
+ *   param_bf16  bf16 [n_rows, ld]   optional shadow copy, rewritten as RNE(theta) for touched rows
+ *   m, v        float[n_rows, ld]   Adam moments (updated in place)
+ * dim must be a multiple of 4.  M = 0 is valid (no-op).  This is the only call that writes a table.
+ */
+int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows,
+                    int32_t dim, int64_t ld, const int32_t *idx, const float *grads, int64_t M,
+                    const kge_adam_cfg_t *cfg, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Link prediction (Section 3.2, "Inference"): for each query (h_q, r_q), q < Q, rank all
+ * candidate tails t in [cand_lo, cand_hi) and return the K best by (score descending, index
+ * ascending):  out_idx int32[Q*K], out_score float[Q*K].  If K exceeds the number of candidates
+ * the tail of each list is padded with index -1 and score -inf.  The candidate range is the
+ * single-GPU image of "score against the local shard E_i"; D shard-wise lists merge to the global
+ * top-K (Section 4, "Inference").
+ * Exactness: candidates are pre-selected with matrix-core scores, the survivors are re-scored with
+ * a sequential fp64 fused-multiply-add loop and ordered by that key, and a rigorous error bound
+ * checks that no candidate outside the pre-selection could belong to the top-K; queries that fail
+ * the check are re-ranked by an exhaustive fp64 scan.  The returned indices therefore equal the
+ * ordering by the fp64 key exactly.
+ * true_t int32[Q] / out_rank int64[Q] (both or neither): 1-based rank of the held-out tail among
+ * the candidates.  Exact whenever rank <= K (it is the list position); beyond K it is counted
+ * with the matrix-core scores and may differ from the fp64 rank by the number of candidates whose
+ * score lies within the rounding error of the true tail's score.
+ * Scorers: DistMult and TransE (others: KGE_E_UNSUPPORTED).  1 <= K <= 1024.
+ */
+int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64_t Q,
+             int64_t cand_lo, int64_t cand_hi, int32_t K, int32_t *out_idx, float *out_score,
+             const int32_t *true_t, int64_t *out_rank, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Partition bucketing (Section 4, "Partitioning"): entity e belongs to shard e / part_size
+ * (part_size = ceil(|E|/D), ids assumed already randomly permuted); triple i falls in bucket
+ * (h_i / part_size) * D + (t_i / part_size).  Outputs a stable counting sort by bucket:
+ *   bucket_offsets int64[D*D + 1]   exclusive prefix sums of the bucket sizes
+ *   order          int64[n]         order[k] = input position of the k-th triple in bucket order;
+ *                                   triples of one bucket keep their input order
+ * D <= 64.
+ */
+int kge_partition_triples(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size,
+                          int32_t D, int64_t *bucket_offsets, int64_t *order, void *ws,
+                          size_t ws_bytes, void *hip_stream);
+
+/*
+ * Workspace size in bytes for one call (pure function; host only).  Meaning of (B, N, K):
+ *   KGE_OP_SCORE, KGE_OP_LOSS_BWD  B triples, N shared negatives, K unused
+ *   KGE_OP_SPARSE_ADAM             B = M gradient rows, N = dim, K unused; model may be NULL
+ *   KGE_OP_TOPK                    B = Q queries, N = number of candidates, K
+ *   KGE_OP_PARTITION               B = n triples, N = D; model may be NULL
+ * Returns 0 for an invalid request.
+ */
+size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t N, int64_t K);
+
+/* Static description of a status code. */
+const char *kge_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KGE_H_ */

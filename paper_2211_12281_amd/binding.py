@@ -1,0 +1,223 @@
+"""ctypes binding of libkge_mi355x.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch supplies device memory and the
+stream.  There is no CPU fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkge_mi355x.so")
+
+SCORERS = {"transe": 0, "transh": 1, "rotate": 2, "distmult": 3, "complex": 4}
+LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
+OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION = 0, 1, 2, 3, 4
+EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
+           "kge_partition_triples", "kge_workspace_bytes", "kge_status_string"]
+
+
+class KgeModelT(C.Structure):
+    _fields_ = [("scorer", C.c_int32), ("p_norm", C.c_int32), ("dtype", C.c_int32), ("dim", C.c_int32),
+                ("rel_dim", C.c_int32), ("reserved", C.c_int32), ("n_ent", C.c_int64), ("n_rel", C.c_int64),
+                ("ent", C.c_void_p), ("rel", C.c_void_p), ("relw", C.c_void_p),
+                ("ent_ld", C.c_int64), ("rel_ld", C.c_int64), ("relw_ld", C.c_int64)]
+
+
+class KgeLossCfgT(C.Structure):
+    _fields_ = [("loss", C.c_int32), ("gamma", C.c_float), ("adv_temp", C.c_float), ("loss_scale", C.c_float),
+                ("n_ent_for_c", C.c_int64)]
+
+
+class KgeAdamCfgT(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("step", C.c_int64)]
+
+
+class KgeError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load():
+    """Loads the library or raises; never builds it and never falls back to anything else."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise KgeError(f"{LIB_PATH} is missing: build it with `python -m paper_2211_12281_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        lib.kge_workspace_bytes.restype = C.c_size_t
+        lib.kge_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
+        lib.kge_status_string.restype = C.c_char_p
+        lib.kge_status_string.argtypes = [C.c_int]
+        lib.kge_sample_negatives.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
+                                             C.c_void_p, C.c_void_p]
+        lib.kge_score.argtypes = [C.c_void_p] + [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_int64] + \
+            [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
+        lib.kge_loss_bwd.argtypes = [C.c_void_p, C.c_void_p] + [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_int64] + \
+            [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
+        lib.kge_sparse_adam.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                                           C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kge_topk.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_int64, C.c_int64, C.c_int32] + [C.c_void_p] * 5 + \
+            [C.c_size_t, C.c_void_p]
+        lib.kge_partition_triples.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return load().kge_status_string(code).decode()
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise KgeError(f"{what} failed: {status_string(code)} ({code})")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _i32(t):
+    assert t.dtype == torch.int32 and t.is_cuda and t.is_contiguous(), "index tensors: contiguous int32 on the GPU"
+    return t
+
+
+class Workspace:
+    """A grow-only device buffer handed to the library as its scratch space."""
+
+    def __init__(self):
+        self.buf = None
+
+    def get(self, nbytes: int):
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = None
+            self.buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        return self.buf
+
+
+_default_ws = Workspace()
+
+
+class Model:
+    """Scorer + embedding tables (device tensors, fp32 or bf16, row-major 2-D)."""
+
+    def __init__(self, scorer: str, ent, rel, relw=None, p_norm: int = 2):
+        self.scorer = scorer
+        self.ent, self.rel, self.relw = ent, rel, relw
+        assert ent.is_cuda and rel.is_cuda and ent.dim() == 2 and rel.dim() == 2
+        assert ent.dtype == rel.dtype and ent.dtype in (torch.float32, torch.bfloat16)
+        assert ent.stride(1) == 1 and rel.stride(1) == 1
+        self.dim = ent.shape[1]
+        s = KgeModelT()
+        s.scorer = SCORERS[scorer]
+        s.p_norm = p_norm
+        s.dtype = 1 if ent.dtype == torch.bfloat16 else 0
+        s.dim = self.dim
+        s.rel_dim = rel.shape[1]
+        s.n_ent, s.n_rel = ent.shape[0], rel.shape[0]
+        s.ent, s.rel = ent.data_ptr(), rel.data_ptr()
+        s.ent_ld, s.rel_ld = ent.stride(0), rel.stride(0)
+        if relw is not None:
+            assert relw.is_cuda and relw.dtype == ent.dtype and relw.stride(1) == 1
+            s.relw, s.relw_ld = relw.data_ptr(), relw.stride(0)
+        self.struct = s
+
+    @property
+    def ref(self):
+        return C.byref(self.struct)
+
+
+def workspace_bytes(op: int, model: Model | None, B: int, N: int, K: int = 0) -> int:
+    return int(load().kge_workspace_bytes(op, model.ref if model is not None else None, B, N, K))
+
+
+def sample_negatives(seed: int, step: int, tag: int, lo: int, hi: int, n: int, out=None):
+    if out is None:
+        out = torch.empty(n, dtype=torch.int32, device="cuda")
+    _check(load().kge_sample_negatives(seed, step, tag, lo, hi, n, _ptr(out), _stream()), "kge_sample_negatives")
+    return out
+
+
+def score(model: Model, h, r, t, neg, want_neg: bool = True, ws: Workspace | None = None):
+    B, N = h.numel(), neg.numel()
+    pos = torch.empty(B, dtype=torch.float32, device="cuda")
+    blk = torch.empty((B, N), dtype=torch.float32, device="cuda") if want_neg else None
+    ws = ws or _default_ws
+    nbytes = workspace_bytes(OP_SCORE, model, B, N)
+    buf = ws.get(nbytes)
+    _check(load().kge_score(model.ref, _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B, _ptr(_i32(neg)), N,
+                            _ptr(pos), _ptr(blk), _ptr(buf), buf.numel(), _stream()), "kge_score")
+    return pos, blk
+
+
+def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp: float = 0.0,
+             loss_scale: float = 0.0, n_ent_for_c: int = 0, ws: Workspace | None = None, out=None):
+    B, N, d = h.numel(), neg.numel(), model.dim
+    k = model.rel.shape[1]
+    if out is None:
+        out = {
+            "loss": torch.empty(1, dtype=torch.float32, device="cuda"),
+            "g_ent": torch.empty((2 * B + N, d), dtype=torch.float32, device="cuda"),
+            "g_ent_idx": torch.empty(2 * B + N, dtype=torch.int32, device="cuda"),
+            "g_rel": torch.empty((B, k), dtype=torch.float32, device="cuda"),
+            "g_relw": torch.empty((B, d), dtype=torch.float32, device="cuda") if model.relw is not None else None,
+            "g_rel_idx": torch.empty(B, dtype=torch.int32, device="cuda"),
+        }
+    cfg = KgeLossCfgT(LOSSES[loss], gamma, adv_temp, loss_scale, n_ent_for_c)
+    ws = ws or _default_ws
+    buf = ws.get(workspace_bytes(OP_LOSS_BWD, model, B, N))
+    _check(load().kge_loss_bwd(model.ref, C.byref(cfg), _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B,
+                               _ptr(_i32(neg)), N, _ptr(out["loss"]), _ptr(out["g_ent"]), _ptr(out["g_ent_idx"]),
+                               _ptr(out["g_rel"]), _ptr(out["g_relw"]), _ptr(out["g_rel_idx"]), _ptr(buf),
+                               buf.numel(), _stream()), "kge_loss_bwd")
+    return out
+
+
+def sparse_adam(param, shadow, m, v, idx, grads, lr: float, beta1: float = 0.9, beta2: float = 0.999,
+                eps: float = 1e-8, step: int = 1, ws: Workspace | None = None):
+    assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
+    assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
+    assert m.stride() == param.stride() and v.stride() == param.stride()
+    if shadow is not None:
+        assert shadow.dtype == torch.bfloat16 and shadow.stride() == param.stride()
+    M, d = idx.numel(), param.shape[1]
+    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step)
+    ws = ws or _default_ws
+    buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, d))
+    _check(load().kge_sparse_adam(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
+                                  _ptr(_i32(idx)), _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream()),
+           "kge_sparse_adam")
+
+
+def topk(model: Model, h, r, cand_lo: int, cand_hi: int, K: int, true_t=None, ws: Workspace | None = None):
+    Q = h.numel()
+    out_idx = torch.empty((Q, K), dtype=torch.int32, device="cuda")
+    out_score = torch.empty((Q, K), dtype=torch.float32, device="cuda")
+    rank = torch.empty(Q, dtype=torch.int64, device="cuda") if true_t is not None else None
+    ws = ws or _default_ws
+    buf = ws.get(workspace_bytes(OP_TOPK, model, Q, cand_hi - cand_lo, K))
+    _check(load().kge_topk(model.ref, _ptr(_i32(h)), _ptr(_i32(r)), Q, cand_lo, cand_hi, K, _ptr(out_idx),
+                           _ptr(out_score), _ptr(true_t), _ptr(rank), _ptr(buf), buf.numel(), _stream()), "kge_topk")
+    return out_idx, out_score, rank
+
+
+def partition_triples(h, t, part_size: int, D: int, ws: Workspace | None = None):
+    n = h.numel()
+    offsets = torch.empty(D * D + 1, dtype=torch.int64, device="cuda")
+    order = torch.empty(n, dtype=torch.int64, device="cuda")
+    ws = ws or _default_ws
+    buf = ws.get(workspace_bytes(OP_PARTITION, None, n, D))
+    _check(load().kge_partition_triples(_ptr(_i32(h)), _ptr(_i32(t)), n, part_size, D, _ptr(offsets), _ptr(order),
+                                        _ptr(buf), buf.numel(), _stream()), "kge_partition_triples")
+    return offsets, order

@@ -1,0 +1,343 @@
+// extern "C" entry points: argument validation, workspace carving, kernel sequencing.
+#include "prep_kernels.h"
+#include <math.h>
+
+int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
+                        const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
+                        size_t ws_bytes, hipStream_t st);
+size_t kge_sparse_adam_ws(int64_t M);
+int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, int64_t Q, int64_t lo, int64_t hi,
+                 int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
+                 size_t ws_bytes, hipStream_t st);
+size_t kge_topk_ws(const kge_model_t &model, int64_t Q, int64_t ncand, int K);
+int kge_run_partition(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int D, int64_t *offsets,
+                      int64_t *order, void *ws, size_t ws_bytes, hipStream_t st);
+size_t kge_partition_ws(int64_t n, int D);
+
+namespace {
+
+struct Geometry {
+    bool bf16, transh;
+    int es, rb, dp, kind;
+    int B, N, Bp, Np;
+    int own_tiles_b, own_tiles_n;       // 128-row tiles
+    int str_tiles_b, str_tiles_n;       // 32-row tiles
+    int nsplit_q, tps_q;                // row-owner launches: splits over the negatives
+    int nsplit_t, tps_t;                // column-owner launches: splits over the queries
+    int dsplit_q, dsplit_t;
+};
+
+constexpr int TARGET_WGS = 256;         // one workgroup per compute unit
+
+int validate_model(const kge_model_t *m) {
+    if (!m) return KGE_E_INVALID_ARG;
+    if (m->scorer < KGE_TRANSE || m->scorer > KGE_COMPLEX) return KGE_E_INVALID_ARG;
+    if (m->dtype != KGE_F32 && m->dtype != KGE_BF16) return KGE_E_INVALID_ARG;
+    const int es = m->dtype == KGE_BF16 ? 2 : 4;
+    if (m->dim <= 0 || m->dim % (32 / es) != 0 || m->dim * es > 1024) return KGE_E_INVALID_ARG;
+    const bool dist = m->scorer == KGE_TRANSE || m->scorer == KGE_TRANSH || m->scorer == KGE_ROTATE;
+    if (dist && m->p_norm == 1) return KGE_E_UNSUPPORTED;
+    if (dist && m->p_norm != 2) return KGE_E_INVALID_ARG;
+    const int k = m->scorer == KGE_ROTATE ? m->dim / 2 : m->dim;
+    if (m->rel_dim != k) return KGE_E_INVALID_ARG;
+    if (m->n_ent <= 0 || m->n_rel <= 0 || m->n_ent >= (1ll << 31) || m->n_rel >= (1ll << 31)) return KGE_E_INVALID_ARG;
+    if (!m->ent || !m->rel || m->ent_ld < m->dim || m->rel_ld < k) return KGE_E_INVALID_ARG;
+    if (m->scorer == KGE_TRANSH && (!m->relw || m->relw_ld < m->dim)) return KGE_E_INVALID_ARG;
+    return KGE_OK;
+}
+
+Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
+    Geometry g{};
+    g.bf16 = m.dtype == KGE_BF16;
+    g.transh = m.scorer == KGE_TRANSH;
+    g.es = g.bf16 ? 2 : 4;
+    g.rb = m.dim * g.es <= 512 ? 512 : 1024;
+    g.dp = g.rb / g.es;
+    g.kind = (m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
+    g.B = (int)B; g.N = (int)N;
+    g.Bp = (int)kge_round_up(B, KGE_PAD); g.Np = (int)kge_round_up(N, KGE_PAD);
+    g.own_tiles_b = g.Bp / KGE_OWN_TILE; g.own_tiles_n = g.Np / KGE_OWN_TILE;
+    g.str_tiles_b = g.Bp / KGE_STREAM_TILE; g.str_tiles_n = g.Np / KGE_STREAM_TILE;
+    auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps) {
+        if (own_tiles == 0 || str_tiles == 0) { nsplit = 0; tps = 0; return; }
+        int want = (TARGET_WGS + own_tiles - 1) / own_tiles;
+        if (want > str_tiles) want = str_tiles;
+        if (want < 1) want = 1;
+        tps = (str_tiles + want - 1) / want;
+        nsplit = (str_tiles + tps - 1) / tps;
+    };
+    split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q);
+    split(g.own_tiles_n, g.str_tiles_b, g.nsplit_t, g.tps_t);
+    g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
+    g.dsplit_t = (g.bf16 && g.rb == 1024) ? 2 : 1;
+    return g;
+}
+
+// bump allocator over the caller's workspace (256-byte granules); with base == nullptr it only sizes
+struct Carver {
+    char *base; size_t off = 0;
+    explicit Carver(void *p) : base((char *)p) {}
+    template <typename T> T *take(size_t count) {
+        size_t bytes = (count * sizeof(T) + 255) / 256 * 256;
+        T *p = base ? (T *)(base + off) : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+struct Buffers {
+    void *Q, *W, *Q2, *T, *Qt, *Wt, *Tt;
+    KgeRowInfo *rowinfo; float *tn, *pos, *lossb, *gpos;
+    float4 *stat_part; float *accq, *accq2; float4 *sumq; float *acct; float4 *sumt;
+};
+
+size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
+    Carver c(ws);
+    const size_t es = g.es, rowsB = (size_t)g.Bp * g.dp, rowsN = (size_t)g.Np * g.dp;
+    b.Q = c.take<char>(rowsB * es);
+    b.W = g.transh ? c.take<char>(rowsB * es) : nullptr;
+    b.T = c.take<char>(rowsN * es);
+    b.rowinfo = c.take<KgeRowInfo>(g.Bp);
+    b.tn = c.take<float>(g.Np);
+    b.pos = c.take<float>(g.Bp);
+    b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
+    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr;
+    if (bwd) {
+        b.Q2 = g.transh ? c.take<char>(rowsB * es) : nullptr;
+        b.Qt = c.take<char>(rowsB * es);
+        b.Wt = g.transh ? c.take<char>(rowsB * es) : nullptr;
+        b.Tt = c.take<char>(rowsN * es);
+        b.lossb = c.take<float>(g.Bp);
+        b.gpos = c.take<float>(g.Bp);
+        b.stat_part = c.take<float4>((size_t)g.nsplit_q * g.Bp);
+        b.accq = c.take<float>((size_t)g.nsplit_q * rowsB);
+        b.accq2 = g.transh ? c.take<float>((size_t)g.nsplit_q * rowsB) : nullptr;
+        b.sumq = c.take<float4>((size_t)g.nsplit_q * g.Bp);
+        b.acct = c.take<float>((size_t)g.nsplit_t * rowsN);
+        b.sumt = c.take<float4>((size_t)g.nsplit_t * g.Np);
+    }
+    return c.off + 256;
+}
+
+KgeModelDev dev_model(const kge_model_t &m) {
+    KgeModelDev d;
+    d.scorer = m.scorer; d.bf16 = m.dtype == KGE_BF16; d.dim = m.dim; d.rel_dim = m.rel_dim;
+    d.ent = m.ent; d.rel = m.rel; d.relw = m.relw;
+    d.ent_ld = m.ent_ld; d.rel_ld = m.rel_ld; d.relw_ld = m.relw_ld;
+    return d;
+}
+
+int launch_block(const Geometry &g, bool own_row, int mode, const KgeBlockArgs &a, int own_tiles, int nsplit,
+                 int dsplit, hipStream_t st) {
+    if (g.bf16) return kge_launch_block_bf16(g.rb, own_row, mode, g.transh, a, own_tiles, nsplit, dsplit, st);
+    return kge_launch_block_f32(g.rb, own_row, mode, g.transh, a, own_tiles, nsplit, dsplit, st);
+}
+
+void *align_ws(void *ws, size_t &bytes) {
+    uintptr_t p = (uintptr_t)ws, q = (p + 255) & ~(uintptr_t)255;
+    bytes = bytes >= (q - p) ? bytes - (q - p) : 0;
+    return (void *)q;
+}
+
+}  // namespace
+
+// the per-part launchers live in eight translation units
+#define KGE_DECL(name) int kge_launch_block_##name(int, bool, int, bool, const KgeBlockArgs &, int, int, int, hipStream_t);
+KGE_DECL(f32_score) KGE_DECL(f32_stats) KGE_DECL(f32_gradq) KGE_DECL(f32_gradt)
+KGE_DECL(bf16_score) KGE_DECL(bf16_stats) KGE_DECL(bf16_gradq) KGE_DECL(bf16_gradt)
+
+int kge_launch_block_f32(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a, int own_tiles,
+                         int nsplit, int dsplit, hipStream_t st) {
+    if (mode == KGE_MODE_SCORE) return kge_launch_block_f32_score(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
+    if (mode == KGE_MODE_STATS) return kge_launch_block_f32_stats(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
+    return own_row ? kge_launch_block_f32_gradq(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st)
+                   : kge_launch_block_f32_gradt(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
+}
+int kge_launch_block_bf16(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a, int own_tiles,
+                          int nsplit, int dsplit, hipStream_t st) {
+    if (mode == KGE_MODE_SCORE) return kge_launch_block_bf16_score(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
+    if (mode == KGE_MODE_STATS) return kge_launch_block_bf16_stats(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
+    return own_row ? kge_launch_block_bf16_gradq(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st)
+                   : kge_launch_block_bf16_gradt(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
+}
+
+extern "C" {
+
+const char *kge_status_string(int status) {
+    switch (status) {
+    case KGE_OK: return "ok";
+    case KGE_E_INVALID_ARG: return "invalid argument";
+    case KGE_E_UNSUPPORTED: return "unsupported configuration";
+    case KGE_E_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case KGE_E_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t N, int64_t K) {
+    if (B < 0 || N < 0) return 0;
+    switch (op) {
+    case KGE_OP_SCORE:
+    case KGE_OP_LOSS_BWD: {
+        if (validate_model(model) != KGE_OK || B >= (1ll << 30) || N >= (1ll << 30)) return 0;
+        Geometry g = make_geometry(*model, B, N);
+        Buffers b;
+        return carve(g, op == KGE_OP_LOSS_BWD, nullptr, b);
+    }
+    case KGE_OP_SPARSE_ADAM: return kge_sparse_adam_ws(B);
+    case KGE_OP_TOPK:
+        if (validate_model(model) != KGE_OK || K < 1 || K > 256) return 0;
+        return kge_topk_ws(*model, B, N, (int)K);
+    case KGE_OP_PARTITION: return (N >= 1 && N <= 64) ? kge_partition_ws(B, (int)N) : 0;
+    default: return 0;
+    }
+}
+
+int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int64_t lo, int64_t hi, int64_t n,
+                         int32_t *out_idx, void *hip_stream) {
+    if (n < 0 || hi <= lo || lo < 0 || hi > (1ll << 31) || step >= (1ull << 32)) return KGE_E_INVALID_ARG;
+    if (n == 0) return KGE_OK;
+    if (!out_idx) return KGE_E_INVALID_ARG;
+    return kge_run_negatives(seed, step, stream_tag, lo, hi, n, out_idx, (hipStream_t)hip_stream);
+}
+
+int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, const int32_t *t, int64_t B,
+              const int32_t *neg, int64_t N, float *pos_out, float *neg_out, void *ws, size_t ws_bytes,
+              void *hip_stream) {
+    int rc = validate_model(model);
+    if (rc != KGE_OK) return rc;
+    if (B < 0 || N < 0 || B >= (1ll << 30) || N >= (1ll << 30)) return KGE_E_INVALID_ARG;
+    if (B == 0) return KGE_OK;
+    if (!h || !r || !t || (N > 0 && !neg)) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool block = N > 0 && neg_out;
+    Geometry g = make_geometry(*model, B, block ? N : 0);
+    Buffers b;
+    ws = align_ws(ws, ws_bytes);
+    if (carve(g, false, nullptr, b) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    carve(g, false, ws, b);
+    KgeModelDev md = dev_model(*model);
+    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.rowinfo, b.pos, pos_out, st);
+    if (rc != KGE_OK || !block) return rc;
+    rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st);
+    if (rc != KGE_OK) return rc;
+    KgeBlockArgs a{};
+    a.own = b.T; a.str = b.Q; a.str2 = b.W; a.rowinfo = b.rowinfo; a.tn = b.tn;
+    a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_b; a.tiles_per_split = g.tps_t;
+    a.kind = g.kind; a.S_out = neg_out; a.own_pad = g.Np;
+    return launch_block(g, false, KGE_MODE_SCORE, a, g.own_tiles_n, g.nsplit_t, 1, st);
+}
+
+int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
+                 const int32_t *t, int64_t B, const int32_t *neg, int64_t N, float *loss_out, float *g_ent,
+                 int32_t *g_ent_idx, float *g_rel, float *g_relw, int32_t *g_rel_idx, void *ws, size_t ws_bytes,
+                 void *hip_stream) {
+    int rc = validate_model(model);
+    if (rc != KGE_OK) return rc;
+    if (!cfg || (cfg->loss != KGE_LOGSIGMOID && cfg->loss != KGE_SAMPLED_SOFTMAX)) return KGE_E_INVALID_ARG;
+    if (B < 0 || N < 0 || B >= (1ll << 30) || N >= (1ll << 30)) return KGE_E_INVALID_ARG;
+    if (!(cfg->adv_temp >= 0.f)) return KGE_E_INVALID_ARG;
+    if (cfg->loss == KGE_SAMPLED_SOFTMAX && N > 0 && cfg->n_ent_for_c < 2) return KGE_E_INVALID_ARG;
+    if (!loss_out) return KGE_E_INVALID_ARG;
+    if (B > 0 && (!h || !r || !t || !g_ent || !g_ent_idx || !g_rel || !g_rel_idx)) return KGE_E_INVALID_ARG;
+    if (N > 0 && (!neg || !g_ent || !g_ent_idx)) return KGE_E_INVALID_ARG;
+    if (model->scorer == KGE_TRANSH && B > 0 && !g_relw) return KGE_E_INVALID_ARG;
+    Geometry g = make_geometry(*model, B, N);
+    if (g.transh && g.rb > 512) return KGE_E_UNSUPPORTED;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Buffers b;
+    ws = align_ws(ws, ws_bytes);
+    if (carve(g, true, nullptr, b) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    carve(g, true, ws, b);
+    KgeModelDev md = dev_model(*model);
+    const float scale = cfg->loss_scale > 0.f ? cfg->loss_scale : (B > 0 ? 1.f / (float)B : 1.f);
+    const float c_corr = (cfg->loss == KGE_SAMPLED_SOFTMAX && N > 0)
+                             ? (float)log((double)(cfg->n_ent_for_c - 1) / (double)N) : 0.f;
+    const bool have_block = B > 0 && N > 0;
+
+    if ((rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.rowinfo, b.pos, nullptr, st)) != KGE_OK) return rc;
+    KgeBlockArgs a{};
+    if (have_block) {
+        if ((rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st)) != KGE_OK) return rc;
+        if ((rc = kge_run_transpose(b.T, b.Tt, g.Np, g.dp, g.bf16, st)) != KGE_OK) return rc;
+        if ((rc = kge_run_transpose(g.transh ? b.Q2 : b.Q, b.Qt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
+        if (g.transh && (rc = kge_run_transpose(b.W, b.Wt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
+        // pass 1: row statistics of the block
+        a.own = b.Q; a.own2 = b.W; a.str = b.T; a.rowinfo = b.rowinfo; a.tn = b.tn;
+        a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_n; a.tiles_per_split = g.tps_q;
+        a.kind = g.kind; a.loss = cfg->loss; a.gamma = cfg->gamma; a.adv_temp = cfg->adv_temp; a.c_corr = c_corr;
+        a.stat_part = b.stat_part; a.own_pad = g.Bp;
+        if ((rc = launch_block(g, true, KGE_MODE_STATS, a, g.own_tiles_b, g.nsplit_q, 1, st)) != KGE_OK) return rc;
+    }
+    if ((rc = kge_run_rowfinish(b.stat_part, have_block ? g.nsplit_q : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
+                                cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, loss_out, st)) != KGE_OK) return rc;
+    if (have_block) {
+        // pass 2: gradient of the queries (row owner) ...
+        a.strT = b.Tt; a.strT_ld = g.Np; a.acc_part = b.accq; a.acc_part2 = b.accq2; a.sum_part = b.sumq;
+        if ((rc = launch_block(g, true, KGE_MODE_GRAD, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
+        // ... and of the shared negatives (column owner)
+        KgeBlockArgs c = a;
+        c.own = b.T; c.own2 = nullptr; c.str = b.Q; c.str2 = b.W; c.strT = b.Qt; c.strT2 = b.Wt; c.strT_ld = g.Bp;
+        c.str_tiles = g.str_tiles_b; c.tiles_per_split = g.tps_t;
+        c.acc_part = b.acct; c.acc_part2 = nullptr; c.sum_part = b.sumt; c.own_pad = g.Np;
+        if ((rc = launch_block(g, false, KGE_MODE_GRAD, c, g.own_tiles_n, g.nsplit_t, g.dsplit_t, st)) != KGE_OK) return rc;
+    }
+    if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, have_block ? g.nsplit_q : 0, b.gpos,
+                            g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, st)) != KGE_OK) return rc;
+    if (N > 0) {
+        // with B == 0 there are no partials: nsplit 0 writes zero rows
+        rc = kge_run_tfinish(b.acct, b.sumt, have_block ? g.nsplit_t : 0, g.Np, g.N, g.dp, model->dim,
+                             g.kind == KGE_KIND_DIST, b.T, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
+                             g_ent_idx + 2 * B, st);
+    }
+    return rc;
+}
+
+int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
+                    int64_t ld, const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t *cfg,
+                    void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!cfg || M < 0 || n_rows <= 0 || n_rows >= (1ll << 31) || dim <= 0 || dim % 4 != 0 || ld < dim || ld % 4 != 0)
+        return KGE_E_INVALID_ARG;
+    if (cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f))
+        return KGE_E_INVALID_ARG;
+    if (M == 0) return KGE_OK;
+    if (M >= (1ll << 31)) return KGE_E_INVALID_ARG;
+    if (!param_f32 || !m || !v || !idx || !grads) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (kge_sparse_adam_ws(M) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_sparse_adam(param_f32, param_bf16, m, v, n_rows, dim, ld, idx, grads, M, *cfg, ws, ws_bytes,
+                               (hipStream_t)hip_stream);
+}
+
+int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64_t Q, int64_t cand_lo,
+             int64_t cand_hi, int32_t K, int32_t *out_idx, float *out_score, const int32_t *true_t,
+             int64_t *out_rank, void *ws, size_t ws_bytes, void *hip_stream) {
+    int rc = validate_model(model);
+    if (rc != KGE_OK) return rc;
+    if (Q < 0 || Q >= (1ll << 30) || cand_lo < 0 || cand_hi < cand_lo || cand_hi > model->n_ent) return KGE_E_INVALID_ARG;
+    if (K < 1 || K > 256) return KGE_E_INVALID_ARG;
+    if ((true_t == nullptr) != (out_rank == nullptr)) return KGE_E_INVALID_ARG;
+    if (model->scorer != KGE_DISTMULT && model->scorer != KGE_TRANSE) return KGE_E_UNSUPPORTED;
+    if (Q == 0) return KGE_OK;
+    if (!h || !r || !out_idx || !out_score) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (kge_topk_ws(*model, Q, cand_hi - cand_lo, K) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_topk(*model, h, r, Q, cand_lo, cand_hi, K, out_idx, out_score, true_t, out_rank, ws, ws_bytes,
+                        (hipStream_t)hip_stream);
+}
+
+int kge_partition_triples(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int32_t D,
+                          int64_t *bucket_offsets, int64_t *order, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (n < 0 || part_size <= 0 || D < 1 || D > 64 || !bucket_offsets) return KGE_E_INVALID_ARG;
+    if (n > 0 && (!h || !t || !order)) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (kge_partition_ws(n, D) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_partition(h, t, n, part_size, D, bucket_offsets, order, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

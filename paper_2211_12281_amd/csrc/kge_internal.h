@@ -1,0 +1,63 @@
+// Internal declarations shared by the translation units of the gfx950 library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/kge.h"
+
+#define KGE_HIP_TRY(expr)                                   \
+    do {                                                    \
+        hipError_t e__ = (expr);                            \
+        if (e__ != hipSuccess) return KGE_E_HIP;            \
+    } while (0)
+
+static inline int kge_launch_status() {
+    return hipGetLastError() == hipSuccess ? KGE_OK : KGE_E_HIP;
+}
+
+static inline int64_t kge_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// ---------------------------------------------------------------------------------------------
+// Tile geometry of the block kernels
+// ---------------------------------------------------------------------------------------------
+constexpr int KGE_OWN_TILE = 128;     // rows owned by one workgroup (4 waves x 32)
+constexpr int KGE_STREAM_TILE = 32;   // rows streamed through LDS per iteration
+constexpr int KGE_PAD = 128;          // B and N are padded to this in the workspace copies
+
+enum { KGE_MODE_SCORE = 0, KGE_MODE_STATS = 1, KGE_MODE_GRAD = 2 };
+enum { KGE_KIND_MULT = 0, KGE_KIND_DIST = 1 };
+
+// Per-row side information of the queries: squared norm of q, c = w.q (TransH), the
+// per-row constant of the gradient coefficient, spare.
+struct __attribute__((aligned(16))) KgeRowInfo { float qn, c, K, spare; };
+
+// Arguments of one block-kernel launch.  "own" is the operand a workgroup keeps in registers
+// (queries when OWN_ROW, negatives otherwise); "str" is the operand streamed through LDS.
+struct KgeBlockArgs {
+    const void *own, *own2;        // [own_pad][dp]; own2: TransH normals when OWN_ROW
+    const void *str, *str2;        // [str_pad][dp]; str2: TransH normals when !OWN_ROW
+    const void *strT, *strT2;      // [dp][strT_ld] transposed stream operand(s), GRAD only
+    int64_t strT_ld;               // elements
+    const KgeRowInfo *rowinfo;     // [Bp]
+    const float *tn;               // [Np] squared norms of the negatives
+    int32_t B, N;                  // true sizes (padding is masked)
+    int32_t dp;                    // padded dim (elements) = RB / sizeof(elem)
+    int32_t str_tiles;             // number of stream tiles in total
+    int32_t tiles_per_split;       // stream tiles handled by one workgroup
+    int32_t kind;                  // KGE_KIND_*
+    int32_t loss;                  // kge_loss_t
+    float gamma, adv_temp, c_corr; // c_corr: sampled-softmax correction c
+    // outputs
+    float *S_out;                  // SCORE: [B][N]
+    float4 *stat_part;             // STATS: [nsplit][Bp] {m, l, accL, 0}
+    float *acc_part, *acc_part2;   // GRAD: [nsplit][own_pad][dp]
+    float4 *sum_part;              // GRAD: [nsplit][own_pad] {s1, s2, s3, 0}
+    int32_t own_pad;
+    int32_t dblk0_stride;          // GRAD with a split of the output columns: blocks per z-slice
+};
+
+// launchers implemented in block_*.hip (one per element type to bound compile time per file)
+int kge_launch_block_f32(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a,
+                         int own_tiles, int nsplit, int dsplit, hipStream_t st);
+int kge_launch_block_bf16(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a,
+                          int own_tiles, int nsplit, int dsplit, hipStream_t st);

@@ -1,0 +1,29 @@
+// Host-side launchers of the row-wise kernels (implemented in prep_kernels.hip).
+#pragma once
+#include "kge_internal.h"
+
+// Device-side view of kge_model_t.
+struct KgeModelDev {
+    int32_t scorer, bf16, dim, rel_dim;
+    const void *ent, *rel, *relw;
+    int64_t ent_ld, rel_ld, relw_ld;
+};
+
+int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, int64_t hi, int64_t n,
+                      int32_t *out, hipStream_t st);
+int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
+                   int dp, void *Q, void *W, void *Q2, KgeRowInfo *rowinfo, float *pos_ws, float *pos_out,
+                   hipStream_t st);
+int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
+                    hipStream_t st);
+int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipStream_t st);
+int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma,
+                      float c_corr, float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb,
+                      float *gpos, float *loss_out, hipStream_t st);
+int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
+                  const float *acc_part, const float *acc_part2, const float4 *sum_part, int nsplit,
+                  const float *gpos, float *g_ent, float *g_rel, float *g_relw, int32_t *g_ent_idx,
+                  int32_t *g_rel_idx, hipStream_t st);
+int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N, int dp, int d,
+                    int dist_kind, const void *T, bool bf16, const int32_t *neg, float *g_neg, int32_t *g_neg_idx,
+                    hipStream_t st);

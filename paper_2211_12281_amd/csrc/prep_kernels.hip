@@ -1,0 +1,497 @@
+// Row-wise kernels around the block kernel: negative ids, gather + query build + positive score,
+// gather of the shared negatives, transposes, per-row loss finish, chain rule of the query build.
+#include "prep_kernels.h"
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void kge_philox_round(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c[0]), lo0 = 0xD2511F53u * c[0];
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c[2]), lo1 = 0xCD9E8D57u * c[2];
+    const uint32_t n0 = hi1 ^ c[1] ^ k0, n2 = hi0 ^ c[3] ^ k1;
+    c[0] = n0; c[1] = lo1; c[2] = n2; c[3] = lo0;
+}
+
+__global__ void kge_negatives_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t step, uint32_t tag,
+                                     int64_t lo, uint64_t range, int64_t n, int32_t *out) {
+    // one thread per Philox block = two ids
+    const int64_t blk = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (2 * blk >= n) return;
+    uint32_t c[4] = { (uint32_t)blk, (uint32_t)((uint64_t)blk >> 32), step, tag };
+    uint32_t k0 = seed_lo, k1 = seed_hi;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        kge_philox_round(c, k0, k1);
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    const uint64_t x0 = ((uint64_t)c[1] << 32) | c[0], x1 = ((uint64_t)c[3] << 32) | c[2];
+    out[2 * blk] = (int32_t)(lo + (int64_t)__umul64hi(x0, range));
+    if (2 * blk + 1 < n) out[2 * blk + 1] = (int32_t)(lo + (int64_t)__umul64hi(x1, range));
+}
+
+int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, int64_t hi, int64_t n,
+                      int32_t *out, hipStream_t st) {
+    const int64_t blocks = (n + 1) / 2;
+    const int grid = (int)((blocks + 255) / 256);
+    hipLaunchKernelGGL(kge_negatives_kernel, dim3(grid), dim3(256), 0, st, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), (uint32_t)step, tag, lo, (uint64_t)(hi - lo), n, out);
+    return kge_launch_status();
+}
+
+// ---------------------------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------------------------
+template <bool BF16> struct El;
+template <> struct El<true> {
+    using T = __bf16;
+    static __device__ __forceinline__ float ld(const void *p, int64_t i) { return (float)((const __bf16 *)p)[i]; }
+    static __device__ __forceinline__ void st(void *p, int64_t i, float v) { ((__bf16 *)p)[i] = (__bf16)v; }
+    static __device__ __forceinline__ float rnd(float v) { return (float)(__bf16)v; }
+};
+template <> struct El<false> {
+    using T = float;
+    static __device__ __forceinline__ float ld(const void *p, int64_t i) { return ((const float *)p)[i]; }
+    static __device__ __forceinline__ void st(void *p, int64_t i, float v) { ((float *)p)[i] = v; }
+    static __device__ __forceinline__ float rnd(float v) { return v; }
+};
+
+__device__ __forceinline__ float kge_wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+constexpr int KGE_MAXJ = 8;   // dim <= 512 -> at most 8 columns per lane
+
+// The query of triple b (fp32, unrounded), spread over a wave: lane holds columns lane + 64*k.
+// Returns through references what the callers need besides q.
+template <bool BF16>
+struct KgeRowCtx {
+    float h[KGE_MAXJ], r[KGE_MAXJ], w[KGE_MAXJ], q[KGE_MAXJ];
+    float wh;      // w_hat . h     (TransH)
+    float wnorm;   // ||w|| clamped (TransH)
+};
+
+// Builds q for one triple.  For complex scorers lane column j < d/2 pairs with j + d/2, which is a
+// different lane/slot in general, so partner values are fetched from memory again (L1/L2 hits).
+template <bool BF16>
+__device__ __forceinline__ void kge_build_query(const KgeModelDev &m, int hi, int ri, int lane,
+                                                KgeRowCtx<BF16> &cx) {
+    const int d = m.dim, c = d >> 1;
+    const char *hrow = (const char *)m.ent;  // element indexing below
+    const int64_t hoff = (int64_t)hi * m.ent_ld, roff = (int64_t)ri * m.rel_ld, woff = (int64_t)ri * m.relw_ld;
+    (void)hrow;
+    float wn2 = 0.f, whp = 0.f;
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        cx.h[k] = cx.r[k] = cx.w[k] = cx.q[k] = 0.f;
+        if (j >= d) continue;
+        const float hj = El<BF16>::ld(m.ent, hoff + j);
+        cx.h[k] = hj;
+        switch (m.scorer) {
+        case KGE_TRANSE: { float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj; cx.q[k] = hj + rj; break; }
+        case KGE_DISTMULT: { float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj; cx.q[k] = hj * rj; break; }
+        case KGE_COMPLEX: {
+            float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj;
+            if (j < c) {
+                float him = El<BF16>::ld(m.ent, hoff + j + c), rim = El<BF16>::ld(m.rel, roff + j + c);
+                cx.q[k] = hj * rj - him * rim;                         // q_re = h_re r_re - h_im r_im
+            } else {
+                float hre = El<BF16>::ld(m.ent, hoff + j - c), rre = El<BF16>::ld(m.rel, roff + j - c);
+                cx.q[k] = hre * rj + hj * rre;                         // q_im = h_re r_im + h_im r_re
+            }
+            break;
+        }
+        case KGE_ROTATE: {
+            const int jj = j < c ? j : j - c;
+            float ph = El<BF16>::ld(m.rel, roff + jj); cx.r[k] = ph;
+            float sn, cs; sincosf(ph, &sn, &cs);
+            if (j < c) { float him = El<BF16>::ld(m.ent, hoff + j + c); cx.q[k] = hj * cs - him * sn; }
+            else       { float hre = El<BF16>::ld(m.ent, hoff + j - c); cx.q[k] = hre * sn + hj * cs; }
+            break;
+        }
+        case KGE_TRANSH: {
+            float rj = El<BF16>::ld(m.rel, roff + j), wj = El<BF16>::ld(m.relw, woff + j);
+            cx.r[k] = rj; cx.w[k] = wj; wn2 += wj * wj; whp += wj * hj;
+            break;
+        }
+        }
+    }
+    cx.wh = 0.f; cx.wnorm = 1.f;
+    if (m.scorer == KGE_TRANSH) {
+        wn2 = kge_wave_sum(wn2); whp = kge_wave_sum(whp);
+        const float nrm = fmaxf(sqrtf(wn2), 1e-12f), inv = 1.f / nrm;
+        cx.wnorm = nrm; cx.wh = whp * inv;
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) {
+            cx.w[k] *= inv;                                           // unit normal
+            cx.q[k] = (lane + 64 * k < d) ? cx.h[k] - cx.wh * cx.w[k] + cx.r[k] : 0.f;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gather + query build + positive score (one wave per triple; rows >= B are written as zeros)
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t,
+                                  int B, int Bp, int dp, void *Q, void *W, void *Q2, KgeRowInfo *rowinfo,
+                                  float *pos_ws, float *pos_out) {
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (b >= Bp) return;
+    if (b >= B) {
+        for (int j = lane; j < dp; j += 64) {
+            El<BF16>::st(Q, (int64_t)b * dp + j, 0.f);
+            if (W) El<BF16>::st(W, (int64_t)b * dp + j, 0.f);
+            if (Q2) El<BF16>::st(Q2, (int64_t)b * dp + j, 0.f);
+        }
+        if (lane == 0) { rowinfo[b] = KgeRowInfo{0.f, 0.f, 0.f, 0.f}; if (pos_ws) pos_ws[b] = 0.f; }
+        return;
+    }
+    KgeRowCtx<BF16> cx;
+    kge_build_query<BF16>(m, h[b], r[b], lane, cx);
+    const int d = m.dim;
+    const int64_t toff = (int64_t)t[b] * m.ent_ld;
+    float qn = 0.f, cq = 0.f, wn = 0.f, s_pos = 0.f, wt = 0.f;
+    float tv[KGE_MAXJ];
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        tv[k] = j < d ? El<BF16>::ld(m.ent, toff + j) : 0.f;
+        const float qr = El<BF16>::rnd(cx.q[k]), wr = El<BF16>::rnd(cx.w[k]);
+        qn += qr * qr; cq += wr * qr; wn += wr * wr;          // norms of what the matrix cores will see
+        wt += cx.w[k] * tv[k];
+        if (j < dp) {
+            El<BF16>::st(Q, (int64_t)b * dp + j, cx.q[k]);
+            if (W) El<BF16>::st(W, (int64_t)b * dp + j, cx.w[k]);
+        }
+    }
+    qn = kge_wave_sum(qn);
+    if (m.scorer == KGE_TRANSH) { cq = kge_wave_sum(cq); wn = kge_wave_sum(wn); wt = kge_wave_sum(wt); }
+    if (Q2) {   // TransH: q - c * w_hat, the operand of the negatives' gradient contraction
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) {
+            const int j = lane + 64 * k;
+            if (j < dp) El<BF16>::st(Q2, (int64_t)b * dp + j, El<BF16>::rnd(cx.q[k]) - cq * El<BF16>::rnd(cx.w[k]));
+        }
+    }
+    // positive score by the direct formula (Table 2), fp32
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        if (m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX) s_pos += cx.q[k] * tv[k];
+        else {
+            float x = cx.q[k] - tv[k];
+            if (m.scorer == KGE_TRANSH) x += wt * cx.w[k];
+            s_pos += x * x;
+        }
+    }
+    s_pos = kge_wave_sum(s_pos);
+    if (!(m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX)) s_pos = -sqrtf(s_pos);
+    if (lane == 0) {
+        rowinfo[b] = KgeRowInfo{qn, cq, 0.f, wn};
+        if (pos_ws) pos_ws[b] = s_pos;
+        if (pos_out) pos_out[b] = s_pos;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gather of the shared negatives: T[n] = ent[neg[n]], tn[n] = ||T[n]||^2 (zeros past N)
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (n >= Np) return;
+    float s = 0.f;
+    const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
+    for (int j = lane; j < dp; j += 64) {
+        float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
+        El<BF16>::st(T, (int64_t)n * dp + j, v);
+        s += v * v;
+    }
+    s = kge_wave_sum(s);
+    if (lane == 0) tn[n] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// transpose: src [R][C] -> dst [C][R]   (R, C multiples of 32; elements of 2 or 4 bytes)
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void kge_transpose_kernel(const T *src, T *dst, int R, int C) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 256 threads: 32 x 8
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    for (int i = ty; i < 32; i += 8) tile[i][tx] = src[(int64_t)(r0 + i) * C + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) dst[(int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-row finish of the loss (Section 3.1): combines the split statistics with the positive score
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float kge_softplus_f(float y) { return fmaxf(y, 0.f) + log1pf(expf(-fabsf(y))); }
+
+__global__ void kge_rowfinish_kernel(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss,
+                                     float gamma, float c_corr, float scale, const float *pos,
+                                     KgeRowInfo *rowinfo, float *lossb, float *gpos) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= Bp) return;
+    if (b >= B) { lossb[b] = 0.f; gpos[b] = 0.f; rowinfo[b].K = -INFINITY; return; }
+    float m = -INFINITY, l = 0.f, ac = 0.f;
+    for (int s = 0; s < nsplit; ++s) {                      // fixed order
+        const float4 p = stat_part[(size_t)s * Bp + b];
+        if (p.x == -INFINITY) continue;
+        const float mn = fmaxf(m, p.x);
+        const float r0 = expf(m - mn), r1 = expf(p.x - mn);
+        l = l * r0 + p.y * r1; ac = ac * r0 + p.z * r1; m = mn;
+    }
+    const float fp = pos[b];
+    float L, gp, K;
+    if (loss == KGE_LOGSIGMOID) {
+        L = kge_softplus_f(-(gamma + fp));
+        const float e = expf(-fabsf(gamma + fp));           // sigma(-(gamma+fp)), stable
+        gp = -((gamma + fp) >= 0.f ? e / (1.f + e) : 1.f / (1.f + e)) * scale;
+        if (N > 0 && l > 0.f) { L += ac / l; K = -m - logf(l) + logf(scale); } else K = -INFINITY;
+    } else {
+        if (N > 0 && l > 0.f) {
+            const float M = fmaxf(m, fp);
+            const float Z = l * expf(m - M) + expf(fp - M);
+            const float lse = M + logf(Z);
+            L = lse - fp;
+            gp = (expf(fp - lse) - 1.f) * scale;
+            K = c_corr - lse + logf(scale);
+        } else { L = 0.f; gp = 0.f; K = -INFINITY; }
+    }
+    lossb[b] = L; gpos[b] = gp; rowinfo[b].K = K;
+}
+
+// loss_out = scale * sum_b lossb[b], one workgroup, fixed summation tree
+__global__ void kge_loss_reduce_kernel(const float *lossb, int B, float scale, float *loss_out) {
+    __shared__ double sh[256];
+    double s = 0.0;
+    for (int b = threadIdx.x; b < B; b += 256) s += (double)lossb[b];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss_out = (float)(sh[0] * (double)scale);
+}
+
+// ---------------------------------------------------------------------------------------------
+// chain rule of the query build + positive triple: one wave per triple
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t, int B,
+                                 int Bp, int dp, const float *acc_part, const float *acc_part2,
+                                 const float4 *sum_part, int nsplit, const float *gpos, float *g_ent,
+                                 float *g_rel, float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx) {
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (b >= B) return;
+    const int d = m.dim, c = d >> 1;
+    KgeRowCtx<BF16> cx;
+    kge_build_query<BF16>(m, h[b], r[b], lane, cx);
+    const int64_t toff = (int64_t)t[b] * m.ent_ld;
+    const float gp = gpos[b];
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    for (int s = 0; s < nsplit; ++s) { const float4 p = sum_part[(size_t)s * Bp + b]; s1 += p.x; s2 += p.y; s3 += p.z; }
+    float a1[KGE_MAXJ], a2[KGE_MAXJ], tv[KGE_MAXJ], dq[KGE_MAXJ], dtp[KGE_MAXJ];
+    float wt = 0.f;
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        a1[k] = a2[k] = tv[k] = 0.f;
+        if (j >= d) continue;
+        for (int s = 0; s < nsplit; ++s) {
+            a1[k] += acc_part[((size_t)s * Bp + b) * dp + j];
+            if (m.scorer == KGE_TRANSH) a2[k] += acc_part2[((size_t)s * Bp + b) * dp + j];
+        }
+        tv[k] = El<BF16>::ld(m.ent, toff + j);
+        wt += cx.w[k] * tv[k];
+    }
+    const bool mult = m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX;
+    float dwh[KGE_MAXJ];
+    if (mult) {
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) { dq[k] = a1[k] + gp * tv[k]; dtp[k] = gp * cx.q[k]; }
+    } else {
+        if (m.scorer == KGE_TRANSH) wt = kge_wave_sum(wt);
+        float u[KGE_MAXJ], d2 = 0.f;
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) {
+            u[k] = cx.q[k] - tv[k] + (m.scorer == KGE_TRANSH ? wt * cx.w[k] : 0.f);
+            d2 += u[k] * u[k];
+        }
+        d2 = kge_wave_sum(d2);
+        const float dist = sqrtf(d2);
+        const float ap = dist > 0.f ? -gp / dist : 0.f;            // gp * df/du = ap * u
+        float aw = 0.f, cq = 0.f;
+        if (m.scorer == KGE_TRANSH) {
+#pragma unroll
+            for (int k = 0; k < KGE_MAXJ; ++k) { aw += ap * u[k] * cx.w[k]; cq += cx.w[k] * cx.q[k]; }
+            aw = kge_wave_sum(aw); cq = kge_wave_sum(cq);
+        }
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) {
+            const float apu = ap * u[k];
+            dq[k] = a1[k] - s1 * cx.q[k] + apu;
+            dtp[k] = -apu;
+            if (m.scorer == KGE_TRANSH) {
+                dq[k] -= s2 * cx.w[k];
+                dtp[k] = -(apu - aw * cx.w[k]);
+                // gradient with respect to the unit normal: negatives' part + positive's part
+                dwh[k] = -cq * a1[k] - s2 * cx.q[k] + a2[k] - s3 * cx.w[k] + aw * tv[k] + wt * apu;
+            }
+        }
+    }
+    // dq -> dh, dr (and dw)
+    float wdq = 0.f;
+    if (m.scorer == KGE_TRANSH) {
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) wdq += cx.w[k] * dq[k];
+        wdq = kge_wave_sum(wdq);
+        float wdw = 0.f;
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) { dwh[k] += -cx.wh * dq[k] - wdq * cx.h[k]; wdw += cx.w[k] * dwh[k]; }
+        wdw = kge_wave_sum(wdw);
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) dwh[k] = (dwh[k] - cx.w[k] * wdw) / cx.wnorm;
+    }
+    float *gh = g_ent + (int64_t)b * d, *gt = g_ent + (int64_t)(B + b) * d;
+    const int k_rel = m.rel_dim;
+    float *gr = g_rel + (int64_t)b * k_rel;
+    // complex scorers need the partner component of dq, held by another lane: exchange through LDS
+    if (m.scorer == KGE_COMPLEX || m.scorer == KGE_ROTATE) {
+        __shared__ float xch[4][KGE_MAXJ * 64];
+        float *tmp = xch[threadIdx.x >> 6];
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) tmp[lane + 64 * k] = dq[k];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) {
+            const int j = lane + 64 * k;
+            if (j >= d) continue;
+            const bool re = j < c;
+            const int jp = re ? j + c : j - c;
+            const float dq_re = re ? dq[k] : tmp[jp], dq_im = re ? tmp[jp] : dq[k];
+            const float h_re = re ? cx.h[k] : El<BF16>::ld(m.ent, (int64_t)h[b] * m.ent_ld + jp);
+            const float h_im = re ? El<BF16>::ld(m.ent, (int64_t)h[b] * m.ent_ld + jp) : cx.h[k];
+            if (m.scorer == KGE_COMPLEX) {
+                const float r_re = re ? cx.r[k] : El<BF16>::ld(m.rel, (int64_t)r[b] * m.rel_ld + jp);
+                const float r_im = re ? El<BF16>::ld(m.rel, (int64_t)r[b] * m.rel_ld + jp) : cx.r[k];
+                gh[j] = re ? dq_re * r_re + dq_im * r_im : -dq_re * r_im + dq_im * r_re;
+                gr[j] = re ? dq_re * h_re + dq_im * h_im : -dq_re * h_im + dq_im * h_re;
+            } else {
+                float sn, cs; sincosf(cx.r[k], &sn, &cs);
+                gh[j] = re ? dq_re * cs + dq_im * sn : -dq_re * sn + dq_im * cs;
+                if (re) {
+                    const float q_re = cx.q[k], q_im = h_re * sn + h_im * cs;
+                    gr[j] = -dq_re * q_im + dq_im * q_re;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        if (j >= d) continue;
+        gt[j] = dtp[k];
+        switch (m.scorer) {
+        case KGE_TRANSE: gh[j] = dq[k]; gr[j] = dq[k]; break;
+        case KGE_DISTMULT: gh[j] = dq[k] * cx.r[k]; gr[j] = dq[k] * cx.h[k]; break;
+        case KGE_TRANSH: gh[j] = dq[k] - wdq * cx.w[k]; gr[j] = dq[k]; g_relw[(int64_t)b * d + j] = dwh[k]; break;
+        default: break;
+        }
+    }
+    if (lane == 0) { g_ent_idx[b] = h[b]; g_ent_idx[B + b] = t[b]; g_rel_idx[b] = r[b]; }
+}
+
+// gradient rows of the shared negatives: sum of the split partials minus colsum * t (distances)
+template <bool BF16>
+__global__ void kge_tfinish_kernel(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N,
+                                   int dp, int d, int dist_kind, const void *T, const int32_t *neg,
+                                   float *g_neg, int32_t *g_neg_idx) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (n >= N) return;
+    float cs = 0.f;
+    for (int s = 0; s < nsplit; ++s) cs += sumT_part[(size_t)s * Np + n].x;
+    for (int j = lane; j < d; j += 64) {
+        float v = 0.f;
+        for (int s = 0; s < nsplit; ++s) v += accT_part[((size_t)s * Np + n) * dp + j];
+        if (dist_kind) v -= cs * El<BF16>::ld(T, (int64_t)n * dp + j);
+        g_neg[(int64_t)n * d + j] = v;
+    }
+    if (lane == 0) g_neg_idx[n] = neg[n];
+}
+
+__global__ void kge_zero_rows_kernel(float *p, int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// host launchers
+// ---------------------------------------------------------------------------------------------
+int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
+                   int dp, void *Q, void *W, void *Q2, KgeRowInfo *rowinfo, float *pos_ws, float *pos_out,
+                   hipStream_t st) {
+    const int grid = (Bp + 3) / 4;
+    if (grid == 0) return KGE_OK;
+    if (m.bf16) hipLaunchKernelGGL(kge_qbuild_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, rowinfo, pos_ws, pos_out);
+    else        hipLaunchKernelGGL(kge_qbuild_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, rowinfo, pos_ws, pos_out);
+    return kge_launch_status();
+}
+
+int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, hipStream_t st) {
+    const int grid = (Np + 3) / 4;
+    if (grid == 0) return KGE_OK;
+    if (m.bf16) hipLaunchKernelGGL(kge_tgather_kernel<true>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn);
+    else        hipLaunchKernelGGL(kge_tgather_kernel<false>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn);
+    return kge_launch_status();
+}
+
+int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipStream_t st) {
+    if (R == 0 || C == 0) return KGE_OK;
+    dim3 grid(C / 32, R / 32);
+    if (bf16) hipLaunchKernelGGL(kge_transpose_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)src, (uint16_t *)dst, R, C);
+    else      hipLaunchKernelGGL(kge_transpose_kernel<uint32_t>, grid, dim3(256), 0, st, (const uint32_t *)src, (uint32_t *)dst, R, C);
+    return kge_launch_status();
+}
+
+int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma,
+                      float c_corr, float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb,
+                      float *gpos, float *loss_out, hipStream_t st) {
+    if (Bp > 0)
+        hipLaunchKernelGGL(kge_rowfinish_kernel, dim3((Bp + 255) / 256), dim3(256), 0, st, stat_part, nsplit, Bp, B, N,
+                           loss, gamma, c_corr, scale, pos, rowinfo, lossb, gpos);
+    hipLaunchKernelGGL(kge_loss_reduce_kernel, dim3(1), dim3(256), 0, st, lossb, B, scale, loss_out);
+    return kge_launch_status();
+}
+
+int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
+                  const float *acc_part, const float *acc_part2, const float4 *sum_part, int nsplit,
+                  const float *gpos, float *g_ent, float *g_rel, float *g_relw, int32_t *g_ent_idx,
+                  int32_t *g_rel_idx, hipStream_t st) {
+    if (B == 0) return KGE_OK;
+    const int grid = (B + 3) / 4;
+    if (m.bf16) hipLaunchKernelGGL(kge_chain_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
+    else        hipLaunchKernelGGL(kge_chain_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
+    return kge_launch_status();
+}
+
+int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N, int dp, int d,
+                    int dist_kind, const void *T, bool bf16, const int32_t *neg, float *g_neg, int32_t *g_neg_idx,
+                    hipStream_t st) {
+    if (N == 0) return KGE_OK;
+    const int grid = (N + 3) / 4;
+    if (bf16) hipLaunchKernelGGL(kge_tfinish_kernel<true>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx);
+    else      hipLaunchKernelGGL(kge_tfinish_kernel<false>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx);
+    return kge_launch_status();
+}

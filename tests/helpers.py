@@ -39,3 +39,42 @@ def small_graph(scorer, n_ent=1000, n_rel=10, dim=32, B=64, N=64, seed=ks.BASE_S
     t = ks.uniform_ids(g, 0, n_ent, B)
     neg = ks.uniform_ids(ks.rng(seed, ks.TAG_NEG), 0, n_ent, N)
     return dict(ent=ent, rel=rel, relw=relw, h=h, r=r, t=t, neg=neg)
+
+
+# ---------------------------------------------------------------------------------------------
+# GPU-side helpers (imported lazily by the gpu tests)
+# ---------------------------------------------------------------------------------------------
+def to_dev(a, bf16=False):
+    """numpy fp32 array -> device tensor; for bf16 the values must already be bf16-representable."""
+    import torch
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32 and bf16:
+        bits = ks.f32_to_bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def make_case(scorer, n_ent, n_rel, dim, B, N, bf16, seed=ks.BASE_SEED, amp=0.1, zipf=False):
+    """Tables (host fp32 values, already rounded to bf16 when bf16=True) and a micro-batch."""
+    G = small_graph(scorer, n_ent, n_rel, dim, B, N, seed=seed, amp=amp)
+    if zipf:
+        z = ks.ZipfIds(n_ent, 1.1)
+        g = ks.rng(seed, ks.TAG_BATCH, 1)
+        G["h"], G["t"] = z.draw(g, B), z.draw(g, B)
+    if bf16:
+        for k in ("ent", "rel", "relw"):
+            if G[k] is not None:
+                G[k] = ks.round_to_bf16(G[k])
+    return G
+
+
+def gpu_model(scorer, G, bf16):
+    import paper_2211_12281_amd as kge
+    return kge.Model(scorer, to_dev(G["ent"], bf16), to_dev(G["rel"], bf16), to_dev(G["relw"], bf16))
+
+
+def dev_idx(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()

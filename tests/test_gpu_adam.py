@@ -1,0 +1,122 @@
+"""kge_sparse_adam against the oracle: duplicate-aware scatter-add and the lazy Adam step."""
+import numpy as np
+import pytest
+import torch
+
+import kge_synth as ks
+from helpers import RTOL_F32, norm_err
+
+pytestmark = pytest.mark.gpu
+F = np.float32
+
+
+def update_err_ok(got_new, old, ref_new):
+    """The UPDATE theta_new - theta_old must match the oracle's to RTOL_F32 of its largest entry, plus
+    the rounding of the fp32 master itself: the kernel stores theta_new in fp32 (half an ulp of
+    theta, which can exceed 1e-5 of a 1e-3-sized update), the oracle keeps it in fp64."""
+    got_upd = got_new.astype(np.float64) - old
+    ref_upd = ref_new - old
+    allowed = RTOL_F32 * np.max(np.abs(ref_upd)) + np.spacing(np.abs(got_new).astype(F)).astype(np.float64)
+    return bool(np.all(np.abs(got_upd - ref_upd) <= allowed))
+
+
+def _state(n_rows, d, seed, warm):
+    g = np.random.default_rng(seed)
+    theta = g.normal(size=(n_rows, d)).astype(F) * F(0.1)
+    if warm:
+        m = (g.normal(size=(n_rows, d)) * 1e-3).astype(F)
+        v = (g.normal(size=(n_rows, d)) ** 2 * 1e-5).astype(F)
+    else:
+        m = np.zeros((n_rows, d), F); v = np.zeros((n_rows, d), F)
+    return theta, m, v
+
+
+def _check(orc, n_rows, d, M, step, warm, shadow, zipf=True, seed=0, lr=1e-3):
+    import paper_2211_12281_amd as kge
+    theta, m, v = _state(n_rows, d, seed, warm)
+    g = np.random.default_rng(seed + 100)
+    idx = ks.ZipfIds(n_rows, 1.1).draw(g, M) if zipf else g.integers(0, n_rows, M).astype(np.int32)
+    grads = (g.normal(size=(M, d)) * 1e-2).astype(F)
+    b1, b2, eps = float(F(0.9)), float(F(0.999)), float(F(1e-8))
+    lr = float(F(lr))
+    dth, dm, dv = [torch.from_numpy(a.copy()).cuda() for a in (theta, m, v)]
+    dsh = torch.zeros((n_rows, d), dtype=torch.bfloat16, device="cuda") if shadow else None
+    kge.sparse_adam(dth, dsh, dm, dv, torch.from_numpy(idx).cuda(), torch.from_numpy(grads).cuda(), lr, b1, b2, eps, step)
+    rth, rm, rv, touched = orc.sparse_adam(theta, m, v, idx, grads, lr, b1, b2, eps, step)
+    gth, gm, gv = dth.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy()
+    # untouched rows: bit-identical to the input
+    assert np.array_equal(gth[~touched], theta[~touched]) and np.array_equal(gm[~touched], m[~touched])
+    assert np.array_equal(gv[~touched], v[~touched])
+    if M == 0:
+        return
+    # touched rows: compare the UPDATE, not the value (lr would hide errors otherwise)
+    assert update_err_ok(gth[touched], theta[touched], rth[touched])
+    assert norm_err(gm[touched], rm[touched]) <= RTOL_F32
+    assert norm_err(gv[touched], rv[touched]) <= RTOL_F32
+    if shadow:
+        sh = dsh.view(torch.int16).cpu().numpy().view(np.uint16)
+        # the shadow is RNE(theta_new) of the fp32 master the kernel itself wrote: bit-exact
+        assert np.array_equal(sh[touched], orc.bf16_rne(gth[touched]))
+        assert np.all(sh[~touched] == 0)
+        ref_sh = ks.bf16_bits_to_f32(orc.bf16_rne(rth[touched].astype(F)))
+        assert norm_err(ks.bf16_bits_to_f32(sh[touched]), ref_sh) <= 2.0 ** -7
+
+
+@pytest.mark.parametrize("n_rows,d,M", [(1000, 32, 192), (50000, 256, 24576), (300, 128, 5000), (70000, 64, 1),
+                                         (1 << 20, 16, 3000), (40, 4, 1025)])
+def test_update_matches_oracle(orc, n_rows, d, M):
+    _check(orc, n_rows, d, M, step=7, warm=True, shadow=False)
+
+
+def test_first_step_from_zero_state(orc):
+    _check(orc, 2000, 32, 500, step=1, warm=False, shadow=False, zipf=False)
+
+
+def test_bf16_shadow(orc):
+    _check(orc, 20000, 256, 6000, step=3, warm=True, shadow=True)
+
+
+def test_all_indices_equal_and_empty(orc):
+    import paper_2211_12281_amd as kge
+    theta, m, v = _state(50, 64, 3, True)
+    idx = np.full(700, 17, np.int32)
+    grads = (np.random.default_rng(5).normal(size=(700, 64)) * 1e-2).astype(F)
+    dth, dm, dv = [torch.from_numpy(a.copy()).cuda() for a in (theta, m, v)]
+    kge.sparse_adam(dth, None, dm, dv, torch.from_numpy(idx).cuda(), torch.from_numpy(grads).cuda(), 1e-3, step=2)
+    rth, rm, rv, touched = orc.sparse_adam(theta, m, v, idx, grads, float(F(1e-3)), float(F(0.9)), float(F(0.999)),
+                                           float(F(1e-8)), 2)
+    assert touched.sum() == 1
+    assert update_err_ok(dth.cpu().numpy()[17], theta[17], rth[17])
+    _check(orc, 100, 8, 0, step=1, warm=True, shadow=False)
+
+
+def test_padded_row_stride(orc):
+    """Tables whose row stride exceeds dim (ld > dim): padding columns stay untouched."""
+    import paper_2211_12281_amd as kge
+    n_rows, d, ld, M = 500, 24, 32, 300
+    g = np.random.default_rng(11)
+    full = [g.normal(size=(n_rows, ld)).astype(F) * F(0.1) for _ in range(2)] + [(g.normal(size=(n_rows, ld)) ** 2 * 1e-4).astype(F)]
+    dev = [torch.from_numpy(a.copy()).cuda() for a in full]
+    idx = g.integers(0, n_rows, M).astype(np.int32)
+    grads = (g.normal(size=(M, d)) * 1e-2).astype(F)
+    kge.sparse_adam(dev[0][:, :d], None, dev[1][:, :d], dev[2][:, :d], torch.from_numpy(idx).cuda(),
+                    torch.from_numpy(grads).cuda(), 1e-3, step=4)
+    rth, _, _, touched = orc.sparse_adam(full[0][:, :d], full[1][:, :d], full[2][:, :d], idx, grads, float(F(1e-3)),
+                                         float(F(0.9)), float(F(0.999)), float(F(1e-8)), 4)
+    got = dev[0].cpu().numpy()
+    assert np.array_equal(got[:, d:], full[0][:, d:])
+    assert update_err_ok(got[touched, :d], full[0][touched, :d], rth[touched])
+
+
+def test_result_does_not_depend_on_scheduling(orc):
+    import paper_2211_12281_amd as kge
+    theta, m, v = _state(3000, 64, 9, True)
+    g = np.random.default_rng(10)
+    idx = ks.ZipfIds(3000, 1.1).draw(g, 8000)
+    grads = (g.normal(size=(8000, 64)) * 1e-2).astype(F)
+    outs = []
+    for _ in range(3):
+        dth, dm, dv = [torch.from_numpy(a.copy()).cuda() for a in (theta, m, v)]
+        kge.sparse_adam(dth, None, dm, dv, torch.from_numpy(idx).cuda(), torch.from_numpy(grads).cuda(), 1e-3, step=5)
+        outs.append(dth.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])

@@ -1,0 +1,91 @@
+"""kge_loss_bwd against the oracle: loss value and every gradient row, all scorers, both losses."""
+import numpy as np
+import pytest
+
+from helpers import RTOL_BF16, RTOL_F32, dev_idx, gpu_model, make_case, norm_err
+
+pytestmark = pytest.mark.gpu
+SCORERS = ["transe", "transh", "rotate", "distmult", "complex"]
+
+
+def _kw(scorer, loss, n_ent):
+    if loss == "sampled_softmax":
+        return dict(n_ent_for_c=n_ent)
+    if scorer in ("distmult", "complex"):
+        return dict(gamma=0.0, adv_temp=0.0)
+    return dict(gamma=2.0, adv_temp=0.8)
+
+
+def _compare(orc, scorer, loss, G, bf16, n_ent, kw=None, loss_scale=None):
+    import paper_2211_12281_amd as kge
+    kw = kw or _kw(scorer, loss, n_ent)
+    model = gpu_model(scorer, G, bf16)
+    out = kge.loss_bwd(model, loss, dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]),
+                       loss_scale=loss_scale or 0.0, **kw)
+    ref = orc.loss_bwd(scorer, loss, G["ent"], G["rel"], G["relw"], G["h"], G["r"], G["t"], G["neg"],
+                       loss_scale=loss_scale, **kw)
+    tol = RTOL_BF16 if bf16 else RTOL_F32
+    errs = {"loss": abs(out["loss"].item() - ref["loss"]) / max(abs(ref["loss"]), 1e-30)}
+    for k in ("g_ent", "g_rel", "g_relw"):
+        if ref[k] is not None and ref[k].size:
+            errs[k] = norm_err(out[k].cpu().numpy(), ref[k])
+    # heads, positive tails and negatives separately: a small block must not hide behind a large one
+    B, N = len(G["h"]), len(G["neg"])
+    ge = out["g_ent"].cpu().numpy()
+    for name, sl in (("g_head", slice(0, B)), ("g_tail", slice(B, 2 * B)), ("g_neg", slice(2 * B, 2 * B + N))):
+        if ref["g_ent"][sl].size:
+            errs[name] = norm_err(ge[sl], ref["g_ent"][sl])
+    assert np.array_equal(out["g_ent_idx"].cpu().numpy(), ref["g_ent_idx"])
+    assert np.array_equal(out["g_rel_idx"].cpu().numpy(), ref["g_rel_idx"])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (bad, errs)
+    return errs
+
+
+@pytest.mark.parametrize("scorer", SCORERS)
+@pytest.mark.parametrize("loss", ["logsigmoid", "sampled_softmax"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_loss_and_gradients_match_oracle(orc, scorer, loss, bf16):
+    amp = 0.5 if scorer in ("distmult", "complex") else 0.1
+    G = make_case(scorer, 4000, 12, 64, 200, 333, bf16, amp=amp, zipf=True)
+    _compare(orc, scorer, loss, G, bf16, 4000)
+
+
+@pytest.mark.parametrize("scorer,dim,bf16", [("complex", 256, True), ("transe", 256, False), ("distmult", 128, False),
+                                             ("transh", 128, False), ("transh", 256, True), ("rotate", 256, True),
+                                             ("distmult", 32, False), ("complex", 512, True)])
+def test_other_row_sizes(orc, scorer, dim, bf16):
+    G = make_case(scorer, 3000, 9, dim, 150, 260, bf16, amp=0.3 if scorer in ("distmult", "complex") else 0.1)
+    _compare(orc, scorer, "sampled_softmax", G, bf16, 3000)
+    _compare(orc, scorer, "logsigmoid", G, bf16, 3000)
+
+
+@pytest.mark.parametrize("scorer", ["transe", "complex"])
+def test_edge_shapes(orc, scorer):
+    for (B, N) in [(1, 1), (3, 0), (130, 1), (1, 130)]:
+        G = make_case(scorer, 500, 4, 32, B, N, False, amp=0.3)
+        for loss in ("logsigmoid", "sampled_softmax"):
+            _compare(orc, scorer, loss, G, False, 500)
+    G = make_case(scorer, 500, 4, 32, 20, 30, False, amp=0.3)
+    _compare(orc, scorer, "logsigmoid", G, False, 500, loss_scale=0.37)
+
+
+def test_tiny_distmult_training_config(orc):
+    """1,000 entities, 10 relations, dim 32 fp32, N(0, 0.1^2), B = N = 64, log-sigmoid, margin 0."""
+    import kge_synth as ks
+    from helpers import small_graph
+    G = small_graph("distmult", 1000, 10, 32, 64, 64, normal=True)
+    G["neg"] = orc.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, 0, 1000, 64)
+    _compare(orc, "distmult", "logsigmoid", G, False, 1000, kw=dict(gamma=0.0, adv_temp=0.0))
+
+
+def test_repeated_calls_are_bitwise_identical(orc):
+    import paper_2211_12281_amd as kge
+    G = make_case("complex", 4000, 12, 64, 200, 333, True, amp=0.5, zipf=True)
+    model = gpu_model("complex", G, True)
+    args = (dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]))
+    a = kge.loss_bwd(model, "sampled_softmax", *args, n_ent_for_c=4000)
+    a = {k: v.clone() for k, v in a.items() if v is not None}
+    b = kge.loss_bwd(model, "sampled_softmax", *args, n_ent_for_c=4000)
+    for k in a:
+        assert bool((a[k] == b[k]).all()), k
