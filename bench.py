@@ -1,0 +1,363 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X knowledge-graph-embedding hot path (one GPU).
+
+A "step" is one pass of the whole path over one micro-batch of seeded synthetic input that is
+already resident in HBM: sample the shared negatives, gather + score + loss + backward, and the
+duplicate-aware sparse Adam update of the entity and relation tables (workload c3, the default);
+or one scoring / ranking call for the forward-only workloads.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # dense bf16 MFMA, MI355X
+PEAK_F32_TFLOPS = 157.3       # fp32 matrix
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--scorer", default=None, help="c2 / c4: restrict to one scorer")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the entity table (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+# ---------------------------------------------------------------------------------------------
+# workloads
+# ---------------------------------------------------------------------------------------------
+class TrainWorkload:
+    """c3 / c5 / c1: forward + backward + sparse Adam on bf16 shadow / fp32 master tables."""
+
+    def __init__(self, name, P, scale):
+        import torch
+        import kge_synth as ks
+        import kge_synth.device as ksd
+        import paper_2211_12281_amd as kge
+        self.kge, self.torch, self.ks, self.P, self.name = kge, torch, ks, P, name
+        self.scorer = P["scorers"][0]
+        self.n_ent = max(1000, int(P["n_ent"] * scale))
+        self.n_rel, self.d, self.B, self.N = P["n_rel"], P["dim"], P["B"], P["N"]
+        self.bf16 = P["dtype"] == "bf16"
+        dev = "cuda"
+        t0 = time.time()
+        self.ent = torch.empty((self.n_ent, self.d), dtype=torch.float32, device=dev)
+        ksd.fill_uniform(self.ent, ks.BASE_SEED, ks.TAG_ENT, P["amp"])
+        self.ent_m = torch.zeros_like(self.ent)
+        self.ent_v = torch.zeros_like(self.ent)
+        self.ent_sh = None
+        if self.bf16:
+            self.ent_sh = torch.empty((self.n_ent, self.d), dtype=torch.bfloat16, device=dev)
+            ksd.fill_uniform(self.ent_sh, ks.BASE_SEED, ks.TAG_ENT, P["amp"])
+        rel, relw = ks.relation_tables(self.scorer, self.n_rel, self.d, ks.BASE_SEED, P["amp"])
+        self.rel = torch.from_numpy(rel).to(dev)
+        self.rel_m, self.rel_v = torch.zeros_like(self.rel), torch.zeros_like(self.rel)
+        self.rel_sh = self.rel.to(torch.bfloat16) if self.bf16 else None
+        self.relw = self.relw_m = self.relw_v = self.relw_sh = None
+        if relw is not None:
+            self.relw = torch.from_numpy(relw).to(dev)
+            self.relw_m, self.relw_v = torch.zeros_like(self.relw), torch.zeros_like(self.relw)
+            self.relw_sh = self.relw.to(torch.bfloat16) if self.bf16 else None
+        self.model = kge.Model(self.scorer, self.ent_sh if self.bf16 else self.ent,
+                               self.rel_sh if self.bf16 else self.rel, self.relw_sh if self.bf16 else self.relw)
+        # index streams: a ring of pre-drawn micro-batches, resident on the device
+        self.batches = []
+        self.host_batches = []
+        nb = 8
+        if P["ids"] == "zipf":
+            z = ks.ZipfIds(self.n_ent, P["zipf_s"])
+        for i in range(nb):
+            g = ks.rng(ks.BASE_SEED, ks.TAG_BATCH, i)
+            if name == "c5":
+                # one partition pair (i, j) per step: heads in shard i, tails (and negatives) in shard j
+                D = P["D"]; part = -(-self.n_ent // D)
+                pi, pj = (i // D) % D, i % D
+                h = self._zipf_in_range(z, g, pi * part, min(self.n_ent, (pi + 1) * part), self.B)
+                t = self._zipf_in_range(z, g, pj * part, min(self.n_ent, (pj + 1) * part), self.B)
+                lo, hi = pj * part, min(self.n_ent, (pj + 1) * part)
+            else:
+                h = z.draw(g, self.B) if P["ids"] == "zipf" else ks.uniform_ids(g, 0, self.n_ent, self.B)
+                t = z.draw(g, self.B) if P["ids"] == "zipf" else ks.uniform_ids(g, 0, self.n_ent, self.B)
+                lo, hi = 0, self.n_ent
+            if "rel_zipf_s" in P:
+                r = ks.ZipfIds(self.n_rel, P["rel_zipf_s"]).draw(g, self.B)
+            else:
+                r = ks.uniform_ids(g, 0, self.n_rel, self.B)
+            self.host_batches.append((h, r, t, lo, hi))
+            self.batches.append(tuple(torch.from_numpy(x).to(dev) for x in (h, r, t)) + (lo, hi))
+        self.neg = torch.empty(self.N, dtype=torch.int32, device=dev)
+        k = self.rel.shape[1]
+        self.out = {
+            "loss": torch.empty(1, dtype=torch.float32, device=dev),
+            "g_ent": torch.empty((2 * self.B + self.N, self.d), dtype=torch.float32, device=dev),
+            "g_ent_idx": torch.empty(2 * self.B + self.N, dtype=torch.int32, device=dev),
+            "g_rel": torch.empty((self.B, k), dtype=torch.float32, device=dev),
+            "g_relw": torch.empty((self.B, self.d), dtype=torch.float32, device=dev) if relw is not None else None,
+            "g_rel_idx": torch.empty(self.B, dtype=torch.int32, device=dev),
+        }
+        self.loss_kw = dict(gamma=P.get("gamma", 0.0), adv_temp=P.get("adv_temp", 0.0))
+        if P["loss"] == "sampled_softmax":
+            self.loss_kw = dict(n_ent_for_c=self.n_ent)
+        torch.cuda.synchronize()
+        self.setup_s = time.time() - t0
+
+    def _zipf_in_range(self, z, g, lo, hi, n):
+        out = np.empty(0, dtype=np.int32)
+        while out.size < n:                      # rejection: keeps the Zipf shape inside one shard
+            ids = z.draw(g, 4 * n * self.P["D"])
+            out = np.concatenate([out, ids[(ids >= lo) & (ids < hi)]])
+        return np.ascontiguousarray(out[:n])
+
+    def step(self, i):
+        kge, ks = self.kge, self.ks
+        h, r, t, lo, hi = self.batches[i % len(self.batches)]
+        kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=self.neg)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, self.neg, out=self.out, **self.loss_kw)
+        lr = self.P["lr"]
+        kge.sparse_adam(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent_idx"], self.out["g_ent"], lr,
+                        step=i + 1)
+        kge.sparse_adam(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel_idx"], self.out["g_rel"], lr,
+                        step=i + 1)
+        if self.relw is not None:
+            kge.sparse_adam(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_rel_idx"],
+                            self.out["g_relw"], lr, step=i + 1)
+
+    def pairs_per_step(self):
+        return self.B * (self.N + 1)
+
+    def extra(self, ms):
+        return {"triples_per_s": self.B / (ms * 1e-3)}
+
+    def mfma_flops(self, slot):
+        gemms = 2 if self.scorer == "transh" else 1
+        return 2.0 * self.B * self.N * self.d * gemms     # algorithmic: one contraction per pass (recompute is no credit)
+
+    def cpu_baseline(self, orc):
+        """Oracle forward + backward + sparse Adam on the first rows of batch 0 against all negatives."""
+        ks = self.ks
+        h, r, t, lo, hi = self.host_batches[0]
+        bs = min(self.B, 256 if self.d >= 256 else 512)
+        h, r, t = h[:bs], r[:bs], t[:bs]
+        neg = orc.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, lo, hi, self.N)
+        uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg)
+        rows = ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, uniq, self.d, self.P["amp"])
+        if self.bf16:
+            rows = ks.round_to_bf16(rows)
+        rel, relw = ks.relation_tables(self.scorer, self.n_rel, self.d, ks.BASE_SEED, self.P["amp"])
+        if self.bf16:
+            rel = ks.round_to_bf16(rel)
+            relw = None if relw is None else ks.round_to_bf16(relw)
+        kw = dict(self.loss_kw)
+        t0 = time.time()
+        out = orc.loss_bwd(self.scorer, self.P["loss"], rows, rel, relw, ch, r, ct, cn, **kw)
+        z = np.zeros_like(rows, dtype=np.float64)
+        orc.sparse_adam(rows, z, z, out["g_ent_idx"], out["g_ent"].astype(np.float32), self.P["lr"])
+        dt = time.time() - t0
+        return {"value": bs * (self.N + 1) / dt, "unit": "scored_pairs/s", "cores": orc.num_threads(),
+                "kind": "oracle", "seconds": round(dt, 2),
+                "sample": f"first {bs} of {self.B} triples of batch 0 against all {self.N} shared negatives: "
+                          f"forward + backward + sparse Adam"}
+
+
+class ScoreWorkload:
+    """c2: scoring-only forward, all five scorers in one step."""
+
+    def __init__(self, P, scale, only=None):
+        import torch
+        import kge_synth as ks
+        import kge_synth.device as ksd
+        import paper_2211_12281_amd as kge
+        self.kge, self.torch, self.ks, self.P = kge, torch, ks, P
+        self.n_ent = max(1000, int(P["n_ent"] * scale))
+        self.d, self.B, self.N = P["dim"], P["B"], P["N"]
+        self.scorers = [only] if only else P["scorers"]
+        self.ent = torch.empty((self.n_ent, self.d), dtype=torch.float32, device="cuda")
+        ksd.fill_uniform(self.ent, ks.BASE_SEED, ks.TAG_ENT, P["amp"])
+        self.models = {}
+        for s in self.scorers:
+            rel, relw = ks.relation_tables(s, P["n_rel"], self.d, ks.BASE_SEED, P["amp"])
+            self.models[s] = kge.Model(s, self.ent, torch.from_numpy(rel).cuda(),
+                                       None if relw is None else torch.from_numpy(relw).cuda())
+        g = ks.rng(ks.BASE_SEED, ks.TAG_BATCH, 0)
+        self.h_host, self.r_host, self.t_host = (ks.uniform_ids(g, 0, self.n_ent, self.B),
+                                                  ks.uniform_ids(g, 0, P["n_rel"], self.B),
+                                                  ks.uniform_ids(g, 0, self.n_ent, self.B))
+        self.h, self.r, self.t = (torch.from_numpy(x).cuda() for x in (self.h_host, self.r_host, self.t_host))
+        self.neg = kge.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, 0, self.n_ent, self.N)
+        self.bf16 = False
+        torch.cuda.synchronize()
+
+    def step(self, i):
+        for s in self.scorers:
+            self.kge.score(self.models[s], self.h, self.r, self.t, self.neg)
+
+    def pairs_per_step(self):
+        return len(self.scorers) * self.B * (self.N + 1)
+
+    def extra(self, ms):
+        return {"scorers": self.scorers}
+
+    def mfma_flops(self, slot):
+        # per launch, averaged over the scorers of a step (TransH runs two contractions)
+        g = sum(2 if s == "transh" else 1 for s in self.scorers) / len(self.scorers)
+        return 2.0 * self.B * self.N * self.d * g
+
+    def cpu_baseline(self, orc):
+        ks = self.ks
+        bs = 256
+        neg = orc.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, 0, self.n_ent, self.N)
+        h, r, t = self.h_host[:bs], self.r_host[:bs], self.t_host[:bs]
+        uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg)
+        rows = ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, uniq, self.d, self.P["amp"])
+        t0 = time.time()
+        for s in self.scorers:
+            rel, relw = ks.relation_tables(s, self.P["n_rel"], self.d, ks.BASE_SEED, self.P["amp"])
+            orc.score_batch(s, rows, rel, relw, ch, r, ct, cn)
+        dt = time.time() - t0
+        return {"value": len(self.scorers) * bs * (self.N + 1) / dt, "unit": "scored_pairs/s",
+                "cores": orc.num_threads(), "kind": "oracle", "seconds": round(dt, 2),
+                "sample": f"first {bs} of {self.B} queries against all {self.N} negatives, {len(self.scorers)} scorers"}
+
+
+class RankWorkload:
+    """c4: full-entity ranking, top-K and rank of a held-out tail."""
+
+    def __init__(self, P, scale, only=None):
+        import torch
+        import kge_synth as ks
+        import kge_synth.device as ksd
+        import paper_2211_12281_amd as kge
+        self.kge, self.torch, self.ks, self.P = kge, torch, ks, P
+        self.n_ent = max(1000, int(P["n_ent"] * scale))
+        self.d, self.Q, self.K = P["dim"], P["Q"], P["K"]
+        self.scorers = [only] if only else P["scorers"]
+        self.bf16 = P["dtype"] == "bf16"
+        dt = torch.bfloat16 if self.bf16 else torch.float32
+        self.ent = torch.empty((self.n_ent, self.d), dtype=dt, device="cuda")
+        ksd.fill_uniform(self.ent, ks.BASE_SEED, ks.TAG_ENT, P["amp"])
+        self.models = {}
+        for s in self.scorers:
+            rel, _ = ks.relation_tables(s, P["n_rel"], self.d, ks.BASE_SEED, P["amp"])
+            self.models[s] = kge.Model(s, self.ent, torch.from_numpy(rel).cuda().to(dt))
+        g = ks.rng(ks.BASE_SEED, ks.TAG_QUERY, 0)
+        self.h_host = ks.ZipfIds(self.n_ent, P["zipf_s"]).draw(g, self.Q)
+        self.r_host = ks.uniform_ids(g, 0, P["n_rel"], self.Q)
+        self.t_host = ks.uniform_ids(ks.rng(ks.BASE_SEED, ks.TAG_HELDOUT, 0), 0, self.n_ent, self.Q)
+        self.h, self.r, self.t = (torch.from_numpy(x).cuda() for x in (self.h_host, self.r_host, self.t_host))
+        torch.cuda.synchronize()
+
+    def step(self, i):
+        for s in self.scorers:
+            self.last = self.kge.topk(self.models[s], self.h, self.r, 0, self.n_ent, self.K, self.t)
+
+    def pairs_per_step(self):
+        return len(self.scorers) * self.Q * self.n_ent
+
+    def extra(self, ms):
+        return {"scorers": self.scorers, "queries_per_s": len(self.scorers) * self.Q / (ms * 1e-3)}
+
+    def mfma_flops(self, slot):
+        return 2.0 * self.Q * self.n_ent * self.d       # summed over the chunk launches of one call
+
+    def cpu_baseline(self, orc):
+        ks = self.ks
+        nq = 8
+        ent = self.ent.float().cpu().numpy()
+        t0 = time.time()
+        for s in self.scorers:
+            rel, _ = ks.relation_tables(s, self.P["n_rel"], self.d, ks.BASE_SEED, self.P["amp"])
+            if self.bf16:
+                rel = ks.round_to_bf16(rel)
+            orc.topk(s, ent, rel, None, self.h_host[:nq], self.r_host[:nq], 0, self.n_ent, self.K, self.t_host[:nq])
+        dt = time.time() - t0
+        return {"value": len(self.scorers) * nq * self.n_ent / dt, "unit": "scored_pairs/s",
+                "cores": orc.num_threads(), "kind": "oracle", "seconds": round(dt, 2),
+                "sample": f"first {nq} of {self.Q} queries against all {self.n_ent} entities, top-{self.K} + rank"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (see DESIGN.md, sharding)",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import kge_synth as ks
+    import paper_2211_12281_amd as kge
+    kge.load()
+    P = ks.PRESETS[a.workload]
+    if a.workload in ("c1", "c3", "c5"):
+        wl = TrainWorkload(a.workload, P, a.scale)
+    elif a.workload == "c2":
+        wl = ScoreWorkload(P, a.scale, a.scorer)
+    else:
+        wl = RankWorkload(P, a.scale, a.scorer)
+
+    for i in range(a.warmup):
+        wl.step(i)
+    torch.cuda.synchronize()
+    kge.profile_enable(True)
+    t0 = time.perf_counter()
+    for i in range(a.warmup, a.warmup + a.steps):
+        wl.step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kge.profile_enable(False)
+    ms = dt * 1e3 / a.steps
+
+    prof = {}
+    for slot in kge.binding.PROF_SLOTS:
+        tot, n = kge.profile_collect(slot)
+        if n:
+            prof[slot] = {"total_ms": tot, "launches": n, "avg_us": 1e3 * tot / n}
+    roof = None
+    if prof:
+        dom = max(prof, key=lambda k: prof[k]["total_ms"])
+        avg_s = prof[dom]["avg_us"] * 1e-6
+        if dom.startswith("block") or dom == "topk_scan":
+            flops = wl.mfma_flops(dom)
+            if dom == "topk_scan":
+                avg_s = prof[dom]["total_ms"] * 1e-3 / (a.steps * len(wl.scorers))   # all chunk launches of one call
+            peak = PEAK_BF16_TFLOPS if wl.bf16 else PEAK_F32_TFLOPS
+            ach = flops / avg_s / 1e12
+            roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                    "frac": ach / peak, "traffic": None, "avg_us": avg_s * 1e6}
+        else:
+            roof = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": None, "traffic": None, "avg_us": avg_s * 1e6}
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        cpu = wl.cpu_baseline(oracle)
+
+    pairs = wl.pairs_per_step()
+    line = {
+        "metric": "scored (query,candidate) pairs/s", "value": pairs / (ms * 1e-3), "unit": "pairs/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": P["dtype"], "data": "synthetic",
+        "config": {"workload": a.workload, **{k: v for k, v in P.items() if k in
+                                              ("n_ent", "n_rel", "dim", "B", "N", "Q", "K", "loss")}},
+        "roofline": roof, "cpu_baseline": cpu, "kernels": prof,
+    }
+    line.update(wl.extra(ms))
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -187,6 +187,17 @@ int kge_partition_triples(const int32_t *h, const int32_t *t, int64_t n, int64_t
  */
 size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t N, int64_t K);
 
+/*
+ * Optional instrumentation for benchmarks: while enabled, the library brackets the launches of its
+ * dominant kernels with HIP events on the caller's stream.  kge_profile_collect() waits for the
+ * recorded events of one slot, returns their summed duration and count, and forgets them.
+ * Host-side state shared by all callers of the process; not thread-safe; off by default.
+ */
+enum { KGE_PROF_BLOCK_SCORE = 0, KGE_PROF_BLOCK_STATS = 1, KGE_PROF_BLOCK_GRADQ = 2, KGE_PROF_BLOCK_GRADT = 3,
+       KGE_PROF_ADAM = 4, KGE_PROF_SORT = 5, KGE_PROF_TOPK_SCAN = 6, KGE_PROF_SLOTS = 7 };
+int kge_profile_enable(int on);
+int kge_profile_collect(int slot, double *total_ms, int64_t *launches);
+
 /* Static description of a status code. */
 const char *kge_status_string(int status);
 

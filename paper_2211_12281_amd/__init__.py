@@ -1,4 +1,4 @@
 """MI355X-native hot path of BESS-style knowledge-graph-embedding training and inference
 (arXiv 2211.12281): a C-ABI HIP library (csrc/, include/kge.h) and its thin ctypes binding."""
-from .binding import (KgeError, Model, Workspace, load, loss_bwd, partition_triples, sample_negatives, score,  # noqa: F401
+from .binding import (KgeError, Model, Workspace, load, loss_bwd, partition_triples, profile_collect, profile_enable, sample_negatives, score,  # noqa: F401
                       sparse_adam, status_string, topk, workspace_bytes)

@@ -17,7 +17,10 @@ SCORERS = {"transe": 0, "transh": 1, "rotate": 2, "distmult": 3, "complex": 4}
 LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
 OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION = 0, 1, 2, 3, 4
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
-           "kge_partition_triples", "kge_workspace_bytes", "kge_status_string"]
+           "kge_partition_triples", "kge_workspace_bytes", "kge_status_string", "kge_profile_enable",
+           "kge_profile_collect"]
+PROF_SLOTS = {"block_score": 0, "block_stats": 1, "block_gradq": 2, "block_gradt": 3, "adam": 4, "sort": 5,
+              "topk_scan": 6}
 
 
 class KgeModelT(C.Structure):
@@ -210,6 +213,17 @@ def topk(model: Model, h, r, cand_lo: int, cand_hi: int, K: int, true_t=None, ws
     _check(load().kge_topk(model.ref, _ptr(_i32(h)), _ptr(_i32(r)), Q, cand_lo, cand_hi, K, _ptr(out_idx),
                            _ptr(out_score), _ptr(true_t), _ptr(rank), _ptr(buf), buf.numel(), _stream()), "kge_topk")
     return out_idx, out_score, rank
+
+
+def profile_enable(on: bool):
+    _check(load().kge_profile_enable(1 if on else 0), "kge_profile_enable")
+
+
+def profile_collect(slot: str):
+    """(total milliseconds, launches) of the instrumented kernel `slot` since the last collect."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(load().kge_profile_collect(PROF_SLOTS[slot], C.byref(ms), C.byref(n)), "kge_profile_collect")
+    return ms.value, n.value
 
 
 def partition_triples(h, t, part_size: int, D: int, ws: Workspace | None = None):

@@ -129,6 +129,8 @@ KgeModelDev dev_model(const kge_model_t &m) {
 
 int launch_block(const Geometry &g, bool own_row, int mode, const KgeBlockArgs &a, int own_tiles, int nsplit,
                  int dsplit, hipStream_t st) {
+    KgeProfScope prof(mode == KGE_MODE_SCORE ? KGE_PROF_BLOCK_SCORE : mode == KGE_MODE_STATS ? KGE_PROF_BLOCK_STATS
+                      : own_row ? KGE_PROF_BLOCK_GRADQ : KGE_PROF_BLOCK_GRADT, st);
     if (g.bf16) return kge_launch_block_bf16(g.rb, own_row, mode, g.transh, a, own_tiles, nsplit, dsplit, st);
     return kge_launch_block_f32(g.rb, own_row, mode, g.transh, a, own_tiles, nsplit, dsplit, st);
 }
@@ -289,7 +291,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     if (N > 0) {
         // with B == 0 there are no partials: nsplit 0 writes zero rows
         rc = kge_run_tfinish(b.acct, b.sumt, have_block ? g.nsplit_t : 0, g.Np, g.N, g.dp, model->dim,
-                             g.kind == KGE_KIND_DIST, b.T, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
+                             have_block && g.kind == KGE_KIND_DIST, b.T, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
                              g_ent_idx + 2 * B, st);
     }
     return rc;

@@ -15,6 +15,13 @@ static inline int kge_launch_status() {
     return hipGetLastError() == hipSuccess ? KGE_OK : KGE_E_HIP;
 }
 
+// RAII pair of HIP events around a kernel launch; a no-op unless kge_profile_enable(1) was called.
+struct KgeProfScope {
+    KgeProfScope(int slot, hipStream_t st);
+    ~KgeProfScope();
+    int slot_; hipStream_t st_; void *a_, *b_;
+};
+
 static inline int64_t kge_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // ---------------------------------------------------------------------------------------------

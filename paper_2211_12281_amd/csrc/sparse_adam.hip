@@ -206,7 +206,11 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
                         size_t ws_bytes, hipStream_t st) {
     (void)ws_bytes;
     const uint32_t *sk, *sp;
-    int rc = kge_sort_pairs(idx, nullptr, nullptr, 1, 1, M, n_rows, ws, &sk, &sp, st);
+    int rc;
+    {
+        KgeProfScope prof(KGE_PROF_SORT, st);
+        rc = kge_sort_pairs(idx, nullptr, nullptr, 1, 1, M, n_rows, ws, &sk, &sp, st);
+    }
     if (rc != KGE_OK) return rc;
     AdamConst c;
     c.lr = cfg.lr; c.b1 = cfg.beta1; c.b2 = cfg.beta2; c.eps = cfg.eps;
@@ -214,6 +218,7 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
     c.inv_bc1 = (float)(1.0 / (1.0 - pow((double)cfg.beta1, (double)cfg.step)));
     c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)cfg.beta2, (double)cfg.step)));
     const int grid = (int)((M + 3) / 4);
+    KgeProfScope prof(KGE_PROF_ADAM, st);
     hipLaunchKernelGGL(adam_segment_kernel, dim3(grid), dim3(256), 0, st, sk, sp, M, grads, dim, ld, param,
                        (uint16_t *)shadow, m, v, c);
     return kge_launch_status();
