@@ -19,8 +19,7 @@ OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION = 0, 1, 2, 3, 4
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
            "kge_partition_triples", "kge_workspace_bytes", "kge_status_string", "kge_profile_enable",
            "kge_profile_collect"]
-PROF_SLOTS = {"block_score": 0, "block_stats": 1, "block_gradq": 2, "block_gradt": 3, "adam": 4, "sort": 5,
-              "topk_scan": 6}
+PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5}
 
 
 class KgeModelT(C.Structure):

@@ -1,0 +1,24 @@
+// Dispatch of the block-kernel instantiations.
+#include "kge_internal.h"
+
+#define KGE_DECL(name) int kge_launch_block_##name(int, int, bool, int, int, int, const KgeBlockArgs &, int, int, hipStream_t);
+KGE_DECL(f32_score) KGE_DECL(f32_fwd_ls) KGE_DECL(f32_fwd_sm) KGE_DECL(f32_gradt_ls) KGE_DECL(f32_gradt_sm)
+KGE_DECL(bf16_score) KGE_DECL(bf16_fwd_ls) KGE_DECL(bf16_fwd_sm) KGE_DECL(bf16_gradt_ls) KGE_DECL(bf16_gradt_sm)
+
+int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
+                     int own_tiles, int nsplit, hipStream_t st) {
+    if (mode == KGE_MODE_SCORE)
+        return bf16 ? kge_launch_block_bf16_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st)
+                    : kge_launch_block_f32_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st);
+    const bool ls = loss == KGE_LOGSIGMOID;
+    if (mode == KGE_MODE_FWD) {
+        if (bf16) return ls ? kge_launch_block_bf16_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
+                            : kge_launch_block_bf16_fwd_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
+        return ls ? kge_launch_block_f32_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
+                  : kge_launch_block_f32_fwd_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
+    }
+    if (bf16) return ls ? kge_launch_block_bf16_gradt_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
+                        : kge_launch_block_bf16_gradt_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
+    return ls ? kge_launch_block_f32_gradt_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
+              : kge_launch_block_f32_gradt_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
+}

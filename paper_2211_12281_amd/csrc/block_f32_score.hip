@@ -1,15 +1,17 @@
-// Instantiations of the block kernel for f32 operands (split over files to bound compile time).
+// Instantiations of the block kernel: f32 operands, pass "score" (split over files to bound compile time).
 #include "block_kernel.hpp"
 
-#define KGE_INST(RB, OWN, MODE, TH, DS) \
-    if (rb == RB && own_row == OWN && mode == MODE && transh == TH && dsplit == DS) \
-        return kge_block_launch<false, RB, OWN, MODE, TH, DS>(a, own_tiles, nsplit, st);
+#define KGE_INST(RB, MODE, TH, KIND, LOSS, DS) \
+    if (rb == RB && mode == MODE && transh == TH && kind == KIND && loss == LOSS && dsplit == DS) \
+        return kge_block_launch<false, RB, MODE, TH, KIND, LOSS, DS>(a, own_tiles, nsplit, st);
 
-int kge_launch_block_f32_score(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a,
-                         int own_tiles, int nsplit, int dsplit, hipStream_t st) {
-    KGE_INST(512, false, KGE_MODE_SCORE, false, 1)
-    KGE_INST(1024, false, KGE_MODE_SCORE, false, 1)
-    KGE_INST(512, false, KGE_MODE_SCORE, true, 1)
-    KGE_INST(1024, false, KGE_MODE_SCORE, true, 1)
+int kge_launch_block_f32_score(int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
+                         int own_tiles, int nsplit, hipStream_t st) {
+    KGE_INST(512, KGE_MODE_SCORE, false, KGE_KIND_MULT, 0, 1)
+    KGE_INST(512, KGE_MODE_SCORE, false, KGE_KIND_DIST, 0, 1)
+    KGE_INST(512, KGE_MODE_SCORE, true, KGE_KIND_DIST, 0, 1)
+    KGE_INST(1024, KGE_MODE_SCORE, false, KGE_KIND_MULT, 0, 1)
+    KGE_INST(1024, KGE_MODE_SCORE, false, KGE_KIND_DIST, 0, 1)
+    KGE_INST(1024, KGE_MODE_SCORE, true, KGE_KIND_DIST, 0, 1)
     return KGE_E_UNSUPPORTED;
 }

@@ -127,12 +127,11 @@ KgeModelDev dev_model(const kge_model_t &m) {
     return d;
 }
 
-int launch_block(const Geometry &g, bool own_row, int mode, const KgeBlockArgs &a, int own_tiles, int nsplit,
-                 int dsplit, hipStream_t st) {
-    KgeProfScope prof(mode == KGE_MODE_SCORE ? KGE_PROF_BLOCK_SCORE : mode == KGE_MODE_STATS ? KGE_PROF_BLOCK_STATS
-                      : own_row ? KGE_PROF_BLOCK_GRADQ : KGE_PROF_BLOCK_GRADT, st);
-    if (g.bf16) return kge_launch_block_bf16(g.rb, own_row, mode, g.transh, a, own_tiles, nsplit, dsplit, st);
-    return kge_launch_block_f32(g.rb, own_row, mode, g.transh, a, own_tiles, nsplit, dsplit, st);
+int launch_block(const Geometry &g, int mode, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, int dsplit,
+                 hipStream_t st) {
+    KgeProfScope prof(mode == KGE_MODE_SCORE ? KGE_PROF_BLOCK_SCORE : mode == KGE_MODE_FWD ? KGE_PROF_BLOCK_FWD
+                                                                                        : KGE_PROF_BLOCK_GRADT, st);
+    return kge_launch_block(g.bf16, g.rb, mode, g.transh, g.kind, loss, dsplit, a, own_tiles, nsplit, st);
 }
 
 void *align_ws(void *ws, size_t &bytes) {
@@ -142,26 +141,6 @@ void *align_ws(void *ws, size_t &bytes) {
 }
 
 }  // namespace
-
-// the per-part launchers live in eight translation units
-#define KGE_DECL(name) int kge_launch_block_##name(int, bool, int, bool, const KgeBlockArgs &, int, int, int, hipStream_t);
-KGE_DECL(f32_score) KGE_DECL(f32_stats) KGE_DECL(f32_gradq) KGE_DECL(f32_gradt)
-KGE_DECL(bf16_score) KGE_DECL(bf16_stats) KGE_DECL(bf16_gradq) KGE_DECL(bf16_gradt)
-
-int kge_launch_block_f32(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a, int own_tiles,
-                         int nsplit, int dsplit, hipStream_t st) {
-    if (mode == KGE_MODE_SCORE) return kge_launch_block_f32_score(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
-    if (mode == KGE_MODE_STATS) return kge_launch_block_f32_stats(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
-    return own_row ? kge_launch_block_f32_gradq(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st)
-                   : kge_launch_block_f32_gradt(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
-}
-int kge_launch_block_bf16(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a, int own_tiles,
-                          int nsplit, int dsplit, hipStream_t st) {
-    if (mode == KGE_MODE_SCORE) return kge_launch_block_bf16_score(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
-    if (mode == KGE_MODE_STATS) return kge_launch_block_bf16_stats(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
-    return own_row ? kge_launch_block_bf16_gradq(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st)
-                   : kge_launch_block_bf16_gradt(rb, own_row, mode, transh, a, own_tiles, nsplit, dsplit, st);
-}
 
 extern "C" {
 
@@ -228,7 +207,7 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     a.own = b.T; a.str = b.Q; a.str2 = b.W; a.rowinfo = b.rowinfo; a.tn = b.tn;
     a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_b; a.tiles_per_split = g.tps_t;
     a.kind = g.kind; a.S_out = neg_out; a.own_pad = g.Np;
-    return launch_block(g, false, KGE_MODE_SCORE, a, g.own_tiles_n, g.nsplit_t, 1, st);
+    return launch_block(g, KGE_MODE_SCORE, 0, a, g.own_tiles_n, g.nsplit_t, 1, st);
 }
 
 int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
@@ -266,27 +245,24 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         if ((rc = kge_run_transpose(b.T, b.Tt, g.Np, g.dp, g.bf16, st)) != KGE_OK) return rc;
         if ((rc = kge_run_transpose(g.transh ? b.Q2 : b.Q, b.Qt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
         if (g.transh && (rc = kge_run_transpose(b.W, b.Wt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
-        // pass 1: row statistics of the block
-        a.own = b.Q; a.own2 = b.W; a.str = b.T; a.rowinfo = b.rowinfo; a.tn = b.tn;
+        // pass 1 (row owner): loss statistics of every row and the unnormalised gradient of the queries
+        a.own = b.Q; a.own2 = b.W; a.str = b.T; a.strT = b.Tt; a.strT_ld = g.Np; a.rowinfo = b.rowinfo; a.tn = b.tn;
         a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_n; a.tiles_per_split = g.tps_q;
         a.kind = g.kind; a.loss = cfg->loss; a.gamma = cfg->gamma; a.adv_temp = cfg->adv_temp; a.c_corr = c_corr;
-        a.stat_part = b.stat_part; a.own_pad = g.Bp;
-        if ((rc = launch_block(g, true, KGE_MODE_STATS, a, g.own_tiles_b, g.nsplit_q, 1, st)) != KGE_OK) return rc;
+        a.stat_part = b.stat_part; a.acc_part = b.accq; a.acc_part2 = b.accq2; a.sum_part = b.sumq; a.own_pad = g.Bp;
+        if ((rc = launch_block(g, KGE_MODE_FWD, cfg->loss, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
     }
     if ((rc = kge_run_rowfinish(b.stat_part, have_block ? g.nsplit_q : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
                                 cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, loss_out, st)) != KGE_OK) return rc;
     if (have_block) {
-        // pass 2: gradient of the queries (row owner) ...
-        a.strT = b.Tt; a.strT_ld = g.Np; a.acc_part = b.accq; a.acc_part2 = b.accq2; a.sum_part = b.sumq;
-        if ((rc = launch_block(g, true, KGE_MODE_GRAD, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
-        // ... and of the shared negatives (column owner)
+        // pass 2 (column owner): gradient of the shared negatives from the finished row constants
         KgeBlockArgs c = a;
         c.own = b.T; c.own2 = nullptr; c.str = b.Q; c.str2 = b.W; c.strT = b.Qt; c.strT2 = b.Wt; c.strT_ld = g.Bp;
         c.str_tiles = g.str_tiles_b; c.tiles_per_split = g.tps_t;
-        c.acc_part = b.acct; c.acc_part2 = nullptr; c.sum_part = b.sumt; c.own_pad = g.Np;
-        if ((rc = launch_block(g, false, KGE_MODE_GRAD, c, g.own_tiles_n, g.nsplit_t, g.dsplit_t, st)) != KGE_OK) return rc;
+        c.acc_part = b.acct; c.acc_part2 = nullptr; c.sum_part = b.sumt; c.stat_part = nullptr; c.own_pad = g.Np;
+        if ((rc = launch_block(g, KGE_MODE_GRADT, cfg->loss, c, g.own_tiles_n, g.nsplit_t, g.dsplit_t, st)) != KGE_OK) return rc;
     }
-    if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, have_block ? g.nsplit_q : 0, b.gpos,
+    if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, have_block ? g.nsplit_q : 0, b.gpos,
                             g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, st)) != KGE_OK) return rc;
     if (N > 0) {
         // with B == 0 there are no partials: nsplit 0 writes zero rows

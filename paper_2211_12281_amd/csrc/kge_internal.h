@@ -31,12 +31,13 @@ constexpr int KGE_OWN_TILE = 128;     // rows owned by one workgroup (4 waves x 
 constexpr int KGE_STREAM_TILE = 32;   // rows streamed through LDS per iteration
 constexpr int KGE_PAD = 128;          // B and N are padded to this in the workspace copies
 
-enum { KGE_MODE_SCORE = 0, KGE_MODE_STATS = 1, KGE_MODE_GRAD = 2 };
+enum { KGE_MODE_SCORE = 0, KGE_MODE_FWD = 1, KGE_MODE_GRADT = 2 };
 enum { KGE_KIND_MULT = 0, KGE_KIND_DIST = 1 };
 
-// Per-row side information of the queries: squared norm of q, c = w.q (TransH), the
-// per-row constant of the gradient coefficient, spare.
-struct __attribute__((aligned(16))) KgeRowInfo { float qn, c, K, spare; };
+// Per-row side information of the queries: squared norm of q, c = w.q (TransH), the per-row
+// constant K of the gradient coefficient exp2(x * log2e + K) (log2 domain), squared norm of the
+// (rounded) TransH normal.
+struct __attribute__((aligned(16))) KgeRowInfo { float qn, c, K, wn; };
 
 // Arguments of one block-kernel launch.  "own" is the operand a workgroup keeps in registers
 // (queries when OWN_ROW, negatives otherwise); "str" is the operand streamed through LDS.
@@ -56,15 +57,12 @@ struct KgeBlockArgs {
     float gamma, adv_temp, c_corr; // c_corr: sampled-softmax correction c
     // outputs
     float *S_out;                  // SCORE: [B][N]
-    float4 *stat_part;             // STATS: [nsplit][Bp] {m, l, accL, 0}
-    float *acc_part, *acc_part2;   // GRAD: [nsplit][own_pad][dp]
-    float4 *sum_part;              // GRAD: [nsplit][own_pad] {s1, s2, s3, 0}
+    float4 *stat_part;             // FWD: [nsplit][Bp] {running max (log2 domain), sum of weights, weighted loss, 0}
+    float *acc_part, *acc_part2;   // FWD / GRADT: [nsplit][own_pad][dp]
+    float4 *sum_part;              // FWD / GRADT: [nsplit][own_pad] {s1, s2, s3, 0}
     int32_t own_pad;
-    int32_t dblk0_stride;          // GRAD with a split of the output columns: blocks per z-slice
 };
 
-// launchers implemented in block_*.hip (one per element type to bound compile time per file)
-int kge_launch_block_f32(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a,
-                         int own_tiles, int nsplit, int dsplit, hipStream_t st);
-int kge_launch_block_bf16(int rb, bool own_row, int mode, bool transh, const KgeBlockArgs &a,
-                          int own_tiles, int nsplit, int dsplit, hipStream_t st);
+// launchers implemented in block_*.hip (one file per element type and pass to bound compile time)
+int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
+                     int own_tiles, int nsplit, hipStream_t st);

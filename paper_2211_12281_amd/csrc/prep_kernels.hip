@@ -78,9 +78,7 @@ template <bool BF16>
 __device__ __forceinline__ void kge_build_query(const KgeModelDev &m, int hi, int ri, int lane,
                                                 KgeRowCtx<BF16> &cx) {
     const int d = m.dim, c = d >> 1;
-    const char *hrow = (const char *)m.ent;  // element indexing below
     const int64_t hoff = (int64_t)hi * m.ent_ld, roff = (int64_t)ri * m.rel_ld, woff = (int64_t)ri * m.relw_ld;
-    (void)hrow;
     float wn2 = 0.f, whp = 0.f;
 #pragma unroll
     for (int k = 0; k < KGE_MAXJ; ++k) {
@@ -190,7 +188,7 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
     s_pos = kge_wave_sum(s_pos);
     if (!(m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX)) s_pos = -sqrtf(s_pos);
     if (lane == 0) {
-        rowinfo[b] = KgeRowInfo{qn, cq, 0.f, wn};
+        rowinfo[b] = KgeRowInfo{qn, cq, 0.f, m.scorer == KGE_TRANSH ? wn : 1.f};
         if (pos_ws) pos_ws[b] = s_pos;
         if (pos_out) pos_out[b] = s_pos;
     }
@@ -236,15 +234,18 @@ __device__ __forceinline__ float kge_softplus_f(float y) { return fmaxf(y, 0.f) 
 __global__ void kge_rowfinish_kernel(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss,
                                      float gamma, float c_corr, float scale, const float *pos,
                                      KgeRowInfo *rowinfo, float *lossb, float *gpos) {
+    const float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= Bp) return;
     if (b >= B) { lossb[b] = 0.f; gpos[b] = 0.f; rowinfo[b].K = -INFINITY; return; }
+    // merge the splits: m is the running maximum of x * log2(e) (x = a*s or s), l the sum of
+    // exp(x - max), ac the sum of exp(x - max) * softplus(gamma + s)
     float m = -INFINITY, l = 0.f, ac = 0.f;
     for (int s = 0; s < nsplit; ++s) {                      // fixed order
         const float4 p = stat_part[(size_t)s * Bp + b];
         if (p.x == -INFINITY) continue;
         const float mn = fmaxf(m, p.x);
-        const float r0 = expf(m - mn), r1 = expf(p.x - mn);
+        const float r0 = exp2f(m - mn), r1 = exp2f(p.x - mn);
         l = l * r0 + p.y * r1; ac = ac * r0 + p.z * r1; m = mn;
     }
     const float fp = pos[b];
@@ -253,15 +254,15 @@ __global__ void kge_rowfinish_kernel(const float4 *stat_part, int nsplit, int Bp
         L = kge_softplus_f(-(gamma + fp));
         const float e = expf(-fabsf(gamma + fp));           // sigma(-(gamma+fp)), stable
         gp = -((gamma + fp) >= 0.f ? e / (1.f + e) : 1.f / (1.f + e)) * scale;
-        if (N > 0 && l > 0.f) { L += ac / l; K = -m - logf(l) + logf(scale); } else K = -INFINITY;
+        if (N > 0 && l > 0.f) { L += ac / l; K = -m - log2f(l) + log2f(scale); } else K = -INFINITY;
     } else {
         if (N > 0 && l > 0.f) {
-            const float M = fmaxf(m, fp);
-            const float Z = l * expf(m - M) + expf(fp - M);
-            const float lse = M + logf(Z);
+            const float A = c_corr + logf(l) + m * LN2;     // log of the negatives' share of the partition sum
+            const float M = fmaxf(A, fp);
+            const float lse = M + logf(expf(A - M) + expf(fp - M));
             L = lse - fp;
             gp = (expf(fp - lse) - 1.f) * scale;
-            K = c_corr - lse + logf(scale);
+            K = (c_corr - lse + logf(scale)) * LOG2E;
         } else { L = 0.f; gp = 0.f; K = -INFINITY; }
     }
     lossb[b] = L; gpos[b] = gp; rowinfo[b].K = K;
@@ -287,7 +288,8 @@ __global__ void kge_loss_reduce_kernel(const float *lossb, int B, float scale, f
 template <bool BF16>
 __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t, int B,
                                  int Bp, int dp, const float *acc_part, const float *acc_part2,
-                                 const float4 *sum_part, int nsplit, const float *gpos, float *g_ent,
+                                 const float4 *sum_part, const float4 *stat_part, const KgeRowInfo *rowinfo,
+                                 int nsplit, const float *gpos, float *g_ent,
                                  float *g_rel, float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx) {
     const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -297,8 +299,19 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     kge_build_query<BF16>(m, h[b], r[b], lane, cx);
     const int64_t toff = (int64_t)t[b] * m.ent_ld;
     const float gp = gpos[b];
+    // the row pass leaves, per split, sums of UNNORMALISED weights relative to that split's running
+    // maximum m_s; exp2(m_s + K) turns them into gradient coefficients
+    const float K2 = rowinfo[b].K;
+    auto kappa = [&](int s) {
+        const float ms = stat_part[(size_t)s * Bp + b].x;
+        return ms > -INFINITY ? exp2f(ms + K2) : 0.f;
+    };
     float s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    for (int s = 0; s < nsplit; ++s) { const float4 p = sum_part[(size_t)s * Bp + b]; s1 += p.x; s2 += p.y; s3 += p.z; }
+    for (int s = 0; s < nsplit; ++s) {
+        const float kap = kappa(s);
+        const float4 p = sum_part[(size_t)s * Bp + b];
+        s1 += kap * p.x; s2 += kap * p.y; s3 += kap * p.z;
+    }
     float a1[KGE_MAXJ], a2[KGE_MAXJ], tv[KGE_MAXJ], dq[KGE_MAXJ], dtp[KGE_MAXJ];
     float wt = 0.f;
 #pragma unroll
@@ -307,8 +320,9 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         a1[k] = a2[k] = tv[k] = 0.f;
         if (j >= d) continue;
         for (int s = 0; s < nsplit; ++s) {
-            a1[k] += acc_part[((size_t)s * Bp + b) * dp + j];
-            if (m.scorer == KGE_TRANSH) a2[k] += acc_part2[((size_t)s * Bp + b) * dp + j];
+            const float kap = kappa(s);
+            a1[k] += kap * acc_part[((size_t)s * Bp + b) * dp + j];
+            if (m.scorer == KGE_TRANSH) a2[k] += kap * acc_part2[((size_t)s * Bp + b) * dp + j];
         }
         tv[k] = El<BF16>::ld(m.ent, toff + j);
         wt += cx.w[k] * tv[k];
@@ -476,13 +490,13 @@ int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N,
 }
 
 int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
-                  const float *acc_part, const float *acc_part2, const float4 *sum_part, int nsplit,
-                  const float *gpos, float *g_ent, float *g_rel, float *g_relw, int32_t *g_ent_idx,
-                  int32_t *g_rel_idx, hipStream_t st) {
+                  const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
+                  const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
+                  float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, hipStream_t st) {
     if (B == 0) return KGE_OK;
     const int grid = (B + 3) / 4;
-    if (m.bf16) hipLaunchKernelGGL(kge_chain_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
-    else        hipLaunchKernelGGL(kge_chain_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
+    if (m.bf16) hipLaunchKernelGGL(kge_chain_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
+    else        hipLaunchKernelGGL(kge_chain_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
     return kge_launch_status();
 }
 
