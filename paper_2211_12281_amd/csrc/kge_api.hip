@@ -5,7 +5,7 @@
 int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
                         const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
                         size_t ws_bytes, hipStream_t st);
-size_t kge_sparse_adam_ws(int64_t M);
+size_t kge_sparse_adam_ws(int64_t M, int dim);
 int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, int64_t Q, int64_t lo, int64_t hi,
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
@@ -165,7 +165,7 @@ size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t 
         Buffers b;
         return carve(g, op == KGE_OP_LOSS_BWD, nullptr, b);
     }
-    case KGE_OP_SPARSE_ADAM: return kge_sparse_adam_ws(B);
+    case KGE_OP_SPARSE_ADAM: return N <= 4096 ? kge_sparse_adam_ws(B, (int)N) : 0;
     case KGE_OP_TOPK:
         if (validate_model(model) != KGE_OK || K < 1 || K > 256) return 0;
         return kge_topk_ws(*model, B, N, (int)K);
@@ -285,7 +285,7 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
     if (!param_f32 || !m || !v || !idx || !grads) return KGE_E_INVALID_ARG;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
     ws = align_ws(ws, ws_bytes);
-    if (kge_sparse_adam_ws(M) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     return kge_run_sparse_adam(param_f32, param_bf16, m, v, n_rows, dim, ld, idx, grads, M, *cfg, ws, ws_bytes,
                                (hipStream_t)hip_stream);
 }

@@ -107,54 +107,151 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 struct AdamConst { float lr, b1, b2, eps, omb1, omb2, inv_bc1, inv_bc2; };
 
-// One wave per sorted position; only the first position of a run of equal rows does work.
-__global__ void adam_segment_kernel(const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads, int dim,
-                                    int64_t ld, float *param, uint16_t *shadow, float *mom, float *var,
-                                    AdamConst c) {
+constexpr int SEG_CHUNK = 32;     // sorted positions per chunk of the two-level reduction
+
+// Sum of the gradient rows at sorted positions [k0, k1), columns col..col+3, in position order.
+__device__ __forceinline__ float4 reduce_rows(const uint32_t *sp, int64_t k0, int64_t k1, const float *grads, int dim,
+                                              int col) {
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+    int64_t k = k0;
+    for (; k + 8 <= k1; k += 8) {                          // eight independent loads in flight, fixed add order
+        float4 t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = *(const float4 *)(grads + (int64_t)sp[k + u] * dim + col);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { g.x += t[u].x; g.y += t[u].y; g.z += t[u].z; g.w += t[u].w; }
+    }
+    for (; k < k1; ++k) {
+        const float4 t = *(const float4 *)(grads + (int64_t)sp[k] * dim + col);
+        g.x += t.x; g.y += t.y; g.z += t.z; g.w += t.w;
+    }
+    return g;
+}
+
+__device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int64_t ld, float *param, uint16_t *shadow,
+                                           float *mom, float *var, const AdamConst &c) {
+    const int64_t o = (int64_t)key * ld + col;
+    float4 th = *(float4 *)(param + o), m = *(float4 *)(mom + o), v = *(float4 *)(var + o);
+    const float gg[4] = { g.x, g.y, g.z, g.w };
+    float tt[4] = { th.x, th.y, th.z, th.w }, mm[4] = { m.x, m.y, m.z, m.w }, vv[4] = { v.x, v.y, v.z, v.w };
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        mm[q] = c.b1 * mm[q] + c.omb1 * gg[q];
+        vv[q] = c.b2 * vv[q] + c.omb2 * gg[q] * gg[q];
+        tt[q] -= c.lr * (mm[q] * c.inv_bc1) / (sqrtf(vv[q] * c.inv_bc2) + c.eps);
+    }
+    *(float4 *)(param + o) = make_float4(tt[0], tt[1], tt[2], tt[3]);
+    *(float4 *)(mom + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+    *(float4 *)(var + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    if (shadow) *(uint2 *)(shadow + o) = make_uint2(pack_bf16x2(tt[0], tt[1]), pack_bf16x2(tt[2], tt[3]));
+}
+
+// Runs of equal rows ("segments") in the sorted order are reduced in two ways:
+//  - a segment that lies inside one aligned chunk of SEG_CHUNK positions is summed and updated by the
+//    wave of its first position (kernel A): full parallelism over the many short segments;
+//  - a segment that crosses a chunk boundary (every long one does) is cut at the boundaries; each piece
+//    is summed by the wave of its chunk (kernel B1) and the wave of the chunk where the segment starts
+//    adds the pieces in order and updates the row (kernel B2).
+// The association order is a function of the sorted positions only: results are run-to-run identical.
+
+// A: one wave per sorted position.
+__global__ void adam_interior_kernel(const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads, int dim,
+                                     int64_t ld, float *param, uint16_t *shadow, float *mom, float *var, AdamConst c) {
     const int lane = threadIdx.x & 63;
     const int64_t i = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (i >= M) return;
     const uint32_t key = sk[i];
-    if (i > 0 && sk[i - 1] == key) return;
-    int64_t e = i + 1;
-    while (e < M && sk[e] == key) ++e;
-    for (int col = lane * 4; col < dim; col += 256) {
-        float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-        int64_t k = i;
-        for (; k + 4 <= e; k += 4) {                       // four independent loads in flight, fixed add order
-            const float4 g0 = *(const float4 *)(grads + (int64_t)sp[k] * dim + col);
-            const float4 g1 = *(const float4 *)(grads + (int64_t)sp[k + 1] * dim + col);
-            const float4 g2 = *(const float4 *)(grads + (int64_t)sp[k + 2] * dim + col);
-            const float4 g3 = *(const float4 *)(grads + (int64_t)sp[k + 3] * dim + col);
-            g.x += g0.x; g.y += g0.y; g.z += g0.z; g.w += g0.w;
-            g.x += g1.x; g.y += g1.y; g.z += g1.z; g.w += g1.w;
-            g.x += g2.x; g.y += g2.y; g.z += g2.z; g.w += g2.w;
-            g.x += g3.x; g.y += g3.y; g.z += g3.z; g.w += g3.w;
-        }
-        for (; k < e; ++k) {
-            const float4 g0 = *(const float4 *)(grads + (int64_t)sp[k] * dim + col);
-            g.x += g0.x; g.y += g0.y; g.z += g0.z; g.w += g0.w;
-        }
-        const int64_t o = (int64_t)key * ld + col;
-        float4 th = *(float4 *)(param + o), m = *(float4 *)(mom + o), v = *(float4 *)(var + o);
-        const float gg[4] = { g.x, g.y, g.z, g.w };
-        float tt[4] = { th.x, th.y, th.z, th.w }, mm[4] = { m.x, m.y, m.z, m.w }, vv[4] = { v.x, v.y, v.z, v.w };
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            mm[q] = c.b1 * mm[q] + c.omb1 * gg[q];
-            vv[q] = c.b2 * vv[q] + c.omb2 * gg[q] * gg[q];
-            tt[q] -= c.lr * (mm[q] * c.inv_bc1) / (sqrtf(vv[q] * c.inv_bc2) + c.eps);
-        }
-        *(float4 *)(param + o) = make_float4(tt[0], tt[1], tt[2], tt[3]);
-        *(float4 *)(mom + o) = make_float4(mm[0], mm[1], mm[2], mm[3]);
-        *(float4 *)(var + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
-        if (shadow) *(uint2 *)(shadow + o) = make_uint2(pack_bf16x2(tt[0], tt[1]), pack_bf16x2(tt[2], tt[3]));
+    if (i > 0 && sk[i - 1] == key) return;                 // not the first position of its segment
+    const int64_t chunk_end = (i / SEG_CHUNK + 1) * SEG_CHUNK < M ? (i / SEG_CHUNK + 1) * SEG_CHUNK : M;
+    // length of the run inside the chunk: lanes probe the following positions
+    const int64_t probe = i + lane;
+    const bool same = probe < chunk_end && sk[probe] == key;   // SEG_CHUNK <= 64 lanes
+    const uint64_t mask = __ballot(same);
+    const int run = __builtin_ctzll(~mask);                // leading ones from lane 0
+    const int64_t e = i + run;
+    if (e == chunk_end && chunk_end < M && sk[chunk_end] == key) return;   // crosses the boundary: kernels B
+    for (int col = lane * 4; col < dim; col += 256)
+        adam_apply(key, col, reduce_rows(sp, i, e, grads, dim, col), ld, param, shadow, mom, var, c);
+}
+
+// B1: one wave per chunk; partial sums of its boundary-crossing pieces.
+//   part[2k]   : the run at the chunk start when it continues a segment from chunk k-1
+//   part[2k+1] : the run that reaches the chunk end and continues into chunk k+1, unless it is part[2k]
+__global__ void adam_piece_kernel(const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads, int dim,
+                                  float *part) {
+    const int lane = threadIdx.x & 63;
+    const int64_t k = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t c0 = k * SEG_CHUNK;
+    if (c0 >= M) return;
+    const int64_t c1 = c0 + SEG_CHUNK < M ? c0 + SEG_CHUNK : M;
+    const int n = (int)(c1 - c0);
+    const uint32_t kv = lane < n ? sk[c0 + lane] : 0u;
+    const uint32_t first = __shfl(kv, 0), last = __shfl(kv, n - 1);
+    const bool cont_in = c0 > 0 && sk[c0 - 1] == first;
+    const bool cont_out = c1 < M && sk[c1] == last;
+    const uint64_t valid = n == 64 ? ~0ull : ((1ull << n) - 1ull);
+    if (cont_in) {
+        const uint64_t m = __ballot(lane < n && kv == first);
+        const int run = __builtin_ctzll(~m);
+        for (int col = lane * 4; col < dim; col += 256)
+            *(float4 *)(part + (2 * k) * (int64_t)dim + col) = reduce_rows(sp, c0, c0 + run, grads, dim, col);
+        if (run == n) return;                               // the whole chunk is one continued run
+    }
+    if (cont_out) {
+        const uint64_t m = __ballot(lane < n && kv == last) & valid;
+        const uint64_t others = ~m & valid;
+        const int start = others ? 64 - __builtin_clzll(others) : 0;   // first position of the trailing run of `last`
+        if (cont_in && start == 0) return;
+        for (int col = lane * 4; col < dim; col += 256)
+            *(float4 *)(part + (2 * k + 1) * (int64_t)dim + col) = reduce_rows(sp, c0 + start, c1, grads, dim, col);
     }
 }
 
-struct SortWs { uint32_t *ka, *kb, *pa, *pb, *hist; int nblk, rounds; };
+// B2: one wave per chunk; if a boundary-crossing segment STARTS in this chunk, add its pieces and update.
+__global__ void adam_boundary_kernel(const uint32_t *sk, int64_t M, int dim, int64_t ld, const float *part,
+                                     float *param, uint16_t *shadow, float *mom, float *var, AdamConst c) {
+    const int lane = threadIdx.x & 63;
+    const int64_t k = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t c0 = k * SEG_CHUNK;
+    if (c0 >= M) return;
+    const int64_t c1 = c0 + SEG_CHUNK < M ? c0 + SEG_CHUNK : M;
+    if (c1 >= M) return;                                    // nothing continues past the last chunk
+    const uint32_t key = sk[c1 - 1];
+    if (sk[c1] != key) return;                              // no segment crosses this chunk's end
+    const int n = (int)(c1 - c0);
+    const uint32_t kv = lane < n ? sk[c0 + lane] : ~key;
+    const bool all_same = __ballot(lane < n && kv == key) == (n == 64 ? ~0ull : ((1ull << n) - 1ull));
+    if (all_same && c0 > 0 && sk[c0 - 1] == key) return;    // the segment started in an earlier chunk
+    // pieces: part[2k+1] here, then part[2j] of the following chunks while they continue the segment
+    int64_t jend = k + 1;                                   // one past the last continuing chunk
+    for (;;) {                                              // 64 chunk starts are probed per round
+        const int64_t pos = (jend + lane) * SEG_CHUNK;
+        const uint64_t cont = __ballot(pos < M && sk[pos] == key);
+        const int run = cont == ~0ull ? 64 : __builtin_ctzll(~cont);
+        jend += run;
+        if (run < 64) break;
+    }
+    for (int col = lane * 4; col < dim; col += 256) {
+        float4 g = *(const float4 *)(part + (2 * k + 1) * (int64_t)dim + col);
+        int64_t j = k + 1;
+        for (; j + 8 <= jend; j += 8) {
+            float4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = *(const float4 *)(part + (2 * (j + u)) * (int64_t)dim + col);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { g.x += t[u].x; g.y += t[u].y; g.z += t[u].z; g.w += t[u].w; }
+        }
+        for (; j < jend; ++j) {
+            const float4 t = *(const float4 *)(part + (2 * j) * (int64_t)dim + col);
+            g.x += t.x; g.y += t.y; g.z += t.z; g.w += t.w;
+        }
+        adam_apply(key, col, g, ld, param, shadow, mom, var, c);
+    }
+}
 
-size_t sort_carve(int64_t M, void *ws, SortWs &s) {
+struct SortWs { uint32_t *ka, *kb, *pa, *pb, *hist; float *part; int nblk, rounds; };
+
+size_t sort_carve(int64_t M, int dim, void *ws, SortWs &s) {
     char *p = (char *)ws;
     size_t off = 0;
     auto take = [&](size_t bytes) { void *q = p ? p + off : nullptr; off += (bytes + 255) / 256 * 256; return q; };
@@ -165,25 +262,26 @@ size_t sort_carve(int64_t M, void *ws, SortWs &s) {
     s.ka = (uint32_t *)take((size_t)M * 4); s.kb = (uint32_t *)take((size_t)M * 4);
     s.pa = (uint32_t *)take((size_t)M * 4); s.pb = (uint32_t *)take((size_t)M * 4);
     s.hist = (uint32_t *)take((size_t)256 * s.nblk * 4);
+    s.part = (float *)take((size_t)2 * ((M + SEG_CHUNK - 1) / SEG_CHUNK) * (size_t)dim * 4);
     return off + 256;
 }
 
 }  // namespace
 
-size_t kge_sparse_adam_ws(int64_t M) {
-    if (M < 0 || M >= (1ll << 31)) return 0;
+size_t kge_sparse_adam_ws(int64_t M, int dim) {
+    if (M < 0 || M >= (1ll << 31) || dim < 0) return 0;
     SortWs s;
-    return sort_carve(M, nullptr, s);
+    return sort_carve(M, dim, nullptr, s);
 }
 
-size_t kge_sort_ws(int64_t M) { return kge_sparse_adam_ws(M); }
+size_t kge_sort_ws(int64_t M) { return kge_sparse_adam_ws(M, 0); }
 
 // Sorts (key, position) pairs by key, stable; returns the buffers that hold the result.  Keys are
 // either the given row ids, or (when h and t are given) the partition-pair bucket of each triple.
 int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64_t part_size, int D, int64_t M,
                    int64_t key_range, void *ws, const uint32_t **sk, const uint32_t **sp, hipStream_t st) {
     SortWs s;
-    sort_carve(M, ws, s);
+    sort_carve(M, 0, ws, s);
     const int grid_e = (int)((M + 255) / 256);
     if (idx) hipLaunchKernelGGL(sort_init_kernel, dim3(grid_e), dim3(256), 0, st, idx, M, s.ka, s.pa);
     else     hipLaunchKernelGGL(sort_init_bucket_kernel, dim3(grid_e), dim3(256), 0, st, h, t, M, part_size, D, s.ka, s.pa);
@@ -217,9 +315,18 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
     c.omb1 = 1.f - cfg.beta1; c.omb2 = 1.f - cfg.beta2;
     c.inv_bc1 = (float)(1.0 / (1.0 - pow((double)cfg.beta1, (double)cfg.step)));
     c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)cfg.beta2, (double)cfg.step)));
-    const int grid = (int)((M + 3) / 4);
+    SortWs s;
+    sort_carve(M, dim, ws, s);                              // the piece buffer lies behind the sort buffers
     KgeProfScope prof(KGE_PROF_ADAM, st);
-    hipLaunchKernelGGL(adam_segment_kernel, dim3(grid), dim3(256), 0, st, sk, sp, M, grads, dim, ld, param,
+    const int grid = (int)((M + 3) / 4);
+    hipLaunchKernelGGL(adam_interior_kernel, dim3(grid), dim3(256), 0, st, sk, sp, M, grads, dim, ld, param,
                        (uint16_t *)shadow, m, v, c);
+    const int64_t nchunk = (M + SEG_CHUNK - 1) / SEG_CHUNK;
+    if (nchunk > 1) {
+        const int gridc = (int)((nchunk + 3) / 4);
+        hipLaunchKernelGGL(adam_piece_kernel, dim3(gridc), dim3(256), 0, st, sk, sp, M, grads, dim, s.part);
+        hipLaunchKernelGGL(adam_boundary_kernel, dim3(gridc), dim3(256), 0, st, sk, M, dim, ld, s.part, param,
+                           (uint16_t *)shadow, m, v, c);
+    }
     return kge_launch_status();
 }
