@@ -10,7 +10,8 @@
  * Conventions for every entry point
  *  - Structs (kge_model_t, kge_loss_cfg_t, kge_adam_cfg_t) are read on the HOST during the call.
  *    Every other pointer is a DEVICE pointer into memory owned by the caller; the library neither
- *    allocates nor frees device memory and keeps no state between calls.  Scratch space comes
+ *    allocates nor frees device memory and keeps no state between calls (the optional profiling
+ *    hooks at the end of this file aside).  Scratch space comes
  *    from the caller's workspace `ws` (size from kge_workspace_bytes(); 256-byte aligned).
  *  - Work is enqueued on `hip_stream` (a hipStream_t, may be NULL for the default stream) and the
  *    call returns without waiting for it.  Calls that share a workspace must be ordered on one
@@ -158,7 +159,7 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
  * the candidates.  Exact whenever rank <= K (it is the list position); beyond K it is counted
  * with the matrix-core scores and may differ from the fp64 rank by the number of candidates whose
  * score lies within the rounding error of the true tail's score.
- * Scorers: DistMult and TransE (others: KGE_E_UNSUPPORTED).  1 <= K <= 1024.
+ * Scorers: DistMult and TransE (others: KGE_E_UNSUPPORTED).  1 <= K <= 256.
  */
 int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64_t Q,
              int64_t cand_lo, int64_t cand_hi, int32_t K, int32_t *out_idx, float *out_score,

@@ -1,6 +1,7 @@
 // Row-wise kernels around the block kernel: negative ids, gather + query build + positive score,
 // gather of the shared negatives, transposes, per-row loss finish, chain rule of the query build.
 #include "prep_kernels.h"
+#include "row_ops.hpp"
 
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11)
@@ -36,97 +37,6 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
     hipLaunchKernelGGL(kge_negatives_kernel, dim3(grid), dim3(256), 0, st, (uint32_t)seed,
                        (uint32_t)(seed >> 32), (uint32_t)step, tag, lo, (uint64_t)(hi - lo), n, out);
     return kge_launch_status();
-}
-
-// ---------------------------------------------------------------------------------------------
-// helpers
-// ---------------------------------------------------------------------------------------------
-template <bool BF16> struct El;
-template <> struct El<true> {
-    using T = __bf16;
-    static __device__ __forceinline__ float ld(const void *p, int64_t i) { return (float)((const __bf16 *)p)[i]; }
-    static __device__ __forceinline__ void st(void *p, int64_t i, float v) { ((__bf16 *)p)[i] = (__bf16)v; }
-    static __device__ __forceinline__ float rnd(float v) { return (float)(__bf16)v; }
-};
-template <> struct El<false> {
-    using T = float;
-    static __device__ __forceinline__ float ld(const void *p, int64_t i) { return ((const float *)p)[i]; }
-    static __device__ __forceinline__ void st(void *p, int64_t i, float v) { ((float *)p)[i] = v; }
-    static __device__ __forceinline__ float rnd(float v) { return v; }
-};
-
-__device__ __forceinline__ float kge_wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-
-constexpr int KGE_MAXJ = 8;   // dim <= 512 -> at most 8 columns per lane
-
-// The query of triple b (fp32, unrounded), spread over a wave: lane holds columns lane + 64*k.
-// Returns through references what the callers need besides q.
-template <bool BF16>
-struct KgeRowCtx {
-    float h[KGE_MAXJ], r[KGE_MAXJ], w[KGE_MAXJ], q[KGE_MAXJ];
-    float wh;      // w_hat . h     (TransH)
-    float wnorm;   // ||w|| clamped (TransH)
-};
-
-// Builds q for one triple.  For complex scorers lane column j < d/2 pairs with j + d/2, which is a
-// different lane/slot in general, so partner values are fetched from memory again (L1/L2 hits).
-template <bool BF16>
-__device__ __forceinline__ void kge_build_query(const KgeModelDev &m, int hi, int ri, int lane,
-                                                KgeRowCtx<BF16> &cx) {
-    const int d = m.dim, c = d >> 1;
-    const int64_t hoff = (int64_t)hi * m.ent_ld, roff = (int64_t)ri * m.rel_ld, woff = (int64_t)ri * m.relw_ld;
-    float wn2 = 0.f, whp = 0.f;
-#pragma unroll
-    for (int k = 0; k < KGE_MAXJ; ++k) {
-        const int j = lane + 64 * k;
-        cx.h[k] = cx.r[k] = cx.w[k] = cx.q[k] = 0.f;
-        if (j >= d) continue;
-        const float hj = El<BF16>::ld(m.ent, hoff + j);
-        cx.h[k] = hj;
-        switch (m.scorer) {
-        case KGE_TRANSE: { float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj; cx.q[k] = hj + rj; break; }
-        case KGE_DISTMULT: { float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj; cx.q[k] = hj * rj; break; }
-        case KGE_COMPLEX: {
-            float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj;
-            if (j < c) {
-                float him = El<BF16>::ld(m.ent, hoff + j + c), rim = El<BF16>::ld(m.rel, roff + j + c);
-                cx.q[k] = hj * rj - him * rim;                         // q_re = h_re r_re - h_im r_im
-            } else {
-                float hre = El<BF16>::ld(m.ent, hoff + j - c), rre = El<BF16>::ld(m.rel, roff + j - c);
-                cx.q[k] = hre * rj + hj * rre;                         // q_im = h_re r_im + h_im r_re
-            }
-            break;
-        }
-        case KGE_ROTATE: {
-            const int jj = j < c ? j : j - c;
-            float ph = El<BF16>::ld(m.rel, roff + jj); cx.r[k] = ph;
-            float sn, cs; sincosf(ph, &sn, &cs);
-            if (j < c) { float him = El<BF16>::ld(m.ent, hoff + j + c); cx.q[k] = hj * cs - him * sn; }
-            else       { float hre = El<BF16>::ld(m.ent, hoff + j - c); cx.q[k] = hre * sn + hj * cs; }
-            break;
-        }
-        case KGE_TRANSH: {
-            float rj = El<BF16>::ld(m.rel, roff + j), wj = El<BF16>::ld(m.relw, woff + j);
-            cx.r[k] = rj; cx.w[k] = wj; wn2 += wj * wj; whp += wj * hj;
-            break;
-        }
-        }
-    }
-    cx.wh = 0.f; cx.wnorm = 1.f;
-    if (m.scorer == KGE_TRANSH) {
-        wn2 = kge_wave_sum(wn2); whp = kge_wave_sum(whp);
-        const float nrm = fmaxf(sqrtf(wn2), 1e-12f), inv = 1.f / nrm;
-        cx.wnorm = nrm; cx.wh = whp * inv;
-#pragma unroll
-        for (int k = 0; k < KGE_MAXJ; ++k) {
-            cx.w[k] *= inv;                                           // unit normal
-            cx.q[k] = (lane + 64 * k < d) ? cx.h[k] - cx.wh * cx.w[k] + cx.r[k] : 0.f;
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------------------------

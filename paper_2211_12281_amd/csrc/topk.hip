@@ -1,5 +1,572 @@
-// placeholder until the ranking kernels land
-#include "kge_internal.h"
-size_t kge_topk_ws(const kge_model_t &, int64_t, int64_t, int) { return 256; }
-int kge_run_topk(const kge_model_t &, const int32_t *, const int32_t *, int64_t, int64_t, int64_t, int, int32_t *,
-                 float *, const int32_t *, int64_t *, void *, size_t, hipStream_t) { return KGE_E_UNSUPPORTED; }
+// Link prediction (arXiv 2211.12281, Section 3.2 "Inference"): every query is scored against a range of
+// entity rows and the K best are kept.
+//
+//   1. prep      build the queries (Table 2), their norms and rounding residuals, squared norms of the candidates
+//   2. scan      MFMA scoring of [256 queries] x [candidate tiles]; an accumulator entry that beats the
+//                query's current threshold is appended to the query's candidate buffer (rare after warm-up);
+//                the table is walked in growing chunks, thresholds are refreshed between chunks
+//   3. compact   per query: keep the KP best buffered entries (KP > K), new threshold = the KP-th value
+//   4. rescore   survivors get the ranking key in fp64 with a sequential fused-multiply-add loop
+//   5. final     sort by (key, index), check with a rigorous rounding bound that no discarded candidate
+//                could belong to the top-K, write the list and the rank of the held-out tail
+//   6. fallback  queries that fail the check (or overflowed their buffer) are re-ranked by an exhaustive
+//                fp64 scan
+#include "row_ops.hpp"
+#include "block_kernel.hpp"
+#include <math.h>
+
+namespace {
+
+constexpr int TK_ST = 32;               // candidate rows per tile
+
+struct TopkArgs {
+    const void *Qmat;                   // [Qp][dp] queries (table element type)
+    const char *ent;                    // first candidate row
+    int64_t ent_stride;                 // bytes between rows
+    int32_t valid_bytes;                // d * sizeof(element)
+    int64_t ncand;
+    int64_t cand_lo;                    // entity id of candidate 0
+    const float *tn;                    // [ncand rounded up to a tile] squared norms of the candidates
+    const float *thr;                   // [Qp] current threshold (local value units)
+    const float *vt;                    // [Qp] value of the held-out tail (local units), +inf when absent
+    const int32_t *true_t;              // [Q] entity ids, or nullptr
+    int32_t *cnt;                       // [Qp] entries in each buffer
+    uint2 *buf;                         // [Qp][cap] {value bits, candidate index}
+    int32_t cap;
+    uint32_t *rankcnt;                  // [Qp] candidates whose value beats the held-out tail's
+    int32_t nq;                         // number of real queries (rows past it are padding)
+    int64_t tile_lo, tile_hi;
+    int32_t tiles_per_wg;
+};
+
+// "Local value": larger is better; DistMult: q.t; TransE: 2 q.t - |t|^2 (= -dist^2 + |q|^2).
+template <bool BF16, int RB, int KIND, int OB>
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256)))
+void topk_scan_kernel(const TopkArgs a) {
+    constexpr int KS = RB / 32;
+    constexpr int X_STRIDE = RB + 16;
+    constexpr int X_BYTES = TK_ST * X_STRIDE;
+    constexpr int STAGE_BYTES = X_BYTES + TK_ST * 4;
+    constexpr int X_UNITS = TK_ST * RB / 16 / 256;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
+    const int own_base = blockIdx.x * (128 * OB);
+    const int64_t t0 = a.tile_lo + (int64_t)blockIdx.y * a.tiles_per_wg;
+    const int64_t t1 = t0 + a.tiles_per_wg < a.tile_hi ? t0 + a.tiles_per_wg : a.tile_hi;
+    if (t0 >= t1) return;
+
+    uint4 own[OB][KS];
+    float thr[OB], vt[OB];
+    int qid[OB], tt[OB];
+    uint32_t above[OB];
+#pragma unroll
+    for (int ob = 0; ob < OB; ++ob) {
+        qid[ob] = own_base + (wave * OB + ob) * 32 + lr;
+        const char *p = (const char *)a.Qmat + (size_t)qid[ob] * RB + g * 16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) own[ob][ks] = *(const uint4 *)(p + ks * 32);
+        thr[ob] = a.thr[qid[ob]];
+        vt[ob] = a.vt[qid[ob]];
+        tt[ob] = (a.true_t && qid[ob] < a.nq) ? a.true_t[qid[ob]] : -1;
+        above[ob] = 0;
+    }
+
+    kge_u32x4 px[X_UNITS];
+    float ptn = 0.f;
+    auto gload = [&](int64_t tile) {
+#pragma unroll
+        for (int u = 0; u < X_UNITS; ++u) {
+            const int unit = tid + u * 256, row = unit / (RB / 16), cu = unit % (RB / 16);
+            int64_t cand = tile * TK_ST + row;
+            cand = cand < a.ncand ? cand : a.ncand - 1;                    // rows past the end are masked later
+            kge_u32x4 v = {0u, 0u, 0u, 0u};
+            if (cu * 16 < a.valid_bytes) v = *(const kge_u32x4 *)(a.ent + cand * a.ent_stride + cu * 16);
+            px[u] = v;
+        }
+        if (tid < TK_ST) ptn = a.tn[tile * TK_ST + tid];
+    };
+    auto lstore = [&](int stage) {
+        char *base = lds + stage * STAGE_BYTES;
+#pragma unroll
+        for (int u = 0; u < X_UNITS; ++u) {
+            const int unit = tid + u * 256, row = unit / (RB / 16), cu = unit % (RB / 16);
+            *(kge_u32x4 *)(base + row * X_STRIDE + cu * 16) = px[u];
+        }
+        if (tid < TK_ST) *(float *)(base + X_BYTES + tid * 4) = ptn;
+    };
+
+    gload(t0);
+    lstore(0);
+    __syncthreads();
+    for (int64_t tile = t0; tile < t1; ++tile) {
+        const int stage = (int)((tile - t0) & 1);
+        const bool more = tile + 1 < t1;
+        if (more) gload(tile + 1);
+        const char *base = lds + stage * STAGE_BYTES;
+        kge_f32x16 acc[OB];
+#pragma unroll
+        for (int ob = 0; ob < OB; ++ob) for (int i = 0; i < 16; ++i) acc[ob][i] = 0.f;
+        const char *xrow = base + lr * X_STRIDE + g * 16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint4 av = *(const uint4 *)(xrow + ks * 32);
+#pragma unroll
+            for (int ob = 0; ob < OB; ++ob) acc[ob] = kge_mma16<BF16>(acc[ob], av, own[ob][ks]);
+        }
+        const int64_t cbase = tile * TK_ST + 4 * g;         // candidate of register i: cbase + 8*(i/4) + (i%4)
+        const bool tile_full = tile * TK_ST + TK_ST <= a.ncand;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
+            const int64_t cand = cbase + 8 * (i >> 2) + (i & 3);
+            float tnv = 0.f;
+            if constexpr (KIND == KGE_KIND_DIST) tnv = *(const float *)(base + X_BYTES + sl * 4);
+#pragma unroll
+            for (int ob = 0; ob < OB; ++ob) {
+                float v = KIND == KGE_KIND_DIST ? fmaf(2.f, acc[ob][i], -tnv) : acc[ob][i];
+                if (!tile_full && cand >= a.ncand) v = -INFINITY;
+                if (a.true_t) above[ob] += (v > vt[ob] && (int)(cand + a.cand_lo) != tt[ob]) ? 1u : 0u;
+                if (v > thr[ob] && qid[ob] < a.nq) {
+                    const int slot = atomicAdd(a.cnt + qid[ob], 1);
+                    if (slot < a.cap) a.buf[(size_t)qid[ob] * a.cap + slot] = make_uint2(__float_as_uint(v), (uint32_t)cand);
+                }
+            }
+        }
+        if (more) lstore(stage ^ 1);
+        __syncthreads();
+    }
+    if (a.true_t) {
+#pragma unroll
+        for (int ob = 0; ob < OB; ++ob) if (above[ob] && qid[ob] < a.nq) atomicAdd(a.rankcnt + qid[ob], above[ob]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// bitonic sorts in LDS (256 threads)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t pack_value(uint32_t vbits, uint32_t idx) {
+    // unsigned order of the float, then smaller index first: sort DESCENDING on the packed word
+    const uint32_t ord = vbits ^ ((vbits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+    return ((uint64_t)ord << 32) | (uint64_t)(0xFFFFFFFFu - idx);
+}
+__device__ __forceinline__ uint2 unpack_value(uint64_t w) {
+    const uint32_t ord = (uint32_t)(w >> 32);
+    const uint32_t vbits = ord ^ ((ord >> 31) ? 0x80000000u : 0xFFFFFFFFu);
+    return make_uint2(vbits, 0xFFFFFFFFu - (uint32_t)w);
+}
+
+__device__ void bitonic_desc_u64(uint64_t *s, int P) {
+    for (int k = 2; k <= P; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < P / 2; t += blockDim.x) {
+                const int i = 2 * t - (t & (j - 1)), p = i + j;          // pair (i, i + j)
+                const bool desc = (i & k) == 0;
+                const uint64_t x = s[i], y = s[p];
+                if ((x < y) == desc) { s[i] = y; s[p] = x; }
+            }
+            __syncthreads();
+        }
+}
+
+struct KeyIdx { double key; int idx; };
+__device__ __forceinline__ bool worse(double ka, int ia, double kb, int ib) { return ka > kb || (ka == kb && ia > ib); }
+
+__device__ void bitonic_asc_pair(double *key, int *idx, int P) {
+    for (int k = 2; k <= P; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < P / 2; t += blockDim.x) {
+                const int i = 2 * t - (t & (j - 1)), p = i + j;
+                const bool asc = (i & k) == 0;
+                const double kx = key[i], ky = key[p];
+                const int ix = idx[i], iy = idx[p];
+                if (worse(kx, ix, ky, iy) == asc) { key[i] = ky; key[p] = kx; idx[i] = iy; idx[p] = ix; }
+            }
+            __syncthreads();
+        }
+}
+
+// per query: keep the KP best buffered entries, refresh the threshold.  force: sort even when <= KP.
+__global__ void topk_compact_kernel(int32_t *cnt, uint2 *buf, int cap, int KP, float *thr, int32_t *flag, int Q,
+                                    int force) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    uint64_t *s = (uint64_t *)lds;
+    const int q = blockIdx.x;
+    if (q >= Q) return;
+    int n = cnt[q];
+    if (n > cap) { if (threadIdx.x == 0) flag[q] = 1; n = cap; }      // entries were dropped: exhaustive re-rank
+    if (n <= KP && !force) { if (threadIdx.x == 0 && cnt[q] != n) cnt[q] = n; return; }
+    int P = 1;
+    while (P < n) P <<= 1;
+    if (P < 2) P = 2;
+    for (int i = threadIdx.x; i < P; i += blockDim.x) {
+        uint64_t w = 0;                                      // padding sorts last
+        if (i < n) { const uint2 e = buf[(size_t)q * cap + i]; w = pack_value(e.x, e.y); }
+        s[i] = w;
+    }
+    __syncthreads();
+    bitonic_desc_u64(s, P);
+    const int keep = n < KP ? n : KP;
+    for (int i = threadIdx.x; i < keep; i += blockDim.x) buf[(size_t)q * cap + i] = unpack_value(s[i]);
+    if (threadIdx.x == 0) {
+        cnt[q] = keep;
+        if (n >= KP) thr[q] = __uint_as_float(unpack_value(s[KP - 1]).x);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp64 ranking key (smaller is better): DistMult -sum fma(h r, t), TransE sum fma(x, x), x = (h + r) - t
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__device__ double canonical_key(int scorer, int d, const void *ent, int64_t hoff, const void *rel, int64_t roff,
+                                int64_t toff) {
+    double acc = 0.0;
+    if (scorer == KGE_DISTMULT) {
+        for (int j = 0; j < d; ++j) {
+            const double hr = (double)El<BF16>::ld(ent, hoff + j) * (double)El<BF16>::ld(rel, roff + j);
+            acc = fma(hr, (double)El<BF16>::ld(ent, toff + j), acc);
+        }
+        return -acc;
+    }
+    for (int j = 0; j < d; ++j) {
+        const double x = ((double)El<BF16>::ld(ent, hoff + j) + (double)El<BF16>::ld(rel, roff + j)) -
+                         (double)El<BF16>::ld(ent, toff + j);
+        acc = fma(x, x, acc);
+    }
+    return acc;
+}
+
+template <bool BF16>
+__global__ void topk_rescore_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q, int64_t cand_lo,
+                                    const int32_t *cnt, const uint2 *buf, int cap, int KP, double *keyd) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int q = (int)(t / KP), s = (int)(t % KP);
+    if (q >= Q || s >= cnt[q]) return;
+    const int64_t cand = cand_lo + buf[(size_t)q * cap + s].y;
+    keyd[(size_t)q * KP + s] = canonical_key<BF16>(m.scorer, m.dim, m.ent, (int64_t)h[q] * m.ent_ld, m.rel,
+                                                   (int64_t)r[q] * m.rel_ld, cand * m.ent_ld);
+}
+
+struct QInfo { double qn; float eps_a, eps_b; float pad; };   // |q~|^2 (fp64), rounding-bound coefficients
+
+// final ordering, safety check, outputs
+template <bool BF16>
+__global__ void topk_final_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q, int64_t cand_lo,
+                                  int64_t ncand, const int32_t *cnt, const uint2 *buf, int cap, int KP, int KPP,
+                                  const double *keyd, const float *thr, const QInfo *qinfo, const float *tmax2,
+                                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t,
+                                  const uint32_t *rankcnt, int64_t *out_rank, int32_t *flag) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    double *key = (double *)lds;
+    int *idx = (int *)(lds + (size_t)KPP * 8);
+    const int q = blockIdx.x;
+    if (q >= Q) return;
+    const int n = cnt[q];
+    for (int i = threadIdx.x; i < KPP; i += blockDim.x) {
+        key[i] = i < n ? keyd[(size_t)q * KP + i] : INFINITY;
+        idx[i] = i < n ? (int)buf[(size_t)q * cap + i].y : 0x7FFFFFFF;
+    }
+    __syncthreads();
+    bitonic_asc_pair(key, idx, KPP);
+    const bool dm = m.scorer == KGE_DISTMULT;
+    for (int i = threadIdx.x; i < K; i += blockDim.x) {
+        const bool ok = i < n;
+        out_idx[(size_t)q * K + i] = ok ? (int32_t)(cand_lo + idx[i]) : -1;
+        out_score[(size_t)q * K + i] = ok ? (dm ? (float)(-key[i]) : (float)(-sqrt(key[i]))) : -INFINITY;
+    }
+    if (threadIdx.x == 0) {
+        // Everything that was discarded has a matrix-core value <= theta (the KP-th best value).  Its
+        // exact value is at most theta + eps; the list is safe if that stays strictly below the exact
+        // value of the K-th entry.  eps bounds the rounding of the query to the table type and the
+        // fp32 accumulation:  DistMult (|dq| + d 2^-23 |q~|) Tmax;  TransE 2|dq|(|q~|+Tmax) + |dq|^2 +
+        // d 2^-22 (|q~|+Tmax)^2, with Tmax the largest candidate norm.
+        if (n >= KP && ncand > KP && K <= n) {
+            const QInfo qi = qinfo[q];
+            const double Tm = sqrt((double)*tmax2);
+            double eps, exactK;
+            if (dm) { eps = ((double)qi.eps_a + (double)qi.eps_b) * Tm; exactK = -key[K - 1]; }
+            else {
+                const double s = sqrt(qi.qn) + Tm;
+                eps = 2.0 * qi.eps_a * s + (double)qi.eps_a * qi.eps_a + (double)qi.eps_b * s * s;
+                exactK = -key[K - 1] + qi.qn;
+            }
+            eps = eps * 1.01 + 1e-30;
+            if (!((double)thr[q] + eps < exactK)) flag[q] = 1;
+        }
+        if (out_rank) {
+            const int tt = true_t[q];
+            int64_t rank = 1 + (int64_t)rankcnt[q];
+            bool in_range = tt >= cand_lo && tt < cand_lo + ncand;
+            int pos = -1;
+            const int lim = K < n ? K : n;
+            for (int i = 0; i < lim; ++i) if (cand_lo + idx[i] == tt) { pos = i; break; }
+            if (pos >= 0) rank = pos + 1;                    // exact: position in the fp64 ordering
+            else if (in_range && rank <= lim) rank = lim + 1; // it is not in the exact list, so it ranks below it
+            out_rank[q] = rank;
+        }
+    }
+}
+
+// exhaustive fp64 re-rank of one flagged query per workgroup
+template <bool BF16>
+__global__ void topk_exact_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q, int64_t cand_lo,
+                                  int64_t ncand, int K, int32_t *out_idx, float *out_score, const int32_t *true_t,
+                                  int64_t *out_rank, const int32_t *flag) {
+    constexpr int CAPX = 2048;
+    __shared__ double key[CAPX];
+    __shared__ int idx[CAPX];
+    __shared__ int count;
+    __shared__ double tau;
+    __shared__ unsigned long long above;
+    const int q = blockIdx.x;
+    if (q >= Q || !flag[q]) return;
+    const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
+    double tkey = 0.0; int tt = -1;
+    if (true_t) { tt = true_t[q]; tkey = canonical_key<BF16>(m.scorer, m.dim, m.ent, hoff, m.rel, roff, (int64_t)tt * m.ent_ld); }
+    if (threadIdx.x == 0) { count = 0; tau = INFINITY; above = 0ull; }
+    for (int i = threadIdx.x; i < CAPX; i += blockDim.x) { key[i] = INFINITY; idx[i] = 0x7FFFFFFF; }
+    __syncthreads();
+    unsigned long long mine = 0;
+    for (int64_t c0 = 0; c0 < ncand; c0 += blockDim.x) {
+        const int64_t c = c0 + threadIdx.x;
+        if (c < ncand) {
+            const double kc = canonical_key<BF16>(m.scorer, m.dim, m.ent, hoff, m.rel, roff, (cand_lo + c) * m.ent_ld);
+            if (true_t && (kc < tkey || (kc == tkey && cand_lo + c < tt))) ++mine;
+            if (kc <= tau) { const int s = atomicAdd(&count, 1); key[s] = kc; idx[s] = (int)c; }   // s < CAPX by the compaction below
+        }
+        __syncthreads();
+        if (count > CAPX - (int)blockDim.x) {                // next round could overflow: compact to the K best
+            bitonic_asc_pair(key, idx, CAPX);
+            if (threadIdx.x == 0) { count = K; tau = key[K - 1]; }
+            __syncthreads();
+            for (int i = K + threadIdx.x; i < CAPX; i += blockDim.x) { key[i] = INFINITY; idx[i] = 0x7FFFFFFF; }
+            __syncthreads();
+        }
+    }
+    bitonic_asc_pair(key, idx, CAPX);
+    const bool dm = m.scorer == KGE_DISTMULT;
+    for (int i = threadIdx.x; i < K; i += blockDim.x) {
+        const bool ok = idx[i] != 0x7FFFFFFF;
+        out_idx[(size_t)q * K + i] = ok ? (int32_t)(cand_lo + idx[i]) : -1;
+        out_score[(size_t)q * K + i] = ok ? (dm ? (float)(-key[i]) : (float)(-sqrt(key[i]))) : -INFINITY;
+    }
+    if (true_t) {
+        atomicAdd(&above, mine);
+        __syncthreads();
+        if (threadIdx.x == 0) out_rank[q] = 1 + (int64_t)above;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// preparation
+// ---------------------------------------------------------------------------------------------
+// one wave per query: Q row in the table type, value of the held-out tail, rounding-bound coefficients
+template <bool BF16>
+__global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *true_t, int Q,
+                                 int Qp, int dp, void *Qm, float *vt, QInfo *qinfo, float *thr, int32_t *cnt,
+                                 int32_t *flag, uint32_t *rankcnt) {
+    const int lane = threadIdx.x & 63;
+    const int q = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (q >= Qp) return;
+    if (q >= Q) {
+        for (int j = lane; j < dp; j += 64) El<BF16>::st(Qm, (int64_t)q * dp + j, 0.f);
+        if (lane == 0) { vt[q] = INFINITY; thr[q] = INFINITY; cnt[q] = 0; flag[q] = 0; rankcnt[q] = 0; }
+        return;
+    }
+    KgeRowCtx<BF16> cx;
+    kge_build_query<BF16>(m, h[q], r[q], lane, cx);
+    const int d = m.dim;
+    const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
+    double qn = 0.0, dq2 = 0.0;
+    float vtl = 0.f, tnl = 0.f;
+    const int64_t toff = true_t ? (int64_t)true_t[q] * m.ent_ld : 0;
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        const float qr = El<BF16>::rnd(cx.q[k]);
+        if (j < dp) El<BF16>::st(Qm, (int64_t)q * dp + j, cx.q[k]);
+        if (j >= d) continue;
+        const double hx = (double)El<BF16>::ld(m.ent, hoff + j), rx = (double)El<BF16>::ld(m.rel, roff + j);
+        const double qex = m.scorer == KGE_DISTMULT ? hx * rx : hx + rx;      // the exact query component
+        const double dq = (double)qr - qex;
+        qn += (double)qr * (double)qr; dq2 += dq * dq;
+        if (true_t) { const float tv = El<BF16>::ld(m.ent, toff + j); vtl += qr * tv; tnl += tv * tv; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        qn += __shfl_xor(qn, o); dq2 += __shfl_xor(dq2, o); vtl += __shfl_xor(vtl, o); tnl += __shfl_xor(tnl, o);
+    }
+    if (lane == 0) {
+        QInfo qi;
+        qi.qn = qn;
+        qi.eps_a = (float)(sqrt(dq2) * 1.0001);
+        qi.eps_b = m.scorer == KGE_DISTMULT ? (float)(d * 1.1920929e-07 * sqrt(qn) * 1.0001)    // d 2^-23 |q~|
+                                            : (float)(d * 2.3841858e-07);                        // d 2^-22
+        qi.pad = 0.f;
+        qinfo[q] = qi;
+        vt[q] = true_t ? (m.scorer == KGE_DISTMULT ? vtl : 2.f * vtl - tnl) : INFINITY;
+        thr[q] = -INFINITY; cnt[q] = 0; flag[q] = 0; rankcnt[q] = 0;
+    }
+}
+
+// squared norms of the candidate rows (one wave per row) and their maximum
+template <bool BF16>
+__global__ void topk_tnorm_kernel(const char *ent, int64_t stride, int d, int64_t ncand, int64_t npad, float *tn,
+                                  uint32_t *tmax_bits) {
+    const int lane = threadIdx.x & 63;
+    const int64_t c = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (c >= npad) return;
+    float s = 0.f;
+    if (c < ncand) for (int j = lane; j < d; j += 64) { const float v = El<BF16>::ld(ent + c * stride, j); s += v * v; }
+    s = kge_wave_sum(s);
+    if (lane == 0) { tn[c] = s; if (c < ncand) atomicMax(tmax_bits, __float_as_uint(s)); }   // s >= 0: bit order = value order
+}
+
+__global__ void topk_fill_empty_kernel(int32_t *out_idx, float *out_score, int64_t n, int64_t *out_rank, int Q) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { out_idx[i] = -1; out_score[i] = -INFINITY; }
+    if (out_rank && i < Q) out_rank[i] = 1;
+}
+
+__global__ void topk_zero_kernel(uint32_t *p) { *p = 0u; }
+
+struct TopkPlan {
+    bool bf16; int es, rb, dp, ob, own; int Qp; int KP, KPP, cap; int64_t npad;
+};
+
+TopkPlan make_plan(const kge_model_t &m, int64_t Q, int64_t ncand, int K) {
+    TopkPlan p{};
+    p.bf16 = m.dtype == KGE_BF16; p.es = p.bf16 ? 2 : 4;
+    p.rb = m.dim * p.es <= 512 ? 512 : 1024; p.dp = p.rb / p.es;
+    p.ob = p.rb == 512 ? 2 : 1; p.own = 128 * p.ob;
+    p.Qp = (int)kge_round_up(Q, p.own);
+    p.KP = (int)kge_round_up(2 * K + 56, 64);
+    p.KPP = 1; while (p.KPP < p.KP) p.KPP <<= 1;
+    p.cap = 1; while (p.cap < 16 * p.KP) p.cap <<= 1;
+    p.npad = kge_round_up(ncand > 0 ? ncand : 1, TK_ST);
+    return p;
+}
+
+struct TopkWs {
+    void *Qm; float *vt, *thr, *tn; QInfo *qinfo; int32_t *cnt, *flag; uint32_t *rankcnt, *tmax; uint2 *buf; double *keyd;
+};
+
+size_t topk_carve(const TopkPlan &p, void *ws, TopkWs &w) {
+    char *b = (char *)ws; size_t off = 0;
+    auto take = [&](size_t bytes) { void *q = b ? b + off : nullptr; off += (bytes + 255) / 256 * 256; return q; };
+    w.Qm = take((size_t)p.Qp * p.rb);
+    w.vt = (float *)take((size_t)p.Qp * 4); w.thr = (float *)take((size_t)p.Qp * 4);
+    w.qinfo = (QInfo *)take((size_t)p.Qp * sizeof(QInfo));
+    w.cnt = (int32_t *)take((size_t)p.Qp * 4); w.flag = (int32_t *)take((size_t)p.Qp * 4);
+    w.rankcnt = (uint32_t *)take((size_t)p.Qp * 4); w.tmax = (uint32_t *)take(256);
+    w.tn = (float *)take((size_t)p.npad * 4);
+    w.buf = (uint2 *)take((size_t)p.Qp * p.cap * 8);
+    w.keyd = (double *)take((size_t)p.Qp * p.KP * 8);
+    return off + 256;
+}
+
+template <bool BF16, int RB, int KIND, int OB>
+int launch_scan(const TopkArgs &a, int own_tiles, int nsplit, hipStream_t st) {
+    constexpr int LDS = 2 * (TK_ST * (RB + 16) + TK_ST * 4);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void *)topk_scan_kernel<BF16, RB, KIND, OB>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
+            return KGE_E_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((topk_scan_kernel<BF16, RB, KIND, OB>), dim3(own_tiles, nsplit), dim3(256), LDS, st, a);
+    return kge_launch_status();
+}
+
+}  // namespace
+
+size_t kge_topk_ws(const kge_model_t &model, int64_t Q, int64_t ncand, int K) {
+    if (Q < 0 || ncand < 0 || K < 1 || K > 256) return 0;
+    TopkPlan p = make_plan(model, Q, ncand, K);
+    TopkWs w;
+    return topk_carve(p, nullptr, w);
+}
+
+int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, int64_t Q, int64_t lo, int64_t hi,
+                 int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
+                 size_t ws_bytes, hipStream_t st) {
+    (void)ws_bytes;
+    const int64_t ncand = hi - lo;
+    if (ncand == 0) {
+        const int64_t n = Q * K;
+        hipLaunchKernelGGL(topk_fill_empty_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, out_idx, out_score, n,
+                           out_rank, (int)Q);
+        return kge_launch_status();
+    }
+    const TopkPlan p = make_plan(model, Q, ncand, K);
+    TopkWs w;
+    topk_carve(p, ws, w);
+    KgeModelDev md;
+    md.scorer = model.scorer; md.bf16 = p.bf16; md.dim = model.dim; md.rel_dim = model.rel_dim;
+    md.ent = model.ent; md.rel = model.rel; md.relw = model.relw;
+    md.ent_ld = model.ent_ld; md.rel_ld = model.rel_ld; md.relw_ld = model.relw_ld;
+    const char *cand0 = (const char *)model.ent + lo * model.ent_ld * p.es;
+    const int64_t stride = model.ent_ld * p.es;
+    const int kind = model.scorer == KGE_DISTMULT ? KGE_KIND_MULT : KGE_KIND_DIST;
+
+    hipLaunchKernelGGL(topk_zero_kernel, dim3(1), dim3(1), 0, st, w.tmax);
+    if (p.bf16) {
+        hipLaunchKernelGGL(topk_prep_kernel<true>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
+        hipLaunchKernelGGL(topk_tnorm_kernel<true>, dim3((unsigned)((p.npad + 3) / 4)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
+    } else {
+        hipLaunchKernelGGL(topk_prep_kernel<false>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
+        hipLaunchKernelGGL(topk_tnorm_kernel<false>, dim3((unsigned)((p.npad + 3) / 4)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
+    }
+    if (hipGetLastError() != hipSuccess) return KGE_E_HIP;
+
+    TopkArgs base{};
+    base.Qmat = w.Qm; base.ent = cand0; base.ent_stride = stride; base.valid_bytes = model.dim * p.es;
+    base.ncand = ncand; base.cand_lo = lo; base.tn = w.tn; base.thr = w.thr; base.vt = w.vt; base.true_t = true_t;
+    base.cnt = w.cnt; base.buf = w.buf; base.cap = p.cap; base.rankcnt = w.rankcnt; base.nq = (int)Q;
+    const int own_tiles = p.Qp / p.own;
+    const int64_t total_tiles = p.npad / TK_ST;
+    // growing chunks: the first fills the buffers half, later ones are 7x what has been seen, so a query
+    // with a well-mixed candidate order appends about 7 KP entries per chunk (the buffer holds 16 KP)
+    int64_t seen = 0;
+    const int compact_lds = p.cap * 8;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)topk_compact_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8) != hipSuccess)
+            return KGE_E_HIP;
+        attr_done = true;
+    }
+    while (seen < total_tiles) {
+        int64_t tiles = seen == 0 ? (p.cap / 2) / TK_ST : 7 * seen;
+        if (tiles > total_tiles - seen) tiles = total_tiles - seen;
+        TopkArgs c = base;
+        c.tile_lo = seen; c.tile_hi = seen + tiles;
+        int want = (1024 + own_tiles - 1) / own_tiles;        // a few workgroups per compute unit
+        if (want > tiles) want = (int)tiles;
+        c.tiles_per_wg = (int)((tiles + want - 1) / want);
+        const int nsplit = (int)((tiles + c.tiles_per_wg - 1) / c.tiles_per_wg);
+        int rc;
+        {
+            KgeProfScope prof(KGE_PROF_TOPK_SCAN, st);
+            if (p.bf16 && p.rb == 512) rc = kind == KGE_KIND_MULT ? launch_scan<true, 512, KGE_KIND_MULT, 2>(c, own_tiles, nsplit, st) : launch_scan<true, 512, KGE_KIND_DIST, 2>(c, own_tiles, nsplit, st);
+            else if (p.bf16) rc = kind == KGE_KIND_MULT ? launch_scan<true, 1024, KGE_KIND_MULT, 1>(c, own_tiles, nsplit, st) : launch_scan<true, 1024, KGE_KIND_DIST, 1>(c, own_tiles, nsplit, st);
+            else if (p.rb == 512) rc = kind == KGE_KIND_MULT ? launch_scan<false, 512, KGE_KIND_MULT, 2>(c, own_tiles, nsplit, st) : launch_scan<false, 512, KGE_KIND_DIST, 2>(c, own_tiles, nsplit, st);
+            else rc = kind == KGE_KIND_MULT ? launch_scan<false, 1024, KGE_KIND_MULT, 1>(c, own_tiles, nsplit, st) : launch_scan<false, 1024, KGE_KIND_DIST, 1>(c, own_tiles, nsplit, st);
+        }
+        if (rc != KGE_OK) return rc;
+        seen += tiles;
+        const int force = seen >= total_tiles;
+        hipLaunchKernelGGL(topk_compact_kernel, dim3((unsigned)Q), dim3(256), compact_lds, st, w.cnt, w.buf, p.cap, p.KP, w.thr, w.flag, (int)Q, force);
+    }
+    const int64_t nres = Q * p.KP;
+    const int final_lds = p.KPP * 12;
+    if (p.bf16) {
+        hipLaunchKernelGGL(topk_rescore_kernel<true>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.buf, p.cap, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_final_kernel<true>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.buf, p.cap, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
+        hipLaunchKernelGGL(topk_exact_kernel<true>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
+    } else {
+        hipLaunchKernelGGL(topk_rescore_kernel<false>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.buf, p.cap, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_final_kernel<false>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.buf, p.cap, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
+        hipLaunchKernelGGL(topk_exact_kernel<false>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
+    }
+    return kge_launch_status();
+}
