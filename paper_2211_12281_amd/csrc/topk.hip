@@ -18,6 +18,7 @@
 namespace {
 
 constexpr int TK_ST = 32;               // candidate rows per tile
+constexpr int TK_HALF = 64;             // entries of one private append area
 
 struct TopkArgs {
     const void *Qmat;                   // [Qp][dp] queries (table element type)
@@ -30,112 +31,190 @@ struct TopkArgs {
     const float *thr;                   // [Qp] current threshold (local value units)
     const float *vt;                    // [Qp] value of the held-out tail (local units), +inf when absent
     const int32_t *true_t;              // [Q] entity ids, or nullptr
-    int32_t *cnt;                       // [Qp] entries in each buffer
-    uint2 *buf;                         // [Qp][cap] {value bits, candidate index}
-    int32_t cap;
+    uint2 *seg;                         // [Qp][nseg][2][TK_HALF] {value bits, candidate index}: private append
+    int32_t *segcnt;                    // [Qp][nseg][2]           areas of each (query, split, lane half)
+    int32_t nseg;
     uint32_t *rankcnt;                  // [Qp] candidates whose value beats the held-out tail's
     int32_t nq;                         // number of real queries (rows past it are padding)
     int64_t tile_lo, tile_hi;
     int32_t tiles_per_wg;
+    int32_t own_tiles;
+    const void *zeros;                  // 16 zero bytes (source of the padding columns)
 };
 
+// Asynchronous global -> LDS copies (gfx950): lane l of a wave-wide instruction writes its 16 (or 4)
+// bytes to LDS byte address m0 + l*16 (l*4); the data never passes through registers, completion is
+// tracked by vmcnt.  The compiler does not see these loads, so the waits are explicit.
+__device__ __forceinline__ void async_copy16(const void *g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+__device__ __forceinline__ void async_copy4(const void *g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // "Local value": larger is better; DistMult: q.t; TransE: 2 q.t - |t|^2 (= -dist^2 + |q|^2).
+//
+// Candidate tiles (32 rows) stream through an LDS ring of NSTAGE stages filled by asynchronous copies,
+// so several tiles are in flight per compute unit.  A row of RB bytes is stored unpadded with its
+// 16-byte chunks XOR-swizzled by (row & 7): the MFMA A-fragment reads of 8 consecutive rows then fall
+// into 8 different bank groups.  The MFMAs of tile t+1 are issued before the epilogue of tile t, so the
+// matrix pipe works while the vector ALU filters.
 template <bool BF16, int RB, int KIND, int OB>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256)))
 void topk_scan_kernel(const TopkArgs a) {
     constexpr int KS = RB / 32;
-    constexpr int X_STRIDE = RB + 16;
-    constexpr int X_BYTES = TK_ST * X_STRIDE;
-    constexpr int STAGE_BYTES = X_BYTES + TK_ST * 4;
-    constexpr int X_UNITS = TK_ST * RB / 16 / 256;
+    constexpr int TILE_BYTES = TK_ST * RB;
+    constexpr int NINST = TILE_BYTES / 1024;            // wave-wide 1 KB copies per tile
+    constexpr int IPW = NINST / 4;                      // ... per wave
+    constexpr int LPW = IPW + 1;                        // plus the norms
+    constexpr int NSTAGE = RB == 512 ? 4 : 3;
+    constexpr int SIDE_SLOTS = NSTAGE + 1;
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    char *side_base = lds + NSTAGE * TILE_BYTES;        // [SIDE_SLOTS][4 waves][64 floats]
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
-    const int own_base = blockIdx.x * (128 * OB);
-    const int64_t t0 = a.tile_lo + (int64_t)blockIdx.y * a.tiles_per_wg;
+    // Workgroups are handed to the 8 XCDs round-robin.  All query tiles that walk the same candidate
+    // range are given ids with the same residue mod 8, so they share one XCD's L2 and the range is
+    // fetched from HBM once.
+    const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
+    const int own_tile = kk % a.own_tiles, split = xcd + 8 * (kk / a.own_tiles);
+    const int own_base = own_tile * (128 * OB);
+    const int64_t t0 = a.tile_lo + (int64_t)split * a.tiles_per_wg;
     const int64_t t1 = t0 + a.tiles_per_wg < a.tile_hi ? t0 + a.tiles_per_wg : a.tile_hi;
-    if (t0 >= t1) return;
+    // Every (query, split, lane half) owns a private append area, so appending needs no atomics: the
+    // count lives in a register and is stored once at the end.  Two lanes (g = 0, 1) serve one query.
+    if (t0 >= t1) {
+        if (split < a.nseg)
+            for (int ob = 0; ob < OB; ++ob)
+                a.segcnt[((size_t)(own_base + (wave * OB + ob) * 32 + lr) * a.nseg + split) * 2 + g] = 0;
+        return;
+    }
 
     uint4 own[OB][KS];
     float thr[OB], vt[OB];
-    int qid[OB], tt[OB];
+    int qid[OB], myc[OB];
+    uint2 *segp[OB];
     uint32_t above[OB];
 #pragma unroll
     for (int ob = 0; ob < OB; ++ob) {
         qid[ob] = own_base + (wave * OB + ob) * 32 + lr;
+        myc[ob] = 0;
+        segp[ob] = a.seg + (((size_t)qid[ob] * a.nseg + split) * 2 + g) * TK_HALF;
         const char *p = (const char *)a.Qmat + (size_t)qid[ob] * RB + g * 16;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) own[ob][ks] = *(const uint4 *)(p + ks * 32);
         thr[ob] = a.thr[qid[ob]];
         vt[ob] = a.vt[qid[ob]];
-        tt[ob] = (a.true_t && qid[ob] < a.nq) ? a.true_t[qid[ob]] : -1;
         above[ob] = 0;
     }
 
-    kge_u32x4 px[X_UNITS];
-    float ptn = 0.f;
-    auto gload = [&](int64_t tile) {
+    // ---- loader geometry of this lane: instruction jj covers LDS bytes [(wave*IPW+jj) KB, +1 KB) ----
+    int ld_row[IPW], ld_col[IPW];
 #pragma unroll
-        for (int u = 0; u < X_UNITS; ++u) {
-            const int unit = tid + u * 256, row = unit / (RB / 16), cu = unit % (RB / 16);
-            int64_t cand = tile * TK_ST + row;
-            cand = cand < a.ncand ? cand : a.ncand - 1;                    // rows past the end are masked later
-            kge_u32x4 v = {0u, 0u, 0u, 0u};
-            if (cu * 16 < a.valid_bytes) v = *(const kge_u32x4 *)(a.ent + cand * a.ent_stride + cu * 16);
-            px[u] = v;
-        }
-        if (tid < TK_ST) ptn = a.tn[tile * TK_ST + tid];
-    };
-    auto lstore = [&](int stage) {
-        char *base = lds + stage * STAGE_BYTES;
+    for (int jj = 0; jj < IPW; ++jj) {
+        const int byte = (wave * IPW + jj) * 1024 + lane * 16;
+        const int r = byte / RB, pos = (byte % RB) / 16;
+        ld_row[jj] = r;
+        ld_col[jj] = (pos ^ (r & 7)) * 16;              // source chunk that belongs at this LDS position
+    }
+    auto issue = [&](int64_t tile, int slot) {
+        tile = tile < t1 ? tile : t1 - 1;               // past the end: a harmless repeat keeps vmcnt uniform
+        const int stage = slot % NSTAGE;
 #pragma unroll
-        for (int u = 0; u < X_UNITS; ++u) {
-            const int unit = tid + u * 256, row = unit / (RB / 16), cu = unit % (RB / 16);
-            *(kge_u32x4 *)(base + row * X_STRIDE + cu * 16) = px[u];
+        for (int jj = 0; jj < IPW; ++jj) {
+            int64_t cand = tile * TK_ST + ld_row[jj];
+            cand = cand < a.ncand ? cand : a.ncand - 1; // rows past the end are masked in the epilogue
+            const char *gp = ld_col[jj] < a.valid_bytes ? a.ent + cand * a.ent_stride + ld_col[jj] : (const char *)a.zeros;
+            async_copy16(gp, __builtin_amdgcn_readfirstlane(lds0 + stage * TILE_BYTES + (wave * IPW + jj) * 1024));
         }
-        if (tid < TK_ST) *(float *)(base + X_BYTES + tid * 4) = ptn;
+        async_copy4(a.tn + tile * TK_ST + lr,
+                    __builtin_amdgcn_readfirstlane(lds0 + NSTAGE * TILE_BYTES + ((slot % SIDE_SLOTS) * 4 + wave) * 256));
     };
-
-    gload(t0);
-    lstore(0);
-    __syncthreads();
-    for (int64_t tile = t0; tile < t1; ++tile) {
-        const int stage = (int)((tile - t0) & 1);
-        const bool more = tile + 1 < t1;
-        if (more) gload(tile + 1);
-        const char *base = lds + stage * STAGE_BYTES;
-        kge_f32x16 acc[OB];
+    // ---- A-fragment addresses: chunk (2 ks + g) of row lr sits at position chunk ^ (lr & 7) -----------
+    int frag_off[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) frag_off[b] = lr * RB + 16 * (((2 * b) ^ (lr & 6)) | (g ^ (lr & 1)));
+    auto mma_tile = [&](int slot, kge_f32x16 (&acc)[OB]) {
+        const char *base = lds + (slot % NSTAGE) * TILE_BYTES;
+        uint4 av[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) av[ks] = *(const uint4 *)(base + frag_off[ks & 3] + 128 * (ks >> 2));
 #pragma unroll
         for (int ob = 0; ob < OB; ++ob) for (int i = 0; i < 16; ++i) acc[ob][i] = 0.f;
-        const char *xrow = base + lr * X_STRIDE + g * 16;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const uint4 av = *(const uint4 *)(xrow + ks * 32);
 #pragma unroll
-            for (int ob = 0; ob < OB; ++ob) acc[ob] = kge_mma16<BF16>(acc[ob], av, own[ob][ks]);
+            for (int ob = 0; ob < OB; ++ob) acc[ob] = kge_mma16<BF16>(acc[ob], av[ks], own[ob][ks]);
         }
-        const int64_t cbase = tile * TK_ST + 4 * g;         // candidate of register i: cbase + 8*(i/4) + (i%4)
+    };
+
+#pragma unroll
+    for (int s2 = 0; s2 < NSTAGE - 1; ++s2) issue(t0 + s2, s2);
+    wait_vmcnt<(NSTAGE - 2) * LPW>();
+    __syncthreads();
+    issue(t0 + NSTAGE - 1, NSTAGE - 1);
+    kge_f32x16 acc[OB];
+    mma_tile(0, acc);
+
+    for (int64_t tile = t0; tile < t1; ++tile) {
+        const int slot = (int)(tile - t0);
+        // ---- tile + 1: wait for its data, refill the stage that tile `tile` just vacated, start its MFMAs
+        kge_f32x16 accn[OB];
+        wait_vmcnt<(NSTAGE - 2) * LPW>();
+        __syncthreads();
+        issue(tile + NSTAGE, slot + NSTAGE);
+        mma_tile(slot + 1, accn);                       // (the last iteration recomputes a stale stage: unused)
+        // ---- epilogue of tile `tile`: cheap wave-level test first, the append path only on a hit ----
+        const char *side = side_base + ((slot % SIDE_SLOTS) * 4 + wave) * 256;
         const bool tile_full = tile * TK_ST + TK_ST <= a.ncand;
+        float vv[OB][16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
-            const int64_t cand = cbase + 8 * (i >> 2) + (i & 3);
             float tnv = 0.f;
-            if constexpr (KIND == KGE_KIND_DIST) tnv = *(const float *)(base + X_BYTES + sl * 4);
+            if constexpr (KIND == KGE_KIND_DIST) tnv = *(const float *)(side + sl * 4);
 #pragma unroll
-            for (int ob = 0; ob < OB; ++ob) {
-                float v = KIND == KGE_KIND_DIST ? fmaf(2.f, acc[ob][i], -tnv) : acc[ob][i];
-                if (!tile_full && cand >= a.ncand) v = -INFINITY;
-                if (a.true_t) above[ob] += (v > vt[ob] && (int)(cand + a.cand_lo) != tt[ob]) ? 1u : 0u;
-                if (v > thr[ob] && qid[ob] < a.nq) {
-                    const int slot = atomicAdd(a.cnt + qid[ob], 1);
-                    if (slot < a.cap) a.buf[(size_t)qid[ob] * a.cap + slot] = make_uint2(__float_as_uint(v), (uint32_t)cand);
+            for (int ob = 0; ob < OB; ++ob) vv[ob][i] = KIND == KGE_KIND_DIST ? fmaf(2.f, acc[ob][i], -tnv) : acc[ob][i];
+        }
+        if (!tile_full) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const bool out = tile * TK_ST + 8 * (i >> 2) + 4 * g + (i & 3) >= a.ncand;
+#pragma unroll
+                for (int ob = 0; ob < OB; ++ob) vv[ob][i] = out ? -INFINITY : vv[ob][i];
+            }
+        }
+#pragma unroll
+        for (int ob = 0; ob < OB; ++ob) {
+            if (a.true_t) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) above[ob] += vv[ob][i] > vt[ob] ? 1u : 0u;
+            }
+            float mx = vv[ob][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, vv[ob][i]);
+            if (__any(mx > thr[ob])) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    if (vv[ob][i] > thr[ob]) {
+                        const int64_t cand = tile * TK_ST + 8 * (i >> 2) + 4 * g + (i & 3);
+                        if (myc[ob] < TK_HALF) segp[ob][myc[ob]] = make_uint2(__float_as_uint(vv[ob][i]), (uint32_t)cand);
+                        ++myc[ob];                      // counts past TK_HALF mark the overflow for the compaction
+                    }
                 }
             }
         }
-        if (more) lstore(stage ^ 1);
-        __syncthreads();
+#pragma unroll
+        for (int ob = 0; ob < OB; ++ob) acc[ob] = accn[ob];
     }
+    wait_vmcnt<0>();                                    // no copy may still be in flight when the LDS is released
+#pragma unroll
+    for (int ob = 0; ob < OB; ++ob) a.segcnt[((size_t)qid[ob] * a.nseg + split) * 2 + g] = myc[ob];
     if (a.true_t) {
 #pragma unroll
         for (int ob = 0; ob < OB; ++ob) if (above[ob] && qid[ob] < a.nq) atomicAdd(a.rankcnt + qid[ob], above[ob]);
@@ -186,30 +265,44 @@ __device__ void bitonic_asc_pair(double *key, int *idx, int P) {
         }
 }
 
-// per query: keep the KP best buffered entries, refresh the threshold.  force: sort even when <= KP.
-__global__ void topk_compact_kernel(int32_t *cnt, uint2 *buf, int cap, int KP, float *thr, int32_t *flag, int Q,
-                                    int force) {
+// per query: merge the kept list with the fresh append areas, keep the KP best, refresh the threshold
+constexpr int TK_SORTCAP = 8192;        // entries one workgroup can sort in LDS
+__global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *seg, const int32_t *segcnt, int nseg,
+                                    int nsplit, int KP, float *thr, int32_t *flag, int Q) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     uint64_t *s = (uint64_t *)lds;
+    __shared__ int total, over;
     const int q = blockIdx.x;
     if (q >= Q) return;
-    int n = cnt[q];
-    if (n > cap) { if (threadIdx.x == 0) flag[q] = 1; n = cap; }      // entries were dropped: exhaustive re-rank
-    if (n <= KP && !force) { if (threadIdx.x == 0 && cnt[q] != n) cnt[q] = n; return; }
-    int P = 1;
-    while (P < n) P <<= 1;
-    if (P < 2) P = 2;
-    for (int i = threadIdx.x; i < P; i += blockDim.x) {
-        uint64_t w = 0;                                      // padding sorts last
-        if (i < n) { const uint2 e = buf[(size_t)q * cap + i]; w = pack_value(e.x, e.y); }
-        s[i] = w;
+    const int kept = keepcnt[q];
+    if (threadIdx.x == 0) { total = kept; over = 0; }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kept; i += blockDim.x) { const uint2 e = keep[(size_t)q * KP + i]; s[i] = pack_value(e.x, e.y); }
+    // areas are appended in (split, half) order; the order does not matter: the sort below is total
+    for (int a2 = threadIdx.x; a2 < nsplit * 2; a2 += blockDim.x) {
+        int c = segcnt[(size_t)q * nseg * 2 + a2];
+        if (c > TK_HALF) { over = 1; c = TK_HALF; }
+        if (c > 0) {
+            const int base = atomicAdd(&total, c);
+            if (base + c <= TK_SORTCAP) {
+                const uint2 *src = seg + ((size_t)q * nseg * 2 + a2) * TK_HALF;
+                for (int i = 0; i < c; ++i) s[base + i] = pack_value(src[i].x, src[i].y);
+            } else over = 1;
+        }
     }
     __syncthreads();
+    if (over) { if (threadIdx.x == 0) flag[q] = 1; }         // entries were dropped: exhaustive re-rank later
+    int n = total < TK_SORTCAP ? total : TK_SORTCAP;
+    if (over && total > TK_SORTCAP) n = kept;                // partially filled: keep the old list
+    int P = 2;
+    while (P < n) P <<= 1;
+    for (int i = n + threadIdx.x; i < P; i += blockDim.x) s[i] = 0;   // padding sorts last
+    __syncthreads();
     bitonic_desc_u64(s, P);
-    const int keep = n < KP ? n : KP;
-    for (int i = threadIdx.x; i < keep; i += blockDim.x) buf[(size_t)q * cap + i] = unpack_value(s[i]);
+    const int keepn = n < KP ? n : KP;
+    for (int i = threadIdx.x; i < keepn; i += blockDim.x) keep[(size_t)q * KP + i] = unpack_value(s[i]);
     if (threadIdx.x == 0) {
-        cnt[q] = keep;
+        keepcnt[q] = keepn;
         if (n >= KP) thr[q] = __uint_as_float(unpack_value(s[KP - 1]).x);
     }
 }
@@ -238,11 +331,11 @@ __device__ double canonical_key(int scorer, int d, const void *ent, int64_t hoff
 
 template <bool BF16>
 __global__ void topk_rescore_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q, int64_t cand_lo,
-                                    const int32_t *cnt, const uint2 *buf, int cap, int KP, double *keyd) {
+                                    const int32_t *cnt, const uint2 *buf, int KP, double *keyd) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int q = (int)(t / KP), s = (int)(t % KP);
     if (q >= Q || s >= cnt[q]) return;
-    const int64_t cand = cand_lo + buf[(size_t)q * cap + s].y;
+    const int64_t cand = cand_lo + buf[(size_t)q * KP + s].y;
     keyd[(size_t)q * KP + s] = canonical_key<BF16>(m.scorer, m.dim, m.ent, (int64_t)h[q] * m.ent_ld, m.rel,
                                                    (int64_t)r[q] * m.rel_ld, cand * m.ent_ld);
 }
@@ -252,7 +345,7 @@ struct QInfo { double qn; float eps_a, eps_b; float pad; };   // |q~|^2 (fp64), 
 // final ordering, safety check, outputs
 template <bool BF16>
 __global__ void topk_final_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q, int64_t cand_lo,
-                                  int64_t ncand, const int32_t *cnt, const uint2 *buf, int cap, int KP, int KPP,
+                                  int64_t ncand, const int32_t *cnt, const uint2 *buf, int KP, int KPP,
                                   const double *keyd, const float *thr, const QInfo *qinfo, const float *tmax2,
                                   int K, int32_t *out_idx, float *out_score, const int32_t *true_t,
                                   const uint32_t *rankcnt, int64_t *out_rank, int32_t *flag) {
@@ -264,7 +357,7 @@ __global__ void topk_final_kernel(KgeModelDev m, const int32_t *h, const int32_t
     const int n = cnt[q];
     for (int i = threadIdx.x; i < KPP; i += blockDim.x) {
         key[i] = i < n ? keyd[(size_t)q * KP + i] : INFINITY;
-        idx[i] = i < n ? (int)buf[(size_t)q * cap + i].y : 0x7FFFFFFF;
+        idx[i] = i < n ? (int)buf[(size_t)q * KP + i].y : 0x7FFFFFFF;
     }
     __syncthreads();
     bitonic_asc_pair(key, idx, KPP);
@@ -409,17 +502,22 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     }
 }
 
-// squared norms of the candidate rows (one wave per row) and their maximum
+// squared norms of the candidate rows and their maximum: a wave walks rows, one atomic per wave
 template <bool BF16>
 __global__ void topk_tnorm_kernel(const char *ent, int64_t stride, int d, int64_t ncand, int64_t npad, float *tn,
                                   uint32_t *tmax_bits) {
     const int lane = threadIdx.x & 63;
-    const int64_t c = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (c >= npad) return;
-    float s = 0.f;
-    if (c < ncand) for (int j = lane; j < d; j += 64) { const float v = El<BF16>::ld(ent + c * stride, j); s += v * v; }
-    s = kge_wave_sum(s);
-    if (lane == 0) { tn[c] = s; if (c < ncand) atomicMax(tmax_bits, __float_as_uint(s)); }   // s >= 0: bit order = value order
+    const int64_t wid = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t nw = (int64_t)gridDim.x * (blockDim.x >> 6);
+    float mx = 0.f;
+    for (int64_t c = wid; c < npad; c += nw) {
+        float s = 0.f;
+        if (c < ncand) for (int j = lane; j < d; j += 64) { const float v = El<BF16>::ld(ent + c * stride, j); s += v * v; }
+        s = kge_wave_sum(s);
+        if (lane == 0) tn[c] = s;
+        mx = fmaxf(mx, s);
+    }
+    if (lane == 0) atomicMax(tmax_bits, __float_as_uint(mx));    // mx >= 0: bit order = value order
 }
 
 __global__ void topk_fill_empty_kernel(int32_t *out_idx, float *out_score, int64_t n, int64_t *out_rank, int Q) {
@@ -428,10 +526,10 @@ __global__ void topk_fill_empty_kernel(int32_t *out_idx, float *out_score, int64
     if (out_rank && i < Q) out_rank[i] = 1;
 }
 
-__global__ void topk_zero_kernel(uint32_t *p) { *p = 0u; }
+__global__ void topk_zero_kernel(uint32_t *p, uint32_t *z) { if (threadIdx.x == 0) *p = 0u; if (threadIdx.x < 64) z[threadIdx.x] = 0u; }
 
 struct TopkPlan {
-    bool bf16; int es, rb, dp, ob, own; int Qp; int KP, KPP, cap; int64_t npad;
+    bool bf16; int es, rb, dp, ob, own; int Qp; int KP, KPP, nseg; int64_t npad;
 };
 
 TopkPlan make_plan(const kge_model_t &m, int64_t Q, int64_t ncand, int K) {
@@ -442,13 +540,13 @@ TopkPlan make_plan(const kge_model_t &m, int64_t Q, int64_t ncand, int K) {
     p.Qp = (int)kge_round_up(Q, p.own);
     p.KP = (int)kge_round_up(2 * K + 56, 64);
     p.KPP = 1; while (p.KPP < p.KP) p.KPP <<= 1;
-    p.cap = 1; while (p.cap < 16 * p.KP) p.cap <<= 1;
+    { int w = 1024 / (p.Qp / p.own); p.nseg = w < 32 ? 32 : (w > 256 ? 256 : w); }
     p.npad = kge_round_up(ncand > 0 ? ncand : 1, TK_ST);
     return p;
 }
 
 struct TopkWs {
-    void *Qm; float *vt, *thr, *tn; QInfo *qinfo; int32_t *cnt, *flag; uint32_t *rankcnt, *tmax; uint2 *buf; double *keyd;
+    void *Qm; float *vt, *thr, *tn; QInfo *qinfo; int32_t *cnt, *flag; uint32_t *rankcnt, *tmax; uint2 *keep, *seg; int32_t *segcnt; double *keyd; uint32_t *zeros;
 };
 
 size_t topk_carve(const TopkPlan &p, void *ws, TopkWs &w) {
@@ -458,23 +556,26 @@ size_t topk_carve(const TopkPlan &p, void *ws, TopkWs &w) {
     w.vt = (float *)take((size_t)p.Qp * 4); w.thr = (float *)take((size_t)p.Qp * 4);
     w.qinfo = (QInfo *)take((size_t)p.Qp * sizeof(QInfo));
     w.cnt = (int32_t *)take((size_t)p.Qp * 4); w.flag = (int32_t *)take((size_t)p.Qp * 4);
-    w.rankcnt = (uint32_t *)take((size_t)p.Qp * 4); w.tmax = (uint32_t *)take(256);
+    w.rankcnt = (uint32_t *)take((size_t)p.Qp * 4); w.tmax = (uint32_t *)take(256); w.zeros = (uint32_t *)take(256);
     w.tn = (float *)take((size_t)p.npad * 4);
-    w.buf = (uint2 *)take((size_t)p.Qp * p.cap * 8);
+    w.keep = (uint2 *)take((size_t)p.Qp * p.KP * 8);
+    w.seg = (uint2 *)take((size_t)p.Qp * p.nseg * 2 * TK_HALF * 8);
+    w.segcnt = (int32_t *)take((size_t)p.Qp * p.nseg * 2 * 4);
     w.keyd = (double *)take((size_t)p.Qp * p.KP * 8);
     return off + 256;
 }
 
 template <bool BF16, int RB, int KIND, int OB>
 int launch_scan(const TopkArgs &a, int own_tiles, int nsplit, hipStream_t st) {
-    constexpr int LDS = 2 * (TK_ST * (RB + 16) + TK_ST * 4);
+    constexpr int NSTAGE = RB == 512 ? 4 : 3;
+    constexpr int LDS = NSTAGE * TK_ST * RB + (NSTAGE + 1) * 4 * 256;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void *)topk_scan_kernel<BF16, RB, KIND, OB>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return KGE_E_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((topk_scan_kernel<BF16, RB, KIND, OB>), dim3(own_tiles, nsplit), dim3(256), LDS, st, a);
+    hipLaunchKernelGGL((topk_scan_kernel<BF16, RB, KIND, OB>), dim3(own_tiles * ((nsplit + 7) / 8 * 8)), dim3(256), LDS, st, a);
     return kge_launch_status();
 }
 
@@ -509,38 +610,40 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
     const int64_t stride = model.ent_ld * p.es;
     const int kind = model.scorer == KGE_DISTMULT ? KGE_KIND_MULT : KGE_KIND_DIST;
 
-    hipLaunchKernelGGL(topk_zero_kernel, dim3(1), dim3(1), 0, st, w.tmax);
+    hipLaunchKernelGGL(topk_zero_kernel, dim3(1), dim3(64), 0, st, w.tmax, w.zeros);
     if (p.bf16) {
         hipLaunchKernelGGL(topk_prep_kernel<true>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
-        hipLaunchKernelGGL(topk_tnorm_kernel<true>, dim3((unsigned)((p.npad + 3) / 4)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
+        hipLaunchKernelGGL(topk_tnorm_kernel<true>, dim3((unsigned)(p.npad / 4 < 8192 ? (p.npad + 3) / 4 : 8192)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
     } else {
         hipLaunchKernelGGL(topk_prep_kernel<false>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
-        hipLaunchKernelGGL(topk_tnorm_kernel<false>, dim3((unsigned)((p.npad + 3) / 4)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
+        hipLaunchKernelGGL(topk_tnorm_kernel<false>, dim3((unsigned)(p.npad / 4 < 8192 ? (p.npad + 3) / 4 : 8192)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
     }
     if (hipGetLastError() != hipSuccess) return KGE_E_HIP;
 
     TopkArgs base{};
     base.Qmat = w.Qm; base.ent = cand0; base.ent_stride = stride; base.valid_bytes = model.dim * p.es;
     base.ncand = ncand; base.cand_lo = lo; base.tn = w.tn; base.thr = w.thr; base.vt = w.vt; base.true_t = true_t;
-    base.cnt = w.cnt; base.buf = w.buf; base.cap = p.cap; base.rankcnt = w.rankcnt; base.nq = (int)Q;
+    base.seg = w.seg; base.segcnt = w.segcnt; base.nseg = p.nseg; base.rankcnt = w.rankcnt; base.nq = (int)Q; base.zeros = w.zeros;
     const int own_tiles = p.Qp / p.own;
     const int64_t total_tiles = p.npad / TK_ST;
-    // growing chunks: the first fills the buffers half, later ones are 7x what has been seen, so a query
-    // with a well-mixed candidate order appends about 7 KP entries per chunk (the buffer holds 16 KP)
+    // Growing chunks: thresholds are refreshed between chunks.  The first chunk appends everything (64
+    // candidates per split and lane half fill a private area exactly); afterwards a chunk is 3x what has
+    // been seen, so a query with a well-mixed candidate order appends about 3 KP entries per chunk,
+    // spread over nsplit x 2 private areas of TK_HALF entries.
     int64_t seen = 0;
-    const int compact_lds = p.cap * 8;
+    const int compact_lds = TK_SORTCAP * 8;
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)topk_compact_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8) != hipSuccess)
+        if (hipFuncSetAttribute((const void *)topk_compact_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, compact_lds) != hipSuccess)
             return KGE_E_HIP;
         attr_done = true;
     }
     while (seen < total_tiles) {
-        int64_t tiles = seen == 0 ? (p.cap / 2) / TK_ST : 7 * seen;
+        int64_t tiles = seen == 0 ? (p.nseg * (TK_HALF / TK_ST) < 128 ? p.nseg * (TK_HALF / TK_ST) : 128) : 3 * seen;
         if (tiles > total_tiles - seen) tiles = total_tiles - seen;
         TopkArgs c = base;
-        c.tile_lo = seen; c.tile_hi = seen + tiles;
-        int want = (1024 + own_tiles - 1) / own_tiles;        // a few workgroups per compute unit
+        c.tile_lo = seen; c.tile_hi = seen + tiles; c.own_tiles = own_tiles;
+        int want = p.nseg;                                    // one split per private area
         if (want > tiles) want = (int)tiles;
         c.tiles_per_wg = (int)((tiles + want - 1) / want);
         const int nsplit = (int)((tiles + c.tiles_per_wg - 1) / c.tiles_per_wg);
@@ -554,18 +657,18 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
         }
         if (rc != KGE_OK) return rc;
         seen += tiles;
-        const int force = seen >= total_tiles;
-        hipLaunchKernelGGL(topk_compact_kernel, dim3((unsigned)Q), dim3(256), compact_lds, st, w.cnt, w.buf, p.cap, p.KP, w.thr, w.flag, (int)Q, force);
+        hipLaunchKernelGGL(topk_compact_kernel, dim3((unsigned)Q), dim3(256), compact_lds, st, w.keep, w.cnt, w.seg, w.segcnt,
+                           p.nseg, (nsplit + 7) / 8 * 8 < p.nseg ? (nsplit + 7) / 8 * 8 : p.nseg, p.KP, w.thr, w.flag, (int)Q);
     }
     const int64_t nres = Q * p.KP;
     const int final_lds = p.KPP * 12;
     if (p.bf16) {
-        hipLaunchKernelGGL(topk_rescore_kernel<true>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.buf, p.cap, p.KP, w.keyd);
-        hipLaunchKernelGGL(topk_final_kernel<true>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.buf, p.cap, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
+        hipLaunchKernelGGL(topk_rescore_kernel<true>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_final_kernel<true>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.keep, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
         hipLaunchKernelGGL(topk_exact_kernel<true>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
     } else {
-        hipLaunchKernelGGL(topk_rescore_kernel<false>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.buf, p.cap, p.KP, w.keyd);
-        hipLaunchKernelGGL(topk_final_kernel<false>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.buf, p.cap, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
+        hipLaunchKernelGGL(topk_rescore_kernel<false>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_final_kernel<false>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.keep, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
         hipLaunchKernelGGL(topk_exact_kernel<false>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
     }
     return kge_launch_status();
