@@ -7,8 +7,11 @@
 // (G T and G^t Q).  The block itself never goes to memory: it is recomputed tile by tile.
 //
 // One template serves all passes.  A workgroup (4 waves) OWNS 128 rows of one operand, held in
-// registers as MFMA B-fragments for the whole launch, and STREAMS the other operand through LDS
-// in tiles of 32 rows (double buffered).  Per tile and wave:
+// registers as MFMA B-fragments for the whole launch, and STREAMS the other operand through an LDS
+// ring of 2-4 stages in tiles of 32 rows.  The ring is filled by asynchronous global->LDS copies
+// (no registers, several tiles in flight); rows are stored unpadded with their 16-byte chunks
+// XOR-swizzled so that the fragment reads of 8 consecutive rows hit 8 different bank groups.
+// Workgroups that stream the same rows are placed on the same XCD (shared L2).  Per tile and wave:
 //   phase 1   acc[32 stream x 32 own] = X_tile . own^t          (contraction over d)
 //   epilogue  score / loss weights / gradient coefficients, element by element
 //   phase 2   out^t[d x 32 own] += Xt_tile[d x 32 stream] . coef[stream x own]
@@ -66,6 +69,20 @@ __device__ __forceinline__ uint32_t kge_pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// Asynchronous global -> LDS copies: lane l of a wave-wide instruction writes its 16 (4) bytes to LDS
+// byte address m0 + 16 l (4 l).  Completion is tracked by vmcnt; the compiler does not see these
+// loads, so the waits are explicit.
+__device__ __forceinline__ void kge_async_copy16(const void *g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+__device__ __forceinline__ void kge_async_copy4(const void *g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+template <int N> __device__ __forceinline__ void kge_wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 __device__ __forceinline__ float kge_elem_to_float(float x) { return x; }
 __device__ __forceinline__ float kge_elem_to_float(__bf16 x) { return (float)x; }
 __device__ __forceinline__ float kge_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -98,39 +115,53 @@ struct KgeBlockCfg {
     static constexpr int ST = KGE_STREAM_TILE;
     static constexpr int NB = DP / 32;                     // 32-column output blocks of phase 2
     static constexpr int NBH = NB / DSPLIT;                // ... handled by one z-slice
-    static constexpr int X_STRIDE = RB + 16;
-    static constexpr int X_BYTES = ST * X_STRIDE;
-    static constexpr int XT_UNIT = BF16 ? 8 : 16;
-    static constexpr int XT_ROWB = ST * ES;
-    static constexpr int XT_STRIDE = XT_ROWB + XT_UNIT;
-    static constexpr int XT_BYTES = DP * XT_STRIDE;
+    static constexpr int X_BYTES = ST * RB;                // [ST rows][RB bytes], chunk c of row r at c ^ (r & 7)
+    static constexpr int XT_ROWB = ST * ES;                // one transposed row: ST stream entries (64 or 128 bytes)
+    static constexpr int XT_BYTES = DP * XT_ROWB;
     static constexpr bool HAS_X2 = TRANSH && !OWN_ROW;     // second streamed operand (normals)
     static constexpr bool HAS_XT = MODE != KGE_MODE_SCORE;
-    static constexpr int SIDE_BYTES = ST * 16;
-    static constexpr int STAGE_BYTES = X_BYTES * (HAS_X2 ? 2 : 1) + (HAS_XT ? XT_BYTES * (HAS_X2 ? 2 : 1) : 0) + SIDE_BYTES;
-    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-    static constexpr int X_UNITS = ST * RB / 16 / 256;     // 16-byte units per thread
-    static constexpr int XT_UNITS = DP * 8 / 256;          // XT_UNIT-byte units per thread
-    static_assert(ST * RB / 16 % 256 == 0 && DP * 8 % 256 == 0, "tile copy must divide evenly");
+    static constexpr int NX = HAS_X2 ? 2 : 1;
+    static constexpr int STAGE_BYTES = X_BYTES * NX + (HAS_XT ? XT_BYTES * NX : 0);
+    static constexpr int SIDE_SLOT = OWN_ROW ? 4 * 256 : 4 * 1024;   // per-wave copies of the tile's side info
+    static constexpr int LDS_MAX = 160 * 1024;
+    static constexpr int NSTAGE_RAW = (LDS_MAX - 5 * SIDE_SLOT) / STAGE_BYTES;
+    static constexpr int NSTAGE = NSTAGE_RAW > 4 ? 4 : NSTAGE_RAW;
+    static constexpr int SIDE_SLOTS = NSTAGE + 1;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES + SIDE_SLOTS * SIDE_SLOT;
+    static constexpr int X_IPW = X_BYTES / 1024 / 4;       // 1 KB wave-wide copies per wave and tile
+    static constexpr int XT_IPW = XT_BYTES / 1024 / 4;
+    static constexpr int LPW = X_IPW * NX + (HAS_XT ? XT_IPW * NX : 0) + 1;
+    static_assert(NSTAGE >= 2, "two stages must fit");
+    static_assert(X_BYTES % 4096 == 0 && XT_BYTES % 4096 == 0, "tile copies must divide over four waves");
+    static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
 };
 
 template <bool BF16, int RB, int MODE, bool TRANSH, int KIND, int LOSS, int DSPLIT>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(1, 1)))
 void kge_block_kernel(const KgeBlockArgs a) {
     using C = KgeBlockCfg<BF16, RB, MODE, TRANSH, DSPLIT>;
-    using XtU = typename std::conditional<BF16, kge_u32x2, kge_u32x4>::type;
     constexpr bool OWN_ROW = C::OWN_ROW;
     constexpr bool PHASE2 = MODE != KGE_MODE_SCORE;
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    char *side_ring = lds + C::NSTAGE * C::STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
-    const int own_base = blockIdx.x * KGE_OWN_TILE;
-    const int split = blockIdx.y;
-    const int dblk0 = blockIdx.z * C::NBH;
+    // Workgroups go to the 8 XCDs round-robin: the workgroups that stream the same rows (same split)
+    // get ids with the same residue mod 8 and share that XCD's L2.
+    // With fewer than 8 splits, each split's own-tiles are dealt to 8 / nsplit XCDs.
+    const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
+    int own_tile, split;
+    if (a.xcd_per == 1) { own_tile = kk % a.own_tiles; split = xcd + 8 * (kk / a.own_tiles); }
+    else { split = xcd / a.xcd_per; own_tile = kk * a.xcd_per + xcd % a.xcd_per; }
+    if (own_tile >= a.own_tiles) return;
+    const int own_base = own_tile * KGE_OWN_TILE;
+    const int dblk0 = blockIdx.y * C::NBH;
     const int oidx = own_base + wave * 32 + lr;
     const int t0 = split * a.tiles_per_split;
     const int t1 = min(a.str_tiles, t0 + a.tiles_per_split);
     const int str_limit = OWN_ROW ? a.N : a.B;            // valid stream rows
+    if (split >= a.nsplit) return;
 
     // ---- own operand fragments: 16 bytes per lane per 32-byte k-step --------------------------
     uint4 own[C::KS];
@@ -167,76 +198,75 @@ void kge_block_kernel(const KgeBlockArgs a) {
     float sum1 = 0.f, sum2 = 0.f, sum3 = 0.f;           // sums of the coefficients over the stream index
     float st_m = -INFINITY, st_l = 0.f, st_acc = 0.f;   // FWD: running max (log2 domain) / sum / weighted loss
 
-    // ---- global -> register -> LDS staging of one stream tile ----------------------------------
-    kge_u32x4 px[C::X_UNITS];
-    kge_u32x4 px2[C::HAS_X2 ? C::X_UNITS : 1];
-    XtU pxt[C::HAS_XT ? C::XT_UNITS : 1];
-    XtU pxt2[(C::HAS_XT && C::HAS_X2) ? C::XT_UNITS : 1];
-    kge_f32x4 pside = {0.f, 0.f, 0.f, 0.f};
-
-    auto gload = [&](int tile) {
+    // ---- asynchronous staging of one stream tile --------------------------------------------------
+    // X tile: instruction jj of this wave covers LDS bytes [(wave*X_IPW + jj) KB, +1 KB) of the tile; the
+    // lane's 16 bytes are position (byte % RB)/16 of row byte/RB and must hold source chunk pos ^ (row & 7).
+    int x_off[C::X_IPW];                                   // source byte offset inside the tile
+#pragma unroll
+    for (int jj = 0; jj < C::X_IPW; ++jj) {
+        const int byte = (wave * C::X_IPW + jj) * 1024 + lane * 16;
+        const int r = byte / RB, pos = (byte % RB) / 16;
+        x_off[jj] = r * RB + ((pos ^ (r & 7)) * 16);
+    }
+    // Xt tile: rows of XT_ROWB bytes (dcol-major).  bf16: 64-byte rows, two rows per 128-byte line, chunk
+    // slot ((row&1)*4 + c) ^ ((row>>1)&7) within the line; fp32: 128-byte rows, chunk c at c ^ (row & 7).
+    int64_t xt_off[C::HAS_XT ? C::XT_IPW : 1];             // source byte offset relative to the tile's first column
+    if constexpr (C::HAS_XT) {
+#pragma unroll
+        for (int jj = 0; jj < C::XT_IPW; ++jj) {
+            const int byte = (wave * C::XT_IPW + jj) * 1024 + lane * 16;
+            const int line = byte >> 7, slot = (byte >> 4) & 7;
+            int row, c;
+            if constexpr (BF16) { const int sslot = slot ^ (line & 7); row = 2 * line + (sslot >> 2); c = sslot & 3; }
+            else { row = line; c = slot ^ (row & 7); }
+            xt_off[jj] = (int64_t)row * a.strT_ld * C::ES + c * 16;
+        }
+    }
+    auto issue = [&](int tile, int slot) {
+        tile = tile < t1 ? tile : t1 - 1;                  // past the end: a harmless repeat keeps vmcnt uniform
+        const uint32_t sbase = lds0 + (slot % C::NSTAGE) * C::STAGE_BYTES;
         const char *src = (const char *)a.str + (size_t)tile * C::ST * RB;
 #pragma unroll
-        for (int u = 0; u < C::X_UNITS; ++u) px[u] = *(const kge_u32x4 *)(src + (size_t)(tid + u * 256) * 16);
+        for (int jj = 0; jj < C::X_IPW; ++jj)
+            kge_async_copy16(src + x_off[jj], __builtin_amdgcn_readfirstlane(sbase + (wave * C::X_IPW + jj) * 1024));
         if constexpr (C::HAS_X2) {
             const char *src2 = (const char *)a.str2 + (size_t)tile * C::ST * RB;
 #pragma unroll
-            for (int u = 0; u < C::X_UNITS; ++u) px2[u] = *(const kge_u32x4 *)(src2 + (size_t)(tid + u * 256) * 16);
+            for (int jj = 0; jj < C::X_IPW; ++jj)
+                kge_async_copy16(src2 + x_off[jj], __builtin_amdgcn_readfirstlane(sbase + C::X_BYTES + (wave * C::X_IPW + jj) * 1024));
         }
         if constexpr (C::HAS_XT) {
+            const char *srct = (const char *)a.strT + (size_t)tile * C::ST * C::ES;
 #pragma unroll
-            for (int u = 0; u < C::XT_UNITS; ++u) {
-                int unit = tid + u * 256, row = unit >> 3, cu = unit & 7;
-                size_t off = ((size_t)row * a.strT_ld + (size_t)tile * C::ST) * C::ES + cu * C::XT_UNIT;
-                pxt[u] = *(const XtU *)((const char *)a.strT + off);
-                if constexpr (C::HAS_X2) pxt2[u] = *(const XtU *)((const char *)a.strT2 + off);
+            for (int jj = 0; jj < C::XT_IPW; ++jj)
+                kge_async_copy16(srct + xt_off[jj], __builtin_amdgcn_readfirstlane(sbase + C::X_BYTES * C::NX + (wave * C::XT_IPW + jj) * 1024));
+            if constexpr (C::HAS_X2) {
+                const char *srct2 = (const char *)a.strT2 + (size_t)tile * C::ST * C::ES;
+#pragma unroll
+                for (int jj = 0; jj < C::XT_IPW; ++jj)
+                    kge_async_copy16(srct2 + xt_off[jj], __builtin_amdgcn_readfirstlane(sbase + C::X_BYTES * C::NX + C::XT_BYTES + (wave * C::XT_IPW + jj) * 1024));
             }
         }
-        if (tid < C::ST) {
-            int sidx = tile * C::ST + tid;
-            if constexpr (OWN_ROW) {
-                pside[0] = a.tn[sidx];
-            } else {
-                pside = *(const kge_f32x4 *)(a.rowinfo + sidx);
-            }
-        }
+        // side info of the tile's 32 stream rows, one private copy per wave
+        const uint32_t sside = lds0 + C::NSTAGE * C::STAGE_BYTES + (slot % C::SIDE_SLOTS) * C::SIDE_SLOT;
+        if constexpr (OWN_ROW) kge_async_copy4(a.tn + tile * C::ST + lr, __builtin_amdgcn_readfirstlane(sside + wave * 256));
+        else kge_async_copy16(a.rowinfo + tile * C::ST + lr, __builtin_amdgcn_readfirstlane(sside + wave * 1024));
     };
-    auto lstore = [&](int stage) {
-        char *base = lds + stage * C::STAGE_BYTES;
+    // fragment addresses inside a stage: chunk (2 ks + g) of row lr sits at position chunk ^ (lr & 7)
+    int frag_off[4];
 #pragma unroll
-        for (int u = 0; u < C::X_UNITS; ++u) {
-            int unit = tid + u * 256, row = unit / (RB / 16), cu = unit % (RB / 16);
-            *(kge_u32x4 *)(base + row * C::X_STRIDE + cu * 16) = px[u];
-            if constexpr (C::HAS_X2) *(kge_u32x4 *)(base + C::X_BYTES + row * C::X_STRIDE + cu * 16) = px2[u];
-        }
-        char *xt = base + C::X_BYTES * (C::HAS_X2 ? 2 : 1);
-        if constexpr (C::HAS_XT) {
-#pragma unroll
-            for (int u = 0; u < C::XT_UNITS; ++u) {
-                int unit = tid + u * 256, row = unit >> 3, cu = unit & 7;
-                *(XtU *)(xt + row * C::XT_STRIDE + cu * C::XT_UNIT) = pxt[u];
-                if constexpr (C::HAS_X2) *(XtU *)(xt + C::XT_BYTES + row * C::XT_STRIDE + cu * C::XT_UNIT) = pxt2[u];
-            }
-        }
-        if (tid < C::ST) {
-            char *side = base + C::STAGE_BYTES - C::SIDE_BYTES;
-            *(kge_f32x4 *)(side + tid * 16) = pside;
-        }
-    };
+    for (int b = 0; b < 4; ++b) frag_off[b] = lr * RB + 16 * (((2 * b) ^ (lr & 6)) | (g ^ (lr & 1)));
 
-    if (t0 < t1) {
-        gload(t0);
-        lstore(0);
-    }
-    __syncthreads();
+#pragma unroll
+    for (int s2 = 0; s2 < C::NSTAGE - 1; ++s2) issue(t0 + s2, s2);
 
     // The FWD pass keeps all weights relative to a per-row reference exponent st_m that is only
     // raised (and the accumulators rescaled) when a tile's maximum exceeds it by more than KGE_TAU:
     // weights stay below 2^KGE_TAU, and the rescaling code sits outside the hot loop.  A tile that
     // trips the check leaves the inner loop before using its weights and is redone after the
-    // rescale (its next-tile prefetch is already in flight: have_next).
+    // rescale (its stage is already published: resume).
     int tile = t0;
-    bool have_next = false;
+    bool resume = false;                                  // the tile's stage is already published
     float pend_max = -INFINITY;
     for (;;) {
         if constexpr (MODE == KGE_MODE_FWD) {
@@ -255,26 +285,37 @@ void kge_block_kernel(const KgeBlockArgs a) {
         }
         bool redo = false;
         for (; tile < t1; ++tile) {
-        const int stage = (tile - t0) & 1;
-        const bool more = tile + 1 < t1;
-        if (more && !have_next) gload(tile + 1);
-        have_next = more;
-
-        const char *base = lds + stage * C::STAGE_BYTES;
-        const char *side = base + C::STAGE_BYTES - C::SIDE_BYTES;
-        // ---- phase 1: acc[stream, own] -------------------------------------------------------
+        const int slot = tile - t0;
+        if (!resume) {
+            // tile `tile` has landed when at most NSTAGE-2 younger tiles are still in flight; after the
+            // barrier every wave has finished tile-1, whose stage receives tile + NSTAGE - 1
+            kge_wait_vmcnt<(C::NSTAGE - 2) * C::LPW>();
+            __syncthreads();
+            issue(tile + C::NSTAGE - 1, slot + C::NSTAGE - 1);
+        }
+        resume = false;
+        const char *base = lds + (slot % C::NSTAGE) * C::STAGE_BYTES;
+        const char *side = side_ring + (slot % C::SIDE_SLOTS) * C::SIDE_SLOT + wave * (OWN_ROW ? 256 : 1024);
+        // ---- phase 1: acc[stream, own]; all fragments are requested before the first MFMA --------
         kge_f32x16 acc, accw;
         for (int i = 0; i < 16; ++i) { acc[i] = 0.f; accw[i] = 0.f; }
         {
-            const char *xrow = base + lr * C::X_STRIDE + g * 16;
+            constexpr int HALF = C::KS > 16 ? 16 : C::KS;          // at most 64 registers of fragments in flight
 #pragma unroll
-            for (int ks = 0; ks < C::KS; ++ks) {
-                uint4 av = *(const uint4 *)(xrow + ks * 32);
-                acc = kge_mma16<BF16>(acc, av, own[ks]);
-                if constexpr (TRANSH && OWN_ROW) accw = kge_mma16<BF16>(accw, av, ownw[ks]);
-                if constexpr (TRANSH && !OWN_ROW) {
-                    uint4 aw = *(const uint4 *)(xrow + C::X_BYTES + ks * 32);
-                    accw = kge_mma16<BF16>(accw, aw, own[ks]);
+            for (int k0 = 0; k0 < C::KS; k0 += HALF) {
+                uint4 av[HALF], aw[(TRANSH && !OWN_ROW) ? HALF : 1];
+#pragma unroll
+                for (int k = 0; k < HALF; ++k) {
+                    const int ks = k0 + k;
+                    av[k] = *(const uint4 *)(base + frag_off[ks & 3] + 128 * (ks >> 2));
+                    if constexpr (TRANSH && !OWN_ROW) aw[k] = *(const uint4 *)(base + C::X_BYTES + frag_off[ks & 3] + 128 * (ks >> 2));
+                }
+#pragma unroll
+                for (int k = 0; k < HALF; ++k) {
+                    const int ks = k0 + k;
+                    acc = kge_mma16<BF16>(acc, av[k], own[ks]);
+                    if constexpr (TRANSH && OWN_ROW) accw = kge_mma16<BF16>(accw, av[k], ownw[ks]);
+                    if constexpr (TRANSH && !OWN_ROW) accw = kge_mma16<BF16>(accw, aw[k], own[ks]);
                 }
             }
         }
@@ -291,7 +332,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
                 s = acc[i];
             } else {
                 float qn, cc, wn, tnv;
-                if constexpr (OWN_ROW) { qn = o_qn; cc = o_c; wn = o_wn; tnv = *(const float *)(side + sl * 16); }
+                if constexpr (OWN_ROW) { qn = o_qn; cc = o_c; wn = o_wn; tnv = *(const float *)(side + sl * 4); }
                 else { float4 ri = *(const float4 *)(side + sl * 16); qn = ri.x; cc = ri.y; wn = ri.w; tnv = o_tn; }
                 float d2 = fmaf(-2.f, acc[i], qn + tnv);
                 if constexpr (TRANSH) { const float A = accw[i]; Av[i] = A; d2 += A * (2.f * cc - A * (2.f - wn)); }
@@ -333,7 +374,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
             // lanes l and l^32 hold the two halves of the same row and feed ONE contraction in
             // phase 2, so they must share the reference
             tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 32));
-            if (__any(tile_max > st_m + KGE_TAU)) { pend_max = tile_max; redo = true; break; }
+            if (__any(tile_max > st_m + KGE_TAU)) { pend_max = tile_max; redo = true; resume = true; break; }
             const float m_safe = st_m > -INFINITY ? st_m : 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -378,7 +419,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
         }
         // ---- phase 2: out^t[d, own] += Xt[d, stream] . coef[stream, own] -----------------------
         if constexpr (PHASE2) {
-            const char *xt = base + C::X_BYTES * (C::HAS_X2 ? 2 : 1);
+            const char *xt = base + C::X_BYTES * C::NX;
             if constexpr (BF16) {
                 uint4 bf[2], bf2[2];
 #pragma unroll
@@ -393,49 +434,60 @@ void kge_block_kernel(const KgeBlockArgs a) {
                                              kge_pack_bf16x2(coef2[8 * s2 + 4], coef2[8 * s2 + 5]),
                                              kge_pack_bf16x2(coef2[8 * s2 + 6], coef2[8 * s2 + 7]));
                 }
+                // The transposed operand keeps, inside every group of 16 stream entries, the 8 entries of one
+                // lane half contiguous (the producer swaps bits 2 and 3 of the column), so the A-fragment of
+                // (block, s2) is ONE 16-byte chunk: chunk 2*s2 + g of row dcol, at its swizzled slot.
+                uint4 av2[C::NBH][2], aw2[(TRANSH && !OWN_ROW) ? C::NBH : 1][2];
 #pragma unroll
                 for (int blk = 0; blk < C::NBH; ++blk) {
-                    const char *p = xt + ((dblk0 + blk) * 32 + lr) * C::XT_STRIDE + g * 8;
+                    const int row = (dblk0 + blk) * 32 + lr;
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2) {
-                        uint2 lo = *(const uint2 *)(p + 32 * s2), hi = *(const uint2 *)(p + 32 * s2 + 16);
-                        uint4 av = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                        acc2[blk] = kge_mma16<true>(acc2[blk], av, bf[s2]);
-                        if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma16<true>(acc2b[blk], av, bf2[s2]);
-                        if constexpr (TRANSH && !OWN_ROW) {
-                            uint2 lo2 = *(const uint2 *)(p + C::XT_BYTES + 32 * s2);
-                            uint2 hi2 = *(const uint2 *)(p + C::XT_BYTES + 32 * s2 + 16);
-                            acc2[blk] = kge_mma16<true>(acc2[blk], make_uint4(lo2.x, lo2.y, hi2.x, hi2.y), bf2[s2]);
-                        }
+                        const int sslot = (((row & 1) << 2) | (2 * s2 + g)) ^ ((row >> 1) & 7);
+                        const char *p = xt + (row >> 1) * 128 + sslot * 16;
+                        av2[blk][s2] = *(const uint4 *)p;
+                        if constexpr (TRANSH && !OWN_ROW) aw2[blk][s2] = *(const uint4 *)(p + C::XT_BYTES);
+                    }
+                }
+#pragma unroll
+                for (int blk = 0; blk < C::NBH; ++blk) {
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        acc2[blk] = kge_mma16<true>(acc2[blk], av2[blk][s2], bf[s2]);
+                        if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma16<true>(acc2b[blk], av2[blk][s2], bf2[s2]);
+                        if constexpr (TRANSH && !OWN_ROW) acc2[blk] = kge_mma16<true>(acc2[blk], aw2[blk][s2], bf2[s2]);
                     }
                 }
             } else {
 #pragma unroll
                 for (int blk = 0; blk < C::NBH; ++blk) {
-                    const char *p = xt + ((dblk0 + blk) * 32 + lr) * C::XT_STRIDE + g * 16;
+                    const int row = (dblk0 + blk) * 32 + lr;
+                    const char *p = xt + row * 128;
+                    kge_f32x4 av[4], av2[(TRANSH && !OWN_ROW) ? 4 : 1];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        kge_f32x4 av = *(const kge_f32x4 *)(p + 32 * j);
-                        kge_f32x4 av2;
-                        if constexpr (TRANSH && !OWN_ROW) av2 = *(const kge_f32x4 *)(p + C::XT_BYTES + 32 * j);
+                        const int off = ((2 * j + g) ^ (row & 7)) * 16;
+                        av[j] = *(const kge_f32x4 *)(p + off);
+                        if constexpr (TRANSH && !OWN_ROW) av2[j] = *(const kge_f32x4 *)(p + C::XT_BYTES + off);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            acc2[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[r], coef[4 * j + r], acc2[blk], 0, 0, 0);
+                            acc2[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coef[4 * j + r], acc2[blk], 0, 0, 0);
                             if constexpr (TRANSH && OWN_ROW)
-                                acc2b[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[r], coef2[4 * j + r], acc2b[blk], 0, 0, 0);
+                                acc2b[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coef2[4 * j + r], acc2b[blk], 0, 0, 0);
                             if constexpr (TRANSH && !OWN_ROW)
-                                acc2[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av2[r], coef2[4 * j + r], acc2[blk], 0, 0, 0);
+                                acc2[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av2[j][r], coef2[4 * j + r], acc2[blk], 0, 0, 0);
                         }
                     }
                 }
             }
         }
-        if (more) lstore(stage ^ 1);
-        have_next = false;
-        __syncthreads();
         }
         if (MODE != KGE_MODE_FWD || !redo) break;
     }
+    kge_wait_vmcnt<0>();                                  // no copy may be in flight when the LDS is released
 
     // ---- write-out ---------------------------------------------------------------------------------
     if constexpr (PHASE2) {
@@ -443,7 +495,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
         // add their scalars.  The phase-2 accumulators already contain both halves.
         if constexpr (MODE == KGE_MODE_FWD) { st_l += __shfl_xor(st_l, 32); st_acc += __shfl_xor(st_acc, 32); }
         sum1 += __shfl_xor(sum1, 32); sum2 += __shfl_xor(sum2, 32); sum3 += __shfl_xor(sum3, 32);
-        if (g == 0 && blockIdx.z == 0) {
+        if (g == 0 && blockIdx.y == 0) {
             a.sum_part[(size_t)split * a.own_pad + oidx] = make_float4(sum1, sum2, sum3, 0.f);
             if constexpr (MODE == KGE_MODE_FWD) a.stat_part[(size_t)split * a.own_pad + oidx] = make_float4(st_m, st_l, st_acc, 0.f);
         }
@@ -471,7 +523,17 @@ int kge_block_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream
             return KGE_E_HIP;
         attr_set = true;
     }
-    dim3 grid(own_tiles, nsplit, MODE != KGE_MODE_SCORE ? DSPLIT : 1);
-    hipLaunchKernelGGL(kern, grid, dim3(256), C::LDS_BYTES, st, a);
+    KgeBlockArgs b = a;
+    b.own_tiles = own_tiles; b.nsplit = nsplit;
+    int groups;                                            // workgroups per XCD
+    if (nsplit >= 8) { b.xcd_per = 1; groups = own_tiles * ((nsplit + 7) / 8); }
+    else {
+        int s2 = 1;
+        while (s2 < nsplit) s2 <<= 1;
+        b.xcd_per = 8 / s2;
+        groups = (own_tiles + b.xcd_per - 1) / b.xcd_per;
+    }
+    dim3 grid(8 * groups, MODE != KGE_MODE_SCORE ? DSPLIT : 1);
+    hipLaunchKernelGGL(kern, grid, dim3(256), C::LDS_BYTES, st, b);
     return kge_launch_status();
 }

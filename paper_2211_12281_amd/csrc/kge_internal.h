@@ -61,6 +61,8 @@ struct KgeBlockArgs {
     float *acc_part, *acc_part2;   // FWD / GRADT: [nsplit][own_pad][dp]
     float4 *sum_part;              // FWD / GRADT: [nsplit][own_pad] {s1, s2, s3, 0}
     int32_t own_pad;
+    int32_t own_tiles, nsplit;     // launch geometry (the grid is one-dimensional in (split, own tile))
+    int32_t xcd_per;               // XCDs that share one split (1 when there are 8 or more splits)
 };
 
 // launchers implemented in block_*.hip (one file per element type and pass to bound compile time)

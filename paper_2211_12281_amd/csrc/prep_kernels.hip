@@ -124,16 +124,20 @@ __global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// transpose: src [R][C] -> dst [C][R]   (R, C multiples of 32; elements of 2 or 4 bytes)
+// transpose: src [R][C] -> dst [C][R]   (R, C multiples of 32; elements of 2 or 4 bytes).
+// PERM: inside every group of 16 source rows, bits 2 and 3 of the row number are swapped in the
+// destination column, which makes the 8 entries that one lane half of the block kernel contracts in
+// its second phase contiguous (one 16-byte fragment for 2-byte elements).
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool PERM>
 __global__ void kge_transpose_kernel(const T *src, T *dst, int R, int C) {
     __shared__ T tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 256 threads: 32 x 8
     const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
     for (int i = ty; i < 32; i += 8) tile[i][tx] = src[(int64_t)(r0 + i) * C + c0 + tx];
     __syncthreads();
-    for (int i = ty; i < 32; i += 8) dst[(int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+    const int px = PERM ? ((tx & ~12) | ((tx & 4) << 1) | ((tx & 8) >> 1)) : tx;
+    for (int i = ty; i < 32; i += 8) dst[(int64_t)(c0 + i) * R + r0 + px] = tile[tx][i];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -384,8 +388,8 @@ int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int
 int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipStream_t st) {
     if (R == 0 || C == 0) return KGE_OK;
     dim3 grid(C / 32, R / 32);
-    if (bf16) hipLaunchKernelGGL(kge_transpose_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)src, (uint16_t *)dst, R, C);
-    else      hipLaunchKernelGGL(kge_transpose_kernel<uint32_t>, grid, dim3(256), 0, st, (const uint32_t *)src, (uint32_t *)dst, R, C);
+    if (bf16) hipLaunchKernelGGL((kge_transpose_kernel<uint16_t, true>), grid, dim3(256), 0, st, (const uint16_t *)src, (uint16_t *)dst, R, C);
+    else      hipLaunchKernelGGL((kge_transpose_kernel<uint32_t, false>), grid, dim3(256), 0, st, (const uint32_t *)src, (uint32_t *)dst, R, C);
     return kge_launch_status();
 }
 
