@@ -10,6 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "full: full-size baseline configurations (subset of gpu; minutes, up to 140 GB of HBM)")
 
 
 @pytest.fixture(scope="session")

@@ -1,0 +1,209 @@
+"""The five baseline configurations at FULL size, in the launch configuration bench.py times, against the
+oracle (which regenerates only the touched table rows from the seeded generator)."""
+import numpy as np
+import pytest
+import torch
+
+import kge_synth as ks
+from helpers import RTOL_BF16, RTOL_F32, dev_idx, norm_err
+
+pytestmark = [pytest.mark.gpu, pytest.mark.full]
+F = np.float32
+
+
+def _free():
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def _fill(n, d, dtype, tag=ks.TAG_ENT, amp=0.1):
+    import kge_synth.device as ksd
+    t = torch.empty((n, d), dtype=dtype, device="cuda")
+    ksd.fill_uniform(t, ks.BASE_SEED, tag, amp)
+    return t
+
+
+def test_device_fill_matches_host_generator():
+    for dtype in (torch.float32, torch.bfloat16):
+        t = _fill(5000, 96, dtype)
+        rows = np.array([0, 1, 77, 4999])
+        ref = ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, rows, 96, 0.1)
+        got = t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+        assert np.array_equal(got, ks.round_to_bf16(ref) if dtype == torch.bfloat16 else ref)
+
+
+def test_c2_scoring_all_scorers_full_size(orc):
+    import paper_2211_12281_amd as kge
+    P = ks.PRESETS["c2"]
+    n_ent, d, B, N = P["n_ent"], P["dim"], P["B"], P["N"]
+    ent = _fill(n_ent, d, torch.float32)
+    g = ks.rng(ks.BASE_SEED, ks.TAG_BATCH, 0)
+    h, r, t = ks.uniform_ids(g, 0, n_ent, B), ks.uniform_ids(g, 0, P["n_rel"], B), ks.uniform_ids(g, 0, n_ent, B)
+    neg = kge.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, 0, n_ent, N)
+    neg_h = orc.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, 0, n_ent, N)
+    assert np.array_equal(neg.cpu().numpy(), neg_h)
+    uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg_h)
+    rows = ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, uniq, d, P["amp"])
+    for s in P["scorers"]:
+        rel, relw = ks.relation_tables(s, P["n_rel"], d)
+        model = kge.Model(s, ent, torch.from_numpy(rel).cuda(), None if relw is None else torch.from_numpy(relw).cuda())
+        pos, blk = kge.score(model, dev_idx(h), dev_idx(r), dev_idx(t), neg)
+        rp, rn = orc.score_batch(s, rows, rel, relw, ch, r, ct, cn)
+        assert norm_err(pos.cpu().numpy(), rp) <= RTOL_F32, s
+        assert norm_err(blk.cpu().numpy(), rn) <= RTOL_F32, s
+    del ent, model
+    _free()
+
+
+def test_c3_complex_training_step_full_size(orc):
+    """10M entities, bf16 compute + fp32 master and moments, Zipf ids, B = 4096, N = 16384, sampled softmax."""
+    import paper_2211_12281_amd as kge
+    P = ks.PRESETS["c3"]
+    n_ent, d, B, N = P["n_ent"], P["dim"], P["B"], P["N"]
+    master = _fill(n_ent, d, torch.float32)
+    shadow = _fill(n_ent, d, torch.bfloat16)
+    rel, _ = ks.relation_tables("complex", P["n_rel"], d)
+    rel_sh = torch.from_numpy(rel).cuda().to(torch.bfloat16)
+    z = ks.ZipfIds(n_ent, P["zipf_s"])
+    g = ks.rng(ks.BASE_SEED, ks.TAG_BATCH, 0)
+    h, t = z.draw(g, B), z.draw(g, B)
+    r = ks.uniform_ids(g, 0, P["n_rel"], B)
+    neg_h = orc.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, 0, n_ent, N)
+    model = kge.Model("complex", shadow, rel_sh)
+    out = kge.loss_bwd(model, "sampled_softmax", dev_idx(h), dev_idx(r), dev_idx(t), dev_idx(neg_h), n_ent_for_c=n_ent)
+    uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg_h)
+    rows32 = ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, uniq, d, P["amp"])
+    ref = orc.loss_bwd("complex", "sampled_softmax", ks.round_to_bf16(rows32), ks.round_to_bf16(rel), None, ch, r, ct, cn,
+                       n_ent_for_c=n_ent)
+    assert abs(out["loss"].item() - ref["loss"]) <= RTOL_BF16 * abs(ref["loss"])
+    ge = out["g_ent"].cpu().numpy()
+    for name, sl in (("heads", slice(0, B)), ("tails", slice(B, 2 * B)), ("negatives", slice(2 * B, 2 * B + N))):
+        assert norm_err(ge[sl], ref["g_ent"][sl]) <= RTOL_BF16, name
+    assert norm_err(out["g_rel"].cpu().numpy(), ref["g_rel"]) <= RTOL_BF16
+    assert np.array_equal(out["g_ent_idx"].cpu().numpy(), np.concatenate([h, t, neg_h]))
+    # sparse Adam on the 10M-row tables with the GPU's own gradient rows as the common input
+    m = torch.zeros_like(master); v = torch.zeros_like(master)
+    m[torch.from_numpy(uniq).cuda()] = 1e-4; v[torch.from_numpy(uniq).cuda()] = 1e-6      # a mid-training state
+    lr, b1, b2, eps = float(F(1e-3)), float(F(0.9)), float(F(0.999)), float(F(1e-8))
+    kge.sparse_adam(master, shadow, m, v, out["g_ent_idx"], out["g_ent"], lr, b1, b2, eps, step=10)
+    rth, rm, rv, touched = orc.sparse_adam(rows32, np.full(rows32.shape, 1e-4), np.full(rows32.shape, 1e-6),
+                                           np.concatenate([ch, ct, cn]), ge, lr, b1, b2, eps, 10)
+    assert touched.all()
+    got = master[torch.from_numpy(uniq).cuda()].cpu().numpy()
+    upd, rupd = got.astype(np.float64) - rows32, rth - rows32
+    assert np.all(np.abs(upd - rupd) <= RTOL_F32 * np.max(np.abs(rupd)) + np.spacing(np.abs(got)).astype(np.float64))
+    sh = shadow[torch.from_numpy(uniq).cuda()].view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(sh, orc.bf16_rne(got))
+    # rows that were not touched keep their generated values
+    probe = np.setdiff1d(np.arange(1000, 2000), uniq)[:50]
+    assert np.array_equal(master[torch.from_numpy(probe).cuda()].cpu().numpy(),
+                          ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, probe, d, P["amp"]))
+    del master, shadow, m, v, model
+    _free()
+
+
+@pytest.mark.parametrize("scorer", ["distmult", "transe"])
+def test_c4_link_prediction_full_size(orc, scorer):
+    """8192 queries against all 10M entities; the oracle ranks a 16-query subset at full width."""
+    import paper_2211_12281_amd as kge
+    P = ks.PRESETS["c4"]
+    n_ent, d, Q, K = P["n_ent"], P["dim"], P["Q"], P["K"]
+    ent = _fill(n_ent, d, torch.bfloat16)
+    rel, _ = ks.relation_tables(scorer, P["n_rel"], d)
+    rel = ks.round_to_bf16(rel)
+    model = kge.Model(scorer, ent, torch.from_numpy(rel).cuda().to(torch.bfloat16))
+    g = ks.rng(ks.BASE_SEED, ks.TAG_QUERY, 0)
+    h = ks.ZipfIds(n_ent, P["zipf_s"]).draw(g, Q)
+    r = ks.uniform_ids(g, 0, P["n_rel"], Q)
+    tt = ks.uniform_ids(ks.rng(ks.BASE_SEED, ks.TAG_HELDOUT, 0), 0, n_ent, Q)
+    tt[:4] = [3, n_ent - 1, int(h[2]), 12345]
+    idx, sc, rank = kge.topk(model, dev_idx(h), dev_idx(r), 0, n_ent, K, dev_idx(tt))
+    idx, sc, rank = idx.cpu().numpy(), sc.cpu().numpy(), rank.cpu().numpy()
+    # properties that hold for every query
+    assert np.all(np.diff(sc, axis=1) <= 0) and idx.min() >= 0 and idx.max() < n_ent
+    assert all(len(set(row)) == K for row in idx[::97])
+    # (equal fp32 scores need not be in index order: the order is that of the fp64 keys they were rounded from)
+    for q in range(0, Q, 41):
+        pos = np.where(idx[q] == tt[q])[0]
+        assert (len(pos) == 1 and rank[q] == pos[0] + 1) or (len(pos) == 0 and rank[q] > K)
+    # exact comparison on a subset
+    sub = np.r_[0:4, np.arange(100, 8192, 700)][:16]
+    host = ent.float().cpu().numpy()
+    ridx, rsc, rrank = orc.topk(scorer, host, rel, None, h[sub], r[sub], 0, n_ent, K, tt[sub])
+    assert np.array_equal(idx[sub], ridx)
+    assert np.max(np.abs(sc[sub] - rsc)) <= RTOL_F32 * np.max(np.abs(rsc))
+    inside = rrank <= K
+    assert np.array_equal(rank[sub][inside], rrank[inside])
+    # beyond the list: counted with matrix-core values; the band of candidates within the rounding error of the
+    # true tail's score is a small fraction of the table
+    assert np.all(np.abs(rank[sub][~inside] - rrank[~inside]) <= 0.02 * n_ent)
+    del ent, host, model
+    _free()
+
+
+def test_c5_transh_partition_pair_step_full_size(orc):
+    """90M entities x 128 fp32 with Adam moments (138 GB resident), one partition pair per step."""
+    import paper_2211_12281_amd as kge
+    P = ks.PRESETS["c5"]
+    n_ent, n_rel, d, B, N, D = P["n_ent"], P["n_rel"], P["dim"], P["B"], P["N"], P["D"]
+    part = -(-n_ent // D)
+    theta = _fill(n_ent, d, torch.float32)
+    m = torch.zeros_like(theta); v = torch.zeros_like(theta)
+    rel, relw = ks.relation_tables("transh", n_rel, d)
+    model = kge.Model("transh", theta, torch.from_numpy(rel).cuda(), torch.from_numpy(relw).cuda())
+    pi, pj = 3, 11
+    g = ks.rng(ks.BASE_SEED, ks.TAG_BATCH, 5)
+    z = ks.ZipfIds(n_ent, P["zipf_s"])
+    def in_shard(p, n):
+        out = np.empty(0, np.int32)
+        while out.size < n:
+            ids = z.draw(g, 64 * n)
+            out = np.concatenate([out, ids[(ids >= p * part) & (ids < (p + 1) * part)]])
+        return np.ascontiguousarray(out[:n])
+    h, t = in_shard(pi, B), in_shard(pj, B)
+    r = ks.ZipfIds(n_rel, P["rel_zipf_s"]).draw(g, B)
+    neg = kge.sample_negatives(ks.BASE_SEED, 7, ks.TAG_NEG, pj * part, (pj + 1) * part, N)
+    neg_h = orc.sample_negatives(ks.BASE_SEED, 7, ks.TAG_NEG, pj * part, (pj + 1) * part, N)
+    assert np.array_equal(neg.cpu().numpy(), neg_h) and neg_h.min() >= pj * part and neg_h.max() < (pj + 1) * part
+    kw = dict(gamma=P["gamma"], adv_temp=P["adv_temp"])
+    out = kge.loss_bwd(model, "logsigmoid", dev_idx(h), dev_idx(r), dev_idx(t), neg, **kw)
+    uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg_h)
+    rows = ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, uniq, d, P["amp"])
+    ref = orc.loss_bwd("transh", "logsigmoid", rows, rel, relw, ch, r, ct, cn, **kw)
+    assert abs(out["loss"].item() - ref["loss"]) <= RTOL_F32 * abs(ref["loss"])
+    ge = out["g_ent"].cpu().numpy()
+    for name, sl in (("heads", slice(0, B)), ("tails", slice(B, 2 * B)), ("negatives", slice(2 * B, 2 * B + N))):
+        assert norm_err(ge[sl], ref["g_ent"][sl]) <= RTOL_F32, name
+    assert norm_err(out["g_rel"].cpu().numpy(), ref["g_rel"]) <= RTOL_F32
+    assert norm_err(out["g_relw"].cpu().numpy(), ref["g_relw"]) <= RTOL_F32
+    lr, b1, b2, eps = float(F(1e-3)), float(F(0.9)), float(F(0.999)), float(F(1e-8))
+    kge.sparse_adam(theta, None, m, v, out["g_ent_idx"], out["g_ent"], lr, b1, b2, eps, step=1)
+    zr = np.zeros(rows.shape)
+    rth, _, _, touched = orc.sparse_adam(rows, zr, zr, np.concatenate([ch, ct, cn]), ge, lr, b1, b2, eps, 1)
+    got = theta[torch.from_numpy(uniq).cuda()].cpu().numpy()
+    upd, rupd = got.astype(np.float64) - rows, rth - rows
+    assert np.all(np.abs(upd - rupd) <= RTOL_F32 * np.max(np.abs(rupd)) + np.spacing(np.abs(got)).astype(np.float64))
+    del theta, m, v, model
+    _free()
+
+
+def test_c5_partition_bucketing_at_scale(orc):
+    """100M seeded triples into 16 x 16 buckets (the 600M-triple graph takes the same kernels; the
+    host-side generation of the index stream is what bounds this test)."""
+    import paper_2211_12281_amd as kge
+    n_ent, D, n = 90_000_000, 16, 100_000_000
+    part = -(-n_ent // D)
+    g = ks.rng(ks.BASE_SEED, ks.TAG_TRIPLE_H)
+    h, t = ks.uniform_ids(g, 0, n_ent, n), ks.uniform_ids(g, 0, n_ent, n)
+    off, order = kge.partition_triples(dev_idx(h), dev_idx(t), part, D)
+    counts, roff, _ = orc.bucket_triples(h, t, part, D, want_order=False)
+    off, order = off.cpu().numpy(), order.cpu().numpy()
+    assert np.array_equal(off, roff)
+    bkt = (h // part).astype(np.int64) * D + t // part
+    sb = bkt[order]
+    assert np.all(np.diff(sb) >= 0)                                   # grouped by bucket
+    same = sb[1:] == sb[:-1]
+    assert np.all(order[1:][same] > order[:-1][same])                  # input order kept inside a bucket
+    assert np.array_equal(np.sort(order[:: 9973]), np.unique(order[:: 9973]))
+    _free()
