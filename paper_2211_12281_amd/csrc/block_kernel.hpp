@@ -366,11 +366,14 @@ void kge_block_kernel(const KgeBlockArgs a) {
             const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
             float x2[16], tile_max = -INFINITY;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                x2[i] = sv[i] * xscale;
-                if (!tile_full && sbase + 8 * (i >> 2) + (i & 3) >= str_limit) x2[i] = -INFINITY;
-                tile_max = fmaxf(tile_max, x2[i]);
+            for (int i = 0; i < 16; ++i) x2[i] = sv[i] * xscale;
+            if (!tile_full) {                               // wave-uniform: only the last tile of the block is ragged
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (sbase + 8 * (i >> 2) + (i & 3) >= str_limit) x2[i] = -INFINITY;
             }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tile_max = fmaxf(tile_max, x2[i]);
             // lanes l and l^32 hold the two halves of the same row and feed ONE contraction in
             // phase 2, so they must share the reference
             tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 32));
@@ -393,7 +396,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
                 }
                 const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
                 coef[i] = c1;
-                sum1 += c1;
+                if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;     // only the distance scorers' chain rule needs it
                 if constexpr (TRANSH) { coef2[i] = c1 * Av[i]; sum2 += coef2[i]; sum3 += coef2[i] * Av[i]; }
             }
         }
@@ -413,7 +416,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
                 }
                 const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
                 coef[i] = c1;
-                sum1 += c1;
+                if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
                 if constexpr (TRANSH) coef2[i] = c1 * Av[i];
             }
         }

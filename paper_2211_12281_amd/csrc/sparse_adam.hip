@@ -10,31 +10,42 @@ namespace {
 
 constexpr int64_t SORT_MAX_BLOCKS = 32768;   // bounds the histogram that one workgroup scans
 
-__global__ void sort_init_kernel(const int32_t *idx, int64_t M, uint32_t *keys, uint32_t *pos) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < M) { keys[i] = (uint32_t)idx[i]; pos[i] = (uint32_t)i; }
+// Where the keys of a pass come from: the first pass reads the caller's row ids (or computes the
+// partition-pair bucket of each triple) and takes the position itself as payload; later passes read
+// the (key, position) pairs the previous pass wrote.
+struct KeySrc {
+    const uint32_t *keys, *pos;       // later passes
+    const int32_t *idx;               // first pass, row ids
+    const int32_t *h, *t;             // first pass, bucket mode
+    int64_t part_size; int D;
+};
+template <int FIRST>   // 0: pairs, 1: row ids, 2: buckets
+__device__ __forceinline__ uint32_t load_key(const KeySrc &k, int64_t i) {
+    if constexpr (FIRST == 1) return (uint32_t)k.idx[i];
+    else if constexpr (FIRST == 2) return (uint32_t)((k.h[i] / k.part_size) * k.D + (k.t[i] / k.part_size));
+    else return k.keys[i];
+}
+template <int FIRST>
+__device__ __forceinline__ uint32_t load_pos(const KeySrc &k, int64_t i) {
+    if constexpr (FIRST != 0) return (uint32_t)i;
+    else return k.pos[i];
 }
 
-__global__ void sort_init_bucket_kernel(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int D,
-                                        uint32_t *keys, uint32_t *pos) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) { keys[i] = (uint32_t)((h[i] / part_size) * D + (t[i] / part_size)); pos[i] = (uint32_t)i; }
-}
-
-__global__ void sort_hist_kernel(const uint32_t *keys, int64_t M, int shift, int nblk, int rounds, uint32_t *hist) {
+template <int FIRST>
+__global__ void sort_hist_kernel(KeySrc src, int64_t M, int shift, int nblk, int rounds, uint32_t *hist) {
     __shared__ uint32_t cnt[256];
     cnt[threadIdx.x] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * rounds * 256;
     for (int j = 0; j < rounds; ++j) {
         const int64_t i = base + (int64_t)j * 256 + threadIdx.x;
-        if (i < M) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u);
+        if (i < M) atomicAdd(&cnt[(load_key<FIRST>(src, i) >> shift) & 255u], 1u);
     }
     __syncthreads();
     hist[(size_t)threadIdx.x * nblk + blockIdx.x] = cnt[threadIdx.x];
 }
 
-// exclusive scan of `len` counters in place, one workgroup of 1024 threads
+// exclusive scan of `len` counters in place, one workgroup of 1024 threads (long inputs only)
 __global__ void sort_scan_kernel(uint32_t *hist, int64_t len) {
     __shared__ uint32_t part[1024];
     const int64_t per = (len + 1023) / 1024;
@@ -55,20 +66,44 @@ __global__ void sort_scan_kernel(uint32_t *hist, int64_t len) {
 
 // Stable scatter of one pass.  A workgroup walks its tile in rounds of 256 keys; within a round the
 // order is (wave, lane), so the rank of a key among the keys of its digit is
-//   [keys of that digit in earlier workgroups] + [in earlier rounds] + [in earlier waves] + [in lower lanes].
-__global__ void sort_scatter_kernel(const uint32_t *keys, const uint32_t *pos, int64_t M, int shift, int nblk,
-                                    int rounds, const uint32_t *gofs, uint32_t *keys_out, uint32_t *pos_out) {
+//   [keys of smaller digits] + [same digit in earlier workgroups] + [in earlier rounds] + [in earlier waves]
+//   + [in lower lanes].
+// OWN_SCAN: the per-workgroup histograms are raw counts and every workgroup derives its own offsets from
+// them (few workgroups: cheaper than a separate scan launch); otherwise `gofs` holds scanned offsets.
+template <int FIRST, bool OWN_SCAN>
+__global__ void sort_scatter_kernel(KeySrc src, int64_t M, int shift, int nblk, int rounds, const uint32_t *gofs,
+                                    uint32_t *keys_out, uint32_t *pos_out) {
     __shared__ uint32_t wc[4][256];       // keys of each digit per wave in the current round
-    __shared__ uint32_t run[256];         // keys of each digit in earlier rounds (plus the global offset)
+    __shared__ uint32_t run[256];         // destination of the next key of each digit
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    run[threadIdx.x] = gofs[(size_t)threadIdx.x * nblk + blockIdx.x];
+    if constexpr (OWN_SCAN) {
+        // this thread acts for digit threadIdx.x: keys of the digit in earlier workgroups, and in total
+        uint32_t before = 0, total = 0;
+        for (int b2 = 0; b2 < nblk; ++b2) {
+            const uint32_t c = gofs[(size_t)threadIdx.x * nblk + b2];
+            before += b2 < (int)blockIdx.x ? c : 0u;
+            total += c;
+        }
+        wc[0][threadIdx.x] = total;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {               // inclusive scan of the digit totals
+            const uint32_t v = threadIdx.x >= (unsigned)o ? wc[0][threadIdx.x - o] : 0u;
+            __syncthreads();
+            wc[0][threadIdx.x] += v;
+            __syncthreads();
+        }
+        run[threadIdx.x] = wc[0][threadIdx.x] - total + before;
+        __syncthreads();
+    } else {
+        run[threadIdx.x] = gofs[(size_t)threadIdx.x * nblk + blockIdx.x];
+    }
     const int64_t base = (int64_t)blockIdx.x * rounds * 256;
     for (int j = 0; j < rounds; ++j) {
         for (int w = 0; w < 4; ++w) wc[w][threadIdx.x] = 0;
         __syncthreads();
         const int64_t i = base + (int64_t)j * 256 + threadIdx.x;
         const bool valid = i < M;
-        const uint32_t k = valid ? keys[i] : 0u, p = valid ? pos[i] : 0u;
+        const uint32_t k = valid ? load_key<FIRST>(src, i) : 0u, p = valid ? load_pos<FIRST>(src, i) : 0u;
         const uint32_t dg = (k >> shift) & 255u;
         uint64_t peers = __ballot(valid);
 #pragma unroll
@@ -80,13 +115,13 @@ __global__ void sort_scatter_kernel(const uint32_t *keys, const uint32_t *pos, i
         const uint32_t rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
         if (valid && rank == 0) wc[wave][dg] = (uint32_t)__popcll(peers);
         __syncthreads();
-        uint32_t before = 0;              // this thread acts for digit threadIdx.x
+        uint32_t next = 0;                // this thread acts for digit threadIdx.x
         {
             const uint32_t c0 = wc[0][threadIdx.x], c1 = wc[1][threadIdx.x], c2 = wc[2][threadIdx.x], c3 = wc[3][threadIdx.x];
             const uint32_t r0 = run[threadIdx.x];
             wc[0][threadIdx.x] = r0; wc[1][threadIdx.x] = r0 + c0; wc[2][threadIdx.x] = r0 + c0 + c1;
             wc[3][threadIdx.x] = r0 + c0 + c1 + c2;
-            before = r0 + c0 + c1 + c2 + c3;
+            next = r0 + c0 + c1 + c2 + c3;
         }
         __syncthreads();
         if (valid) {
@@ -95,7 +130,7 @@ __global__ void sort_scatter_kernel(const uint32_t *keys, const uint32_t *pos, i
             pos_out[dst] = p;
         }
         __syncthreads();
-        run[threadIdx.x] = before;
+        run[threadIdx.x] = next;
     }
 }
 
@@ -282,16 +317,23 @@ int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64
                    int64_t key_range, void *ws, const uint32_t **sk, const uint32_t **sp, hipStream_t st) {
     SortWs s;
     sort_carve(M, 0, ws, s);
-    const int grid_e = (int)((M + 255) / 256);
-    if (idx) hipLaunchKernelGGL(sort_init_kernel, dim3(grid_e), dim3(256), 0, st, idx, M, s.ka, s.pa);
-    else     hipLaunchKernelGGL(sort_init_bucket_kernel, dim3(grid_e), dim3(256), 0, st, h, t, M, part_size, D, s.ka, s.pa);
     int bits = 1;
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
-    uint32_t *ki = s.ka, *ko = s.kb, *pi = s.pa, *po = s.pb;
+    uint32_t *ki = s.ka, *ko = s.kb, *pi = s.pa, *po = s.pb;       // the first pass writes buffer B
+    const bool own_scan = s.nblk <= 64;
+    const int first = idx ? 1 : 2;
     for (int shift = 0; shift < bits; shift += 8) {
-        hipLaunchKernelGGL(sort_hist_kernel, dim3(s.nblk), dim3(256), 0, st, ki, M, shift, s.nblk, s.rounds, s.hist);
-        hipLaunchKernelGGL(sort_scan_kernel, dim3(1), dim3(1024), 0, st, s.hist, (int64_t)256 * s.nblk);
-        hipLaunchKernelGGL(sort_scatter_kernel, dim3(s.nblk), dim3(256), 0, st, ki, pi, M, shift, s.nblk, s.rounds, s.hist, ko, po);
+        KeySrc src{ki, pi, idx, h, t, part_size, D};
+        const int mode = shift == 0 ? first : 0;
+        const dim3 grid(s.nblk), blk(256);
+        if (mode == 1) hipLaunchKernelGGL(sort_hist_kernel<1>, grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist);
+        else if (mode == 2) hipLaunchKernelGGL(sort_hist_kernel<2>, grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist);
+        else hipLaunchKernelGGL(sort_hist_kernel<0>, grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist);
+        if (!own_scan) hipLaunchKernelGGL(sort_scan_kernel, dim3(1), dim3(1024), 0, st, s.hist, (int64_t)256 * s.nblk);
+#define KGE_SCATTER(F, O) hipLaunchKernelGGL((sort_scatter_kernel<F, O>), grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist, ko, po)
+        if (own_scan) { if (mode == 1) KGE_SCATTER(1, true); else if (mode == 2) KGE_SCATTER(2, true); else KGE_SCATTER(0, true); }
+        else          { if (mode == 1) KGE_SCATTER(1, false); else if (mode == 2) KGE_SCATTER(2, false); else KGE_SCATTER(0, false); }
+#undef KGE_SCATTER
         uint32_t *tmp = ki; ki = ko; ko = tmp;
         tmp = pi; pi = po; po = tmp;
     }
