@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--scorer", default=None, help="c2 / c4: restrict to one scorer")
+    ap.add_argument("--scorer", default=None, help="restrict to one scorer (training workloads: replaces the configured one)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the entity table (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -45,13 +45,13 @@ def parse():
 class TrainWorkload:
     """c3 / c5 / c1: forward + backward + sparse Adam on bf16 shadow / fp32 master tables."""
 
-    def __init__(self, name, P, scale):
+    def __init__(self, name, P, scale, only=None):
         import torch
         import kge_synth as ks
         import kge_synth.device as ksd
         import paper_2211_12281_amd as kge
         self.kge, self.torch, self.ks, self.P, self.name = kge, torch, ks, P, name
-        self.scorer = P["scorers"][0]
+        self.scorer = only or P["scorers"][0]
         self.n_ent = max(1000, int(P["n_ent"] * scale))
         self.n_rel, self.d, self.B, self.N = P["n_rel"], P["dim"], P["B"], P["N"]
         self.bf16 = P["dtype"] == "bf16"
@@ -142,11 +142,13 @@ class TrainWorkload:
         return self.B * (self.N + 1)
 
     def extra(self, ms):
-        return {"triples_per_s": self.B / (ms * 1e-3)}
+        return {"triples_per_s": self.B / (ms * 1e-3), "scorer": self.scorer}
 
     def mfma_flops(self, slot):
-        gemms = 2 if self.scorer == "transh" else 1
-        return 2.0 * self.B * self.N * self.d * gemms     # algorithmic: one contraction per pass (recompute is no credit)
+        # algorithmic contractions of 2 B N d flop each: the FWD pass computes the scores AND the queries'
+        # gradient (two), the GRADT pass the negatives' gradient (one; its recomputed scores earn no credit)
+        gemms = (2 if slot == "block_fwd" else 1) * (2 if self.scorer == "transh" else 1)
+        return 2.0 * self.B * self.N * self.d * gemms
 
     def cpu_baseline(self, orc):
         """Oracle forward + backward + sparse Adam on the first rows of batch 0 against all negatives."""
@@ -303,7 +305,7 @@ def main():
     kge.load()
     P = ks.PRESETS[a.workload]
     if a.workload in ("c1", "c3", "c5"):
-        wl = TrainWorkload(a.workload, P, a.scale)
+        wl = TrainWorkload(a.workload, P, a.scale, a.scorer)
     elif a.workload == "c2":
         wl = ScoreWorkload(P, a.scale, a.scorer)
     else:

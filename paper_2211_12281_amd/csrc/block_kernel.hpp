@@ -106,9 +106,11 @@ __device__ __noinline__ float kge_direct_d2(const void *qv, const void *tv, cons
     return acc;
 }
 
-template <bool BF16, int RB, int MODE, bool TRANSH, int DSPLIT>
+template <bool BF16, int RB, int MODE, bool TRANSH, int KIND, int DSPLIT>
 struct KgeBlockCfg {
     static constexpr bool OWN_ROW = MODE == KGE_MODE_FWD;
+    static constexpr int OW = kge_block_ow(BF16, RB, TRANSH, MODE, KIND);   // 32-row own fragments per wave
+    static constexpr int OWN_TILE = 128 * OW;              // own rows of a workgroup
     static constexpr int ES = KgeElem<BF16>::size;
     static constexpr int DP = RB / ES;                     // padded dim
     static constexpr int KS = RB / 32;                     // 32-byte k-steps of phase 1
@@ -134,14 +136,16 @@ struct KgeBlockCfg {
     static_assert(NSTAGE >= 2, "two stages must fit");
     static_assert(X_BYTES % 4096 == 0 && XT_BYTES % 4096 == 0, "tile copies must divide over four waves");
     static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
+    static_assert(OW == 1 || !TRANSH, "two own fragments per wave leave no registers for the TransH operands");
 };
 
 template <bool BF16, int RB, int MODE, bool TRANSH, int KIND, int LOSS, int DSPLIT>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(1, 1)))
 void kge_block_kernel(const KgeBlockArgs a) {
-    using C = KgeBlockCfg<BF16, RB, MODE, TRANSH, DSPLIT>;
+    using C = KgeBlockCfg<BF16, RB, MODE, TRANSH, KIND, DSPLIT>;
     constexpr bool OWN_ROW = C::OWN_ROW;
     constexpr bool PHASE2 = MODE != KGE_MODE_SCORE;
+    constexpr int OW = C::OW;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     char *side_ring = lds + C::NSTAGE * C::STAGE_BYTES;
@@ -155,48 +159,54 @@ void kge_block_kernel(const KgeBlockArgs a) {
     if (a.xcd_per == 1) { own_tile = kk % a.own_tiles; split = xcd + 8 * (kk / a.own_tiles); }
     else { split = xcd / a.xcd_per; own_tile = kk * a.xcd_per + xcd % a.xcd_per; }
     if (own_tile >= a.own_tiles) return;
-    const int own_base = own_tile * KGE_OWN_TILE;
+    const int own_base = own_tile * C::OWN_TILE;
     const int dblk0 = blockIdx.y * C::NBH;
-    const int oidx = own_base + wave * 32 + lr;
+    const int oidx0 = own_base + wave * 32 * OW + lr;     // own row of fragment h: oidx0 + 32 h
     const int t0 = split * a.tiles_per_split;
     const int t1 = min(a.str_tiles, t0 + a.tiles_per_split);
     const int str_limit = OWN_ROW ? a.N : a.B;            // valid stream rows
     if (split >= a.nsplit) return;
 
     // ---- own operand fragments: 16 bytes per lane per 32-byte k-step --------------------------
-    uint4 own[C::KS];
+    uint4 own[OW][C::KS];
     uint4 ownw[(TRANSH && OWN_ROW) ? C::KS : 1];
-    {
+    float o_qn[OW], o_c[OW], o_wn[OW], o_tn[OW];          // own-side scalars
+#pragma unroll
+    for (int h = 0; h < OW; ++h) {
+        const int oidx = oidx0 + 32 * h;
         const char *p = (const char *)a.own + (size_t)oidx * RB + g * 16;
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) own[ks] = *(const uint4 *)(p + ks * 32);
+        for (int ks = 0; ks < C::KS; ++ks) own[h][ks] = *(const uint4 *)(p + ks * 32);
         if constexpr (TRANSH && OWN_ROW) {
             const char *pw = (const char *)a.own2 + (size_t)oidx * RB + g * 16;
 #pragma unroll
             for (int ks = 0; ks < C::KS; ++ks) ownw[ks] = *(const uint4 *)(pw + ks * 32);
         }
-    }
-    // own-side scalars
-    float o_qn = 0.f, o_c = 0.f, o_wn = 1.f, o_tn = 0.f;
-    if constexpr (OWN_ROW) {
-        KgeRowInfo ri = a.rowinfo[oidx];
-        o_qn = ri.qn; o_c = ri.c; o_wn = ri.wn;
-    } else {
-        o_tn = a.tn[oidx];
+        o_qn[h] = 0.f; o_c[h] = 0.f; o_wn[h] = 1.f; o_tn[h] = 0.f;
+        if constexpr (OWN_ROW) {
+            KgeRowInfo ri = a.rowinfo[oidx];
+            o_qn[h] = ri.qn; o_c[h] = ri.c; o_wn[h] = ri.wn;
+        } else {
+            o_tn[h] = a.tn[oidx];
+        }
     }
 
     // ---- accumulators of the launch ------------------------------------------------------------
-    kge_f32x16 acc2[PHASE2 ? C::NBH : 1];
+    kge_f32x16 acc2[OW][PHASE2 ? C::NBH : 1];
     kge_f32x16 acc2b[(PHASE2 && TRANSH && OWN_ROW) ? C::NBH : 1];
     if constexpr (PHASE2) {
 #pragma unroll
         for (int b = 0; b < C::NBH; ++b) {
-            for (int i = 0; i < 16; ++i) acc2[b][i] = 0.f;
+#pragma unroll
+            for (int h = 0; h < OW; ++h)
+                for (int i = 0; i < 16; ++i) acc2[h][b][i] = 0.f;
             if constexpr (TRANSH && OWN_ROW) for (int i = 0; i < 16; ++i) acc2b[b][i] = 0.f;
         }
     }
-    float sum1 = 0.f, sum2 = 0.f, sum3 = 0.f;           // sums of the coefficients over the stream index
-    float st_m = -INFINITY, st_l = 0.f, st_acc = 0.f;   // FWD: running max (log2 domain) / sum / weighted loss
+    float sum1[OW], sum2[OW], sum3[OW];                   // sums of the coefficients over the stream index
+    float st_m[OW], st_l[OW], st_acc[OW];                 // FWD: running max (log2 domain) / sum / weighted loss
+#pragma unroll
+    for (int h = 0; h < OW; ++h) { sum1[h] = sum2[h] = sum3[h] = 0.f; st_m[h] = -INFINITY; st_l[h] = st_acc[h] = 0.f; }
 
     // ---- asynchronous staging of one stream tile --------------------------------------------------
     // X tile: instruction jj of this wave covers LDS bytes [(wave*X_IPW + jj) KB, +1 KB) of the tile; the
@@ -259,48 +269,40 @@ void kge_block_kernel(const KgeBlockArgs a) {
 
 #pragma unroll
     for (int s2 = 0; s2 < C::NSTAGE - 1; ++s2) issue(t0 + s2, s2);
+    // Pin the own operand as loaded before the loop.  Otherwise the compiler defers its waits for these
+    // ordinary loads to their first uses inside the hot loop, and such a wait (which counts every memory
+    // operation in flight) would also drain the asynchronous copies of the coming tiles on every iteration.
+#pragma unroll
+    for (int h = 0; h < OW; ++h) {
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            asm volatile("" : "+v"(own[h][ks].x), "+v"(own[h][ks].y), "+v"(own[h][ks].z), "+v"(own[h][ks].w));
+            if constexpr (TRANSH && OWN_ROW)
+                asm volatile("" : "+v"(ownw[ks].x), "+v"(ownw[ks].y), "+v"(ownw[ks].z), "+v"(ownw[ks].w));
+        }
+        asm volatile("" : "+v"(o_qn[h]), "+v"(o_c[h]), "+v"(o_wn[h]), "+v"(o_tn[h]));
+    }
 
     // The FWD pass keeps all weights relative to a per-row reference exponent st_m that is only
-    // raised (and the accumulators rescaled) when a tile's maximum exceeds it by more than KGE_TAU:
-    // weights stay below 2^KGE_TAU, and the rescaling code sits outside the hot loop.  A tile that
-    // trips the check leaves the inner loop before using its weights and is redone after the
-    // rescale (its stage is already published: resume).
-    int tile = t0;
-    bool resume = false;                                  // the tile's stage is already published
-    float pend_max = -INFINITY;
-    for (;;) {
-        if constexpr (MODE == KGE_MODE_FWD) {
-            if (tile >= t1) break;
-            const float m_new = fmaxf(st_m, pend_max);
-            const float r = m_new > st_m ? kge_exp2(st_m - m_new) : 1.f;      // exp2(-inf) = 0 at the start
-            st_m = m_new;
-            st_l *= r; st_acc *= r; sum1 *= r; sum2 *= r; sum3 *= r;
-#pragma unroll
-            for (int b = 0; b < C::NBH; ++b) {
-                // one block at a time: the accumulators live in AGPRs and pass through VGPRs here
-                for (int i = 0; i < 16; ++i) acc2[b][i] *= r;
-                asm volatile("" ::: "memory");
-                if constexpr (TRANSH) { for (int i = 0; i < 16; ++i) acc2b[b][i] *= r; asm volatile("" ::: "memory"); }
-            }
-        }
-        bool redo = false;
-        for (; tile < t1; ++tile) {
+    // raised (and what the row has accumulated rescaled) when a tile's maximum exceeds it by more than
+    // KGE_TAU: weights stay below 2^KGE_TAU, and the rescaling is a rarely taken branch of the loop.
+    for (int tile = t0; tile < t1; ++tile) {
         const int slot = tile - t0;
-        if (!resume) {
-            // tile `tile` has landed when at most NSTAGE-2 younger tiles are still in flight; after the
-            // barrier every wave has finished tile-1, whose stage receives tile + NSTAGE - 1
-            kge_wait_vmcnt<(C::NSTAGE - 2) * C::LPW>();
-            __syncthreads();
-            issue(tile + C::NSTAGE - 1, slot + C::NSTAGE - 1);
-        }
-        resume = false;
+        // tile `tile` has landed when at most NSTAGE-2 younger tiles are still in flight; after the
+        // barrier every wave has finished tile-1, whose stage receives tile + NSTAGE - 1
+        kge_wait_vmcnt<(C::NSTAGE - 2) * C::LPW>();
+        __syncthreads();
+        issue(tile + C::NSTAGE - 1, slot + C::NSTAGE - 1);
         const char *base = lds + (slot % C::NSTAGE) * C::STAGE_BYTES;
         const char *side = side_ring + (slot % C::SIDE_SLOTS) * C::SIDE_SLOT + wave * (OWN_ROW ? 256 : 1024);
-        // ---- phase 1: acc[stream, own]; all fragments are requested before the first MFMA --------
-        kge_f32x16 acc, accw;
-        for (int i = 0; i < 16; ++i) { acc[i] = 0.f; accw[i] = 0.f; }
+        // ---- phase 1: acc[h][stream, own]; every fragment read from the LDS feeds all own fragments ----
+        kge_f32x16 acc[OW], accw;
+#pragma unroll
+        for (int h = 0; h < OW; ++h) for (int i = 0; i < 16; ++i) acc[h][i] = 0.f;
+        for (int i = 0; i < 16; ++i) accw[i] = 0.f;
         {
-            constexpr int HALF = C::KS > 16 ? 16 : C::KS;          // at most 64 registers of fragments in flight
+            // fragments requested ahead of the MFMAs that use them: at most 64 (32) registers in flight
+            constexpr int HALF = OW > 1 ? 8 : (C::KS > 16 ? 16 : C::KS);
 #pragma unroll
             for (int k0 = 0; k0 < C::KS; k0 += HALF) {
                 uint4 av[HALF], aw[(TRANSH && !OWN_ROW) ? HALF : 1];
@@ -313,152 +315,203 @@ void kge_block_kernel(const KgeBlockArgs a) {
 #pragma unroll
                 for (int k = 0; k < HALF; ++k) {
                     const int ks = k0 + k;
-                    acc = kge_mma16<BF16>(acc, av[k], own[ks]);
+#pragma unroll
+                    for (int h = 0; h < OW; ++h) acc[h] = kge_mma16<BF16>(acc[h], av[k], own[h][ks]);
                     if constexpr (TRANSH && OWN_ROW) accw = kge_mma16<BF16>(accw, av[k], ownw[ks]);
-                    if constexpr (TRANSH && !OWN_ROW) accw = kge_mma16<BF16>(accw, aw[k], own[ks]);
+                    if constexpr (TRANSH && !OWN_ROW) accw = kge_mma16<BF16>(accw, aw[k], own[0][ks]);
                 }
             }
         }
         // ---- epilogue ------------------------------------------------------------------------
         const int sbase = tile * C::ST + 4 * g;            // stream index of register i: sbase + 8*(i/4) + (i%4)
         const bool tile_full = tile * C::ST + C::ST <= str_limit;
-        float sv[16], dv[16], Av[16];                      // score, 1/distance, w.t
+        const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
+        uint4 bf[OW][2], bf2[2];                           // bf16 B-operands of phase 2
+        float coefs[BF16 ? 1 : 16], coefs2[BF16 ? 1 : 16]; // fp32 B-operands of phase 2 (OW == 1)
+        // scores of own fragment h against the tile (SCORE mode stores them), 1/distance, w.t
+        auto scores = [&](int h, float (&sv)[16], float (&dv)[16], float (&Av)[16]) {
+            const int oidx = oidx0 + 32 * h;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
-            float s;
-            dv[i] = 0.f; Av[i] = 0.f;
-            if constexpr (KIND == KGE_KIND_MULT) {
-                s = acc[i];
-            } else {
-                float qn, cc, wn, tnv;
-                if constexpr (OWN_ROW) { qn = o_qn; cc = o_c; wn = o_wn; tnv = *(const float *)(side + sl * 4); }
-                else { float4 ri = *(const float4 *)(side + sl * 16); qn = ri.x; cc = ri.y; wn = ri.w; tnv = o_tn; }
-                float d2 = fmaf(-2.f, acc[i], qn + tnv);
-                if constexpr (TRANSH) { const float A = accw[i]; Av[i] = A; d2 += A * (2.f * cc - A * (2.f - wn)); }
-                if (d2 < 1e-3f * (qn + tnv)) {             // cancellation: redo this entry by direct differences
-                    const int sidx = tile * C::ST + sl;
-                    const int b = OWN_ROW ? oidx : sidx, n = OWN_ROW ? sidx : oidx;
-                    const char *qb = (const char *)(OWN_ROW ? a.own : a.str) + (size_t)b * RB;
-                    const char *tb = (const char *)(OWN_ROW ? a.str : a.own) + (size_t)n * RB;
-                    const char *wb = TRANSH ? (const char *)(OWN_ROW ? a.own2 : a.str2) + (size_t)b * RB : nullptr;
-                    d2 = kge_direct_d2<BF16, TRANSH>(qb, tb, wb, C::DP);
+            for (int i = 0; i < 16; ++i) {
+                const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
+                float s;
+                dv[i] = 0.f; Av[i] = 0.f;
+                if constexpr (KIND == KGE_KIND_MULT) {
+                    s = acc[h][i];
+                } else {
+                    float qn, cc, wn, tnv;
+                    if constexpr (OWN_ROW) { qn = o_qn[h]; cc = o_c[h]; wn = o_wn[h]; tnv = *(const float *)(side + sl * 4); }
+                    else { float4 ri = *(const float4 *)(side + sl * 16); qn = ri.x; cc = ri.y; wn = ri.w; tnv = o_tn[h]; }
+                    float d2 = fmaf(-2.f, acc[h][i], qn + tnv);
+                    if constexpr (TRANSH) { const float A = accw[i]; Av[i] = A; d2 += A * (2.f * cc - A * (2.f - wn)); }
+                    if (d2 < 1e-3f * (qn + tnv)) {             // cancellation: redo this entry by direct differences
+                        const int sidx = tile * C::ST + sl;
+                        const int b = OWN_ROW ? oidx : sidx, n = OWN_ROW ? sidx : oidx;
+                        const char *qb = (const char *)(OWN_ROW ? a.own : a.str) + (size_t)b * RB;
+                        const char *tb = (const char *)(OWN_ROW ? a.str : a.own) + (size_t)n * RB;
+                        const char *wb = TRANSH ? (const char *)(OWN_ROW ? a.own2 : a.str2) + (size_t)b * RB : nullptr;
+                        d2 = kge_direct_d2<BF16, TRANSH>(qb, tb, wb, C::DP);
+                    }
+                    d2 = fmaxf(d2, 0.f);
+                    const float inv = d2 > 0.f ? __builtin_amdgcn_rsqf(d2) : 0.f;
+                    dv[i] = inv;
+                    s = -d2 * inv;                              // -sqrt(d2)
                 }
-                d2 = fmaxf(d2, 0.f);
-                const float inv = d2 > 0.f ? __builtin_amdgcn_rsqf(d2) : 0.f;
-                dv[i] = inv;
-                s = -d2 * inv;                              // -sqrt(d2)
+                sv[i] = s;
             }
-            sv[i] = s;
-        }
-        if constexpr (MODE == KGE_MODE_SCORE) {
-            if (oidx < a.N) {
+            if constexpr (MODE == KGE_MODE_SCORE) {
+                if (oidx < a.N) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int b = sbase + 8 * (i >> 2) + (i & 3);
-                    if (b < a.B) a.S_out[(size_t)b * a.N + oidx] = sv[i];
+                    for (int i = 0; i < 16; ++i) {
+                        const int b = sbase + 8 * (i >> 2) + (i & 3);
+                        if (b < a.B) a.S_out[(size_t)b * a.N + oidx] = sv[i];
+                    }
                 }
             }
-        }
-        float coef[16], coef2[16];
-        if constexpr (MODE == KGE_MODE_FWD) {
-            // softmax weights of this row over the stream index, relative to the reference st_m (log2 domain)
-            const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
-            float x2[16], tile_max = -INFINITY;
+        };
+        // FWD: exponents of the softmax weights of own fragment h relative to its reference st_m (log2
+        // domain; entries past the end of the stream operand get -inf: only the last tile has any, the
+        // branch is wave-uniform), and their maximum over the tile.  Lanes l and l^32 hold the two halves
+        // of the same own row and feed ONE contraction in phase 2, so they share the maximum.
+        auto exponents = [&](int h, const float (&sv)[16], float (&x2)[16]) -> float {
+            const float m_neg = st_m[h] > -INFINITY ? -st_m[h] : 0.f;
+            float tm = -INFINITY;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) x2[i] = sv[i] * xscale;
-            if (!tile_full) {                               // wave-uniform: only the last tile of the block is ragged
+            for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
+            if (!tile_full) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
                     if (sbase + 8 * (i >> 2) + (i & 3) >= str_limit) x2[i] = -INFINITY;
             }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) tile_max = fmaxf(tile_max, x2[i]);
-            // lanes l and l^32 hold the two halves of the same row and feed ONE contraction in
-            // phase 2, so they must share the reference
-            tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 32));
-            if (__any(tile_max > st_m + KGE_TAU)) { pend_max = tile_max; redo = true; resume = true; break; }
-            const float m_safe = st_m > -INFINITY ? st_m : 0.f;
+            for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
+            return fmaxf(tm, __shfl_xor(tm, 32));
+        };
+        // the coefficients of phase 2 for own fragment h, packed as its B-operand
+        auto weights = [&](int h, const float (&sv)[16], const float (&dv)[16], const float (&Av)[16], const float (&x2)[16]) {
+            float coef[16], coef2[16];
+            if constexpr (MODE == KGE_MODE_FWD) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float e = kge_exp2(x2[i] - m_safe);                    // masked entries: exp2(-inf) = 0
-                st_l += e;
-                float u = e;
-                if constexpr (LOSS == KGE_LOGSIGMOID) {
-                    // weight * sigma(gamma + s) for the gradient, weight * softplus(gamma + s) for the loss
-                    const float y = a.gamma + sv[i];
-                    const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
-                    const float rcp = __builtin_amdgcn_rcpf(1.f + t);
-                    const float sig = y >= 0.f ? rcp : t * rcp;
-                    const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + t);
-                    if (e > 0.f) st_acc = fmaf(e, softplus, st_acc);
-                    u = e * sig;
+                for (int i = 0; i < 16; ++i) {
+                    const float e = kge_exp2(x2[i]);                             // masked entries: exp2(-inf) = 0
+                    st_l[h] += e;
+                    float u = e;
+                    if constexpr (LOSS == KGE_LOGSIGMOID) {
+                        // weight * sigma(gamma + s) for the gradient, weight * softplus(gamma + s) for the loss
+                        const float y = a.gamma + sv[i];
+                        const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                        const float rcp = __builtin_amdgcn_rcpf(1.f + t);
+                        const float sig = y >= 0.f ? rcp : t * rcp;
+                        const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + t);
+                        if (e > 0.f) st_acc[h] = fmaf(e, softplus, st_acc[h]);
+                        u = e * sig;
+                    }
+                    const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                    coef[i] = c1;
+                    if constexpr (KIND == KGE_KIND_DIST) sum1[h] += c1;  // only the distance scorers' chain rule needs it
+                    if constexpr (TRANSH) { coef2[i] = c1 * Av[i]; sum2[h] += coef2[i]; sum3[h] += coef2[i] * Av[i]; }
                 }
-                const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
-                coef[i] = c1;
-                if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;     // only the distance scorers' chain rule needs it
-                if constexpr (TRANSH) { coef2[i] = c1 * Av[i]; sum2 += coef2[i]; sum3 += coef2[i] * Av[i]; }
             }
-        }
-        if constexpr (MODE == KGE_MODE_GRADT) {
-            // gradient coefficient of every (query, negative) pair from the finished row constants
-            const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
+            if constexpr (MODE == KGE_MODE_GRADT) {
+                // gradient coefficient of every (query, negative) pair from the finished row constants
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
-                const float K2 = *(const float *)(side + sl * 16 + 8);       // -inf for padded queries
-                float u = kge_exp2(fmaf(sv[i], xscale, K2));
-                if constexpr (LOSS == KGE_LOGSIGMOID) {
-                    const float y = a.gamma + sv[i];
-                    const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
-                    const float rcp = __builtin_amdgcn_rcpf(1.f + t);
-                    u *= y >= 0.f ? rcp : t * rcp;
+                for (int i = 0; i < 16; ++i) {
+                    const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
+                    const float K2 = *(const float *)(side + sl * 16 + 8);       // -inf for padded queries
+                    float u = kge_exp2(fmaf(sv[i], xscale, K2));
+                    if constexpr (LOSS == KGE_LOGSIGMOID) {
+                        const float y = a.gamma + sv[i];
+                        const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                        const float rcp = __builtin_amdgcn_rcpf(1.f + t);
+                        u *= y >= 0.f ? rcp : t * rcp;
+                    }
+                    const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                    coef[i] = c1;
+                    if constexpr (KIND == KGE_KIND_DIST) sum1[h] += c1;
+                    if constexpr (TRANSH) coef2[i] = c1 * Av[i];
                 }
-                const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
-                coef[i] = c1;
-                if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
-                if constexpr (TRANSH) coef2[i] = c1 * Av[i];
             }
+            if constexpr (PHASE2) {
+                if constexpr (BF16) {
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        bf[h][s2] = make_uint4(kge_pack_bf16x2(coef[8 * s2 + 0], coef[8 * s2 + 1]),
+                                               kge_pack_bf16x2(coef[8 * s2 + 2], coef[8 * s2 + 3]),
+                                               kge_pack_bf16x2(coef[8 * s2 + 4], coef[8 * s2 + 5]),
+                                               kge_pack_bf16x2(coef[8 * s2 + 6], coef[8 * s2 + 7]));
+                        if constexpr (TRANSH)
+                            bf2[s2] = make_uint4(kge_pack_bf16x2(coef2[8 * s2 + 0], coef2[8 * s2 + 1]),
+                                                 kge_pack_bf16x2(coef2[8 * s2 + 2], coef2[8 * s2 + 3]),
+                                                 kge_pack_bf16x2(coef2[8 * s2 + 4], coef2[8 * s2 + 5]),
+                                                 kge_pack_bf16x2(coef2[8 * s2 + 6], coef2[8 * s2 + 7]));
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) { coefs[i] = coef[i]; if constexpr (TRANSH) coefs2[i] = coef2[i]; }
+                }
+            }
+        };
+#pragma unroll
+        for (int h = 0; h < OW; ++h) {
+            float sv[16], dv[16], Av[16], x2[16];
+            scores(h, sv, dv, Av);
+            if constexpr (MODE == KGE_MODE_FWD) {
+                const float tm = exponents(h, sv, x2);
+                const bool have = st_m[h] > -INFINITY;
+                const bool trip = tm > (have ? KGE_TAU : -INFINITY);   // without a reference, any finite entry sets one
+                if (__any(trip)) {
+                    // the rows that tripped take the tile's maximum as their reference
+                    const float m_new = trip ? (have ? tm + st_m[h] : tm) : st_m[h];
+                    const float shift = trip ? -tm : 0.f;              // exponents relative to the new reference
+                    const float r = trip ? (have ? kge_exp2(-tm) : 0.f) : 1.f;   // nothing accumulated yet without one
+                    st_m[h] = m_new;
+                    st_l[h] *= r; st_acc[h] *= r; sum1[h] *= r; sum2[h] *= r; sum3[h] *= r;
+#pragma unroll
+                    for (int b = 0; b < C::NBH; ++b) {
+                        // one block at a time: the accumulators live in AGPRs and pass through VGPRs here; the
+                        // empty statements keep this rarely executed code from being turned into selects
+                        for (int i = 0; i < 16; ++i) acc2[h][b][i] *= r;
+                        asm volatile("" ::: "memory");
+                        if constexpr (TRANSH) { for (int i = 0; i < 16; ++i) acc2b[b][i] *= r; asm volatile("" ::: "memory"); }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) x2[i] += shift;       // masked entries stay at -inf
+                }
+            }
+            weights(h, sv, dv, Av, x2);
         }
         // ---- phase 2: out^t[d, own] += Xt[d, stream] . coef[stream, own] -----------------------
         if constexpr (PHASE2) {
             const char *xt = base + C::X_BYTES * C::NX;
             if constexpr (BF16) {
-                uint4 bf[2], bf2[2];
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    bf[s2] = make_uint4(kge_pack_bf16x2(coef[8 * s2 + 0], coef[8 * s2 + 1]),
-                                        kge_pack_bf16x2(coef[8 * s2 + 2], coef[8 * s2 + 3]),
-                                        kge_pack_bf16x2(coef[8 * s2 + 4], coef[8 * s2 + 5]),
-                                        kge_pack_bf16x2(coef[8 * s2 + 6], coef[8 * s2 + 7]));
-                    if constexpr (TRANSH)
-                        bf2[s2] = make_uint4(kge_pack_bf16x2(coef2[8 * s2 + 0], coef2[8 * s2 + 1]),
-                                             kge_pack_bf16x2(coef2[8 * s2 + 2], coef2[8 * s2 + 3]),
-                                             kge_pack_bf16x2(coef2[8 * s2 + 4], coef2[8 * s2 + 5]),
-                                             kge_pack_bf16x2(coef2[8 * s2 + 6], coef2[8 * s2 + 7]));
-                }
                 // The transposed operand keeps, inside every group of 16 stream entries, the 8 entries of one
                 // lane half contiguous (the producer swaps bits 2 and 3 of the column), so the A-fragment of
                 // (block, s2) is ONE 16-byte chunk: chunk 2*s2 + g of row dcol, at its swizzled slot.
-                uint4 av2[C::NBH][2], aw2[(TRANSH && !OWN_ROW) ? C::NBH : 1][2];
+                constexpr int BG = OW > 1 ? 4 : C::NBH;    // blocks whose fragments are requested together
 #pragma unroll
-                for (int blk = 0; blk < C::NBH; ++blk) {
-                    const int row = (dblk0 + blk) * 32 + lr;
+                for (int b0 = 0; b0 < C::NBH; b0 += BG) {
+                    uint4 av2[BG][2], aw2[(TRANSH && !OWN_ROW) ? BG : 1][2];
 #pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) {
-                        const int sslot = (((row & 1) << 2) | (2 * s2 + g)) ^ ((row >> 1) & 7);
-                        const char *p = xt + (row >> 1) * 128 + sslot * 16;
-                        av2[blk][s2] = *(const uint4 *)p;
-                        if constexpr (TRANSH && !OWN_ROW) aw2[blk][s2] = *(const uint4 *)(p + C::XT_BYTES);
+                    for (int bb = 0; bb < BG; ++bb) {
+                        const int row = (dblk0 + b0 + bb) * 32 + lr;
+#pragma unroll
+                        for (int s2 = 0; s2 < 2; ++s2) {
+                            const int sslot = (((row & 1) << 2) | (2 * s2 + g)) ^ ((row >> 1) & 7);
+                            const char *p = xt + (row >> 1) * 128 + sslot * 16;
+                            av2[bb][s2] = *(const uint4 *)p;
+                            if constexpr (TRANSH && !OWN_ROW) aw2[bb][s2] = *(const uint4 *)(p + C::XT_BYTES);
+                        }
                     }
-                }
 #pragma unroll
-                for (int blk = 0; blk < C::NBH; ++blk) {
+                    for (int bb = 0; bb < BG; ++bb) {
+                        const int blk = b0 + bb;
 #pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) {
-                        acc2[blk] = kge_mma16<true>(acc2[blk], av2[blk][s2], bf[s2]);
-                        if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma16<true>(acc2b[blk], av2[blk][s2], bf2[s2]);
-                        if constexpr (TRANSH && !OWN_ROW) acc2[blk] = kge_mma16<true>(acc2[blk], aw2[blk][s2], bf2[s2]);
+                        for (int s2 = 0; s2 < 2; ++s2) {
+#pragma unroll
+                            for (int h = 0; h < OW; ++h) acc2[h][blk] = kge_mma16<true>(acc2[h][blk], av2[bb][s2], bf[h][s2]);
+                            if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma16<true>(acc2b[blk], av2[bb][s2], bf2[s2]);
+                            if constexpr (TRANSH && !OWN_ROW) acc2[0][blk] = kge_mma16<true>(acc2[0][blk], aw2[bb][s2], bf2[s2]);
+                        }
                     }
                 }
             } else {
@@ -477,40 +530,43 @@ void kge_block_kernel(const KgeBlockArgs a) {
                     for (int j = 0; j < 4; ++j) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            acc2[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coef[4 * j + r], acc2[blk], 0, 0, 0);
+                            acc2[0][blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coefs[4 * j + r], acc2[0][blk], 0, 0, 0);
                             if constexpr (TRANSH && OWN_ROW)
-                                acc2b[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coef2[4 * j + r], acc2b[blk], 0, 0, 0);
+                                acc2b[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coefs2[4 * j + r], acc2b[blk], 0, 0, 0);
                             if constexpr (TRANSH && !OWN_ROW)
-                                acc2[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av2[j][r], coef2[4 * j + r], acc2[blk], 0, 0, 0);
+                                acc2[0][blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av2[j][r], coefs2[4 * j + r], acc2[0][blk], 0, 0, 0);
                         }
                     }
                 }
             }
         }
-        }
-        if (MODE != KGE_MODE_FWD || !redo) break;
     }
     kge_wait_vmcnt<0>();                                  // no copy may be in flight when the LDS is released
 
     // ---- write-out ---------------------------------------------------------------------------------
     if constexpr (PHASE2) {
-        // lanes l and l^32 hold the same own row over disjoint stream entries (same running max):
-        // add their scalars.  The phase-2 accumulators already contain both halves.
-        if constexpr (MODE == KGE_MODE_FWD) { st_l += __shfl_xor(st_l, 32); st_acc += __shfl_xor(st_acc, 32); }
-        sum1 += __shfl_xor(sum1, 32); sum2 += __shfl_xor(sum2, 32); sum3 += __shfl_xor(sum3, 32);
-        if (g == 0 && blockIdx.y == 0) {
-            a.sum_part[(size_t)split * a.own_pad + oidx] = make_float4(sum1, sum2, sum3, 0.f);
-            if constexpr (MODE == KGE_MODE_FWD) a.stat_part[(size_t)split * a.own_pad + oidx] = make_float4(st_m, st_l, st_acc, 0.f);
-        }
 #pragma unroll
-        for (int blk = 0; blk < C::NBH; ++blk) {
+        for (int h = 0; h < OW; ++h) {
+            const int oidx = oidx0 + 32 * h;
+            // lanes l and l^32 hold the same own row over disjoint stream entries (same running max):
+            // add their scalars.  The phase-2 accumulators already contain both halves.
+            if constexpr (MODE == KGE_MODE_FWD) { st_l[h] += __shfl_xor(st_l[h], 32); st_acc[h] += __shfl_xor(st_acc[h], 32); }
+            sum1[h] += __shfl_xor(sum1[h], 32); sum2[h] += __shfl_xor(sum2[h], 32); sum3[h] += __shfl_xor(sum3[h], 32);
+            if (g == 0 && blockIdx.y == 0) {
+                a.sum_part[(size_t)split * a.own_pad + oidx] = make_float4(sum1[h], sum2[h], sum3[h], 0.f);
+                if constexpr (MODE == KGE_MODE_FWD)
+                    a.stat_part[(size_t)split * a.own_pad + oidx] = make_float4(st_m[h], st_l[h], st_acc[h], 0.f);
+            }
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int dcol = (dblk0 + blk) * 32 + 8 * q4 + 4 * g;
-                const size_t o = ((size_t)split * a.own_pad + oidx) * C::DP + dcol;
-                *(float4 *)(a.acc_part + o) = make_float4(acc2[blk][4 * q4], acc2[blk][4 * q4 + 1], acc2[blk][4 * q4 + 2], acc2[blk][4 * q4 + 3]);
-                if constexpr (TRANSH && OWN_ROW)
-                    *(float4 *)(a.acc_part2 + o) = make_float4(acc2b[blk][4 * q4], acc2b[blk][4 * q4 + 1], acc2b[blk][4 * q4 + 2], acc2b[blk][4 * q4 + 3]);
+            for (int blk = 0; blk < C::NBH; ++blk) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int dcol = (dblk0 + blk) * 32 + 8 * q4 + 4 * g;
+                    const size_t o = ((size_t)split * a.own_pad + oidx) * C::DP + dcol;
+                    *(float4 *)(a.acc_part + o) = make_float4(acc2[h][blk][4 * q4], acc2[h][blk][4 * q4 + 1], acc2[h][blk][4 * q4 + 2], acc2[h][blk][4 * q4 + 3]);
+                    if constexpr (TRANSH && OWN_ROW)
+                        *(float4 *)(a.acc_part2 + o) = make_float4(acc2b[blk][4 * q4], acc2b[blk][4 * q4 + 1], acc2b[blk][4 * q4 + 2], acc2b[blk][4 * q4 + 3]);
+                }
             }
         }
     }
@@ -518,7 +574,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
 
 template <bool BF16, int RB, int MODE, bool TRANSH, int KIND, int LOSS, int DSPLIT>
 int kge_block_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
-    using C = KgeBlockCfg<BF16, RB, MODE, TRANSH, DSPLIT>;
+    using C = KgeBlockCfg<BF16, RB, MODE, TRANSH, KIND, DSPLIT>;
     auto kern = kge_block_kernel<BF16, RB, MODE, TRANSH, KIND, LOSS, DSPLIT>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -526,6 +582,7 @@ int kge_block_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream
             return KGE_E_HIP;
         attr_set = true;
     }
+    if ((int64_t)own_tiles * C::OWN_TILE != a.own_pad) return KGE_E_INVALID_ARG;   // the caller's geometry must match
     KgeBlockArgs b = a;
     b.own_tiles = own_tiles; b.nsplit = nsplit;
     int groups;                                            // workgroups per XCD

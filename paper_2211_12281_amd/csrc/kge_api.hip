@@ -20,7 +20,7 @@ struct Geometry {
     bool bf16, transh;
     int es, rb, dp, kind;
     int B, N, Bp, Np;
-    int own_tiles_b, own_tiles_n;       // 128-row tiles
+    int own_tiles_b, own_tiles_n;       // own tiles of the FWD pass (queries) and of the SCORE / GRADT passes (negatives)
     int str_tiles_b, str_tiles_n;       // 32-row tiles
     int nsplit_q, tps_q;                // row-owner launches: splits over the negatives
     int nsplit_t, tps_t;                // column-owner launches: splits over the queries
@@ -56,7 +56,9 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.kind = (m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
     g.B = (int)B; g.N = (int)N;
     g.Bp = (int)kge_round_up(B, KGE_PAD); g.Np = (int)kge_round_up(N, KGE_PAD);
-    g.own_tiles_b = g.Bp / KGE_OWN_TILE; g.own_tiles_n = g.Np / KGE_OWN_TILE;
+    // (SCORE and GRADT own the negatives with the same number of fragments per wave)
+    g.own_tiles_b = g.Bp / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_FWD, g.kind));
+    g.own_tiles_n = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_GRADT, g.kind));
     g.str_tiles_b = g.Bp / KGE_STREAM_TILE; g.str_tiles_n = g.Np / KGE_STREAM_TILE;
     auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps) {
         if (own_tiles == 0 || str_tiles == 0) { nsplit = 0; tps = 0; return; }

@@ -27,12 +27,21 @@ static inline int64_t kge_round_up(int64_t x, int64_t m) { return (x + m - 1) / 
 // ---------------------------------------------------------------------------------------------
 // Tile geometry of the block kernels
 // ---------------------------------------------------------------------------------------------
-constexpr int KGE_OWN_TILE = 128;     // rows owned by one workgroup (4 waves x 32)
 constexpr int KGE_STREAM_TILE = 32;   // rows streamed through LDS per iteration
-constexpr int KGE_PAD = 128;          // B and N are padded to this in the workspace copies
+constexpr int KGE_PAD = 256;          // B and N are padded to this in the workspace copies
 
 enum { KGE_MODE_SCORE = 0, KGE_MODE_FWD = 1, KGE_MODE_GRADT = 2 };
 enum { KGE_KIND_MULT = 0, KGE_KIND_DIST = 1 };
+
+// 32-row fragments of its operand that each of a workgroup's four waves owns (the workgroup owns
+// 128 times this many rows).  Two where the registers allow it: every fragment read from the LDS then
+// feeds two MFMAs, which halves the LDS traffic per flop - the limit of the bf16 kernels.  Not with
+// the TransH operands, and not in the FWD pass, whose gradient accumulators for two fragments of 256
+// dimensions would take the whole accumulator file and more.
+constexpr int kge_block_ow(bool bf16, int rb, bool transh, int mode, int kind) {
+    (void)kind;
+    return (bf16 && rb == 512 && !transh && mode != KGE_MODE_FWD) ? 2 : 1;
+}
 
 // Per-row side information of the queries: squared norm of q, c = w.q (TransH), the per-row
 // constant K of the gradient coefficient exp2(x * log2e + K) (log2 domain), squared norm of the
