@@ -137,6 +137,7 @@ struct KgeBlockCfg {
     static_assert(X_BYTES % 4096 == 0 && XT_BYTES % 4096 == 0, "tile copies must divide over four waves");
     static_assert((NSTAGE - 2) * LPW < 64, "vmcnt range");
     static_assert(OW == 1 || !TRANSH, "two own fragments per wave leave no registers for the TransH operands");
+    static_assert(KS % 8 == 0, "phase 1 works in groups of four fragments, split in two halves");
 };
 
 template <bool BF16, int RB, int MODE, bool TRANSH, int KIND, int LOSS, int DSPLIT>
@@ -283,174 +284,237 @@ void kge_block_kernel(const KgeBlockArgs a) {
         asm volatile("" : "+v"(o_qn[h]), "+v"(o_c[h]), "+v"(o_wn[h]), "+v"(o_tn[h]));
     }
 
-    // The FWD pass keeps all weights relative to a per-row reference exponent st_m that is only
-    // raised (and what the row has accumulated rescaled) when a tile's maximum exceeds it by more than
-    // KGE_TAU: weights stay below 2^KGE_TAU, and the rescaling is a rarely taken branch of the loop.
-    for (int tile = t0; tile < t1; ++tile) {
-        const int slot = tile - t0;
-        // tile `tile` has landed when at most NSTAGE-2 younger tiles are still in flight; after the
-        // barrier every wave has finished tile-1, whose stage receives tile + NSTAGE - 1
-        kge_wait_vmcnt<(C::NSTAGE - 2) * C::LPW>();
-        __syncthreads();
-        issue(tile + C::NSTAGE - 1, slot + C::NSTAGE - 1);
-        const char *base = lds + (slot % C::NSTAGE) * C::STAGE_BYTES;
-        const char *side = side_ring + (slot % C::SIDE_SLOTS) * C::SIDE_SLOT + wave * (OWN_ROW ? 256 : 1024);
-        // ---- phase 1: acc[h][stream, own]; every fragment read from the LDS feeds all own fragments ----
-        kge_f32x16 acc[OW], accw;
+    // ---- state of the tile in work (set by the loops below, used by the pieces) -------------------
+    int tile = t0;
+    const char *base = lds, *side = side_ring;
+    int sbase = 0;                                        // stream index of register i: sbase + 8*(i/4) + (i%4)
+    bool tile_full = true;
+    const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
+    auto set_tile = [&](int t) {
+        tile = t;
+        const int slot = t - t0;
+        base = lds + (slot % C::NSTAGE) * C::STAGE_BYTES;
+        side = side_ring + (slot % C::SIDE_SLOTS) * C::SIDE_SLOT + wave * (OWN_ROW ? 256 : 1024);
+        sbase = t * C::ST + 4 * g;
+        tile_full = t * C::ST + C::ST <= str_limit;
+    };
+    kge_f32x16 acc[OW], accw;                              // phase-1 accumulators: [stream, own]
+    uint4 bf[OW][2], bf2[2];                               // bf16 B-operands of phase 2
+    float coefs[BF16 ? 1 : 16], coefs2[BF16 ? 1 : 16];     // fp32 B-operands of phase 2 (OW == 1)
+
+    // ---- phase 1: acc[h][stream, own] = X_tile . own^t; a fragment read from the LDS feeds all own fragments
+    constexpr bool HASW = TRANSH && !OWN_ROW;
+    constexpr int G1 = HASW ? 2 : 4, NG1 = C::KS / G1;      // fragments per group, groups
+    uint4 av[C::KS], aw[HASW ? C::KS : 1];
+    auto ld1 = [&](const char *stage, int grp) {
+#pragma unroll
+        for (int k = 0; k < G1; ++k) {
+            const int ks = grp * G1 + k;
+            av[ks] = *(const uint4 *)(stage + frag_off[ks & 3] + 128 * (ks >> 2));
+            if constexpr (HASW) aw[ks] = *(const uint4 *)(stage + C::X_BYTES + frag_off[ks & 3] + 128 * (ks >> 2));
+        }
+    };
+    auto zero1 = [&]() {
 #pragma unroll
         for (int h = 0; h < OW; ++h) for (int i = 0; i < 16; ++i) acc[h][i] = 0.f;
         for (int i = 0; i < 16; ++i) accw[i] = 0.f;
-        {
-            // fragments requested ahead of the MFMAs that use them: at most 64 (32) registers in flight
-            constexpr int HALF = OW > 1 ? 8 : (C::KS > 16 ? 16 : C::KS);
+    };
+    auto mma1 = [&](int grp) {
 #pragma unroll
-            for (int k0 = 0; k0 < C::KS; k0 += HALF) {
-                uint4 av[HALF], aw[(TRANSH && !OWN_ROW) ? HALF : 1];
+        for (int k = 0; k < G1; ++k) {
+            const int ks = grp * G1 + k;
 #pragma unroll
-                for (int k = 0; k < HALF; ++k) {
-                    const int ks = k0 + k;
-                    av[k] = *(const uint4 *)(base + frag_off[ks & 3] + 128 * (ks >> 2));
-                    if constexpr (TRANSH && !OWN_ROW) aw[k] = *(const uint4 *)(base + C::X_BYTES + frag_off[ks & 3] + 128 * (ks >> 2));
+            for (int h = 0; h < OW; ++h) acc[h] = kge_mma16<BF16>(acc[h], av[ks], own[h][ks]);
+            if constexpr (TRANSH && OWN_ROW) accw = kge_mma16<BF16>(accw, av[ks], ownw[ks]);
+            if constexpr (HASW) accw = kge_mma16<BF16>(accw, aw[ks], own[0][ks]);
+        }
+    };
+    // ---- phase 2: out^t[d, own] += Xt_tile[d, stream] . coef[stream, own] ---------------------------
+    constexpr int G2 = BF16 ? (HASW ? 1 : 2) : 1;          // blocks per group
+    constexpr int NG2 = PHASE2 ? C::NBH / G2 : 0;
+    constexpr int F2 = BF16 ? 2 : 4;                       // 16-byte fragments per block
+    uint4 av2[PHASE2 ? C::NBH : 1][F2], aw2[(PHASE2 && HASW) ? C::NBH : 1][F2];
+    auto ld2 = [&](const char *stage, int grp) {
+        const char *xt = stage + C::X_BYTES * C::NX;
+#pragma unroll
+        for (int bb = 0; bb < G2; ++bb) {
+            const int blk = grp * G2 + bb;
+            const int row = (dblk0 + blk) * 32 + lr;
+#pragma unroll
+            for (int f = 0; f < F2; ++f) {
+                const char *p;
+                if constexpr (BF16) {
+                    // The transposed operand keeps, inside every group of 16 stream entries, the 8 entries of
+                    // one lane half contiguous (the producer swaps bits 2 and 3 of the column), so the
+                    // A-fragment of (block, f) is ONE 16-byte chunk: chunk 2 f + g of row dcol, at its slot.
+                    const int sslot = (((row & 1) << 2) | (2 * f + g)) ^ ((row >> 1) & 7);
+                    p = xt + (row >> 1) * 128 + sslot * 16;
+                } else {
+                    p = xt + row * 128 + ((2 * f + g) ^ (row & 7)) * 16;
                 }
+                av2[blk][f] = *(const uint4 *)p;
+                if constexpr (HASW) aw2[blk][f] = *(const uint4 *)(p + C::XT_BYTES);
+            }
+        }
+    };
+    auto mma2 = [&](int grp) {
 #pragma unroll
-                for (int k = 0; k < HALF; ++k) {
-                    const int ks = k0 + k;
+        for (int bb = 0; bb < G2; ++bb) {
+            const int blk = grp * G2 + bb;
+            if constexpr (BF16) {
 #pragma unroll
-                    for (int h = 0; h < OW; ++h) acc[h] = kge_mma16<BF16>(acc[h], av[k], own[h][ks]);
-                    if constexpr (TRANSH && OWN_ROW) accw = kge_mma16<BF16>(accw, av[k], ownw[ks]);
-                    if constexpr (TRANSH && !OWN_ROW) accw = kge_mma16<BF16>(accw, aw[k], own[0][ks]);
+                for (int s2 = 0; s2 < 2; ++s2) {
+#pragma unroll
+                    for (int h = 0; h < OW; ++h) acc2[h][blk] = kge_mma16<true>(acc2[h][blk], av2[blk][s2], bf[h][s2]);
+                    if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma16<true>(acc2b[blk], av2[blk][s2], bf2[s2]);
+                    if constexpr (HASW) acc2[0][blk] = kge_mma16<true>(acc2[0][blk], aw2[blk][s2], bf2[s2]);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const kge_f32x4 fa = __builtin_bit_cast(kge_f32x4, av2[blk][j]);
+                    kge_f32x4 fw;
+                    if constexpr (HASW) fw = __builtin_bit_cast(kge_f32x4, aw2[blk][j]);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        acc2[0][blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[r], coefs[4 * j + r], acc2[0][blk], 0, 0, 0);
+                        if constexpr (TRANSH && OWN_ROW)
+                            acc2b[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[r], coefs2[4 * j + r], acc2b[blk], 0, 0, 0);
+                        if constexpr (HASW)
+                            acc2[0][blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[r], coefs2[4 * j + r], acc2[0][blk], 0, 0, 0);
+                    }
                 }
             }
         }
-        // ---- epilogue ------------------------------------------------------------------------
-        const int sbase = tile * C::ST + 4 * g;            // stream index of register i: sbase + 8*(i/4) + (i%4)
-        const bool tile_full = tile * C::ST + C::ST <= str_limit;
-        const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
-        uint4 bf[OW][2], bf2[2];                           // bf16 B-operands of phase 2
-        float coefs[BF16 ? 1 : 16], coefs2[BF16 ? 1 : 16]; // fp32 B-operands of phase 2 (OW == 1)
-        // scores of own fragment h against the tile (SCORE mode stores them), 1/distance, w.t
-        auto scores = [&](int h, float (&sv)[16], float (&dv)[16], float (&Av)[16]) {
-            const int oidx = oidx0 + 32 * h;
+    };
+    // ---- epilogue: scores / loss weights / gradient coefficients of the tile, element by element ----
+    // scores of own fragment h against the tile (SCORE mode stores them), 1/distance, w.t
+    auto scores = [&](int h, float (&sv)[16], float (&dv)[16], float (&Av)[16]) {
+        const int oidx = oidx0 + 32 * h;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
+            float s;
+            dv[i] = 0.f; Av[i] = 0.f;
+            if constexpr (KIND == KGE_KIND_MULT) {
+                s = acc[h][i];
+            } else {
+                float qn, cc, wn, tnv;
+                if constexpr (OWN_ROW) { qn = o_qn[h]; cc = o_c[h]; wn = o_wn[h]; tnv = *(const float *)(side + sl * 4); }
+                else { float4 ri = *(const float4 *)(side + sl * 16); qn = ri.x; cc = ri.y; wn = ri.w; tnv = o_tn[h]; }
+                float d2 = fmaf(-2.f, acc[h][i], qn + tnv);
+                if constexpr (TRANSH) { const float A = accw[i]; Av[i] = A; d2 += A * (2.f * cc - A * (2.f - wn)); }
+                if (d2 < 1e-3f * (qn + tnv)) {             // cancellation: redo this entry by direct differences
+                    const int sidx = tile * C::ST + sl;
+                    const int b = OWN_ROW ? oidx : sidx, n = OWN_ROW ? sidx : oidx;
+                    const char *qb = (const char *)(OWN_ROW ? a.own : a.str) + (size_t)b * RB;
+                    const char *tb = (const char *)(OWN_ROW ? a.str : a.own) + (size_t)n * RB;
+                    const char *wb = TRANSH ? (const char *)(OWN_ROW ? a.own2 : a.str2) + (size_t)b * RB : nullptr;
+                    d2 = kge_direct_d2<BF16, TRANSH>(qb, tb, wb, C::DP);
+                }
+                d2 = fmaxf(d2, 0.f);
+                const float inv = d2 > 0.f ? __builtin_amdgcn_rsqf(d2) : 0.f;
+                dv[i] = inv;
+                s = -d2 * inv;                              // -sqrt(d2)
+            }
+            sv[i] = s;
+        }
+        if constexpr (MODE == KGE_MODE_SCORE) {
+            if (oidx < a.N) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int b = sbase + 8 * (i >> 2) + (i & 3);
+                    if (b < a.B) a.S_out[(size_t)b * a.N + oidx] = sv[i];
+                }
+            }
+        }
+    };
+    // FWD: exponents of the softmax weights of own fragment h relative to its reference st_m (log2
+    // domain; entries past the end of the stream operand get -inf: only the last tile has any, the
+    // branch is wave-uniform), and their maximum over the tile.  Lanes l and l^32 hold the two halves
+    // of the same own row and feed ONE contraction in phase 2, so they share the maximum.
+    auto exponents = [&](int h, const float (&sv)[16], float (&x2)[16]) -> float {
+        const float m_neg = st_m[h] > -INFINITY ? -st_m[h] : 0.f;
+        float tm = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
+        if (!tile_full) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (sbase + 8 * (i >> 2) + (i & 3) >= str_limit) x2[i] = -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
+        return fmaxf(tm, __shfl_xor(tm, 32));
+    };
+    // the coefficients of phase 2 for own fragment h, packed as its B-operand
+    auto weights = [&](int h, const float (&sv)[16], const float (&dv)[16], const float (&Av)[16], const float (&x2)[16]) {
+        float coef[16], coef2[16];
+        if constexpr (MODE == KGE_MODE_FWD) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float e = kge_exp2(x2[i]);                             // masked entries: exp2(-inf) = 0
+                st_l[h] += e;
+                float u = e;
+                if constexpr (LOSS == KGE_LOGSIGMOID) {
+                    // weight * sigma(gamma + s) for the gradient, weight * softplus(gamma + s) for the loss
+                    const float y = a.gamma + sv[i];
+                    const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                    const float rcp = __builtin_amdgcn_rcpf(1.f + t);
+                    const float sig = y >= 0.f ? rcp : t * rcp;
+                    const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + t);
+                    if (e > 0.f) st_acc[h] = fmaf(e, softplus, st_acc[h]);
+                    u = e * sig;
+                }
+                const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                coef[i] = c1;
+                if constexpr (KIND == KGE_KIND_DIST) sum1[h] += c1;  // only the distance scorers' chain rule needs it
+                if constexpr (TRANSH) { coef2[i] = c1 * Av[i]; sum2[h] += coef2[i]; sum3[h] += coef2[i] * Av[i]; }
+            }
+        }
+        if constexpr (MODE == KGE_MODE_GRADT) {
+            // gradient coefficient of every (query, negative) pair from the finished row constants
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
-                float s;
-                dv[i] = 0.f; Av[i] = 0.f;
-                if constexpr (KIND == KGE_KIND_MULT) {
-                    s = acc[h][i];
-                } else {
-                    float qn, cc, wn, tnv;
-                    if constexpr (OWN_ROW) { qn = o_qn[h]; cc = o_c[h]; wn = o_wn[h]; tnv = *(const float *)(side + sl * 4); }
-                    else { float4 ri = *(const float4 *)(side + sl * 16); qn = ri.x; cc = ri.y; wn = ri.w; tnv = o_tn[h]; }
-                    float d2 = fmaf(-2.f, acc[h][i], qn + tnv);
-                    if constexpr (TRANSH) { const float A = accw[i]; Av[i] = A; d2 += A * (2.f * cc - A * (2.f - wn)); }
-                    if (d2 < 1e-3f * (qn + tnv)) {             // cancellation: redo this entry by direct differences
-                        const int sidx = tile * C::ST + sl;
-                        const int b = OWN_ROW ? oidx : sidx, n = OWN_ROW ? sidx : oidx;
-                        const char *qb = (const char *)(OWN_ROW ? a.own : a.str) + (size_t)b * RB;
-                        const char *tb = (const char *)(OWN_ROW ? a.str : a.own) + (size_t)n * RB;
-                        const char *wb = TRANSH ? (const char *)(OWN_ROW ? a.own2 : a.str2) + (size_t)b * RB : nullptr;
-                        d2 = kge_direct_d2<BF16, TRANSH>(qb, tb, wb, C::DP);
-                    }
-                    d2 = fmaxf(d2, 0.f);
-                    const float inv = d2 > 0.f ? __builtin_amdgcn_rsqf(d2) : 0.f;
-                    dv[i] = inv;
-                    s = -d2 * inv;                              // -sqrt(d2)
+                const float K2 = *(const float *)(side + sl * 16 + 8);       // -inf for padded queries
+                float u = kge_exp2(fmaf(sv[i], xscale, K2));
+                if constexpr (LOSS == KGE_LOGSIGMOID) {
+                    const float y = a.gamma + sv[i];
+                    const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                    const float rcp = __builtin_amdgcn_rcpf(1.f + t);
+                    u *= y >= 0.f ? rcp : t * rcp;
                 }
-                sv[i] = s;
+                const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                coef[i] = c1;
+                if constexpr (KIND == KGE_KIND_DIST) sum1[h] += c1;
+                if constexpr (TRANSH) coef2[i] = c1 * Av[i];
             }
-            if constexpr (MODE == KGE_MODE_SCORE) {
-                if (oidx < a.N) {
+        }
+        if constexpr (PHASE2) {
+            if constexpr (BF16) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int b = sbase + 8 * (i >> 2) + (i & 3);
-                        if (b < a.B) a.S_out[(size_t)b * a.N + oidx] = sv[i];
-                    }
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    bf[h][s2] = make_uint4(kge_pack_bf16x2(coef[8 * s2 + 0], coef[8 * s2 + 1]),
+                                           kge_pack_bf16x2(coef[8 * s2 + 2], coef[8 * s2 + 3]),
+                                           kge_pack_bf16x2(coef[8 * s2 + 4], coef[8 * s2 + 5]),
+                                           kge_pack_bf16x2(coef[8 * s2 + 6], coef[8 * s2 + 7]));
+                    if constexpr (TRANSH)
+                        bf2[s2] = make_uint4(kge_pack_bf16x2(coef2[8 * s2 + 0], coef2[8 * s2 + 1]),
+                                             kge_pack_bf16x2(coef2[8 * s2 + 2], coef2[8 * s2 + 3]),
+                                             kge_pack_bf16x2(coef2[8 * s2 + 4], coef2[8 * s2 + 5]),
+                                             kge_pack_bf16x2(coef2[8 * s2 + 6], coef2[8 * s2 + 7]));
                 }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { coefs[i] = coef[i]; if constexpr (TRANSH) coefs2[i] = coef2[i]; }
             }
-        };
-        // FWD: exponents of the softmax weights of own fragment h relative to its reference st_m (log2
-        // domain; entries past the end of the stream operand get -inf: only the last tile has any, the
-        // branch is wave-uniform), and their maximum over the tile.  Lanes l and l^32 hold the two halves
-        // of the same own row and feed ONE contraction in phase 2, so they share the maximum.
-        auto exponents = [&](int h, const float (&sv)[16], float (&x2)[16]) -> float {
-            const float m_neg = st_m[h] > -INFINITY ? -st_m[h] : 0.f;
-            float tm = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
-            if (!tile_full) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (sbase + 8 * (i >> 2) + (i & 3) >= str_limit) x2[i] = -INFINITY;
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
-            return fmaxf(tm, __shfl_xor(tm, 32));
-        };
-        // the coefficients of phase 2 for own fragment h, packed as its B-operand
-        auto weights = [&](int h, const float (&sv)[16], const float (&dv)[16], const float (&Av)[16], const float (&x2)[16]) {
-            float coef[16], coef2[16];
-            if constexpr (MODE == KGE_MODE_FWD) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float e = kge_exp2(x2[i]);                             // masked entries: exp2(-inf) = 0
-                    st_l[h] += e;
-                    float u = e;
-                    if constexpr (LOSS == KGE_LOGSIGMOID) {
-                        // weight * sigma(gamma + s) for the gradient, weight * softplus(gamma + s) for the loss
-                        const float y = a.gamma + sv[i];
-                        const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
-                        const float rcp = __builtin_amdgcn_rcpf(1.f + t);
-                        const float sig = y >= 0.f ? rcp : t * rcp;
-                        const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + t);
-                        if (e > 0.f) st_acc[h] = fmaf(e, softplus, st_acc[h]);
-                        u = e * sig;
-                    }
-                    const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
-                    coef[i] = c1;
-                    if constexpr (KIND == KGE_KIND_DIST) sum1[h] += c1;  // only the distance scorers' chain rule needs it
-                    if constexpr (TRANSH) { coef2[i] = c1 * Av[i]; sum2[h] += coef2[i]; sum3[h] += coef2[i] * Av[i]; }
-                }
-            }
-            if constexpr (MODE == KGE_MODE_GRADT) {
-                // gradient coefficient of every (query, negative) pair from the finished row constants
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
-                    const float K2 = *(const float *)(side + sl * 16 + 8);       // -inf for padded queries
-                    float u = kge_exp2(fmaf(sv[i], xscale, K2));
-                    if constexpr (LOSS == KGE_LOGSIGMOID) {
-                        const float y = a.gamma + sv[i];
-                        const float t = kge_exp2(-fabsf(y) * KGE_LOG2E);
-                        const float rcp = __builtin_amdgcn_rcpf(1.f + t);
-                        u *= y >= 0.f ? rcp : t * rcp;
-                    }
-                    const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
-                    coef[i] = c1;
-                    if constexpr (KIND == KGE_KIND_DIST) sum1[h] += c1;
-                    if constexpr (TRANSH) coef2[i] = c1 * Av[i];
-                }
-            }
-            if constexpr (PHASE2) {
-                if constexpr (BF16) {
-#pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) {
-                        bf[h][s2] = make_uint4(kge_pack_bf16x2(coef[8 * s2 + 0], coef[8 * s2 + 1]),
-                                               kge_pack_bf16x2(coef[8 * s2 + 2], coef[8 * s2 + 3]),
-                                               kge_pack_bf16x2(coef[8 * s2 + 4], coef[8 * s2 + 5]),
-                                               kge_pack_bf16x2(coef[8 * s2 + 6], coef[8 * s2 + 7]));
-                        if constexpr (TRANSH)
-                            bf2[s2] = make_uint4(kge_pack_bf16x2(coef2[8 * s2 + 0], coef2[8 * s2 + 1]),
-                                                 kge_pack_bf16x2(coef2[8 * s2 + 2], coef2[8 * s2 + 3]),
-                                                 kge_pack_bf16x2(coef2[8 * s2 + 4], coef2[8 * s2 + 5]),
-                                                 kge_pack_bf16x2(coef2[8 * s2 + 6], coef2[8 * s2 + 7]));
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) { coefs[i] = coef[i]; if constexpr (TRANSH) coefs2[i] = coef2[i]; }
-                }
-            }
-        };
+        }
+    };
+    // The FWD pass keeps all weights relative to a per-row reference exponent st_m that is only
+    // raised (and what the row has accumulated rescaled) when a tile's maximum exceeds it by more than
+    // KGE_TAU: weights stay below 2^KGE_TAU, and the rescaling is a rarely taken branch of the loop.
+    auto epilogue = [&]() {
 #pragma unroll
         for (int h = 0; h < OW; ++h) {
             float sv[16], dv[16], Av[16], x2[16];
@@ -480,64 +544,36 @@ void kge_block_kernel(const KgeBlockArgs a) {
             }
             weights(h, sv, dv, Av, x2);
         }
-        // ---- phase 2: out^t[d, own] += Xt[d, stream] . coef[stream, own] -----------------------
+    };
+
+    for (int t = t0; t < t1; ++t) {
+        // tile t has landed when at most NSTAGE-2 younger tiles are still in flight; after the
+        // barrier every wave has finished tile t-1, whose stage receives tile t + NSTAGE - 1
+        kge_wait_vmcnt<(C::NSTAGE - 2) * C::LPW>();
+        __syncthreads();
+        issue(t + C::NSTAGE - 1, t - t0 + C::NSTAGE - 1);
+        set_tile(t);
+        // The fragments of a chunk are requested before its first MFMA (the whole phase where the registers
+        // allow it).  Deeper software pipelining of the reads, enforced with scheduling barriers, was
+        // measured and did not pay: inside a chunk the order is left to the compiler.
+        zero1();
+        constexpr int CH1 = OW > 1 ? 1 : (NG1 > 4 ? 4 : NG1);   // groups per chunk: at most 64 (16) registers in flight
+#pragma unroll
+        for (int c0 = 0; c0 < NG1; c0 += CH1) {
+#pragma unroll
+            for (int gq = c0; gq < c0 + CH1; ++gq) ld1(base, gq);
+#pragma unroll
+            for (int gq = c0; gq < c0 + CH1; ++gq) mma1(gq);
+        }
+        epilogue();
         if constexpr (PHASE2) {
-            const char *xt = base + C::X_BYTES * C::NX;
-            if constexpr (BF16) {
-                // The transposed operand keeps, inside every group of 16 stream entries, the 8 entries of one
-                // lane half contiguous (the producer swaps bits 2 and 3 of the column), so the A-fragment of
-                // (block, s2) is ONE 16-byte chunk: chunk 2*s2 + g of row dcol, at its swizzled slot.
-                constexpr int BG = OW > 1 ? 4 : C::NBH;    // blocks whose fragments are requested together
+            constexpr int CH2 = OW > 1 ? 1 : NG2;
 #pragma unroll
-                for (int b0 = 0; b0 < C::NBH; b0 += BG) {
-                    uint4 av2[BG][2], aw2[(TRANSH && !OWN_ROW) ? BG : 1][2];
+            for (int c0 = 0; c0 < NG2; c0 += CH2) {
 #pragma unroll
-                    for (int bb = 0; bb < BG; ++bb) {
-                        const int row = (dblk0 + b0 + bb) * 32 + lr;
+                for (int gq = c0; gq < c0 + CH2; ++gq) ld2(base, gq);
 #pragma unroll
-                        for (int s2 = 0; s2 < 2; ++s2) {
-                            const int sslot = (((row & 1) << 2) | (2 * s2 + g)) ^ ((row >> 1) & 7);
-                            const char *p = xt + (row >> 1) * 128 + sslot * 16;
-                            av2[bb][s2] = *(const uint4 *)p;
-                            if constexpr (TRANSH && !OWN_ROW) aw2[bb][s2] = *(const uint4 *)(p + C::XT_BYTES);
-                        }
-                    }
-#pragma unroll
-                    for (int bb = 0; bb < BG; ++bb) {
-                        const int blk = b0 + bb;
-#pragma unroll
-                        for (int s2 = 0; s2 < 2; ++s2) {
-#pragma unroll
-                            for (int h = 0; h < OW; ++h) acc2[h][blk] = kge_mma16<true>(acc2[h][blk], av2[bb][s2], bf[h][s2]);
-                            if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma16<true>(acc2b[blk], av2[bb][s2], bf2[s2]);
-                            if constexpr (TRANSH && !OWN_ROW) acc2[0][blk] = kge_mma16<true>(acc2[0][blk], aw2[bb][s2], bf2[s2]);
-                        }
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int blk = 0; blk < C::NBH; ++blk) {
-                    const int row = (dblk0 + blk) * 32 + lr;
-                    const char *p = xt + row * 128;
-                    kge_f32x4 av[4], av2[(TRANSH && !OWN_ROW) ? 4 : 1];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int off = ((2 * j + g) ^ (row & 7)) * 16;
-                        av[j] = *(const kge_f32x4 *)(p + off);
-                        if constexpr (TRANSH && !OWN_ROW) av2[j] = *(const kge_f32x4 *)(p + C::XT_BYTES + off);
-                    }
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            acc2[0][blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coefs[4 * j + r], acc2[0][blk], 0, 0, 0);
-                            if constexpr (TRANSH && OWN_ROW)
-                                acc2b[blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j][r], coefs2[4 * j + r], acc2b[blk], 0, 0, 0);
-                            if constexpr (TRANSH && !OWN_ROW)
-                                acc2[0][blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(av2[j][r], coefs2[4 * j + r], acc2[0][blk], 0, 0, 0);
-                        }
-                    }
-                }
+                for (int gq = c0; gq < c0 + CH2; ++gq) mma2(gq);
             }
         }
     }

@@ -20,10 +20,11 @@ struct Geometry {
     bool bf16, transh;
     int es, rb, dp, kind;
     int B, N, Bp, Np;
-    int own_tiles_b, own_tiles_n;       // own tiles of the FWD pass (queries) and of the SCORE / GRADT passes (negatives)
+    int own_tiles_b, own_tiles_n, own_tiles_s;   // own tiles of the FWD pass (queries), the GRADT and the SCORE pass (negatives)
     int str_tiles_b, str_tiles_n;       // 32-row tiles
     int nsplit_q, tps_q;                // row-owner launches: splits over the negatives
-    int nsplit_t, tps_t;                // column-owner launches: splits over the queries
+    int nsplit_t, tps_t;                // GRADT launches: splits over the queries
+    int nsplit_s, tps_s;                // SCORE launches: splits over the queries
     int dsplit_q, dsplit_t;
 };
 
@@ -56,9 +57,9 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.kind = (m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
     g.B = (int)B; g.N = (int)N;
     g.Bp = (int)kge_round_up(B, KGE_PAD); g.Np = (int)kge_round_up(N, KGE_PAD);
-    // (SCORE and GRADT own the negatives with the same number of fragments per wave)
     g.own_tiles_b = g.Bp / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_FWD, g.kind));
     g.own_tiles_n = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_GRADT, g.kind));
+    g.own_tiles_s = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_SCORE, g.kind));
     g.str_tiles_b = g.Bp / KGE_STREAM_TILE; g.str_tiles_n = g.Np / KGE_STREAM_TILE;
     auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps) {
         if (own_tiles == 0 || str_tiles == 0) { nsplit = 0; tps = 0; return; }
@@ -70,6 +71,7 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     };
     split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q);
     split(g.own_tiles_n, g.str_tiles_b, g.nsplit_t, g.tps_t);
+    split(g.own_tiles_s, g.str_tiles_b, g.nsplit_s, g.tps_s);
     g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
     g.dsplit_t = (g.bf16 && g.rb == 1024) ? 2 : 1;
     return g;
@@ -207,9 +209,9 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     if (rc != KGE_OK) return rc;
     KgeBlockArgs a{};
     a.own = b.T; a.str = b.Q; a.str2 = b.W; a.rowinfo = b.rowinfo; a.tn = b.tn;
-    a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_b; a.tiles_per_split = g.tps_t;
+    a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_b; a.tiles_per_split = g.tps_s;
     a.kind = g.kind; a.S_out = neg_out; a.own_pad = g.Np;
-    return launch_block(g, KGE_MODE_SCORE, 0, a, g.own_tiles_n, g.nsplit_t, 1, st);
+    return launch_block(g, KGE_MODE_SCORE, 0, a, g.own_tiles_s, g.nsplit_s, 1, st);
 }
 
 int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,

@@ -35,12 +35,13 @@ enum { KGE_KIND_MULT = 0, KGE_KIND_DIST = 1 };
 
 // 32-row fragments of its operand that each of a workgroup's four waves owns (the workgroup owns
 // 128 times this many rows).  Two where the registers allow it: every fragment read from the LDS then
-// feeds two MFMAs, which halves the LDS traffic per flop - the limit of the bf16 kernels.  Not with
-// the TransH operands, and not in the FWD pass, whose gradient accumulators for two fragments of 256
-// dimensions would take the whole accumulator file and more.
+// feeds two MFMAs, which halves the LDS traffic per flop.  Not with the TransH operands; not in the
+// FWD pass, whose gradient accumulators for two fragments of 256 dimensions would take the whole
+// accumulator file and more; not in the GRADT pass of the distance scorers, whose epilogue needs
+// the registers.
 constexpr int kge_block_ow(bool bf16, int rb, bool transh, int mode, int kind) {
-    (void)kind;
-    return (bf16 && rb == 512 && !transh && mode != KGE_MODE_FWD) ? 2 : 1;
+    if (!bf16 || rb != 512 || transh || mode == KGE_MODE_FWD) return 1;
+    return (mode == KGE_MODE_GRADT && kind == KGE_KIND_DIST) ? 1 : 2;
 }
 
 // Per-row side information of the queries: squared norm of q, c = w.q (TransH), the per-row
