@@ -392,32 +392,48 @@ void kge_block_kernel(const KgeBlockArgs a) {
     auto scores = [&](int h, float (&sv)[16], float (&dv)[16], float (&Av)[16]) {
         const int oidx = oidx0 + 32 * h;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
-            float s;
-            dv[i] = 0.f; Av[i] = 0.f;
-            if constexpr (KIND == KGE_KIND_MULT) {
-                s = acc[h][i];
-            } else {
+        for (int i = 0; i < 16; ++i) { dv[i] = 0.f; Av[i] = 0.f; }
+        if constexpr (KIND == KGE_KIND_MULT) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sv[i] = acc[h][i];
+        } else {
+            // squared distance by the norm expansion |q|^2 + |t|^2 - 2 q.t (TransH: plus the terms of the
+            // projection); entries where it cancels (below 1e-3 of the norms) are redone by direct
+            // differences in a rarely taken branch
+            float d2[16], thr[16];
+            bool cancel = false;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
                 float qn, cc, wn, tnv;
                 if constexpr (OWN_ROW) { qn = o_qn[h]; cc = o_c[h]; wn = o_wn[h]; tnv = *(const float *)(side + sl * 4); }
                 else { float4 ri = *(const float4 *)(side + sl * 16); qn = ri.x; cc = ri.y; wn = ri.w; tnv = o_tn[h]; }
-                float d2 = fmaf(-2.f, acc[h][i], qn + tnv);
-                if constexpr (TRANSH) { const float A = accw[i]; Av[i] = A; d2 += A * (2.f * cc - A * (2.f - wn)); }
-                if (d2 < 1e-3f * (qn + tnv)) {             // cancellation: redo this entry by direct differences
-                    const int sidx = tile * C::ST + sl;
-                    const int b = OWN_ROW ? oidx : sidx, n = OWN_ROW ? sidx : oidx;
-                    const char *qb = (const char *)(OWN_ROW ? a.own : a.str) + (size_t)b * RB;
-                    const char *tb = (const char *)(OWN_ROW ? a.str : a.own) + (size_t)n * RB;
-                    const char *wb = TRANSH ? (const char *)(OWN_ROW ? a.own2 : a.str2) + (size_t)b * RB : nullptr;
-                    d2 = kge_direct_d2<BF16, TRANSH>(qb, tb, wb, C::DP);
-                }
-                d2 = fmaxf(d2, 0.f);
-                const float inv = d2 > 0.f ? __builtin_amdgcn_rsqf(d2) : 0.f;
-                dv[i] = inv;
-                s = -d2 * inv;                              // -sqrt(d2)
+                d2[i] = fmaf(-2.f, acc[h][i], qn + tnv);
+                if constexpr (TRANSH) { const float A = accw[i]; Av[i] = A; d2[i] += A * (2.f * cc - A * (2.f - wn)); }
+                thr[i] = 1e-3f * (qn + tnv);
+                cancel = cancel || d2[i] < thr[i];
             }
-            sv[i] = s;
+            if (__any(cancel)) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    if (d2[i] < thr[i]) {
+                        const int sidx = tile * C::ST + 8 * (i >> 2) + 4 * g + (i & 3);
+                        const int b = OWN_ROW ? oidx : sidx, n = OWN_ROW ? sidx : oidx;
+                        const char *qb = (const char *)(OWN_ROW ? a.own : a.str) + (size_t)b * RB;
+                        const char *tb = (const char *)(OWN_ROW ? a.str : a.own) + (size_t)n * RB;
+                        const char *wb = TRANSH ? (const char *)(OWN_ROW ? a.own2 : a.str2) + (size_t)b * RB : nullptr;
+                        d2[i] = kge_direct_d2<BF16, TRANSH>(qb, tb, wb, C::DP);
+                    }
+                    asm volatile("" ::: "memory");          // keeps the branch from being turned into selects
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float dd = fmaxf(d2[i], 0.f);
+                const float inv = dd > 0.f ? __builtin_amdgcn_rsqf(dd) : 0.f;
+                dv[i] = inv;
+                sv[i] = -dd * inv;                          // -sqrt(d2)
+            }
         }
         if constexpr (MODE == KGE_MODE_SCORE) {
             if (oidx < a.N) {
