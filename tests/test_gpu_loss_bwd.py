@@ -89,3 +89,18 @@ def test_repeated_calls_are_bitwise_identical(orc):
     b = kge.loss_bwd(model, "sampled_softmax", *args, n_ent_for_c=4000)
     for k in a:
         assert bool((a[k] == b[k]).all()), k
+
+
+@pytest.mark.parametrize("scorer,loss", [("distmult", "sampled_softmax"), ("complex", "logsigmoid"),
+                                         ("transe", "logsigmoid")])
+def test_wide_score_range_raises_the_reference_repeatedly(orc, scorer, loss):
+    """Scores spread over tens of nats and negatives ordered by ascending score of the first query:
+    the running reference exponent of the softmax weights is raised many times along the stream."""
+    amp = 1.2 if scorer != "transe" else 2.5
+    G = make_case(scorer, 3000, 7, 64, 130, 700, False, amp=amp)
+    s0 = orc.score_batch(scorer, G["ent"], G["rel"], G["relw"], G["h"][:1], G["r"][:1], G["t"][:1], G["neg"])[1][0]
+    a_t = 3.0 if scorer == "transe" else 1.0               # the weights' exponents are adv_temp * score
+    assert (s0.max() - s0.min()) * a_t * 1.4427 > 20.0     # log2 units: several times the kernel's headroom of 8
+    G["neg"] = G["neg"][np.argsort(s0, kind="stable")]
+    kw = dict(n_ent_for_c=3000) if loss == "sampled_softmax" else dict(gamma=1.0, adv_temp=a_t)
+    _compare(orc, scorer, loss, G, False, 3000, kw=kw)
