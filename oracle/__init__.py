@@ -40,6 +40,7 @@ def lib():
         _lib.orc_score_one.restype = C.c_double
         _lib.orc_loss_one.restype = C.c_double
         _lib.orc_loss_bwd.restype = C.c_double
+        _lib.orc_l3_norm.restype = C.c_double
         _lib.orc_bf16_rne.restype = C.c_uint16
     return _lib
 
@@ -130,8 +131,16 @@ def loss_one(loss, gamma, adv_temp, n_ent_for_c, fp, s):
     return float(L), float(dfp.value), ds
 
 
+def l3_norm(x, lam=0.0):
+    """(||x||_3, lam * gradient) of one embedding row (Section 3.1 "Regularisation")."""
+    x = _f32(x)
+    g = np.zeros(x.shape[0], dtype=np.float64)
+    n = lib().orc_l3_norm(C.c_int(x.shape[0]), _p(x, C.c_float), C.c_double(lam), _p(g, C.c_double))
+    return float(n), g
+
+
 def loss_bwd(scorer, loss, ent, rel, relw, h, r, t, neg, gamma=0.0, adv_temp=0.0,
-             loss_scale=None, n_ent_for_c=0, want_grads=True):
+             loss_scale=None, n_ent_for_c=0, want_grads=True, reg_l3=0.0):
     ent, rel, relw = _f32(ent), _f32(rel), _f32(relw)
     h, r, t, neg = _i32(h), _i32(r), _i32(t), _i32(neg)
     B, N, d = h.shape[0], neg.shape[0], ent.shape[1]
@@ -146,7 +155,7 @@ def loss_bwd(scorer, loss, ent, rel, relw, h, r, t, neg, gamma=0.0, adv_temp=0.0
                            _p(rel, C.c_float), _p(relw, C.c_float), _p(h, C.c_int32),
                            _p(r, C.c_int32), _p(t, C.c_int32), C.c_int64(B), _p(neg, C.c_int32),
                            C.c_int64(N), C.c_double(gamma), C.c_double(adv_temp),
-                           C.c_double(loss_scale), C.c_int64(n_ent_for_c), _p(g_ent, C.c_double),
+                           C.c_double(loss_scale), C.c_int64(n_ent_for_c), C.c_double(reg_l3), _p(g_ent, C.c_double),
                            _p(g_rel, C.c_double), _p(g_relw, C.c_double), _p(per, C.c_double))
     return {"loss": float(L), "g_ent": g_ent, "g_rel": g_rel, "g_relw": g_relw,
             "g_ent_idx": np.concatenate([h, t, neg]).astype(np.int32), "g_rel_idx": r.copy(),

@@ -389,10 +389,29 @@ double orc_loss_one(int loss, double gamma, double adv_temp, int64_t n_ent_for_c
  *   g_ent  [(2B+N) * d] : heads (slots 0..B), positive tails (B..2B), shared negatives (2B..2B+N)
  *   g_rel  [B * k], g_relw [B * d] (TransH only)
  */
+/* L3 norm of one embedding row, (sum_j |x_j|^3)^(1/3) (Section 3.1 "Regularisation": the norm itself,
+   not its cube), and, when g is given, lambda * its gradient added to g:
+   d||x||_3 / dx_j = sign(x_j) x_j^2 / ||x||_3^2, taken as 0 at x = 0. */
+double orc_l3_norm(int d, const float *x, double lambda, double *g)
+{
+    double s = 0.0;
+    for (int j = 0; j < d; ++j) { double a = fabs((double)x[j]); s += a * a * a; }
+    double nrm = cbrt(s);
+    if (g && nrm > 0.0)
+        for (int j = 0; j < d; ++j) {
+            double v = (double)x[j];
+            g[j] += lambda * (v < 0.0 ? -1.0 : 1.0) * v * v / (nrm * nrm);
+        }
+    return nrm;
+}
+
+/* Micro-batch loss loss_scale * sum_b L_b + reg_l3 * Omega_S with
+   Omega_S = sum_b (||h_b||_3 + ||t_b||_3) + sum_i ||t'_i||_3 over the gathered shallow embeddings
+   (Section 3.1 "Regularisation"; without text features Omega_T = Omega_S and Omega_F = 0). */
 double orc_loss_bwd(int scorer, int loss, int d, const float *ent, const float *rel,
                     const float *relw, const int32_t *h, const int32_t *r, const int32_t *t,
                     int64_t B, const int32_t *neg, int64_t N, double gamma, double adv_temp,
-                    double loss_scale, int64_t n_ent_for_c, double *g_ent, double *g_rel,
+                    double loss_scale, int64_t n_ent_for_c, double reg_l3, double *g_ent, double *g_rel,
                     double *g_relw, double *per_triple_loss)
 {
     int k = orc_rel_dim(scorer, d);
@@ -458,7 +477,17 @@ double orc_loss_bwd(int scorer, int loss, int d, const float *ent, const float *
         }
     }
     free(Lb); free(G); free(Gp);
-    return loss_scale * total;
+    double omega = 0.0;
+    if (reg_l3 != 0.0) {
+        /* one term per gathered slot, in slot order: heads, positive tails, shared negatives */
+        for (int64_t b = 0; b < B; ++b)
+            omega += orc_l3_norm(d, ent + (int64_t)h[b] * d, reg_l3, g_ent ? g_ent + b * d : NULL);
+        for (int64_t b = 0; b < B; ++b)
+            omega += orc_l3_norm(d, ent + (int64_t)t[b] * d, reg_l3, g_ent ? g_ent + (B + b) * d : NULL);
+        for (int64_t n = 0; n < N; ++n)
+            omega += orc_l3_norm(d, ent + (int64_t)neg[n] * d, reg_l3, g_ent ? g_ent + (2 * B + n) * d : NULL);
+    }
+    return loss_scale * total + reg_l3 * omega;
 }
 
 /* ------------------------------------------------------------------------------------------ */
