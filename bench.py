@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--scorer", default=None, help="restrict to one scorer (training workloads: replaces the configured one)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the entity table (debugging only)")
+    ap.add_argument("--reg-l3", type=float, default=0.0,
+                    help="training workloads: weight of the L3 regulariser of the gathered rows (default off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy first (reference for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -45,7 +47,7 @@ def parse():
 class TrainWorkload:
     """c3 / c5 / c1: forward + backward + sparse Adam on bf16 shadow / fp32 master tables."""
 
-    def __init__(self, name, P, scale, only=None):
+    def __init__(self, name, P, scale, only=None, reg_l3=0.0):
         import torch
         import kge_synth as ks
         import kge_synth.device as ksd
@@ -114,6 +116,8 @@ class TrainWorkload:
         self.loss_kw = dict(gamma=P.get("gamma", 0.0), adv_temp=P.get("adv_temp", 0.0))
         if P["loss"] == "sampled_softmax":
             self.loss_kw = dict(n_ent_for_c=self.n_ent)
+        if reg_l3 > 0.0:
+            self.loss_kw["reg_l3"] = reg_l3
         torch.cuda.synchronize()
         self.setup_s = time.time() - t0
 
@@ -142,7 +146,7 @@ class TrainWorkload:
         return self.B * (self.N + 1)
 
     def extra(self, ms):
-        return {"triples_per_s": self.B / (ms * 1e-3), "scorer": self.scorer}
+        return {"triples_per_s": self.B / (ms * 1e-3), "scorer": self.scorer, "reg_l3": self.loss_kw.get("reg_l3", 0.0)}
 
     def mfma_flops(self, slot):
         # algorithmic contractions of 2 B N d flop each: the FWD pass computes the scores AND the queries'
@@ -305,7 +309,7 @@ def main():
     kge.load()
     P = ks.PRESETS[a.workload]
     if a.workload in ("c1", "c3", "c5"):
-        wl = TrainWorkload(a.workload, P, a.scale, a.scorer)
+        wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3)
     elif a.workload == "c2":
         wl = ScoreWorkload(P, a.scale, a.scorer)
     else:

@@ -75,6 +75,10 @@ typedef struct {
     float adv_temp;        /* a >= 0, temperature of the self-adversarial weights (StopGrad) */
     float loss_scale;      /* the micro-batch loss is loss_scale * sum_b L_b; <= 0 selects 1/B */
     int64_t n_ent_for_c;   /* |E| in the sampled-softmax correction c = log((|E|-1)/N) */
+    float reg_l3;          /* lambda_S >= 0 of Section 3.1 "Regularisation": reg_l3 * Omega_S is added to the
+                              loss (NOT scaled by loss_scale), Omega_S = sum over the 2B+N gathered entity slots
+                              of the L3 norm (sum_j |x_j|^3)^(1/3) of the slot's embedding row; 0 = off */
+    int32_t reserved;      /* 0 */
 } kge_loss_cfg_t;
 
 typedef struct {
@@ -109,7 +113,7 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
 /*
  * Forward + backward of one micro-batch (losses of Section 3.1; the shared negative block is
  * never written to memory):
- *   loss_out      float[1]           loss_scale * sum_b L_b
+ *   loss_out      float[1]           loss_scale * sum_b L_b + reg_l3 * Omega_S
  *   g_ent         float[(2B+N) * d]  gradient rows, one per gathered entity slot, in the order
  *                                    heads (B), positive tails (B), shared negatives (N);
  *                                    duplicates are NOT merged (kge_sparse_adam does that)

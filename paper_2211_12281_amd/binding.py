@@ -31,7 +31,7 @@ class KgeModelT(C.Structure):
 
 class KgeLossCfgT(C.Structure):
     _fields_ = [("loss", C.c_int32), ("gamma", C.c_float), ("adv_temp", C.c_float), ("loss_scale", C.c_float),
-                ("n_ent_for_c", C.c_int64)]
+                ("n_ent_for_c", C.c_int64), ("reg_l3", C.c_float), ("reserved", C.c_int32)]
 
 
 class KgeAdamCfgT(C.Structure):
@@ -164,7 +164,8 @@ def score(model: Model, h, r, t, neg, want_neg: bool = True, ws: Workspace | Non
 
 
 def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp: float = 0.0,
-             loss_scale: float = 0.0, n_ent_for_c: int = 0, ws: Workspace | None = None, out=None):
+             loss_scale: float = 0.0, n_ent_for_c: int = 0, ws: Workspace | None = None, out=None,
+             reg_l3: float = 0.0):
     B, N, d = h.numel(), neg.numel(), model.dim
     k = model.rel.shape[1]
     if out is None:
@@ -176,7 +177,7 @@ def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp
             "g_relw": torch.empty((B, d), dtype=torch.float32, device="cuda") if model.relw is not None else None,
             "g_rel_idx": torch.empty(B, dtype=torch.int32, device="cuda"),
         }
-    cfg = KgeLossCfgT(LOSSES[loss], gamma, adv_temp, loss_scale, n_ent_for_c)
+    cfg = KgeLossCfgT(LOSSES[loss], gamma, adv_temp, loss_scale, n_ent_for_c, reg_l3, 0)
     ws = ws or _default_ws
     buf = ws.get(workspace_bytes(OP_LOSS_BWD, model, B, N))
     _check(load().kge_loss_bwd(model.ref, C.byref(cfg), _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B,

@@ -93,6 +93,7 @@ struct Buffers {
     void *Q, *W, *Q2, *T, *Qt, *Wt, *Tt;
     KgeRowInfo *rowinfo; float *tn, *pos, *lossb, *gpos;
     float4 *stat_part; float *accq, *accq2; float4 *sumq; float *acct; float4 *sumt;
+    float *regv;                       // L3 norms of the gathered slots: [Bp heads][Bp tails][Np negatives]
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -105,7 +106,7 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
     b.tn = c.take<float>(g.Np);
     b.pos = c.take<float>(g.Bp);
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
-    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr;
+    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr;
     if (bwd) {
         b.Q2 = g.transh ? c.take<char>(rowsB * es) : nullptr;
         b.Qt = c.take<char>(rowsB * es);
@@ -119,6 +120,7 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
         b.sumq = c.take<float4>((size_t)g.nsplit_q * g.Bp);
         b.acct = c.take<float>((size_t)g.nsplit_t * rowsN);
         b.sumt = c.take<float4>((size_t)g.nsplit_t * g.Np);
+        b.regv = c.take<float>((size_t)2 * g.Bp + g.Np);
     }
     return c.off + 256;
 }
@@ -222,7 +224,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     if (rc != KGE_OK) return rc;
     if (!cfg || (cfg->loss != KGE_LOGSIGMOID && cfg->loss != KGE_SAMPLED_SOFTMAX)) return KGE_E_INVALID_ARG;
     if (B < 0 || N < 0 || B >= (1ll << 30) || N >= (1ll << 30)) return KGE_E_INVALID_ARG;
-    if (!(cfg->adv_temp >= 0.f)) return KGE_E_INVALID_ARG;
+    if (!(cfg->adv_temp >= 0.f) || !(cfg->reg_l3 >= 0.f)) return KGE_E_INVALID_ARG;
     if (cfg->loss == KGE_SAMPLED_SOFTMAX && N > 0 && cfg->n_ent_for_c < 2) return KGE_E_INVALID_ARG;
     if (!loss_out) return KGE_E_INVALID_ARG;
     if (B > 0 && (!h || !r || !t || !g_ent || !g_ent_idx || !g_rel || !g_rel_idx)) return KGE_E_INVALID_ARG;
@@ -267,13 +269,15 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         if ((rc = launch_block(g, KGE_MODE_GRADT, cfg->loss, c, g.own_tiles_n, g.nsplit_t, g.dsplit_t, st)) != KGE_OK) return rc;
     }
     if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, have_block ? g.nsplit_q : 0, b.gpos,
-                            g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, st)) != KGE_OK) return rc;
+                            g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, cfg->reg_l3, b.regv, st)) != KGE_OK) return rc;
     if (N > 0) {
         // with B == 0 there are no partials: nsplit 0 writes zero rows
         rc = kge_run_tfinish(b.acct, b.sumt, have_block ? g.nsplit_t : 0, g.Np, g.N, g.dp, model->dim,
                              have_block && g.kind == KGE_KIND_DIST, b.T, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
-                             g_ent_idx + 2 * B, st);
+                             g_ent_idx + 2 * B, model->ent, model->ent_ld, cfg->reg_l3, b.regv + (size_t)2 * g.Bp, st);
+        if (rc != KGE_OK) return rc;
     }
+    if (cfg->reg_l3 > 0.f && B + N > 0) rc = kge_run_reg_add(b.regv, g.B, g.Bp, g.N, cfg->reg_l3, loss_out, st);
     return rc;
 }
 

@@ -23,7 +23,9 @@ int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N,
 int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
                   const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
                   const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
-                  float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, hipStream_t st);
+                  float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv, hipStream_t st);
 int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N, int dp, int d,
                     int dist_kind, const void *T, bool bf16, const int32_t *neg, float *g_neg, int32_t *g_neg_idx,
-                    hipStream_t st);
+                    const void *ent, int64_t ent_ld, float reg, float *regn, hipStream_t st);
+// loss_out += reg * (sum of regv over the 2B + N gathered slots), laid out [Bp heads][Bp tails][N negatives]
+int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st);

@@ -204,7 +204,8 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
                                  int Bp, int dp, const float *acc_part, const float *acc_part2,
                                  const float4 *sum_part, const float4 *stat_part, const KgeRowInfo *rowinfo,
                                  int nsplit, const float *gpos, float *g_ent,
-                                 float *g_rel, float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx) {
+                                 float *g_rel, float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg,
+                                 float *regv) {
     const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (b >= B) return;
@@ -338,25 +339,68 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         }
     }
     if (lane == 0) { g_ent_idx[b] = h[b]; g_ent_idx[B + b] = t[b]; g_rel_idx[b] = r[b]; }
+    if (reg > 0.f) {
+        // L3 regulariser of the head and tail rows (Section 3.1, Regularisation): reg * ||x||_3 joins the loss,
+        // reg * sign(x_j) x_j^2 / ||x||_3^2 the gradient of the slot (every lane re-reads what it wrote above)
+        float ch = 0.f, ct = 0.f;
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) { ch += fabsf(cx.h[k]) * cx.h[k] * cx.h[k]; ct += fabsf(tv[k]) * tv[k] * tv[k]; }
+        const float nh = cbrtf(kge_wave_sum(ch)), nt = cbrtf(kge_wave_sum(ct));
+        const float fh = nh > 0.f ? reg / (nh * nh) : 0.f, ft = nt > 0.f ? reg / (nt * nt) : 0.f;
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) {
+            const int j = lane + 64 * k;
+            if (j >= d) continue;
+            gh[j] += fh * fabsf(cx.h[k]) * cx.h[k];
+            gt[j] += ft * fabsf(tv[k]) * tv[k];
+        }
+        if (lane == 0) { regv[b] = nh; regv[Bp + b] = nt; }
+    }
 }
 
-// gradient rows of the shared negatives: sum of the split partials minus colsum * t (distances)
+// gradient rows of the shared negatives: sum of the split partials minus colsum * t (distances), plus
+// the L3 regulariser of the row (read from the table itself, so it is there without a scored block)
 template <bool BF16>
 __global__ void kge_tfinish_kernel(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N,
                                    int dp, int d, int dist_kind, const void *T, const int32_t *neg,
-                                   float *g_neg, int32_t *g_neg_idx) {
+                                   float *g_neg, int32_t *g_neg_idx, const void *ent, int64_t ent_ld, float reg,
+                                   float *regn) {
     const int lane = threadIdx.x & 63;
     const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (n >= N) return;
     float cs = 0.f;
     for (int s = 0; s < nsplit; ++s) cs += sumT_part[(size_t)s * Np + n].x;
+    float nrm = 0.f, f = 0.f;
+    if (reg > 0.f) {
+        float c3 = 0.f;
+        for (int j = lane; j < d; j += 64) { const float x = El<BF16>::ld(ent, (int64_t)neg[n] * ent_ld + j); c3 += fabsf(x) * x * x; }
+        nrm = cbrtf(kge_wave_sum(c3));
+        f = nrm > 0.f ? reg / (nrm * nrm) : 0.f;
+        if (lane == 0) regn[n] = nrm;
+    }
     for (int j = lane; j < d; j += 64) {
         float v = 0.f;
         for (int s = 0; s < nsplit; ++s) v += accT_part[((size_t)s * Np + n) * dp + j];
         if (dist_kind) v -= cs * El<BF16>::ld(T, (int64_t)n * dp + j);
+        if (reg > 0.f) { const float x = El<BF16>::ld(ent, (int64_t)neg[n] * ent_ld + j); v += f * fabsf(x) * x; }
         g_neg[(int64_t)n * d + j] = v;
     }
     if (lane == 0) g_neg_idx[n] = neg[n];
+}
+
+// loss += reg * (sum of the L3 norms of the 2B + N gathered slots): one workgroup, fixed summation tree
+__global__ void kge_reg_add_kernel(const float *regv, int B, int Bp, int N, float reg, float *loss_out) {
+    __shared__ double sh[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < B; i += 256) s += (double)regv[i] + (double)regv[Bp + i];
+    for (int i = threadIdx.x; i < N; i += 256) s += (double)regv[2 * (size_t)Bp + i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss_out = (float)((double)*loss_out + (double)reg * sh[0]);
 }
 
 __global__ void kge_zero_rows_kernel(float *p, int64_t count) {
@@ -406,20 +450,25 @@ int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N,
 int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
                   const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
                   const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
-                  float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, hipStream_t st) {
+                  float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv, hipStream_t st) {
     if (B == 0) return KGE_OK;
     const int grid = (B + 3) / 4;
-    if (m.bf16) hipLaunchKernelGGL(kge_chain_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
-    else        hipLaunchKernelGGL(kge_chain_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx);
+    if (m.bf16) hipLaunchKernelGGL(kge_chain_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv);
+    else        hipLaunchKernelGGL(kge_chain_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv);
     return kge_launch_status();
 }
 
 int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N, int dp, int d,
                     int dist_kind, const void *T, bool bf16, const int32_t *neg, float *g_neg, int32_t *g_neg_idx,
-                    hipStream_t st) {
+                    const void *ent, int64_t ent_ld, float reg, float *regn, hipStream_t st) {
     if (N == 0) return KGE_OK;
     const int grid = (N + 3) / 4;
-    if (bf16) hipLaunchKernelGGL(kge_tfinish_kernel<true>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx);
-    else      hipLaunchKernelGGL(kge_tfinish_kernel<false>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx);
+    if (bf16) hipLaunchKernelGGL(kge_tfinish_kernel<true>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, ent, ent_ld, reg, regn);
+    else      hipLaunchKernelGGL(kge_tfinish_kernel<false>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, ent, ent_ld, reg, regn);
+    return kge_launch_status();
+}
+
+int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st) {
+    hipLaunchKernelGGL(kge_reg_add_kernel, dim3(1), dim3(256), 0, st, regv, B, Bp, N, reg, loss_out);
     return kge_launch_status();
 }

@@ -104,3 +104,25 @@ def test_wide_score_range_raises_the_reference_repeatedly(orc, scorer, loss):
     G["neg"] = G["neg"][np.argsort(s0, kind="stable")]
     kw = dict(n_ent_for_c=3000) if loss == "sampled_softmax" else dict(gamma=1.0, adv_temp=a_t)
     _compare(orc, scorer, loss, G, False, 3000, kw=kw)
+
+
+@pytest.mark.parametrize("scorer", SCORERS)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_l3_regulariser_matches_oracle(orc, scorer, bf16):
+    """lambda_S * Omega_S over the 2B + N gathered rows joins loss and gradients (Section 3.1, Regularisation)."""
+    loss = "sampled_softmax" if scorer in ("distmult", "complex") else "logsigmoid"
+    G = make_case(scorer, 2000, 9, 64, 150, 300, bf16, amp=0.4, zipf=True)
+    kw = dict(_kw(scorer, loss, 2000), reg_l3=0.03)
+    errs = _compare(orc, scorer, loss, G, bf16, 2000, kw=kw)
+    # the regulariser is a visible part of what is compared: without it the same call differs
+    plain = orc.loss_bwd(scorer, loss, G["ent"], G["rel"], G["relw"], G["h"], G["r"], G["t"], G["neg"],
+                         **_kw(scorer, loss, 2000))
+    reg = orc.loss_bwd(scorer, loss, G["ent"], G["rel"], G["relw"], G["h"], G["r"], G["t"], G["neg"], **kw)
+    assert norm_err(plain["g_ent"], reg["g_ent"]) > 10 * (RTOL_BF16 if bf16 else RTOL_F32), errs
+
+
+def test_l3_regulariser_edge_shapes(orc):
+    for B, N in ((0, 40), (33, 0), (1, 1)):
+        G = make_case("transe", 500, 4, 32, B, N, False, amp=0.3)
+        _compare(orc, "transe", "logsigmoid", G, False, 500, kw=dict(gamma=2.0, adv_temp=0.5, reg_l3=0.1),
+                 loss_scale=0.5)
