@@ -41,6 +41,7 @@ def lib():
         _lib.orc_loss_one.restype = C.c_double
         _lib.orc_loss_bwd.restype = C.c_double
         _lib.orc_l3_norm.restype = C.c_double
+        _lib.orc_cbrt_weight.restype = C.c_uint64
         _lib.orc_bf16_rne.restype = C.c_uint16
     return _lib
 
@@ -209,3 +210,38 @@ def bucket_triples(h, t, part_size, D, want_order=True):
                              C.c_int64(part_size), C.c_int(D), _p(counts, C.c_int64),
                              _p(offsets, C.c_int64), _p(order, C.c_int64))
     return counts, offsets, order
+
+
+def cbrt_weight(n: int) -> int:
+    """floor(2^20 * n^(1/3)): the integer weight of a relation with n triples in a bucket."""
+    return int(lib().orc_cbrt_weight(C.c_uint64(n)))
+
+
+def sampler_build(h, r, t, part_size, D, n_rel):
+    """(order, rel_offsets, cdf) of the relation-aware sampler (Section 4, "Training")."""
+    h, r, t = _i32(h), _i32(r), _i32(t)
+    n, groups = h.shape[0], D * D * n_rel
+    order = np.zeros(n, dtype=np.int64)
+    offs = np.zeros(groups + 1, dtype=np.int64)
+    cdf = np.zeros(groups, dtype=np.uint64)
+    lib().orc_sampler_build(_p(h, C.c_int32), _p(r, C.c_int32), _p(t, C.c_int32), C.c_int64(n),
+                            C.c_int64(part_size), C.c_int(D), C.c_int64(n_rel), _p(order, C.c_int64),
+                            _p(offs, C.c_int64), _p(cdf, C.c_uint64))
+    return order, offs, cdf
+
+
+def sample_triples(seed, step, tag, bucket_lo, n_buckets, per_bucket, n_rel, rel_offsets, cdf, order):
+    out = np.zeros(n_buckets * per_bucket, dtype=np.int64)
+    lib().orc_sample_triples(C.c_uint64(seed), C.c_uint64(step), C.c_uint32(tag), C.c_int64(bucket_lo),
+                             C.c_int64(n_buckets), C.c_int64(per_bucket), C.c_int64(n_rel),
+                             _p(np.ascontiguousarray(rel_offsets, dtype=np.int64), C.c_int64),
+                             _p(np.ascontiguousarray(cdf, dtype=np.uint64), C.c_uint64),
+                             _p(np.ascontiguousarray(order, dtype=np.int64), C.c_int64), _p(out, C.c_int64))
+    return out
+
+
+def sample_negatives_sharded(seed, step, tag, part_size, n_ent, D, per_shard):
+    out = np.zeros(D * per_shard, dtype=np.int32)
+    lib().orc_sample_negatives_sharded(C.c_uint64(seed), C.c_uint64(step), C.c_uint32(tag), C.c_int64(part_size),
+                                       C.c_int64(n_ent), C.c_int(D), C.c_int64(per_shard), _p(out, C.c_int32))
+    return out

@@ -670,3 +670,104 @@ void orc_bucket_triples(const int32_t *h, const int32_t *t, int64_t n, int64_t p
         free(cur);
     }
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Relation-aware triple sampler (Section 4, "Training")                                       */
+/* ------------------------------------------------------------------------------------------ */
+
+/* Weight of a relation with n triples in a bucket: w(n) = floor(2^20 * n^(1/3)), the largest integer
+   whose cube does not exceed n * 2^60.  Exact integer arithmetic, so that every implementation of the
+   sampler draws from the same table.  The paper's law is p(r) proportional to the cube root of n_r;
+   the truncation changes a probability by less than one part in 2^20.  n < 2^32. */
+uint64_t orc_cbrt_weight(uint64_t n)
+{
+    unsigned __int128 target = (unsigned __int128)n << 60;
+    uint64_t w = 0;
+    for (int bit = 31; bit >= 0; --bit) {       /* w < 2^32 since n < 2^32 */
+        uint64_t c = w | (1ull << bit);
+        unsigned __int128 cube = (unsigned __int128)c * c * c;
+        if (cube <= target) w = c;
+    }
+    return w;
+}
+
+/* Index over the triples: a stable sort by (bucket, relation), bucket = (h / part_size) * D + t / part_size
+   (Section 4, "Partitioning"), with
+     order       [n]                position in the input of the k-th triple of the sorted list
+     rel_offsets [D*D*n_rel + 1]    first sorted position of every (bucket, relation) group
+     cdf         [D*D*n_rel]        inclusive prefix sums, inside each bucket, of w(n_r)                  */
+void orc_sampler_build(const int32_t *h, const int32_t *r, const int32_t *t, int64_t n, int64_t part_size,
+                       int D, int64_t n_rel, int64_t *order, int64_t *rel_offsets, uint64_t *cdf)
+{
+    int64_t groups = (int64_t)D * D * n_rel;
+    for (int64_t g = 0; g <= groups; ++g) rel_offsets[g] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t g = ((h[i] / part_size) * D + (t[i] / part_size)) * n_rel + r[i];
+        rel_offsets[g + 1]++;
+    }
+    for (int64_t g = 0; g < groups; ++g) rel_offsets[g + 1] += rel_offsets[g];
+    int64_t *cur = (int64_t *)malloc(sizeof(int64_t) * (size_t)(groups > 0 ? groups : 1));
+    for (int64_t g = 0; g < groups; ++g) cur[g] = rel_offsets[g];
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t g = ((h[i] / part_size) * D + (t[i] / part_size)) * n_rel + r[i];
+        order[cur[g]++] = i;
+    }
+    free(cur);
+    for (int64_t b = 0; b < (int64_t)D * D; ++b) {
+        uint64_t run = 0;
+        for (int64_t q = 0; q < n_rel; ++q) {
+            int64_t g = b * n_rel + q;
+            run += orc_cbrt_weight((uint64_t)(rel_offsets[g + 1] - rel_offsets[g]));
+            cdf[g] = run;
+        }
+    }
+}
+
+/* Draw q of the call, q < n_buckets * per_bucket, samples from bucket bucket_lo + q / per_bucket: first a
+   relation with probability w(n_r) / sum_r' w(n_r'), then one of its n_r triples uniformly, with replacement:
+       p((h, r, t)) = (1 / n_r) * cbrt(n_r) / sum_r' cbrt(n_r').
+   Philox4x32-10 with key = seed and counter (q_lo, q_hi, step, tag); x = w1:w0 picks the relation as the
+   first one whose cdf exceeds floor(x * total / 2^64), y = w3:w2 the triple floor(y * n_r / 2^64) of the group.
+   out_pos[q] = position of the triple in the input arrays, or -1 when the bucket is empty. */
+void orc_sample_triples(uint64_t seed, uint64_t step, uint32_t tag, int64_t bucket_lo, int64_t n_buckets,
+                        int64_t per_bucket, int64_t n_rel, const int64_t *rel_offsets, const uint64_t *cdf,
+                        const int64_t *order, int64_t *out_pos)
+{
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    for (int64_t q = 0; q < n_buckets * per_bucket; ++q) {
+        int64_t b = bucket_lo + q / per_bucket;
+        const uint64_t *c = cdf + b * n_rel;
+        uint64_t total = n_rel > 0 ? c[n_rel - 1] : 0;
+        if (total == 0) { out_pos[q] = -1; continue; }
+        uint32_t ctr[4] = { (uint32_t)q, (uint32_t)((uint64_t)q >> 32), (uint32_t)step, tag };
+        uint32_t w[4];
+        orc_philox4x32_10(ctr, key, w);
+        uint64_t x = ((uint64_t)w[1] << 32) | w[0], y = ((uint64_t)w[3] << 32) | w[2];
+        uint64_t pick = (uint64_t)(((unsigned __int128)x * total) >> 64);
+        int64_t rel = 0;
+        while (c[rel] <= pick) ++rel;           /* plain scan: the first relation whose cdf exceeds pick */
+        int64_t g = b * n_rel + rel;
+        uint64_t cnt = (uint64_t)(rel_offsets[g + 1] - rel_offsets[g]);
+        uint64_t k = (uint64_t)(((unsigned __int128)y * cnt) >> 64);
+        out_pos[q] = order[rel_offsets[g] + (int64_t)k];
+    }
+}
+
+/* Shared negatives of one worker's micro-batch (Section 4, eq. (negsamples)): per_shard ids from every
+   entity shard E_j = [j * part_size, min(n_ent, (j+1) * part_size)), slot n belongs to shard n / per_shard.
+   Same generator layout as orc_sample_negatives (block n/2, two ids per block). */
+void orc_sample_negatives_sharded(uint64_t seed, uint64_t step, uint32_t tag, int64_t part_size, int64_t n_ent,
+                                  int D, int64_t per_shard, int32_t *out)
+{
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    for (int64_t i = 0; i < (int64_t)D * per_shard; ++i) {
+        int64_t j = i / per_shard, lo = j * part_size, hi = lo + part_size < n_ent ? lo + part_size : n_ent;
+        uint64_t block = (uint64_t)i / 2;
+        uint32_t ctr[4] = { (uint32_t)block, (uint32_t)(block >> 32), (uint32_t)step, tag };
+        uint32_t w[4];
+        orc_philox4x32_10(ctr, key, w);
+        int half = (int)(i & 1);
+        uint64_t x = ((uint64_t)w[2 * half + 1] << 32) | (uint64_t)w[2 * half];
+        out[i] = (int32_t)(lo + (int64_t)(uint64_t)(((unsigned __int128)x * (uint64_t)(hi - lo)) >> 64));
+    }
+}
