@@ -43,7 +43,7 @@ typedef enum { KGE_TRANSE = 0, KGE_TRANSH = 1, KGE_ROTATE = 2, KGE_DISTMULT = 3,
 typedef enum { KGE_LOGSIGMOID = 0, KGE_SAMPLED_SOFTMAX = 1 } kge_loss_t;
 typedef enum { KGE_F32 = 0, KGE_BF16 = 1 } kge_dtype_t;
 typedef enum { KGE_OP_SCORE = 0, KGE_OP_LOSS_BWD = 1, KGE_OP_SPARSE_ADAM = 2, KGE_OP_TOPK = 3,
-               KGE_OP_PARTITION = 4 } kge_op_t;
+               KGE_OP_PARTITION = 4, KGE_OP_SAMPLER_BUILD = 5 } kge_op_t;
 
 enum {
     KGE_OK = 0,
@@ -183,11 +183,52 @@ int kge_partition_triples(const int32_t *h, const int32_t *t, int64_t n, int64_t
                           size_t ws_bytes, void *hip_stream);
 
 /*
+ * Relation-aware triple sampler (Section 4, "Training"): the triples of a micro-batch part B_ij are
+ * drawn with replacement from partition bucket T_ij with
+ *     p((h, r, t)) = (1 / n_r) * cbrt(n_r) / sum_r' cbrt(n_r'),   n_r = triples of relation r in T_ij,
+ * i.e. first a relation by the cube root of its frequency in the bucket, then one of its triples uniformly.
+ *
+ * kge_sampler_build (one-off) indexes the triples: a stable sort by (bucket, relation), bucket as in
+ * kge_partition_triples, giving
+ *   order        int64[n]                 input position of the k-th triple of the sorted list
+ *   rel_offsets  int64[D*D*n_rel + 1]     first sorted position of every (bucket, relation) group
+ *   cdf          uint64[D*D*n_rel]        inclusive prefix sums, inside each bucket, of the integer weights
+ *                                         w(n_r) = floor(2^20 * n_r^(1/3)) (exact: the largest integer whose
+ *                                         cube is <= n_r * 2^60), so every implementation draws alike
+ * n < 2^31, D <= 64, D*D*n_rel < 2^31.
+ *
+ * kge_sample_triples draws n_buckets * per_bucket triples: draw q comes from bucket
+ * bucket_lo + q / per_bucket.  One worker's micro-batch of eq. (microbatch) is bucket_lo = i*D,
+ * n_buckets = D, per_bucket = B/D; a single partition pair is n_buckets = 1.  Philox4x32-10, key = seed,
+ * counter (q_lo, q_hi, step, stream_tag): x = w1:w0 selects the first relation whose cdf exceeds
+ * floor(x * total / 2^64), y = w3:w2 the triple floor(y * n_r / 2^64) of that group.  Bit-exact, no state.
+ * Outputs (device; any of out_pos and the out_h/out_r/out_t triple may be NULL): out_pos int64[draws] =
+ * position in the triple arrays, out_h/out_r/out_t int32[draws] = the triple itself (needs h, r, t).
+ * Draws from an empty bucket give -1.
+ *
+ * kge_sample_negatives_sharded: the shared negatives of eq. (negsamples), per_shard ids from every
+ * entity shard E_j = [j*part_size, min(n_ent, (j+1)*part_size)); slot i belongs to shard i / per_shard and
+ * uses the generator block of slot i of kge_sample_negatives.  out_idx: device int32[D * per_shard].
+ */
+int kge_sampler_build(const int32_t *h, const int32_t *r, const int32_t *t, int64_t n, int64_t part_size,
+                      int32_t D, int64_t n_rel, int64_t *order, int64_t *rel_offsets, uint64_t *cdf,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+int kge_sample_triples(uint64_t seed, uint64_t step, uint32_t stream_tag, int64_t bucket_lo,
+                       int64_t n_buckets, int64_t per_bucket, int32_t D, int64_t n_rel,
+                       const int64_t *rel_offsets, const uint64_t *cdf, const int64_t *order,
+                       const int32_t *h, const int32_t *r, const int32_t *t, int64_t *out_pos,
+                       int32_t *out_h, int32_t *out_r, int32_t *out_t, void *hip_stream);
+int kge_sample_negatives_sharded(uint64_t seed, uint64_t step, uint32_t stream_tag, int64_t part_size,
+                                 int64_t n_ent, int32_t D, int64_t per_shard, int32_t *out_idx,
+                                 void *hip_stream);
+
+/*
  * Workspace size in bytes for one call (pure function; host only).  Meaning of (B, N, K):
  *   KGE_OP_SCORE, KGE_OP_LOSS_BWD  B triples, N shared negatives, K unused
  *   KGE_OP_SPARSE_ADAM             B = M gradient rows, N = dim, K unused; model may be NULL
  *   KGE_OP_TOPK                    B = Q queries, N = number of candidates, K
  *   KGE_OP_PARTITION               B = n triples, N = D; model may be NULL
+ *   KGE_OP_SAMPLER_BUILD           B = n triples, N = D; model may be NULL
  * Returns 0 for an invalid request.
  */
 size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t N, int64_t K);

@@ -15,10 +15,10 @@ LIB_PATH = os.path.join(_HERE, "libkge_mi355x.so")
 
 SCORERS = {"transe": 0, "transh": 1, "rotate": 2, "distmult": 3, "complex": 4}
 LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
-OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION = 0, 1, 2, 3, 4
+OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION, OP_SAMPLER_BUILD = 0, 1, 2, 3, 4, 5
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
-           "kge_partition_triples", "kge_workspace_bytes", "kge_status_string", "kge_profile_enable",
-           "kge_profile_collect"]
+           "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
+           "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5}
 
 
@@ -53,6 +53,12 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise KgeError(f"{LIB_PATH} is missing: build it with `python -m paper_2211_12281_amd.build`")
         lib = C.CDLL(LIB_PATH)
+        lib.kge_sampler_build.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_int64, C.c_int32, C.c_int64] + \
+            [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+        lib.kge_sample_triples.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
+                                           C.c_int32, C.c_int64] + [C.c_void_p] * 11
+        lib.kge_sample_negatives_sharded.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64,
+                                                     C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         lib.kge_workspace_bytes.restype = C.c_size_t
         lib.kge_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
         lib.kge_status_string.restype = C.c_char_p
@@ -69,6 +75,12 @@ def load():
             [C.c_size_t, C.c_void_p]
         lib.kge_partition_triples.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kge_sampler_build.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_int64, C.c_int32, C.c_int64] + \
+            [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+        lib.kge_sample_triples.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
+                                           C.c_int32, C.c_int64] + [C.c_void_p] * 11
+        lib.kge_sample_negatives_sharded.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64,
+                                                     C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -235,3 +247,43 @@ def partition_triples(h, t, part_size: int, D: int, ws: Workspace | None = None)
     _check(load().kge_partition_triples(_ptr(_i32(h)), _ptr(_i32(t)), n, part_size, D, _ptr(offsets), _ptr(order),
                                         _ptr(buf), buf.numel(), _stream()), "kge_partition_triples")
     return offsets, order
+
+
+class TripleSampler:
+    """Index of kge_sampler_build over device triple arrays (h, r, t: int32), and draws from it."""
+
+    def __init__(self, h, r, t, part_size: int, D: int, n_rel: int, ws: Workspace | None = None):
+        self.h, self.r, self.t = _i32(h), _i32(r), _i32(t)
+        self.part_size, self.D, self.n_rel = part_size, D, n_rel
+        n, groups = self.h.numel(), D * D * n_rel
+        self.order = torch.empty(max(n, 1), dtype=torch.int64, device="cuda")[:n]
+        self.rel_offsets = torch.empty(groups + 1, dtype=torch.int64, device="cuda")
+        self.cdf = torch.empty(groups, dtype=torch.int64, device="cuda")       # bit pattern of uint64
+        ws = ws or _default_ws
+        buf = ws.get(workspace_bytes(OP_SAMPLER_BUILD, None, n, D))
+        _check(load().kge_sampler_build(_ptr(self.h), _ptr(self.r), _ptr(self.t), n, part_size, D, n_rel,
+                                        _ptr(self.order), _ptr(self.rel_offsets), _ptr(self.cdf), _ptr(buf),
+                                        buf.numel(), _stream()), "kge_sampler_build")
+
+    def sample(self, seed: int, step: int, stream_tag: int, bucket_lo: int, n_buckets: int, per_bucket: int,
+               want_pos: bool = False):
+        n = n_buckets * per_bucket
+        oh, orr, ot = (torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(3))
+        pos = torch.empty(n, dtype=torch.int64, device="cuda") if want_pos else None
+        # (an index over zero triples still hands over valid pointers: its storage has one spare element)
+        order = self.order if self.order.numel() else self.order.new_zeros(1)
+        h, r, t = ((x if x.numel() else x.new_zeros(1)) for x in (self.h, self.r, self.t))
+        _check(load().kge_sample_triples(seed, step, stream_tag, bucket_lo, n_buckets, per_bucket, self.D, self.n_rel,
+                                         _ptr(self.rel_offsets), _ptr(self.cdf), _ptr(order), _ptr(h),
+                                         _ptr(r), _ptr(t), _ptr(pos), _ptr(oh), _ptr(orr), _ptr(ot),
+                                         _stream()), "kge_sample_triples")
+        return (oh, orr, ot, pos) if want_pos else (oh, orr, ot)
+
+
+def sample_negatives_sharded(seed: int, step: int, stream_tag: int, part_size: int, n_ent: int, D: int,
+                             per_shard: int, out=None):
+    if out is None:
+        out = torch.empty(D * per_shard, dtype=torch.int32, device="cuda")
+    _check(load().kge_sample_negatives_sharded(seed, step, stream_tag, part_size, n_ent, D, per_shard, _ptr(out),
+                                               _stream()), "kge_sample_negatives_sharded")
+    return out

@@ -13,6 +13,15 @@ size_t kge_topk_ws(const kge_model_t &model, int64_t Q, int64_t ncand, int K);
 int kge_run_partition(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int D, int64_t *offsets,
                       int64_t *order, void *ws, size_t ws_bytes, hipStream_t st);
 size_t kge_partition_ws(int64_t n, int D);
+size_t kge_sampler_ws(int64_t n);
+int kge_run_sampler_build(const int32_t *h, const int32_t *r, const int32_t *t, int64_t n, int64_t part_size, int D,
+                          int64_t n_rel, int64_t *order, int64_t *rel_offsets, uint64_t *cdf, void *ws, hipStream_t st);
+int kge_run_sample_triples(uint64_t seed, uint64_t step, uint32_t tag, int64_t bucket_lo, int64_t draws, int64_t per_bucket,
+                           int64_t n_rel, const int64_t *rel_offsets, const uint64_t *cdf, const int64_t *order,
+                           const int32_t *h, const int32_t *r, const int32_t *t, int64_t *out_pos, int32_t *out_h,
+                           int32_t *out_r, int32_t *out_t, hipStream_t st);
+int kge_run_negatives_sharded(uint64_t seed, uint64_t step, uint32_t tag, int64_t part_size, int64_t n_ent, int64_t per_shard,
+                              int64_t n, int32_t *out, hipStream_t st);
 
 namespace {
 
@@ -176,6 +185,7 @@ size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t 
         if (validate_model(model) != KGE_OK || K < 1 || K > 256) return 0;
         return kge_topk_ws(*model, B, N, (int)K);
     case KGE_OP_PARTITION: return (N >= 1 && N <= 64) ? kge_partition_ws(B, (int)N) : 0;
+    case KGE_OP_SAMPLER_BUILD: return (N >= 1 && N <= 64) ? kge_sampler_ws(B) : 0;
     default: return 0;
     }
 }
@@ -186,6 +196,45 @@ int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int6
     if (n == 0) return KGE_OK;
     if (!out_idx) return KGE_E_INVALID_ARG;
     return kge_run_negatives(seed, step, stream_tag, lo, hi, n, out_idx, (hipStream_t)hip_stream);
+}
+
+int kge_sampler_build(const int32_t *h, const int32_t *r, const int32_t *t, int64_t n, int64_t part_size, int32_t D,
+                      int64_t n_rel, int64_t *order, int64_t *rel_offsets, uint64_t *cdf, void *ws, size_t ws_bytes,
+                      void *hip_stream) {
+    if (n < 0 || n >= (1ll << 31) || part_size <= 0 || D < 1 || D > 64 || n_rel < 1) return KGE_E_INVALID_ARG;
+    if ((int64_t)D * D * n_rel >= (1ll << 31)) return KGE_E_INVALID_ARG;
+    if (!rel_offsets || !cdf || (n > 0 && (!h || !r || !t || !order))) return KGE_E_INVALID_ARG;
+    if (n > 0 && !ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (n > 0 && kge_sampler_ws(n) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_sampler_build(h, r, t, n, part_size, D, n_rel, order, rel_offsets, cdf, ws, (hipStream_t)hip_stream);
+}
+
+int kge_sample_triples(uint64_t seed, uint64_t step, uint32_t stream_tag, int64_t bucket_lo, int64_t n_buckets,
+                       int64_t per_bucket, int32_t D, int64_t n_rel, const int64_t *rel_offsets, const uint64_t *cdf,
+                       const int64_t *order, const int32_t *h, const int32_t *r, const int32_t *t, int64_t *out_pos,
+                       int32_t *out_h, int32_t *out_r, int32_t *out_t, void *hip_stream) {
+    if (D < 1 || D > 64 || n_rel < 1 || bucket_lo < 0 || n_buckets < 0 || per_bucket < 0 || step >= (1ull << 32))
+        return KGE_E_INVALID_ARG;
+    if (bucket_lo + n_buckets > (int64_t)D * D) return KGE_E_INVALID_ARG;
+    const int64_t draws = n_buckets * per_bucket;
+    if (draws == 0) return KGE_OK;
+    if (draws >= (1ll << 31) || !rel_offsets || !cdf || !order) return KGE_E_INVALID_ARG;
+    if (!out_pos && !out_h) return KGE_E_INVALID_ARG;
+    if (out_h && (!out_r || !out_t || !h || !r || !t)) return KGE_E_INVALID_ARG;
+    return kge_run_sample_triples(seed, step, stream_tag, bucket_lo, draws, per_bucket, n_rel, rel_offsets, cdf, order, h, r,
+                                  t, out_pos, out_h, out_r, out_t, (hipStream_t)hip_stream);
+}
+
+int kge_sample_negatives_sharded(uint64_t seed, uint64_t step, uint32_t stream_tag, int64_t part_size, int64_t n_ent,
+                                 int32_t D, int64_t per_shard, int32_t *out_idx, void *hip_stream) {
+    if (D < 1 || D > 64 || part_size <= 0 || per_shard < 0 || n_ent <= 0 || n_ent > (1ll << 31) || step >= (1ull << 32))
+        return KGE_E_INVALID_ARG;
+    if ((int64_t)(D - 1) * part_size >= n_ent || (int64_t)D * part_size < n_ent) return KGE_E_INVALID_ARG;   // D non-empty shards
+    const int64_t n = (int64_t)D * per_shard;
+    if (n == 0) return KGE_OK;
+    if (n >= (1ll << 31) || !out_idx) return KGE_E_INVALID_ARG;
+    return kge_run_negatives_sharded(seed, step, stream_tag, part_size, n_ent, per_shard, n, out_idx, (hipStream_t)hip_stream);
 }
 
 int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, const int32_t *t, int64_t B,

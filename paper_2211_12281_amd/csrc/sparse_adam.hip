@@ -18,11 +18,13 @@ struct KeySrc {
     const int32_t *idx;               // first pass, row ids
     const int32_t *h, *t;             // first pass, bucket mode
     int64_t part_size; int D;
+    const int32_t *r; int64_t n_rel;  // first pass, (bucket, relation) mode
 };
-template <int FIRST>   // 0: pairs, 1: row ids, 2: buckets
+template <int FIRST>   // 0: pairs, 1: row ids, 2: buckets, 3: (bucket, relation)
 __device__ __forceinline__ uint32_t load_key(const KeySrc &k, int64_t i) {
     if constexpr (FIRST == 1) return (uint32_t)k.idx[i];
     else if constexpr (FIRST == 2) return (uint32_t)((k.h[i] / k.part_size) * k.D + (k.t[i] / k.part_size));
+    else if constexpr (FIRST == 3) return (uint32_t)(((k.h[i] / k.part_size) * k.D + (k.t[i] / k.part_size)) * k.n_rel + k.r[i]);
     else return k.keys[i];
 }
 template <int FIRST>
@@ -312,27 +314,30 @@ size_t kge_sparse_adam_ws(int64_t M, int dim) {
 size_t kge_sort_ws(int64_t M) { return kge_sparse_adam_ws(M, 0); }
 
 // Sorts (key, position) pairs by key, stable; returns the buffers that hold the result.  Keys are
-// either the given row ids, or (when h and t are given) the partition-pair bucket of each triple.
+// either the given row ids, or (when h and t are given) the partition-pair bucket of each triple, or
+// (with r as well) bucket * n_rel + relation.
 int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64_t part_size, int D, int64_t M,
-                   int64_t key_range, void *ws, const uint32_t **sk, const uint32_t **sp, hipStream_t st) {
+                   int64_t key_range, void *ws, const uint32_t **sk, const uint32_t **sp, hipStream_t st,
+                   const int32_t *r, int64_t n_rel) {
     SortWs s;
     sort_carve(M, 0, ws, s);
     int bits = 1;
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
     uint32_t *ki = s.ka, *ko = s.kb, *pi = s.pa, *po = s.pb;       // the first pass writes buffer B
     const bool own_scan = s.nblk <= 64;
-    const int first = idx ? 1 : 2;
+    const int first = idx ? 1 : (r ? 3 : 2);
     for (int shift = 0; shift < bits; shift += 8) {
-        KeySrc src{ki, pi, idx, h, t, part_size, D};
+        KeySrc src{ki, pi, idx, h, t, part_size, D, r, n_rel};
         const int mode = shift == 0 ? first : 0;
         const dim3 grid(s.nblk), blk(256);
         if (mode == 1) hipLaunchKernelGGL(sort_hist_kernel<1>, grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist);
         else if (mode == 2) hipLaunchKernelGGL(sort_hist_kernel<2>, grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist);
+        else if (mode == 3) hipLaunchKernelGGL(sort_hist_kernel<3>, grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist);
         else hipLaunchKernelGGL(sort_hist_kernel<0>, grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist);
         if (!own_scan) hipLaunchKernelGGL(sort_scan_kernel, dim3(1), dim3(1024), 0, st, s.hist, (int64_t)256 * s.nblk);
 #define KGE_SCATTER(F, O) hipLaunchKernelGGL((sort_scatter_kernel<F, O>), grid, blk, 0, st, src, M, shift, s.nblk, s.rounds, s.hist, ko, po)
-        if (own_scan) { if (mode == 1) KGE_SCATTER(1, true); else if (mode == 2) KGE_SCATTER(2, true); else KGE_SCATTER(0, true); }
-        else          { if (mode == 1) KGE_SCATTER(1, false); else if (mode == 2) KGE_SCATTER(2, false); else KGE_SCATTER(0, false); }
+        if (own_scan) { if (mode == 1) KGE_SCATTER(1, true); else if (mode == 2) KGE_SCATTER(2, true); else if (mode == 3) KGE_SCATTER(3, true); else KGE_SCATTER(0, true); }
+        else          { if (mode == 1) KGE_SCATTER(1, false); else if (mode == 2) KGE_SCATTER(2, false); else if (mode == 3) KGE_SCATTER(3, false); else KGE_SCATTER(0, false); }
 #undef KGE_SCATTER
         uint32_t *tmp = ki; ki = ko; ko = tmp;
         tmp = pi; pi = po; po = tmp;
@@ -349,7 +354,7 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
     int rc;
     {
         KgeProfScope prof(KGE_PROF_SORT, st);
-        rc = kge_sort_pairs(idx, nullptr, nullptr, 1, 1, M, n_rows, ws, &sk, &sp, st);
+        rc = kge_sort_pairs(idx, nullptr, nullptr, 1, 1, M, n_rows, ws, &sk, &sp, st, nullptr, 0);
     }
     if (rc != KGE_OK) return rc;
     AdamConst c;

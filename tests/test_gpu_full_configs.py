@@ -207,3 +207,39 @@ def test_c5_partition_bucketing_at_scale(orc):
     assert np.all(order[1:][same] > order[:-1][same])                  # input order kept inside a bucket
     assert np.array_equal(np.sort(order[:: 9973]), np.unique(order[:: 9973]))
     _free()
+
+
+def test_c5_relation_sampler_at_scale(orc):
+    """100M seeded triples, 1,400 Zipf(1.0) relations, 16 x 16 buckets: the index is checked by its
+    properties, the draws of one worker's micro-batch (8,192 triples, 512 per tail partition) against the
+    oracle's sampler running on the index the library built."""
+    import paper_2211_12281_amd as kge
+    n_ent, D, n, n_rel = 90_000_000, 16, 100_000_000, 1400
+    part = -(-n_ent // D)
+    g = ks.rng(ks.BASE_SEED, ks.TAG_TRIPLE_H)
+    h, t = ks.uniform_ids(g, 0, n_ent, n), ks.uniform_ids(g, 0, n_ent, n)
+    p = 1.0 / np.arange(1, n_rel + 1); p /= p.sum()
+    r = np.searchsorted(np.cumsum(p), g.random(n)).clip(0, n_rel - 1).astype(np.int32)
+    smp = kge.TripleSampler(dev_idx(h), dev_idx(r), dev_idx(t), part, D, n_rel)
+    order, offs, cdf = smp.order.cpu().numpy(), smp.rel_offsets.cpu().numpy(), smp.cdf.cpu().numpy().view(np.uint64)
+    key = ((h // part).astype(np.int64) * D + t // part) * n_rel + r
+    sk = key[order]
+    assert np.all(np.diff(sk) >= 0)                                    # grouped by (bucket, relation)
+    same = sk[1:] == sk[:-1]
+    assert np.all(order[1:][same] > order[:-1][same])                   # stable
+    assert np.array_equal(offs, np.searchsorted(sk, np.arange(D * D * n_rel + 1)))
+    cnt = np.diff(offs)
+    for gi in (0, 1, 1399, 1400 * 37 + 5, D * D * n_rel - 1):
+        prev = 0 if gi % n_rel == 0 else int(cdf[gi - 1])
+        assert int(cdf[gi]) - prev == orc.cbrt_weight(int(cnt[gi]))
+    worker = 5
+    ref = orc.sample_triples(ks.BASE_SEED, 9, ks.TAG_BATCH, worker * D, D, 512, n_rel, offs, cdf, order)
+    oh, orr, ot, pos = smp.sample(ks.BASE_SEED, 9, ks.TAG_BATCH, worker * D, D, 512, want_pos=True)
+    assert np.array_equal(pos.cpu().numpy(), ref)
+    oh, ot = oh.cpu().numpy(), ot.cpu().numpy()
+    assert np.all(oh // part == worker) and np.array_equal(ot // part, np.repeat(np.arange(D), 512))
+    # the drawn relations are flatter than the graph's: the top relation's share drops from ~13 % to a few %
+    share = (orr.cpu().numpy() == 0).mean()
+    assert share < 0.5 * (r == 0).mean()
+    del smp
+    _free()
