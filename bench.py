@@ -35,6 +35,10 @@ def parse():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the entity table (debugging only)")
     ap.add_argument("--reg-l3", type=float, default=0.0,
                     help="training workloads: weight of the L3 regulariser of the gathered rows (default off)")
+    ap.add_argument("--sampled-batches", type=int, default=0, metavar="TRIPLES",
+                    help="training workloads: draw every micro-batch on the GPU with the relation-aware sampler "
+                         "(one worker's all-partition micro-batch and sharded negatives) from a synthetic list of "
+                         "this many triples, instead of replaying pre-drawn index streams")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy first (reference for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -47,7 +51,7 @@ def parse():
 class TrainWorkload:
     """c3 / c5 / c1: forward + backward + sparse Adam on bf16 shadow / fp32 master tables."""
 
-    def __init__(self, name, P, scale, only=None, reg_l3=0.0):
+    def __init__(self, name, P, scale, only=None, reg_l3=0.0, sampled=0):
         import torch
         import kge_synth as ks
         import kge_synth.device as ksd
@@ -118,6 +122,19 @@ class TrainWorkload:
             self.loss_kw = dict(n_ent_for_c=self.n_ent)
         if reg_l3 > 0.0:
             self.loss_kw["reg_l3"] = reg_l3
+        self.sampler = None
+        if sampled > 0:
+            # the paper's generator: worker i's micro-batch takes B/D triples from each bucket T_ij by the
+            # cube-root relation law, and N/D negatives from each entity shard (Section 4, "Training")
+            self.D = P.get("D", 8)
+            self.part = -(-self.n_ent // self.D)
+            g = ks.rng(ks.BASE_SEED, ks.TAG_TRIPLE_H)
+            zz = ks.ZipfIds(self.n_ent, P.get("zipf_s", 1.1))
+            th, tt = zz.draw(g, sampled), zz.draw(g, sampled)
+            tr = ks.ZipfIds(self.n_rel, P.get("rel_zipf_s", 1.0)).draw(g, sampled)
+            self.sampler = kge.TripleSampler(*(torch.from_numpy(x).to(dev) for x in (th, tr, tt)), self.part, self.D,
+                                             self.n_rel)
+            self.n_triples = sampled
         torch.cuda.synchronize()
         self.setup_s = time.time() - t0
 
@@ -130,8 +147,13 @@ class TrainWorkload:
 
     def step(self, i):
         kge, ks = self.kge, self.ks
-        h, r, t, lo, hi = self.batches[i % len(self.batches)]
-        kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=self.neg)
+        if self.sampler is not None:
+            h, r, t = self.sampler.sample(ks.BASE_SEED, i, ks.TAG_BATCH, (i % self.D) * self.D, self.D, self.B // self.D)
+            kge.sample_negatives_sharded(ks.BASE_SEED, i, ks.TAG_NEG, self.part, self.n_ent, self.D, self.N // self.D,
+                                         out=self.neg)
+        else:
+            h, r, t, lo, hi = self.batches[i % len(self.batches)]
+            kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=self.neg)
         kge.loss_bwd(self.model, self.P["loss"], h, r, t, self.neg, out=self.out, **self.loss_kw)
         lr = self.P["lr"]
         kge.sparse_adam(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent_idx"], self.out["g_ent"], lr,
@@ -146,7 +168,12 @@ class TrainWorkload:
         return self.B * (self.N + 1)
 
     def extra(self, ms):
-        return {"triples_per_s": self.B / (ms * 1e-3), "scorer": self.scorer, "reg_l3": self.loss_kw.get("reg_l3", 0.0)}
+        out = {"triples_per_s": self.B / (ms * 1e-3), "scorer": self.scorer, "reg_l3": self.loss_kw.get("reg_l3", 0.0)}
+        if self.sampler is not None:
+            out["micro_batch"] = f"sampled on the GPU per step: {self.D} x {self.B // self.D} triples of one worker by the " \
+                                 f"cube-root relation law from {self.n_triples} synthetic triples, {self.D} x " \
+                                 f"{self.N // self.D} sharded negatives"
+        return out
 
     def mfma_flops(self, slot):
         # algorithmic contractions of 2 B N d flop each: the FWD pass computes the scores AND the queries'
@@ -309,7 +336,7 @@ def main():
     kge.load()
     P = ks.PRESETS[a.workload]
     if a.workload in ("c1", "c3", "c5"):
-        wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3)
+        wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3, a.sampled_batches)
     elif a.workload == "c2":
         wl = ScoreWorkload(P, a.scale, a.scorer)
     else:

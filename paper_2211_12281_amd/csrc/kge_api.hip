@@ -322,7 +322,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     if (N > 0) {
         // with B == 0 there are no partials: nsplit 0 writes zero rows
         rc = kge_run_tfinish(b.acct, b.sumt, have_block ? g.nsplit_t : 0, g.Np, g.N, g.dp, model->dim,
-                             have_block && g.kind == KGE_KIND_DIST, b.T, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
+                             have_block && g.kind == KGE_KIND_DIST, have_block ? b.T : nullptr, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
                              g_ent_idx + 2 * B, model->ent, model->ent_ld, cfg->reg_l3, b.regv + (size_t)2 * g.Bp, st);
         if (rc != KGE_OK) return rc;
     }

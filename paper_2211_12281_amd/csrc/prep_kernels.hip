@@ -370,33 +370,54 @@ __global__ void kge_tfinish_kernel(const float *accT_part, const float4 *sumT_pa
     if (n >= N) return;
     float cs = 0.f;
     for (int s = 0; s < nsplit; ++s) cs += sumT_part[(size_t)s * Np + n].x;
-    float nrm = 0.f, f = 0.f;
+    // the row is read once (from the gathered copy when there is one, else from the table) and kept in registers
+    float x[KGE_MAXJ], f = 0.f;
+    const bool need_row = reg > 0.f || dist_kind;
+    const int64_t rbase = T ? (int64_t)n * dp : (int64_t)neg[n] * ent_ld;
+    const void *rsrc = T ? T : ent;
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        x[k] = (need_row && j < d) ? El<BF16>::ld(rsrc, rbase + j) : 0.f;
+    }
     if (reg > 0.f) {
         float c3 = 0.f;
-        for (int j = lane; j < d; j += 64) { const float x = El<BF16>::ld(ent, (int64_t)neg[n] * ent_ld + j); c3 += fabsf(x) * x * x; }
-        nrm = cbrtf(kge_wave_sum(c3));
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) c3 += fabsf(x[k]) * x[k] * x[k];
+        const float nrm = cbrtf(kge_wave_sum(c3));
         f = nrm > 0.f ? reg / (nrm * nrm) : 0.f;
         if (lane == 0) regn[n] = nrm;
     }
-    for (int j = lane; j < d; j += 64) {
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        if (j >= d) continue;
         float v = 0.f;
         for (int s = 0; s < nsplit; ++s) v += accT_part[((size_t)s * Np + n) * dp + j];
-        if (dist_kind) v -= cs * El<BF16>::ld(T, (int64_t)n * dp + j);
-        if (reg > 0.f) { const float x = El<BF16>::ld(ent, (int64_t)neg[n] * ent_ld + j); v += f * fabsf(x) * x; }
+        if (dist_kind) v -= cs * x[k];
+        if (reg > 0.f) v += f * fabsf(x[k]) * x[k];
         g_neg[(int64_t)n * d + j] = v;
     }
     if (lane == 0) g_neg_idx[n] = neg[n];
 }
 
-// loss += reg * (sum of the L3 norms of the 2B + N gathered slots): one workgroup, fixed summation tree
+// loss += reg * (sum of the L3 norms of the 2B + N gathered slots): one workgroup of 1024 threads, fixed
+// summation order (eight interleaved partial sums per thread keep the loads in flight, then a tree)
 __global__ void kge_reg_add_kernel(const float *regv, int B, int Bp, int N, float reg, float *loss_out) {
-    __shared__ double sh[256];
-    double s = 0.0;
-    for (int i = threadIdx.x; i < B; i += 256) s += (double)regv[i] + (double)regv[Bp + i];
-    for (int i = threadIdx.x; i < N; i += 256) s += (double)regv[2 * (size_t)Bp + i];
-    sh[threadIdx.x] = s;
+    __shared__ double sh[1024];
+    double p[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto add_range = [&](const float *v, int n) {
+        for (int i0 = threadIdx.x; i0 < n; i0 += 8 * 1024) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const int i = i0 + u * 1024; p[u] += i < n ? (double)v[i] : 0.0; }
+        }
+    };
+    add_range(regv, B);
+    add_range(regv + Bp, B);
+    add_range(regv + 2 * (size_t)Bp, N);
+    sh[threadIdx.x] = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
+    for (int o = 512; o > 0; o >>= 1) {
         if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
         __syncthreads();
     }
@@ -469,6 +490,6 @@ int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit,
 }
 
 int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st) {
-    hipLaunchKernelGGL(kge_reg_add_kernel, dim3(1), dim3(256), 0, st, regv, B, Bp, N, reg, loss_out);
+    hipLaunchKernelGGL(kge_reg_add_kernel, dim3(1), dim3(1024), 0, st, regv, B, Bp, N, reg, loss_out);
     return kge_launch_status();
 }
