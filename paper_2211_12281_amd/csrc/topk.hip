@@ -64,7 +64,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // into 8 different bank groups.  The MFMAs of tile t+1 are issued before the epilogue of tile t, so the
 // matrix pipe works while the vector ALU filters.
 template <bool BF16, int RB, int KIND, int OB>
-__global__ __attribute__((amdgpu_flat_work_group_size(256, 256)))
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
 void topk_scan_kernel(const TopkArgs a) {
     constexpr int KS = RB / 32;
     constexpr int TILE_BYTES = TK_ST * RB;
@@ -144,8 +144,22 @@ void topk_scan_kernel(const TopkArgs a) {
         uint4 av[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) av[ks] = *(const uint4 *)(base + frag_off[ks & 3] + 128 * (ks >> 2));
+        if constexpr (KIND == KGE_KIND_DIST) {
+            // TransE: the accumulators start at -|t|^2 of their candidate row and the queries are stored
+            // doubled, so the contraction itself yields 2 q.t - |t|^2
+            const char *tside = side_base + ((slot % SIDE_SLOTS) * 4 + wave) * 256;
+            // (rows 8 j + 4 g .. + 3 of the tile are registers 4 j .. 4 j + 3: one 16-byte read per j)
 #pragma unroll
-        for (int ob = 0; ob < OB; ++ob) for (int i = 0; i < 16; ++i) acc[ob][i] = 0.f;
+            for (int j = 0; j < 4; ++j) {
+                const kge_f32x4 tn4 = *(const kge_f32x4 *)(tside + (8 * j + 4 * g) * 4);
+#pragma unroll
+                for (int ob = 0; ob < OB; ++ob)
+                    for (int u = 0; u < 4; ++u) acc[ob][4 * j + u] = -tn4[u];
+            }
+        } else {
+#pragma unroll
+            for (int ob = 0; ob < OB; ++ob) for (int i = 0; i < 16; ++i) acc[ob][i] = 0.f;
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
@@ -170,16 +184,12 @@ void topk_scan_kernel(const TopkArgs a) {
         issue(tile + NSTAGE, slot + NSTAGE);
         mma_tile(slot + 1, accn);                       // (the last iteration recomputes a stale stage: unused)
         // ---- epilogue of tile `tile`: cheap wave-level test first, the append path only on a hit ----
-        const char *side = side_base + ((slot % SIDE_SLOTS) * 4 + wave) * 256;
         const bool tile_full = tile * TK_ST + TK_ST <= a.ncand;
-        float vv[OB][16];
+        float vv[OB][16];                               // the values are the accumulators themselves
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int sl = 8 * (i >> 2) + 4 * g + (i & 3);
-            float tnv = 0.f;
-            if constexpr (KIND == KGE_KIND_DIST) tnv = *(const float *)(side + sl * 4);
 #pragma unroll
-            for (int ob = 0; ob < OB; ++ob) vv[ob][i] = KIND == KGE_KIND_DIST ? fmaf(2.f, acc[ob][i], -tnv) : acc[ob][i];
+            for (int ob = 0; ob < OB; ++ob) vv[ob][i] = acc[ob][i];
         }
         if (!tile_full) {
 #pragma unroll
@@ -477,7 +487,8 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     for (int k = 0; k < KGE_MAXJ; ++k) {
         const int j = lane + 64 * k;
         const float qr = El<BF16>::rnd(cx.q[k]);
-        if (j < dp) El<BF16>::st(Qm, (int64_t)q * dp + j, cx.q[k]);
+        // (TransE: stored doubled - exact - so that the scan's contraction yields 2 q.t directly)
+        if (j < dp) El<BF16>::st(Qm, (int64_t)q * dp + j, m.scorer == KGE_DISTMULT ? cx.q[k] : 2.f * cx.q[k]);
         if (j >= d) continue;
         const double hx = (double)El<BF16>::ld(m.ent, hoff + j), rx = (double)El<BF16>::ld(m.rel, roff + j);
         const double qex = m.scorer == KGE_DISTMULT ? hx * rx : hx + rx;      // the exact query component
@@ -494,7 +505,7 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         qi.qn = qn;
         qi.eps_a = (float)(sqrt(dq2) * 1.0001);
         qi.eps_b = m.scorer == KGE_DISTMULT ? (float)(d * 1.1920929e-07 * sqrt(qn) * 1.0001)    // d 2^-23 |q~|
-                                            : (float)(d * 2.3841858e-07);                        // d 2^-22
+                                            : (float)((d + 2) * 2.3841858e-07);                  // (d+2) 2^-22: d products and the -|t|^2 start value
         qi.pad = 0.f;
         qinfo[q] = qi;
         vt[q] = true_t ? (m.scorer == KGE_DISTMULT ? vtl : 2.f * vtl - tnl) : INFINITY;
