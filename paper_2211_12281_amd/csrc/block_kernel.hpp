@@ -125,8 +125,11 @@ struct KgeBlockCfg {
     static constexpr int NX = HAS_X2 ? 2 : 1;
     static constexpr int STAGE_BYTES = X_BYTES * NX + (HAS_XT ? XT_BYTES * NX : 0);
     static constexpr int SIDE_SLOT = OWN_ROW ? 4 * 256 : 4 * 1024;   // per-wave copies of the tile's side info
-    static constexpr int LDS_MAX = 160 * 1024;
-    static constexpr int NSTAGE_RAW = (LDS_MAX - 5 * SIDE_SLOT) / STAGE_BYTES;
+    // Workgroups per compute unit (= waves per SIMD): two where a workgroup's registers fit in 256, so that
+    // the MFMA, LDS and vector phases of one workgroup run under those of the other.
+    static constexpr int OCC = kge_block_occ(BF16, RB, TRANSH, MODE);
+    static constexpr int LDS_MAX = 160 * 1024 / OCC;
+    static constexpr int NSTAGE_RAW = (LDS_MAX - SIDE_SLOT) / (STAGE_BYTES + SIDE_SLOT);   // n stages + (n+1) side slots fit
     static constexpr int NSTAGE = NSTAGE_RAW > 4 ? 4 : NSTAGE_RAW;
     static constexpr int SIDE_SLOTS = NSTAGE + 1;
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES + SIDE_SLOTS * SIDE_SLOT;
@@ -141,7 +144,8 @@ struct KgeBlockCfg {
 };
 
 template <bool BF16, int RB, int MODE, bool TRANSH, int KIND, int LOSS, int DSPLIT>
-__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(1, 1)))
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256),
+                          amdgpu_waves_per_eu(kge_block_occ(BF16, RB, TRANSH, MODE), kge_block_occ(BF16, RB, TRANSH, MODE))))
 void kge_block_kernel(const KgeBlockArgs a) {
     using C = KgeBlockCfg<BF16, RB, MODE, TRANSH, KIND, DSPLIT>;
     constexpr bool OWN_ROW = C::OWN_ROW;

@@ -70,17 +70,17 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.own_tiles_n = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_GRADT, g.kind));
     g.own_tiles_s = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_SCORE, g.kind));
     g.str_tiles_b = g.Bp / KGE_STREAM_TILE; g.str_tiles_n = g.Np / KGE_STREAM_TILE;
-    auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps) {
+    auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps, int occ) {
         if (own_tiles == 0 || str_tiles == 0) { nsplit = 0; tps = 0; return; }
-        int want = (TARGET_WGS + own_tiles - 1) / own_tiles;
+        int want = (TARGET_WGS * occ + own_tiles - 1) / own_tiles;
         if (want > str_tiles) want = str_tiles;
         if (want < 1) want = 1;
         tps = (str_tiles + want - 1) / want;
         nsplit = (str_tiles + tps - 1) / tps;
     };
-    split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q);
-    split(g.own_tiles_n, g.str_tiles_b, g.nsplit_t, g.tps_t);
-    split(g.own_tiles_s, g.str_tiles_b, g.nsplit_s, g.tps_s);
+    split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_FWD));
+    split(g.own_tiles_n, g.str_tiles_b, g.nsplit_t, g.tps_t, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_GRADT));
+    split(g.own_tiles_s, g.str_tiles_b, g.nsplit_s, g.tps_s, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_SCORE));
     g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
     g.dsplit_t = (g.bf16 && g.rb == 1024) ? 2 : 1;
     return g;

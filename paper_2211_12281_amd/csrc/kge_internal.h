@@ -44,6 +44,13 @@ constexpr int kge_block_ow(bool bf16, int rb, bool transh, int mode, int kind) {
     return (mode == KGE_MODE_GRADT && kind == KGE_KIND_DIST) ? 1 : 2;
 }
 
+// Workgroups of a block-kernel pass that share a compute unit: the SCORE pass keeps no gradient
+// accumulators and fits two, where two ring stages of its tiles fit in half of the LDS.
+constexpr int kge_block_occ(bool bf16, int rb, bool transh, int mode) {
+    (void)bf16;
+    return (mode == KGE_MODE_SCORE && !transh && KGE_STREAM_TILE * rb <= 32 * 1024) ? 2 : 1;
+}
+
 // Per-row side information of the queries: squared norm of q, c = w.q (TransH), the per-row
 // constant K of the gradient coefficient exp2(x * log2e + K) (log2 domain), squared norm of the
 // (rounded) TransH normal.
