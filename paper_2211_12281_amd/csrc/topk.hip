@@ -339,15 +339,70 @@ __device__ double canonical_key(int scorer, int d, const void *ent, int64_t hoff
     return acc;
 }
 
+// One wave re-scores 64 survivors of one query, lane = survivor, so that the 64 sequential fp64 chains run in
+// lockstep.  The candidate rows arrive through the LDS in chunks of 64 columns: coalesced row reads on the way
+// in, conflict-free column reads (row stride odd in dwords) on the way out; the query's factor of a column
+// (h r, or h + r, exact in fp64) is computed once per wave.  The key is the one of canonical_key, term by term.
 template <bool BF16>
-__global__ void topk_rescore_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q, int64_t cand_lo,
-                                    const int32_t *cnt, const uint2 *buf, int KP, double *keyd) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int q = (int)(t / KP), s = (int)(t % KP);
-    if (q >= Q || s >= cnt[q]) return;
-    const int64_t cand = cand_lo + buf[(size_t)q * KP + s].y;
-    keyd[(size_t)q * KP + s] = canonical_key<BF16>(m.scorer, m.dim, m.ent, (int64_t)h[q] * m.ent_ld, m.rel,
-                                                   (int64_t)r[q] * m.rel_ld, cand * m.ent_ld);
+__global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q,
+                                                           int64_t cand_lo, const int32_t *cnt, const uint2 *buf, int KP,
+                                                           double *keyd) {
+    constexpr int DW = BF16 ? 32 : 64;                  // dwords per row chunk of 64 columns
+    __shared__ uint32_t rows[4][64 * (DW + 1)];
+    __shared__ double qd[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int groups = KP / 64;
+    const int64_t task = (int64_t)blockIdx.x * 4 + wave;
+    const int q = (int)(task / groups), s0 = (int)(task % groups) * 64;
+    if (q >= Q) return;
+    const int n = cnt[q];
+    if (s0 >= n) return;
+    const bool valid = s0 + lane < n;
+    const int64_t cand = cand_lo + buf[(size_t)q * KP + (valid ? s0 + lane : s0)].y;
+    const int d = m.dim;
+    const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
+    uint32_t *mine = rows[wave];
+    double acc = 0.0;
+    for (int c0 = 0; c0 < d; c0 += 64) {
+        const int cols = d - c0 < 64 ? d - c0 : 64;
+        if (lane < cols) {
+            const double hv = (double)El<BF16>::ld(m.ent, hoff + c0 + lane), rv = (double)El<BF16>::ld(m.rel, roff + c0 + lane);
+            qd[wave][lane] = m.scorer == KGE_DISTMULT ? hv * rv : hv + rv;
+        }
+        constexpr int RPI = 64 / DW;                    // rows per wave-wide load
+        const int sub = lane / DW, dw = lane % DW;
+        for (int rr = 0; rr < 64; rr += RPI) {
+            const int64_t c = __shfl(cand, rr + sub);
+            uint32_t v = 0u;
+            if (dw * (BF16 ? 2 : 1) < cols)
+                v = *(const uint32_t *)((const char *)m.ent + (c * m.ent_ld + c0) * (BF16 ? 2 : 4) + dw * 4);
+            mine[(rr + sub) * (DW + 1) + dw] = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint32_t *row = mine + lane * (DW + 1);
+        if (m.scorer == KGE_DISTMULT) {
+            for (int j = 0; j < cols; ++j) {
+                float tv;
+                if constexpr (BF16) tv = __uint_as_float((j & 1) ? (row[j >> 1] & 0xffff0000u) : (row[j >> 1] << 16));
+                else tv = __uint_as_float(row[j]);
+                acc = fma(qd[wave][j], (double)tv, acc);
+            }
+        } else {
+            for (int j = 0; j < cols; ++j) {
+                float tv;
+                if constexpr (BF16) tv = __uint_as_float((j & 1) ? (row[j >> 1] & 0xffff0000u) : (row[j >> 1] << 16));
+                else tv = __uint_as_float(row[j]);
+                const double x = qd[wave][j] - (double)tv;
+                acc = fma(x, x, acc);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    if (valid) keyd[(size_t)q * KP + s0 + lane] = m.scorer == KGE_DISTMULT ? -acc : acc;
 }
 
 struct QInfo { double qn; float eps_a, eps_b; float pad; };   // |q~|^2 (fp64), rounding-bound coefficients
@@ -674,11 +729,11 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
     const int64_t nres = Q * p.KP;
     const int final_lds = p.KPP * 12;
     if (p.bf16) {
-        hipLaunchKernelGGL(topk_rescore_kernel<true>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_rescore_kernel<true>, dim3((unsigned)((nres / 64 + 3) / 4)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
         hipLaunchKernelGGL(topk_final_kernel<true>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.keep, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
         hipLaunchKernelGGL(topk_exact_kernel<true>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
     } else {
-        hipLaunchKernelGGL(topk_rescore_kernel<false>, dim3((unsigned)((nres + 255) / 256)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_rescore_kernel<false>, dim3((unsigned)((nres / 64 + 3) / 4)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
         hipLaunchKernelGGL(topk_final_kernel<false>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.keep, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
         hipLaunchKernelGGL(topk_exact_kernel<false>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
     }
