@@ -285,19 +285,35 @@ __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *
     const int q = blockIdx.x;
     if (q >= Q) return;
     const int kept = keepcnt[q];
-    if (threadIdx.x == 0) { total = kept; over = 0; }
+    __shared__ int abase[512 + 1];                          // start of every area's entries in the sort buffer
+    const int nareas = nsplit * 2;                          // <= 2 * nseg <= 512
+    if (threadIdx.x == 0) over = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < kept; i += blockDim.x) { const uint2 e = keep[(size_t)q * KP + i]; s[i] = pack_value(e.x, e.y); }
-    // areas are appended in (split, half) order; the order does not matter: the sort below is total
-    for (int a2 = threadIdx.x; a2 < nsplit * 2; a2 += blockDim.x) {
+    // counts (clamped to the area size), then their exclusive prefix sums behind the kept list
+    for (int a2 = threadIdx.x; a2 < nareas; a2 += blockDim.x) {
         int c = segcnt[(size_t)q * nseg * 2 + a2];
         if (c > TK_HALF) { over = 1; c = TK_HALF; }
-        if (c > 0) {
-            const int base = atomicAdd(&total, c);
-            if (base + c <= TK_SORTCAP) {
-                const uint2 *src = seg + ((size_t)q * nseg * 2 + a2) * TK_HALF;
-                for (int i = 0; i < c; ++i) s[base + i] = pack_value(src[i].x, src[i].y);
-            } else over = 1;
+        abase[a2 + 1] = c;
+    }
+    if (threadIdx.x == 0) abase[0] = kept;
+    __syncthreads();
+    if (threadIdx.x == 0) { for (int a2 = 0; a2 < nareas; ++a2) abase[a2 + 1] += abase[a2]; total = abase[nareas]; }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kept; i += blockDim.x) { const uint2 e = keep[(size_t)q * KP + i]; s[i] = pack_value(e.x, e.y); }
+    // the areas are copied by 64 threads each, four at a time (the order does not matter: the sort below is total)
+    {
+        const int sub = threadIdx.x >> 6, li = threadIdx.x & 63;
+        for (int a0 = 0; a0 < nareas; a0 += 4) {
+            const int a2 = a0 + sub;
+            if (a2 < nareas) {
+                const int base = abase[a2], c = abase[a2 + 1] - base;
+                if (li < c) {
+                    if (base + c <= TK_SORTCAP) {
+                        const uint2 e = seg[((size_t)q * nseg * 2 + a2) * TK_HALF + li];
+                        s[base + li] = pack_value(e.x, e.y);
+                    } else over = 1;
+                }
+            }
         }
     }
     __syncthreads();
@@ -568,7 +584,8 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     }
 }
 
-// squared norms of the candidate rows and their maximum: a wave walks rows, one atomic per wave
+// squared norms of the candidate rows and their maximum, one atomic per wave.  Fast path (rows of 16-byte
+// aligned power-of-two length): a lane reads 16 bytes, a wave 64 / LPR rows per step, four steps in flight.
 template <bool BF16>
 __global__ void topk_tnorm_kernel(const char *ent, int64_t stride, int d, int64_t ncand, int64_t npad, float *tn,
                                   uint32_t *tmax_bits) {
@@ -576,13 +593,46 @@ __global__ void topk_tnorm_kernel(const char *ent, int64_t stride, int d, int64_
     const int64_t wid = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int64_t nw = (int64_t)gridDim.x * (blockDim.x >> 6);
     float mx = 0.f;
-    for (int64_t c = wid; c < npad; c += nw) {
-        float s = 0.f;
-        if (c < ncand) for (int j = lane; j < d; j += 64) { const float v = El<BF16>::ld(ent + c * stride, j); s += v * v; }
-        s = kge_wave_sum(s);
-        if (lane == 0) tn[c] = s;
-        mx = fmaxf(mx, s);
+    const int rowb = d * (BF16 ? 2 : 4), lpr = rowb / 16;           // lanes per row
+    const bool fast = rowb % 16 == 0 && lpr <= 64 && (lpr & (lpr - 1)) == 0 && stride % 16 == 0 && ((uintptr_t)ent & 15) == 0;
+    if (fast) {
+        const int rpw = 64 / lpr, sub = lane / lpr, li = lane % lpr;    // rows per wave step
+        constexpr int U = 4;
+        for (int64_t c0 = wid * rpw * U; c0 < npad; c0 += nw * rpw * U) {
+            kge_u32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t c = c0 + u * rpw + sub;
+                v[u] = kge_u32x4{0u, 0u, 0u, 0u};
+                if (c < ncand) v[u] = *(const kge_u32x4 *)(ent + c * stride + li * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if constexpr (BF16) {
+                        const float a0 = __uint_as_float(v[u][k] << 16), a1 = __uint_as_float(v[u][k] & 0xffff0000u);
+                        s += a0 * a0; s += a1 * a1;
+                    } else { const float a0 = __uint_as_float(v[u][k]); s += a0 * a0; }
+                }
+                for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o);
+                const int64_t c = c0 + u * rpw + sub;
+                if (li == 0 && c < npad) tn[c] = s;
+                mx = fmaxf(mx, s);
+            }
+        }
+    } else {
+        for (int64_t c = wid; c < npad; c += nw) {
+            float s = 0.f;
+            if (c < ncand) for (int j = lane; j < d; j += 64) { const float v = El<BF16>::ld(ent + c * stride, j); s += v * v; }
+            s = kge_wave_sum(s);
+            if (lane == 0) tn[c] = s;
+            mx = fmaxf(mx, s);
+        }
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
     if (lane == 0) atomicMax(tmax_bits, __float_as_uint(mx));    // mx >= 0: bit order = value order
 }
 
