@@ -42,6 +42,7 @@ def lib():
         _lib.orc_loss_bwd.restype = C.c_double
         _lib.orc_l3_norm.restype = C.c_double
         _lib.orc_cbrt_weight.restype = C.c_uint64
+        _lib.orc_encode.restype = C.c_double
         _lib.orc_bf16_rne.restype = C.c_uint16
     return _lib
 
@@ -245,3 +246,32 @@ def sample_negatives_sharded(seed, step, tag, part_size, n_ent, D, per_shard):
     lib().orc_sample_negatives_sharded(C.c_uint64(seed), C.c_uint64(step), C.c_uint32(tag), C.c_int64(part_size),
                                        C.c_int64(n_ent), C.c_int(D), C.c_int64(per_shard), _p(out, C.c_int32))
     return out
+
+
+def encode(ent_s, feat, m_h, m_t, idx, B, N, p=0.0, seed=0, step=0, tag=0, reg_t=0.0, reg_s=0.0, reg_f=0.0):
+    """Feature-projection encoder (Section 3.1, eq. (embedding)) over the 2B+N slots: (reg value, proj, e)."""
+    ent_s, feat, m_h, m_t, idx = _f32(ent_s), _f32(feat), _f32(m_h), _f32(m_t), _i32(idx)
+    d, fd, n = ent_s.shape[1], feat.shape[1], 2 * B + N
+    proj = np.zeros((n, d), dtype=np.float64)
+    e = np.zeros((n, d), dtype=np.float64)
+    om = lib().orc_encode(C.c_int(d), C.c_int(fd), _p(ent_s, C.c_float), _p(feat, C.c_float), _p(m_h, C.c_float),
+                          _p(m_t, C.c_float), _p(idx, C.c_int32), C.c_int64(B), C.c_int64(N), C.c_double(p),
+                          C.c_uint64(seed), C.c_uint64(step), C.c_uint32(tag), C.c_double(reg_t), C.c_double(reg_s),
+                          C.c_double(reg_f), _p(proj, C.c_double), _p(e, C.c_double))
+    return float(om), proj, e
+
+
+def encode_bwd(ent_s, feat, m_h, m_t, idx, B, N, de, p=0.0, seed=0, step=0, tag=0, reg_t=0.0, reg_s=0.0, reg_f=0.0):
+    """Backward of encode: (g_s [(2B+N), d], g_mh [d, fd], g_mt [d, fd])."""
+    ent_s, feat, m_h, m_t, idx = _f32(ent_s), _f32(feat), _f32(m_h), _f32(m_t), _i32(idx)
+    d, fd, n = ent_s.shape[1], feat.shape[1], 2 * B + N
+    de = np.ascontiguousarray(de, dtype=np.float64)
+    g_s = np.zeros((n, d), dtype=np.float64)
+    g_mh = np.zeros((d, fd), dtype=np.float64)
+    g_mt = np.zeros((d, fd), dtype=np.float64)
+    lib().orc_encode_bwd(C.c_int(d), C.c_int(fd), _p(ent_s, C.c_float), _p(feat, C.c_float), _p(m_h, C.c_float),
+                         _p(m_t, C.c_float), _p(idx, C.c_int32), C.c_int64(B), C.c_int64(N), C.c_double(p),
+                         C.c_uint64(seed), C.c_uint64(step), C.c_uint32(tag), C.c_double(reg_t), C.c_double(reg_s),
+                         C.c_double(reg_f), _p(de, C.c_double), _p(g_s, C.c_double), _p(g_mh, C.c_double),
+                         _p(g_mt, C.c_double))
+    return g_s, g_mh, g_mt

@@ -771,3 +771,90 @@ void orc_sample_negatives_sharded(uint64_t seed, uint64_t step, uint32_t tag, in
         out[i] = (int32_t)(lo + (int64_t)(uint64_t)(((unsigned __int128)x * (uint64_t)(hi - lo)) >> 64));
     }
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Feature-projection encoder (Section 3.1 "Encoder", eq. (embedding))                         */
+/* ------------------------------------------------------------------------------------------ */
+
+/* Dropout mask of element (slot, column): Philox4x32-10, key = seed, counter (slot_lo, slot_hi / column block,
+   step, tag): counter = (slot, column / 4, step, tag), word column % 4; the element is KEPT when its word is
+   >= floor(p * 2^32) and then scaled by 1 / (1 - p) (Section 3.1 "Regularisation": dropout on the linear
+   projections before they are summed with the shallow embedding).  p = 0 keeps everything. */
+static double orc_dropout_factor(uint64_t seed, uint64_t step, uint32_t tag, int64_t slot, int col, double p)
+{
+    if (p <= 0.0) return 1.0;
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t ctr[4] = { (uint32_t)slot, (uint32_t)(col / 4), (uint32_t)step, tag };
+    uint32_t w[4];
+    orc_philox4x32_10(ctr, key, w);
+    uint32_t thr = (uint32_t)floor(p * 4294967296.0);
+    return w[col % 4] >= thr ? 1.0 / (1.0 - p) : 0.0;
+}
+
+/* Forward over the 2B + N gathered slots (heads, positive tails, shared negatives):
+     proj[i] = M f_i          (M = M_H for the B head slots, M_T for the others; f_i the slot's feature row)
+     e[i]    = s_i + D_i o proj[i]      (s_i the slot's shallow embedding, D the dropout factors)
+   and the regulariser value reg_t sum ||e_i||_3 + reg_s sum ||s_i||_3 + reg_f sum ||proj_i||_3.
+   idx: the 2B + N entity ids in slot order.  proj, e: [(2B+N), d] fp64. */
+double orc_encode(int d, int fd, const float *ent_s, const float *feat, const float *m_h, const float *m_t,
+                  const int32_t *idx, int64_t B, int64_t N, double p, uint64_t seed, uint64_t step, uint32_t tag,
+                  double reg_t, double reg_s, double reg_f, double *proj, double *e)
+{
+    int64_t n = 2 * B + N;
+    double omega = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        const float *M = i < B ? m_h : m_t;
+        const float *f = feat + (int64_t)idx[i] * fd, *s = ent_s + (int64_t)idx[i] * d;
+        double t3 = 0.0, s3 = 0.0, f3 = 0.0;
+        for (int j = 0; j < d; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < fd; ++k) acc += (double)M[(int64_t)j * fd + k] * (double)f[k];
+            proj[i * d + j] = acc;
+            double ev = (double)s[j] + orc_dropout_factor(seed, step, tag, i, j, p) * acc;
+            e[i * d + j] = ev;
+            t3 += fabs(ev) * ev * ev; s3 += fabs((double)s[j]) * (double)s[j] * (double)s[j]; f3 += fabs(acc) * acc * acc;
+        }
+        omega += reg_t * cbrt(t3) + reg_s * cbrt(s3) + reg_f * cbrt(f3);
+    }
+    return omega;
+}
+
+static void orc_l3_grad_d(int d, const double *x, double lambda, double *g)
+{
+    double s = 0.0;
+    for (int j = 0; j < d; ++j) s += fabs(x[j]) * x[j] * x[j];
+    double nrm = cbrt(s);
+    if (nrm > 0.0)
+        for (int j = 0; j < d; ++j) g[j] += lambda * (x[j] < 0.0 ? -1.0 : 1.0) * x[j] * x[j] / (nrm * nrm);
+}
+
+/* Backward: de [(2B+N), d] is the gradient of the loss with respect to e.  With e = s + D o proj, proj = M f:
+     de' = de + reg_t grad||e||_3;   g_s = de' + reg_s grad||s||_3;   dproj = D o de' + reg_f grad||proj||_3;
+     g_mh = sum over head slots of dproj_i f_i^t,   g_mt = the same over the tail and negative slots. */
+void orc_encode_bwd(int d, int fd, const float *ent_s, const float *feat, const float *m_h, const float *m_t,
+                    const int32_t *idx, int64_t B, int64_t N, double p, uint64_t seed, uint64_t step, uint32_t tag,
+                    double reg_t, double reg_s, double reg_f, const double *de, double *g_s, double *g_mh,
+                    double *g_mt)
+{
+    int64_t n = 2 * B + N;
+    double *proj = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)d);
+    double *e = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)d);
+    orc_encode(d, fd, ent_s, feat, m_h, m_t, idx, B, N, p, seed, step, tag, 0.0, 0.0, 0.0, proj, e);
+    memset(g_mh, 0, sizeof(double) * (size_t)d * (size_t)fd);
+    memset(g_mt, 0, sizeof(double) * (size_t)d * (size_t)fd);
+    double *dep = (double *)malloc(sizeof(double) * (size_t)d), *dpr = (double *)malloc(sizeof(double) * (size_t)d);
+    double *sd = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int64_t i = 0; i < n; ++i) {
+        const float *f = feat + (int64_t)idx[i] * fd, *s = ent_s + (int64_t)idx[i] * d;
+        double *gm = i < B ? g_mh : g_mt;
+        for (int j = 0; j < d; ++j) { dep[j] = de[i * d + j]; sd[j] = (double)s[j]; }
+        orc_l3_grad_d(d, e + i * d, reg_t, dep);
+        for (int j = 0; j < d; ++j) g_s[i * d + j] = dep[j];
+        orc_l3_grad_d(d, sd, reg_s, g_s + i * d);
+        for (int j = 0; j < d; ++j) dpr[j] = orc_dropout_factor(seed, step, tag, i, j, p) * dep[j];
+        orc_l3_grad_d(d, proj + i * d, reg_f, dpr);
+        for (int j = 0; j < d; ++j)
+            for (int k = 0; k < fd; ++k) gm[(int64_t)j * fd + k] += dpr[j] * (double)f[k];
+    }
+    free(proj); free(e); free(dep); free(dpr); free(sd);
+}
