@@ -43,7 +43,7 @@ typedef enum { KGE_TRANSE = 0, KGE_TRANSH = 1, KGE_ROTATE = 2, KGE_DISTMULT = 3,
 typedef enum { KGE_LOGSIGMOID = 0, KGE_SAMPLED_SOFTMAX = 1 } kge_loss_t;
 typedef enum { KGE_F32 = 0, KGE_BF16 = 1 } kge_dtype_t;
 typedef enum { KGE_OP_SCORE = 0, KGE_OP_LOSS_BWD = 1, KGE_OP_SPARSE_ADAM = 2, KGE_OP_TOPK = 3,
-               KGE_OP_PARTITION = 4, KGE_OP_SAMPLER_BUILD = 5 } kge_op_t;
+               KGE_OP_PARTITION = 4, KGE_OP_SAMPLER_BUILD = 5, KGE_OP_ENCODE = 6, KGE_OP_ENCODE_BWD = 7 } kge_op_t;
 
 enum {
     KGE_OK = 0,
@@ -223,12 +223,62 @@ int kge_sample_negatives_sharded(uint64_t seed, uint64_t step, uint32_t stream_t
                                  void *hip_stream);
 
 /*
+ * Feature-projection encoder (Section 3.1 "Encoder", eq. (embedding)): the final embedding of an entity is
+ *     e = e_S + M_H e_F  as a head,    e = e_S + M_T e_F  as a tail,
+ * e_S the trainable shallow row, e_F the entity's fixed text-feature row, M_H, M_T trainable [dim, feat_dim]
+ * projections (they may alias).  Dropout with probability `dropout` acts on the projection before the sum,
+ * and the L3 norms of e, e_S and M e_F are regularised with weights reg_t, reg_s, reg_f (Section 3.1
+ * "Regularisation").  Dropout mask of element (slot, column): Philox4x32-10, key = seed, counter
+ * (slot, column / 4, step, dropout_tag), word column % 4; kept iff word >= floor(dropout * 2^32), then
+ * scaled by 1 / (1 - dropout).
+ *
+ * kge_encode works on the 2B + N gathered slots of a micro-batch in the order heads (B, M_H), positive tails
+ * (B, M_T), shared negatives (N, M_T) and writes
+ *   e_out     [(2B+N), dim] in the encoder's dtype, row stride dim: a compact entity table for kge_score /
+ *             kge_loss_bwd with h = 0..B-1, t = B..2B-1, neg = 2B..2B+N-1
+ *   proj_out  float[(2B+N) * dim]  the projections M e_F (before dropout); kge_encode_bwd takes them back
+ *   reg_out   float[1] (may be NULL) reg_t sum ||e||_3 + reg_s sum ||e_S||_3 + reg_f sum ||M e_F||_3
+ * kge_encode_bwd takes de = float[(2B+N) * dim], the gradient of the loss with respect to e_out's rows (the
+ * g_ent of kge_loss_bwd on the compact table), and writes
+ *   g_es      float[(2B+N) * dim]  gradient rows of the shallow embeddings, one per slot (target rows: h, t, neg;
+ *             duplicates not merged - kge_sparse_adam does that), regulariser terms included
+ *   g_mh, g_mt float[dim * feat_dim] dense gradients of M_H and M_T (add them when the two alias)
+ * With bf16 tables the projections run on the bf16 matrix cores with fp32 accumulation, and the backward
+ * contraction rounds its left operand to bf16.  Limits: dim <= 512, feat_dim <= 1024, both multiples of 16
+ * (bf16) / 8 (fp32); rows of feat, m_h, m_t 16-byte aligned.  step < 2^32.
+ */
+typedef struct {
+    int32_t dtype;         /* kge_dtype_t of ent_s, feat, m_h, m_t as the kernels read them */
+    int32_t dim;           /* d */
+    int32_t feat_dim;      /* |e_F| (768 in the paper) */
+    uint32_t dropout_tag;  /* stream tag of the dropout generator */
+    int64_t n_ent;
+    const void *ent_s;     /* [n_ent, ent_ld] */
+    const void *feat;      /* [n_ent, feat_ld] */
+    const void *m_h, *m_t; /* [dim, m_ld] */
+    int64_t ent_ld, feat_ld, m_ld;
+    float dropout;         /* in [0, 1) */
+    float reg_t, reg_s, reg_f;
+} kge_encoder_t;
+
+int kge_encode(const kge_encoder_t *enc, const int32_t *h, const int32_t *t, int64_t B, const int32_t *neg,
+               int64_t N, uint64_t seed, uint64_t step, void *e_out, float *proj_out, float *reg_out,
+               void *ws, size_t ws_bytes, void *hip_stream);
+int kge_encode_bwd(const kge_encoder_t *enc, const int32_t *h, const int32_t *t, int64_t B,
+                   const int32_t *neg, int64_t N, uint64_t seed, uint64_t step, const float *proj,
+                   const float *de, float *g_es, float *g_mh, float *g_mt, void *ws, size_t ws_bytes,
+                   void *hip_stream);
+/* Workspace of the two calls above (op = KGE_OP_ENCODE or KGE_OP_ENCODE_BWD); 0 for invalid arguments. */
+size_t kge_encode_workspace_bytes(int op, const kge_encoder_t *enc, int64_t B, int64_t N);
+
+/*
  * Workspace size in bytes for one call (pure function; host only).  Meaning of (B, N, K):
  *   KGE_OP_SCORE, KGE_OP_LOSS_BWD  B triples, N shared negatives, K unused
  *   KGE_OP_SPARSE_ADAM             B = M gradient rows, N = dim, K unused; model may be NULL
  *   KGE_OP_TOPK                    B = Q queries, N = number of candidates, K
  *   KGE_OP_PARTITION               B = n triples, N = D; model may be NULL
  *   KGE_OP_SAMPLER_BUILD           B = n triples, N = D; model may be NULL
+ *   KGE_OP_ENCODE, KGE_OP_ENCODE_BWD  see kge_encode_workspace_bytes (these two take a kge_encoder_t)
  * Returns 0 for an invalid request.
  */
 size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t N, int64_t K);

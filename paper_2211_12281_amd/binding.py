@@ -15,11 +15,19 @@ LIB_PATH = os.path.join(_HERE, "libkge_mi355x.so")
 
 SCORERS = {"transe": 0, "transh": 1, "rotate": 2, "distmult": 3, "complex": 4}
 LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
-OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION, OP_SAMPLER_BUILD = 0, 1, 2, 3, 4, 5
+OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION, OP_SAMPLER_BUILD, OP_ENCODE, OP_ENCODE_BWD = range(8)
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
            "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
+           "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5}
+
+
+class KgeEncoderT(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("dim", C.c_int32), ("feat_dim", C.c_int32), ("dropout_tag", C.c_uint32),
+                ("n_ent", C.c_int64), ("ent_s", C.c_void_p), ("feat", C.c_void_p), ("m_h", C.c_void_p),
+                ("m_t", C.c_void_p), ("ent_ld", C.c_int64), ("feat_ld", C.c_int64), ("m_ld", C.c_int64),
+                ("dropout", C.c_float), ("reg_t", C.c_float), ("reg_s", C.c_float), ("reg_f", C.c_float)]
 
 
 class KgeModelT(C.Structure):
@@ -53,6 +61,12 @@ def load():
         if not os.path.exists(LIB_PATH):
             raise KgeError(f"{LIB_PATH} is missing: build it with `python -m paper_2211_12281_amd.build`")
         lib = C.CDLL(LIB_PATH)
+        lib.kge_encode.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_int64, C.c_uint64, C.c_uint64] + \
+            [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+        lib.kge_encode_bwd.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_int64, C.c_uint64, C.c_uint64] + \
+            [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+        lib.kge_encode_workspace_bytes.restype = C.c_size_t
+        lib.kge_encode_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64]
         lib.kge_sampler_build.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_int64, C.c_int32, C.c_int64] + \
             [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
         lib.kge_sample_triples.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
@@ -287,3 +301,47 @@ def sample_negatives_sharded(seed: int, step: int, stream_tag: int, part_size: i
     _check(load().kge_sample_negatives_sharded(seed, step, stream_tag, part_size, n_ent, D, per_shard, _ptr(out),
                                                _stream()), "kge_sample_negatives_sharded")
     return out
+
+
+class Encoder:
+    """kge_encoder_t over device tensors: shallow table, feature table, projections M_H, M_T (may be the same)."""
+
+    def __init__(self, ent_s, feat, m_h, m_t, dropout: float = 0.0, reg_t: float = 0.0, reg_s: float = 0.0,
+                 reg_f: float = 0.0, dropout_tag: int = 12):
+        assert ent_s.dtype == feat.dtype == m_h.dtype == m_t.dtype and ent_s.dtype in (torch.float32, torch.bfloat16)
+        self.ent_s, self.feat, self.m_h, self.m_t = ent_s, feat, m_h, m_t
+        self.dim, self.feat_dim = ent_s.shape[1], feat.shape[1]
+        self.ref = KgeEncoderT(1 if ent_s.dtype == torch.bfloat16 else 0, self.dim, self.feat_dim, dropout_tag, ent_s.shape[0], ent_s.data_ptr(),
+                               feat.data_ptr(), m_h.data_ptr(), m_t.data_ptr(), ent_s.stride(0), feat.stride(0),
+                               m_h.stride(0), dropout, reg_t, reg_s, reg_f)
+
+    def _ws(self, op, B, N, ws):
+        ws = ws or _default_ws
+        n = load().kge_encode_workspace_bytes(op, C.byref(self.ref), B, N)
+        if n == 0:
+            raise KgeError("kge_encode_workspace_bytes: invalid arguments")
+        return ws.get(n)
+
+    def encode(self, h, t, neg, seed: int = 0, step: int = 0, ws: Workspace | None = None):
+        """(e [(2B+N), dim] in the table dtype, proj fp32 [(2B+N), dim], reg fp32 [1])."""
+        B, N = h.numel(), neg.numel()
+        n = 2 * B + N
+        e = torch.empty((n, self.dim), dtype=self.ent_s.dtype, device="cuda")
+        proj = torch.empty((n, self.dim), dtype=torch.float32, device="cuda")
+        reg = torch.empty(1, dtype=torch.float32, device="cuda")
+        buf = self._ws(OP_ENCODE, B, N, ws)
+        _check(load().kge_encode(C.byref(self.ref), _ptr(_i32(h)), _ptr(_i32(t)), B, _ptr(_i32(neg)), N, seed, step,
+                                 _ptr(e), _ptr(proj), _ptr(reg), _ptr(buf), buf.numel(), _stream()), "kge_encode")
+        return e, proj, reg
+
+    def encode_bwd(self, h, t, neg, proj, de, seed: int = 0, step: int = 0, ws: Workspace | None = None):
+        """(g_es fp32 [(2B+N), dim], g_mh, g_mt fp32 [dim, feat_dim])."""
+        B, N = h.numel(), neg.numel()
+        g_es = torch.empty((2 * B + N, self.dim), dtype=torch.float32, device="cuda")
+        g_mh = torch.empty((self.dim, self.feat_dim), dtype=torch.float32, device="cuda")
+        g_mt = torch.empty_like(g_mh)
+        buf = self._ws(OP_ENCODE_BWD, B, N, ws)
+        _check(load().kge_encode_bwd(C.byref(self.ref), _ptr(_i32(h)), _ptr(_i32(t)), B, _ptr(_i32(neg)), N, seed, step,
+                                     _ptr(proj), _ptr(de), _ptr(g_es), _ptr(g_mh), _ptr(g_mt), _ptr(buf), buf.numel(),
+                                     _stream()), "kge_encode_bwd")
+        return g_es, g_mh, g_mt

@@ -14,6 +14,13 @@ int kge_run_partition(const int32_t *h, const int32_t *t, int64_t n, int64_t par
                       int64_t *order, void *ws, size_t ws_bytes, hipStream_t st);
 size_t kge_partition_ws(int64_t n, int D);
 size_t kge_sampler_ws(int64_t n);
+int kge_validate_encoder(const kge_encoder_t *e);
+size_t kge_encode_ws(const kge_encoder_t &e, int64_t B, int64_t N, bool bwd);
+int kge_run_encode(const kge_encoder_t &e, const int32_t *h, const int32_t *t, int64_t B, const int32_t *neg, int64_t N,
+                   uint64_t seed, uint64_t step, void *e_out, float *proj_out, float *reg_out, void *ws, hipStream_t st);
+int kge_run_encode_bwd(const kge_encoder_t &e, const int32_t *h, const int32_t *t, int64_t B, const int32_t *neg, int64_t N,
+                       uint64_t seed, uint64_t step, const float *proj, const float *de, float *g_es, float *g_mh, float *g_mt,
+                       void *ws, hipStream_t st);
 int kge_run_sampler_build(const int32_t *h, const int32_t *r, const int32_t *t, int64_t n, int64_t part_size, int D,
                           int64_t n_rel, int64_t *order, int64_t *rel_offsets, uint64_t *cdf, void *ws, hipStream_t st);
 int kge_run_sample_triples(uint64_t seed, uint64_t step, uint32_t tag, int64_t bucket_lo, int64_t draws, int64_t per_bucket,
@@ -196,6 +203,43 @@ int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int6
     if (n == 0) return KGE_OK;
     if (!out_idx) return KGE_E_INVALID_ARG;
     return kge_run_negatives(seed, step, stream_tag, lo, hi, n, out_idx, (hipStream_t)hip_stream);
+}
+
+size_t kge_encode_workspace_bytes(int op, const kge_encoder_t *enc, int64_t B, int64_t N) {
+    if ((op != KGE_OP_ENCODE && op != KGE_OP_ENCODE_BWD) || kge_validate_encoder(enc) != KGE_OK) return 0;
+    if (B < 0 || N < 0 || 2 * B + N >= (1ll << 30)) return 0;
+    return kge_encode_ws(*enc, B, N, op == KGE_OP_ENCODE_BWD);
+}
+
+int kge_encode(const kge_encoder_t *enc, const int32_t *h, const int32_t *t, int64_t B, const int32_t *neg, int64_t N,
+               uint64_t seed, uint64_t step, void *e_out, float *proj_out, float *reg_out, void *ws, size_t ws_bytes,
+               void *hip_stream) {
+    int rc = kge_validate_encoder(enc);
+    if (rc != KGE_OK) return rc;
+    if (B < 0 || N < 0 || 2 * B + N >= (1ll << 30) || step >= (1ull << 32)) return KGE_E_INVALID_ARG;
+    if (B > 0 && (!h || !t)) return KGE_E_INVALID_ARG;
+    if (N > 0 && !neg) return KGE_E_INVALID_ARG;
+    if (2 * B + N > 0 && (!e_out || !proj_out)) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (kge_encode_ws(*enc, B, N, false) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_encode(*enc, h, t, B, neg, N, seed, step, e_out, proj_out, reg_out, ws, (hipStream_t)hip_stream);
+}
+
+int kge_encode_bwd(const kge_encoder_t *enc, const int32_t *h, const int32_t *t, int64_t B, const int32_t *neg, int64_t N,
+                   uint64_t seed, uint64_t step, const float *proj, const float *de, float *g_es, float *g_mh, float *g_mt,
+                   void *ws, size_t ws_bytes, void *hip_stream) {
+    int rc = kge_validate_encoder(enc);
+    if (rc != KGE_OK) return rc;
+    if (B < 0 || N < 0 || 2 * B + N >= (1ll << 30) || step >= (1ull << 32)) return KGE_E_INVALID_ARG;
+    if (B > 0 && (!h || !t)) return KGE_E_INVALID_ARG;
+    if (N > 0 && !neg) return KGE_E_INVALID_ARG;
+    if (2 * B + N > 0 && (!proj || !de || !g_es)) return KGE_E_INVALID_ARG;
+    if (!g_mh || !g_mt) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (kge_encode_ws(*enc, B, N, true) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_encode_bwd(*enc, h, t, B, neg, N, seed, step, proj, de, g_es, g_mh, g_mt, ws, (hipStream_t)hip_stream);
 }
 
 int kge_sampler_build(const int32_t *h, const int32_t *r, const int32_t *t, int64_t n, int64_t part_size, int32_t D,
