@@ -39,6 +39,9 @@ def parse():
                     help="training workloads: draw every micro-batch on the GPU with the relation-aware sampler "
                          "(one worker's all-partition micro-batch and sharded negatives) from a synthetic list of "
                          "this many triples, instead of replaying pre-drawn index streams")
+    ap.add_argument("--encoder", type=int, default=0, metavar="FEAT_DIM",
+                    help="training workloads: entities are encoded as e_S + M e_F from synthetic text features of "
+                         "this width (768 in the paper) with dropout 0.1, trained M_H and M_T; default: shallow only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy first (reference for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -51,7 +54,7 @@ def parse():
 class TrainWorkload:
     """c3 / c5 / c1: forward + backward + sparse Adam on bf16 shadow / fp32 master tables."""
 
-    def __init__(self, name, P, scale, only=None, reg_l3=0.0, sampled=0):
+    def __init__(self, name, P, scale, only=None, reg_l3=0.0, sampled=0, feat_dim=0):
         import torch
         import kge_synth as ks
         import kge_synth.device as ksd
@@ -122,6 +125,24 @@ class TrainWorkload:
             self.loss_kw = dict(n_ent_for_c=self.n_ent)
         if reg_l3 > 0.0:
             self.loss_kw["reg_l3"] = reg_l3
+        self.enc = None
+        if feat_dim > 0:
+            # text features stand-ins: fixed U(-0.5, 0.5) rows; projections start at U(-0.05, 0.05)
+            tdt = torch.bfloat16 if self.bf16 else torch.float32
+            self.feat = torch.empty((self.n_ent, feat_dim), dtype=tdt, device=dev)
+            ksd.fill_uniform(self.feat, ks.BASE_SEED, 21, 0.5)
+            self.mproj = []
+            for tag in (22, 23):
+                m = torch.from_numpy(ks.uniform_rows(ks.BASE_SEED, tag, np.arange(self.d), feat_dim, 0.05)).to(dev)
+                self.mproj.append({"p": m, "m": torch.zeros_like(m), "v": torch.zeros_like(m),
+                                   "sh": m.to(torch.bfloat16) if self.bf16 else None})
+            tbl = lambda q: q["sh"] if self.bf16 else q["p"]
+            self.enc = kge.Encoder(self.ent_sh if self.bf16 else self.ent, self.feat, tbl(self.mproj[0]), tbl(self.mproj[1]),
+                                   dropout=0.1, reg_t=reg_l3)
+            self.feat_dim = feat_dim
+            self.rows_d = torch.arange(self.d, dtype=torch.int32, device=dev)
+            self.ar = torch.arange(2 * self.B + self.N, dtype=torch.int32, device=dev)
+            self.loss_kw.pop("reg_l3", None)               # the regulariser acts on the encoded e inside the encoder
         self.sampler = None
         if sampled > 0:
             # the paper's generator: worker i's micro-batch takes B/D triples from each bucket T_ij by the
@@ -154,10 +175,21 @@ class TrainWorkload:
         else:
             h, r, t, lo, hi = self.batches[i % len(self.batches)]
             kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=self.neg)
-        kge.loss_bwd(self.model, self.P["loss"], h, r, t, self.neg, out=self.out, **self.loss_kw)
         lr = self.P["lr"]
-        kge.sparse_adam(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent_idx"], self.out["g_ent"], lr,
-                        step=i + 1)
+        if self.enc is not None:
+            B, N = self.B, self.N
+            e, proj, _ = self.enc.encode(h, t, self.neg, seed=ks.BASE_SEED, step=i)
+            model = kge.Model(self.scorer, e, self.model.rel, self.model.relw)
+            kge.loss_bwd(model, self.P["loss"], self.ar[:B], r, self.ar[B:2 * B], self.ar[2 * B:], out=self.out, **self.loss_kw)
+            g_es, g_mh, g_mt = self.enc.encode_bwd(h, t, self.neg, proj, self.out["g_ent"], seed=ks.BASE_SEED, step=i)
+            idx = self.torch.cat([h, t, self.neg])
+            kge.sparse_adam(self.ent, self.ent_sh, self.ent_m, self.ent_v, idx, g_es, lr, step=i + 1)
+            for q, gm in zip(self.mproj, (g_mh, g_mt)):
+                kge.sparse_adam(q["p"], q["sh"], q["m"], q["v"], self.rows_d, gm, lr, step=i + 1)
+        else:
+            kge.loss_bwd(self.model, self.P["loss"], h, r, t, self.neg, out=self.out, **self.loss_kw)
+            kge.sparse_adam(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent_idx"], self.out["g_ent"], lr,
+                            step=i + 1)
         kge.sparse_adam(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel_idx"], self.out["g_rel"], lr,
                         step=i + 1)
         if self.relw is not None:
@@ -169,6 +201,8 @@ class TrainWorkload:
 
     def extra(self, ms):
         out = {"triples_per_s": self.B / (ms * 1e-3), "scorer": self.scorer, "reg_l3": self.loss_kw.get("reg_l3", 0.0)}
+        if self.enc is not None:
+            out["encoder"] = f"e_S + M e_F, synthetic features of width {self.feat_dim}, dropout 0.1, M_H and M_T trained"
         if self.sampler is not None:
             out["micro_batch"] = f"sampled on the GPU per step: {self.D} x {self.B // self.D} triples of one worker by the " \
                                  f"cube-root relation law from {self.n_triples} synthetic triples, {self.D} x " \
@@ -178,6 +212,8 @@ class TrainWorkload:
     def mfma_flops(self, slot):
         # algorithmic contractions of 2 B N d flop each: the FWD pass computes the scores AND the queries'
         # gradient (two), the GRADT pass the negatives' gradient (one; its recomputed scores earn no credit)
+        if slot in ("enc_fwd", "enc_bwd"):                 # projection of the 2B+N slots, or its gradient to M_H, M_T
+            return 2.0 * (2 * self.B + self.N) * self.feat_dim * self.d
         gemms = (2 if slot == "block_fwd" else 1) * (2 if self.scorer == "transh" else 1)
         return 2.0 * self.B * self.N * self.d * gemms
 
@@ -336,7 +372,7 @@ def main():
     kge.load()
     P = ks.PRESETS[a.workload]
     if a.workload in ("c1", "c3", "c5"):
-        wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3, a.sampled_batches)
+        wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3, a.sampled_batches, a.encoder)
     elif a.workload == "c2":
         wl = ScoreWorkload(P, a.scale, a.scorer)
     else:
@@ -369,7 +405,7 @@ def main():
     if prof:
         dom = max(prof, key=lambda k: prof[k]["total_ms"])
         avg_s = prof[dom]["avg_us"] * 1e-6
-        if dom.startswith("block") or dom == "topk_scan":
+        if dom.startswith("block") or dom.startswith("enc_") or dom == "topk_scan":
             flops = wl.mfma_flops(dom)
             if dom == "topk_scan":
                 avg_s = prof[dom]["total_ms"] * 1e-3 / (a.steps * len(wl.scorers))   # all chunk launches of one call
@@ -380,6 +416,15 @@ def main():
         else:
             roof = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": None, "traffic": None, "avg_us": avg_s * 1e6}
+
+    enc_roof = None
+    if "enc_fwd" in prof:                                  # the encoder's contractions against the same matrix peak
+        peak = PEAK_BF16_TFLOPS if wl.bf16 else PEAK_F32_TFLOPS
+        enc_roof = {}
+        for slot in ("enc_fwd", "enc_bwd"):
+            ach = wl.mfma_flops(slot) / (prof[slot]["avg_us"] * 1e-6) / 1e12
+            enc_roof[slot] = {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                              "avg_us": prof[slot]["avg_us"]}
 
     cpu = None
     if not a.no_cpu_baseline:
@@ -414,6 +459,8 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, "kernels": prof,
     }
     line.update(wl.extra(ms))
+    if enc_roof:
+        line["encoder_roofline"] = enc_roof
     print(json.dumps(line))
 
 

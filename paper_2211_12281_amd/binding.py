@@ -20,7 +20,8 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
            "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect"]
-PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5}
+PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
+              "enc_fwd": 6, "enc_bwd": 7}
 
 
 class KgeEncoderT(C.Structure):

@@ -15,13 +15,14 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 enc_bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float enc_f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float enc_f32x4;
+typedef uint32_t enc_u32x4 __attribute__((ext_vector_type(4)));   // (arrays of HIP's uint4 struct end up in scratch memory)
 
 namespace {
 
 constexpr int ENC_TILE = 128;          // rows and columns of a workgroup's output tile; slot counts are padded to it
 
 template <bool BF16>
-__device__ __forceinline__ enc_f32x16 enc_mma16(enc_f32x16 acc, uint4 a, uint4 b) {
+__device__ __forceinline__ enc_f32x16 enc_mma16(enc_f32x16 acc, enc_u32x4 a, enc_u32x4 b) {
     if constexpr (BF16) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(enc_bf16x8, a), __builtin_bit_cast(enc_bf16x8, b),
                                                        acc, 0, 0, 0);
@@ -33,65 +34,126 @@ __device__ __forceinline__ enc_f32x16 enc_mma16(enc_f32x16 acc, uint4 a, uint4 b
     }
 }
 
-// C[split][M, N] (fp32) = A[M, K] . B[N, K]^t over the k-steps of the split.  A k-step is 32 bytes of a row
-// (16 bf16 or 8 fp32); lane l of a fragment reads the 16 bytes at half l / 32 of row l % 32.  Rows at or
-// beyond m_valid / n_valid read as zero.  a_idx (optional) maps A's row number to a table row.
-// Workgroup = 128 x 128 outputs, wave = 64 x 64 (2 x 2 blocks of 32 x 32).
+// One contraction C[split][M, N] (fp32) = A[M, K] . B[N, K]^t, K counted in k-steps of 32 bytes of a row (16 bf16
+// or 8 fp32).  Rows at or beyond m_valid / n_valid read as zero.  A's row r is table row idx0[r] for r < n_idx0,
+// idx1[r - n_idx0] beyond (gather == 0: row r itself): the gather of the feature rows is part of the load.
+struct EncGemm {
+    const char *A; int64_t lda_b; const int32_t *idx0, *idx1; int n_idx0; int gather; int m_valid;
+    const char *B; int64_t ldb_b; int n_valid;
+    float *C; int64_t ldc, split_stride;
+    int ksteps, kps, nsplit, tiles_m, tiles_n;
+};
+// A launch runs two contractions (heads against M_H, tails and negatives against M_T) so that the chip is filled
+// once; workgroup ids enumerate (contraction, split, tile).
+struct EncGemmPair { EncGemm g[2]; int wgs0; };
+
+// Workgroup = 128 x 128 outputs, wave = 64 x 64 (2 x 2 blocks of 32 x 32).  Both operands pass through the LDS
+// in chunks of four k-steps (128 bytes of every row: each row is read from memory as one contiguous segment by
+// 8 lanes), double-buffered in the LDS and two chunks deep in registers: the loads of chunks c+1 and c+2 are in
+// flight while chunk c is multiplied.  A 128-byte LDS row keeps its 16-byte pieces XOR-swizzled by (row & 7), so
+// that the fragment reads of 8 consecutive rows fall into 8 different bank groups.  Fragment of (row block,
+// k-step): lane l reads piece 2 ks + l / 32 of row l % 32.
 template <bool BF16>
-__global__ __launch_bounds__(256) void enc_gemm_nt_kernel(const char *A, int64_t lda_b, const int32_t *a_idx, int m_valid,
-                                                          const char *Bm, int64_t ldb_b, int n_valid, float *C, int64_t ldc,
-                                                          int64_t c_split_stride, int ksteps, int ksteps_per_split) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lr = lane & 31, g = lane >> 5;
-    const int m0 = blockIdx.x * ENC_TILE + (wave & 1) * 64, n0 = blockIdx.y * ENC_TILE + (wave >> 1) * 64;
-    const int k_lo = blockIdx.z * ksteps_per_split, k_hi = min(ksteps, k_lo + ksteps_per_split);
-    const char *pa[2], *pb[2];
-    bool va[2], vb[2];
+__global__ __launch_bounds__(256) void enc_gemm_nt_kernel(const EncGemmPair pr) {
+    __shared__ __attribute__((aligned(16))) char lds[2][2][ENC_TILE * 128];      // [buffer][A, B][row][128 bytes]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
+    const bool second = (int)blockIdx.x >= pr.wgs0;
+    const EncGemm &q = pr.g[second ? 1 : 0];
+    int w = (int)blockIdx.x - (second ? pr.wgs0 : 0);
+    const int tn = w % q.tiles_n; w /= q.tiles_n;
+    const int tm = w % q.tiles_m, split = w / q.tiles_m;
+    const int m0 = tm * ENC_TILE, n0 = tn * ENC_TILE;
+    const int k_lo = split * q.kps, k_hi = min(q.ksteps, k_lo + q.kps);
+    // staging: thread t moves piece t % 8 of rows t / 8 + 32 j (j < 4) of both tiles
+    const int piece = tid & 7, srow = tid >> 3;
+    const char *ga[4], *gb[4];
+    bool va[4], vb[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = m0 + 32 * i + lr;
-        va[i] = row < m_valid;
-        const int64_t src = va[i] ? (a_idx ? (int64_t)a_idx[row] : (int64_t)row) : 0;
-        pa[i] = A + src * lda_b + g * 16;
-        const int col = n0 + 32 * i + lr;
-        vb[i] = col < n_valid;
-        pb[i] = Bm + (int64_t)(vb[i] ? col : 0) * ldb_b + g * 16;
+    for (int j = 0; j < 4; ++j) {
+        const int ra = m0 + srow + 32 * j, rb = n0 + srow + 32 * j;
+        va[j] = ra < q.m_valid; vb[j] = rb < q.n_valid;
+        int64_t src = 0;
+        if (va[j]) src = q.gather ? (ra < q.n_idx0 ? (int64_t)q.idx0[ra] : (int64_t)q.idx1[ra - q.n_idx0]) : (int64_t)ra;
+        ga[j] = q.A + src * q.lda_b + piece * 16;
+        gb[j] = q.B + (int64_t)(vb[j] ? rb : 0) * q.ldb_b + piece * 16;
     }
+    const enc_u32x4 zero = {0u, 0u, 0u, 0u};
+    enc_u32x4 sa[2][4], sb[2][4];                          // two chunks in flight
+    // chunk = k-steps [ks0, ks0 + 4); pieces past k_hi and rows past the valid ones read as zero.  The loads
+    // themselves are unconditional (a clamped, always valid address) so that all eight are in flight together;
+    // the zeros are selected afterwards.
+    auto gload = [&](int set, int ks0) {
+        const bool in = ks0 + (piece >> 1) < k_hi;
+        const int64_t kb = (int64_t)(in ? ks0 : k_lo) * 32 - (in ? 0 : (piece >> 1) * 32);   // piece 0/1 of k_lo when out
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            sa[set][j] = *(const enc_u32x4 *)(ga[j] + kb);
+            sb[set][j] = *(const enc_u32x4 *)(gb[j] + kb);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (!(in && va[j])) sa[set][j] = zero;
+            if (!(in && vb[j])) sb[set][j] = zero;
+        }
+    };
+    auto lstore = [&](int set, int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = srow + 32 * j, off = row * 128 + ((piece ^ (row & 7)) * 16);
+            *(enc_u32x4 *)(lds[buf][0] + off) = sa[set][j];
+            *(enc_u32x4 *)(lds[buf][1] + off) = sb[set][j];
+        }
+    };
     enc_f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
         for (int j = 0; j < 2; ++j)
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-    constexpr int U = 4;                                   // k-steps in flight
-    for (int ks = k_lo; ks < k_hi; ks += U) {
-        uint4 fa[U][2], fb[U][2];
+    const int wm = (wave & 1) * 64, wn = (wave >> 1) * 64;
+    auto compute = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool in = ks + u < k_hi;
+        for (int ks = 0; ks < 4; ++ks) {
+            enc_u32x4 fa[2], fb[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                fa[u][i] = (in && va[i]) ? *(const uint4 *)(pa[i] + (int64_t)(ks + u) * 32) : zero;
-                fb[u][i] = (in && vb[i]) ? *(const uint4 *)(pb[i] + (int64_t)(ks + u) * 32) : zero;
+                const int rowa = wm + 32 * i + lr, rowb = wn + 32 * i + lr;
+                fa[i] = *(const enc_u32x4 *)(lds[buf][0] + rowa * 128 + (((2 * ks + g) ^ (rowa & 7)) * 16));
+                fb[i] = *(const enc_u32x4 *)(lds[buf][1] + rowb * 128 + (((2 * ks + g) ^ (rowb & 7)) * 16));
             }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = enc_mma16<BF16>(acc[i][j], fa[u][i], fb[u][j]);
+                for (int j = 0; j < 2; ++j) acc[i][j] = enc_mma16<BF16>(acc[i][j], fa[i], fb[j]);
+        }
+    };
+    // chunk c lives in LDS buffer c % 2 and was loaded into register set c % 2
+    gload(0, k_lo);
+    gload(1, k_lo + 4);
+    lstore(0, 0);
+    __syncthreads();
+    for (int ks0 = k_lo; ks0 < k_hi; ks0 += 8) {
+        // even chunk: its register set is free again -> request chunk + 2; the odd chunk's registers go to the LDS
+        gload(0, ks0 + 8);
+        compute(0);
+        lstore(1, 1);
+        __syncthreads();
+        if (ks0 + 4 >= k_hi) break;
+        gload(1, ks0 + 12);
+        compute(1);
+        lstore(0, 0);
+        __syncthreads();
     }
     // accumulator layout: lane holds column lr of the B side; register e holds A-side row 8 (e/4) + 4 g + e%4
-    float *Cs = C + (int64_t)blockIdx.z * c_split_stride;
+    float *Cs = q.C + (int64_t)split * q.split_stride;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int col = n0 + 32 * j + lr;
+            const int col = n0 + wn + 32 * j + lr;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = m0 + 32 * i + 8 * (e >> 2) + 4 * g + (e & 3);
-                if (row < m_valid && col < n_valid) Cs[(int64_t)row * ldc + col] = acc[i][j][e];
+                const int row = m0 + wm + 32 * i + 8 * (e >> 2) + 4 * g + (e & 3);
+                if (row < q.m_valid && col < q.n_valid) Cs[(int64_t)row * q.ldc + col] = acc[i][j][e];
             }
         }
 }
@@ -161,21 +223,56 @@ __global__ void enc_reg_reduce_kernel(const float *regv, int n, int on, float *r
     if (threadIdx.x == 0) *reg_out = (float)sh[0];
 }
 
-// Column of slot i in the transposed buffers of the backward pass: heads first, padded to a tile, then the
-// tail and negative slots (the two groups contract against different projection matrices).
-__device__ __forceinline__ int enc_slot_col(int i, int B, int Bh) { return i < B ? i : Bh + (i - B); }
+// Transposed buffers of the backward pass: columns [0, Bh) hold the head slots (Bh = B padded to a tile), columns
+// [Bh, Bh + B + N) the tail and negative slots - the two groups contract against different projection matrices.
+// The row kernels below work on groups of 32 slots that never straddle the two sections: workgroup w takes head
+// slots 32 w .. if w < ceil(B / 32), else tail-section slots 32 (w - ceil(B / 32)) ..
+struct EncGroup { int slot0, count, col0; };      // first slot, valid slots (<= 32), first column
+__device__ __forceinline__ EncGroup enc_group(int w, int B, int N, int Bh) {
+    const int hg = (B + 31) / 32;
+    EncGroup gr;
+    if (w < hg) { gr.slot0 = 32 * w; gr.count = min(32, B - gr.slot0); gr.col0 = gr.slot0; }
+    else { const int o = 32 * (w - hg); gr.slot0 = B + o; gr.count = min(32, B + N - o); gr.col0 = Bh + o; }
+    return gr;
+}
 
-// backward rows (a workgroup takes 32 slots, a wave 8 of them in turn): de' = de + reg_t grad||e||,
+// 32 x len tile (fp32 in the LDS, row stride len + 1) -> rows of the transposed buffer, 8 columns per store
+template <bool BF16>
+__device__ __forceinline__ void enc_write_transposed(const float *tile, int ldt, int len, void *dst, int64_t ncols,
+                                                      const EncGroup &gr) {
+    // element (j, 8 q .. 8 q + 7): one 16-byte (bf16) or two 16-byte (fp32) stores; columns past the group's count
+    // are padding or belong to nobody (they stay zero / are written as zero)
+    for (int idx = threadIdx.x; idx < len * 4; idx += 256) {
+        const int j = idx >> 2, q = idx & 3;
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (8 * q + u < gr.count) ? tile[(8 * q + u) * ldt + j] : 0.f;
+        if (8 * q >= gr.count) continue;
+        char *p = (char *)dst + ((int64_t)j * ncols + gr.col0 + 8 * q) * (BF16 ? 2 : 4);
+        if constexpr (BF16) {
+            typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf2;
+            enc_u32x4 o;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { bf2 t = { (__bf16)v[2 * u], (__bf16)v[2 * u + 1] }; o[u] = __builtin_bit_cast(uint32_t, t); }
+            *(enc_u32x4 *)p = o;
+        } else {
+            *(enc_f32x4 *)p = enc_f32x4{v[0], v[1], v[2], v[3]};
+            *(enc_f32x4 *)(p + 16) = enc_f32x4{v[4], v[5], v[6], v[7]};
+        }
+    }
+}
+
+// backward rows (a workgroup takes a group of 32 slots, a wave 8 of them in turn): de' = de + reg_t grad||e||,
 // g_es = de' + reg_s grad||s||, dP = D o de' + reg_f grad||P||; dP leaves through the LDS as dP^t[d][columns]
 template <bool BF16>
 __global__ __launch_bounds__(256) void enc_bwd_rows_kernel(EncRowArgs a, const float *P, const float *de, float *g_es,
                                                            void *dPt, int Bh, int64_t ncols) {
     extern __shared__ float tile[];                        // [32][d + 1]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = 2 * a.B + a.N;
-    const int i0 = blockIdx.x * 32, ldt = a.d + 1;
-    for (int r = wave; r < 32; r += 4) {
-        const int i = i0 + r;
-        if (i >= n) { for (int j = lane; j < a.d; j += 64) tile[r * ldt + j] = 0.f; continue; }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const EncGroup gr = enc_group(blockIdx.x, a.B, a.N, Bh);
+    const int ldt = a.d + 1;
+    for (int r = wave; r < gr.count; r += 4) {
+        const int i = gr.slot0 + r;
         const int64_t soff = (int64_t)enc_slot_entity(a, i) * a.ent_ld;
         float pv[KGE_MAXJ], sv[KGE_MAXJ], ev[KGE_MAXJ], dv[KGE_MAXJ], Df[KGE_MAXJ];
         float ct = 0.f, cs = 0.f, cf = 0.f;
@@ -203,34 +300,45 @@ __global__ __launch_bounds__(256) void enc_bwd_rows_kernel(EncRowArgs a, const f
         }
     }
     __syncthreads();
-    // transposed write-out: row j of dP^t gets the 32 slots of this workgroup (they are contiguous columns unless
-    // the group straddles the head / tail boundary, hence the per-slot column)
-    for (int idx = threadIdx.x; idx < a.d * 32; idx += 256) {
-        const int j = idx >> 5, r = idx & 31, i = i0 + r;
-        if (i < n) El<BF16>::st(dPt, (int64_t)j * ncols + enc_slot_col(i, a.B, Bh), tile[r * ldt + j]);
-    }
+    enc_write_transposed<BF16>(tile, ldt, a.d, dPt, ncols, gr);
 }
 
-// F^t[f][columns] of the gathered slots (a workgroup takes 32 slots)
+// F^t[f][columns] of the gathered slots (a workgroup takes a group of 32 slots); rows are read with 16-byte loads
 template <bool BF16>
 __global__ __launch_bounds__(256) void enc_gather_t_kernel(EncRowArgs a, const void *feat, int64_t feat_ld, int fd, void *Ft,
                                                            int Bh, int64_t ncols) {
     extern __shared__ float tile[];                        // [32][fd + 1]
-    const int n = 2 * a.B + a.N, i0 = blockIdx.x * 32, ldt = fd + 1;
-    for (int idx = threadIdx.x; idx < 32 * fd; idx += 256) {
-        const int r = idx / fd, k = idx % fd, i = i0 + r;
-        tile[r * ldt + k] = i < n ? El<BF16>::ld(feat, (int64_t)enc_slot_entity(a, i) * feat_ld + k) : 0.f;
+    const EncGroup gr = enc_group(blockIdx.x, a.B, a.N, Bh);
+    const int ldt = fd + 1;
+    constexpr int EPV = BF16 ? 8 : 4;                      // elements per 16 bytes
+    const int ppr = fd / EPV;                              // 16-byte pieces per row
+    for (int idx = threadIdx.x; idx < gr.count * ppr; idx += 256) {
+        const int r = idx / ppr, pc = idx % ppr;
+        const char *src = (const char *)feat + ((int64_t)enc_slot_entity(a, gr.slot0 + r) * feat_ld + pc * EPV) * (BF16 ? 2 : 4);
+        const enc_u32x4 v = *(const enc_u32x4 *)src;
+        float *dst = tile + r * ldt + pc * EPV;
+        if constexpr (BF16) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { dst[2 * u] = __uint_as_float(v[u] << 16); dst[2 * u + 1] = __uint_as_float(v[u] & 0xffff0000u); }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dst[u] = __uint_as_float(v[u]);
+        }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < fd * 32; idx += 256) {
-        const int k = idx >> 5, r = idx & 31, i = i0 + r;
-        if (i < n) El<BF16>::st(Ft, (int64_t)k * ncols + enc_slot_col(i, a.B, Bh), tile[r * ldt + k]);
-    }
+    enc_write_transposed<BF16>(tile, ldt, fd, Ft, ncols, gr);
 }
 
-__global__ void enc_zero_kernel(uint32_t *p, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
+// the padding columns [B, Bh) and [Bh + B + N, ncols) of the transposed buffers must read as zero
+template <bool BF16>
+__global__ void enc_zero_pad_kernel(void *buf, int rows, int64_t ncols, int B, int Bh, int tail_end) {
+    const int row = blockIdx.x;
+    if (row >= rows) return;
+    const int pad1 = Bh - B, pad2 = (int)(ncols - tail_end);
+    for (int c = threadIdx.x; c < pad1 + pad2; c += blockDim.x) {
+        const int64_t col = c < pad1 ? B + c : tail_end + (c - pad1);
+        El<BF16>::st(buf, (int64_t)row * ncols + col, 0.f);
+    }
 }
 
 // out[e] = sum over the splits, in split order
@@ -269,12 +377,25 @@ EncRowArgs enc_row_args(const kge_encoder_t &e, const int32_t *h, const int32_t 
     return a;
 }
 
-template <bool BF16>
-void enc_launch_gemm(const void *A, int64_t lda_b, const int32_t *a_idx, int m_valid, const void *Bm, int64_t ldb_b, int n_valid,
-                     float *C, int64_t ldc, int64_t split_stride, int ksteps, int kps, int nsplit, hipStream_t st) {
-    dim3 grid((m_valid + ENC_TILE - 1) / ENC_TILE, (n_valid + ENC_TILE - 1) / ENC_TILE, nsplit);
-    hipLaunchKernelGGL(enc_gemm_nt_kernel<BF16>, grid, dim3(256), 0, st, (const char *)A, lda_b, a_idx, m_valid, (const char *)Bm,
-                       ldb_b, n_valid, C, ldc, split_stride, ksteps, kps);
+EncGemm enc_gemm_desc(const void *A, int64_t lda_b, bool gather, const int32_t *idx0, int n_idx0, const int32_t *idx1, int m_valid,
+                      const void *Bm, int64_t ldb_b, int n_valid, float *C, int64_t ldc, int64_t split_stride, int ksteps,
+                      int kps, int nsplit) {
+    EncGemm q{};
+    q.A = (const char *)A; q.lda_b = lda_b; q.idx0 = idx0; q.idx1 = idx1; q.n_idx0 = n_idx0; q.gather = gather ? 1 : 0; q.m_valid = m_valid;
+    q.B = (const char *)Bm; q.ldb_b = ldb_b; q.n_valid = n_valid; q.C = C; q.ldc = ldc; q.split_stride = split_stride;
+    q.ksteps = ksteps; q.kps = kps; q.nsplit = m_valid > 0 && ksteps > 0 ? nsplit : 0;
+    q.tiles_m = (m_valid + ENC_TILE - 1) / ENC_TILE; q.tiles_n = (n_valid + ENC_TILE - 1) / ENC_TILE;
+    return q;
+}
+
+void enc_launch_pair(bool bf16, const EncGemm &g0, const EncGemm &g1, hipStream_t st) {
+    EncGemmPair pr{};
+    pr.g[0] = g0; pr.g[1] = g1;
+    pr.wgs0 = g0.tiles_m * g0.tiles_n * g0.nsplit;
+    const int total = pr.wgs0 + g1.tiles_m * g1.tiles_n * g1.nsplit;
+    if (total == 0) return;
+    if (bf16) hipLaunchKernelGGL(enc_gemm_nt_kernel<true>, dim3(total), dim3(256), 0, st, pr);
+    else      hipLaunchKernelGGL(enc_gemm_nt_kernel<false>, dim3(total), dim3(256), 0, st, pr);
 }
 
 }  // namespace
@@ -302,8 +423,7 @@ size_t kge_encode_ws(const kge_encoder_t &e, int64_t B, int64_t N, bool bwd) {
     if (bwd) {
         take((size_t)e.dim * p.ncols * p.es);                                     // dP^t
         take((size_t)e.feat_dim * p.ncols * p.es);                                // F^t
-        const int ns = p.nsplit_h > p.nsplit_t ? p.nsplit_h : p.nsplit_t;
-        take((size_t)(ns > 0 ? ns : 1) * e.dim * e.feat_dim * 4);                 // split partials
+        take((size_t)(p.nsplit_h + p.nsplit_t + 1) * e.dim * e.feat_dim * 4);     // split partials of both contractions
     }
     return off + 256;
 }
@@ -314,17 +434,13 @@ int kge_run_encode(const kge_encoder_t &e, const int32_t *h, const int32_t *t, i
     const bool bf16 = e.dtype == KGE_BF16;
     float *regv = (float *)ws;
     const int ksteps = e.feat_dim * p.es / 32;
-    if (B > 0) {
-        if (bf16) enc_launch_gemm<true>(e.feat, e.feat_ld * p.es, h, (int)B, e.m_h, e.m_ld * p.es, e.dim, proj_out, e.dim, 0, ksteps, ksteps, 1, st);
-        else      enc_launch_gemm<false>(e.feat, e.feat_ld * p.es, h, (int)B, e.m_h, e.m_ld * p.es, e.dim, proj_out, e.dim, 0, ksteps, ksteps, 1, st);
-        float *pt = proj_out + (size_t)B * e.dim;
-        if (bf16) enc_launch_gemm<true>(e.feat, e.feat_ld * p.es, t, (int)B, e.m_t, e.m_ld * p.es, e.dim, pt, e.dim, 0, ksteps, ksteps, 1, st);
-        else      enc_launch_gemm<false>(e.feat, e.feat_ld * p.es, t, (int)B, e.m_t, e.m_ld * p.es, e.dim, pt, e.dim, 0, ksteps, ksteps, 1, st);
-    }
-    if (N > 0) {
-        float *pn = proj_out + (size_t)2 * B * e.dim;
-        if (bf16) enc_launch_gemm<true>(e.feat, e.feat_ld * p.es, neg, (int)N, e.m_t, e.m_ld * p.es, e.dim, pn, e.dim, 0, ksteps, ksteps, 1, st);
-        else      enc_launch_gemm<false>(e.feat, e.feat_ld * p.es, neg, (int)N, e.m_t, e.m_ld * p.es, e.dim, pn, e.dim, 0, ksteps, ksteps, 1, st);
+    {
+        KgeProfScope prof(KGE_PROF_ENC_FWD, st);          // heads against M_H, tails and negatives against M_T: one launch
+        const EncGemm gh = enc_gemm_desc(e.feat, e.feat_ld * p.es, true, h, (int)B, nullptr, (int)B, e.m_h, e.m_ld * p.es, e.dim,
+                                         proj_out, e.dim, 0, ksteps, ksteps, 1);
+        const EncGemm gt = enc_gemm_desc(e.feat, e.feat_ld * p.es, true, t, (int)B, neg, (int)(B + N), e.m_t, e.m_ld * p.es, e.dim,
+                                         proj_out + (size_t)B * e.dim, e.dim, 0, ksteps, ksteps, 1);
+        enc_launch_pair(bf16, gh, gt, st);
     }
     const EncRowArgs a = enc_row_args(e, h, t, B, neg, N, seed, step);
     const bool reg = e.reg_t > 0.f || e.reg_s > 0.f || e.reg_f > 0.f;
@@ -348,9 +464,17 @@ int kge_run_encode_bwd(const kge_encoder_t &e, const int32_t *h, const int32_t *
     void *Ft = take((size_t)e.feat_dim * p.ncols * p.es);
     float *part = (float *)take(1);
     const int64_t mcount = (int64_t)e.dim * e.feat_dim;
-    // padding columns must read as zero: clear both transposed buffers (a fill kernel, so that the call can be captured)
-    const int64_t zwords = (int64_t)(((char *)part - (char *)dPt) / 4);
-    hipLaunchKernelGGL(enc_zero_kernel, dim3((unsigned)((zwords + 255) / 256)), dim3(256), 0, st, (uint32_t *)dPt, zwords);
+    // padding columns must read as zero (a fill kernel rather than a memset, so that the call can be captured)
+    {
+        const int tail_end = p.Bh + (int)(B + N);
+        if (bf16) {
+            hipLaunchKernelGGL(enc_zero_pad_kernel<true>, dim3(e.dim), dim3(256), 0, st, dPt, e.dim, p.ncols, (int)B, p.Bh, tail_end);
+            hipLaunchKernelGGL(enc_zero_pad_kernel<true>, dim3(e.feat_dim), dim3(256), 0, st, Ft, e.feat_dim, p.ncols, (int)B, p.Bh, tail_end);
+        } else {
+            hipLaunchKernelGGL(enc_zero_pad_kernel<false>, dim3(e.dim), dim3(256), 0, st, dPt, e.dim, p.ncols, (int)B, p.Bh, tail_end);
+            hipLaunchKernelGGL(enc_zero_pad_kernel<false>, dim3(e.feat_dim), dim3(256), 0, st, Ft, e.feat_dim, p.ncols, (int)B, p.Bh, tail_end);
+        }
+    }
     // the row kernels stage 32 rows in the LDS: more than the default dynamic limit for long rows
     static bool attr_done = false;
     if (!attr_done) {
@@ -364,7 +488,7 @@ int kge_run_encode_bwd(const kge_encoder_t &e, const int32_t *h, const int32_t *
     }
     const EncRowArgs a = enc_row_args(e, h, t, B, neg, N, seed, step);
     if (p.n > 0) {
-        const int grid = (p.n + 31) / 32;
+        const int grid = (int)((B + 31) / 32 + (B + N + 31) / 32);
         if (bf16) {
             hipLaunchKernelGGL(enc_bwd_rows_kernel<true>, dim3(grid), dim3(256), 32 * (e.dim + 1) * 4, st, a, proj, de, g_es, dPt, p.Bh, p.ncols);
             hipLaunchKernelGGL(enc_gather_t_kernel<true>, dim3(grid), dim3(256), 32 * (e.feat_dim + 1) * 4, st, a, e.feat, e.feat_ld, e.feat_dim, Ft, p.Bh, p.ncols);
@@ -373,18 +497,18 @@ int kge_run_encode_bwd(const kge_encoder_t &e, const int32_t *h, const int32_t *
             hipLaunchKernelGGL(enc_gather_t_kernel<false>, dim3(grid), dim3(256), 32 * (e.feat_dim + 1) * 4, st, a, e.feat, e.feat_ld, e.feat_dim, Ft, p.Bh, p.ncols);
         }
     }
-    // G[d, f] = dP^t[d, cols] . F^t[f, cols]^t over the head columns (M_H), then over the tail / negative columns (M_T)
+    // G[d, f] = dP^t[d, cols] . F^t[f, cols]^t over the head columns (M_H) and over the tail / negative columns (M_T):
+    // one launch, split over the columns, then the partials are summed in split order
     const int per = 32 / p.es;                             // slots per k-step
-    for (int side = 0; side < 2; ++side) {
-        const int64_t col0 = side == 0 ? 0 : p.Bh;
-        const int ksteps = (side == 0 ? p.Bh : p.Th) / per, nsplit = side == 0 ? p.nsplit_h : p.nsplit_t;
-        float *out = side == 0 ? g_mh : g_mt;
-        const char *Ap = (const char *)dPt + col0 * p.es, *Bp = (const char *)Ft + col0 * p.es;
-        if (nsplit > 0) {
-            if (bf16) enc_launch_gemm<true>(Ap, p.ncols * p.es, nullptr, e.dim, Bp, p.ncols * p.es, e.feat_dim, part, e.feat_dim, mcount, ksteps, p.kps, nsplit, st);
-            else      enc_launch_gemm<false>(Ap, p.ncols * p.es, nullptr, e.dim, Bp, p.ncols * p.es, e.feat_dim, part, e.feat_dim, mcount, ksteps, p.kps, nsplit, st);
-        }
-        hipLaunchKernelGGL(enc_split_reduce_kernel, dim3((unsigned)((mcount + 255) / 256)), dim3(256), 0, st, part, nsplit, mcount, out);
-    }
+    KgeProfScope prof(KGE_PROF_ENC_BWD, st);
+    float *part_t = part + (size_t)p.nsplit_h * mcount;
+    const EncGemm gh = enc_gemm_desc(dPt, p.ncols * p.es, false, nullptr, 0, nullptr, B > 0 ? e.dim : 0, Ft, p.ncols * p.es, e.feat_dim,
+                                     part, e.feat_dim, mcount, p.Bh / per, p.kps, p.nsplit_h);
+    const EncGemm gt = enc_gemm_desc((const char *)dPt + (size_t)p.Bh * p.es, p.ncols * p.es, false, nullptr, 0, nullptr,
+                                     B + N > 0 ? e.dim : 0, (const char *)Ft + (size_t)p.Bh * p.es, p.ncols * p.es, e.feat_dim,
+                                     part_t, e.feat_dim, mcount, p.Th / per, p.kps, p.nsplit_t);
+    enc_launch_pair(bf16, gh, gt, st);
+    hipLaunchKernelGGL(enc_split_reduce_kernel, dim3((unsigned)((mcount + 255) / 256)), dim3(256), 0, st, part, gh.nsplit, mcount, g_mh);
+    hipLaunchKernelGGL(enc_split_reduce_kernel, dim3((unsigned)((mcount + 255) / 256)), dim3(256), 0, st, part_t, gt.nsplit, mcount, g_mt);
     return kge_launch_status();
 }
