@@ -44,65 +44,76 @@ struct EncGemm {
     int ksteps, kps, nsplit, tiles_m, tiles_n;
 };
 // A launch runs two contractions (heads against M_H, tails and negatives against M_T) so that the chip is filled
-// once; workgroup ids enumerate (contraction, split, tile).
-struct EncGemmPair { EncGemm g[2]; int wgs0; };
+// once; work items enumerate (contraction, split, row tile, column tile), column tile fastest.
+struct EncGemmPair { EncGemm g[2]; int wgs0, total; };
+
+constexpr int ENC_NSTAGE = 4;                                // chunks resident in the LDS ring
+constexpr int ENC_ROW_BYTES = 64;                            // a chunk is two k-steps: 64 bytes of every row
+constexpr int ENC_HALF_BYTES = ENC_TILE * ENC_ROW_BYTES;     // one operand's rows of one chunk
+constexpr int ENC_STAGE_BYTES = 2 * ENC_HALF_BYTES;
+constexpr int ENC_LDS_BYTES = ENC_NSTAGE * ENC_STAGE_BYTES;  // 64 KB: two workgroups per compute unit
+constexpr int ENC_LPW = 4;                                   // asynchronous copies per wave and chunk
+
+__device__ __forceinline__ void enc_async_copy16(const void *g, uint32_t lds_addr) {
+    // lane l of the wave writes its 16 bytes to LDS byte address lds_addr + 16 l; completion is tracked by vmcnt and
+    // the compiler does not see the load, so the waits below are explicit
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+template <int N> __device__ __forceinline__ void enc_wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // Workgroup = 128 x 128 outputs, wave = 64 x 64 (2 x 2 blocks of 32 x 32).  Both operands pass through the LDS
-// in chunks of four k-steps (128 bytes of every row: each row is read from memory as one contiguous segment by
-// 8 lanes), double-buffered in the LDS and two chunks deep in registers: the loads of chunks c+1 and c+2 are in
-// flight while chunk c is multiplied.  A 128-byte LDS row keeps its 16-byte pieces XOR-swizzled by (row & 7), so
-// that the fragment reads of 8 consecutive rows fall into 8 different bank groups.  Fragment of (row block,
-// k-step): lane l reads piece 2 ks + l / 32 of row l % 32.
+// in chunks of two k-steps (64 bytes of every row).  The chunks are copied global -> LDS asynchronously into a
+// ring of ENC_NSTAGE stages, so that the rows of ENC_NSTAGE - 1 chunks (random table rows in the forward pass:
+// pure latency) are in flight while one chunk is multiplied; no registers are tied up by the copies.  The ring
+// takes 64 KB and the kernel at most 128 registers per lane, so two workgroups share a compute unit: one's
+// prologue, barriers and write-out overlap the other's products.  A 64-byte LDS row keeps its four 16-byte pieces
+// XOR-swizzled by (row / 2) % 4, so that the fragment reads of 8 consecutive rows fall into 8 different bank
+// groups; a copy instruction fills 16 rows, lane l fetching piece (l % 4) ^ ((l / 8) % 4) of row l / 4 into slot
+// l % 4.  Fragment of (row block, k-step): lane l reads piece 2 ks + l / 32 of row l % 32.  Rows beyond m_valid /
+// n_valid are read from row 0 instead (valid memory); their outputs are never stored.  An odd last k-step goes
+// through registers with zeros selected for the missing pieces.
+// Workgroup ids are dealt round-robin to the 8 dies: id -> work item (id % 8) * ceil(total / 8) + id / 8, so that
+// the tiles that share operand rows run on the same die and meet in its L2.
 template <bool BF16>
-__global__ __launch_bounds__(256) void enc_gemm_nt_kernel(const EncGemmPair pr) {
-    __shared__ __attribute__((aligned(16))) char lds[2][2][ENC_TILE * 128];      // [buffer][A, B][row][128 bytes]
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void enc_gemm_nt_kernel(const EncGemmPair pr) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
-    const bool second = (int)blockIdx.x >= pr.wgs0;
+    const int per = (pr.total + 7) >> 3;
+    int w = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+    if (w >= pr.total) return;
+    const bool second = w >= pr.wgs0;
     const EncGemm &q = pr.g[second ? 1 : 0];
-    int w = (int)blockIdx.x - (second ? pr.wgs0 : 0);
+    w -= second ? pr.wgs0 : 0;
     const int tn = w % q.tiles_n; w /= q.tiles_n;
     const int tm = w % q.tiles_m, split = w / q.tiles_m;
     const int m0 = tm * ENC_TILE, n0 = tn * ENC_TILE;
     const int k_lo = split * q.kps, k_hi = min(q.ksteps, k_lo + q.kps);
-    // staging: thread t moves piece t % 8 of rows t / 8 + 32 j (j < 4) of both tiles
-    const int piece = tid & 7, srow = tid >> 3;
-    const char *ga[4], *gb[4];
-    bool va[4], vb[4];
+    const int nfull = (k_hi - k_lo) >> 1, rem = (k_hi - k_lo) & 1;
+    // staging: copy j (j < 2) of wave v fills rows 32 v + 16 j .. + 15 of a tile; this lane's row and piece
+    const int srow = lane >> 2, piece = (lane & 3) ^ ((srow >> 1) & 3);
+    const char *ga[2], *gb[2];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int ra = m0 + srow + 32 * j, rb = n0 + srow + 32 * j;
-        va[j] = ra < q.m_valid; vb[j] = rb < q.n_valid;
+    for (int j = 0; j < 2; ++j) {
+        const int ra = m0 + 32 * wave + 16 * j + srow, rb = n0 + 32 * wave + 16 * j + srow;
         int64_t src = 0;
-        if (va[j]) src = q.gather ? (ra < q.n_idx0 ? (int64_t)q.idx0[ra] : (int64_t)q.idx1[ra - q.n_idx0]) : (int64_t)ra;
-        ga[j] = q.A + src * q.lda_b + piece * 16;
-        gb[j] = q.B + (int64_t)(vb[j] ? rb : 0) * q.ldb_b + piece * 16;
+        if (ra < q.m_valid) src = q.gather ? (ra < q.n_idx0 ? (int64_t)q.idx0[ra] : (int64_t)q.idx1[ra - q.n_idx0]) : (int64_t)ra;
+        ga[j] = q.A + src * q.lda_b + piece * 16 + (int64_t)k_lo * 32;
+        gb[j] = q.B + (int64_t)(rb < q.n_valid ? rb : 0) * q.ldb_b + piece * 16 + (int64_t)k_lo * 32;
     }
-    const enc_u32x4 zero = {0u, 0u, 0u, 0u};
-    enc_u32x4 sa[2][4], sb[2][4];                          // two chunks in flight
-    // chunk = k-steps [ks0, ks0 + 4); pieces past k_hi and rows past the valid ones read as zero.  The loads
-    // themselves are unconditional (a clamped, always valid address) so that all eight are in flight together;
-    // the zeros are selected afterwards.
-    auto gload = [&](int set, int ks0) {
-        const bool in = ks0 + (piece >> 1) < k_hi;
-        const int64_t kb = (int64_t)(in ? ks0 : k_lo) * 32 - (in ? 0 : (piece >> 1) * 32);   // piece 0/1 of k_lo when out
+    // the row indices must have arrived before the loop: a compiler-inserted wait inside it would drain the ring
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            sa[set][j] = *(const enc_u32x4 *)(ga[j] + kb);
-            sb[set][j] = *(const enc_u32x4 *)(gb[j] + kb);
-        }
+    for (int j = 0; j < 2; ++j) asm volatile("" : "+v"(ga[j]), "+v"(gb[j]));
+    auto issue = [&](int c) {                             // chunk min(c, nfull - 1) -> stage c % ENC_NSTAGE
+        const int64_t off = (int64_t)min(c, nfull - 1) * ENC_ROW_BYTES;
+        const uint32_t sb = lds0 + (uint32_t)(c & (ENC_NSTAGE - 1)) * ENC_STAGE_BYTES + (uint32_t)wave * (32 * ENC_ROW_BYTES);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (!(in && va[j])) sa[set][j] = zero;
-            if (!(in && vb[j])) sb[set][j] = zero;
-        }
-    };
-    auto lstore = [&](int set, int buf) {
+        for (int j = 0; j < 2; ++j) enc_async_copy16(ga[j] + off, __builtin_amdgcn_readfirstlane(sb + j * 1024));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = srow + 32 * j, off = row * 128 + ((piece ^ (row & 7)) * 16);
-            *(enc_u32x4 *)(lds[buf][0] + off) = sa[set][j];
-            *(enc_u32x4 *)(lds[buf][1] + off) = sb[set][j];
-        }
+        for (int j = 0; j < 2; ++j) enc_async_copy16(gb[j] + off, __builtin_amdgcn_readfirstlane(sb + ENC_HALF_BYTES + j * 1024));
     };
     enc_f32x16 acc[2][2];
 #pragma unroll
@@ -110,15 +121,16 @@ __global__ __launch_bounds__(256) void enc_gemm_nt_kernel(const EncGemmPair pr) 
         for (int j = 0; j < 2; ++j)
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     const int wm = (wave & 1) * 64, wn = (wave >> 1) * 64;
-    auto compute = [&](int buf) {
+    auto compute = [&](int stage) {
+        const char *sa = lds + stage * ENC_STAGE_BYTES, *sb = sa + ENC_HALF_BYTES;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int ks = 0; ks < 2; ++ks) {
             enc_u32x4 fa[2], fb[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int rowa = wm + 32 * i + lr, rowb = wn + 32 * i + lr;
-                fa[i] = *(const enc_u32x4 *)(lds[buf][0] + rowa * 128 + (((2 * ks + g) ^ (rowa & 7)) * 16));
-                fb[i] = *(const enc_u32x4 *)(lds[buf][1] + rowb * 128 + (((2 * ks + g) ^ (rowb & 7)) * 16));
+                fa[i] = *(const enc_u32x4 *)(sa + rowa * ENC_ROW_BYTES + (((2 * ks + g) ^ ((rowa >> 1) & 3)) * 16));
+                fb[i] = *(const enc_u32x4 *)(sb + rowb * ENC_ROW_BYTES + (((2 * ks + g) ^ ((rowb >> 1) & 3)) * 16));
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -126,22 +138,32 @@ __global__ __launch_bounds__(256) void enc_gemm_nt_kernel(const EncGemmPair pr) 
                 for (int j = 0; j < 2; ++j) acc[i][j] = enc_mma16<BF16>(acc[i][j], fa[i], fb[j]);
         }
     };
-    // chunk c lives in LDS buffer c % 2 and was loaded into register set c % 2
-    gload(0, k_lo);
-    gload(1, k_lo + 4);
-    lstore(0, 0);
-    __syncthreads();
-    for (int ks0 = k_lo; ks0 < k_hi; ks0 += 8) {
-        // even chunk: its register set is free again -> request chunk + 2; the odd chunk's registers go to the LDS
-        gload(0, ks0 + 8);
+    static_assert((ENC_NSTAGE & (ENC_NSTAGE - 1)) == 0 && (ENC_NSTAGE - 2) * ENC_LPW < 64, "ring size");
+    if (nfull > 0) {
+        for (int c = 0; c < ENC_NSTAGE - 1; ++c) issue(c);
+        for (int c = 0; c < nfull; ++c) {
+            // chunks up to c + ENC_NSTAGE - 2 are issued; all but the last ENC_NSTAGE - 2 of them must have landed
+            enc_wait_vmcnt<(ENC_NSTAGE - 2) * ENC_LPW>();
+            __syncthreads();                                // chunk c is complete; everyone is done with chunk c - 1
+            issue(c + ENC_NSTAGE - 1);                      // ... whose stage is refilled (past the end: a harmless repeat)
+            compute(c & (ENC_NSTAGE - 1));
+        }
+        enc_wait_vmcnt<0>();                                // no copy may be in flight when the LDS is reused or released
+    }
+    if (rem > 0) {
+        __syncthreads();
+        const enc_u32x4 zero = {0u, 0u, 0u, 0u};
+        const bool in = (piece >> 1) < rem;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const enc_u32x4 xa = in ? *(const enc_u32x4 *)(ga[j] + (int64_t)nfull * ENC_ROW_BYTES) : zero;
+            const enc_u32x4 xb = in ? *(const enc_u32x4 *)(gb[j] + (int64_t)nfull * ENC_ROW_BYTES) : zero;
+            char *dst = lds + (32 * wave + 16 * j) * ENC_ROW_BYTES + lane * 16;
+            *(enc_u32x4 *)dst = xa;
+            *(enc_u32x4 *)(dst + ENC_HALF_BYTES) = xb;
+        }
+        __syncthreads();
         compute(0);
-        lstore(1, 1);
-        __syncthreads();
-        if (ks0 + 4 >= k_hi) break;
-        gload(1, ks0 + 12);
-        compute(1);
-        lstore(0, 0);
-        __syncthreads();
     }
     // accumulator layout: lane holds column lr of the B side; register e holds A-side row 8 (e/4) + 4 g + e%4
     float *Cs = q.C + (int64_t)split * q.split_stride;
@@ -388,14 +410,24 @@ EncGemm enc_gemm_desc(const void *A, int64_t lda_b, bool gather, const int32_t *
     return q;
 }
 
-void enc_launch_pair(bool bf16, const EncGemm &g0, const EncGemm &g1, hipStream_t st) {
+int enc_launch_pair(bool bf16, const EncGemm &g0, const EncGemm &g1, hipStream_t st) {
+    // the ring of stages is larger than the default dynamic limit
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void *)enc_gemm_nt_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, ENC_LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)enc_gemm_nt_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, ENC_LDS_BYTES) != hipSuccess)
+            return KGE_E_HIP;
+        attr_done = true;
+    }
     EncGemmPair pr{};
     pr.g[0] = g0; pr.g[1] = g1;
     pr.wgs0 = g0.tiles_m * g0.tiles_n * g0.nsplit;
-    const int total = pr.wgs0 + g1.tiles_m * g1.tiles_n * g1.nsplit;
-    if (total == 0) return;
-    if (bf16) hipLaunchKernelGGL(enc_gemm_nt_kernel<true>, dim3(total), dim3(256), 0, st, pr);
-    else      hipLaunchKernelGGL(enc_gemm_nt_kernel<false>, dim3(total), dim3(256), 0, st, pr);
+    pr.total = pr.wgs0 + g1.tiles_m * g1.tiles_n * g1.nsplit;
+    if (pr.total == 0) return KGE_OK;
+    const int grid = (pr.total + 7) / 8 * 8;
+    if (bf16) hipLaunchKernelGGL(enc_gemm_nt_kernel<true>, dim3(grid), dim3(256), ENC_LDS_BYTES, st, pr);
+    else      hipLaunchKernelGGL(enc_gemm_nt_kernel<false>, dim3(grid), dim3(256), ENC_LDS_BYTES, st, pr);
+    return KGE_OK;
 }
 
 }  // namespace
@@ -440,7 +472,7 @@ int kge_run_encode(const kge_encoder_t &e, const int32_t *h, const int32_t *t, i
                                          proj_out, e.dim, 0, ksteps, ksteps, 1);
         const EncGemm gt = enc_gemm_desc(e.feat, e.feat_ld * p.es, true, t, (int)B, neg, (int)(B + N), e.m_t, e.m_ld * p.es, e.dim,
                                          proj_out + (size_t)B * e.dim, e.dim, 0, ksteps, ksteps, 1);
-        enc_launch_pair(bf16, gh, gt, st);
+        if (int rc = enc_launch_pair(bf16, gh, gt, st)) return rc;
     }
     const EncRowArgs a = enc_row_args(e, h, t, B, neg, N, seed, step);
     const bool reg = e.reg_t > 0.f || e.reg_s > 0.f || e.reg_f > 0.f;
@@ -500,14 +532,16 @@ int kge_run_encode_bwd(const kge_encoder_t &e, const int32_t *h, const int32_t *
     // G[d, f] = dP^t[d, cols] . F^t[f, cols]^t over the head columns (M_H) and over the tail / negative columns (M_T):
     // one launch, split over the columns, then the partials are summed in split order
     const int per = 32 / p.es;                             // slots per k-step
-    KgeProfScope prof(KGE_PROF_ENC_BWD, st);
     float *part_t = part + (size_t)p.nsplit_h * mcount;
     const EncGemm gh = enc_gemm_desc(dPt, p.ncols * p.es, false, nullptr, 0, nullptr, B > 0 ? e.dim : 0, Ft, p.ncols * p.es, e.feat_dim,
                                      part, e.feat_dim, mcount, p.Bh / per, p.kps, p.nsplit_h);
     const EncGemm gt = enc_gemm_desc((const char *)dPt + (size_t)p.Bh * p.es, p.ncols * p.es, false, nullptr, 0, nullptr,
                                      B + N > 0 ? e.dim : 0, (const char *)Ft + (size_t)p.Bh * p.es, p.ncols * p.es, e.feat_dim,
                                      part_t, e.feat_dim, mcount, p.Th / per, p.kps, p.nsplit_t);
-    enc_launch_pair(bf16, gh, gt, st);
+    {
+        KgeProfScope prof(KGE_PROF_ENC_BWD, st);
+        if (int rc = enc_launch_pair(bf16, gh, gt, st)) return rc;
+    }
     hipLaunchKernelGGL(enc_split_reduce_kernel, dim3((unsigned)((mcount + 255) / 256)), dim3(256), 0, st, part, gh.nsplit, mcount, g_mh);
     hipLaunchKernelGGL(enc_split_reduce_kernel, dim3((unsigned)((mcount + 255) / 256)), dim3(256), 0, st, part_t, gt.nsplit, mcount, g_mt);
     return kge_launch_status();
