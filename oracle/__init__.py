@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "kge_oracle.c")
 _LIB = os.path.join(_HERE, "libkge_oracle.so")
 
-SCORERS = {"transe": 0, "transh": 1, "rotate": 2, "distmult": 3, "complex": 4}
+SCORERS = {"transe": 0, "transh": 1, "rotate": 2, "distmult": 3, "complex": 4,
+           "transe_l1": 5, "transh_l1": 6, "rotate_l1": 7}
 LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
 
 

@@ -25,14 +25,26 @@
  *
  * Parity pins: every function below is pinned by tests/test_oracle_*.py (closed forms, reductions
  * between scorers, finite differences, torch CPU optimisers, brute-force sorting, an independent
- * big-integer Philox).  Nothing here is "parity unpinned".
+ * big-integer Philox; the 1-norm scorers against numpy's 1-norm of independently built difference
+ * vectors, norm-equivalence bounds, the kink's sub-gradient).  Nothing here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORC_TRANSE = 0, ORC_TRANSH = 1, ORC_ROTATE = 2, ORC_DISTMULT = 3, ORC_COMPLEX = 4 };
+enum { ORC_TRANSE = 0, ORC_TRANSH = 1, ORC_ROTATE = 2, ORC_DISTMULT = 3, ORC_COMPLEX = 4,
+       /* the distance scorers with the 1-norm (Table 2: p in {1, 2}) */
+       ORC_TRANSE_L1 = 5, ORC_TRANSH_L1 = 6, ORC_ROTATE_L1 = 7 };
+
+static int orc_is_l1(int scorer) { return scorer >= ORC_TRANSE_L1 && scorer <= ORC_ROTATE_L1; }
+static int orc_base_scorer(int scorer)
+{
+    return scorer == ORC_TRANSE_L1 ? ORC_TRANSE : scorer == ORC_TRANSH_L1 ? ORC_TRANSH
+         : scorer == ORC_ROTATE_L1 ? ORC_ROTATE : scorer;
+}
+/* sub-gradient of |x|: 0 at the kink */
+static double orc_sign(double x) { return (double)(x > 0.0) - (double)(x < 0.0); }
 enum { ORC_LOGSIGMOID = 0, ORC_SAMPLED_SOFTMAX = 1 };
 
 /* ------------------------------------------------------------------------------------------ */
@@ -130,19 +142,24 @@ static double orc_unit_normal(const float *w, int d, double *what)
  * DistMult and TransE use the sequential fused form that also serves as the ranking key:
  *   DistMult  acc = fma(h_j * r_j, t_j, acc)             (h_j * r_j is exact in fp64)
  *   TransE    x = (h_j + r_j) - t_j; acc = fma(x, x, acc); f = -sqrt(acc)
+ * 1-norm variants: f = -sum_j |x_j| over the same difference vector x; for RotatE the vector is taken in
+ * R^d (|Re x_j| + |Im x_j| per complex coordinate), following the identification C^{d/2} = R^d of
+ * Section 3.1.  sq_out receives the ranking key (smaller = better): the squared distance, the 1-norm,
+ * or minus the score.
  */
 static double orc_score_one_ex(int scorer, int d, const float *h, const float *r, const float *w,
                                const float *t, double *sq_out)
 {
     double acc = 0.0;
-    switch (scorer) {
+    const int l1 = orc_is_l1(scorer);
+    switch (orc_base_scorer(scorer)) {
     case ORC_TRANSE:
         for (int j = 0; j < d; ++j) {
             double x = ((double)h[j] + (double)r[j]) - (double)t[j];
-            acc = fma(x, x, acc);
+            acc = l1 ? acc + fabs(x) : fma(x, x, acc);
         }
         if (sq_out) *sq_out = acc;
-        return -sqrt(acc);
+        return l1 ? -acc : -sqrt(acc);
     case ORC_DISTMULT:
         for (int j = 0; j < d; ++j) {
             double hr = (double)h[j] * (double)r[j];
@@ -170,10 +187,10 @@ static double orc_score_one_ex(int scorer, int d, const float *h, const float *r
             double qre = hre * cs - him * sn;
             double qim = hre * sn + him * cs;
             double xre = qre - (double)t[j], xim = qim - (double)t[j + c];
-            acc += xre * xre + xim * xim;
+            acc += l1 ? fabs(xre) + fabs(xim) : xre * xre + xim * xim;
         }
         if (sq_out) *sq_out = acc;
-        return -sqrt(acc);
+        return l1 ? -acc : -sqrt(acc);
     }
     case ORC_TRANSH: {
         double *what = (double *)malloc(sizeof(double) * (size_t)d);
@@ -184,11 +201,11 @@ static double orc_score_one_ex(int scorer, int d, const float *h, const float *r
             double hp = (double)h[j] - wh * what[j];
             double tp = (double)t[j] - wt * what[j];
             double x = hp + (double)r[j] - tp;
-            acc += x * x;
+            acc += l1 ? fabs(x) : x * x;
         }
         free(what);
         if (sq_out) *sq_out = acc;
-        return -sqrt(acc);
+        return l1 ? -acc : -sqrt(acc);
     }
     default:
         return NAN;
@@ -201,7 +218,7 @@ double orc_score_one(int scorer, int d, const float *h, const float *r, const fl
     return orc_score_one_ex(scorer, d, h, r, w, t, NULL);
 }
 
-static int orc_rel_dim(int scorer, int d) { return scorer == ORC_ROTATE ? d / 2 : d; }
+static int orc_rel_dim(int scorer, int d) { return orc_base_scorer(scorer) == ORC_ROTATE ? d / 2 : d; }
 
 /*
  * Positive scores pos[b] = f(h_b, r_b, t_b) and the shared-negative block
@@ -232,7 +249,9 @@ static void orc_score_grad_one(int scorer, int d, const float *h, const float *r
                                const float *t, double g, double *dh, double *dr, double *dw,
                                double *dt)
 {
-    switch (scorer) {
+    /* 1-norm variants: df/dx_j = -sign(x_j) replaces -x_j / ||x||_2; the chain through x is unchanged */
+    const int l1 = orc_is_l1(scorer);
+    switch (orc_base_scorer(scorer)) {
     case ORC_TRANSE: {
         double acc = 0.0;
         for (int j = 0; j < d; ++j) {
@@ -243,7 +262,7 @@ static void orc_score_grad_one(int scorer, int d, const float *h, const float *r
         if (dist == 0.0) return;              /* sub-gradient 0 at the kink */
         for (int j = 0; j < d; ++j) {
             double x = ((double)h[j] + (double)r[j]) - (double)t[j];
-            double a = -g * x / dist;         /* g * df/dx_j */
+            double a = l1 ? -g * orc_sign(x) : -g * x / dist;         /* g * df/dx_j */
             dh[j] += a; dr[j] += a; dt[j] -= a;
         }
         return;
@@ -285,8 +304,8 @@ static void orc_score_grad_one(int scorer, int d, const float *h, const float *r
             double hre = h[j], him = h[j + c];
             double cs = cos((double)r[j]), sn = sin((double)r[j]);
             double qre = hre * cs - him * sn, qim = hre * sn + him * cs;
-            double are = -g * (qre - (double)t[j]) / dist;      /* g * df/dq_re */
-            double aim = -g * (qim - (double)t[j + c]) / dist;  /* g * df/dq_im */
+            double are = l1 ? -g * orc_sign(qre - (double)t[j]) : -g * (qre - (double)t[j]) / dist;          /* g * df/dq_re */
+            double aim = l1 ? -g * orc_sign(qim - (double)t[j + c]) : -g * (qim - (double)t[j + c]) / dist;  /* g * df/dq_im */
             dh[j]     += are * cs + aim * sn;
             dh[j + c] += -are * sn + aim * cs;
             dr[j]     += are * (-qim) + aim * qre;              /* dq_re/dr = -q_im, dq_im/dr = q_re */
@@ -310,7 +329,7 @@ static void orc_score_grad_one(int scorer, int d, const float *h, const float *r
         double dist = sqrt(acc);
         if (dist == 0.0) { free(buf); return; }
         double aw = 0.0;
-        for (int j = 0; j < d; ++j) { a[j] = -g * x[j] / dist; aw += a[j] * what[j]; }
+        for (int j = 0; j < d; ++j) { a[j] = l1 ? -g * orc_sign(x[j]) : -g * x[j] / dist; aw += a[j] * what[j]; }
         for (int j = 0; j < d; ++j) {
             double ax = a[j] - aw * what[j];           /* through (h - t) */
             dh[j] += ax; dt[j] -= ax; dr[j] += a[j];
@@ -632,7 +651,7 @@ void orc_topk(int scorer, int d, const float *ent, const float *rel, const float
             orc_sift_down(hp, cnt, 0);
             out_idx[q * K + i] = worst.idx;
             double sc;
-            if (scorer == ORC_DISTMULT || scorer == ORC_COMPLEX) sc = -worst.key;
+            if (scorer == ORC_DISTMULT || scorer == ORC_COMPLEX || orc_is_l1(scorer)) sc = -worst.key;
             else sc = -sqrt(worst.key);
             out_score[q * K + i] = sc;
         }

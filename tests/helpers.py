@@ -26,7 +26,7 @@ def small_graph(scorer, n_ent=1000, n_rel=10, dim=32, B=64, N=64, seed=ks.BASE_S
         ent = ks.normal_table(seed, ks.TAG_ENT, n_ent, dim, amp)
     else:
         ent = ks.uniform_table(seed, ks.TAG_ENT, n_ent, dim, amp)
-    rel, relw = ks.relation_tables(scorer, n_rel, dim, seed, amp)
+    rel, relw = ks.relation_tables(scorer.replace("_l1", ""), n_rel, dim, seed, amp)   # same tables for both norms
     if grid_bits is not None:
         q = float(1 << grid_bits)
         ent = (np.round(ent * q) / q).astype(np.float32)
