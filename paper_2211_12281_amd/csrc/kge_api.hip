@@ -33,7 +33,7 @@ int kge_run_negatives_sharded(uint64_t seed, uint64_t step, uint32_t tag, int64_
 namespace {
 
 struct Geometry {
-    bool bf16, transh;
+    bool bf16, transh, l1;              // l1: distance scorer with the 1-norm (vector-pipe kernels, score block in memory)
     int es, rb, dp, kind;
     int B, N, Bp, Np;
     int own_tiles_b, own_tiles_n, own_tiles_s;   // own tiles of the FWD pass (queries), the GRADT and the SCORE pass (negatives)
@@ -53,8 +53,8 @@ int validate_model(const kge_model_t *m) {
     const int es = m->dtype == KGE_BF16 ? 2 : 4;
     if (m->dim <= 0 || m->dim % (32 / es) != 0 || m->dim * es > 1024) return KGE_E_INVALID_ARG;
     const bool dist = m->scorer == KGE_TRANSE || m->scorer == KGE_TRANSH || m->scorer == KGE_ROTATE;
-    if (dist && m->p_norm == 1) return KGE_E_UNSUPPORTED;
-    if (dist && m->p_norm != 2) return KGE_E_INVALID_ARG;
+    if (dist && m->p_norm != 1 && m->p_norm != 2) return KGE_E_INVALID_ARG;
+    if (m->p_norm == 1 && m->scorer == KGE_TRANSH) return KGE_E_UNSUPPORTED;
     const int k = m->scorer == KGE_ROTATE ? m->dim / 2 : m->dim;
     if (m->rel_dim != k) return KGE_E_INVALID_ARG;
     if (m->n_ent <= 0 || m->n_rel <= 0 || m->n_ent >= (1ll << 31) || m->n_rel >= (1ll << 31)) return KGE_E_INVALID_ARG;
@@ -71,6 +71,7 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.rb = m.dim * g.es <= 512 ? 512 : 1024;
     g.dp = g.rb / g.es;
     g.kind = (m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
+    g.l1 = g.kind == KGE_KIND_DIST && m.p_norm == 1;
     g.B = (int)B; g.N = (int)N;
     g.Bp = (int)kge_round_up(B, KGE_PAD); g.Np = (int)kge_round_up(N, KGE_PAD);
     g.own_tiles_b = g.Bp / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_FWD, g.kind));
@@ -90,6 +91,10 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     split(g.own_tiles_s, g.str_tiles_b, g.nsplit_s, g.tps_s, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_SCORE));
     g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
     g.dsplit_t = (g.bf16 && g.rb == 1024) ? 2 : 1;
+    if (g.l1) {
+        g.nsplit_q = kge_l1_nsplit(g.Bp, g.Np, g.dp);
+        g.nsplit_t = kge_l1_nsplit(g.Np, g.Bp, g.dp);
+    }
     return g;
 }
 
@@ -110,6 +115,7 @@ struct Buffers {
     KgeRowInfo *rowinfo; float *tn, *pos, *lossb, *gpos;
     float4 *stat_part; float *accq, *accq2; float4 *sumq; float *acct; float4 *sumt;
     float *regv;                       // L3 norms of the gathered slots: [Bp heads][Bp tails][Np negatives]
+    float *S, *Q32;                    // 1-norm scorers: the score block [Bp][Np], the queries unrounded [Bp][dp]
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -121,13 +127,18 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
     b.rowinfo = c.take<KgeRowInfo>(g.Bp);
     b.tn = c.take<float>(g.Np);
     b.pos = c.take<float>(g.Bp);
+    b.Q32 = g.l1 ? c.take<float>(rowsB) : nullptr;
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
-    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr;
+    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr;
     if (bwd) {
         b.Q2 = g.transh ? c.take<char>(rowsB * es) : nullptr;
-        b.Qt = c.take<char>(rowsB * es);
-        b.Wt = g.transh ? c.take<char>(rowsB * es) : nullptr;
-        b.Tt = c.take<char>(rowsN * es);
+        if (!g.l1) {
+            b.Qt = c.take<char>(rowsB * es);
+            b.Wt = g.transh ? c.take<char>(rowsB * es) : nullptr;
+            b.Tt = c.take<char>(rowsN * es);
+        } else {
+            b.S = c.take<float>((size_t)g.Bp * g.Np);
+        }
         b.lossb = c.take<float>(g.Bp);
         b.gpos = c.take<float>(g.Bp);
         b.stat_part = c.take<float4>((size_t)g.nsplit_q * g.Bp);
@@ -144,6 +155,7 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
 KgeModelDev dev_model(const kge_model_t &m) {
     KgeModelDev d;
     d.scorer = m.scorer; d.bf16 = m.dtype == KGE_BF16; d.dim = m.dim; d.rel_dim = m.rel_dim;
+    d.p1 = (m.scorer == KGE_TRANSE || m.scorer == KGE_TRANSH || m.scorer == KGE_ROTATE) && m.p_norm == 1;
     d.ent = m.ent; d.rel = m.rel; d.relw = m.relw;
     d.ent_ld = m.ent_ld; d.rel_ld = m.rel_ld; d.relw_ld = m.relw_ld;
     return d;
@@ -298,10 +310,11 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     if (carve(g, false, nullptr, b) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     carve(g, false, ws, b);
     KgeModelDev md = dev_model(*model);
-    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.rowinfo, b.pos, pos_out, st);
+    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.rowinfo, b.pos, pos_out, st);
     if (rc != KGE_OK || !block) return rc;
     rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st);
     if (rc != KGE_OK) return rc;
+    if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);
     KgeBlockArgs a{};
     a.own = b.T; a.str = b.Q; a.str2 = b.W; a.rowinfo = b.rowinfo; a.tn = b.tn;
     a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_b; a.tiles_per_split = g.tps_s;
@@ -337,9 +350,14 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
                              ? (float)log((double)(cfg->n_ent_for_c - 1) / (double)N) : 0.f;
     const bool have_block = B > 0 && N > 0;
 
-    if ((rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.rowinfo, b.pos, nullptr, st)) != KGE_OK) return rc;
+    if ((rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.rowinfo, b.pos, nullptr, st)) != KGE_OK) return rc;
     KgeBlockArgs a{};
-    if (have_block) {
+    if (have_block && g.l1) {
+        // 1-norm: the score block goes to memory, one row pass gives the loss statistics
+        if ((rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st)) != KGE_OK) return rc;
+        if ((rc = kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, g.Np, st)) != KGE_OK) return rc;
+        if ((rc = kge_run_l1_rowstat(b.S, g.Np, g.B, g.N, g.Bp, cfg->loss, cfg->gamma, cfg->adv_temp, b.stat_part, st)) != KGE_OK) return rc;
+    } else if (have_block) {
         if ((rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st)) != KGE_OK) return rc;
         if ((rc = kge_run_transpose(b.T, b.Tt, g.Np, g.dp, g.bf16, st)) != KGE_OK) return rc;
         if ((rc = kge_run_transpose(g.transh ? b.Q2 : b.Q, b.Qt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
@@ -351,9 +369,15 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         a.stat_part = b.stat_part; a.acc_part = b.accq; a.acc_part2 = b.accq2; a.sum_part = b.sumq; a.own_pad = g.Bp;
         if ((rc = launch_block(g, KGE_MODE_FWD, cfg->loss, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
     }
-    if ((rc = kge_run_rowfinish(b.stat_part, have_block ? g.nsplit_q : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
+    if ((rc = kge_run_rowfinish(b.stat_part, have_block ? (g.l1 ? 1 : g.nsplit_q) : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
                                 cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, loss_out, st)) != KGE_OK) return rc;
-    if (have_block) {
+    if (have_block && g.l1) {
+        // gradient rows of the queries and of the shared negatives from S and the finished row constants
+        if ((rc = kge_run_l1_grad(g.bf16, true, b.Q32, b.T, b.S, g.Np, b.rowinfo, g.B, g.N, g.Bp, g.Np, g.dp, cfg->loss, cfg->gamma,
+                                  cfg->adv_temp, g.nsplit_q, b.accq, st)) != KGE_OK) return rc;
+        if ((rc = kge_run_l1_grad(g.bf16, false, b.T, b.Q32, b.S, g.Np, b.rowinfo, g.B, g.N, g.Np, g.Bp, g.dp, cfg->loss, cfg->gamma,
+                                  cfg->adv_temp, g.nsplit_t, b.acct, st)) != KGE_OK) return rc;
+    } else if (have_block) {
         // pass 2 (column owner): gradient of the shared negatives from the finished row constants
         KgeBlockArgs c = a;
         c.own = b.T; c.own2 = nullptr; c.str = b.Q; c.str2 = b.W; c.strT = b.Qt; c.strT2 = b.Wt; c.strT_ld = g.Bp;
@@ -366,7 +390,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     if (N > 0) {
         // with B == 0 there are no partials: nsplit 0 writes zero rows
         rc = kge_run_tfinish(b.acct, b.sumt, have_block ? g.nsplit_t : 0, g.Np, g.N, g.dp, model->dim,
-                             have_block && g.kind == KGE_KIND_DIST, have_block ? b.T : nullptr, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
+                             have_block && g.kind == KGE_KIND_DIST && !g.l1, have_block ? b.T : nullptr, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
                              g_ent_idx + 2 * B, model->ent, model->ent_ld, cfg->reg_l3, b.regv + (size_t)2 * g.Bp, st);
         if (rc != KGE_OK) return rc;
     }
@@ -400,6 +424,7 @@ int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64
     if (K < 1 || K > 256) return KGE_E_INVALID_ARG;
     if ((true_t == nullptr) != (out_rank == nullptr)) return KGE_E_INVALID_ARG;
     if (model->scorer != KGE_DISTMULT && model->scorer != KGE_TRANSE) return KGE_E_UNSUPPORTED;
+    if (model->scorer == KGE_TRANSE && model->p_norm != 2) return KGE_E_UNSUPPORTED;
     if (Q == 0) return KGE_OK;
     if (!h || !r || !out_idx || !out_score) return KGE_E_INVALID_ARG;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;

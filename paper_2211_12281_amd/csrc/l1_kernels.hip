@@ -1,0 +1,226 @@
+// The distance scorers with the 1-norm (Table 2, p = 1): f = -sum_j |q_j - t_j| over the query q = h + r (TransE)
+// or h o e^{ir} taken in R^d (RotatE).  There is no contraction form: every (query, negative, dimension) triple
+// costs vector instructions, so the score block IS written to memory here (4 bytes per pair against 2 d vector
+// operations) and the backward pass reads it back instead of recomputing it:
+//   scores      S[b, n] = -sum_j |q_bj - t_nj|
+//   row pass    per query the maximum and the sums of the loss weights over its row of S
+//   gradients   dq[b, j] = -sum_n w(b, n) sign(q_bj - t_nj),   dt[n, j] = +sum_b w(b, n) sign(q_bj - t_nj)
+// with w(b, n) = dL/dS[b, n] from S and the finished row constants; sign(0) = 0 (sub-gradient at the kink).
+// The queries are read from an unrounded fp32 copy also when the tables are bf16 (a sign flips when rounding moves a
+// difference across zero; the table rows themselves are exact).  All three block kernels stage 64 x 64 fp32 tiles in the LDS (row pitch 68 floats: the 16 lanes that read 16
+// different rows at one column offset hit 16 different 16-byte bank groups) and keep a 4 x 4 register tile per
+// thread; they are bound by the vector pipe.
+#include "row_ops.hpp"
+
+namespace {
+
+constexpr int L1_TILE = 64;            // rows and columns of a staged tile
+constexpr int L1_PITCH = 68;           // floats per LDS row
+constexpr float L1_LOG2E = 1.4426950408889634f, L1_LN2 = 0.6931471805599453f;
+
+typedef float l1_f32x4 __attribute__((ext_vector_type(4)));
+
+// rows [r0, r0 + 64) x columns [c0, c0 + 64) of a row-major [rows][ld] array of the table type -> fp32 LDS tile
+template <bool BF16>
+__device__ __forceinline__ void l1_stage(const void *src, int64_t ld, int r0, int c0, float *tile) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int e = threadIdx.x + 256 * k, row = e >> 4, cq = e & 15;
+        const int64_t off = (int64_t)(r0 + row) * ld + c0 + 4 * cq;
+        l1_f32x4 v;
+        if constexpr (BF16) {
+            const uint2 raw = *(const uint2 *)((const __bf16 *)src + off);
+            v = l1_f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                         __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u)};
+        } else {
+            v = *(const l1_f32x4 *)((const float *)src + off);
+        }
+        *(l1_f32x4 *)(tile + row * L1_PITCH + 4 * cq) = v;
+    }
+}
+
+// S[b, n] = -sum_j |q_bj - t_nj|; workgroup = 64 queries x 64 negatives, thread = queries 4 ty + i, negatives tx + 16 k
+template <bool BF16>
+__global__ __launch_bounds__(256) void l1_score_kernel(const float *Q, const void *T, int B, int N, int dp, float *S, int64_t ldS) {
+    __shared__ __attribute__((aligned(16))) float qs[L1_TILE * L1_PITCH], ts[L1_TILE * L1_PITCH];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int n0 = blockIdx.x * L1_TILE, b0 = blockIdx.y * L1_TILE;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        for (int k = 0; k < 4; ++k) acc[i][k] = 0.f;
+    for (int j0 = 0; j0 < dp; j0 += L1_TILE) {
+        __syncthreads();
+        l1_stage<false>(Q, dp, b0, j0, qs);
+        l1_stage<BF16>(T, dp, n0, j0, ts);
+        __syncthreads();
+#pragma unroll 4
+        for (int jq = 0; jq < 16; ++jq) {
+            l1_f32x4 q4[4], t4[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                q4[i] = *(const l1_f32x4 *)(qs + (4 * ty + i) * L1_PITCH + 4 * jq);
+                t4[i] = *(const l1_f32x4 *)(ts + (tx + 16 * i) * L1_PITCH + 4 * jq);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[i][k] += fabsf(q4[i][c] - t4[k][c]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int b = b0 + 4 * ty + i;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int n = n0 + tx + 16 * k;
+            if (b < B && n < N) S[(int64_t)b * ldS + n] = -acc[i][k];
+        }
+    }
+}
+
+__device__ __forceinline__ float l1_wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float l1_sigmoid(float y) {
+    const float t = __builtin_amdgcn_exp2f(-fabsf(y) * L1_LOG2E), rcp = 1.f / (1.f + t);
+    return y >= 0.f ? rcp : t * rcp;
+}
+
+// Row statistics of the loss (Section 3.1 "Loss Functions"), one wave per query: with x = a s (log-sigmoid
+// loss, a the self-adversarial temperature) or x = s (sampled softmax), both times log2(e):
+// {m = max_n x_n, sum_n 2^(x_n - m), sum_n 2^(x_n - m) softplus(gamma + s_n), 0}
+__global__ __launch_bounds__(256) void l1_rowstat_kernel(const float *S, int64_t ldS, int B, int N, int Bp, int loss, float gamma,
+                                                         float adv_temp, float4 *stat) {
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (b >= Bp) return;
+    if (b >= B) { if (lane == 0) stat[b] = make_float4(-INFINITY, 0.f, 0.f, 0.f); return; }
+    const float xscale = (loss == KGE_LOGSIGMOID ? adv_temp : 1.f) * L1_LOG2E;
+    const float *row = S + (int64_t)b * ldS;
+    float m = -INFINITY;
+    for (int n = lane; n < N; n += 64) m = fmaxf(m, row[n] * xscale);
+    m = l1_wave_max(m);
+    float l = 0.f, ac = 0.f;
+    for (int n = lane; n < N; n += 64) {
+        const float s = row[n], e = __builtin_amdgcn_exp2f(fmaf(s, xscale, -m));
+        l += e;
+        if (loss == KGE_LOGSIGMOID) {
+            const float y = gamma + s;
+            const float t = __builtin_amdgcn_exp2f(-fabsf(y) * L1_LOG2E);
+            ac = fmaf(e, fmaxf(y, 0.f) + L1_LN2 * __builtin_amdgcn_logf(1.f + t), ac);
+        }
+    }
+    l = kge_wave_sum(l); ac = kge_wave_sum(ac);
+    if (lane == 0) stat[b] = make_float4(m, l, ac, 0.f);
+}
+
+// out[split][o, j] = -sum_s w(o, s) sign(own_oj - str_sj) over the split's rows of the streamed operand: with
+// own = queries this is dq (s runs over the negatives), with own = negatives it is dt (s runs over the queries;
+// the sign flips twice).  Workgroup = 64 own rows x 64 dimensions; thread = own rows 4 ty + i, dimensions
+// 4 tx + c.  Per chunk of 64 streamed rows the weights w = 2^(x log2e + K_b) (times sigma(gamma + s) for the
+// log-sigmoid loss) are computed once from S and the finished row constants into the LDS.
+template <bool BF16, bool OWN_Q>
+__global__ __launch_bounds__(256) void l1_grad_kernel(const void *own, const void *str, const float *S, int64_t ldS,
+                                                      const KgeRowInfo *rowinfo, int B, int N, int own_pad, int dp,
+                                                      int chunks, int cps, int loss, float gamma, float adv_temp,
+                                                      float *acc_part) {
+    __shared__ __attribute__((aligned(16))) float ss[L1_TILE * L1_PITCH], ws[L1_TILE * L1_PITCH];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int o0 = blockIdx.x * L1_TILE, j0 = blockIdx.y * L1_TILE, split = blockIdx.z;
+    const float xscale = (loss == KGE_LOGSIGMOID ? adv_temp : 1.f) * L1_LOG2E;
+    float ov[4][4], acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            ov[i][c] = El<BF16 && !OWN_Q>::ld(own, (int64_t)(o0 + 4 * ty + i) * dp + j0 + 4 * tx + c);
+            acc[i][c] = 0.f;
+        }
+    const int c_hi = min(chunks, (split + 1) * cps);
+    for (int ch = split * cps; ch < c_hi; ++ch) {
+        const int s0 = ch * L1_TILE;
+        __syncthreads();
+        l1_stage<BF16 && OWN_Q>(str, dp, s0, j0, ss);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int e = threadIdx.x + 256 * k;
+            // consecutive threads take consecutive negatives: the reads of S are coalesced either way
+            const int ol = OWN_Q ? e >> 6 : e & 63, sl = OWN_Q ? e & 63 : e >> 6;
+            const int b = OWN_Q ? o0 + ol : s0 + sl, n = OWN_Q ? s0 + sl : o0 + ol;
+            float w = 0.f;
+            if (b < B && n < N) {
+                const float s = S[(int64_t)b * ldS + n];
+                w = __builtin_amdgcn_exp2f(fmaf(s, xscale, rowinfo[b].K));
+                if (loss == KGE_LOGSIGMOID) w *= l1_sigmoid(gamma + s);
+            }
+            ws[sl * L1_PITCH + ol] = w;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int sl = 0; sl < L1_TILE; ++sl) {
+            const l1_f32x4 w4 = *(const l1_f32x4 *)(ws + sl * L1_PITCH + 4 * ty);
+            const l1_f32x4 t4 = *(const l1_f32x4 *)(ss + sl * L1_PITCH + 4 * tx);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    acc[i][c] += t4[c] < ov[i][c] ? -w4[i] : (t4[c] > ov[i][c] ? w4[i] : 0.f);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        *(l1_f32x4 *)(acc_part + ((int64_t)split * own_pad + o0 + 4 * ty + i) * dp + j0 + 4 * tx) =
+            l1_f32x4{acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
+}
+
+}  // namespace
+
+int kge_run_l1_score(bool bf16, const float *Q, const void *T, int B, int N, int Bp, int Np, int dp, float *S, int64_t ldS,
+                     hipStream_t st) {
+    if (Bp % L1_TILE || Np % L1_TILE || dp % L1_TILE) return KGE_E_INVALID_ARG;
+    if (Bp == 0 || Np == 0) return KGE_OK;
+    if (Bp / L1_TILE > 65535) return KGE_E_UNSUPPORTED;   // grid limit of the second dimension
+    KgeProfScope prof(KGE_PROF_BLOCK_SCORE, st);
+    const dim3 grid(Np / L1_TILE, Bp / L1_TILE);
+    if (bf16) hipLaunchKernelGGL(l1_score_kernel<true>, grid, dim3(256), 0, st, Q, T, B, N, dp, S, ldS);
+    else      hipLaunchKernelGGL(l1_score_kernel<false>, grid, dim3(256), 0, st, Q, T, B, N, dp, S, ldS);
+    return kge_launch_status();
+}
+
+int kge_run_l1_rowstat(const float *S, int64_t ldS, int B, int N, int Bp, int loss, float gamma, float adv_temp,
+                       float4 *stat, hipStream_t st) {
+    if (Bp == 0) return KGE_OK;
+    hipLaunchKernelGGL(l1_rowstat_kernel, dim3((Bp + 3) / 4), dim3(256), 0, st, S, ldS, B, N, Bp, loss, gamma, adv_temp, stat);
+    return kge_launch_status();
+}
+
+// splits over the streamed rows: enough workgroups for about four per compute unit
+int kge_l1_nsplit(int own_pad, int str_pad, int dp) {
+    const int base = (own_pad / L1_TILE) * (dp / L1_TILE), chunks = str_pad / L1_TILE;
+    if (base == 0 || chunks == 0) return 0;
+    int want = (1024 + base - 1) / base;
+    if (want > chunks) want = chunks;
+    const int cps = (chunks + want - 1) / want;
+    return (chunks + cps - 1) / cps;
+}
+
+int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *str, const float *S, int64_t ldS,
+                    const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp, int loss, float gamma,
+                    float adv_temp, int nsplit, float *acc_part, hipStream_t st) {
+    if (own_pad % L1_TILE || str_pad % L1_TILE || dp % L1_TILE) return KGE_E_INVALID_ARG;
+    if (nsplit <= 0 || nsplit != kge_l1_nsplit(own_pad, str_pad, dp)) return KGE_E_INVALID_ARG;
+    KgeProfScope prof(own_is_query ? KGE_PROF_BLOCK_FWD : KGE_PROF_BLOCK_GRADT, st);
+    const int chunks = str_pad / L1_TILE, cps = (chunks + nsplit - 1) / nsplit;
+    const dim3 grid(own_pad / L1_TILE, dp / L1_TILE, nsplit);
+#define L1_GRAD(BF, OQ) hipLaunchKernelGGL((l1_grad_kernel<BF, OQ>), grid, dim3(256), 0, st, own, str, S, ldS, rowinfo, B, N, \
+                                           own_pad, dp, chunks, cps, loss, gamma, adv_temp, acc_part)
+    if (bf16) { if (own_is_query) L1_GRAD(true, true); else L1_GRAD(true, false); }
+    else      { if (own_is_query) L1_GRAD(false, true); else L1_GRAD(false, false); }
+#undef L1_GRAD
+    return kge_launch_status();
+}

@@ -5,6 +5,7 @@
 // Device-side view of kge_model_t.
 struct KgeModelDev {
     int32_t scorer, bf16, dim, rel_dim;
+    int32_t p1;                    // distance scorers: 1 = the 1-norm variant (Table 2, p = 1)
     const void *ent, *rel, *relw;
     int64_t ent_ld, rel_ld, relw_ld;
 };
@@ -12,14 +13,15 @@ struct KgeModelDev {
 int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, int64_t hi, int64_t n,
                       int32_t *out, hipStream_t st);
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
-                   int dp, void *Q, void *W, void *Q2, KgeRowInfo *rowinfo, float *pos_ws, float *pos_out,
-                   hipStream_t st);
+                   int dp, void *Q, void *W, void *Q2, float *Q32, KgeRowInfo *rowinfo, float *pos_ws,
+                   float *pos_out, hipStream_t st);
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
                     hipStream_t st);
 int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipStream_t st);
 int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma,
                       float c_corr, float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb,
                       float *gpos, float *loss_out, hipStream_t st);
+// m.p1: acc_part holds finished gradient rows (coefficients already normalised), sum_part / stat_part are not read
 int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
                   const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
                   const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
@@ -29,3 +31,13 @@ int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit,
                     const void *ent, int64_t ent_ld, float reg, float *regn, hipStream_t st);
 // loss_out += reg * (sum of regv over the 2B + N gathered slots), laid out [Bp heads][Bp tails][N negatives]
 int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st);
+
+// 1-norm distance scorers (l1_kernels.hip): score block, row statistics of the loss, gradient rows
+int kge_run_l1_score(bool bf16, const float *Q, const void *T, int B, int N, int Bp, int Np, int dp, float *S, int64_t ldS,
+                     hipStream_t st);
+int kge_run_l1_rowstat(const float *S, int64_t ldS, int B, int N, int Bp, int loss, float gamma, float adv_temp,
+                       float4 *stat, hipStream_t st);
+int kge_l1_nsplit(int own_pad, int str_pad, int dp);
+int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *str, const float *S, int64_t ldS,
+                    const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp, int loss, float gamma,
+                    float adv_temp, int nsplit, float *acc_part, hipStream_t st);

@@ -44,7 +44,7 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 // ---------------------------------------------------------------------------------------------
 template <bool BF16>
 __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t,
-                                  int B, int Bp, int dp, void *Q, void *W, void *Q2, KgeRowInfo *rowinfo,
+                                  int B, int Bp, int dp, void *Q, void *W, void *Q2, float *Q32, KgeRowInfo *rowinfo,
                                   float *pos_ws, float *pos_out) {
     const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -54,6 +54,7 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
             El<BF16>::st(Q, (int64_t)b * dp + j, 0.f);
             if (W) El<BF16>::st(W, (int64_t)b * dp + j, 0.f);
             if (Q2) El<BF16>::st(Q2, (int64_t)b * dp + j, 0.f);
+            if (Q32) Q32[(int64_t)b * dp + j] = 0.f;
         }
         if (lane == 0) { rowinfo[b] = KgeRowInfo{0.f, 0.f, 0.f, 0.f}; if (pos_ws) pos_ws[b] = 0.f; }
         return;
@@ -74,6 +75,7 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
         if (j < dp) {
             El<BF16>::st(Q, (int64_t)b * dp + j, cx.q[k]);
             if (W) El<BF16>::st(W, (int64_t)b * dp + j, cx.w[k]);
+            if (Q32) Q32[(int64_t)b * dp + j] = cx.q[k];      // unrounded copy for the 1-norm kernels
         }
     }
     qn = kge_wave_sum(qn);
@@ -92,11 +94,11 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
         else {
             float x = cx.q[k] - tv[k];
             if (m.scorer == KGE_TRANSH) x += wt * cx.w[k];
-            s_pos += x * x;
+            s_pos += m.p1 ? fabsf(x) : x * x;
         }
     }
     s_pos = kge_wave_sum(s_pos);
-    if (!(m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX)) s_pos = -sqrtf(s_pos);
+    if (!(m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX)) s_pos = m.p1 ? -s_pos : -sqrtf(s_pos);
     if (lane == 0) {
         rowinfo[b] = KgeRowInfo{qn, cq, 0.f, m.scorer == KGE_TRANSH ? wn : 1.f};
         if (pos_ws) pos_ws[b] = s_pos;
@@ -217,12 +219,14 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     // the row pass leaves, per split, sums of UNNORMALISED weights relative to that split's running
     // maximum m_s; exp2(m_s + K) turns them into gradient coefficients
     const float K2 = rowinfo[b].K;
+    // (the 1-norm kernels apply the finished coefficients themselves: their partials are summed as they are)
     auto kappa = [&](int s) {
+        if (m.p1) return 1.f;
         const float ms = stat_part[(size_t)s * Bp + b].x;
         return ms > -INFINITY ? exp2f(ms + K2) : 0.f;
     };
     float s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
+    for (int s = 0; s < (m.p1 ? 0 : nsplit); ++s) {
         const float kap = kappa(s);
         const float4 p = sum_part[(size_t)s * Bp + b];
         s1 += kap * p.x; s2 += kap * p.y; s3 += kap * p.z;
@@ -266,7 +270,8 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         }
 #pragma unroll
         for (int k = 0; k < KGE_MAXJ; ++k) {
-            const float apu = ap * u[k];
+            // positive triple: gp * df/du_k, df/du = -u / ||u||_2, or -sign(u) for the 1-norm
+            const float apu = m.p1 ? (u[k] > 0.f ? -gp : (u[k] < 0.f ? gp : 0.f)) : ap * u[k];
             dq[k] = a1[k] - s1 * cx.q[k] + apu;
             dtp[k] = -apu;
             if (m.scorer == KGE_TRANSH) {
@@ -369,7 +374,8 @@ __global__ void kge_tfinish_kernel(const float *accT_part, const float4 *sumT_pa
     const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (n >= N) return;
     float cs = 0.f;
-    for (int s = 0; s < nsplit; ++s) cs += sumT_part[(size_t)s * Np + n].x;
+    if (dist_kind)
+        for (int s = 0; s < nsplit; ++s) cs += sumT_part[(size_t)s * Np + n].x;
     // the row is read once (from the gathered copy when there is one, else from the table) and kept in registers
     float x[KGE_MAXJ], f = 0.f;
     const bool need_row = reg > 0.f || dist_kind;
@@ -433,12 +439,12 @@ __global__ void kge_zero_rows_kernel(float *p, int64_t count) {
 // host launchers
 // ---------------------------------------------------------------------------------------------
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
-                   int dp, void *Q, void *W, void *Q2, KgeRowInfo *rowinfo, float *pos_ws, float *pos_out,
-                   hipStream_t st) {
+                   int dp, void *Q, void *W, void *Q2, float *Q32, KgeRowInfo *rowinfo, float *pos_ws,
+                   float *pos_out, hipStream_t st) {
     const int grid = (Bp + 3) / 4;
     if (grid == 0) return KGE_OK;
-    if (m.bf16) hipLaunchKernelGGL(kge_qbuild_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, rowinfo, pos_ws, pos_out);
-    else        hipLaunchKernelGGL(kge_qbuild_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, rowinfo, pos_ws, pos_out);
+    if (m.bf16) hipLaunchKernelGGL(kge_qbuild_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, rowinfo, pos_ws, pos_out);
+    else        hipLaunchKernelGGL(kge_qbuild_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, rowinfo, pos_ws, pos_out);
     return kge_launch_status();
 }
 

@@ -1,0 +1,136 @@
+"""The 1-norm variants of TransE and RotatE on the GPU (kge_score, kge_loss_bwd with p_norm = 1) against the
+oracle.  The gradient of a 1-norm is discontinuous where a coordinate of h + r - t crosses zero, so the TransE
+cases put the tables on a binary grid on which every sum and difference is exact in fp32 and in bf16 (no sign can
+differ between the two implementations; with the relations on the same grid the micro-batch is full of exact ties,
+which must give the sub-gradient 0).  RotatE goes through sin / cos, where a sign may flip for a coordinate within
+rounding of zero: there a handful of outlying gradient elements is tolerated and counted."""
+import numpy as np
+import pytest
+
+import kge_synth as ks
+from helpers import RTOL_BF16, RTOL_F32, dev_idx, norm_err, small_graph, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _grid_case(scorer, n_ent, n_rel, dim, B, N, ties, seed=ks.BASE_SEED):
+    G = small_graph(scorer, n_ent, n_rel, dim, B, N, seed=seed, amp=0.5)
+    G["ent"] = (np.round(G["ent"] * 64) / 64).astype(np.float32)
+    if scorer == "transe":
+        # off the entities' grid by half a step: no coordinate of h + r - t can be zero
+        G["rel"] = (np.round(G["rel"] * 64) / 64 + (0.0 if ties else 1.0 / 128)).astype(np.float32)
+    z = ks.ZipfIds(n_ent, 1.1)
+    g = ks.rng(seed, ks.TAG_BATCH, 1)
+    G["h"], G["t"] = z.draw(g, B), z.draw(g, B)
+    return G
+
+
+def _model(scorer, G, bf16):
+    import paper_2211_12281_amd as kge
+    return kge.Model(scorer, to_dev(G["ent"], bf16), to_dev(G["rel"], bf16), None, p_norm=1)
+
+
+def _outliers(x, ref, tol):
+    e = np.abs(np.asarray(x, np.float64) - ref) / max(float(np.max(np.abs(ref))), 1e-300)
+    return int(np.sum(e > tol)), float(e.max()) if e.size else 0.0
+
+
+def _compare(orc, scorer, loss, G, bf16, n_ent, kw, max_outliers=0):
+    import paper_2211_12281_amd as kge
+    out = kge.loss_bwd(_model(scorer, G, bf16), loss, dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]), **kw)
+    ref = orc.loss_bwd(scorer + "_l1", loss, G["ent"], G["rel"], None, G["h"], G["r"], G["t"], G["neg"], **kw)
+    tol = RTOL_BF16 if bf16 else RTOL_F32
+    assert abs(out["loss"].item() - ref["loss"]) <= tol * abs(ref["loss"])
+    B, N = len(G["h"]), len(G["neg"])
+    ge = out["g_ent"].cpu().numpy()
+    total = 0
+    for name, x, r in (("g_head", ge[:B], ref["g_ent"][:B]), ("g_tail", ge[B:2 * B], ref["g_ent"][B:2 * B]),
+                       ("g_neg", ge[2 * B:], ref["g_ent"][2 * B:]), ("g_rel", out["g_rel"].cpu().numpy(), ref["g_rel"])):
+        if r.size == 0:
+            continue
+        bad, worst = _outliers(x, r, tol)
+        total += bad
+        assert bad <= max_outliers and worst < 0.5, (name, bad, worst)
+    assert np.array_equal(out["g_ent_idx"].cpu().numpy(), ref["g_ent_idx"])
+    assert np.array_equal(out["g_rel_idx"].cpu().numpy(), ref["g_rel_idx"])
+    return total
+
+
+@pytest.mark.parametrize("scorer", ["transe", "rotate"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_scores_match_oracle(orc, scorer, bf16):
+    import paper_2211_12281_amd as kge
+    for (B, N, dim) in [(70, 300, 32), (257, 1000, 208)]:
+        G = small_graph(scorer, 3000, 9, dim, B, N, amp=0.3)
+        if bf16:
+            G["ent"], G["rel"] = ks.round_to_bf16(G["ent"]), ks.round_to_bf16(G["rel"])
+        pos, neg = kge.score(_model(scorer, G, bf16), dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]))
+        rp, rn = orc.score_batch(scorer + "_l1", G["ent"], G["rel"], None, G["h"], G["r"], G["t"], G["neg"])
+        # the arithmetic is fp32 also for bf16 tables (the query is not rounded to the table type)
+        assert norm_err(pos.cpu().numpy(), rp) <= RTOL_F32
+        assert norm_err(neg.cpu().numpy(), rn) <= RTOL_F32
+
+
+@pytest.mark.parametrize("loss", ["logsigmoid", "sampled_softmax"])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("ties", [False, True])
+def test_transe_loss_and_gradients(orc, loss, bf16, ties):
+    G = _grid_case("transe", 4000, 12, 64, 200, 333, ties)
+    kw = dict(n_ent_for_c=4000) if loss == "sampled_softmax" else dict(gamma=6.0, adv_temp=0.5)
+    _compare(orc, "transe", loss, G, bf16, 4000, kw)
+    if ties:
+        # the case is only worth its name if exact ties are frequent
+        q = G["ent"][G["h"]] + G["rel"][G["r"]]
+        assert np.mean(q[:, None, :] == G["ent"][G["neg"]][None, :, :]) > 0.005
+
+
+@pytest.mark.parametrize("loss", ["logsigmoid", "sampled_softmax"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_rotate_loss_and_gradients(orc, loss, bf16):
+    G = small_graph("rotate", 4000, 12, 64, 200, 333, amp=0.3)
+    if bf16:
+        G["ent"], G["rel"] = ks.round_to_bf16(G["ent"]), ks.round_to_bf16(G["rel"])
+    kw = dict(n_ent_for_c=4000) if loss == "sampled_softmax" else dict(gamma=8.0, adv_temp=0.3)
+    # the arithmetic is fp32 for both table types: fp32 tolerance, at most a few sign flips in 4.3 M coordinates
+    G2 = dict(G)
+    import paper_2211_12281_amd as kge
+    out = kge.loss_bwd(_model("rotate", G, bf16), loss, dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]), **kw)
+    ref = orc.loss_bwd("rotate_l1", loss, G["ent"], G["rel"], None, G["h"], G["r"], G["t"], G["neg"], **kw)
+    assert abs(out["loss"].item() - ref["loss"]) <= RTOL_F32 * abs(ref["loss"])
+    bad_total = 0
+    for x, r in ((out["g_ent"].cpu().numpy(), ref["g_ent"]), (out["g_rel"].cpu().numpy(), ref["g_rel"])):
+        bad, worst = _outliers(x, r, 2e-5)
+        bad_total += bad
+        assert worst < 0.5
+    assert bad_total <= 6, bad_total
+
+
+@pytest.mark.parametrize("dim,bf16", [(128, False), (256, True), (512, True), (32, False)])
+def test_other_row_sizes_and_shapes(orc, dim, bf16):
+    for (B, N) in [(150, 260), (1, 1), (3, 0), (130, 1), (1, 130)]:
+        G = _grid_case("transe", 3000, 9, dim, B, N, False)
+        _compare(orc, "transe", "sampled_softmax", G, bf16, 3000, dict(n_ent_for_c=3000))
+        # the margin follows the typical distance (about 0.35 per coordinate on this grid), else sigma(gamma + s)
+        # underflows in fp32 for the long rows
+        _compare(orc, "transe", "logsigmoid", G, bf16, 3000, dict(gamma=0.35 * dim, adv_temp=0.2, loss_scale=0.37))
+
+
+def test_regulariser_and_repeatability(orc):
+    import paper_2211_12281_amd as kge
+    G = _grid_case("transe", 2000, 5, 64, 96, 200, True)
+    kw = dict(n_ent_for_c=2000, reg_l3=1e-2)
+    _compare(orc, "transe", "sampled_softmax", G, False, 2000, kw)
+    m = _model("transe", G, False)
+    args = (dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]))
+    a = {k: v.clone() for k, v in kge.loss_bwd(m, "sampled_softmax", *args, **kw).items() if v is not None}
+    b = kge.loss_bwd(m, "sampled_softmax", *args, **kw)
+    for k in a:
+        assert bool((a[k] == b[k]).all()), k
+
+
+def test_transh_with_the_one_norm_is_refused():
+    import paper_2211_12281_amd as kge
+    G = small_graph("transh", 100, 3, 32, 8, 8)
+    m = kge.Model("transh", to_dev(G["ent"]), to_dev(G["rel"]), to_dev(G["relw"]), p_norm=1)
+    with pytest.raises(kge.KgeError):
+        kge.score(m, dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]))
