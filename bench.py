@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--encoder", type=int, default=0, metavar="FEAT_DIM",
                     help="training workloads: entities are encoded as e_S + M e_F from synthetic text features of "
                          "this width (768 in the paper) with dropout 0.1, trained M_H and M_T; default: shallow only")
+    ap.add_argument("--p-norm", type=int, default=2, choices=[1, 2],
+                    help="training workloads with --scorer transe or rotate: the norm of the distance (Table 2); 1 runs the "
+                         "vector-pipe kernels of the 1-norm variants")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy first (reference for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -54,13 +57,16 @@ def parse():
 class TrainWorkload:
     """c3 / c5 / c1: forward + backward + sparse Adam on bf16 shadow / fp32 master tables."""
 
-    def __init__(self, name, P, scale, only=None, reg_l3=0.0, sampled=0, feat_dim=0):
+    def __init__(self, name, P, scale, only=None, reg_l3=0.0, sampled=0, feat_dim=0, p_norm=2):
         import torch
         import kge_synth as ks
         import kge_synth.device as ksd
         import paper_2211_12281_amd as kge
         self.kge, self.torch, self.ks, self.P, self.name = kge, torch, ks, P, name
         self.scorer = only or P["scorers"][0]
+        self.p_norm = p_norm
+        if p_norm == 1 and self.scorer not in ("transe", "rotate"):
+            raise SystemExit("--p-norm 1 needs --scorer transe or --scorer rotate")
         self.n_ent = max(1000, int(P["n_ent"] * scale))
         self.n_rel, self.d, self.B, self.N = P["n_rel"], P["dim"], P["B"], P["N"]
         self.bf16 = P["dtype"] == "bf16"
@@ -84,7 +90,8 @@ class TrainWorkload:
             self.relw_m, self.relw_v = torch.zeros_like(self.relw), torch.zeros_like(self.relw)
             self.relw_sh = self.relw.to(torch.bfloat16) if self.bf16 else None
         self.model = kge.Model(self.scorer, self.ent_sh if self.bf16 else self.ent,
-                               self.rel_sh if self.bf16 else self.rel, self.relw_sh if self.bf16 else self.relw)
+                               self.rel_sh if self.bf16 else self.rel, self.relw_sh if self.bf16 else self.relw,
+                               p_norm=p_norm)
         # index streams: a ring of pre-drawn micro-batches, resident on the device
         self.batches = []
         self.host_batches = []
@@ -179,7 +186,7 @@ class TrainWorkload:
         if self.enc is not None:
             B, N = self.B, self.N
             e, proj, _ = self.enc.encode(h, t, self.neg, seed=ks.BASE_SEED, step=i)
-            model = kge.Model(self.scorer, e, self.model.rel, self.model.relw)
+            model = kge.Model(self.scorer, e, self.model.rel, self.model.relw, p_norm=self.p_norm)
             kge.loss_bwd(model, self.P["loss"], self.ar[:B], r, self.ar[B:2 * B], self.ar[2 * B:], out=self.out, **self.loss_kw)
             g_es, g_mh, g_mt = self.enc.encode_bwd(h, t, self.neg, proj, self.out["g_ent"], seed=ks.BASE_SEED, step=i)
             idx = self.torch.cat([h, t, self.neg])
@@ -201,6 +208,8 @@ class TrainWorkload:
 
     def extra(self, ms):
         out = {"triples_per_s": self.B / (ms * 1e-3), "scorer": self.scorer, "reg_l3": self.loss_kw.get("reg_l3", 0.0)}
+        if self.p_norm == 1:
+            out["p_norm"] = 1
         if self.enc is not None:
             out["encoder"] = f"e_S + M e_F, synthetic features of width {self.feat_dim}, dropout 0.1, M_H and M_T trained"
         if self.sampler is not None:
@@ -216,6 +225,11 @@ class TrainWorkload:
             return 2.0 * (2 * self.B + self.N) * self.feat_dim * self.d
         gemms = (2 if slot == "block_fwd" else 1) * (2 if self.scorer == "transh" else 1)
         return 2.0 * self.B * self.N * self.d * gemms
+
+    def alu_ops(self, slot):
+        # 1-norm kernels: two vector operations per (query, negative, dimension) and pass - subtract and
+        # accumulate |.| for the scores, select by the sign and accumulate for a gradient pass
+        return 2.0 * self.B * self.N * self.d
 
     def cpu_baseline(self, orc):
         """Oracle forward + backward + sparse Adam on the first rows of batch 0 against all negatives."""
@@ -234,7 +248,7 @@ class TrainWorkload:
             relw = None if relw is None else ks.round_to_bf16(relw)
         kw = dict(self.loss_kw)
         t0 = time.time()
-        out = orc.loss_bwd(self.scorer, self.P["loss"], rows, rel, relw, ch, r, ct, cn, **kw)
+        out = orc.loss_bwd(self.scorer + ("_l1" if self.p_norm == 1 else ""), self.P["loss"], rows, rel, relw, ch, r, ct, cn, **kw)
         z = np.zeros_like(rows, dtype=np.float64)
         orc.sparse_adam(rows, z, z, out["g_ent_idx"], out["g_ent"].astype(np.float32), self.P["lr"])
         dt = time.time() - t0
@@ -372,7 +386,7 @@ def main():
     kge.load()
     P = ks.PRESETS[a.workload]
     if a.workload in ("c1", "c3", "c5"):
-        wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3, a.sampled_batches, a.encoder)
+        wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3, a.sampled_batches, a.encoder, a.p_norm)
     elif a.workload == "c2":
         wl = ScoreWorkload(P, a.scale, a.scorer)
     else:
@@ -405,7 +419,13 @@ def main():
     if prof:
         dom = max(prof, key=lambda k: prof[k]["total_ms"])
         avg_s = prof[dom]["avg_us"] * 1e-6
-        if dom.startswith("block") or dom.startswith("enc_") or dom == "topk_scan":
+        if dom.startswith("block") and getattr(wl, "p_norm", 2) == 1:
+            # vector pipe: 256 compute units x 128 lanes x 2.4 GHz = 78.6 T operations/s (the fp32 vector peak of
+            # 157.3 TFLOP/s counts a fused multiply-add as two; these kernels have none to fuse)
+            ach = wl.alu_ops(dom) / avg_s / 1e12
+            roof = {"kernel": dom, "bound": "alu", "achieved": ach, "peak": PEAK_F32_TFLOPS / 2, "unit": "Top/s",
+                    "frac": ach / (PEAK_F32_TFLOPS / 2), "traffic": None, "avg_us": avg_s * 1e6}
+        elif dom.startswith("block") or dom.startswith("enc_") or dom == "topk_scan":
             flops = wl.mfma_flops(dom)
             if dom == "topk_scan":
                 avg_s = prof[dom]["total_ms"] * 1e-3 / (a.steps * len(wl.scorers))   # all chunk launches of one call
@@ -440,7 +460,7 @@ def main():
         cpu["seconds"] = round(secs, 2)
         cpu["sample"] += f" (x{reps})"
 
-    if roof is not None:
+    if roof is not None and roof["bound"] == "mfma":
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
             try:
