@@ -123,44 +123,43 @@ __global__ __launch_bounds__(256) void l1_rowstat_kernel(const float *S, int64_t
 
 // out[split][o, j] = -sum_s w(o, s) sign(own_oj - str_sj) over the split's rows of the streamed operand: with
 // own = queries this is dq (s runs over the negatives), with own = negatives it is dt (s runs over the queries;
-// the sign flips twice).  Workgroup = 128 own rows x 128 dimensions; thread = own rows 4 ty + i + 64 i',
-// dimensions 4 tx + c + 64 c' (an 8 x 8 register tile: four 16-byte LDS reads feed 64 sign terms).  The queries
+// the sign flips twice).  Workgroup = 128 own rows x 64 dimensions; thread = own rows 4 ty + i + 64 i',
+// dimensions 4 tx + c (an 8 x 4 register tile: three 16-byte LDS reads feed 32 sign terms; about 120 registers,
+// four waves per SIMD).  The queries
 // are fp32, the negatives of the table type.  Both operands are scaled by 2^100 when they are loaded (exact), so that
 // sign(own - str) = median(-1, (own - str) 2^100, 1) is one subtraction and one median: a non-zero difference of
 // two floats whose magnitudes exceed 2^-76 is at least 2^-100, its scaled value at least 1; a zero difference
-// stays zero (sub-gradient 0).  Three vector operations per (own row, streamed row, dimension).  Per chunk of 64
+// stays zero (sub-gradient 0).  Three vector operations per (own row, streamed row, dimension).  Per chunk of 32
 // streamed rows the weights w = 2^(x log2e + K_b) (times sigma(gamma + s) for the log-sigmoid loss) are computed
-// once from S and the finished row constants into the LDS.  Two workgroups share a compute unit (66 KB of LDS each,
-// at most 256 registers per lane): one's loads and weight computation overlap the other's sign terms.
-constexpr int L1_GT = 128;             // own rows and dimensions of a gradient workgroup
-constexpr int L1_GP = 132;             // floats per LDS row of the gradient kernel (16 lanes x 16 bytes stay conflict-free)
+// once from S and the finished row constants into the LDS.
+constexpr int L1_GO = 128, L1_GD = 64, L1_GS = 32;   // own rows, dimensions, streamed rows per chunk of a gradient workgroup
+constexpr int L1_WP = 132;                            // floats per LDS row of the weights (16 lanes x 16 bytes stay conflict-free)
 
 template <bool BF16, bool OWN_Q>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void l1_grad_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void l1_grad_kernel(
         const void *own, const void *str, const float *S, int64_t ldS, const KgeRowInfo *rowinfo, int B, int N, int own_pad,
         int dp, int chunks, int cps, int loss, float gamma, float adv_temp, float *acc_part) {
-    extern __shared__ __attribute__((aligned(16))) float l1_lds[];
-    float *ss = l1_lds, *ws = l1_lds + L1_TILE * L1_GP;     // [64 streamed rows][128 dims], [64 streamed rows][128 own rows]
+    __shared__ __attribute__((aligned(16))) float ss[L1_GS * L1_PITCH], ws[L1_GS * L1_WP];
     constexpr bool SBF = BF16 && OWN_Q, OBF = BF16 && !OWN_Q;   // table type of the streamed / own operand
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const int o0 = blockIdx.x * L1_GT, j0 = blockIdx.y * L1_GT, split = blockIdx.z;
+    const int o0 = blockIdx.x * L1_GO, j0 = blockIdx.y * L1_GD, split = blockIdx.z;
     const float xscale = (loss == KGE_LOGSIGMOID ? adv_temp : 1.f) * L1_LOG2E;
-    float ov[8][8], acc[8][8];
+    float ov[8][4], acc[8][4];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const int o = o0 + 4 * ty + (i & 3) + 64 * (i >> 2), j = j0 + 4 * tx + (c & 3) + 64 * (c >> 2);
-            ov[i][c] = El<OBF>::ld(own, (int64_t)o * dp + j) * L1_BIG;
+        for (int c = 0; c < 4; ++c) {
+            const int o = o0 + 4 * ty + (i & 3) + 64 * (i >> 2);
+            ov[i][c] = El<OBF>::ld(own, (int64_t)o * dp + j0 + 4 * tx + c) * L1_BIG;
             acc[i][c] = 0.f;
         }
     const int c_lo = split * cps, c_hi = min(chunks, (split + 1) * cps);
     for (int ch = c_lo; ch < c_hi; ++ch) {
-        const int s0 = ch * L1_TILE;
+        const int s0 = ch * L1_GS;
         __syncthreads();                                    // everyone is done with the previous chunk
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int e = threadIdx.x + 256 * k, row = e >> 5, cq = e & 31;
+        for (int k = 0; k < 2; ++k) {
+            const int e = threadIdx.x + 256 * k, row = e >> 4, cq = e & 15;
             const int64_t off = (int64_t)(s0 + row) * dp + j0 + 4 * cq;
             l1_f32x4 v;
             if constexpr (SBF) {
@@ -170,13 +169,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             } else {
                 v = *(const l1_f32x4 *)((const float *)str + off);
             }
-            *(l1_f32x4 *)(ss + row * L1_GP + 4 * cq) = v * L1_BIG;
+            *(l1_f32x4 *)(ss + row * L1_PITCH + 4 * cq) = v * L1_BIG;
         }
-#pragma unroll 8
-        for (int k = 0; k < 32; ++k) {
+#pragma unroll 4
+        for (int k = 0; k < 16; ++k) {
             const int e = threadIdx.x + 256 * k;
             // consecutive threads take consecutive negatives: the reads of S are coalesced either way
-            const int ol = OWN_Q ? e >> 6 : e & 127, sl = OWN_Q ? e & 63 : e >> 7;
+            const int ol = OWN_Q ? e >> 5 : e & 127, sl = OWN_Q ? e & 31 : e >> 7;
             const int b = OWN_Q ? o0 + ol : s0 + sl, n = OWN_Q ? s0 + sl : o0 + ol;
             float w = 0.f;
             if (b < B && n < N) {
@@ -184,30 +183,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 w = __builtin_amdgcn_exp2f(fmaf(sc, xscale, rowinfo[b].K));
                 if (loss == KGE_LOGSIGMOID) w *= l1_sigmoid(gamma + sc);
             }
-            ws[sl * L1_GP + ol] = w;
+            ws[sl * L1_WP + ol] = w;
         }
         __syncthreads();
-#pragma unroll 2
-        for (int sl = 0; sl < L1_TILE; ++sl) {
-            l1_f32x4 w4[2], t4[2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                w4[u] = *(const l1_f32x4 *)(ws + sl * L1_GP + 4 * ty + 64 * u);
-                t4[u] = *(const l1_f32x4 *)(ss + sl * L1_GP + 4 * tx + 64 * u);
-            }
+#pragma unroll 4
+        for (int sl = 0; sl < L1_GS; ++sl) {
+            const l1_f32x4 w4[2] = { *(const l1_f32x4 *)(ws + sl * L1_WP + 4 * ty), *(const l1_f32x4 *)(ws + sl * L1_WP + 4 * ty + 64) };
+            const l1_f32x4 t4 = *(const l1_f32x4 *)(ss + sl * L1_PITCH + 4 * tx);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
-                for (int c = 0; c < 8; ++c)
-                    acc[i][c] = fmaf(-w4[i >> 2][i & 3], __builtin_amdgcn_fmed3f(ov[i][c] - t4[c >> 2][c & 3], -1.f, 1.f), acc[i][c]);
+                for (int c = 0; c < 4; ++c)
+                    acc[i][c] = fmaf(-w4[i >> 2][i & 3], __builtin_amdgcn_fmed3f(ov[i][c] - t4[c], -1.f, 1.f), acc[i][c]);
         }
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-            *(l1_f32x4 *)(acc_part + ((int64_t)split * own_pad + o0 + 4 * ty + (i & 3) + 64 * (i >> 2)) * dp + j0 + 4 * tx + 64 * u) =
-                l1_f32x4{acc[i][4 * u], acc[i][4 * u + 1], acc[i][4 * u + 2], acc[i][4 * u + 3]};
+        *(l1_f32x4 *)(acc_part + ((int64_t)split * own_pad + o0 + 4 * ty + (i & 3) + 64 * (i >> 2)) * dp + j0 + 4 * tx) =
+            l1_f32x4{acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
 }
 
 }  // namespace
@@ -231,11 +224,11 @@ int kge_run_l1_rowstat(const float *S, int64_t ldS, int B, int N, int Bp, int lo
     return kge_launch_status();
 }
 
-// splits over the streamed rows: enough workgroups for about two per compute unit
+// splits over the streamed rows: enough workgroups for about four per compute unit
 int kge_l1_nsplit(int own_pad, int str_pad, int dp) {
-    const int base = (own_pad / L1_GT) * (dp / L1_GT), chunks = str_pad / L1_TILE;
+    const int base = (own_pad / L1_GO) * (dp / L1_GD), chunks = str_pad / L1_GS;
     if (base == 0 || chunks == 0) return 0;
-    int want = (512 + base - 1) / base;
+    int want = (1024 + base - 1) / base;
     if (want > chunks) want = chunks;
     const int cps = (chunks + want - 1) / want;
     return (chunks + cps - 1) / cps;
@@ -244,22 +237,12 @@ int kge_l1_nsplit(int own_pad, int str_pad, int dp) {
 int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *str, const float *S, int64_t ldS,
                     const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp, int loss, float gamma,
                     float adv_temp, int nsplit, float *acc_part, hipStream_t st) {
-    if (own_pad % L1_GT || str_pad % L1_TILE || dp % L1_GT) return KGE_E_INVALID_ARG;
+    if (own_pad % L1_GO || str_pad % L1_GS || dp % L1_GD) return KGE_E_INVALID_ARG;
     if (nsplit <= 0 || nsplit != kge_l1_nsplit(own_pad, str_pad, dp)) return KGE_E_INVALID_ARG;
-    constexpr int LDS = 2 * L1_TILE * L1_GP * (int)sizeof(float);     // 66 KB: above the default dynamic limit
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)l1_grad_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess ||
-            hipFuncSetAttribute((const void *)l1_grad_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess ||
-            hipFuncSetAttribute((const void *)l1_grad_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess ||
-            hipFuncSetAttribute((const void *)l1_grad_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
-            return KGE_E_HIP;
-        attr_done = true;
-    }
     KgeProfScope prof(own_is_query ? KGE_PROF_BLOCK_FWD : KGE_PROF_BLOCK_GRADT, st);
-    const int chunks = str_pad / L1_TILE, cps = (chunks + nsplit - 1) / nsplit;
-    const dim3 grid(own_pad / L1_GT, dp / L1_GT, nsplit);
-#define L1_GRAD(BF, OQ) hipLaunchKernelGGL((l1_grad_kernel<BF, OQ>), grid, dim3(256), LDS, st, own, str, S, ldS, rowinfo, B, N, \
+    const int chunks = str_pad / L1_GS, cps = (chunks + nsplit - 1) / nsplit;
+    const dim3 grid(own_pad / L1_GO, dp / L1_GD, nsplit);
+#define L1_GRAD(BF, OQ) hipLaunchKernelGGL((l1_grad_kernel<BF, OQ>), grid, dim3(256), 0, st, own, str, S, ldS, rowinfo, B, N, \
                                            own_pad, dp, chunks, cps, loss, gamma, adv_temp, acc_part)
     if (bf16) { if (own_is_query) L1_GRAD(true, true); else L1_GRAD(true, false); }
     else      { if (own_is_query) L1_GRAD(false, true); else L1_GRAD(false, false); }
