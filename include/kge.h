@@ -48,7 +48,7 @@ typedef enum { KGE_OP_SCORE = 0, KGE_OP_LOSS_BWD = 1, KGE_OP_SPARSE_ADAM = 2, KG
 enum {
     KGE_OK = 0,
     KGE_E_INVALID_ARG = -1,         /* NULL where data is required, negative size, bad enum, bad dim */
-    KGE_E_UNSUPPORTED = -2,         /* valid request this build has no kernel for (e.g. p_norm = 1) */
+    KGE_E_UNSUPPORTED = -2,         /* valid request this build has no kernel for (e.g. TransH with p_norm = 1) */
     KGE_E_WORKSPACE_TOO_SMALL = -3,
     KGE_E_HIP = -4                  /* a HIP runtime call failed (launch error) */
 };
@@ -56,7 +56,11 @@ enum {
 /* A model = scorer + tables (Section 3.1: shallow entity / relation embeddings; TransH adds w_r). */
 typedef struct {
     int32_t scorer;      /* kge_scorer_t */
-    int32_t p_norm;      /* distance scorers: 2 (1 is not implemented -> KGE_E_UNSUPPORTED) */
+    int32_t p_norm;      /* distance scorers: 2, or 1 (Table 2: p in {1, 2}) for TransE and RotatE - RotatE then takes
+                            the 1-norm in R^d, |Re| + |Im| per complex coordinate; the 1-norm has no contraction
+                            form, its kernels run on the vector pipe and kge_loss_bwd keeps the B x N score block
+                            in the workspace.  TransH with p_norm = 1, and kge_topk with p_norm = 1:
+                            KGE_E_UNSUPPORTED.  Ignored by DistMult and ComplEx. */
     int32_t dtype;       /* kge_dtype_t of ent, rel, relw as the kernels read them */
     int32_t dim;         /* d */
     int32_t rel_dim;     /* d, or d/2 for RotatE */
@@ -155,7 +159,8 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
  * single-GPU image of "score against the local shard E_i"; D shard-wise lists merge to the global
  * top-K (Section 4, "Inference").
  * Exactness: candidates are pre-selected with matrix-core scores, the survivors are re-scored with
- * a sequential fp64 fused-multiply-add loop and ordered by that key, and a rigorous error bound
+ * a sequential fp64 loop (the direct formula of Table 2, every operation rounded on its own; DistMult
+ * and TransE with one fused multiply-add per column) and ordered by that key, and a rigorous error bound
  * checks that no candidate outside the pre-selection could belong to the top-K; queries that fail
  * the check are re-ranked by an exhaustive fp64 scan.  The returned indices therefore equal the
  * ordering by the fp64 key exactly.
@@ -163,7 +168,9 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
  * the candidates.  Exact whenever rank <= K (it is the list position); beyond K it is counted
  * with the matrix-core scores and may differ from the fp64 rank by the number of candidates whose
  * score lies within the rounding error of the true tail's score.
- * Scorers: DistMult and TransE (others: KGE_E_UNSUPPORTED).  1 <= K <= 256.
+ * Scorers: DistMult, ComplEx, TransE and RotatE with p_norm = 2 (TransH, p_norm = 1: KGE_E_UNSUPPORTED).
+ * RotatE's key passes through cos / sin of the phases in fp64: its last bit is the math library's.
+ * 1 <= K <= 256.
  */
 int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64_t Q,
              int64_t cand_lo, int64_t cand_hi, int32_t K, int32_t *out_idx, float *out_score,

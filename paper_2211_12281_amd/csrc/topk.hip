@@ -334,36 +334,69 @@ __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *
 }
 
 // ---------------------------------------------------------------------------------------------
-// fp64 ranking key (smaller is better): DistMult -sum fma(h r, t), TransE sum fma(x, x), x = (h + r) - t
+// fp64 ranking key (smaller is better), defined on the exact query q (fp64 from the table values) and the tail row:
+//   DistMult  q = h r,            key = -acc,  acc = fma(q_j, t_j, acc)
+//   TransE    q = h + r,          key =  acc,  x = q_j - t_j, acc = fma(x, x, acc)
+//   ComplEx   q = h * r (complex),  key = -acc,  acc = acc + (q_re t_re + q_im t_im) per complex coordinate
+//   RotatE    q = h * e^{ir},       key =  acc,  acc = acc + (x_re^2 + x_im^2), x = q - t
+// every operation rounded on its own (no contraction), in this order: the same sequence of IEEE operations as
+// the direct loops of Table 2 written in C give.  RotatE goes through cos / sin of the phase in fp64, whose last
+// bit is the math library's.
 // ---------------------------------------------------------------------------------------------
+constexpr int TK_MAXD = 512;
+
+__device__ __forceinline__ bool topk_mult(int scorer) { return scorer == KGE_DISTMULT || scorer == KGE_COMPLEX; }
+__device__ __forceinline__ bool topk_cplx(int scorer) { return scorer == KGE_COMPLEX || scorer == KGE_ROTATE; }
+
+// component j of the exact query (complex scorers: j < d/2 real parts, then imaginary parts)
 template <bool BF16>
-__device__ double canonical_key(int scorer, int d, const void *ent, int64_t hoff, const void *rel, int64_t roff,
-                                int64_t toff) {
+__device__ double query_f64(const KgeModelDev &m, int64_t hoff, int64_t roff, int j) {
+    if (m.scorer == KGE_DISTMULT) return __dmul_rn((double)El<BF16>::ld(m.ent, hoff + j), (double)El<BF16>::ld(m.rel, roff + j));
+    if (m.scorer == KGE_TRANSE) return __dadd_rn((double)El<BF16>::ld(m.ent, hoff + j), (double)El<BF16>::ld(m.rel, roff + j));
+    const int c = m.dim >> 1, jr = j < c ? j : j - c;
+    const double hre = (double)El<BF16>::ld(m.ent, hoff + jr), him = (double)El<BF16>::ld(m.ent, hoff + jr + c);
+    double rre, rim;
+    if (m.scorer == KGE_COMPLEX) { rre = (double)El<BF16>::ld(m.rel, roff + jr); rim = (double)El<BF16>::ld(m.rel, roff + jr + c); }
+    else { const double ph = (double)El<BF16>::ld(m.rel, roff + jr); rre = cos(ph); rim = sin(ph); }
+    return j < c ? __dsub_rn(__dmul_rn(hre, rre), __dmul_rn(him, rim)) : __dadd_rn(__dmul_rn(hre, rim), __dmul_rn(him, rre));
+}
+
+// one step of the key's accumulation: real scorers one column, complex scorers one complex coordinate
+__device__ __forceinline__ double key_step(int scorer, double acc, double q0, double t0, double q1, double t1) {
+    switch (scorer) {
+    case KGE_DISTMULT: return fma(q0, t0, acc);
+    case KGE_TRANSE: { const double x = __dsub_rn(q0, t0); return fma(x, x, acc); }
+    case KGE_COMPLEX: return __dadd_rn(acc, __dadd_rn(__dmul_rn(q0, t0), __dmul_rn(q1, t1)));
+    default: { const double xr = __dsub_rn(q0, t0), xi = __dsub_rn(q1, t1);
+               return __dadd_rn(acc, __dadd_rn(__dmul_rn(xr, xr), __dmul_rn(xi, xi))); }
+    }
+}
+
+// key of one tail row against the exact query qv[0 .. d)
+template <bool BF16>
+__device__ double canonical_key(int scorer, int d, const double *qv, const void *ent, int64_t toff) {
     double acc = 0.0;
-    if (scorer == KGE_DISTMULT) {
-        for (int j = 0; j < d; ++j) {
-            const double hr = (double)El<BF16>::ld(ent, hoff + j) * (double)El<BF16>::ld(rel, roff + j);
-            acc = fma(hr, (double)El<BF16>::ld(ent, toff + j), acc);
-        }
-        return -acc;
+    if (topk_cplx(scorer)) {
+        const int c = d >> 1;
+        for (int j = 0; j < c; ++j)
+            acc = key_step(scorer, acc, qv[j], (double)El<BF16>::ld(ent, toff + j), qv[j + c], (double)El<BF16>::ld(ent, toff + j + c));
+    } else {
+        for (int j = 0; j < d; ++j) acc = key_step(scorer, acc, qv[j], (double)El<BF16>::ld(ent, toff + j), 0.0, 0.0);
     }
-    for (int j = 0; j < d; ++j) {
-        const double x = ((double)El<BF16>::ld(ent, hoff + j) + (double)El<BF16>::ld(rel, roff + j)) -
-                         (double)El<BF16>::ld(ent, toff + j);
-        acc = fma(x, x, acc);
-    }
-    return acc;
+    return topk_mult(scorer) ? -acc : acc;
 }
 
 // One wave re-scores 64 survivors of one query, lane = survivor, so that the 64 sequential fp64 chains run in
-// lockstep.  The candidate rows arrive through the LDS in chunks of 64 columns: coalesced row reads on the way
-// in, conflict-free column reads (row stride odd in dwords) on the way out; the query's factor of a column
-// (h r, or h + r, exact in fp64) is computed once per wave.  The key is the one of canonical_key, term by term.
+// lockstep.  The candidate rows arrive through the LDS in chunks of 64 columns (complex scorers: 32 real parts
+// followed by the 32 imaginary parts of the same coordinates): coalesced row reads on the way in, conflict-free
+// column reads (row stride odd in dwords) on the way out; the exact query components of a chunk are computed once
+// per wave.  The key is the one of canonical_key, step by step.
 template <bool BF16>
 __global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q,
                                                            int64_t cand_lo, const int32_t *cnt, const uint2 *buf, int KP,
                                                            double *keyd) {
     constexpr int DW = BF16 ? 32 : 64;                  // dwords per row chunk of 64 columns
+    constexpr int E = BF16 ? 2 : 1;                     // columns per dword
     __shared__ uint32_t rows[4][64 * (DW + 1)];
     __shared__ double qd[4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -375,50 +408,45 @@ __global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const 
     if (s0 >= n) return;
     const bool valid = s0 + lane < n;
     const int64_t cand = cand_lo + buf[(size_t)q * KP + (valid ? s0 + lane : s0)].y;
-    const int d = m.dim;
+    const int d = m.dim, half = d >> 1;
+    const bool cplx = topk_cplx(m.scorer);
+    const int span = cplx ? 32 : 64, total = cplx ? half : d;      // key steps per chunk, in all
     const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
     uint32_t *mine = rows[wave];
+    auto elem = [&](const uint32_t *row, int e) -> double {        // staged element e of a row
+        if constexpr (BF16) return (double)__uint_as_float((e & 1) ? (row[e >> 1] & 0xffff0000u) : (row[e >> 1] << 16));
+        else return (double)__uint_as_float(row[e]);
+    };
     double acc = 0.0;
-    for (int c0 = 0; c0 < d; c0 += 64) {
-        const int cols = d - c0 < 64 ? d - c0 : 64;
-        if (lane < cols) {
-            const double hv = (double)El<BF16>::ld(m.ent, hoff + c0 + lane), rv = (double)El<BF16>::ld(m.rel, roff + c0 + lane);
-            qd[wave][lane] = m.scorer == KGE_DISTMULT ? hv * rv : hv + rv;
-        }
+    for (int c0 = 0; c0 < total; c0 += span) {
+        const int steps = total - c0 < span ? total - c0 : span;
+        // staged element e <-> table column: real scorers c0 + e; complex: c0 + e (e < 32), d/2 + c0 + e - 32 (else)
+        auto column = [&](int e) { return cplx ? (e < 32 ? c0 + e : half + c0 + e - 32) : c0 + e; };
+        auto live = [&](int e) { return (cplx ? (e & 31) : e) < steps; };
+        if (live(lane)) qd[wave][lane] = query_f64<BF16>(m, hoff, roff, column(lane));
         constexpr int RPI = 64 / DW;                    // rows per wave-wide load
         const int sub = lane / DW, dw = lane % DW;
         for (int rr = 0; rr < 64; rr += RPI) {
             const int64_t c = __shfl(cand, rr + sub);
             uint32_t v = 0u;
-            if (dw * (BF16 ? 2 : 1) < cols)
-                v = *(const uint32_t *)((const char *)m.ent + (c * m.ent_ld + c0) * (BF16 ? 2 : 4) + dw * 4);
+            if (live(dw * E))
+                v = *(const uint32_t *)((const char *)m.ent + (c * m.ent_ld + column(dw * E)) * (BF16 ? 2 : 4));
             mine[(rr + sub) * (DW + 1) + dw] = v;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const uint32_t *row = mine + lane * (DW + 1);
-        if (m.scorer == KGE_DISTMULT) {
-            for (int j = 0; j < cols; ++j) {
-                float tv;
-                if constexpr (BF16) tv = __uint_as_float((j & 1) ? (row[j >> 1] & 0xffff0000u) : (row[j >> 1] << 16));
-                else tv = __uint_as_float(row[j]);
-                acc = fma(qd[wave][j], (double)tv, acc);
-            }
+        if (cplx) {
+            for (int j = 0; j < steps; ++j) acc = key_step(m.scorer, acc, qd[wave][j], elem(row, j), qd[wave][32 + j], elem(row, 32 + j));
         } else {
-            for (int j = 0; j < cols; ++j) {
-                float tv;
-                if constexpr (BF16) tv = __uint_as_float((j & 1) ? (row[j >> 1] & 0xffff0000u) : (row[j >> 1] << 16));
-                else tv = __uint_as_float(row[j]);
-                const double x = qd[wave][j] - (double)tv;
-                acc = fma(x, x, acc);
-            }
+            for (int j = 0; j < steps; ++j) acc = key_step(m.scorer, acc, qd[wave][j], elem(row, j), 0.0, 0.0);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    if (valid) keyd[(size_t)q * KP + s0 + lane] = m.scorer == KGE_DISTMULT ? -acc : acc;
+    if (valid) keyd[(size_t)q * KP + s0 + lane] = topk_mult(m.scorer) ? -acc : acc;
 }
 
 struct QInfo { double qn; float eps_a, eps_b; float pad; };   // |q~|^2 (fp64), rounding-bound coefficients
@@ -442,7 +470,7 @@ __global__ void topk_final_kernel(KgeModelDev m, const int32_t *h, const int32_t
     }
     __syncthreads();
     bitonic_asc_pair(key, idx, KPP);
-    const bool dm = m.scorer == KGE_DISTMULT;
+    const bool dm = topk_mult(m.scorer);
     for (int i = threadIdx.x; i < K; i += blockDim.x) {
         const bool ok = i < n;
         out_idx[(size_t)q * K + i] = ok ? (int32_t)(cand_lo + idx[i]) : -1;
@@ -453,7 +481,8 @@ __global__ void topk_final_kernel(KgeModelDev m, const int32_t *h, const int32_t
         // exact value is at most theta + eps; the list is safe if that stays strictly below the exact
         // value of the K-th entry.  eps bounds the rounding of the query to the table type and the
         // fp32 accumulation:  DistMult (|dq| + d 2^-23 |q~|) Tmax;  TransE 2|dq|(|q~|+Tmax) + |dq|^2 +
-        // d 2^-22 (|q~|+Tmax)^2, with Tmax the largest candidate norm.
+        // d 2^-22 (|q~|+Tmax)^2, with Tmax the largest candidate norm; ComplEx and RotatE are the same two forms on
+        // their own query (h * r, h * e^{ir}), whose fp32 evaluation error is part of dq.
         if (n >= KP && ncand > KP && K <= n) {
             const QInfo qi = qinfo[q];
             const double Tm = sqrt((double)*tmax2);
@@ -495,16 +524,18 @@ __global__ void topk_exact_kernel(KgeModelDev m, const int32_t *h, const int32_t
     const int q = blockIdx.x;
     if (q >= Q || !flag[q]) return;
     const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
-    double tkey = 0.0; int tt = -1;
-    if (true_t) { tt = true_t[q]; tkey = canonical_key<BF16>(m.scorer, m.dim, m.ent, hoff, m.rel, roff, (int64_t)tt * m.ent_ld); }
+    __shared__ double qv[TK_MAXD];
+    for (int j = threadIdx.x; j < m.dim; j += blockDim.x) qv[j] = query_f64<BF16>(m, hoff, roff, j);
     if (threadIdx.x == 0) { count = 0; tau = INFINITY; above = 0ull; }
     for (int i = threadIdx.x; i < CAPX; i += blockDim.x) { key[i] = INFINITY; idx[i] = 0x7FFFFFFF; }
     __syncthreads();
+    double tkey = 0.0; int tt = -1;
+    if (true_t) { tt = true_t[q]; tkey = canonical_key<BF16>(m.scorer, m.dim, qv, m.ent, (int64_t)tt * m.ent_ld); }
     unsigned long long mine = 0;
     for (int64_t c0 = 0; c0 < ncand; c0 += blockDim.x) {
         const int64_t c = c0 + threadIdx.x;
         if (c < ncand) {
-            const double kc = canonical_key<BF16>(m.scorer, m.dim, m.ent, hoff, m.rel, roff, (cand_lo + c) * m.ent_ld);
+            const double kc = canonical_key<BF16>(m.scorer, m.dim, qv, m.ent, (cand_lo + c) * m.ent_ld);
             if (true_t && (kc < tkey || (kc == tkey && cand_lo + c < tt))) ++mine;
             if (kc <= tau) { const int s = atomicAdd(&count, 1); key[s] = kc; idx[s] = (int)c; }   // s < CAPX by the compaction below
         }
@@ -518,7 +549,7 @@ __global__ void topk_exact_kernel(KgeModelDev m, const int32_t *h, const int32_t
         }
     }
     bitonic_asc_pair(key, idx, CAPX);
-    const bool dm = m.scorer == KGE_DISTMULT;
+    const bool dm = topk_mult(m.scorer);
     for (int i = threadIdx.x; i < K; i += blockDim.x) {
         const bool ok = idx[i] != 0x7FFFFFFF;
         out_idx[(size_t)q * K + i] = ok ? (int32_t)(cand_lo + idx[i]) : -1;
@@ -550,6 +581,7 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     KgeRowCtx<BF16> cx;
     kge_build_query<BF16>(m, h[q], r[q], lane, cx);
     const int d = m.dim;
+    const bool mult = topk_mult(m.scorer);
     const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
     double qn = 0.0, dq2 = 0.0;
     float vtl = 0.f, tnl = 0.f;
@@ -559,11 +591,9 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         const int j = lane + 64 * k;
         const float qr = El<BF16>::rnd(cx.q[k]);
         // (TransE: stored doubled - exact - so that the scan's contraction yields 2 q.t directly)
-        if (j < dp) El<BF16>::st(Qm, (int64_t)q * dp + j, m.scorer == KGE_DISTMULT ? cx.q[k] : 2.f * cx.q[k]);
+        if (j < dp) El<BF16>::st(Qm, (int64_t)q * dp + j, mult ? cx.q[k] : 2.f * cx.q[k]);
         if (j >= d) continue;
-        const double hx = (double)El<BF16>::ld(m.ent, hoff + j), rx = (double)El<BF16>::ld(m.rel, roff + j);
-        const double qex = m.scorer == KGE_DISTMULT ? hx * rx : hx + rx;      // the exact query component
-        const double dq = (double)qr - qex;
+        const double dq = (double)qr - query_f64<BF16>(m, hoff, roff, j);     // against the exact query component
         qn += (double)qr * (double)qr; dq2 += dq * dq;
         if (true_t) { const float tv = El<BF16>::ld(m.ent, toff + j); vtl += qr * tv; tnl += tv * tv; }
     }
@@ -575,11 +605,11 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         QInfo qi;
         qi.qn = qn;
         qi.eps_a = (float)(sqrt(dq2) * 1.0001);
-        qi.eps_b = m.scorer == KGE_DISTMULT ? (float)(d * 1.1920929e-07 * sqrt(qn) * 1.0001)    // d 2^-23 |q~|
+        qi.eps_b = mult ? (float)(d * 1.1920929e-07 * sqrt(qn) * 1.0001)                       // d 2^-23 |q~|
                                             : (float)((d + 2) * 2.3841858e-07);                  // (d+2) 2^-22: d products and the -|t|^2 start value
         qi.pad = 0.f;
         qinfo[q] = qi;
-        vt[q] = true_t ? (m.scorer == KGE_DISTMULT ? vtl : 2.f * vtl - tnl) : INFINITY;
+        vt[q] = true_t ? (mult ? vtl : 2.f * vtl - tnl) : INFINITY;
         thr[q] = -INFINITY; cnt[q] = 0; flag[q] = 0; rankcnt[q] = 0;
     }
 }
@@ -719,12 +749,12 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
     TopkWs w;
     topk_carve(p, ws, w);
     KgeModelDev md;
-    md.scorer = model.scorer; md.bf16 = p.bf16; md.dim = model.dim; md.rel_dim = model.rel_dim;
+    md.scorer = model.scorer; md.bf16 = p.bf16; md.dim = model.dim; md.rel_dim = model.rel_dim; md.p1 = 0;
     md.ent = model.ent; md.rel = model.rel; md.relw = model.relw;
     md.ent_ld = model.ent_ld; md.rel_ld = model.rel_ld; md.relw_ld = model.relw_ld;
     const char *cand0 = (const char *)model.ent + lo * model.ent_ld * p.es;
     const int64_t stride = model.ent_ld * p.es;
-    const int kind = model.scorer == KGE_DISTMULT ? KGE_KIND_MULT : KGE_KIND_DIST;
+    const int kind = (model.scorer == KGE_DISTMULT || model.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
 
     hipLaunchKernelGGL(topk_zero_kernel, dim3(1), dim3(64), 0, st, w.tmax, w.zeros);
     if (p.bf16) {

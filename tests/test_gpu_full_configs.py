@@ -136,7 +136,7 @@ def test_c3_shapes_transe_one_norm_full_size(orc):
     _free()
 
 
-@pytest.mark.parametrize("scorer", ["distmult", "transe"])
+@pytest.mark.parametrize("scorer", ["distmult", "transe", "complex", "rotate"])
 def test_c4_link_prediction_full_size(orc, scorer):
     """8192 queries against all 10M entities; the oracle ranks a 16-query subset at full width."""
     import paper_2211_12281_amd as kge
@@ -164,7 +164,13 @@ def test_c4_link_prediction_full_size(orc, scorer):
     sub = np.r_[0:4, np.arange(100, 8192, 700)][:16]
     host = ent.float().cpu().numpy()
     ridx, rsc, rrank = orc.topk(scorer, host, rel, None, h[sub], r[sub], 0, n_ent, K, tt[sub])
-    assert np.array_equal(idx[sub], ridx)
+    if scorer == "rotate":
+        # cos / sin in fp64 differ in the last bit between math libraries: candidates whose keys agree to 1e-12 may swap
+        for (i, k) in np.argwhere(idx[sub] != ridx):
+            mine = orc.score_one(scorer, host[h[sub[i]]], rel[r[sub[i]]], None, host[idx[sub[i], k]])
+            assert abs(mine - rsc[i, k]) <= 1e-12 * abs(rsc[i, k])
+    else:
+        assert np.array_equal(idx[sub], ridx)
     assert np.max(np.abs(sc[sub] - rsc)) <= RTOL_F32 * np.max(np.abs(rsc))
     inside = rrank <= K
     assert np.array_equal(rank[sub][inside], rrank[inside])
