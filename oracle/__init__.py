@@ -276,3 +276,14 @@ def encode_bwd(ent_s, feat, m_h, m_t, idx, B, N, de, p=0.0, seed=0, step=0, tag=
                          C.c_double(reg_f), _p(de, C.c_double), _p(g_s, C.c_double), _p(g_mh, C.c_double),
                          _p(g_mt, C.c_double))
     return g_s, g_mh, g_mt
+
+
+def ensemble(lists, p, K_out=10):
+    """Power-rank ensemble of M top-K lists per query: lists int32 [M, Q, K] -> (idx [Q, K_out], score [Q, K_out])."""
+    lists = np.ascontiguousarray(lists, dtype=np.int32)
+    M, Q, K = lists.shape
+    out_idx = np.zeros((Q, K_out), dtype=np.int32)
+    out_score = np.zeros((Q, K_out), dtype=np.float64)
+    lib().orc_ensemble(_p(lists, C.c_int32), C.c_int(M), C.c_int64(Q), C.c_int(K), C.c_double(p), C.c_int(K_out),
+                       _p(out_idx, C.c_int32), _p(out_score, C.c_double))
+    return out_idx, out_score

@@ -877,3 +877,61 @@ void orc_encode_bwd(int d, int fd, const float *ent_s, const float *feat, const 
     }
     free(proj); free(e); free(dep); free(dpr); free(sd);
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Power-rank ensemble (Section 3.2 "Inference", paragraph "Ensemble", eq. (ensemble))          */
+/* ------------------------------------------------------------------------------------------ */
+
+/*
+ * lists[(m * Q + q) * K + k-1] is the k-th best tail of model m for query q (distinct entities; -1 pads a
+ * short list).  Every entity t gets s(t) = sum over the models, in model order, of
+ *     -sgn(p) k^p          if t is the k-th entry of the model's list (its first occurrence counts),
+ *     -[p > 0] (K + 1)^p   if the model's list does not hold t,
+ * and the K_out entities with the largest s(t), ties to the smaller entity id, are returned.  An entity in no
+ * list has the smallest possible score, so only entities that occur in some list are candidates; if
+ * fewer than K_out occur the output is padded with -1 / -inf.
+ */
+void orc_ensemble(const int32_t *lists, int M, int64_t Q, int K, double p, int K_out, int32_t *out_idx,
+                  double *out_score)
+{
+    const double absent = p > 0.0 ? -pow((double)(K + 1), p) : 0.0;
+    const double sg = p > 0.0 ? -1.0 : 1.0;
+    for (int64_t q = 0; q < Q; ++q) {
+        int32_t *cand = (int32_t *)malloc(sizeof(int32_t) * (size_t)(M * K > 0 ? M * K : 1));
+        double *sc = (double *)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
+        int nc = 0;
+        /* candidates: every entity of every list, once */
+        for (int m = 0; m < M; ++m)
+            for (int k = 0; k < K; ++k) {
+                int32_t t = lists[((int64_t)m * Q + q) * K + k];
+                if (t < 0) continue;
+                int seen = 0;
+                for (int i = 0; i < nc && !seen; ++i) seen = cand[i] == t;
+                if (!seen) cand[nc++] = t;
+            }
+        for (int i = 0; i < nc; ++i) {
+            double s = 0.0;
+            for (int m = 0; m < M; ++m) {
+                const int32_t *lm = lists + ((int64_t)m * Q + q) * K;
+                int rank = 0;
+                for (int k = 0; k < K && !rank; ++k)
+                    if (lm[k] == cand[i]) rank = k + 1;
+                s += rank ? sg * pow((double)rank, p) : absent;
+            }
+            sc[i] = s;
+        }
+        /* selection of the K_out best, one at a time */
+        for (int o = 0; o < K_out; ++o) {
+            int best = -1;
+            for (int i = 0; i < nc; ++i) {
+                if (cand[i] < 0) continue;
+                if (best < 0 || sc[i] > sc[best] || (sc[i] == sc[best] && cand[i] < cand[best])) best = i;
+            }
+            if (best < 0) { out_idx[q * K_out + o] = -1; out_score[q * K_out + o] = -INFINITY; continue; }
+            out_idx[q * K_out + o] = cand[best];
+            out_score[q * K_out + o] = sc[best];
+            cand[best] = -1;
+        }
+        free(cand); free(sc);
+    }
+}
