@@ -177,6 +177,23 @@ int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64
              const int32_t *true_t, int64_t *out_rank, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Power-rank ensemble (Section 3.2 "Inference", paragraph "Ensemble", eq. (ensemble)): combines the top-K lists
+ * of M models.  lists int32[M*Q*K] (device), lists[(m*Q + q)*K + k-1] = the k-th best tail of model m for query
+ * q, e.g. M outputs of kge_topk; entries < 0 pad a short list; an entity that a list holds twice counts at its
+ * first position.  With power p != 0 every entity t scores
+ *     s(t) = sum over m (in model order, fp64) of  -sgn(p) k^p           if t is the k-th entry of list m,
+ *                                                   -[p > 0] (K + 1)^p    if list m does not hold t,
+ * (p = -1: reciprocal-rank fusion; p = 1: minus the sum of the ranks) and the K_out entities with the largest
+ * s(t), ties to the smaller id, go to out_idx int32[Q*K_out] / out_score float[Q*K_out] (padded with -1 / -inf
+ * when fewer entities are listed).  Only listed entities compete: an unlisted one has the smallest possible
+ * score.  The K + 1 possible terms are evaluated with the host's pow().
+ * Limits: M <= 128, K <= 256, M*K <= 8192 (KGE_E_UNSUPPORTED beyond), 1 <= K_out <= 256, 0 < |p| <= 64.
+ * Needs no workspace.
+ */
+int kge_ensemble(const int32_t *lists, int32_t M, int64_t Q, int32_t K, double p, int32_t K_out,
+                 int32_t *out_idx, float *out_score, void *hip_stream);
+
+/*
  * Partition bucketing (Section 4, "Partitioning"): entity e belongs to shard e / part_size
  * (part_size = ceil(|E|/D), ids assumed already randomly permuted); triple i falls in bucket
  * (h_i / part_size) * D + (t_i / part_size).  Outputs a stable counting sort by bucket:

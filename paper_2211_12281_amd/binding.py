@@ -18,7 +18,7 @@ LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
 OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION, OP_SAMPLER_BUILD, OP_ENCODE, OP_ENCODE_BWD = range(8)
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
            "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
-           "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes",
+           "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7}
@@ -88,6 +88,8 @@ def load():
                                                            C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kge_topk.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_int64, C.c_int64, C.c_int32] + [C.c_void_p] * 5 + \
             [C.c_size_t, C.c_void_p]
+        lib.kge_ensemble.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_double, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_void_p]
         lib.kge_partition_triples.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kge_sampler_build.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_int64, C.c_int32, C.c_int64] + \
@@ -240,6 +242,17 @@ def topk(model: Model, h, r, cand_lo: int, cand_hi: int, K: int, true_t=None, ws
     _check(load().kge_topk(model.ref, _ptr(_i32(h)), _ptr(_i32(r)), Q, cand_lo, cand_hi, K, _ptr(out_idx),
                            _ptr(out_score), _ptr(true_t), _ptr(rank), _ptr(buf), buf.numel(), _stream()), "kge_topk")
     return out_idx, out_score, rank
+
+
+def ensemble(lists, p: float, K_out: int = 10):
+    """Power-rank ensemble of M top-K lists: lists int32 [M, Q, K] -> (idx int32 [Q, K_out], score fp32 [Q, K_out])."""
+    assert lists.dtype == torch.int32 and lists.dim() == 3 and lists.is_contiguous()
+    M, Q, K = lists.shape
+    out_idx = torch.empty((Q, K_out), dtype=torch.int32, device="cuda")
+    out_score = torch.empty((Q, K_out), dtype=torch.float32, device="cuda")
+    _check(load().kge_ensemble(_ptr(lists), M, Q, K, float(p), K_out, _ptr(out_idx), _ptr(out_score), _stream()),
+           "kge_ensemble")
+    return out_idx, out_score
 
 
 def profile_enable(on: bool):

@@ -30,6 +30,9 @@ int kge_run_sample_triples(uint64_t seed, uint64_t step, uint32_t tag, int64_t b
 int kge_run_negatives_sharded(uint64_t seed, uint64_t step, uint32_t tag, int64_t part_size, int64_t n_ent, int64_t per_shard,
                               int64_t n, int32_t *out, hipStream_t st);
 
+int kge_run_ensemble(const int32_t *lists, int M, int64_t Q, int K, double p, int K_out, int32_t *out_idx, float *out_score,
+                     hipStream_t st);
+
 namespace {
 
 struct Geometry {
@@ -432,6 +435,15 @@ int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64
     if (kge_topk_ws(*model, Q, cand_hi - cand_lo, K) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     return kge_run_topk(*model, h, r, Q, cand_lo, cand_hi, K, out_idx, out_score, true_t, out_rank, ws, ws_bytes,
                         (hipStream_t)hip_stream);
+}
+
+int kge_ensemble(const int32_t *lists, int32_t M, int64_t Q, int32_t K, double p, int32_t K_out, int32_t *out_idx,
+                 float *out_score, void *hip_stream) {
+    if (M < 1 || K < 1 || Q < 0 || Q >= (1ll << 31) || K_out < 1 || K_out > 256 || !(p != 0.0) || !(p == p) || !(fabs(p) <= 64.0))
+        return KGE_E_INVALID_ARG;
+    if (Q == 0) return KGE_OK;
+    if (!lists || !out_idx || !out_score) return KGE_E_INVALID_ARG;
+    return kge_run_ensemble(lists, M, Q, K, p, K_out, out_idx, out_score, (hipStream_t)hip_stream);
 }
 
 int kge_partition_triples(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int32_t D,
