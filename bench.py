@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--p-norm", type=int, default=2, choices=[1, 2],
                     help="training workloads with --scorer transe or rotate: the norm of the distance (Table 2); 1 runs the "
                          "vector-pipe kernels of the 1-norm variants")
+    ap.add_argument("--ensemble", type=int, default=0, metavar="MODELS",
+                    help="c4: also time the power-rank ensemble of this many synthetic top-K lists per query (reported "
+                         "beside the ranking numbers, outside the timed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy first (reference for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -321,7 +324,7 @@ class ScoreWorkload:
 class RankWorkload:
     """c4: full-entity ranking, top-K and rank of a held-out tail."""
 
-    def __init__(self, P, scale, only=None):
+    def __init__(self, P, scale, only=None, ens_models=0):
         import torch
         import kge_synth as ks
         import kge_synth.device as ksd
@@ -329,6 +332,7 @@ class RankWorkload:
         self.kge, self.torch, self.ks, self.P = kge, torch, ks, P
         self.n_ent = max(1000, int(P["n_ent"] * scale))
         self.d, self.Q, self.K = P["dim"], P["Q"], P["K"]
+        self.ens_models = ens_models
         self.scorers = [only] if only else P["scorers"]
         self.bf16 = P["dtype"] == "bf16"
         dt = torch.bfloat16 if self.bf16 else torch.float32
@@ -353,7 +357,28 @@ class RankWorkload:
         return len(self.scorers) * self.Q * self.n_ent
 
     def extra(self, ms):
-        return {"scorers": self.scorers, "queries_per_s": len(self.scorers) * self.Q / (ms * 1e-3)}
+        out = {"scorers": self.scorers, "queries_per_s": len(self.scorers) * self.Q / (ms * 1e-3)}
+        if self.ens_models > 0:
+            out["ensemble"] = self.time_ensemble()
+        return out
+
+    def time_ensemble(self):
+        """Power-rank ensemble (p = -1) of ens_models lists of K tails per query: every model ranks the same pool of
+        2.6 K candidates of the query in its own random order (overlapping lists, as trained models give)."""
+        torch = self.torch
+        g = torch.Generator(device="cuda"); g.manual_seed(self.ks.BASE_SEED)
+        pool = torch.randint(0, self.n_ent, (self.Q, int(2.6 * self.K)), device="cuda", generator=g, dtype=torch.int32)
+        lists = torch.stack([torch.gather(pool, 1, torch.rand(pool.shape, device="cuda", generator=g).argsort(1)[:, :self.K])
+                             for _ in range(self.ens_models)]).contiguous()
+        self.kge.ensemble(lists, -1.0, 10)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            self.kge.ensemble(lists, -1.0, 10)
+        b.record(); torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 100.0
+        return {"models": self.ens_models, "K": self.K, "K_out": 10, "p": -1.0, "us_per_call": us,
+                "queries_per_s": self.Q / (us * 1e-6)}
 
     def mfma_flops(self, slot):
         return 2.0 * self.Q * self.n_ent * self.d       # summed over the chunk launches of one call
@@ -390,7 +415,7 @@ def main():
     elif a.workload == "c2":
         wl = ScoreWorkload(P, a.scale, a.scorer)
     else:
-        wl = RankWorkload(P, a.scale, a.scorer)
+        wl = RankWorkload(P, a.scale, a.scorer, a.ensemble)
 
     if a.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
