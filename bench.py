@@ -135,6 +135,11 @@ class TrainWorkload:
             self.loss_kw = dict(n_ent_for_c=self.n_ent)
         if reg_l3 > 0.0:
             self.loss_kw["reg_l3"] = reg_l3
+        self.side = torch.cuda.Stream()
+        self.ev_ids, self.ev_plan, self.ev_grad, self.ev_rel = (torch.cuda.Event() for _ in range(4))
+        self.ev_rel.record()
+        self.ws_ent, self.ws_rel, self.ws_relw = kge.Workspace(), kge.Workspace(), kge.Workspace()
+        self.idx_all = torch.empty(2 * self.B + self.N, dtype=torch.int32, device=dev)
         self.enc = None
         if feat_dim > 0:
             # text features stand-ins: fixed U(-0.5, 0.5) rows; projections start at U(-0.05, 0.05)
@@ -197,9 +202,35 @@ class TrainWorkload:
             for q, gm in zip(self.mproj, (g_mh, g_mt)):
                 kge.sparse_adam(q["p"], q["sh"], q["m"], q["v"], self.rows_d, gm, lr, step=i + 1)
         else:
+            # The row ids of the step are known as soon as the negatives are drawn: the sorts that the sparse updates
+            # need run on a second stream beside the forward / backward kernels (kge_sparse_adam_plan), the updates
+            # themselves follow the gradients on the main stream (kge_sparse_adam_apply).
+            torch = self.torch
+            main = torch.cuda.current_stream()
+            self.ev_ids.record(main)
+            with torch.cuda.stream(self.side):
+                self.side.wait_event(self.ev_ids)
+                B = self.B
+                self.idx_all[:B].copy_(h); self.idx_all[B:2 * B].copy_(t); self.idx_all[2 * B:].copy_(self.neg)
+                kge.sparse_adam_plan(self.n_ent, self.d, self.idx_all, self.ws_ent)
+                kge.sparse_adam_plan(self.n_rel, self.rel.shape[1], r, self.ws_rel)
+                if self.relw is not None:
+                    kge.sparse_adam_plan(self.n_rel, self.d, r, self.ws_relw)
+                self.ev_plan.record(self.side)
+            main.wait_event(self.ev_rel)                  # the relation tables of the previous step are in place
             kge.loss_bwd(self.model, self.P["loss"], h, r, t, self.neg, out=self.out, **self.loss_kw)
-            kge.sparse_adam(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent_idx"], self.out["g_ent"], lr,
-                            step=i + 1)
+            self.ev_grad.record(main)
+            main.wait_event(self.ev_plan)
+            kge.sparse_adam_apply(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent, lr, step=i + 1)
+            with torch.cuda.stream(self.side):            # the small relation tables are updated beside the entity table
+                self.side.wait_event(self.ev_grad)
+                kge.sparse_adam_apply(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel, lr,
+                                      step=i + 1)
+                if self.relw is not None:
+                    kge.sparse_adam_apply(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"],
+                                          self.ws_relw, lr, step=i + 1)
+                self.ev_rel.record(self.side)
+            return
         kge.sparse_adam(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel_idx"], self.out["g_rel"], lr,
                         step=i + 1)
         if self.relw is not None:

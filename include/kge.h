@@ -152,6 +152,22 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
                     const kge_adam_cfg_t *cfg, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The same update in two calls, so that the part that needs only the row ids can run while the gradients are
+ * still being computed (the ids of a step - h, t and the negatives - are known before the forward pass;
+ * Section 4 overlaps communication and compute in the same spirit): kge_sparse_adam_plan sorts (idx, position)
+ * into the workspace; kge_sparse_adam_apply reduces the gradient rows of equal ids and takes the Adam step,
+ * reading the plan from the SAME workspace (same M, n_rows and dim; nothing else may use that workspace in
+ * between; the caller orders the two calls, e.g. with an event when they run on different streams).
+ * kge_sparse_adam(...) == plan(...) followed by apply(...), bit for bit.  Workspace size:
+ * kge_workspace_bytes(KGE_OP_SPARSE_ADAM, NULL, M, dim, 0).
+ */
+int kge_sparse_adam_plan(int64_t n_rows, int32_t dim, const int32_t *idx, int64_t M, void *ws, size_t ws_bytes,
+                         void *hip_stream);
+int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
+                          int64_t ld, const float *grads, int64_t M, const kge_adam_cfg_t *cfg, void *ws,
+                          size_t ws_bytes, void *hip_stream);
+
+/*
  * Link prediction (Section 3.2, "Inference"): for each query (h_q, r_q), q < Q, rank all
  * candidate tails t in [cand_lo, cand_hi) and return the K best by (score descending, index
  * ascending):  out_idx int32[Q*K], out_score float[Q*K].  If K exceeds the number of candidates

@@ -18,7 +18,8 @@ LOSSES = {"logsigmoid": 0, "sampled_softmax": 1}
 OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION, OP_SAMPLER_BUILD, OP_ENCODE, OP_ENCODE_BWD = range(8)
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
            "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
-           "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble",
+           "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble", "kge_sparse_adam_plan",
+           "kge_sparse_adam_apply",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7}
@@ -86,6 +87,9 @@ def load():
             [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
         lib.kge_sparse_adam.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                                            C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kge_sparse_adam_plan.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kge_sparse_adam_apply.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_int64,
+                                                                 C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kge_topk.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_int64, C.c_int64, C.c_int32] + [C.c_void_p] * 5 + \
             [C.c_size_t, C.c_void_p]
         lib.kge_ensemble.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_double, C.c_int32, C.c_void_p,
@@ -230,6 +234,29 @@ def sparse_adam(param, shadow, m, v, idx, grads, lr: float, beta1: float = 0.9, 
     _check(load().kge_sparse_adam(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
                                   _ptr(_i32(idx)), _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream()),
            "kge_sparse_adam")
+
+
+def sparse_adam_plan(n_rows: int, dim: int, idx, ws: Workspace):
+    """Sorts the row ids of a later sparse_adam_apply into `ws` (which must be kept for that call alone)."""
+    M = idx.numel()
+    buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, dim))
+    _check(load().kge_sparse_adam_plan(n_rows, dim, _ptr(_i32(idx)), M, _ptr(buf), buf.numel(), _stream()),
+           "kge_sparse_adam_plan")
+
+
+def sparse_adam_apply(param, shadow, m, v, grads, ws: Workspace, lr: float, beta1: float = 0.9, beta2: float = 0.999,
+                      eps: float = 1e-8, step: int = 1):
+    assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
+    assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
+    assert m.stride() == param.stride() and v.stride() == param.stride()
+    if shadow is not None:
+        assert shadow.dtype == torch.bfloat16 and shadow.stride() == param.stride()
+    M, d = grads.shape[0], param.shape[1]
+    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step)
+    buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, d))
+    _check(load().kge_sparse_adam_apply(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
+                                        _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream()),
+           "kge_sparse_adam_apply")
 
 
 def topk(model: Model, h, r, cand_lo: int, cand_hi: int, K: int, true_t=None, ws: Workspace | None = None):

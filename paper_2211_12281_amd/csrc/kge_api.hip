@@ -6,6 +6,9 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
                         const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
                         size_t ws_bytes, hipStream_t st);
 size_t kge_sparse_adam_ws(int64_t M, int dim);
+int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void *ws, hipStream_t st);
+int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
+                              const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st);
 int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, int64_t Q, int64_t lo, int64_t hi,
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
@@ -416,6 +419,35 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
     if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     return kge_run_sparse_adam(param_f32, param_bf16, m, v, n_rows, dim, ld, idx, grads, M, *cfg, ws, ws_bytes,
                                (hipStream_t)hip_stream);
+}
+
+int kge_sparse_adam_plan(int64_t n_rows, int32_t dim, const int32_t *idx, int64_t M, void *ws, size_t ws_bytes,
+                         void *hip_stream) {
+    if (M < 0 || n_rows <= 0 || n_rows >= (1ll << 31) || dim <= 0 || dim % 4 != 0 || dim > 4096) return KGE_E_INVALID_ARG;
+    if (M == 0) return KGE_OK;
+    if (M >= (1ll << 31) || !idx) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_sparse_adam_plan(n_rows, idx, M, ws, (hipStream_t)hip_stream);
+}
+
+int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
+                          int64_t ld, const float *grads, int64_t M, const kge_adam_cfg_t *cfg, void *ws,
+                          size_t ws_bytes, void *hip_stream) {
+    if (!cfg || M < 0 || n_rows <= 0 || n_rows >= (1ll << 31) || dim <= 0 || dim % 4 != 0 || dim > 4096 || ld < dim ||
+        ld % 4 != 0)
+        return KGE_E_INVALID_ARG;
+    if (cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f))
+        return KGE_E_INVALID_ARG;
+    if (M == 0) return KGE_OK;
+    if (M >= (1ll << 31)) return KGE_E_INVALID_ARG;
+    if (!param_f32 || !m || !v || !grads) return KGE_E_INVALID_ARG;
+    if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
+    ws = align_ws(ws, ws_bytes);
+    if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_sparse_adam_apply(param_f32, param_bf16, m, v, n_rows, dim, ld, grads, M, *cfg, ws,
+                                     (hipStream_t)hip_stream);
 }
 
 int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64_t Q, int64_t cand_lo,

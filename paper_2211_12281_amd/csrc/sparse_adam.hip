@@ -346,17 +346,26 @@ int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64
     return kge_launch_status();
 }
 
-int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
-                        const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
-                        size_t ws_bytes, hipStream_t st) {
-    (void)ws_bytes;
+// where kge_sort_pairs leaves its result for M pairs with keys below key_range (the passes ping-pong between two buffers)
+static void sort_result(int64_t M, int64_t key_range, void *ws, const uint32_t **sk, const uint32_t **sp) {
+    SortWs s;
+    sort_carve(M, 0, ws, s);
+    int bits = 1;
+    while (bits < 32 && (1ll << bits) < key_range) ++bits;
+    const int passes = (bits + 7) / 8;
+    *sk = (passes & 1) ? s.kb : s.ka; *sp = (passes & 1) ? s.pb : s.pa;
+}
+
+int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void *ws, hipStream_t st) {
     const uint32_t *sk, *sp;
-    int rc;
-    {
-        KgeProfScope prof(KGE_PROF_SORT, st);
-        rc = kge_sort_pairs(idx, nullptr, nullptr, 1, 1, M, n_rows, ws, &sk, &sp, st, nullptr, 0);
-    }
-    if (rc != KGE_OK) return rc;
+    KgeProfScope prof(KGE_PROF_SORT, st);
+    return kge_sort_pairs(idx, nullptr, nullptr, 1, 1, M, n_rows, ws, &sk, &sp, st, nullptr, 0);
+}
+
+int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
+                              const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st) {
+    const uint32_t *sk, *sp;
+    sort_result(M, n_rows, ws, &sk, &sp);
     AdamConst c;
     c.lr = cfg.lr; c.b1 = cfg.beta1; c.b2 = cfg.beta2; c.eps = cfg.eps;
     c.omb1 = 1.f - cfg.beta1; c.omb2 = 1.f - cfg.beta2;
@@ -376,4 +385,13 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
                            (uint16_t *)shadow, m, v, c);
     }
     return kge_launch_status();
+}
+
+int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
+                        const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
+                        size_t ws_bytes, hipStream_t st) {
+    (void)ws_bytes;
+    const int rc = kge_run_sparse_adam_plan(n_rows, idx, M, ws, st);
+    if (rc != KGE_OK) return rc;
+    return kge_run_sparse_adam_apply(param, shadow, m, v, n_rows, dim, ld, grads, M, cfg, ws, st);
 }

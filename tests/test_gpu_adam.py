@@ -120,3 +120,31 @@ def test_result_does_not_depend_on_scheduling(orc):
         kge.sparse_adam(dth, None, dm, dv, torch.from_numpy(idx).cuda(), torch.from_numpy(grads).cuda(), 1e-3, step=5)
         outs.append(dth.cpu().numpy())
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_plan_on_a_side_stream_then_apply_is_bitwise_the_single_call():
+    """kge_sparse_adam_plan (row ids only) on a second stream, kge_sparse_adam_apply on the main one, ordered by an
+    event: the same bits as kge_sparse_adam, also when the planned workspace is reused step after step."""
+    import paper_2211_12281_amd as kge
+    n_rows, d, M = 50000, 64, 7000
+    g = np.random.default_rng(5)
+    side = torch.cuda.Stream()
+    ws = kge.Workspace()
+    ref = [torch.from_numpy(x).cuda() for x in _state(n_rows, d, 3, True)]
+    two = [x.clone() for x in ref]
+    sh_ref = ref[0].to(torch.bfloat16); sh_two = sh_ref.clone()
+    for step in (1, 2, 3):
+        idx = torch.from_numpy(ks.ZipfIds(n_rows, 1.1).draw(g, M)).cuda()
+        grads = torch.from_numpy((g.normal(size=(M, d)) * 1e-2).astype(F)).cuda()
+        kge.sparse_adam(ref[0], sh_ref, ref[1], ref[2], idx, grads, 1e-3, step=step)
+        start, planned = torch.cuda.Event(), torch.cuda.Event()
+        start.record()
+        with torch.cuda.stream(side):
+            side.wait_event(start)                       # the ids exist, the previous apply is done with the workspace
+            kge.sparse_adam_plan(n_rows, d, idx, ws)
+            planned.record()
+        torch.cuda.current_stream().wait_event(planned)
+        kge.sparse_adam_apply(two[0], sh_two, two[1], two[2], grads, ws, 1e-3, step=step)
+    torch.cuda.synchronize()
+    for a, b in zip(ref + [sh_ref], two + [sh_two]):
+        assert bool((a == b).all())
