@@ -1,5 +1,15 @@
 // Dispatch of the block-kernel instantiations.
 #include "kge_internal.h"
+#include <stdlib.h>
+
+int kge_launch_fwd_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
+
+// The two-role row-owner kernel serves bf16 rows of 512 bytes without the TransH operands; the environment variable
+// KGE_FWD_ONE_ROLE=1 selects the one-role kernel instead (for comparisons).
+static bool kge_use_fwd_pp() {
+    static const bool on = [] { const char *e = getenv("KGE_FWD_ONE_ROLE"); return !(e && e[0] == '1'); }();
+    return on;
+}
 
 #define KGE_DECL(name) int kge_launch_block_##name(int, int, bool, int, int, int, const KgeBlockArgs &, int, int, hipStream_t);
 KGE_DECL(f32_score) KGE_DECL(f32_fwd_ls) KGE_DECL(f32_fwd_sm) KGE_DECL(f32_gradt_ls) KGE_DECL(f32_gradt_sm)
@@ -12,6 +22,7 @@ int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int los
                     : kge_launch_block_f32_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st);
     const bool ls = loss == KGE_LOGSIGMOID;
     if (mode == KGE_MODE_FWD) {
+        if (bf16 && rb == 512 && !transh && dsplit == 1 && kge_use_fwd_pp()) return kge_launch_fwd_pp(kind, loss, a, own_tiles, nsplit, st);
         if (bf16) return ls ? kge_launch_block_bf16_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
                             : kge_launch_block_bf16_fwd_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
         return ls ? kge_launch_block_f32_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)

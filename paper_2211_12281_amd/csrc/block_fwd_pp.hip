@@ -1,0 +1,312 @@
+// The row-owner pass of the block kernel (MODE_FWD of block_kernel.hpp: loss statistics of every query row and
+// the unnormalised gradient of the queries in one pass over the shared negatives) as a two-role kernel for the
+// hot configuration: bf16 operands, rows of 512 bytes (d <= 256), bilinear and distance scorers without the TransH
+// operands.
+//
+// In the one-role kernel a wave owns 32 query rows, keeps 64 registers of own fragments AND 128 registers of
+// gradient accumulators, so only one wave fits per SIMD, and its contraction over d, its element-wise epilogue
+// (exponentials, sums, packing) and its contraction over the stream index run one after another.  Here the two
+// contractions belong to two waves that share a SIMD:
+//   wave A (waves 0-3)  tile t:    acc[32 stream x 32 own] = X_t . own^t, epilogue, coefficients -> LDS
+//   wave B (waves 4-7)  tile t-1:  out^t[d x 32 own] += Xt_{t-1}[d x 32 stream] . coef_{t-1}
+// so that the vector work of A runs under the matrix work of B and both hide each other's LDS latency.  The
+// coefficient tile of a pair (2 KB: the accumulator layout of A is the B-operand layout of B, lane for lane)
+// and the rare rescaling factor of the running reference exponent pass through a double-buffered LDS slot; the one
+// workgroup barrier per tile that the staging ring needs anyway orders the hand-over.  The ring holds four
+// tiles: A reads X of tile t, B reads Xt of tile t-1, tile t+1 has landed or is landing, tile t+2 is requested.
+// Geometry (own tiles of 128 rows, splits over the negatives, placement on the dies), operand layouts, epilogue
+// arithmetic and outputs are those of the one-role kernel, which stays the reference for every other
+// configuration.
+#include "block_kernel.hpp"
+
+int kge_launch_fwd_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
+
+namespace {
+
+constexpr int PP_RB = 512, PP_DP = 256, PP_KS = 16, PP_NB = 8, PP_ST = 32;
+constexpr int PP_X_BYTES = PP_ST * PP_RB;                   // 16 KB: [32 rows][512 bytes], chunk c of row r at c ^ (r & 7)
+constexpr int PP_XT_BYTES = PP_DP * PP_ST * 2;              // 16 KB: transposed tile, 64-byte rows, two per 128-byte line
+constexpr int PP_STAGE = PP_X_BYTES + PP_XT_BYTES;
+constexpr int PP_NSTAGE = 4;
+constexpr int PP_SIDE_SLOT = 4 * 256, PP_SIDE_SLOTS = 5;    // squared norms of a tile's 32 negatives, one copy per A wave
+constexpr int PP_XCH = 2048 + 256;                          // coefficients (64 lanes x 32 bytes) + rescaling factors (64 x 4 bytes)
+constexpr int PP_LDS = PP_NSTAGE * PP_STAGE + PP_SIDE_SLOTS * PP_SIDE_SLOT + 4 * 2 * PP_XCH;
+constexpr int PP_LPW_A = 5, PP_LPW_B = 4;                   // asynchronous copies per tile of an A / B wave
+static_assert(PP_LDS <= 160 * 1024, "LDS budget");
+
+template <int KIND, int LOSS>
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
+void kge_fwd_pp_kernel(const KgeBlockArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    char *side_ring = lds + PP_NSTAGE * PP_STAGE;
+    char *xch_base = side_ring + PP_SIDE_SLOTS * PP_SIDE_SLOT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
+    const bool role_b = wave >= 4;
+    const int pair = wave & 3;
+    // placement as in the one-role kernel: workgroups that stream the same negatives share a die
+    const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
+    int own_tile, split;
+    if (a.xcd_per == 1) { own_tile = kk % a.own_tiles; split = xcd + 8 * (kk / a.own_tiles); }
+    else { split = xcd / a.xcd_per; own_tile = kk * a.xcd_per + xcd % a.xcd_per; }
+    if (own_tile >= a.own_tiles || split >= a.nsplit) return;
+    const int oidx = own_tile * 128 + pair * 32 + lr;       // the pair's own row of this lane
+    const int t0 = split * a.tiles_per_split;
+    const int t1 = min(a.str_tiles, t0 + a.tiles_per_split);
+    const bool work = t1 > t0;
+
+    // ---- staging: every wave copies 2 KB of X and 2 KB of Xt per tile -----------------------------------
+    int x_off[2];
+    int64_t xt_off[2];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+        const int byte = (wave * 2 + jj) * 1024 + lane * 16;
+        const int r = byte / PP_RB, pos = (byte % PP_RB) / 16;
+        x_off[jj] = r * PP_RB + ((pos ^ (r & 7)) * 16);
+        const int line = byte >> 7, slot = (byte >> 4) & 7;
+        const int sslot = slot ^ (line & 7), row = 2 * line + (sslot >> 2), c = sslot & 3;
+        xt_off[jj] = (int64_t)row * a.strT_ld * 2 + c * 16;
+    }
+    auto issue = [&](int tile, int slot) {
+        tile = tile < t1 ? tile : t1 - 1;                   // past the end: a harmless repeat keeps vmcnt uniform
+        const uint32_t sbase = lds0 + (slot % PP_NSTAGE) * PP_STAGE;
+        const char *src = (const char *)a.str + (size_t)tile * PP_ST * PP_RB;
+        const char *srct = (const char *)a.strT + (size_t)tile * PP_ST * 2;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+            kge_async_copy16(src + x_off[jj], __builtin_amdgcn_readfirstlane(sbase + (wave * 2 + jj) * 1024));
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+            kge_async_copy16(srct + xt_off[jj], __builtin_amdgcn_readfirstlane(sbase + PP_X_BYTES + (wave * 2 + jj) * 1024));
+        if (!role_b)
+            kge_async_copy4(a.tn + tile * PP_ST + lr,
+                            __builtin_amdgcn_readfirstlane(lds0 + PP_NSTAGE * PP_STAGE + (slot % PP_SIDE_SLOTS) * PP_SIDE_SLOT + pair * 256));
+    };
+
+    if (!role_b) {
+        // =========================== role A: scores, loss weights, coefficients ===========================
+        uint4 own[PP_KS];
+        {
+            const char *p = (const char *)a.own + (size_t)oidx * PP_RB + g * 16;
+#pragma unroll
+            for (int ks = 0; ks < PP_KS; ++ks) own[ks] = *(const uint4 *)(p + ks * 32);
+        }
+        float o_qn = a.rowinfo[oidx].qn;
+        float sum1 = 0.f, st_m = -INFINITY, st_l = 0.f, st_acc = 0.f;
+        int frag_off[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) frag_off[b] = lr * PP_RB + 16 * (((2 * b) ^ (lr & 6)) | (g ^ (lr & 1)));
+        const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
+        if (work) { issue(t0, 0); issue(t0 + 1, 1); }
+        // the own operand must have arrived before the loop (a wait inside it would drain the ring)
+#pragma unroll
+        for (int ks = 0; ks < PP_KS; ++ks) asm volatile("" : "+v"(own[ks].x), "+v"(own[ks].y), "+v"(own[ks].z), "+v"(own[ks].w));
+        asm volatile("" : "+v"(o_qn));
+        if (work) {
+            for (int t = t0; t <= t1; ++t) {
+                kge_wait_vmcnt<PP_LPW_A>();                 // tile t has landed (this wave's part); tile t + 1 may be in flight
+                __syncthreads();
+                issue(t + 2, t - t0 + 2);
+                if (t == t1) break;                         // the last round belongs to the B waves
+                const int slot = t - t0;
+                const char *stage = lds + (slot % PP_NSTAGE) * PP_STAGE;
+                const char *side = side_ring + (slot % PP_SIDE_SLOTS) * PP_SIDE_SLOT + pair * 256;
+                kge_f32x16 acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+                for (int c0 = 0; c0 < PP_KS; c0 += 8) {
+                    uint4 av[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) av[k] = *(const uint4 *)(stage + frag_off[(c0 + k) & 3] + 128 * ((c0 + k) >> 2));
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) acc = kge_mma16<true>(acc, av[k], own[c0 + k]);
+                }
+                const int sbase = t * PP_ST + 4 * g;        // stream index of register i: sbase + 8 (i / 4) + i % 4
+                float sv[16], dv[16];
+                if constexpr (KIND == KGE_KIND_MULT) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) { sv[i] = acc[i]; dv[i] = 0.f; }
+                } else {
+                    // squared distance by the norm expansion; entries where it cancels are redone by direct differences
+                    float d2[16], thr[16];
+                    bool cancel = false;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float tnv = *(const float *)(side + (8 * (i >> 2) + 4 * g + (i & 3)) * 4);
+                        d2[i] = fmaf(-2.f, acc[i], o_qn + tnv);
+                        thr[i] = 1e-3f * (o_qn + tnv);
+                        cancel = cancel || d2[i] < thr[i];
+                    }
+                    if (__any(cancel)) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            if (d2[i] < thr[i]) {
+                                const int n = sbase + 8 * (i >> 2) + (i & 3);
+                                d2[i] = kge_direct_d2<true, false>((const char *)a.own + (size_t)oidx * PP_RB,
+                                                                   (const char *)a.str + (size_t)n * PP_RB, nullptr, PP_DP);
+                            }
+                            asm volatile("" ::: "memory");  // keeps the branch from being turned into selects
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float dd = fmaxf(d2[i], 0.f);
+                        const float inv = dd > 0.f ? __builtin_amdgcn_rsqf(dd) : 0.f;
+                        dv[i] = inv;
+                        sv[i] = -dd * inv;
+                    }
+                }
+                // exponents of the weights relative to the row's reference st_m (log2 domain); padding entries -> -inf
+                float x2[16];
+                const float m_neg = st_m > -INFINITY ? -st_m : 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
+                if (t * PP_ST + PP_ST > a.N) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (sbase + 8 * (i >> 2) + (i & 3) >= a.N) x2[i] = -INFINITY;
+                }
+                float tm = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
+                tm = fmaxf(tm, __shfl_xor(tm, 32));         // both lanes of an own row share the reference
+                // the reference is only raised (and what the row has accumulated rescaled, here and in wave B) when
+                // the tile's maximum exceeds it by more than KGE_TAU
+                float rsc = 1.f;
+                const bool have = st_m > -INFINITY;
+                const bool trip = tm > (have ? KGE_TAU : -INFINITY);
+                if (__any(trip)) {
+                    const float m_new = trip ? (have ? tm + st_m : tm) : st_m;
+                    const float shift = trip ? -tm : 0.f;
+                    rsc = trip ? (have ? kge_exp2(-tm) : 0.f) : 1.f;
+                    st_m = m_new;
+                    st_l *= rsc; st_acc *= rsc; sum1 *= rsc;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) x2[i] += shift;
+                }
+                float coef[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float e = kge_exp2(x2[i]);
+                    st_l += e;
+                    float u = e;
+                    if constexpr (LOSS == KGE_LOGSIGMOID) {
+                        const float y = a.gamma + sv[i];
+                        const float tt = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                        const float rcp = __builtin_amdgcn_rcpf(1.f + tt);
+                        const float sig = y >= 0.f ? rcp : tt * rcp;
+                        const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + tt);
+                        if (e > 0.f) st_acc = fmaf(e, softplus, st_acc);
+                        u = e * sig;
+                    }
+                    const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                    coef[i] = c1;
+                    if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
+                }
+                char *x = xch_base + (pair * 2 + (slot & 1)) * PP_XCH;
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+                    *(uint4 *)(x + s2 * 1024 + lane * 16) =
+                        make_uint4(kge_pack_bf16x2(coef[8 * s2 + 0], coef[8 * s2 + 1]), kge_pack_bf16x2(coef[8 * s2 + 2], coef[8 * s2 + 3]),
+                                   kge_pack_bf16x2(coef[8 * s2 + 4], coef[8 * s2 + 5]), kge_pack_bf16x2(coef[8 * s2 + 6], coef[8 * s2 + 7]));
+                *(float *)(x + 2048 + lane * 4) = rsc;
+            }
+            kge_wait_vmcnt<0>();                            // no copy may be in flight when the LDS is released
+        }
+        st_l += __shfl_xor(st_l, 32); st_acc += __shfl_xor(st_acc, 32); sum1 += __shfl_xor(sum1, 32);
+        if (g == 0) {
+            a.sum_part[(size_t)split * a.own_pad + oidx] = make_float4(sum1, 0.f, 0.f, 0.f);
+            a.stat_part[(size_t)split * a.own_pad + oidx] = make_float4(st_m, st_l, st_acc, 0.f);
+        }
+    } else {
+        // =========================== role B: gradient of the queries =====================================
+        kge_f32x16 acc2[PP_NB];
+#pragma unroll
+        for (int b = 0; b < PP_NB; ++b)
+            for (int i = 0; i < 16; ++i) acc2[b][i] = 0.f;
+        if (work) {
+            issue(t0, 0); issue(t0 + 1, 1);
+            for (int t = t0; t <= t1; ++t) {
+                kge_wait_vmcnt<PP_LPW_B>();
+                __syncthreads();
+                issue(t + 2, t - t0 + 2);
+                if (t == t0) continue;                      // nothing to consume yet
+                const int slot = t - 1 - t0;
+                const char *xt = lds + (slot % PP_NSTAGE) * PP_STAGE + PP_X_BYTES;
+                const char *x = xch_base + (pair * 2 + (slot & 1)) * PP_XCH;
+                uint4 bf[2];
+                bf[0] = *(const uint4 *)(x + lane * 16);
+                bf[1] = *(const uint4 *)(x + 1024 + lane * 16);
+                const float rsc = *(const float *)(x + 2048 + lane * 4);
+                if (__any(rsc != 1.f)) {
+#pragma unroll
+                    for (int b = 0; b < PP_NB; ++b) {
+                        for (int i = 0; i < 16; ++i) acc2[b][i] *= rsc;
+                        asm volatile("" ::: "memory");      // rarely executed: keep it out of the selects
+                    }
+                }
+#pragma unroll
+                for (int c0 = 0; c0 < PP_NB; c0 += 4) {
+                    uint4 av2[4][2];
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) {
+                        const int row = (c0 + bb) * 32 + lr;
+#pragma unroll
+                        for (int f = 0; f < 2; ++f) {
+                            // the transposed tile keeps the 8 stream entries of one lane half contiguous: chunk 2 f + g of row
+                            const int sslot = (((row & 1) << 2) | (2 * f + g)) ^ ((row >> 1) & 7);
+                            av2[bb][f] = *(const uint4 *)(xt + (row >> 1) * 128 + sslot * 16);
+                        }
+                    }
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+                        for (int f = 0; f < 2; ++f) acc2[c0 + bb] = kge_mma16<true>(acc2[c0 + bb], av2[bb][f], bf[f]);
+                }
+            }
+            kge_wait_vmcnt<0>();
+        }
+#pragma unroll
+        for (int blk = 0; blk < PP_NB; ++blk)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int dcol = blk * 32 + 8 * q4 + 4 * g;
+                const size_t o = ((size_t)split * a.own_pad + oidx) * PP_DP + dcol;
+                *(float4 *)(a.acc_part + o) = make_float4(acc2[blk][4 * q4], acc2[blk][4 * q4 + 1], acc2[blk][4 * q4 + 2], acc2[blk][4 * q4 + 3]);
+            }
+    }
+}
+
+template <int KIND, int LOSS>
+int fwd_pp_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
+    auto kern = kge_fwd_pp_kernel<KIND, LOSS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, PP_LDS) != hipSuccess) return KGE_E_HIP;
+        attr_set = true;
+    }
+    if ((int64_t)own_tiles * 128 != a.own_pad || a.dp != PP_DP) return KGE_E_INVALID_ARG;
+    KgeBlockArgs b = a;
+    b.own_tiles = own_tiles; b.nsplit = nsplit;
+    int groups;
+    if (nsplit >= 8) { b.xcd_per = 1; groups = own_tiles * ((nsplit + 7) / 8); }
+    else {
+        int s2 = 1;
+        while (s2 < nsplit) s2 <<= 1;
+        b.xcd_per = 8 / s2;
+        groups = (own_tiles + b.xcd_per - 1) / b.xcd_per;
+    }
+    hipLaunchKernelGGL(kern, dim3(8 * groups), dim3(512), PP_LDS, st, b);
+    return kge_launch_status();
+}
+
+}  // namespace
+
+int kge_launch_fwd_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
+    if (kind == KGE_KIND_MULT) return loss == KGE_LOGSIGMOID ? fwd_pp_launch<KGE_KIND_MULT, 0>(a, own_tiles, nsplit, st)
+                                                             : fwd_pp_launch<KGE_KIND_MULT, 1>(a, own_tiles, nsplit, st);
+    return loss == KGE_LOGSIGMOID ? fwd_pp_launch<KGE_KIND_DIST, 0>(a, own_tiles, nsplit, st)
+                                  : fwd_pp_launch<KGE_KIND_DIST, 1>(a, own_tiles, nsplit, st);
+}

@@ -126,3 +126,17 @@ def test_l3_regulariser_edge_shapes(orc):
         G = make_case("transe", 500, 4, 32, B, N, False, amp=0.3)
         _compare(orc, "transe", "logsigmoid", G, False, 500, kw=dict(gamma=2.0, adv_temp=0.5, reg_l3=0.1),
                  loss_scale=0.5)
+
+
+@pytest.mark.parametrize("scorer,loss", [("distmult", "sampled_softmax"), ("transe", "logsigmoid"), ("complex", "sampled_softmax")])
+def test_wide_score_range_bf16_tables(orc, scorer, loss):
+    """The same stress of the running reference exponent on bf16 tables, whose row-owner pass hands the coefficients
+    and the rescaling factors from one wave to its partner."""
+    amp = 1.2 if scorer != "transe" else 2.5
+    G = make_case(scorer, 3000, 7, 64, 130, 700, True, amp=amp)
+    s0 = orc.score_batch(scorer, G["ent"], G["rel"], G["relw"], G["h"][:1], G["r"][:1], G["t"][:1], G["neg"])[1][0]
+    a_t = 3.0 if scorer == "transe" else 1.0
+    assert (s0.max() - s0.min()) * a_t * 1.4427 > 20.0
+    G["neg"] = G["neg"][np.argsort(s0, kind="stable")]
+    kw = dict(n_ent_for_c=3000) if loss == "sampled_softmax" else dict(gamma=1.0, adv_temp=a_t)
+    _compare(orc, scorer, loss, G, True, 3000, kw=kw)
