@@ -201,7 +201,9 @@ __global__ void kge_loss_reduce_kernel(const float *lossb, int B, float scale, f
 // ---------------------------------------------------------------------------------------------
 // chain rule of the query build + positive triple: one wave per triple
 // ---------------------------------------------------------------------------------------------
-template <bool BF16>
+// (the scorer is a template parameter: with a run-time switch every load of this kernel sat in its own branch
+// and was waited for on its own)
+template <bool BF16, int SC>
 __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t, int B,
                                  int Bp, int dp, const float *acc_part, const float *acc_part2,
                                  const float4 *sum_part, const float4 *stat_part, const KgeRowInfo *rowinfo,
@@ -213,7 +215,7 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     if (b >= B) return;
     const int d = m.dim, c = d >> 1;
     KgeRowCtx<BF16> cx;
-    kge_build_query<BF16>(m, h[b], r[b], lane, cx);
+    kge_build_query<BF16, SC>(m, h[b], r[b], lane, cx);
     const int64_t toff = (int64_t)t[b] * m.ent_ld;
     const float gp = gpos[b];
     // the row pass leaves, per split, sums of UNNORMALISED weights relative to that split's running
@@ -225,45 +227,60 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         const float ms = stat_part[(size_t)s * Bp + b].x;
         return ms > -INFINITY ? exp2f(ms + K2) : 0.f;
     };
+    // The partials of four splits are requested together (the wave would otherwise wait for one row of one split
+    // at a time) and then added in split order: the sums do not depend on the grouping.
     float s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    for (int s = 0; s < (m.p1 ? 0 : nsplit); ++s) {
-        const float kap = kappa(s);
-        const float4 p = sum_part[(size_t)s * Bp + b];
-        s1 += kap * p.x; s2 += kap * p.y; s3 += kap * p.z;
-    }
     float a1[KGE_MAXJ], a2[KGE_MAXJ], tv[KGE_MAXJ], dq[KGE_MAXJ], dtp[KGE_MAXJ];
     float wt = 0.f;
 #pragma unroll
     for (int k = 0; k < KGE_MAXJ; ++k) {
         const int j = lane + 64 * k;
-        a1[k] = a2[k] = tv[k] = 0.f;
-        if (j >= d) continue;
-        for (int s = 0; s < nsplit; ++s) {
-            const float kap = kappa(s);
-            a1[k] += kap * acc_part[((size_t)s * Bp + b) * dp + j];
-            if (m.scorer == KGE_TRANSH) a2[k] += kap * acc_part2[((size_t)s * Bp + b) * dp + j];
-        }
-        tv[k] = El<BF16>::ld(m.ent, toff + j);
+        a1[k] = a2[k] = 0.f;
+        const float tj = El<BF16>::ld(m.ent, toff + (j < d ? j : 0));
+        tv[k] = j < d ? tj : 0.f;
         wt += cx.w[k] * tv[k];
     }
-    const bool mult = m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX;
+    for (int s0 = 0; s0 < nsplit; s0 += 4) {
+        float kap[4], v1[4][KGE_MAXJ], v2[4][KGE_MAXJ];
+        float4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = s0 + u < nsplit ? s0 + u : nsplit - 1;      // past the end: the last split again, weight 0
+            kap[u] = s0 + u < nsplit ? kappa(s) : 0.f;
+            p[u] = m.p1 ? make_float4(0.f, 0.f, 0.f, 0.f) : sum_part[(size_t)s * Bp + b];
+#pragma unroll
+            for (int k = 0; k < KGE_MAXJ; ++k) {
+                v1[u][k] = v2[u][k] = 0.f;
+                if (64 * k >= dp) continue;                // wave-uniform: the partial rows are dp columns long
+                v1[u][k] = acc_part[((size_t)s * Bp + b) * dp + lane + 64 * k];
+                if (SC == KGE_TRANSH) v2[u][k] = acc_part2[((size_t)s * Bp + b) * dp + lane + 64 * k];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            s1 += kap[u] * p[u].x; s2 += kap[u] * p[u].y; s3 += kap[u] * p[u].z;
+#pragma unroll
+            for (int k = 0; k < KGE_MAXJ; ++k) { a1[k] += kap[u] * v1[u][k]; a2[k] += kap[u] * v2[u][k]; }
+        }
+    }
+    const bool mult = SC == KGE_DISTMULT || SC == KGE_COMPLEX;
     float dwh[KGE_MAXJ];
     if (mult) {
 #pragma unroll
         for (int k = 0; k < KGE_MAXJ; ++k) { dq[k] = a1[k] + gp * tv[k]; dtp[k] = gp * cx.q[k]; }
     } else {
-        if (m.scorer == KGE_TRANSH) wt = kge_wave_sum(wt);
+        if (SC == KGE_TRANSH) wt = kge_wave_sum(wt);
         float u[KGE_MAXJ], d2 = 0.f;
 #pragma unroll
         for (int k = 0; k < KGE_MAXJ; ++k) {
-            u[k] = cx.q[k] - tv[k] + (m.scorer == KGE_TRANSH ? wt * cx.w[k] : 0.f);
+            u[k] = cx.q[k] - tv[k] + (SC == KGE_TRANSH ? wt * cx.w[k] : 0.f);
             d2 += u[k] * u[k];
         }
         d2 = kge_wave_sum(d2);
         const float dist = sqrtf(d2);
         const float ap = dist > 0.f ? -gp / dist : 0.f;            // gp * df/du = ap * u
         float aw = 0.f, cq = 0.f;
-        if (m.scorer == KGE_TRANSH) {
+        if (SC == KGE_TRANSH) {
 #pragma unroll
             for (int k = 0; k < KGE_MAXJ; ++k) { aw += ap * u[k] * cx.w[k]; cq += cx.w[k] * cx.q[k]; }
             aw = kge_wave_sum(aw); cq = kge_wave_sum(cq);
@@ -274,7 +291,7 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
             const float apu = m.p1 ? (u[k] > 0.f ? -gp : (u[k] < 0.f ? gp : 0.f)) : ap * u[k];
             dq[k] = a1[k] - s1 * cx.q[k] + apu;
             dtp[k] = -apu;
-            if (m.scorer == KGE_TRANSH) {
+            if (SC == KGE_TRANSH) {
                 dq[k] -= s2 * cx.w[k];
                 dtp[k] = -(apu - aw * cx.w[k]);
                 // gradient with respect to the unit normal: negatives' part + positive's part
@@ -284,7 +301,7 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     }
     // dq -> dh, dr (and dw)
     float wdq = 0.f;
-    if (m.scorer == KGE_TRANSH) {
+    if (SC == KGE_TRANSH) {
 #pragma unroll
         for (int k = 0; k < KGE_MAXJ; ++k) wdq += cx.w[k] * dq[k];
         wdq = kge_wave_sum(wdq);
@@ -299,7 +316,7 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
     const int k_rel = m.rel_dim;
     float *gr = g_rel + (int64_t)b * k_rel;
     // complex scorers need the partner component of dq, held by another lane: exchange through LDS
-    if (m.scorer == KGE_COMPLEX || m.scorer == KGE_ROTATE) {
+    if (SC == KGE_COMPLEX || SC == KGE_ROTATE) {
         __shared__ float xch[4][KGE_MAXJ * 64];
         float *tmp = xch[threadIdx.x >> 6];
 #pragma unroll
@@ -316,7 +333,7 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
             const float dq_re = re ? dq[k] : tmp[jp], dq_im = re ? tmp[jp] : dq[k];
             const float h_re = re ? cx.h[k] : El<BF16>::ld(m.ent, (int64_t)h[b] * m.ent_ld + jp);
             const float h_im = re ? El<BF16>::ld(m.ent, (int64_t)h[b] * m.ent_ld + jp) : cx.h[k];
-            if (m.scorer == KGE_COMPLEX) {
+            if (SC == KGE_COMPLEX) {
                 const float r_re = re ? cx.r[k] : El<BF16>::ld(m.rel, (int64_t)r[b] * m.rel_ld + jp);
                 const float r_im = re ? El<BF16>::ld(m.rel, (int64_t)r[b] * m.rel_ld + jp) : cx.r[k];
                 gh[j] = re ? dq_re * r_re + dq_im * r_im : -dq_re * r_im + dq_im * r_re;
@@ -336,12 +353,9 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         const int j = lane + 64 * k;
         if (j >= d) continue;
         gt[j] = dtp[k];
-        switch (m.scorer) {
-        case KGE_TRANSE: gh[j] = dq[k]; gr[j] = dq[k]; break;
-        case KGE_DISTMULT: gh[j] = dq[k] * cx.r[k]; gr[j] = dq[k] * cx.h[k]; break;
-        case KGE_TRANSH: gh[j] = dq[k] - wdq * cx.w[k]; gr[j] = dq[k]; g_relw[(int64_t)b * d + j] = dwh[k]; break;
-        default: break;
-        }
+        if constexpr (SC == KGE_TRANSE) { gh[j] = dq[k]; gr[j] = dq[k]; }
+        if constexpr (SC == KGE_DISTMULT) { gh[j] = dq[k] * cx.r[k]; gr[j] = dq[k] * cx.h[k]; }
+        if constexpr (SC == KGE_TRANSH) { gh[j] = dq[k] - wdq * cx.w[k]; gr[j] = dq[k]; g_relw[(int64_t)b * d + j] = dwh[k]; }
     }
     if (lane == 0) { g_ent_idx[b] = h[b]; g_ent_idx[B + b] = t[b]; g_rel_idx[b] = r[b]; }
     if (reg > 0.f) {
@@ -480,8 +494,20 @@ int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, cons
                   float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv, hipStream_t st) {
     if (B == 0) return KGE_OK;
     const int grid = (B + 3) / 4;
-    if (m.bf16) hipLaunchKernelGGL(kge_chain_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv);
-    else        hipLaunchKernelGGL(kge_chain_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv);
+#define KGE_CHAIN(BF, SC) hipLaunchKernelGGL((kge_chain_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, \
+                                             acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv)
+#define KGE_CHAIN_SC(BF)                                  \
+    switch (m.scorer) {                                   \
+    case KGE_TRANSE: KGE_CHAIN(BF, KGE_TRANSE); break;    \
+    case KGE_TRANSH: KGE_CHAIN(BF, KGE_TRANSH); break;    \
+    case KGE_ROTATE: KGE_CHAIN(BF, KGE_ROTATE); break;    \
+    case KGE_DISTMULT: KGE_CHAIN(BF, KGE_DISTMULT); break; \
+    case KGE_COMPLEX: KGE_CHAIN(BF, KGE_COMPLEX); break;  \
+    default: return KGE_E_INVALID_ARG;                    \
+    }
+    if (m.bf16) { KGE_CHAIN_SC(true) } else { KGE_CHAIN_SC(false) }
+#undef KGE_CHAIN_SC
+#undef KGE_CHAIN
     return kge_launch_status();
 }
 

@@ -37,50 +37,50 @@ struct KgeRowCtx {
 
 // Builds q for one triple.  For complex scorers lane column j < d/2 pairs with j + d/2, which is a
 // different lane/slot in general, so partner values are fetched from memory again (L1/L2 hits).
-template <bool BF16>
+// SC >= 0 fixes the scorer at compile time (straight-line code: the loads of a row are issued together).
+template <bool BF16, int SC = -1>
 __device__ __forceinline__ void kge_build_query(const KgeModelDev &m, int hi, int ri, int lane,
                                                 KgeRowCtx<BF16> &cx) {
     const int d = m.dim, c = d >> 1;
     const int64_t hoff = (int64_t)hi * m.ent_ld, roff = (int64_t)ri * m.rel_ld, woff = (int64_t)ri * m.relw_ld;
     float wn2 = 0.f, whp = 0.f;
+    // Branch-free: lanes past the row read column 0 instead and are zeroed afterwards, so that all loads of the row
+    // are issued together rather than one branch (and one wait) at a time.
 #pragma unroll
     for (int k = 0; k < KGE_MAXJ; ++k) {
         const int j = lane + 64 * k;
-        cx.h[k] = cx.r[k] = cx.w[k] = cx.q[k] = 0.f;
-        if (j >= d) continue;
-        const float hj = El<BF16>::ld(m.ent, hoff + j);
-        cx.h[k] = hj;
-        switch (m.scorer) {
-        case KGE_TRANSE: { float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj; cx.q[k] = hj + rj; break; }
-        case KGE_DISTMULT: { float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj; cx.q[k] = hj * rj; break; }
+        const bool ok = j < d;
+        const int js = ok ? j : 0;
+        const bool lo = js < c;
+        const int jp = lo ? js + c : js - c;              // partner component of a complex coordinate
+        const float hj = El<BF16>::ld(m.ent, hoff + js);
+        float rj = 0.f, wj = 0.f, qj = 0.f;
+        switch (SC >= 0 ? SC : m.scorer) {
+        case KGE_TRANSE: rj = El<BF16>::ld(m.rel, roff + js); qj = hj + rj; break;
+        case KGE_DISTMULT: rj = El<BF16>::ld(m.rel, roff + js); qj = hj * rj; break;
         case KGE_COMPLEX: {
-            float rj = El<BF16>::ld(m.rel, roff + j); cx.r[k] = rj;
-            if (j < c) {
-                float him = El<BF16>::ld(m.ent, hoff + j + c), rim = El<BF16>::ld(m.rel, roff + j + c);
-                cx.q[k] = hj * rj - him * rim;                         // q_re = h_re r_re - h_im r_im
-            } else {
-                float hre = El<BF16>::ld(m.ent, hoff + j - c), rre = El<BF16>::ld(m.rel, roff + j - c);
-                cx.q[k] = hre * rj + hj * rre;                         // q_im = h_re r_im + h_im r_re
-            }
+            rj = El<BF16>::ld(m.rel, roff + js);
+            const float hp = El<BF16>::ld(m.ent, hoff + jp), rp = El<BF16>::ld(m.rel, roff + jp);
+            // q_re = h_re r_re - h_im r_im,  q_im = h_re r_im + h_im r_re
+            qj = lo ? hj * rj - hp * rp : hp * rj + hj * rp;
             break;
         }
         case KGE_ROTATE: {
-            const int jj = j < c ? j : j - c;
-            float ph = El<BF16>::ld(m.rel, roff + jj); cx.r[k] = ph;
-            float sn, cs; sincosf(ph, &sn, &cs);
-            if (j < c) { float him = El<BF16>::ld(m.ent, hoff + j + c); cx.q[k] = hj * cs - him * sn; }
-            else       { float hre = El<BF16>::ld(m.ent, hoff + j - c); cx.q[k] = hre * sn + hj * cs; }
+            rj = El<BF16>::ld(m.rel, roff + (lo ? js : js - c));
+            const float hp = El<BF16>::ld(m.ent, hoff + jp);
+            float sn, cs; sincosf(rj, &sn, &cs);
+            qj = lo ? hj * cs - hp * sn : hp * sn + hj * cs;
             break;
         }
-        case KGE_TRANSH: {
-            float rj = El<BF16>::ld(m.rel, roff + j), wj = El<BF16>::ld(m.relw, woff + j);
-            cx.r[k] = rj; cx.w[k] = wj; wn2 += wj * wj; whp += wj * hj;
+        case KGE_TRANSH:
+            rj = El<BF16>::ld(m.rel, roff + js); wj = ok ? El<BF16>::ld(m.relw, woff + js) : 0.f;
+            wn2 += wj * wj; whp += ok ? wj * hj : 0.f;
             break;
         }
-        }
+        cx.h[k] = ok ? hj : 0.f; cx.r[k] = ok ? rj : 0.f; cx.w[k] = wj; cx.q[k] = ok ? qj : 0.f;
     }
     cx.wh = 0.f; cx.wnorm = 1.f;
-    if (m.scorer == KGE_TRANSH) {
+    if ((SC >= 0 ? SC : m.scorer) == KGE_TRANSH) {
         wn2 = kge_wave_sum(wn2); whp = kge_wave_sum(whp);
         const float nrm = fmaxf(sqrtf(wn2), 1e-12f), inv = 1.f / nrm;
         cx.wnorm = nrm; cx.wh = whp * inv;
