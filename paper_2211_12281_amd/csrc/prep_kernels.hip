@@ -42,7 +42,7 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 // ---------------------------------------------------------------------------------------------
 // gather + query build + positive score (one wave per triple; rows >= B are written as zeros)
 // ---------------------------------------------------------------------------------------------
-template <bool BF16>
+template <bool BF16, int SC>
 __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t,
                                   int B, int Bp, int dp, void *Q, void *W, void *Q2, float *Q32, KgeRowInfo *rowinfo,
                                   float *pos_ws, float *pos_out) {
@@ -60,7 +60,7 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
         return;
     }
     KgeRowCtx<BF16> cx;
-    kge_build_query<BF16>(m, h[b], r[b], lane, cx);
+    kge_build_query<BF16, SC>(m, h[b], r[b], lane, cx);
     const int d = m.dim;
     const int64_t toff = (int64_t)t[b] * m.ent_ld;
     float qn = 0.f, cq = 0.f, wn = 0.f, s_pos = 0.f, wt = 0.f;
@@ -68,7 +68,8 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
 #pragma unroll
     for (int k = 0; k < KGE_MAXJ; ++k) {
         const int j = lane + 64 * k;
-        tv[k] = j < d ? El<BF16>::ld(m.ent, toff + j) : 0.f;
+        const float tj = El<BF16>::ld(m.ent, toff + (j < d ? j : 0));
+        tv[k] = j < d ? tj : 0.f;
         const float qr = El<BF16>::rnd(cx.q[k]), wr = El<BF16>::rnd(cx.w[k]);
         qn += qr * qr; cq += wr * qr; wn += wr * wr;          // norms of what the matrix cores will see
         wt += cx.w[k] * tv[k];
@@ -79,7 +80,7 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
         }
     }
     qn = kge_wave_sum(qn);
-    if (m.scorer == KGE_TRANSH) { cq = kge_wave_sum(cq); wn = kge_wave_sum(wn); wt = kge_wave_sum(wt); }
+    if (SC == KGE_TRANSH) { cq = kge_wave_sum(cq); wn = kge_wave_sum(wn); wt = kge_wave_sum(wt); }
     if (Q2) {   // TransH: q - c * w_hat, the operand of the negatives' gradient contraction
 #pragma unroll
         for (int k = 0; k < KGE_MAXJ; ++k) {
@@ -90,17 +91,17 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
     // positive score by the direct formula (Table 2), fp32
 #pragma unroll
     for (int k = 0; k < KGE_MAXJ; ++k) {
-        if (m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX) s_pos += cx.q[k] * tv[k];
+        if (SC == KGE_DISTMULT || SC == KGE_COMPLEX) s_pos += cx.q[k] * tv[k];
         else {
             float x = cx.q[k] - tv[k];
-            if (m.scorer == KGE_TRANSH) x += wt * cx.w[k];
+            if (SC == KGE_TRANSH) x += wt * cx.w[k];
             s_pos += m.p1 ? fabsf(x) : x * x;
         }
     }
     s_pos = kge_wave_sum(s_pos);
-    if (!(m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX)) s_pos = m.p1 ? -s_pos : -sqrtf(s_pos);
+    if (!(SC == KGE_DISTMULT || SC == KGE_COMPLEX)) s_pos = m.p1 ? -s_pos : -sqrtf(s_pos);
     if (lane == 0) {
-        rowinfo[b] = KgeRowInfo{qn, cq, 0.f, m.scorer == KGE_TRANSH ? wn : 1.f};
+        rowinfo[b] = KgeRowInfo{qn, cq, 0.f, SC == KGE_TRANSH ? wn : 1.f};
         if (pos_ws) pos_ws[b] = s_pos;
         if (pos_out) pos_out[b] = s_pos;
     }
@@ -457,8 +458,20 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
                    float *pos_out, hipStream_t st) {
     const int grid = (Bp + 3) / 4;
     if (grid == 0) return KGE_OK;
-    if (m.bf16) hipLaunchKernelGGL(kge_qbuild_kernel<true>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, rowinfo, pos_ws, pos_out);
-    else        hipLaunchKernelGGL(kge_qbuild_kernel<false>, dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, rowinfo, pos_ws, pos_out);
+#define KGE_QBUILD(BF, SC) hipLaunchKernelGGL((kge_qbuild_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, \
+                                              rowinfo, pos_ws, pos_out)
+#define KGE_QBUILD_SC(BF)                                  \
+    switch (m.scorer) {                                    \
+    case KGE_TRANSE: KGE_QBUILD(BF, KGE_TRANSE); break;    \
+    case KGE_TRANSH: KGE_QBUILD(BF, KGE_TRANSH); break;    \
+    case KGE_ROTATE: KGE_QBUILD(BF, KGE_ROTATE); break;    \
+    case KGE_DISTMULT: KGE_QBUILD(BF, KGE_DISTMULT); break; \
+    case KGE_COMPLEX: KGE_QBUILD(BF, KGE_COMPLEX); break;  \
+    default: return KGE_E_INVALID_ARG;                     \
+    }
+    if (m.bf16) { KGE_QBUILD_SC(true) } else { KGE_QBUILD_SC(false) }
+#undef KGE_QBUILD_SC
+#undef KGE_QBUILD
     return kge_launch_status();
 }
 
