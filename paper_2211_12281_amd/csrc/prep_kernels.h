@@ -17,6 +17,9 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
                    float *pos_out, hipStream_t st);
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
                     hipStream_t st);
+// gather of the negatives and their transposed copy Tt [dp][Np] in one launch
+int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
+                      hipStream_t st);
 int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipStream_t st);
 int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma,
                       float c_corr, float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb,

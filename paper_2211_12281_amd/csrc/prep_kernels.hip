@@ -126,6 +126,51 @@ __global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int
     if (lane == 0) tn[n] = s;
 }
 
+// gather of the shared negatives AND their transposed copy in one launch: a workgroup takes 32 negatives, every
+// wave 8 of them (all of a lane's loads are issued before the first is used), the rows pass through the LDS
+// and leave again as the 32-entry segments of the dp rows of Tt (bf16: with the column permutation of
+// kge_transpose_kernel).  NJ = dp / 64.
+template <bool BF16, int NJ>
+__global__ __launch_bounds__(256) void kge_tgather_t_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, void *T, void *Tt,
+                                                            float *tn) {
+    using E = typename El<BF16>::T;
+    constexpr int DP = 64 * NJ, PITCH = DP + (BF16 ? 2 : 1);           // odd stride in 4-byte words
+    extern __shared__ __attribute__((aligned(16))) char tg_lds[];
+    E *tile = (E *)tg_lds;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n0 = blockIdx.x * 32;
+    float v[8][NJ];
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+        const int n = n0 + wave * 8 + rr;
+        const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
+#pragma unroll
+        for (int k = 0; k < NJ; ++k) {
+            const int j = lane + 64 * k;
+            const float x = El<BF16>::ld(m.ent, off + (j < m.dim ? j : 0));
+            v[rr][k] = (n < N && j < m.dim) ? x : 0.f;
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+        const int row = wave * 8 + rr, n = n0 + row;
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < NJ; ++k) {
+            const int j = lane + 64 * k;
+            El<BF16>::st(T, (int64_t)n * DP + j, v[rr][k]);
+            tile[row * PITCH + j] = (E)v[rr][k];
+            s += v[rr][k] * v[rr][k];
+        }
+        s = kge_wave_sum(s);
+        if (lane == 0) tn[n] = s;
+    }
+    __syncthreads();
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int px = BF16 ? ((tx & ~12) | ((tx & 4) << 1) | ((tx & 8) >> 1)) : tx;
+    for (int c = ty; c < DP; c += 8) ((E *)Tt)[(int64_t)c * Np + n0 + px] = tile[tx * PITCH + c];
+}
+
 // ---------------------------------------------------------------------------------------------
 // transpose: src [R][C] -> dst [C][R]   (R, C multiples of 32; elements of 2 or 4 bytes).
 // PERM: inside every group of 16 source rows, bits 2 and 3 of the row number are swapped in the
@@ -480,6 +525,19 @@ int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int
     if (grid == 0) return KGE_OK;
     if (m.bf16) hipLaunchKernelGGL(kge_tgather_kernel<true>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn);
     else        hipLaunchKernelGGL(kge_tgather_kernel<false>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn);
+    return kge_launch_status();
+}
+
+int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
+                      hipStream_t st) {
+    if (Np == 0) return KGE_OK;
+    if (Np % 32 || (dp != 128 && dp != 256 && dp != 512)) return KGE_E_INVALID_ARG;
+    const int grid = Np / 32;
+#define KGE_TG(BF, NJ) hipLaunchKernelGGL((kge_tgather_t_kernel<BF, NJ>), dim3(grid), dim3(256), 32 * (64 * NJ + (BF ? 2 : 1)) * (BF ? 2 : 4), st, \
+                                          m, neg, N, Np, T, Tt, tn)
+    if (m.bf16) { if (dp == 128) KGE_TG(true, 2); else if (dp == 256) KGE_TG(true, 4); else KGE_TG(true, 8); }
+    else        { if (dp == 128) KGE_TG(false, 2); else if (dp == 256) KGE_TG(false, 4); else return KGE_E_INVALID_ARG; }   // fp32 rows: 512 or 1,024 bytes
+#undef KGE_TG
     return kge_launch_status();
 }
 
