@@ -15,6 +15,11 @@ static bool kge_use_fwd_pp() {
 KGE_DECL(f32_score) KGE_DECL(f32_fwd_ls) KGE_DECL(f32_fwd_sm) KGE_DECL(f32_gradt_ls) KGE_DECL(f32_gradt_sm)
 KGE_DECL(bf16_score) KGE_DECL(bf16_fwd_ls) KGE_DECL(bf16_fwd_sm) KGE_DECL(bf16_gradt_ls) KGE_DECL(bf16_gradt_sm)
 
+// whether the row-owner pass of this configuration runs the two-role kernel (which needs no transposed negatives)
+bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
+    return bf16 && rb == 512 && !transh && dsplit == 1 && kge_use_fwd_pp();
+}
+
 int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
                      int own_tiles, int nsplit, hipStream_t st) {
     if (mode == KGE_MODE_SCORE)
@@ -22,7 +27,7 @@ int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int los
                     : kge_launch_block_f32_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st);
     const bool ls = loss == KGE_LOGSIGMOID;
     if (mode == KGE_MODE_FWD) {
-        if (bf16 && rb == 512 && !transh && dsplit == 1 && kge_use_fwd_pp()) return kge_launch_fwd_pp(kind, loss, a, own_tiles, nsplit, st);
+        if (kge_fwd_pp_applies(bf16, rb, transh, dsplit)) return kge_launch_fwd_pp(kind, loss, a, own_tiles, nsplit, st);
         if (bf16) return ls ? kge_launch_block_bf16_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
                             : kge_launch_block_bf16_fwd_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
         return ls ? kge_launch_block_f32_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)

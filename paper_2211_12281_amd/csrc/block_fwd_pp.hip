@@ -13,7 +13,16 @@
 // coefficient tile of a pair (2 KB: the accumulator layout of A is the B-operand layout of B, lane for lane)
 // and the rare rescaling factor of the running reference exponent pass through a double-buffered LDS slot; the one
 // workgroup barrier per tile that the staging ring needs anyway orders the hand-over.  The ring holds four
-// tiles: A reads X of tile t, B reads Xt of tile t-1, tile t+1 has landed or is landing, tile t+2 is requested.
+// tiles: A reads tile t, B reads tile t-1, tile t+1 has landed or is landing, tile t+2 is requested.
+//
+// Only the row-major tile X is staged.  Wave B needs it transposed (for a dimension, 8 consecutive stream entries
+// per lane) and gets that from the LDS transpose read of gfx950 (ds_read_b64_tr_b16): inside a group of 16 lanes,
+// source lane i points at 4 consecutive 16-bit elements, and lane l receives element l % 4 of the source lanes
+// l / 4, l / 4 + 4, l / 4 + 8, l / 4 + 12.  With source lane i at row K[i / 4], dimensions 4 (i % 4) .. + 3, lane l
+// receives dimension l of the rows K[0 .. 3]: one read transposes a 4 x 16 patch, two reads give the 8 entries of
+// an MFMA operand.  Wave A loads stream row pi(m) = (m & ~7) | ((m & 3) << 1) | ((m >> 2) & 1) as row m of its
+// contraction: the four rows K[.] of a read are then two apart, fall into four different 32-byte bank groups
+// under the tile's XOR swizzle, and A's own fragment reads stay conflict-free (pi permutes inside groups of 8).
 // Geometry (own tiles of 128 rows, splits over the negatives, placement on the dies), operand layouts, epilogue
 // arithmetic and outputs are those of the one-role kernel, which stays the reference for every other
 // configuration.
@@ -25,13 +34,14 @@ namespace {
 
 constexpr int PP_RB = 512, PP_DP = 256, PP_KS = 16, PP_NB = 8, PP_ST = 32;
 constexpr int PP_X_BYTES = PP_ST * PP_RB;                   // 16 KB: [32 rows][512 bytes], chunk c of row r at c ^ (r & 7)
-constexpr int PP_XT_BYTES = PP_DP * PP_ST * 2;              // 16 KB: transposed tile, 64-byte rows, two per 128-byte line
-constexpr int PP_STAGE = PP_X_BYTES + PP_XT_BYTES;
+constexpr int PP_STAGE = PP_X_BYTES;
 constexpr int PP_NSTAGE = 4;
 constexpr int PP_SIDE_SLOT = 4 * 256, PP_SIDE_SLOTS = 5;    // squared norms of a tile's 32 negatives, one copy per A wave
 constexpr int PP_XCH = 2048 + 256;                          // coefficients (64 lanes x 32 bytes) + rescaling factors (64 x 4 bytes)
 constexpr int PP_LDS = PP_NSTAGE * PP_STAGE + PP_SIDE_SLOTS * PP_SIDE_SLOT + 4 * 2 * PP_XCH;
-constexpr int PP_LPW_A = 5, PP_LPW_B = 4;                   // asynchronous copies per tile of an A / B wave
+constexpr int PP_LPW_A = 3, PP_LPW_B = 2;                   // asynchronous copies per tile of an A / B wave
+__device__ __forceinline__ int pp_pi(int m) { return (m & ~7) | ((m & 3) << 1) | ((m >> 2) & 1); }
+typedef short pp_i16x4 __attribute__((ext_vector_type(4)));
 static_assert(PP_LDS <= 160 * 1024, "LDS budget");
 
 template <int KIND, int LOSS>
@@ -56,29 +66,21 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
     const int t1 = min(a.str_tiles, t0 + a.tiles_per_split);
     const bool work = t1 > t0;
 
-    // ---- staging: every wave copies 2 KB of X and 2 KB of Xt per tile -----------------------------------
+    // ---- staging: every wave copies 2 KB of the tile ------------------------------------------------------
     int x_off[2];
-    int64_t xt_off[2];
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
         const int byte = (wave * 2 + jj) * 1024 + lane * 16;
         const int r = byte / PP_RB, pos = (byte % PP_RB) / 16;
         x_off[jj] = r * PP_RB + ((pos ^ (r & 7)) * 16);
-        const int line = byte >> 7, slot = (byte >> 4) & 7;
-        const int sslot = slot ^ (line & 7), row = 2 * line + (sslot >> 2), c = sslot & 3;
-        xt_off[jj] = (int64_t)row * a.strT_ld * 2 + c * 16;
     }
     auto issue = [&](int tile, int slot) {
         tile = tile < t1 ? tile : t1 - 1;                   // past the end: a harmless repeat keeps vmcnt uniform
         const uint32_t sbase = lds0 + (slot % PP_NSTAGE) * PP_STAGE;
         const char *src = (const char *)a.str + (size_t)tile * PP_ST * PP_RB;
-        const char *srct = (const char *)a.strT + (size_t)tile * PP_ST * 2;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
             kge_async_copy16(src + x_off[jj], __builtin_amdgcn_readfirstlane(sbase + (wave * 2 + jj) * 1024));
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-            kge_async_copy16(srct + xt_off[jj], __builtin_amdgcn_readfirstlane(sbase + PP_X_BYTES + (wave * 2 + jj) * 1024));
         if (!role_b)
             kge_async_copy4(a.tn + tile * PP_ST + lr,
                             __builtin_amdgcn_readfirstlane(lds0 + PP_NSTAGE * PP_STAGE + (slot % PP_SIDE_SLOTS) * PP_SIDE_SLOT + pair * 256));
@@ -96,7 +98,10 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
         float sum1 = 0.f, st_m = -INFINITY, st_l = 0.f, st_acc = 0.f;
         int frag_off[4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) frag_off[b] = lr * PP_RB + 16 * (((2 * b) ^ (lr & 6)) | (g ^ (lr & 1)));
+        for (int b = 0; b < 4; ++b) {
+            const int R = pp_pi(lr);                        // row m of the contraction is stream row pi(m) of the tile
+            frag_off[b] = R * PP_RB + 16 * (((2 * b) ^ (R & 6)) | (g ^ (R & 1)));
+        }
         const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
         if (work) { issue(t0, 0); issue(t0 + 1, 1); }
         // the own operand must have arrived before the loop (a wait inside it would drain the ring)
@@ -123,7 +128,10 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
                     for (int k = 0; k < 8; ++k) acc = kge_mma16<true>(acc, av[k], own[c0 + k]);
                 }
-                const int sbase = t * PP_ST + 4 * g;        // stream index of register i: sbase + 8 (i / 4) + i % 4
+                // register i holds row 8 (i / 4) + 4 g + i % 4 of the contraction = stream row pi(.) of the tile
+                int srow[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) srow[i] = pp_pi(8 * (i >> 2) + 4 * g + (i & 3));
                 float sv[16], dv[16];
                 if constexpr (KIND == KGE_KIND_MULT) {
 #pragma unroll
@@ -134,7 +142,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
                     bool cancel = false;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const float tnv = *(const float *)(side + (8 * (i >> 2) + 4 * g + (i & 3)) * 4);
+                        const float tnv = *(const float *)(side + srow[i] * 4);
                         d2[i] = fmaf(-2.f, acc[i], o_qn + tnv);
                         thr[i] = 1e-3f * (o_qn + tnv);
                         cancel = cancel || d2[i] < thr[i];
@@ -143,7 +151,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
                             if (d2[i] < thr[i]) {
-                                const int n = sbase + 8 * (i >> 2) + (i & 3);
+                                const int n = t * PP_ST + srow[i];
                                 d2[i] = kge_direct_d2<true, false>((const char *)a.own + (size_t)oidx * PP_RB,
                                                                    (const char *)a.str + (size_t)n * PP_RB, nullptr, PP_DP);
                             }
@@ -166,7 +174,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
                 if (t * PP_ST + PP_ST > a.N) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
-                        if (sbase + 8 * (i >> 2) + (i & 3) >= a.N) x2[i] = -INFINITY;
+                        if (t * PP_ST + srow[i] >= a.N) x2[i] = -INFINITY;
                 }
                 float tm = -INFINITY;
 #pragma unroll
@@ -226,6 +234,16 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
         for (int b = 0; b < PP_NB; ++b)
             for (int i = 0; i < 16; ++i) acc2[b][i] = 0.f;
+        // transpose reads: this lane is source i16 of its group of 16 (dimension sub-block q16 of a 32-block, lane half g):
+        // it points at row 16 f + 8 hh + rx of the tile, dimensions blk 32 + q16 16 + 4 (i16 % 4) .. + 3
+        const int i16 = lane & 15, q16 = (lane >> 4) & 1, rx = 2 * (i16 >> 2) + g;
+        int tr_off[2][2], tr_blk[PP_NB];
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) tr_off[f][hh] = (16 * f + 8 * hh + rx) * PP_RB;
+#pragma unroll
+        for (int blk = 0; blk < PP_NB; ++blk) tr_blk[blk] = (((blk * 4 + q16 * 2 + ((i16 & 3) >> 1)) ^ rx) * 16) + (i16 & 1) * 8;
         if (work) {
             issue(t0, 0); issue(t0 + 1, 1);
             for (int t = t0; t <= t1; ++t) {
@@ -234,7 +252,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
                 issue(t + 2, t - t0 + 2);
                 if (t == t0) continue;                      // nothing to consume yet
                 const int slot = t - 1 - t0;
-                const char *xt = lds + (slot % PP_NSTAGE) * PP_STAGE + PP_X_BYTES;
+                const char *xs = lds + (slot % PP_NSTAGE) * PP_STAGE;
                 const char *x = xch_base + (pair * 2 + (slot & 1)) * PP_XCH;
                 uint4 bf[2];
                 bf[0] = *(const uint4 *)(x + lane * 16);
@@ -251,15 +269,18 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
                 for (int c0 = 0; c0 < PP_NB; c0 += 4) {
                     uint4 av2[4][2];
 #pragma unroll
-                    for (int bb = 0; bb < 4; ++bb) {
-                        const int row = (c0 + bb) * 32 + lr;
+                    for (int bb = 0; bb < 4; ++bb)
 #pragma unroll
-                        for (int f = 0; f < 2; ++f) {
-                            // the transposed tile keeps the 8 stream entries of one lane half contiguous: chunk 2 f + g of row
-                            const int sslot = (((row & 1) << 2) | (2 * f + g)) ^ ((row >> 1) & 7);
-                            av2[bb][f] = *(const uint4 *)(xt + (row >> 1) * 128 + sslot * 16);
-                        }
-                    }
+                        for (int f = 0; f < 2; ++f)
+#pragma unroll
+                            for (int hh = 0; hh < 2; ++hh) {
+                                // k-step f, entries 4 hh .. + 3 of this lane half: rows 16 f + 8 hh + 2 kk + g (= pi of the
+                                // contraction rows 16 f + 8 hh + 4 g + kk); this lane is source i = lane % 16 of its group
+                                const pp_i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                    (pp_i16x4 __attribute__((address_space(3))) *)(xs + tr_off[f][hh] + tr_blk[c0 + bb]));
+                                const uint2 u = __builtin_bit_cast(uint2, v);
+                                if (hh == 0) { av2[bb][f].x = u.x; av2[bb][f].y = u.y; } else { av2[bb][f].z = u.x; av2[bb][f].w = u.y; }
+                            }
 #pragma unroll
                     for (int bb = 0; bb < 4; ++bb)
 #pragma unroll

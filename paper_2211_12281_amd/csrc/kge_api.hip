@@ -364,7 +364,10 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         if ((rc = kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, g.Np, st)) != KGE_OK) return rc;
         if ((rc = kge_run_l1_rowstat(b.S, g.Np, g.B, g.N, g.Bp, cfg->loss, cfg->gamma, cfg->adv_temp, b.stat_part, st)) != KGE_OK) return rc;
     } else if (have_block) {
-        if ((rc = kge_run_tgather_t(md, neg, g.N, g.Np, g.dp, b.T, b.Tt, b.tn, st)) != KGE_OK) return rc;
+        // (the two-role row-owner kernel transposes its tiles in the LDS and needs no transposed copy of the negatives)
+        if (kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q)) rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st);
+        else rc = kge_run_tgather_t(md, neg, g.N, g.Np, g.dp, b.T, b.Tt, b.tn, st);
+        if (rc != KGE_OK) return rc;
         if ((rc = kge_run_transpose(g.transh ? b.Q2 : b.Q, b.Qt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
         if (g.transh && (rc = kge_run_transpose(b.W, b.Wt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
         // pass 1 (row owner): loss statistics of every row and the unnormalised gradient of the queries
