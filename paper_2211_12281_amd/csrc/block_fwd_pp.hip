@@ -29,6 +29,7 @@
 #include "block_kernel.hpp"
 
 int kge_launch_fwd_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
+int kge_launch_gradt_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
 
 namespace {
 
@@ -36,21 +37,26 @@ constexpr int PP_RB = 512, PP_DP = 256, PP_KS = 16, PP_NB = 8, PP_ST = 32;
 constexpr int PP_X_BYTES = PP_ST * PP_RB;                   // 16 KB: [32 rows][512 bytes], chunk c of row r at c ^ (r & 7)
 constexpr int PP_STAGE = PP_X_BYTES;
 constexpr int PP_NSTAGE = 4;
-constexpr int PP_SIDE_SLOT = 4 * 256, PP_SIDE_SLOTS = 5;    // squared norms of a tile's 32 negatives, one copy per A wave
+constexpr int PP_SIDE_SLOTS = 5;                            // side information of a tile's 32 stream rows, one copy per A wave
 constexpr int PP_XCH = 2048 + 256;                          // coefficients (64 lanes x 32 bytes) + rescaling factors (64 x 4 bytes)
-constexpr int PP_LDS = PP_NSTAGE * PP_STAGE + PP_SIDE_SLOTS * PP_SIDE_SLOT + 4 * 2 * PP_XCH;
+constexpr int pp_lds(int mode) { return PP_NSTAGE * PP_STAGE + PP_SIDE_SLOTS * 4 * (mode == KGE_MODE_FWD ? 256 : 1024) + 4 * 2 * PP_XCH; }
 constexpr int PP_LPW_A = 3, PP_LPW_B = 2;                   // asynchronous copies per tile of an A / B wave
 __device__ __forceinline__ int pp_pi(int m) { return (m & ~7) | ((m & 3) << 1) | ((m >> 2) & 1); }
 typedef short pp_i16x4 __attribute__((ext_vector_type(4)));
-static_assert(PP_LDS <= 160 * 1024, "LDS budget");
+static_assert(pp_lds(KGE_MODE_GRADT) <= 160 * 1024, "LDS budget");
 
-template <int KIND, int LOSS>
+// MODE_FWD: own = queries, stream = negatives (statistics of the loss + gradient of the queries);
+// MODE_GRADT: own = negatives, stream = queries (gradient of the negatives from the finished row constants).
+template <int MODE, int KIND, int LOSS>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
-void kge_fwd_pp_kernel(const KgeBlockArgs a) {
+void kge_pp_kernel(const KgeBlockArgs a) {
+    constexpr bool FWD = MODE == KGE_MODE_FWD;
+    constexpr int SIDE_WAVE = FWD ? 256 : 1024;             // per A wave: 64 x 4 bytes of squared norms, or 64 x 16 bytes of row info
+    constexpr int SIDE_SLOT = 4 * SIDE_WAVE;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     char *side_ring = lds + PP_NSTAGE * PP_STAGE;
-    char *xch_base = side_ring + PP_SIDE_SLOTS * PP_SIDE_SLOT;
+    char *xch_base = side_ring + PP_SIDE_SLOTS * SIDE_SLOT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
     const bool role_b = wave >= 4;
@@ -62,6 +68,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
     else { split = xcd / a.xcd_per; own_tile = kk * a.xcd_per + xcd % a.xcd_per; }
     if (own_tile >= a.own_tiles || split >= a.nsplit) return;
     const int oidx = own_tile * 128 + pair * 32 + lr;       // the pair's own row of this lane
+    const int str_limit = FWD ? a.N : a.B;                  // valid stream rows
     const int t0 = split * a.tiles_per_split;
     const int t1 = min(a.str_tiles, t0 + a.tiles_per_split);
     const bool work = t1 > t0;
@@ -81,9 +88,11 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
             kge_async_copy16(src + x_off[jj], __builtin_amdgcn_readfirstlane(sbase + (wave * 2 + jj) * 1024));
-        if (!role_b)
-            kge_async_copy4(a.tn + tile * PP_ST + lr,
-                            __builtin_amdgcn_readfirstlane(lds0 + PP_NSTAGE * PP_STAGE + (slot % PP_SIDE_SLOTS) * PP_SIDE_SLOT + pair * 256));
+        if (!role_b) {
+            const uint32_t sside = lds0 + PP_NSTAGE * PP_STAGE + (slot % PP_SIDE_SLOTS) * SIDE_SLOT + pair * SIDE_WAVE;
+            if constexpr (FWD) kge_async_copy4(a.tn + tile * PP_ST + lr, __builtin_amdgcn_readfirstlane(sside));
+            else kge_async_copy16(a.rowinfo + tile * PP_ST + lr, __builtin_amdgcn_readfirstlane(sside));
+        }
     };
 
     if (!role_b) {
@@ -94,7 +103,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
             for (int ks = 0; ks < PP_KS; ++ks) own[ks] = *(const uint4 *)(p + ks * 32);
         }
-        float o_qn = a.rowinfo[oidx].qn;
+        float o_qn = FWD ? a.rowinfo[oidx].qn : a.tn[oidx];   // squared norm of the own row
         float sum1 = 0.f, st_m = -INFINITY, st_l = 0.f, st_acc = 0.f;
         int frag_off[4];
 #pragma unroll
@@ -116,7 +125,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
                 if (t == t1) break;                         // the last round belongs to the B waves
                 const int slot = t - t0;
                 const char *stage = lds + (slot % PP_NSTAGE) * PP_STAGE;
-                const char *side = side_ring + (slot % PP_SIDE_SLOTS) * PP_SIDE_SLOT + pair * 256;
+                const char *side = side_ring + (slot % PP_SIDE_SLOTS) * SIDE_SLOT + pair * SIDE_WAVE;
                 kge_f32x16 acc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -142,7 +151,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
                     bool cancel = false;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const float tnv = *(const float *)(side + srow[i] * 4);
+                        const float tnv = FWD ? *(const float *)(side + srow[i] * 4) : *(const float *)(side + srow[i] * 16);   // |t|^2 or |q|^2
                         d2[i] = fmaf(-2.f, acc[i], o_qn + tnv);
                         thr[i] = 1e-3f * (o_qn + tnv);
                         cancel = cancel || d2[i] < thr[i];
@@ -151,9 +160,9 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
                             if (d2[i] < thr[i]) {
-                                const int n = t * PP_ST + srow[i];
+                                const int sidx = t * PP_ST + srow[i];
                                 d2[i] = kge_direct_d2<true, false>((const char *)a.own + (size_t)oidx * PP_RB,
-                                                                   (const char *)a.str + (size_t)n * PP_RB, nullptr, PP_DP);
+                                                                   (const char *)a.str + (size_t)sidx * PP_RB, nullptr, PP_DP);
                             }
                             asm volatile("" ::: "memory");  // keeps the branch from being turned into selects
                         }
@@ -166,52 +175,70 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
                         sv[i] = -dd * inv;
                     }
                 }
-                // exponents of the weights relative to the row's reference st_m (log2 domain); padding entries -> -inf
-                float x2[16];
-                const float m_neg = st_m > -INFINITY ? -st_m : 0.f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
-                if (t * PP_ST + PP_ST > a.N) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (t * PP_ST + srow[i] >= a.N) x2[i] = -INFINITY;
-                }
-                float tm = -INFINITY;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
-                tm = fmaxf(tm, __shfl_xor(tm, 32));         // both lanes of an own row share the reference
-                // the reference is only raised (and what the row has accumulated rescaled, here and in wave B) when
-                // the tile's maximum exceeds it by more than KGE_TAU
-                float rsc = 1.f;
-                const bool have = st_m > -INFINITY;
-                const bool trip = tm > (have ? KGE_TAU : -INFINITY);
-                if (__any(trip)) {
-                    const float m_new = trip ? (have ? tm + st_m : tm) : st_m;
-                    const float shift = trip ? -tm : 0.f;
-                    rsc = trip ? (have ? kge_exp2(-tm) : 0.f) : 1.f;
-                    st_m = m_new;
-                    st_l *= rsc; st_acc *= rsc; sum1 *= rsc;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) x2[i] += shift;
-                }
                 float coef[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float e = kge_exp2(x2[i]);
-                    st_l += e;
-                    float u = e;
-                    if constexpr (LOSS == KGE_LOGSIGMOID) {
-                        const float y = a.gamma + sv[i];
-                        const float tt = kge_exp2(-fabsf(y) * KGE_LOG2E);
-                        const float rcp = __builtin_amdgcn_rcpf(1.f + tt);
-                        const float sig = y >= 0.f ? rcp : tt * rcp;
-                        const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + tt);
-                        if (e > 0.f) st_acc = fmaf(e, softplus, st_acc);
-                        u = e * sig;
+                float rsc = 1.f;
+                if constexpr (FWD) {
+                    // exponents of the weights relative to the row's reference st_m (log2 domain); padding entries -> -inf
+                    float x2[16];
+                    const float m_neg = st_m > -INFINITY ? -st_m : 0.f;
+    #pragma unroll
+                    for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
+                    if (t * PP_ST + PP_ST > str_limit) {
+    #pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            if (t * PP_ST + srow[i] >= str_limit) x2[i] = -INFINITY;
                     }
-                    const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
-                    coef[i] = c1;
-                    if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
+                    float tm = -INFINITY;
+    #pragma unroll
+                    for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
+                    tm = fmaxf(tm, __shfl_xor(tm, 32));         // both lanes of an own row share the reference
+                    // the reference is only raised (and what the row has accumulated rescaled, here and in wave B) when
+                    // the tile's maximum exceeds it by more than KGE_TAU
+                    const bool have = st_m > -INFINITY;
+                    const bool trip = tm > (have ? KGE_TAU : -INFINITY);
+                    if (__any(trip)) {
+                        const float m_new = trip ? (have ? tm + st_m : tm) : st_m;
+                        const float shift = trip ? -tm : 0.f;
+                        rsc = trip ? (have ? kge_exp2(-tm) : 0.f) : 1.f;
+                        st_m = m_new;
+                        st_l *= rsc; st_acc *= rsc; sum1 *= rsc;
+    #pragma unroll
+                        for (int i = 0; i < 16; ++i) x2[i] += shift;
+                    }
+    #pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float e = kge_exp2(x2[i]);
+                        st_l += e;
+                        float u = e;
+                        if constexpr (LOSS == KGE_LOGSIGMOID) {
+                            const float y = a.gamma + sv[i];
+                            const float tt = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                            const float rcp = __builtin_amdgcn_rcpf(1.f + tt);
+                            const float sig = y >= 0.f ? rcp : tt * rcp;
+                            const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + tt);
+                            if (e > 0.f) st_acc = fmaf(e, softplus, st_acc);
+                            u = e * sig;
+                        }
+                        const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                        coef[i] = c1;
+                        if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
+                    }
+                } else {
+                    // gradient coefficient of every (query, negative) pair from the finished row constants of the queries
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float K2 = *(const float *)(side + srow[i] * 16 + 8);      // -inf for padded queries
+                        float u = kge_exp2(fmaf(sv[i], xscale, K2));
+                        if constexpr (LOSS == KGE_LOGSIGMOID) {
+                            const float y = a.gamma + sv[i];
+                            const float tt = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                            const float rcp = __builtin_amdgcn_rcpf(1.f + tt);
+                            u *= y >= 0.f ? rcp : tt * rcp;
+                        }
+                        const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                        coef[i] = c1;
+                        if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
+                    }
                 }
                 char *x = xch_base + (pair * 2 + (slot & 1)) * PP_XCH;
 #pragma unroll
@@ -226,7 +253,7 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
         st_l += __shfl_xor(st_l, 32); st_acc += __shfl_xor(st_acc, 32); sum1 += __shfl_xor(sum1, 32);
         if (g == 0) {
             a.sum_part[(size_t)split * a.own_pad + oidx] = make_float4(sum1, 0.f, 0.f, 0.f);
-            a.stat_part[(size_t)split * a.own_pad + oidx] = make_float4(st_m, st_l, st_acc, 0.f);
+            if constexpr (FWD) a.stat_part[(size_t)split * a.own_pad + oidx] = make_float4(st_m, st_l, st_acc, 0.f);
         }
     } else {
         // =========================== role B: gradient of the queries =====================================
@@ -300,12 +327,13 @@ void kge_fwd_pp_kernel(const KgeBlockArgs a) {
     }
 }
 
-template <int KIND, int LOSS>
-int fwd_pp_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
-    auto kern = kge_fwd_pp_kernel<KIND, LOSS>;
+template <int MODE, int KIND, int LOSS>
+int pp_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
+    auto kern = kge_pp_kernel<MODE, KIND, LOSS>;
+    constexpr int LDS = pp_lds(MODE);
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, PP_LDS) != hipSuccess) return KGE_E_HIP;
+        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess) return KGE_E_HIP;
         attr_set = true;
     }
     if ((int64_t)own_tiles * 128 != a.own_pad || a.dp != PP_DP) return KGE_E_INVALID_ARG;
@@ -319,15 +347,23 @@ int fwd_pp_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t 
         b.xcd_per = 8 / s2;
         groups = (own_tiles + b.xcd_per - 1) / b.xcd_per;
     }
-    hipLaunchKernelGGL(kern, dim3(8 * groups), dim3(512), PP_LDS, st, b);
+    hipLaunchKernelGGL(kern, dim3(8 * groups), dim3(512), LDS, st, b);
     return kge_launch_status();
+}
+
+template <int MODE>
+int pp_dispatch(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
+    if (kind == KGE_KIND_MULT) return loss == KGE_LOGSIGMOID ? pp_launch<MODE, KGE_KIND_MULT, 0>(a, own_tiles, nsplit, st)
+                                                             : pp_launch<MODE, KGE_KIND_MULT, 1>(a, own_tiles, nsplit, st);
+    return loss == KGE_LOGSIGMOID ? pp_launch<MODE, KGE_KIND_DIST, 0>(a, own_tiles, nsplit, st)
+                                  : pp_launch<MODE, KGE_KIND_DIST, 1>(a, own_tiles, nsplit, st);
 }
 
 }  // namespace
 
 int kge_launch_fwd_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
-    if (kind == KGE_KIND_MULT) return loss == KGE_LOGSIGMOID ? fwd_pp_launch<KGE_KIND_MULT, 0>(a, own_tiles, nsplit, st)
-                                                             : fwd_pp_launch<KGE_KIND_MULT, 1>(a, own_tiles, nsplit, st);
-    return loss == KGE_LOGSIGMOID ? fwd_pp_launch<KGE_KIND_DIST, 0>(a, own_tiles, nsplit, st)
-                                  : fwd_pp_launch<KGE_KIND_DIST, 1>(a, own_tiles, nsplit, st);
+    return pp_dispatch<KGE_MODE_FWD>(kind, loss, a, own_tiles, nsplit, st);
+}
+int kge_launch_gradt_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
+    return pp_dispatch<KGE_MODE_GRADT>(kind, loss, a, own_tiles, nsplit, st);
 }

@@ -81,7 +81,10 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.B = (int)B; g.N = (int)N;
     g.Bp = (int)kge_round_up(B, KGE_PAD); g.Np = (int)kge_round_up(N, KGE_PAD);
     g.own_tiles_b = g.Bp / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_FWD, g.kind));
-    g.own_tiles_n = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_GRADT, g.kind));
+    g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
+    g.dsplit_t = (g.bf16 && g.rb == 1024) ? 2 : 1;
+    // (the two-role kernel of the pass over the negatives keeps one own fragment per wave)
+    g.own_tiles_n = g.Np / (128 * (kge_gradt_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_t) ? 1 : kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_GRADT, g.kind)));
     g.own_tiles_s = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_SCORE, g.kind));
     g.str_tiles_b = g.Bp / KGE_STREAM_TILE; g.str_tiles_n = g.Np / KGE_STREAM_TILE;
     auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps, int occ) {
@@ -368,7 +371,9 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         if (kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q)) rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st);
         else rc = kge_run_tgather_t(md, neg, g.N, g.Np, g.dp, b.T, b.Tt, b.tn, st);
         if (rc != KGE_OK) return rc;
-        if ((rc = kge_run_transpose(g.transh ? b.Q2 : b.Q, b.Qt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
+        // (nor does the two-role kernel of the pass over the negatives need transposed queries)
+        if (!kge_gradt_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_t) &&
+            (rc = kge_run_transpose(g.transh ? b.Q2 : b.Q, b.Qt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
         if (g.transh && (rc = kge_run_transpose(b.W, b.Wt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
         // pass 1 (row owner): loss statistics of every row and the unnormalised gradient of the queries
         a.own = b.Q; a.own2 = b.W; a.str = b.T; a.strT = b.Tt; a.strT_ld = g.Np; a.rowinfo = b.rowinfo; a.tn = b.tn;

@@ -83,6 +83,7 @@ struct KgeBlockArgs {
 };
 
 bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit);
+bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit);
 // launchers implemented in block_*.hip (one file per element type and pass to bound compile time)
 int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
                      int own_tiles, int nsplit, hipStream_t st);
