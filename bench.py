@@ -371,8 +371,9 @@ class RankWorkload:
         ksd.fill_uniform(self.ent, ks.BASE_SEED, ks.TAG_ENT, P["amp"])
         self.models = {}
         for s in self.scorers:
-            rel, _ = ks.relation_tables(s, P["n_rel"], self.d, ks.BASE_SEED, P["amp"])
-            self.models[s] = kge.Model(s, self.ent, torch.from_numpy(rel).cuda().to(dt))
+            rel, relw = ks.relation_tables(s, P["n_rel"], self.d, ks.BASE_SEED, P["amp"])
+            self.models[s] = kge.Model(s, self.ent, torch.from_numpy(rel).cuda().to(dt),
+                                       None if relw is None else torch.from_numpy(relw).cuda().to(dt))
         g = ks.rng(ks.BASE_SEED, ks.TAG_QUERY, 0)
         self.h_host = ks.ZipfIds(self.n_ent, P["zipf_s"]).draw(g, self.Q)
         self.r_host = ks.uniform_ids(g, 0, P["n_rel"], self.Q)
@@ -412,7 +413,8 @@ class RankWorkload:
                 "queries_per_s": self.Q / (us * 1e-6)}
 
     def mfma_flops(self, slot):
-        return 2.0 * self.Q * self.n_ent * self.d       # summed over the chunk launches of one call
+        # summed over the chunk launches of one call (TransH: the second contraction, w^ . t, is part of the score)
+        return 2.0 * self.Q * self.n_ent * self.d * (2 if self.scorers == ["transh"] else 1)
 
     def cpu_baseline(self, orc):
         ks = self.ks
@@ -420,10 +422,11 @@ class RankWorkload:
         ent = self.ent.float().cpu().numpy()
         t0 = time.time()
         for s in self.scorers:
-            rel, _ = ks.relation_tables(s, self.P["n_rel"], self.d, ks.BASE_SEED, self.P["amp"])
+            rel, relw = ks.relation_tables(s, self.P["n_rel"], self.d, ks.BASE_SEED, self.P["amp"])
             if self.bf16:
                 rel = ks.round_to_bf16(rel)
-            orc.topk(s, ent, rel, None, self.h_host[:nq], self.r_host[:nq], 0, self.n_ent, self.K, self.t_host[:nq])
+                relw = None if relw is None else ks.round_to_bf16(relw)
+            orc.topk(s, ent, rel, relw, self.h_host[:nq], self.r_host[:nq], 0, self.n_ent, self.K, self.t_host[:nq])
         dt = time.time() - t0
         return {"value": len(self.scorers) * nq * self.n_ent / dt, "unit": "scored_pairs/s",
                 "cores": orc.num_threads(), "kind": "oracle", "seconds": round(dt, 2),

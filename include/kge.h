@@ -184,8 +184,12 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
  * the candidates.  Exact whenever rank <= K (it is the list position); beyond K it is counted
  * with the matrix-core scores and may differ from the fp64 rank by the number of candidates whose
  * score lies within the rounding error of the true tail's score.
- * Scorers: DistMult, ComplEx, TransE and RotatE with p_norm = 2 (TransH, p_norm = 1: KGE_E_UNSUPPORTED).
- * RotatE's key passes through cos / sin of the phases in fp64: its last bit is the math library's.
+ * Scorers: DistMult, ComplEx, TransE, RotatE and TransH with p_norm = 2 (p_norm = 1, and TransH rows longer than
+ * 512 bytes: KGE_E_UNSUPPORTED).
+ * RotatE's key passes through cos / sin of the phases in fp64: its last bit is the math library's.  TransH's key
+ * is |q' - t + (u.t) u|^2 with u = w / max(|w|, 1e-12) and q' = (h - (u.h) u) + r made once per query in fp64
+ * (wave-wide sums), then u.t and the squared distance by sequential fused multiply-adds over the columns; it
+ * needs 16 d more workspace bytes per query.
  * 1 <= K <= 256.
  */
 int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64_t Q,

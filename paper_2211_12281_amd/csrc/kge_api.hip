@@ -465,8 +465,9 @@ int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64
     if (Q < 0 || Q >= (1ll << 30) || cand_lo < 0 || cand_hi < cand_lo || cand_hi > model->n_ent) return KGE_E_INVALID_ARG;
     if (K < 1 || K > 256) return KGE_E_INVALID_ARG;
     if ((true_t == nullptr) != (out_rank == nullptr)) return KGE_E_INVALID_ARG;
-    if (model->scorer == KGE_TRANSH) return KGE_E_UNSUPPORTED;
-    if ((model->scorer == KGE_TRANSE || model->scorer == KGE_ROTATE) && model->p_norm != 2) return KGE_E_UNSUPPORTED;
+    if (model->scorer == KGE_TRANSH && (int64_t)model->dim * (model->dtype == KGE_BF16 ? 2 : 4) > 512) return KGE_E_UNSUPPORTED;
+    if ((model->scorer == KGE_TRANSE || model->scorer == KGE_ROTATE || model->scorer == KGE_TRANSH) && model->p_norm != 2)
+        return KGE_E_UNSUPPORTED;
     if (Q == 0) return KGE_OK;
     if (!h || !r || !out_idx || !out_score) return KGE_E_INVALID_ARG;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;

@@ -22,6 +22,8 @@ constexpr int TK_HALF = 64;             // entries of one private append area
 
 struct TopkArgs {
     const void *Qmat;                   // [Qp][dp] queries (table element type)
+    const void *Wmat;                   // [Qp][dp] unit normals of the queries' relations (TransH), else nullptr
+    const float *cq;                    // [Qp] w^ . q' of every query (TransH)
     const char *ent;                    // first candidate row
     int64_t ent_stride;                 // bytes between rows
     int32_t valid_bytes;                // d * sizeof(element)
@@ -56,16 +58,21 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// "Local value": larger is better; DistMult: q.t; TransE: 2 q.t - |t|^2 (= -dist^2 + |q|^2).
+// "Local value": larger is better; DistMult: q.t; TransE: 2 q.t - |t|^2 (= -dist^2 + |q|^2); TransH (TH): with
+// q' = h_perp + r, A = w^ . t and c = w^ . q', -|q' - t_perp|^2 + |q'|^2 + c^2 = 2 q'.t - |t|^2 + (A - c)^2: the
+// wave's two row blocks hold q' and w^ of the SAME 32 queries, so both contractions share every fragment read and
+// meet lane for lane in the accumulators.
 //
 // Candidate tiles (32 rows) stream through an LDS ring of NSTAGE stages filled by asynchronous copies,
 // so several tiles are in flight per compute unit.  A row of RB bytes is stored unpadded with its
 // 16-byte chunks XOR-swizzled by (row & 7): the MFMA A-fragment reads of 8 consecutive rows then fall
 // into 8 different bank groups.  The MFMAs of tile t+1 are issued before the epilogue of tile t, so the
 // matrix pipe works while the vector ALU filters.
-template <bool BF16, int RB, int KIND, int OB>
+template <bool BF16, int RB, int KIND, int OB, bool TH = false>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
 void topk_scan_kernel(const TopkArgs a) {
+    static_assert(!TH || (OB == 2 && KIND == KGE_KIND_DIST), "TransH: one block of queries, one of normals");
+    constexpr int NQ = TH ? 1 : OB;                     // blocks of 32 queries per wave
     constexpr int KS = RB / 32;
     constexpr int TILE_BYTES = TK_ST * RB;
     constexpr int NINST = TILE_BYTES / 1024;            // wave-wide 1 KB copies per tile
@@ -83,26 +90,26 @@ void topk_scan_kernel(const TopkArgs a) {
     // fetched from HBM once.
     const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
     const int own_tile = kk % a.own_tiles, split = xcd + 8 * (kk / a.own_tiles);
-    const int own_base = own_tile * (128 * OB);
+    const int own_base = own_tile * (128 * NQ);
     const int64_t t0 = a.tile_lo + (int64_t)split * a.tiles_per_wg;
     const int64_t t1 = t0 + a.tiles_per_wg < a.tile_hi ? t0 + a.tiles_per_wg : a.tile_hi;
     // Every (query, split, lane half) owns a private append area, so appending needs no atomics: the
     // count lives in a register and is stored once at the end.  Two lanes (g = 0, 1) serve one query.
     if (t0 >= t1) {
         if (split < a.nseg)
-            for (int ob = 0; ob < OB; ++ob)
-                a.segcnt[((size_t)(own_base + (wave * OB + ob) * 32 + lr) * a.nseg + split) * 2 + g] = 0;
+            for (int ob = 0; ob < NQ; ++ob)
+                a.segcnt[((size_t)(own_base + (wave * NQ + ob) * 32 + lr) * a.nseg + split) * 2 + g] = 0;
         return;
     }
 
     uint4 own[OB][KS];
-    float thr[OB], vt[OB];
-    int qid[OB], myc[OB];
-    uint2 *segp[OB];
-    uint32_t above[OB];
+    float thr[NQ], vt[NQ];
+    int qid[NQ], myc[NQ];
+    uint2 *segp[NQ];
+    uint32_t above[NQ];
 #pragma unroll
-    for (int ob = 0; ob < OB; ++ob) {
-        qid[ob] = own_base + (wave * OB + ob) * 32 + lr;
+    for (int ob = 0; ob < NQ; ++ob) {
+        qid[ob] = own_base + (wave * NQ + ob) * 32 + lr;
         myc[ob] = 0;
         segp[ob] = a.seg + (((size_t)qid[ob] * a.nseg + split) * 2 + g) * TK_HALF;
         const char *p = (const char *)a.Qmat + (size_t)qid[ob] * RB + g * 16;
@@ -111,6 +118,13 @@ void topk_scan_kernel(const TopkArgs a) {
         thr[ob] = a.thr[qid[ob]];
         vt[ob] = a.vt[qid[ob]];
         above[ob] = 0;
+    }
+    float cq = 0.f;
+    if constexpr (TH) {
+        const char *p = (const char *)a.Wmat + (size_t)qid[0] * RB + g * 16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) own[1][ks] = *(const uint4 *)(p + ks * 32);
+        cq = a.cq[qid[0]];
     }
 
     // ---- loader geometry of this lane: instruction jj covers LDS bytes [(wave*IPW+jj) KB, +1 KB) ----
@@ -153,9 +167,10 @@ void topk_scan_kernel(const TopkArgs a) {
             for (int j = 0; j < 4; ++j) {
                 const kge_f32x4 tn4 = *(const kge_f32x4 *)(tside + (8 * j + 4 * g) * 4);
 #pragma unroll
-                for (int ob = 0; ob < OB; ++ob)
+                for (int ob = 0; ob < NQ; ++ob)
                     for (int u = 0; u < 4; ++u) acc[ob][4 * j + u] = -tn4[u];
             }
+            if constexpr (TH) for (int i = 0; i < 16; ++i) acc[1][i] = 0.f;
         } else {
 #pragma unroll
             for (int ob = 0; ob < OB; ++ob) for (int i = 0; i < 16; ++i) acc[ob][i] = 0.f;
@@ -185,22 +200,25 @@ void topk_scan_kernel(const TopkArgs a) {
         mma_tile(slot + 1, accn);                       // (the last iteration recomputes a stale stage: unused)
         // ---- epilogue of tile `tile`: cheap wave-level test first, the append path only on a hit ----
         const bool tile_full = tile * TK_ST + TK_ST <= a.ncand;
-        float vv[OB][16];                               // the values are the accumulators themselves
+        float vv[NQ][16];                               // the values are the accumulators themselves
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
+            if constexpr (TH) { const float x = acc[1][i] - cq; vv[0][i] = fmaf(x, x, acc[0][i]); }
+            else {
 #pragma unroll
-            for (int ob = 0; ob < OB; ++ob) vv[ob][i] = acc[ob][i];
+                for (int ob = 0; ob < OB; ++ob) vv[ob][i] = acc[ob][i];
+            }
         }
         if (!tile_full) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const bool out = tile * TK_ST + 8 * (i >> 2) + 4 * g + (i & 3) >= a.ncand;
 #pragma unroll
-                for (int ob = 0; ob < OB; ++ob) vv[ob][i] = out ? -INFINITY : vv[ob][i];
+                for (int ob = 0; ob < NQ; ++ob) vv[ob][i] = out ? -INFINITY : vv[ob][i];
             }
         }
 #pragma unroll
-        for (int ob = 0; ob < OB; ++ob) {
+        for (int ob = 0; ob < NQ; ++ob) {
             if (a.true_t) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) above[ob] += vv[ob][i] > vt[ob] ? 1u : 0u;
@@ -224,10 +242,10 @@ void topk_scan_kernel(const TopkArgs a) {
     }
     wait_vmcnt<0>();                                    // no copy may still be in flight when the LDS is released
 #pragma unroll
-    for (int ob = 0; ob < OB; ++ob) a.segcnt[((size_t)qid[ob] * a.nseg + split) * 2 + g] = myc[ob];
+    for (int ob = 0; ob < NQ; ++ob) a.segcnt[((size_t)qid[ob] * a.nseg + split) * 2 + g] = myc[ob];
     if (a.true_t) {
 #pragma unroll
-        for (int ob = 0; ob < OB; ++ob) if (above[ob] && qid[ob] < a.nq) atomicAdd(a.rankcnt + qid[ob], above[ob]);
+        for (int ob = 0; ob < NQ; ++ob) if (above[ob] && qid[ob] < a.nq) atomicAdd(a.rankcnt + qid[ob], above[ob]);
     }
 }
 
@@ -339,6 +357,8 @@ __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *
 //   TransE    q = h + r,          key =  acc,  x = q_j - t_j, acc = fma(x, x, acc)
 //   ComplEx   q = h * r (complex),  key = -acc,  acc = acc + (q_re t_re + q_im t_im) per complex coordinate
 //   RotatE    q = h * e^{ir},       key =  acc,  acc = acc + (x_re^2 + x_im^2), x = q - t
+//   TransH    u = w / max(|w|, 1e-12), q' = (h - (u.h) u) + r (both fp64, made once per query by the preparation
+//             kernel), A = sum fma(u_j, t_j, .), key = acc, x = fma(A, u_j, q'_j - t_j), acc = fma(x, x, acc)
 // every operation rounded on its own (no contraction), in this order: the same sequence of IEEE operations as
 // the direct loops of Table 2 written in C give.  RotatE goes through cos / sin of the phase in fp64, whose last
 // bit is the math library's.
@@ -386,6 +406,18 @@ __device__ double canonical_key(int scorer, int d, const double *qv, const void 
     return topk_mult(scorer) ? -acc : acc;
 }
 
+// TransH key of one tail row against q' = qv[0 .. d) and the unit normal wv[0 .. d)
+template <bool BF16>
+__device__ double canonical_key_th(int d, const double *qv, const double *wv, const void *ent, int64_t toff) {
+    double A = 0.0, acc = 0.0;
+    for (int j = 0; j < d; ++j) A = fma(wv[j], (double)El<BF16>::ld(ent, toff + j), A);
+    for (int j = 0; j < d; ++j) {
+        const double x = fma(A, wv[j], __dsub_rn(qv[j], (double)El<BF16>::ld(ent, toff + j)));
+        acc = fma(x, x, acc);
+    }
+    return acc;
+}
+
 // One wave re-scores 64 survivors of one query, lane = survivor, so that the 64 sequential fp64 chains run in
 // lockstep.  The candidate rows arrive through the LDS in chunks of 64 columns (complex scorers: 32 real parts
 // followed by the 32 imaginary parts of the same coordinates): coalesced row reads on the way in, conflict-free
@@ -394,11 +426,11 @@ __device__ double canonical_key(int scorer, int d, const double *qv, const void 
 template <bool BF16>
 __global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q,
                                                            int64_t cand_lo, const int32_t *cnt, const uint2 *buf, int KP,
-                                                           double *keyd) {
+                                                           double *keyd, const double *qx) {
     constexpr int DW = BF16 ? 32 : 64;                  // dwords per row chunk of 64 columns
     constexpr int E = BF16 ? 2 : 1;                     // columns per dword
     __shared__ uint32_t rows[4][64 * (DW + 1)];
-    __shared__ double qd[4][64];
+    __shared__ double qd[4][64], wd[4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int groups = KP / 64;
     const int64_t task = (int64_t)blockIdx.x * 4 + wave;
@@ -409,7 +441,8 @@ __global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const 
     const bool valid = s0 + lane < n;
     const int64_t cand = cand_lo + buf[(size_t)q * KP + (valid ? s0 + lane : s0)].y;
     const int d = m.dim, half = d >> 1;
-    const bool cplx = topk_cplx(m.scorer);
+    const bool cplx = topk_cplx(m.scorer), th = m.scorer == KGE_TRANSH;
+    const double *qxq = th ? qx + (size_t)q * 2 * d : nullptr;     // TransH: q' then the unit normal, fp64
     const int span = cplx ? 32 : 64, total = cplx ? half : d;      // key steps per chunk, in all
     const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
     uint32_t *mine = rows[wave];
@@ -417,13 +450,18 @@ __global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const 
         if constexpr (BF16) return (double)__uint_as_float((e & 1) ? (row[e >> 1] & 0xffff0000u) : (row[e >> 1] << 16));
         else return (double)__uint_as_float(row[e]);
     };
-    double acc = 0.0;
+    double acc = 0.0, A = 0.0;
+    // (TransH walks the row twice: first A = u . t, then the squared distance)
+    for (int pass = th ? 0 : 1; pass < 2; ++pass)
     for (int c0 = 0; c0 < total; c0 += span) {
         const int steps = total - c0 < span ? total - c0 : span;
         // staged element e <-> table column: real scorers c0 + e; complex: c0 + e (e < 32), d/2 + c0 + e - 32 (else)
         auto column = [&](int e) { return cplx ? (e < 32 ? c0 + e : half + c0 + e - 32) : c0 + e; };
         auto live = [&](int e) { return (cplx ? (e & 31) : e) < steps; };
-        if (live(lane)) qd[wave][lane] = query_f64<BF16>(m, hoff, roff, column(lane));
+        if (live(lane)) {
+            if (th) { qd[wave][lane] = qxq[c0 + lane]; wd[wave][lane] = qxq[d + c0 + lane]; }
+            else qd[wave][lane] = query_f64<BF16>(m, hoff, roff, column(lane));
+        }
         constexpr int RPI = 64 / DW;                    // rows per wave-wide load
         const int sub = lane / DW, dw = lane % DW;
         for (int rr = 0; rr < 64; rr += RPI) {
@@ -437,7 +475,13 @@ __global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const 
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const uint32_t *row = mine + lane * (DW + 1);
-        if (cplx) {
+        if (th) {
+            if (pass == 0) for (int j = 0; j < steps; ++j) A = fma(wd[wave][j], elem(row, j), A);
+            else for (int j = 0; j < steps; ++j) {
+                const double x = fma(A, wd[wave][j], __dsub_rn(qd[wave][j], elem(row, j)));
+                acc = fma(x, x, acc);
+            }
+        } else if (cplx) {
             for (int j = 0; j < steps; ++j) acc = key_step(m.scorer, acc, qd[wave][j], elem(row, j), qd[wave][32 + j], elem(row, 32 + j));
         } else {
             for (int j = 0; j < steps; ++j) acc = key_step(m.scorer, acc, qd[wave][j], elem(row, j), 0.0, 0.0);
@@ -449,7 +493,7 @@ __global__ __launch_bounds__(256) void topk_rescore_kernel(KgeModelDev m, const 
     if (valid) keyd[(size_t)q * KP + s0 + lane] = topk_mult(m.scorer) ? -acc : acc;
 }
 
-struct QInfo { double qn; float eps_a, eps_b; float pad; };   // |q~|^2 (fp64), rounding-bound coefficients
+struct QInfo { double qn; float eps_a, eps_b; float eps_w, c; };   // |q~|^2 (fp64), rounding-bound coefficients; TransH: |dw|, c
 
 // final ordering, safety check, outputs
 template <bool BF16>
@@ -488,7 +532,20 @@ __global__ void topk_final_kernel(KgeModelDev m, const int32_t *h, const int32_t
             const double Tm = sqrt((double)*tmax2);
             double eps, exactK;
             if (dm) { eps = ((double)qi.eps_a + (double)qi.eps_b) * Tm; exactK = -key[K - 1]; }
-            else {
+            else if (m.scorer == KGE_TRANSH) {
+                // value 2 q~.t - |t|^2 + (A~ - c)^2 against -key + |q~|^2 + c^2: the TransE terms for q~ (the
+                // distance is taken to t_perp, no longer than t), then x = A - c: A~ is off by the rounding of the
+                // normal to the table type (dw) and its fp32 accumulation, c (fp32 of u . q') by |dq| against u . q~.
+                const double s = sqrt(qi.qn) + Tm, dq = qi.eps_a, dw = qi.eps_w, c = fabs((double)qi.c);
+                const double wn = 1.0 + dw;                                            // |w~| <= |u| + |dw|
+                const double dc = dq + 6e-8 * c;
+                const double dx = (dw + (double)m.dim * 1.1920929e-07 * wn) * Tm + dc;
+                const double xm = wn * Tm * 1.0001 + c;                                // |A~ - c| at most
+                eps = 2.0 * dq * s + dq * dq + (double)qi.eps_b * s * s               // q~ for q', fp32 sums
+                      + dx * (2.0 * xm + dx) + 4.8e-7 * (xm * xm + s * s)              // x~^2 for x^2, its fp32 evaluation
+                      + dc * (2.0 * c + dc);                                           // c^2 for (u . q~)^2
+                exactK = -key[K - 1] + qi.qn + (double)qi.c * (double)qi.c;
+            } else {
                 const double s = sqrt(qi.qn) + Tm;
                 eps = 2.0 * qi.eps_a * s + (double)qi.eps_a * qi.eps_a + (double)qi.eps_b * s * s;
                 exactK = -key[K - 1] + qi.qn;
@@ -514,7 +571,7 @@ __global__ void topk_final_kernel(KgeModelDev m, const int32_t *h, const int32_t
 template <bool BF16>
 __global__ void topk_exact_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, int Q, int64_t cand_lo,
                                   int64_t ncand, int K, int32_t *out_idx, float *out_score, const int32_t *true_t,
-                                  int64_t *out_rank, const int32_t *flag) {
+                                  int64_t *out_rank, const int32_t *flag, const double *qx) {
     constexpr int CAPX = 2048;
     __shared__ double key[CAPX];
     __shared__ int idx[CAPX];
@@ -524,18 +581,25 @@ __global__ void topk_exact_kernel(KgeModelDev m, const int32_t *h, const int32_t
     const int q = blockIdx.x;
     if (q >= Q || !flag[q]) return;
     const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld;
-    __shared__ double qv[TK_MAXD];
-    for (int j = threadIdx.x; j < m.dim; j += blockDim.x) qv[j] = query_f64<BF16>(m, hoff, roff, j);
+    __shared__ double qv[TK_MAXD], wv[TK_MAXD];
+    const bool th = m.scorer == KGE_TRANSH;
+    for (int j = threadIdx.x; j < m.dim; j += blockDim.x) {
+        if (th) { qv[j] = qx[(size_t)q * 2 * m.dim + j]; wv[j] = qx[(size_t)q * 2 * m.dim + m.dim + j]; }
+        else qv[j] = query_f64<BF16>(m, hoff, roff, j);
+    }
+    auto key_of = [&](int64_t toff) {
+        return th ? canonical_key_th<BF16>(m.dim, qv, wv, m.ent, toff) : canonical_key<BF16>(m.scorer, m.dim, qv, m.ent, toff);
+    };
     if (threadIdx.x == 0) { count = 0; tau = INFINITY; above = 0ull; }
     for (int i = threadIdx.x; i < CAPX; i += blockDim.x) { key[i] = INFINITY; idx[i] = 0x7FFFFFFF; }
     __syncthreads();
     double tkey = 0.0; int tt = -1;
-    if (true_t) { tt = true_t[q]; tkey = canonical_key<BF16>(m.scorer, m.dim, qv, m.ent, (int64_t)tt * m.ent_ld); }
+    if (true_t) { tt = true_t[q]; tkey = key_of((int64_t)tt * m.ent_ld); }
     unsigned long long mine = 0;
     for (int64_t c0 = 0; c0 < ncand; c0 += blockDim.x) {
         const int64_t c = c0 + threadIdx.x;
         if (c < ncand) {
-            const double kc = canonical_key<BF16>(m.scorer, m.dim, qv, m.ent, (cand_lo + c) * m.ent_ld);
+            const double kc = key_of((cand_lo + c) * m.ent_ld);
             if (true_t && (kc < tkey || (kc == tkey && cand_lo + c < tt))) ++mine;
             if (kc <= tau) { const int s = atomicAdd(&count, 1); key[s] = kc; idx[s] = (int)c; }   // s < CAPX by the compaction below
         }
@@ -607,9 +671,82 @@ __global__ void topk_prep_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         qi.eps_a = (float)(sqrt(dq2) * 1.0001);
         qi.eps_b = mult ? (float)(d * 1.1920929e-07 * sqrt(qn) * 1.0001)                       // d 2^-23 |q~|
                                             : (float)((d + 2) * 2.3841858e-07);                  // (d+2) 2^-22: d products and the -|t|^2 start value
-        qi.pad = 0.f;
+        qi.eps_w = 0.f; qi.c = 0.f;
         qinfo[q] = qi;
         vt[q] = true_t ? (mult ? vtl : 2.f * vtl - tnl) : INFINITY;
+        thr[q] = -INFINITY; cnt[q] = 0; flag[q] = 0; rankcnt[q] = 0;
+    }
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// TransH, one wave per query: unit normal u and q' = (h - (u.h) u) + r in fp64 (kept for the re-scoring), their
+// roundings to the table type (q~ stored doubled, like TransE's), c = u . q', the value of the held-out tail
+// and the rounding-bound coefficients.
+template <bool BF16>
+__global__ void topk_prep_th_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *true_t, int Q,
+                                    int Qp, int dp, void *Qm, void *Wm, float *cq, double *qx, float *vt, QInfo *qinfo,
+                                    float *thr, int32_t *cnt, int32_t *flag, uint32_t *rankcnt) {
+    const int lane = threadIdx.x & 63;
+    const int q = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (q >= Qp) return;
+    if (q >= Q) {
+        for (int j = lane; j < dp; j += 64) { El<BF16>::st(Qm, (int64_t)q * dp + j, 0.f); El<BF16>::st(Wm, (int64_t)q * dp + j, 0.f); }
+        if (lane == 0) { cq[q] = 0.f; vt[q] = INFINITY; thr[q] = INFINITY; cnt[q] = 0; flag[q] = 0; rankcnt[q] = 0; }
+        return;
+    }
+    const int d = m.dim;
+    const int64_t hoff = (int64_t)h[q] * m.ent_ld, roff = (int64_t)r[q] * m.rel_ld, woff = (int64_t)r[q] * m.relw_ld;
+    double hv[KGE_MAXJ], rv[KGE_MAXJ], wv[KGE_MAXJ];
+    double nn = 0.0;
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        const bool ok = j < d;
+        hv[k] = ok ? (double)El<BF16>::ld(m.ent, hoff + j) : 0.0;
+        rv[k] = ok ? (double)El<BF16>::ld(m.rel, roff + j) : 0.0;
+        wv[k] = ok ? (double)El<BF16>::ld(m.relw, woff + j) : 0.0;
+        nn += wv[k] * wv[k];
+    }
+    nn = wave_sum_f64(nn);
+    const double nrm = fmax(sqrt(nn), 1e-12);
+    double wh = 0.0;
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) { wv[k] = wv[k] / nrm; wh += wv[k] * hv[k]; }
+    wh = wave_sum_f64(wh);
+    double ce = 0.0, qn = 0.0, dq2 = 0.0, dw2 = 0.0;
+    float qt = 0.f, tnl = 0.f, wt = 0.f;
+    const int64_t toff = true_t ? (int64_t)true_t[q] * m.ent_ld : 0;
+    double *qxq = qx + (size_t)q * 2 * d;
+#pragma unroll
+    for (int k = 0; k < KGE_MAXJ; ++k) {
+        const int j = lane + 64 * k;
+        const double qe = (hv[k] - wh * wv[k]) + rv[k];
+        const float qr = El<BF16>::rnd((float)qe), wr = El<BF16>::rnd((float)wv[k]);
+        if (j < dp) { El<BF16>::st(Qm, (int64_t)q * dp + j, 2.f * qr); El<BF16>::st(Wm, (int64_t)q * dp + j, wr); }
+        if (j >= d) continue;
+        qxq[j] = qe; qxq[d + j] = wv[k];
+        ce += wv[k] * qe; qn += (double)qr * (double)qr;
+        dq2 += ((double)qr - qe) * ((double)qr - qe); dw2 += ((double)wr - wv[k]) * ((double)wr - wv[k]);
+        if (true_t) { const float tv = El<BF16>::ld(m.ent, toff + j); qt += qr * tv; tnl += tv * tv; wt += wr * tv; }
+    }
+    ce = wave_sum_f64(ce); qn = wave_sum_f64(qn); dq2 = wave_sum_f64(dq2); dw2 = wave_sum_f64(dw2);
+    qt = kge_wave_sum(qt); tnl = kge_wave_sum(tnl); wt = kge_wave_sum(wt);
+    if (lane == 0) {
+        const float c = (float)ce;
+        QInfo qi;
+        qi.qn = qn;
+        qi.eps_a = (float)(sqrt(dq2) * 1.0001);
+        qi.eps_b = (float)((d + 2) * 2.3841858e-07);
+        qi.eps_w = (float)(sqrt(dw2) * 1.0001);
+        qi.c = c;
+        qinfo[q] = qi;
+        cq[q] = c;
+        vt[q] = true_t ? fmaf(wt - c, wt - c, 2.f * qt - tnl) : INFINITY;
         thr[q] = -INFINITY; cnt[q] = 0; flag[q] = 0; rankcnt[q] = 0;
     }
 }
@@ -675,14 +812,15 @@ __global__ void topk_fill_empty_kernel(int32_t *out_idx, float *out_score, int64
 __global__ void topk_zero_kernel(uint32_t *p, uint32_t *z) { if (threadIdx.x == 0) *p = 0u; if (threadIdx.x < 64) z[threadIdx.x] = 0u; }
 
 struct TopkPlan {
-    bool bf16; int es, rb, dp, ob, own; int Qp; int KP, KPP, nseg; int64_t npad;
+    bool bf16, th; int es, rb, dp, ob, own, dim; int Qp; int KP, KPP, nseg; int64_t npad;
 };
 
 TopkPlan make_plan(const kge_model_t &m, int64_t Q, int64_t ncand, int K) {
     TopkPlan p{};
     p.bf16 = m.dtype == KGE_BF16; p.es = p.bf16 ? 2 : 4;
     p.rb = m.dim * p.es <= 512 ? 512 : 1024; p.dp = p.rb / p.es;
-    p.ob = p.rb == 512 ? 2 : 1; p.own = 128 * p.ob;
+    p.th = m.scorer == KGE_TRANSH; p.dim = m.dim;
+    p.ob = p.rb == 512 ? 2 : 1; p.own = p.th ? 128 : 128 * p.ob;          // TransH: the second row block holds the normals
     p.Qp = (int)kge_round_up(Q, p.own);
     p.KP = (int)kge_round_up(2 * K + 56, 64);
     p.KPP = 1; while (p.KPP < p.KP) p.KPP <<= 1;
@@ -693,6 +831,7 @@ TopkPlan make_plan(const kge_model_t &m, int64_t Q, int64_t ncand, int K) {
 
 struct TopkWs {
     void *Qm; float *vt, *thr, *tn; QInfo *qinfo; int32_t *cnt, *flag; uint32_t *rankcnt, *tmax; uint2 *keep, *seg; int32_t *segcnt; double *keyd; uint32_t *zeros;
+    void *Wm; float *cq; double *qx;                    // TransH only
 };
 
 size_t topk_carve(const TopkPlan &p, void *ws, TopkWs &w) {
@@ -708,20 +847,25 @@ size_t topk_carve(const TopkPlan &p, void *ws, TopkWs &w) {
     w.seg = (uint2 *)take((size_t)p.Qp * p.nseg * 2 * TK_HALF * 8);
     w.segcnt = (int32_t *)take((size_t)p.Qp * p.nseg * 2 * 4);
     w.keyd = (double *)take((size_t)p.Qp * p.KP * 8);
+    w.Wm = nullptr; w.cq = nullptr; w.qx = nullptr;
+    if (p.th) {
+        w.Wm = take((size_t)p.Qp * p.rb); w.cq = (float *)take((size_t)p.Qp * 4);
+        w.qx = (double *)take((size_t)p.Qp * 2 * p.dim * 8);
+    }
     return off + 256;
 }
 
-template <bool BF16, int RB, int KIND, int OB>
+template <bool BF16, int RB, int KIND, int OB, bool TH = false>
 int launch_scan(const TopkArgs &a, int own_tiles, int nsplit, hipStream_t st) {
     constexpr int NSTAGE = RB == 512 ? 4 : 3;
     constexpr int LDS = NSTAGE * TK_ST * RB + (NSTAGE + 1) * 4 * 256;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)topk_scan_kernel<BF16, RB, KIND, OB>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
+        if (hipFuncSetAttribute((const void *)topk_scan_kernel<BF16, RB, KIND, OB, TH>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
             return KGE_E_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((topk_scan_kernel<BF16, RB, KIND, OB>), dim3(own_tiles * ((nsplit + 7) / 8 * 8)), dim3(256), LDS, st, a);
+    hipLaunchKernelGGL((topk_scan_kernel<BF16, RB, KIND, OB, TH>), dim3(own_tiles * ((nsplit + 7) / 8 * 8)), dim3(256), LDS, st, a);
     return kge_launch_status();
 }
 
@@ -757,17 +901,21 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
     const int kind = (model.scorer == KGE_DISTMULT || model.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
 
     hipLaunchKernelGGL(topk_zero_kernel, dim3(1), dim3(64), 0, st, w.tmax, w.zeros);
+    if (p.th) {
+        if (p.bf16) hipLaunchKernelGGL(topk_prep_th_kernel<true>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.Wm, w.cq, w.qx, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
+        else hipLaunchKernelGGL(topk_prep_th_kernel<false>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.Wm, w.cq, w.qx, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
+    }
     if (p.bf16) {
-        hipLaunchKernelGGL(topk_prep_kernel<true>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
+        if (!p.th) hipLaunchKernelGGL(topk_prep_kernel<true>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
         hipLaunchKernelGGL(topk_tnorm_kernel<true>, dim3((unsigned)(p.npad / 4 < 8192 ? (p.npad + 3) / 4 : 8192)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
     } else {
-        hipLaunchKernelGGL(topk_prep_kernel<false>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
+        if (!p.th) hipLaunchKernelGGL(topk_prep_kernel<false>, dim3((p.Qp + 3) / 4), dim3(256), 0, st, md, h, r, true_t, (int)Q, p.Qp, p.dp, w.Qm, w.vt, w.qinfo, w.thr, w.cnt, w.flag, w.rankcnt);
         hipLaunchKernelGGL(topk_tnorm_kernel<false>, dim3((unsigned)(p.npad / 4 < 8192 ? (p.npad + 3) / 4 : 8192)), dim3(256), 0, st, cand0, stride, model.dim, ncand, p.npad, w.tn, w.tmax);
     }
     if (hipGetLastError() != hipSuccess) return KGE_E_HIP;
 
     TopkArgs base{};
-    base.Qmat = w.Qm; base.ent = cand0; base.ent_stride = stride; base.valid_bytes = model.dim * p.es;
+    base.Qmat = w.Qm; base.Wmat = w.Wm; base.cq = w.cq; base.ent = cand0; base.ent_stride = stride; base.valid_bytes = model.dim * p.es;
     base.ncand = ncand; base.cand_lo = lo; base.tn = w.tn; base.thr = w.thr; base.vt = w.vt; base.true_t = true_t;
     base.seg = w.seg; base.segcnt = w.segcnt; base.nseg = p.nseg; base.rankcnt = w.rankcnt; base.nq = (int)Q; base.zeros = w.zeros;
     const int own_tiles = p.Qp / p.own;
@@ -796,7 +944,9 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
         int rc;
         {
             KgeProfScope prof(KGE_PROF_TOPK_SCAN, st);
-            if (p.bf16 && p.rb == 512) rc = kind == KGE_KIND_MULT ? launch_scan<true, 512, KGE_KIND_MULT, 2>(c, own_tiles, nsplit, st) : launch_scan<true, 512, KGE_KIND_DIST, 2>(c, own_tiles, nsplit, st);
+            if (p.th) rc = p.bf16 ? launch_scan<true, 512, KGE_KIND_DIST, 2, true>(c, own_tiles, nsplit, st)
+                                  : launch_scan<false, 512, KGE_KIND_DIST, 2, true>(c, own_tiles, nsplit, st);
+            else if (p.bf16 && p.rb == 512) rc = kind == KGE_KIND_MULT ? launch_scan<true, 512, KGE_KIND_MULT, 2>(c, own_tiles, nsplit, st) : launch_scan<true, 512, KGE_KIND_DIST, 2>(c, own_tiles, nsplit, st);
             else if (p.bf16) rc = kind == KGE_KIND_MULT ? launch_scan<true, 1024, KGE_KIND_MULT, 1>(c, own_tiles, nsplit, st) : launch_scan<true, 1024, KGE_KIND_DIST, 1>(c, own_tiles, nsplit, st);
             else if (p.rb == 512) rc = kind == KGE_KIND_MULT ? launch_scan<false, 512, KGE_KIND_MULT, 2>(c, own_tiles, nsplit, st) : launch_scan<false, 512, KGE_KIND_DIST, 2>(c, own_tiles, nsplit, st);
             else rc = kind == KGE_KIND_MULT ? launch_scan<false, 1024, KGE_KIND_MULT, 1>(c, own_tiles, nsplit, st) : launch_scan<false, 1024, KGE_KIND_DIST, 1>(c, own_tiles, nsplit, st);
@@ -809,13 +959,13 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
     const int64_t nres = Q * p.KP;
     const int final_lds = p.KPP * 12;
     if (p.bf16) {
-        hipLaunchKernelGGL(topk_rescore_kernel<true>, dim3((unsigned)((nres / 64 + 3) / 4)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_rescore_kernel<true>, dim3((unsigned)((nres / 64 + 3) / 4)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd, w.qx);
         hipLaunchKernelGGL(topk_final_kernel<true>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.keep, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
-        hipLaunchKernelGGL(topk_exact_kernel<true>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
+        hipLaunchKernelGGL(topk_exact_kernel<true>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag, w.qx);
     } else {
-        hipLaunchKernelGGL(topk_rescore_kernel<false>, dim3((unsigned)((nres / 64 + 3) / 4)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd);
+        hipLaunchKernelGGL(topk_rescore_kernel<false>, dim3((unsigned)((nres / 64 + 3) / 4)), dim3(256), 0, st, md, h, r, (int)Q, lo, w.cnt, w.keep, p.KP, w.keyd, w.qx);
         hipLaunchKernelGGL(topk_final_kernel<false>, dim3((unsigned)Q), dim3(256), final_lds, st, md, h, r, (int)Q, lo, ncand, w.cnt, w.keep, p.KP, p.KPP, w.keyd, w.thr, w.qinfo, (const float *)w.tmax, K, out_idx, out_score, true_t, w.rankcnt, out_rank, w.flag);
-        hipLaunchKernelGGL(topk_exact_kernel<false>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag);
+        hipLaunchKernelGGL(topk_exact_kernel<false>, dim3((unsigned)Q), dim3(256), 0, st, md, h, r, (int)Q, lo, ncand, K, out_idx, out_score, true_t, out_rank, w.flag, w.qx);
     }
     return kge_launch_status();
 }

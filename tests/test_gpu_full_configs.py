@@ -136,16 +136,18 @@ def test_c3_shapes_transe_one_norm_full_size(orc):
     _free()
 
 
-@pytest.mark.parametrize("scorer", ["distmult", "transe", "complex", "rotate"])
+@pytest.mark.parametrize("scorer", ["distmult", "transe", "complex", "rotate", "transh"])
 def test_c4_link_prediction_full_size(orc, scorer):
     """8192 queries against all 10M entities; the oracle ranks a 16-query subset at full width."""
     import paper_2211_12281_amd as kge
     P = ks.PRESETS["c4"]
     n_ent, d, Q, K = P["n_ent"], P["dim"], P["Q"], P["K"]
     ent = _fill(n_ent, d, torch.bfloat16)
-    rel, _ = ks.relation_tables(scorer, P["n_rel"], d)
+    rel, relw = ks.relation_tables(scorer, P["n_rel"], d)
     rel = ks.round_to_bf16(rel)
-    model = kge.Model(scorer, ent, torch.from_numpy(rel).cuda().to(torch.bfloat16))
+    relw = None if relw is None else ks.round_to_bf16(relw)
+    model = kge.Model(scorer, ent, torch.from_numpy(rel).cuda().to(torch.bfloat16),
+                      None if relw is None else torch.from_numpy(relw).cuda().to(torch.bfloat16))
     g = ks.rng(ks.BASE_SEED, ks.TAG_QUERY, 0)
     h = ks.ZipfIds(n_ent, P["zipf_s"]).draw(g, Q)
     r = ks.uniform_ids(g, 0, P["n_rel"], Q)
@@ -163,11 +165,13 @@ def test_c4_link_prediction_full_size(orc, scorer):
     # exact comparison on a subset
     sub = np.r_[0:4, np.arange(100, 8192, 700)][:16]
     host = ent.float().cpu().numpy()
-    ridx, rsc, rrank = orc.topk(scorer, host, rel, None, h[sub], r[sub], 0, n_ent, K, tt[sub])
-    if scorer == "rotate":
-        # cos / sin in fp64 differ in the last bit between math libraries: candidates whose keys agree to 1e-12 may swap
+    ridx, rsc, rrank = orc.topk(scorer, host, rel, relw, h[sub], r[sub], 0, n_ent, K, tt[sub])
+    if scorer in ("rotate", "transh"):
+        # cos / sin in fp64 differ in the last bit between math libraries (TransH: the summation order of the fp64
+        # normalisation and dot products is the implementation's): candidates whose keys agree to 1e-12 may swap
         for (i, k) in np.argwhere(idx[sub] != ridx):
-            mine = orc.score_one(scorer, host[h[sub[i]]], rel[r[sub[i]]], None, host[idx[sub[i], k]])
+            mine = orc.score_one(scorer, host[h[sub[i]]], rel[r[sub[i]]], None if relw is None else relw[r[sub[i]]],
+                                 host[idx[sub[i], k]])
             assert abs(mine - rsc[i, k]) <= 1e-12 * abs(rsc[i, k])
     else:
         assert np.array_equal(idx[sub], ridx)

@@ -13,14 +13,16 @@ def _check(orc, scorer, G, bf16, lo, hi, K, true_t=None):
     model = gpu_model(scorer, G, bf16)
     tt = None if true_t is None else dev_idx(true_t)
     idx, sc, rank = kge.topk(model, dev_idx(G["h"]), dev_idx(G["r"]), lo, hi, K, tt)
-    ridx, rsc, rrank = orc.topk(scorer, G["ent"], G["rel"], None, G["h"], G["r"], lo, hi, K, true_t)
+    relw = G.get("relw")
+    ridx, rsc, rrank = orc.topk(scorer, G["ent"], G["rel"], relw, G["h"], G["r"], lo, hi, K, true_t)
     idx, sc = idx.cpu().numpy(), sc.cpu().numpy()
-    if scorer == "rotate" and not np.array_equal(idx, ridx):
-        # the key passes through cos / sin in fp64, whose last bit belongs to the math library: two candidates whose
-        # keys agree to 1e-12 may legitimately swap places; anything else must be identical
+    if scorer in ("rotate", "transh") and not np.array_equal(idx, ridx):
+        # the key passes through cos / sin in fp64, whose last bit belongs to the math library (TransH: through the
+        # normalisation of w and two fp64 dot products whose summation order is the implementation's): two candidates
+        # whose keys agree to 1e-12 may legitimately swap places; anything else must be identical
         for (q, i) in np.argwhere(idx != ridx):
             one = slice(q, q + 1)
-            _, s = orc.score_batch(scorer, G["ent"], G["rel"], None, G["h"][one], G["r"][one], G["h"][one], idx[q, i:i + 1])
+            _, s = orc.score_batch(scorer, G["ent"], G["rel"], relw, G["h"][one], G["r"][one], G["h"][one], idx[q, i:i + 1])
             assert abs(s[0, 0] - rsc[q, i]) <= 1e-12 * max(abs(rsc[q, i]), 1e-30), (q, i)
     else:
         assert np.array_equal(idx, ridx), np.argwhere(idx != ridx)[:5]
@@ -40,25 +42,29 @@ def _check(orc, scorer, G, bf16, lo, hi, K, true_t=None):
             cand = np.arange(lo, hi, dtype=np.int32)
             for q in np.where(~inside)[0][:16]:
                 one = slice(q, q + 1)
-                st, s = orc.score_batch(scorer, G["ent"], G["rel"], None, G["h"][one], G["r"][one], true_t[one], cand)
+                st, s = orc.score_batch(scorer, G["ent"], G["rel"], relw, G["h"][one], G["r"][one], true_t[one], cand)
                 band = (2e-2 if bf16 else 1e-5) * max(np.max(np.abs(s)), 1e-30)
                 assert abs(int(rank[q]) - int(rrank[q])) <= int(np.sum(np.abs(s[0] - st[0]) <= band)) + 1
 
 
-@pytest.mark.parametrize("scorer", ["distmult", "transe", "complex", "rotate"])
+@pytest.mark.parametrize("scorer", ["distmult", "transe", "complex", "rotate", "transh"])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_full_ranking_small_graph(orc, scorer, bf16):
     """64 queries over all 1,000 entities, K = 100 (the tiny configuration's brute-force ranking)."""
     G = small_graph(scorer, 1000, 10, 32, 64, 0, normal=True)
     if bf16:
         G["ent"], G["rel"] = ks.round_to_bf16(G["ent"]), ks.round_to_bf16(G["rel"])
+        if G["relw"] is not None:
+            G["relw"] = ks.round_to_bf16(G["relw"])
     _check(orc, scorer, G, bf16, 0, 1000, 100, G["t"])
 
 
 @pytest.mark.parametrize("scorer,bf16,dim", [("distmult", True, 256), ("transe", True, 256), ("distmult", False, 64),
                                              ("transe", False, 128), ("distmult", True, 512), ("transe", False, 256),
                                              ("complex", True, 256), ("rotate", True, 256), ("complex", False, 72),
-                                             ("rotate", False, 128), ("complex", True, 512), ("rotate", True, 48)])
+                                             ("rotate", False, 128), ("complex", True, 512), ("rotate", True, 48),
+                                             ("transh", True, 256), ("transh", False, 128), ("transh", True, 80),
+                                             ("transh", False, 24)])
 def test_many_candidates_several_chunks(orc, scorer, bf16, dim):
     G = make_case(scorer, 60000, 20, dim, 300, 0, bf16)
     true_t = ks.uniform_ids(ks.rng(3, ks.TAG_HELDOUT), 0, 60000, 300)
