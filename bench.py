@@ -68,8 +68,8 @@ class TrainWorkload:
         self.kge, self.torch, self.ks, self.P, self.name = kge, torch, ks, P, name
         self.scorer = only or P["scorers"][0]
         self.p_norm = p_norm
-        if p_norm == 1 and self.scorer not in ("transe", "rotate"):
-            raise SystemExit("--p-norm 1 needs --scorer transe or --scorer rotate")
+        if p_norm == 1 and self.scorer not in ("transe", "rotate", "transh"):
+            raise SystemExit("--p-norm 1 needs --scorer transe, rotate or transh")
         self.n_ent = max(1000, int(P["n_ent"] * scale))
         self.n_rel, self.d, self.B, self.N = P["n_rel"], P["dim"], P["B"], P["N"]
         self.bf16 = P["dtype"] == "bf16"
@@ -263,7 +263,12 @@ class TrainWorkload:
     def alu_ops(self, slot):
         # 1-norm kernels: two vector operations per (query, negative, dimension) and pass - subtract and
         # accumulate |.| for the scores, select by the sign and accumulate for a gradient pass
-        return 2.0 * self.B * self.N * self.d
+        # TransH: x = q' - t + A w^ costs two, and the kernels carry A (one, scores), P (one, scores), the gradient of
+        # w^ (two, pass over the queries) or the hyperplane term of dt (one, pass over the negatives) besides
+        per = 2.0
+        if self.scorer == "transh":
+            per = {"block_score": 5.0, "block_fwd": 5.0, "block_gradt": 4.0}.get(slot, 5.0)
+        return per * self.B * self.N * self.d
 
     def cpu_baseline(self, orc):
         """Oracle forward + backward + sparse Adam on the first rows of batch 0 against all negatives."""

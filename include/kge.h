@@ -59,8 +59,9 @@ typedef struct {
     int32_t p_norm;      /* distance scorers: 2, or 1 (Table 2: p in {1, 2}) for TransE and RotatE - RotatE then takes
                             the 1-norm in R^d, |Re| + |Im| per complex coordinate; the 1-norm has no contraction
                             form, its kernels run on the vector pipe and kge_loss_bwd keeps the B x N score block
-                            in the workspace.  TransH with p_norm = 1, and kge_topk with p_norm = 1:
-                            KGE_E_UNSUPPORTED.  Ignored by DistMult and ComplEx. */
+                            in the workspace (TransH: three such blocks - the scores, w^ . t and sign(x) . w^ of
+                            every pair, since the hyperplane term sits inside the absolute values).  kge_topk
+                            with p_norm = 1: KGE_E_UNSUPPORTED.  Ignored by DistMult and ComplEx. */
     int32_t dtype;       /* kge_dtype_t of ent, rel, relw as the kernels read them */
     int32_t dim;         /* d */
     int32_t rel_dim;     /* d, or d/2 for RotatE */

@@ -60,7 +60,6 @@ int validate_model(const kge_model_t *m) {
     if (m->dim <= 0 || m->dim % (32 / es) != 0 || m->dim * es > 1024) return KGE_E_INVALID_ARG;
     const bool dist = m->scorer == KGE_TRANSE || m->scorer == KGE_TRANSH || m->scorer == KGE_ROTATE;
     if (dist && m->p_norm != 1 && m->p_norm != 2) return KGE_E_INVALID_ARG;
-    if (m->p_norm == 1 && m->scorer == KGE_TRANSH) return KGE_E_UNSUPPORTED;
     const int k = m->scorer == KGE_ROTATE ? m->dim / 2 : m->dim;
     if (m->rel_dim != k) return KGE_E_INVALID_ARG;
     if (m->n_ent <= 0 || m->n_rel <= 0 || m->n_ent >= (1ll << 31) || m->n_rel >= (1ll << 31)) return KGE_E_INVALID_ARG;
@@ -101,8 +100,8 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
     g.dsplit_t = (g.bf16 && g.rb == 1024) ? 2 : 1;
     if (g.l1) {
-        g.nsplit_q = kge_l1_nsplit(g.Bp, g.Np, g.dp);
-        g.nsplit_t = kge_l1_nsplit(g.Np, g.Bp, g.dp);
+        g.nsplit_q = kge_l1_nsplit(g.Bp, g.Np, g.dp, g.transh);
+        g.nsplit_t = kge_l1_nsplit(g.Np, g.Bp, g.dp, g.transh);
     }
     return g;
 }
@@ -125,6 +124,7 @@ struct Buffers {
     float4 *stat_part; float *accq, *accq2; float4 *sumq; float *acct; float4 *sumt;
     float *regv;                       // L3 norms of the gathered slots: [Bp heads][Bp tails][Np negatives]
     float *S, *Q32;                    // 1-norm scorers: the score block [Bp][Np], the queries unrounded [Bp][dp]
+    float *W32, *A, *P;                // ... TransH: the unit normals unrounded, w^ . t and sign(x) . w^ per pair [Bp][Np]
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -137,16 +137,19 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
     b.tn = c.take<float>(g.Np);
     b.pos = c.take<float>(g.Bp);
     b.Q32 = g.l1 ? c.take<float>(rowsB) : nullptr;
+    b.W32 = g.l1 && g.transh ? c.take<float>(rowsB) : nullptr;
+    b.A = b.P = nullptr;
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
     b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr;
     if (bwd) {
-        b.Q2 = g.transh ? c.take<char>(rowsB * es) : nullptr;
+        b.Q2 = g.transh && !g.l1 ? c.take<char>(rowsB * es) : nullptr;
         if (!g.l1) {
             b.Qt = c.take<char>(rowsB * es);
             b.Wt = g.transh ? c.take<char>(rowsB * es) : nullptr;
             b.Tt = c.take<char>(rowsN * es);
         } else {
             b.S = c.take<float>((size_t)g.Bp * g.Np);
+            if (g.transh) { b.A = c.take<float>((size_t)g.Bp * g.Np); b.P = c.take<float>((size_t)g.Bp * g.Np); }
         }
         b.lossb = c.take<float>(g.Bp);
         b.gpos = c.take<float>(g.Bp);
@@ -319,10 +322,12 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     if (carve(g, false, nullptr, b) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     carve(g, false, ws, b);
     KgeModelDev md = dev_model(*model);
-    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.rowinfo, b.pos, pos_out, st);
+    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st);
     if (rc != KGE_OK || !block) return rc;
     rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st);
     if (rc != KGE_OK) return rc;
+    if (g.l1 && g.transh)
+        return kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, nullptr, nullptr, g.N, st);
     if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);
     KgeBlockArgs a{};
     a.own = b.T; a.str = b.Q; a.str2 = b.W; a.rowinfo = b.rowinfo; a.tn = b.tn;
@@ -346,7 +351,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     if (N > 0 && (!neg || !g_ent || !g_ent_idx)) return KGE_E_INVALID_ARG;
     if (model->scorer == KGE_TRANSH && B > 0 && !g_relw) return KGE_E_INVALID_ARG;
     Geometry g = make_geometry(*model, B, N);
-    if (g.transh && g.rb > 512) return KGE_E_UNSUPPORTED;
+    if (g.transh && !g.l1 && g.rb > 512) return KGE_E_UNSUPPORTED;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)hip_stream;
     Buffers b;
@@ -359,12 +364,14 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
                              ? (float)log((double)(cfg->n_ent_for_c - 1) / (double)N) : 0.f;
     const bool have_block = B > 0 && N > 0;
 
-    if ((rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.rowinfo, b.pos, nullptr, st)) != KGE_OK) return rc;
+    if ((rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos, nullptr, st)) != KGE_OK) return rc;
     KgeBlockArgs a{};
     if (have_block && g.l1) {
         // 1-norm: the score block goes to memory, one row pass gives the loss statistics
         if ((rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st)) != KGE_OK) return rc;
-        if ((rc = kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, g.Np, st)) != KGE_OK) return rc;
+        rc = g.transh ? kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, b.A, b.P, g.Np, st)
+                      : kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, g.Np, st);
+        if (rc != KGE_OK) return rc;
         if ((rc = kge_run_l1_rowstat(b.S, g.Np, g.B, g.N, g.Bp, cfg->loss, cfg->gamma, cfg->adv_temp, b.stat_part, st)) != KGE_OK) return rc;
     } else if (have_block) {
         // (the two-role row-owner kernel transposes its tiles in the LDS and needs no transposed copy of the negatives)
@@ -384,7 +391,12 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     }
     if ((rc = kge_run_rowfinish(b.stat_part, have_block ? (g.l1 ? 1 : g.nsplit_q) : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
                                 cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, loss_out, st)) != KGE_OK) return rc;
-    if (have_block && g.l1) {
+    if (have_block && g.l1 && g.transh) {
+        if ((rc = kge_run_l1h_grad(g.bf16, true, b.Q32, b.W32, b.T, b.S, b.A, b.P, g.Np, b.rowinfo, g.B, g.N, g.Bp, g.Np, g.dp,
+                                   cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_q, b.accq, b.accq2, st)) != KGE_OK) return rc;
+        if ((rc = kge_run_l1h_grad(g.bf16, false, b.Q32, b.W32, b.T, b.S, b.A, b.P, g.Np, b.rowinfo, g.B, g.N, g.Np, g.Bp, g.dp,
+                                   cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_t, b.acct, nullptr, st)) != KGE_OK) return rc;
+    } else if (have_block && g.l1) {
         // gradient rows of the queries and of the shared negatives from S and the finished row constants
         if ((rc = kge_run_l1_grad(g.bf16, true, b.Q32, b.T, b.S, g.Np, b.rowinfo, g.B, g.N, g.Bp, g.Np, g.dp, cfg->loss, cfg->gamma,
                                   cfg->adv_temp, g.nsplit_q, b.accq, st)) != KGE_OK) return rc;

@@ -203,6 +203,192 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             l1_f32x4{acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
 }
 
+// ---------------------------------------------------------------------------------------------
+// TransH under the 1-norm (Table 2, p = 1): x_j = q'_j - t_j + A w^_j with q' = h_perp + r, A = w^ . t, and
+//   f = -sum_j |x_j|,  u_j = sign(x_j),  P = u . w^
+//   df/dq'_j = -u_j,   df/dt_j = u_j - P w^_j,   df/dw^_j = -(P t_j + A u_j)
+// The hyperplane term sits inside the absolute values, so the score kernel walks the dimensions twice (first A,
+// then the distance and P) and leaves A and P beside S for the two gradient kernels.  Queries and unit normals are
+// unrounded fp32 rows.  Same tiling as above with 64 own rows per gradient workgroup (a 4 x 4 register tile; the
+// pass over the queries carries two accumulators, dq' and dw^).
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void l1h_score_kernel(const float *Q, const float *W, const void *T, int B, int N, int dp,
+                                                        float *S, float *A, float *P, int64_t ldS) {
+    __shared__ __attribute__((aligned(16))) float qs[L1_TILE * L1_PITCH], ws[L1_TILE * L1_PITCH], ts[L1_TILE * L1_PITCH];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int n0 = blockIdx.x * L1_TILE, b0 = blockIdx.y * L1_TILE;
+    float a[4][4], acc[4][4], pp[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        for (int k = 0; k < 4; ++k) a[i][k] = acc[i][k] = pp[i][k] = 0.f;
+    for (int j0 = 0; j0 < dp; j0 += L1_TILE) {
+        __syncthreads();
+        l1_stage<false>(W, dp, b0, j0, ws);
+        l1_stage<BF16>(T, dp, n0, j0, ts);
+        __syncthreads();
+#pragma unroll 4
+        for (int jq = 0; jq < 16; ++jq) {
+            l1_f32x4 w4[4], t4[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                w4[i] = *(const l1_f32x4 *)(ws + (4 * ty + i) * L1_PITCH + 4 * jq);
+                t4[i] = *(const l1_f32x4 *)(ts + (tx + 16 * i) * L1_PITCH + 4 * jq);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) a[i][k] = fmaf(w4[i][c], t4[k][c], a[i][k]);
+        }
+    }
+    for (int j0 = 0; j0 < dp; j0 += L1_TILE) {
+        __syncthreads();
+        l1_stage<false>(Q, dp, b0, j0, qs);
+        l1_stage<false>(W, dp, b0, j0, ws);
+        l1_stage<BF16>(T, dp, n0, j0, ts);
+        __syncthreads();
+#pragma unroll 2
+        for (int jq = 0; jq < 16; ++jq) {
+            l1_f32x4 q4[4], w4[4], t4[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                q4[i] = *(const l1_f32x4 *)(qs + (4 * ty + i) * L1_PITCH + 4 * jq);
+                w4[i] = *(const l1_f32x4 *)(ws + (4 * ty + i) * L1_PITCH + 4 * jq);
+                t4[i] = *(const l1_f32x4 *)(ts + (tx + 16 * i) * L1_PITCH + 4 * jq);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = fmaf(a[i][k], w4[i][c], q4[i][c] - t4[k][c]);
+                        acc[i][k] += fabsf(x);
+                        pp[i][k] = fmaf(__builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f), w4[i][c], pp[i][k]);
+                    }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int b = b0 + 4 * ty + i;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int n = n0 + tx + 16 * k;
+            if (b < B && n < N) {
+                S[(int64_t)b * ldS + n] = -acc[i][k];
+                if (A) { A[(int64_t)b * ldS + n] = a[i][k]; P[(int64_t)b * ldS + n] = pp[i][k]; }
+            }
+        }
+    }
+}
+
+constexpr int L1H_GO = 64;             // own rows of a TransH gradient workgroup
+
+// OWN_Q: own = 64 queries (q' and w^), streamed = negatives: acc_part = dq' = -sum_n w u,
+//        acc_part2 = dw^ = -sum_n (w P) t_n + (w A) u.
+// else:  own = 64 negatives, streamed = queries: acc_part = dt = sum_b w u - (w P) w^_b.
+// u = sign(x) = median(-1, x 2^100, 1) (a non-zero x of magnitude at least 2^-100 scales to at least 1).
+template <bool BF16, bool OWN_Q>
+__global__ __launch_bounds__(256) void l1h_grad_kernel(const float *Q, const float *W, const void *T, const float *S,
+                                                       const float *A, const float *P, int64_t ldS, const KgeRowInfo *rowinfo,
+                                                       int B, int N, int own_pad, int dp, int chunks, int cps, int loss,
+                                                       float gamma, float adv_temp, float *acc_part, float *acc_part2) {
+    __shared__ __attribute__((aligned(16))) float s1[L1_GS * L1_PITCH], s2[L1_GS * L1_PITCH];
+    __shared__ __attribute__((aligned(16))) float cw[L1_GS * L1_PITCH], ca[L1_GS * L1_PITCH], cp[L1_GS * L1_PITCH];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int o0 = blockIdx.x * L1H_GO, j0 = blockIdx.y * L1_GD, split = blockIdx.z;
+    const float xscale = (loss == KGE_LOGSIGMOID ? adv_temp : 1.f) * L1_LOG2E;
+    float o1[4][4], o2[4][4], acc1[4][4], acc2[4][4];      // own rows: (q', w^) or (t, -)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int64_t off = (int64_t)(o0 + 4 * ty + i) * dp + j0 + 4 * tx + c;
+            o1[i][c] = OWN_Q ? Q[off] : El<BF16>::ld(T, off);
+            o2[i][c] = OWN_Q ? W[off] : 0.f;
+            acc1[i][c] = acc2[i][c] = 0.f;
+        }
+    const int c_lo = split * cps, c_hi = min(chunks, (split + 1) * cps);
+    for (int ch = c_lo; ch < c_hi; ++ch) {
+        const int s0 = ch * L1_GS;
+        __syncthreads();                                    // everyone is done with the previous chunk
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int e = threadIdx.x + 256 * k, row = e >> 4, cq = e & 15;
+            const int64_t off = (int64_t)(s0 + row) * dp + j0 + 4 * cq;
+            if constexpr (OWN_Q) {
+                l1_f32x4 v;
+                if constexpr (BF16) {
+                    const uint2 raw = *(const uint2 *)((const __bf16 *)T + off);
+                    v = l1_f32x4{__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                                 __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u)};
+                } else {
+                    v = *(const l1_f32x4 *)((const float *)T + off);
+                }
+                *(l1_f32x4 *)(s1 + row * L1_PITCH + 4 * cq) = v;
+            } else {
+                *(l1_f32x4 *)(s1 + row * L1_PITCH + 4 * cq) = *(const l1_f32x4 *)(Q + off);
+                *(l1_f32x4 *)(s2 + row * L1_PITCH + 4 * cq) = *(const l1_f32x4 *)(W + off);
+            }
+        }
+#pragma unroll 4
+        for (int k = 0; k < 8; ++k) {
+            const int e = threadIdx.x + 256 * k;
+            // consecutive threads take consecutive negatives: the reads of S, A and P are coalesced either way
+            const int ol = OWN_Q ? e >> 5 : e & 63, sl = OWN_Q ? e & 31 : e >> 6;
+            const int b = OWN_Q ? o0 + ol : s0 + sl, n = OWN_Q ? s0 + sl : o0 + ol;
+            float w = 0.f, av = 0.f, pv = 0.f;
+            if (b < B && n < N) {
+                const float sc = S[(int64_t)b * ldS + n];
+                w = __builtin_amdgcn_exp2f(fmaf(sc, xscale, rowinfo[b].K));
+                if (loss == KGE_LOGSIGMOID) w *= l1_sigmoid(gamma + sc);
+                av = A[(int64_t)b * ldS + n];
+                pv = w * P[(int64_t)b * ldS + n];
+            }
+            cw[sl * L1_PITCH + ol] = w; ca[sl * L1_PITCH + ol] = av; cp[sl * L1_PITCH + ol] = pv;
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int sl = 0; sl < L1_GS; ++sl) {
+            const l1_f32x4 w4 = *(const l1_f32x4 *)(cw + sl * L1_PITCH + 4 * ty);
+            const l1_f32x4 a4 = *(const l1_f32x4 *)(ca + sl * L1_PITCH + 4 * ty);
+            const l1_f32x4 p4 = *(const l1_f32x4 *)(cp + sl * L1_PITCH + 4 * ty);
+            const l1_f32x4 r1 = *(const l1_f32x4 *)(s1 + sl * L1_PITCH + 4 * tx);
+            if constexpr (OWN_Q) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float wa = w4[i] * a4[i];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = fmaf(a4[i], o2[i][c], o1[i][c] - r1[c]);
+                        const float u = __builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f);
+                        acc1[i][c] = fmaf(-w4[i], u, acc1[i][c]);
+                        acc2[i][c] = fmaf(-p4[i], r1[c], fmaf(-wa, u, acc2[i][c]));
+                    }
+                }
+            } else {
+                const l1_f32x4 r2 = *(const l1_f32x4 *)(s2 + sl * L1_PITCH + 4 * tx);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = fmaf(a4[i], r2[c], r1[c] - o1[i][c]);
+                        const float u = __builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f);
+                        acc1[i][c] = fmaf(w4[i], u, fmaf(-p4[i], r2[c], acc1[i][c]));
+                    }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t off = ((int64_t)split * own_pad + o0 + 4 * ty + i) * dp + j0 + 4 * tx;
+        *(l1_f32x4 *)(acc_part + off) = l1_f32x4{acc1[i][0], acc1[i][1], acc1[i][2], acc1[i][3]};
+        if constexpr (OWN_Q) *(l1_f32x4 *)(acc_part2 + off) = l1_f32x4{acc2[i][0], acc2[i][1], acc2[i][2], acc2[i][3]};
+    }
+}
+
 }  // namespace
 
 int kge_run_l1_score(bool bf16, const float *Q, const void *T, int B, int N, int Bp, int Np, int dp, float *S, int64_t ldS,
@@ -225,8 +411,8 @@ int kge_run_l1_rowstat(const float *S, int64_t ldS, int B, int N, int Bp, int lo
 }
 
 // splits over the streamed rows: enough workgroups for about four per compute unit
-int kge_l1_nsplit(int own_pad, int str_pad, int dp) {
-    const int base = (own_pad / L1_GO) * (dp / L1_GD), chunks = str_pad / L1_GS;
+int kge_l1_nsplit(int own_pad, int str_pad, int dp, bool transh) {
+    const int base = (own_pad / (transh ? L1H_GO : L1_GO)) * (dp / L1_GD), chunks = str_pad / L1_GS;
     if (base == 0 || chunks == 0) return 0;
     int want = (1024 + base - 1) / base;
     if (want > chunks) want = chunks;
@@ -238,7 +424,7 @@ int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *s
                     const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp, int loss, float gamma,
                     float adv_temp, int nsplit, float *acc_part, hipStream_t st) {
     if (own_pad % L1_GO || str_pad % L1_GS || dp % L1_GD) return KGE_E_INVALID_ARG;
-    if (nsplit <= 0 || nsplit != kge_l1_nsplit(own_pad, str_pad, dp)) return KGE_E_INVALID_ARG;
+    if (nsplit <= 0 || nsplit != kge_l1_nsplit(own_pad, str_pad, dp, false)) return KGE_E_INVALID_ARG;
     KgeProfScope prof(own_is_query ? KGE_PROF_BLOCK_FWD : KGE_PROF_BLOCK_GRADT, st);
     const int chunks = str_pad / L1_GS, cps = (chunks + nsplit - 1) / nsplit;
     const dim3 grid(own_pad / L1_GO, dp / L1_GD, nsplit);
@@ -247,5 +433,35 @@ int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *s
     if (bf16) { if (own_is_query) L1_GRAD(true, true); else L1_GRAD(true, false); }
     else      { if (own_is_query) L1_GRAD(false, true); else L1_GRAD(false, false); }
 #undef L1_GRAD
+    return kge_launch_status();
+}
+
+// TransH: scores (and, with A and P given, the two per-pair scalars that the gradient kernels need)
+int kge_run_l1h_score(bool bf16, const float *Q, const float *W, const void *T, int B, int N, int Bp, int Np, int dp, float *S,
+                      float *A, float *P, int64_t ldS, hipStream_t st) {
+    if (Bp % L1_TILE || Np % L1_TILE || dp % L1_TILE || (A == nullptr) != (P == nullptr)) return KGE_E_INVALID_ARG;
+    if (Bp == 0 || Np == 0) return KGE_OK;
+    if (Bp / L1_TILE > 65535) return KGE_E_UNSUPPORTED;
+    KgeProfScope prof(KGE_PROF_BLOCK_SCORE, st);
+    const dim3 grid(Np / L1_TILE, Bp / L1_TILE);
+    if (bf16) hipLaunchKernelGGL(l1h_score_kernel<true>, grid, dim3(256), 0, st, Q, W, T, B, N, dp, S, A, P, ldS);
+    else      hipLaunchKernelGGL(l1h_score_kernel<false>, grid, dim3(256), 0, st, Q, W, T, B, N, dp, S, A, P, ldS);
+    return kge_launch_status();
+}
+
+int kge_run_l1h_grad(bool bf16, bool own_is_query, const float *Q, const float *W, const void *T, const float *S, const float *A,
+                     const float *P, int64_t ldS, const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp,
+                     int loss, float gamma, float adv_temp, int nsplit, float *acc_part, float *acc_part2, hipStream_t st) {
+    if (own_pad % L1H_GO || str_pad % L1_GS || dp % L1_GD) return KGE_E_INVALID_ARG;
+    if (nsplit <= 0 || nsplit != kge_l1_nsplit(own_pad, str_pad, dp, true)) return KGE_E_INVALID_ARG;
+    KgeProfScope prof(own_is_query ? KGE_PROF_BLOCK_FWD : KGE_PROF_BLOCK_GRADT, st);
+    const int chunks = str_pad / L1_GS, cps = (chunks + nsplit - 1) / nsplit;
+    const dim3 grid(own_pad / L1H_GO, dp / L1_GD, nsplit);
+    if (grid.z > 65535 || grid.y > 65535) return KGE_E_UNSUPPORTED;
+#define L1H_GRAD(BF, OQ) hipLaunchKernelGGL((l1h_grad_kernel<BF, OQ>), grid, dim3(256), 0, st, Q, W, T, S, A, P, ldS, rowinfo, B, N, \
+                                            own_pad, dp, chunks, cps, loss, gamma, adv_temp, acc_part, acc_part2)
+    if (bf16) { if (own_is_query) L1H_GRAD(true, true); else L1H_GRAD(true, false); }
+    else      { if (own_is_query) L1H_GRAD(false, true); else L1H_GRAD(false, false); }
+#undef L1H_GRAD
     return kge_launch_status();
 }

@@ -13,7 +13,7 @@ struct KgeModelDev {
 int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, int64_t hi, int64_t n,
                       int32_t *out, hipStream_t st);
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
-                   int dp, void *Q, void *W, void *Q2, float *Q32, KgeRowInfo *rowinfo, float *pos_ws,
+                   int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                    float *pos_out, hipStream_t st);
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
                     hipStream_t st);
@@ -40,7 +40,14 @@ int kge_run_l1_score(bool bf16, const float *Q, const void *T, int B, int N, int
                      hipStream_t st);
 int kge_run_l1_rowstat(const float *S, int64_t ldS, int B, int N, int Bp, int loss, float gamma, float adv_temp,
                        float4 *stat, hipStream_t st);
-int kge_l1_nsplit(int own_pad, int str_pad, int dp);
+int kge_l1_nsplit(int own_pad, int str_pad, int dp, bool transh);
 int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *str, const float *S, int64_t ldS,
                     const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp, int loss, float gamma,
                     float adv_temp, int nsplit, float *acc_part, hipStream_t st);
+// TransH under the 1-norm: Q, W = unrounded queries q' and unit normals [Bp][dp]; A = w^ . t and P = sign(x) . w^ per
+// pair beside S (both nullptr: scores only); the pass over the queries also fills acc_part2 with the gradient of w^
+int kge_run_l1h_score(bool bf16, const float *Q, const float *W, const void *T, int B, int N, int Bp, int Np, int dp, float *S,
+                      float *A, float *P, int64_t ldS, hipStream_t st);
+int kge_run_l1h_grad(bool bf16, bool own_is_query, const float *Q, const float *W, const void *T, const float *S, const float *A,
+                     const float *P, int64_t ldS, const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp,
+                     int loss, float gamma, float adv_temp, int nsplit, float *acc_part, float *acc_part2, hipStream_t st);

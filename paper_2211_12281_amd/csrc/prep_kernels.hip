@@ -44,8 +44,8 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 // ---------------------------------------------------------------------------------------------
 template <bool BF16, int SC>
 __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t,
-                                  int B, int Bp, int dp, void *Q, void *W, void *Q2, float *Q32, KgeRowInfo *rowinfo,
-                                  float *pos_ws, float *pos_out) {
+                                  int B, int Bp, int dp, void *Q, void *W, void *Q2, float *Q32, float *W32,
+                                  KgeRowInfo *rowinfo, float *pos_ws, float *pos_out) {
     const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (b >= Bp) return;
@@ -55,6 +55,7 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
             if (W) El<BF16>::st(W, (int64_t)b * dp + j, 0.f);
             if (Q2) El<BF16>::st(Q2, (int64_t)b * dp + j, 0.f);
             if (Q32) Q32[(int64_t)b * dp + j] = 0.f;
+            if (W32) W32[(int64_t)b * dp + j] = 0.f;
         }
         if (lane == 0) { rowinfo[b] = KgeRowInfo{0.f, 0.f, 0.f, 0.f}; if (pos_ws) pos_ws[b] = 0.f; }
         return;
@@ -76,7 +77,8 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
         if (j < dp) {
             El<BF16>::st(Q, (int64_t)b * dp + j, cx.q[k]);
             if (W) El<BF16>::st(W, (int64_t)b * dp + j, cx.w[k]);
-            if (Q32) Q32[(int64_t)b * dp + j] = cx.q[k];      // unrounded copy for the 1-norm kernels
+            if (Q32) Q32[(int64_t)b * dp + j] = cx.q[k];      // unrounded copies for the 1-norm kernels
+            if (W32) W32[(int64_t)b * dp + j] = cx.w[k];
         }
     }
     qn = kge_wave_sum(qn);
@@ -325,23 +327,25 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
         d2 = kge_wave_sum(d2);
         const float dist = sqrtf(d2);
         const float ap = dist > 0.f ? -gp / dist : 0.f;            // gp * df/du = ap * u
+        // positive triple: gp * df/du_k, df/du = -u / ||u||_2, or -sign(u) for the 1-norm
+        auto pos_term = [&](int k) { return m.p1 ? (u[k] > 0.f ? -gp : (u[k] < 0.f ? gp : 0.f)) : ap * u[k]; };
         float aw = 0.f, cq = 0.f;
         if (SC == KGE_TRANSH) {
 #pragma unroll
-            for (int k = 0; k < KGE_MAXJ; ++k) { aw += ap * u[k] * cx.w[k]; cq += cx.w[k] * cx.q[k]; }
+            for (int k = 0; k < KGE_MAXJ; ++k) { aw += pos_term(k) * cx.w[k]; cq += cx.w[k] * cx.q[k]; }
             aw = kge_wave_sum(aw); cq = kge_wave_sum(cq);
         }
 #pragma unroll
         for (int k = 0; k < KGE_MAXJ; ++k) {
-            // positive triple: gp * df/du_k, df/du = -u / ||u||_2, or -sign(u) for the 1-norm
-            const float apu = m.p1 ? (u[k] > 0.f ? -gp : (u[k] < 0.f ? gp : 0.f)) : ap * u[k];
+            const float apu = pos_term(k);
             dq[k] = a1[k] - s1 * cx.q[k] + apu;
             dtp[k] = -apu;
             if (SC == KGE_TRANSH) {
                 dq[k] -= s2 * cx.w[k];
                 dtp[k] = -(apu - aw * cx.w[k]);
                 // gradient with respect to the unit normal: negatives' part + positive's part
-                dwh[k] = -cq * a1[k] - s2 * cx.q[k] + a2[k] - s3 * cx.w[k] + aw * tv[k] + wt * apu;
+                // (1-norm: a2 is the finished negatives' part, the sums s1..s3 are zero)
+                dwh[k] = (m.p1 ? 0.f : -cq * a1[k]) - s2 * cx.q[k] + a2[k] - s3 * cx.w[k] + aw * tv[k] + wt * apu;
             }
         }
     }
@@ -499,12 +503,12 @@ __global__ void kge_zero_rows_kernel(float *p, int64_t count) {
 // host launchers
 // ---------------------------------------------------------------------------------------------
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
-                   int dp, void *Q, void *W, void *Q2, float *Q32, KgeRowInfo *rowinfo, float *pos_ws,
+                   int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                    float *pos_out, hipStream_t st) {
     const int grid = (Bp + 3) / 4;
     if (grid == 0) return KGE_OK;
 #define KGE_QBUILD(BF, SC) hipLaunchKernelGGL((kge_qbuild_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, \
-                                              rowinfo, pos_ws, pos_out)
+                                              W32, rowinfo, pos_ws, pos_out)
 #define KGE_QBUILD_SC(BF)                                  \
     switch (m.scorer) {                                    \
     case KGE_TRANSE: KGE_QBUILD(BF, KGE_TRANSE); break;    \
