@@ -36,13 +36,26 @@ namespace {
 constexpr int PP_RB = 512, PP_DP = 256, PP_KS = 16, PP_NB = 8, PP_ST = 32;
 constexpr int PP_X_BYTES = PP_ST * PP_RB;                   // 16 KB: [32 rows][512 bytes], chunk c of row r at c ^ (r & 7)
 constexpr int PP_STAGE = PP_X_BYTES;
-constexpr int PP_NSTAGE = 4;
-constexpr int PP_SIDE_SLOTS = 5;                            // side information of a tile's 32 stream rows, one copy per A wave
+#ifndef PP_AHEAD
+#define PP_AHEAD 2
+#endif
+constexpr int PP_NSTAGE = PP_AHEAD + 3;                      // tiles t - 2 (wave B) .. t + PP_AHEAD (requested)
+#ifndef PP_VALU_PER_MFMA
+#define PP_VALU_PER_MFMA 8
+#endif
+constexpr int PP_SIDE_SLOTS = PP_AHEAD + 3;                            // side information of a tile's 32 stream rows, one copy per A wave
 constexpr int PP_XCH = 2048 + 256;                          // coefficients (64 lanes x 32 bytes) + rescaling factors (64 x 4 bytes)
 constexpr int pp_lds(int mode) { return PP_NSTAGE * PP_STAGE + PP_SIDE_SLOTS * 4 * (mode == KGE_MODE_FWD ? 256 : 1024) + 4 * 2 * PP_XCH; }
 constexpr int PP_LPW_A = 3, PP_LPW_B = 2;                   // asynchronous copies per tile of an A / B wave
 __device__ __forceinline__ int pp_pi(int m) { return (m & ~7) | ((m & 3) << 1) | ((m >> 2) & 1); }
 typedef short pp_i16x4 __attribute__((ext_vector_type(4)));
+// max over a lane and its partner lane ^ 32 without the LDS crossbar (whose counter would make the caller wait for every
+// fragment read in flight): v_permlane32_swap exchanges the upper half of one register with the lower half of another
+__device__ __forceinline__ float pp_max_halves(float v) {
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 static_assert(pp_lds(KGE_MODE_GRADT) <= 160 * 1024, "LDS budget");
 
 // MODE_FWD: own = queries, stream = negatives (statistics of the loss + gradient of the queries);
@@ -112,142 +125,183 @@ void kge_pp_kernel(const KgeBlockArgs a) {
             frag_off[b] = R * PP_RB + 16 * (((2 * b) ^ (R & 6)) | (g ^ (R & 1)));
         }
         const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
-        if (work) { issue(t0, 0); issue(t0 + 1, 1); }
+        if (work) {
+#pragma unroll
+            for (int u = 0; u < PP_AHEAD; ++u) issue(t0 + u, u);
+        }
         // the own operand must have arrived before the loop (a wait inside it would drain the ring)
 #pragma unroll
         for (int ks = 0; ks < PP_KS; ++ks) asm volatile("" : "+v"(own[ks].x), "+v"(own[ks].y), "+v"(own[ks].z), "+v"(own[ks].w));
         asm volatile("" : "+v"(o_qn));
-        if (work) {
-            for (int t = t0; t <= t1; ++t) {
-                kge_wait_vmcnt<PP_LPW_A>();                 // tile t has landed (this wave's part); tile t + 1 may be in flight
-                __syncthreads();
-                issue(t + 2, t - t0 + 2);
-                if (t == t1) break;                         // the last round belongs to the B waves
-                const int slot = t - t0;
-                const char *stage = lds + (slot % PP_NSTAGE) * PP_STAGE;
-                const char *side = side_ring + (slot % PP_SIDE_SLOTS) * SIDE_SLOT + pair * SIDE_WAVE;
-                kge_f32x16 acc;
+        // register i holds row 8 (i / 4) + 4 g + i % 4 of the contraction = stream row pi(.) of the tile
+        int srow[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        for (int i = 0; i < 16; ++i) srow[i] = pp_pi(8 * (i >> 2) + 4 * g + (i & 3));
+        float sv[16], dv[16], x2[16];
+        float rsc = 1.f;
+        // first half of the epilogue of tile t: scores (distance scorers: by the norm expansion, entries where it
+        // cancels are redone by direct differences), then the exponents x2 of the weights - FWD: relative to the
+        // row's running reference st_m, which a tile that exceeds it by more than KGE_TAU raises (rare: what the row
+        // has accumulated is rescaled, here and in wave B); GRADT: from the finished row constants of the queries
+        // side values of a tile's 32 stream rows (squared norms; GRADT: the row constants K), read BEFORE the next
+        // tile's fragments so that waiting for them does not wait for the fragments
+        float side_n[16], side_k[16];
+        auto load_side = [&](int slot) {
+            const char *side = side_ring + (slot % PP_SIDE_SLOTS) * SIDE_SLOT + pair * SIDE_WAVE;
 #pragma unroll
-                for (int c0 = 0; c0 < PP_KS; c0 += 8) {
-                    uint4 av[8];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) av[k] = *(const uint4 *)(stage + frag_off[(c0 + k) & 3] + 128 * ((c0 + k) >> 2));
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) acc = kge_mma16<true>(acc, av[k], own[c0 + k]);
-                }
-                // register i holds row 8 (i / 4) + 4 g + i % 4 of the contraction = stream row pi(.) of the tile
-                int srow[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) srow[i] = pp_pi(8 * (i >> 2) + 4 * g + (i & 3));
-                float sv[16], dv[16];
-                if constexpr (KIND == KGE_KIND_MULT) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) { sv[i] = acc[i]; dv[i] = 0.f; }
-                } else {
-                    // squared distance by the norm expansion; entries where it cancels are redone by direct differences
-                    float d2[16], thr[16];
-                    bool cancel = false;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float tnv = FWD ? *(const float *)(side + srow[i] * 4) : *(const float *)(side + srow[i] * 16);   // |t|^2 or |q|^2
-                        d2[i] = fmaf(-2.f, acc[i], o_qn + tnv);
-                        thr[i] = 1e-3f * (o_qn + tnv);
-                        cancel = cancel || d2[i] < thr[i];
-                    }
-                    if (__any(cancel)) {
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            if (d2[i] < thr[i]) {
-                                const int sidx = t * PP_ST + srow[i];
-                                d2[i] = kge_direct_d2<true, false>((const char *)a.own + (size_t)oidx * PP_RB,
-                                                                   (const char *)a.str + (size_t)sidx * PP_RB, nullptr, PP_DP);
-                            }
-                            asm volatile("" ::: "memory");  // keeps the branch from being turned into selects
-                        }
-                    }
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float dd = fmaxf(d2[i], 0.f);
-                        const float inv = dd > 0.f ? __builtin_amdgcn_rsqf(dd) : 0.f;
-                        dv[i] = inv;
-                        sv[i] = -dd * inv;
-                    }
-                }
-                float coef[16];
-                float rsc = 1.f;
-                if constexpr (FWD) {
-                    // exponents of the weights relative to the row's reference st_m (log2 domain); padding entries -> -inf
-                    float x2[16];
-                    const float m_neg = st_m > -INFINITY ? -st_m : 0.f;
-    #pragma unroll
-                    for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
-                    if (t * PP_ST + PP_ST > str_limit) {
-    #pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            if (t * PP_ST + srow[i] >= str_limit) x2[i] = -INFINITY;
-                    }
-                    float tm = -INFINITY;
-    #pragma unroll
-                    for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
-                    tm = fmaxf(tm, __shfl_xor(tm, 32));         // both lanes of an own row share the reference
-                    // the reference is only raised (and what the row has accumulated rescaled, here and in wave B) when
-                    // the tile's maximum exceeds it by more than KGE_TAU
-                    const bool have = st_m > -INFINITY;
-                    const bool trip = tm > (have ? KGE_TAU : -INFINITY);
-                    if (__any(trip)) {
-                        const float m_new = trip ? (have ? tm + st_m : tm) : st_m;
-                        const float shift = trip ? -tm : 0.f;
-                        rsc = trip ? (have ? kge_exp2(-tm) : 0.f) : 1.f;
-                        st_m = m_new;
-                        st_l *= rsc; st_acc *= rsc; sum1 *= rsc;
-    #pragma unroll
-                        for (int i = 0; i < 16; ++i) x2[i] += shift;
-                    }
-    #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float e = kge_exp2(x2[i]);
-                        st_l += e;
-                        float u = e;
-                        if constexpr (LOSS == KGE_LOGSIGMOID) {
-                            const float y = a.gamma + sv[i];
-                            const float tt = kge_exp2(-fabsf(y) * KGE_LOG2E);
-                            const float rcp = __builtin_amdgcn_rcpf(1.f + tt);
-                            const float sig = y >= 0.f ? rcp : tt * rcp;
-                            const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + tt);
-                            if (e > 0.f) st_acc = fmaf(e, softplus, st_acc);
-                            u = e * sig;
-                        }
-                        const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
-                        coef[i] = c1;
-                        if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
-                    }
-                } else {
-                    // gradient coefficient of every (query, negative) pair from the finished row constants of the queries
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float K2 = *(const float *)(side + srow[i] * 16 + 8);      // -inf for padded queries
-                        float u = kge_exp2(fmaf(sv[i], xscale, K2));
-                        if constexpr (LOSS == KGE_LOGSIGMOID) {
-                            const float y = a.gamma + sv[i];
-                            const float tt = kge_exp2(-fabsf(y) * KGE_LOG2E);
-                            const float rcp = __builtin_amdgcn_rcpf(1.f + tt);
-                            u *= y >= 0.f ? rcp : tt * rcp;
-                        }
-                        const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
-                        coef[i] = c1;
-                        if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
-                    }
-                }
-                char *x = xch_base + (pair * 2 + (slot & 1)) * PP_XCH;
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2)
-                    *(uint4 *)(x + s2 * 1024 + lane * 16) =
-                        make_uint4(kge_pack_bf16x2(coef[8 * s2 + 0], coef[8 * s2 + 1]), kge_pack_bf16x2(coef[8 * s2 + 2], coef[8 * s2 + 3]),
-                                   kge_pack_bf16x2(coef[8 * s2 + 4], coef[8 * s2 + 5]), kge_pack_bf16x2(coef[8 * s2 + 6], coef[8 * s2 + 7]));
-                *(float *)(x + 2048 + lane * 4) = rsc;
+            for (int i = 0; i < 16; ++i) {
+                if constexpr (KIND == KGE_KIND_DIST) side_n[i] = FWD ? *(const float *)(side + srow[i] * 4) : *(const float *)(side + srow[i] * 16);
+                if constexpr (!FWD) side_k[i] = *(const float *)(side + srow[i] * 16 + 8);      // -inf for padded queries
             }
+        };
+        auto epi1 = [&](int t, const kge_f32x16 &acc) {
+            if constexpr (KIND == KGE_KIND_MULT) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { sv[i] = acc[i]; dv[i] = 0.f; }
+            } else {
+                float d2[16], thr[16];
+                bool cancel = false;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float tnv = side_n[i];                // |t|^2 or |q|^2
+                    d2[i] = fmaf(-2.f, acc[i], o_qn + tnv);
+                    thr[i] = 1e-3f * (o_qn + tnv);
+                    cancel = cancel || d2[i] < thr[i];
+                }
+                if (__any(cancel)) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        if (d2[i] < thr[i]) {
+                            const int sidx = t * PP_ST + srow[i];
+                            d2[i] = kge_direct_d2<true, false>((const char *)a.own + (size_t)oidx * PP_RB,
+                                                               (const char *)a.str + (size_t)sidx * PP_RB, nullptr, PP_DP);
+                        }
+                        asm volatile("" ::: "memory");  // keeps the branch from being turned into selects
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float dd = fmaxf(d2[i], 0.f);
+                    const float inv = dd > 0.f ? __builtin_amdgcn_rsqf(dd) : 0.f;
+                    dv[i] = inv;
+                    sv[i] = -dd * inv;
+                }
+            }
+            rsc = 1.f;
+            if constexpr (FWD) {
+                const float m_neg = st_m > -INFINITY ? -st_m : 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, m_neg);
+                if (t * PP_ST + PP_ST > str_limit) {            // padding entries -> -inf
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (t * PP_ST + srow[i] >= str_limit) x2[i] = -INFINITY;
+                    asm volatile("" ::: "memory");              // a rarely taken branch, not sixteen selects per tile
+                }
+                float tm = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) tm = fmaxf(tm, x2[i]);
+                tm = pp_max_halves(tm);                          // both lanes of an own row share the reference
+                const bool have = st_m > -INFINITY;
+                const bool trip = tm > (have ? KGE_TAU : -INFINITY);
+                if (__any(trip)) {
+                    const float m_new = trip ? (have ? tm + st_m : tm) : st_m;
+                    const float shift = trip ? -tm : 0.f;
+                    rsc = trip ? (have ? kge_exp2(-tm) : 0.f) : 1.f;
+                    st_m = m_new;
+                    st_l *= rsc; st_acc *= rsc; sum1 *= rsc;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) x2[i] += shift;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x2[i] = fmaf(sv[i], xscale, side_k[i]);
+            }
+        };
+        // second half: weights, loss sums, coefficients -> LDS (straight-line vector work: it runs under the
+        // contraction of the NEXT tile, which the caller issues in the same block)
+        auto epi2 = [&](int slot) {
+            float coef[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float e = kge_exp2(x2[i]);
+                float u = e;
+                if constexpr (FWD) st_l += e;
+                if constexpr (LOSS == KGE_LOGSIGMOID) {
+                    const float y = a.gamma + sv[i];
+                    const float tt = kge_exp2(-fabsf(y) * KGE_LOG2E);
+                    const float rcp = __builtin_amdgcn_rcpf(1.f + tt);
+                    const float sig = y >= 0.f ? rcp : tt * rcp;
+                    if constexpr (FWD) {
+                        const float softplus = fmaxf(y, 0.f) + KGE_LN2 * kge_log2(1.f + tt);
+                        if (e > 0.f) st_acc = fmaf(e, softplus, st_acc);
+                    }
+                    u = e * sig;
+                }
+                const float c1 = KIND == KGE_KIND_DIST ? u * dv[i] : u;
+                coef[i] = c1;
+                if constexpr (KIND == KGE_KIND_DIST) sum1 += c1;
+            }
+            char *x = xch_base + (pair * 2 + (slot & 1)) * PP_XCH;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+                *(uint4 *)(x + s2 * 1024 + lane * 16) =
+                    make_uint4(kge_pack_bf16x2(coef[8 * s2 + 0], coef[8 * s2 + 1]), kge_pack_bf16x2(coef[8 * s2 + 2], coef[8 * s2 + 3]),
+                               kge_pack_bf16x2(coef[8 * s2 + 4], coef[8 * s2 + 5]), kge_pack_bf16x2(coef[8 * s2 + 6], coef[8 * s2 + 7]));
+            *(float *)(x + 2048 + lane * 4) = rsc;
+        };
+        // the sixteen fragments of a tile are requested together, right after the barrier
+        auto load_tile = [&](int slot, uint4 (&av)[PP_KS]) {
+            const char *stage = lds + (slot % PP_NSTAGE) * PP_STAGE;
+#pragma unroll
+            for (int k = 0; k < PP_KS; ++k) av[k] = *(const uint4 *)(stage + frag_off[k & 3] + 128 * (k >> 2));
+        };
+        auto mma_tile = [&](const uint4 (&av)[PP_KS], kge_f32x16 &acc) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+            for (int k = 0; k < PP_KS; ++k) acc = kge_mma16<true>(acc, av[k], own[k]);
+        };
+        // The wave is one tile ahead with its contraction: round t issues the MFMAs of tile t and, while they run,
+        // finishes the epilogue of tile t - 1 (whose coefficients wave B picks up in round t + 1).
+        if (work) {
+            kge_f32x16 accp;
+            kge_wait_vmcnt<(PP_AHEAD - 1) * PP_LPW_A>();                     // tile t0 has landed (this wave's part); tile t0 + 1 may be in flight
+            __syncthreads();
+            issue(t0 + PP_AHEAD, PP_AHEAD);
+            {
+                uint4 av[PP_KS];
+                load_tile(0, av);
+                mma_tile(av, accp);
+            }
+            for (int t = t0 + 1; t < t1; ++t) {
+                kge_wait_vmcnt<(PP_AHEAD - 1) * PP_LPW_A>();
+                __syncthreads();
+                issue(t + PP_AHEAD, t - t0 + PP_AHEAD);
+                uint4 av[PP_KS];
+                load_side(t - 1 - t0);
+                load_tile(t - t0, av);
+                epi1(t - 1, accp);
+                kge_f32x16 acc;
+                mma_tile(av, acc);
+                epi2(t - 1 - t0);
+                // one MFMA, then a share of the epilogue's vector instructions, sixteen times
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, PP_VALU_PER_MFMA, 0);
+                }
+                accp = acc;
+            }
+            kge_wait_vmcnt<(PP_AHEAD - 1) * PP_LPW_A>();
+            __syncthreads();
+            issue(t1 + PP_AHEAD, t1 - t0 + PP_AHEAD);
+            load_side(t1 - 1 - t0);
+            epi1(t1 - 1, accp);
+            epi2(t1 - 1 - t0);
+            kge_wait_vmcnt<(PP_AHEAD - 1) * PP_LPW_A>();                     // the last round belongs to the B waves
+            __syncthreads();
+            issue(t1 + 1 + PP_AHEAD, t1 - t0 + 1 + PP_AHEAD);
             kge_wait_vmcnt<0>();                            // no copy may be in flight when the LDS is released
         }
         st_l += __shfl_xor(st_l, 32); st_acc += __shfl_xor(st_acc, 32); sum1 += __shfl_xor(sum1, 32);
@@ -272,13 +326,14 @@ void kge_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
         for (int blk = 0; blk < PP_NB; ++blk) tr_blk[blk] = (((blk * 4 + q16 * 2 + ((i16 & 3) >> 1)) ^ rx) * 16) + (i16 & 1) * 8;
         if (work) {
-            issue(t0, 0); issue(t0 + 1, 1);
-            for (int t = t0; t <= t1; ++t) {
-                kge_wait_vmcnt<PP_LPW_B>();
+#pragma unroll
+            for (int u = 0; u < PP_AHEAD; ++u) issue(t0 + u, u);
+            for (int t = t0; t <= t1 + 1; ++t) {
+                kge_wait_vmcnt<(PP_AHEAD - 1) * PP_LPW_B>();
                 __syncthreads();
-                issue(t + 2, t - t0 + 2);
-                if (t == t0) continue;                      // nothing to consume yet
-                const int slot = t - 1 - t0;
+                issue(t + PP_AHEAD, t - t0 + PP_AHEAD);
+                if (t < t0 + 2) continue;                   // nothing to consume yet: wave A hands tile t - 2 over in round t - 1
+                const int slot = t - 2 - t0;
                 const char *xs = lds + (slot % PP_NSTAGE) * PP_STAGE;
                 const char *x = xch_base + (pair * 2 + (slot & 1)) * PP_XCH;
                 uint4 bf[2];
@@ -292,26 +347,30 @@ void kge_pp_kernel(const KgeBlockArgs a) {
                         asm volatile("" ::: "memory");      // rarely executed: keep it out of the selects
                     }
                 }
+                // dimension block blk: two k-steps f, each operand two transpose reads hh (entries 4 hh .. + 3 of this lane
+                // half: rows 16 f + 8 hh + 2 kk + g = pi of the contraction rows 16 f + 8 hh + 4 g + kk).  The reads run two
+                // blocks ahead of the MFMAs; the scheduling barriers keep that order.
+                uint4 av2[PP_NB][2];
+                auto load_blk = [&](int blk) {
 #pragma unroll
-                for (int c0 = 0; c0 < PP_NB; c0 += 4) {
-                    uint4 av2[4][2];
+                    for (int f = 0; f < 2; ++f)
 #pragma unroll
-                    for (int bb = 0; bb < 4; ++bb)
+                        for (int hh = 0; hh < 2; ++hh) {
+                            const pp_i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                (pp_i16x4 __attribute__((address_space(3))) *)(xs + tr_off[f][hh] + tr_blk[blk]));
+                            const uint2 u = __builtin_bit_cast(uint2, v);
+                            if (hh == 0) { av2[blk][f].x = u.x; av2[blk][f].y = u.y; } else { av2[blk][f].z = u.x; av2[blk][f].w = u.y; }
+                        }
+                };
+                load_blk(0); load_blk(1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int f = 0; f < 2; ++f)
+                for (int blk = 0; blk < PP_NB; ++blk) {
+                    if (blk + 2 < PP_NB) load_blk(blk + 2);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                            for (int hh = 0; hh < 2; ++hh) {
-                                // k-step f, entries 4 hh .. + 3 of this lane half: rows 16 f + 8 hh + 2 kk + g (= pi of the
-                                // contraction rows 16 f + 8 hh + 4 g + kk); this lane is source i = lane % 16 of its group
-                                const pp_i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                    (pp_i16x4 __attribute__((address_space(3))) *)(xs + tr_off[f][hh] + tr_blk[c0 + bb]));
-                                const uint2 u = __builtin_bit_cast(uint2, v);
-                                if (hh == 0) { av2[bb][f].x = u.x; av2[bb][f].y = u.y; } else { av2[bb][f].z = u.x; av2[bb][f].w = u.y; }
-                            }
-#pragma unroll
-                    for (int bb = 0; bb < 4; ++bb)
-#pragma unroll
-                        for (int f = 0; f < 2; ++f) acc2[c0 + bb] = kge_mma16<true>(acc2[c0 + bb], av2[bb][f], bf[f]);
+                    for (int f = 0; f < 2; ++f) acc2[blk] = kge_mma16<true>(acc2[blk], av2[blk][f], bf[f]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             kge_wait_vmcnt<0>();
