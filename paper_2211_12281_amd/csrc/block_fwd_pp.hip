@@ -48,6 +48,11 @@ constexpr int PP_XCH = 2048 + 256;                          // coefficients (64 
 constexpr int pp_lds(int mode) { return PP_NSTAGE * PP_STAGE + PP_SIDE_SLOTS * 4 * (mode == KGE_MODE_FWD ? 256 : 1024) + 4 * 2 * PP_XCH; }
 constexpr int PP_LPW_A = 3, PP_LPW_B = 2;                   // asynchronous copies per tile of an A / B wave
 __device__ __forceinline__ int pp_pi(int m) { return (m & ~7) | ((m & 3) << 1) | ((m >> 2) & 1); }
+// 16-byte chunk c of tile row r sits at position c ^ pp_swz(r) of the row: a bit permutation of r % 16 whose upper two bits
+// are (r / 2) % 4.  Sixteen consecutive rows at one chunk index then fall into sixteen different bank groups (wave A's
+// fragment reads run at the LDS's full 256 bytes per clock instead of the 128 that an XOR with r % 8 gives), and so do
+// the four rows two apart x four chunks that one transpose read of wave B touches.
+__device__ __forceinline__ int pp_swz(int r) { return (((r >> 1) & 3) << 2) | (((r >> 3) & 1) << 1) | (r & 1); }
 typedef short pp_i16x4 __attribute__((ext_vector_type(4)));
 // max over a lane and its partner lane ^ 32 without the LDS crossbar (whose counter would make the caller wait for every
 // fragment read in flight): v_permlane32_swap exchanges the upper half of one register with the lower half of another
@@ -92,7 +97,7 @@ void kge_pp_kernel(const KgeBlockArgs a) {
     for (int jj = 0; jj < 2; ++jj) {
         const int byte = (wave * 2 + jj) * 1024 + lane * 16;
         const int r = byte / PP_RB, pos = (byte % PP_RB) / 16;
-        x_off[jj] = r * PP_RB + ((pos ^ (r & 7)) * 16);
+        x_off[jj] = r * PP_RB + ((pos ^ pp_swz(r)) * 16);
     }
     auto issue = [&](int tile, int slot) {
         tile = tile < t1 ? tile : t1 - 1;                   // past the end: a harmless repeat keeps vmcnt uniform
@@ -118,11 +123,11 @@ void kge_pp_kernel(const KgeBlockArgs a) {
         }
         float o_qn = FWD ? a.rowinfo[oidx].qn : a.tn[oidx];   // squared norm of the own row
         float sum1 = 0.f, st_m = -INFINITY, st_l = 0.f, st_acc = 0.f;
-        int frag_off[4];
+        int frag_off[8];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < 8; ++b) {
             const int R = pp_pi(lr);                        // row m of the contraction is stream row pi(m) of the tile
-            frag_off[b] = R * PP_RB + 16 * (((2 * b) ^ (R & 6)) | (g ^ (R & 1)));
+            frag_off[b] = R * PP_RB + 16 * ((2 * b + g) ^ pp_swz(R));    // chunk 2 ks + g of k-step ks = b (mod 8)
         }
         const float xscale = (LOSS == KGE_LOGSIGMOID ? a.adv_temp : 1.f) * KGE_LOG2E;
         if (work) {
@@ -254,7 +259,7 @@ void kge_pp_kernel(const KgeBlockArgs a) {
         auto load_tile = [&](int slot, uint4 (&av)[PP_KS]) {
             const char *stage = lds + (slot % PP_NSTAGE) * PP_STAGE;
 #pragma unroll
-            for (int k = 0; k < PP_KS; ++k) av[k] = *(const uint4 *)(stage + frag_off[k & 3] + 128 * (k >> 2));
+            for (int k = 0; k < PP_KS; ++k) av[k] = *(const uint4 *)(stage + frag_off[k & 7] + 256 * (k >> 3));
         };
         auto mma_tile = [&](const uint4 (&av)[PP_KS], kge_f32x16 &acc) {
 #pragma unroll
@@ -318,13 +323,16 @@ void kge_pp_kernel(const KgeBlockArgs a) {
         // transpose reads: this lane is source i16 of its group of 16 (dimension sub-block q16 of a 32-block, lane half g):
         // it points at row 16 f + 8 hh + rx of the tile, dimensions blk 32 + q16 16 + 4 (i16 % 4) .. + 3
         const int i16 = lane & 15, q16 = (lane >> 4) & 1, rx = 2 * (i16 >> 2) + g;
-        int tr_off[2][2], tr_blk[PP_NB];
+        int tr_off[2][2], tr_blk[2][PP_NB];
 #pragma unroll
         for (int f = 0; f < 2; ++f)
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) tr_off[f][hh] = (16 * f + 8 * hh + rx) * PP_RB;
 #pragma unroll
-        for (int blk = 0; blk < PP_NB; ++blk) tr_blk[blk] = (((blk * 4 + q16 * 2 + ((i16 & 3) >> 1)) ^ rx) * 16) + (i16 & 1) * 8;
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int blk = 0; blk < PP_NB; ++blk)
+                tr_blk[hh][blk] = (((blk * 4 + q16 * 2 + ((i16 & 3) >> 1)) ^ pp_swz(8 * hh + rx)) * 16) + (i16 & 1) * 8;
         if (work) {
 #pragma unroll
             for (int u = 0; u < PP_AHEAD; ++u) issue(t0 + u, u);
@@ -357,7 +365,7 @@ void kge_pp_kernel(const KgeBlockArgs a) {
 #pragma unroll
                         for (int hh = 0; hh < 2; ++hh) {
                             const pp_i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                (pp_i16x4 __attribute__((address_space(3))) *)(xs + tr_off[f][hh] + tr_blk[blk]));
+                                (pp_i16x4 __attribute__((address_space(3))) *)(xs + tr_off[f][hh] + tr_blk[hh][blk]));
                             const uint2 u = __builtin_bit_cast(uint2, v);
                             if (hh == 0) { av2[blk][f].x = u.x; av2[blk][f].y = u.y; } else { av2[blk][f].z = u.x; av2[blk][f].w = u.y; }
                         }
