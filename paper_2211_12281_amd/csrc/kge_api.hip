@@ -364,20 +364,22 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
                              ? (float)log((double)(cfg->n_ent_for_c - 1) / (double)N) : 0.f;
     const bool have_block = B > 0 && N > 0;
 
-    if ((rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos, nullptr, st)) != KGE_OK) return rc;
+    // (the kernels that need no transposed copy of the negatives get queries and negatives from ONE launch)
+    const bool plain_gather = have_block && (g.l1 || kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q));
+    if (plain_gather) rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos,
+                                                  neg, g.N, g.Np, b.T, b.tn, st);
+    else rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos, nullptr, st);
+    if (rc != KGE_OK) return rc;
     KgeBlockArgs a{};
     if (have_block && g.l1) {
         // 1-norm: the score block goes to memory, one row pass gives the loss statistics
-        if ((rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st)) != KGE_OK) return rc;
         rc = g.transh ? kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, b.A, b.P, g.Np, st)
                       : kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, g.Np, st);
         if (rc != KGE_OK) return rc;
         if ((rc = kge_run_l1_rowstat(b.S, g.Np, g.B, g.N, g.Bp, cfg->loss, cfg->gamma, cfg->adv_temp, b.stat_part, st)) != KGE_OK) return rc;
     } else if (have_block) {
         // (the two-role row-owner kernel transposes its tiles in the LDS and needs no transposed copy of the negatives)
-        if (kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q)) rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st);
-        else rc = kge_run_tgather_t(md, neg, g.N, g.Np, g.dp, b.T, b.Tt, b.tn, st);
-        if (rc != KGE_OK) return rc;
+        if (!plain_gather && (rc = kge_run_tgather_t(md, neg, g.N, g.Np, g.dp, b.T, b.Tt, b.tn, st)) != KGE_OK) return rc;
         // (nor does the two-role kernel of the pass over the negatives need transposed queries)
         if (!kge_gradt_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_t) &&
             (rc = kge_run_transpose(g.transh ? b.Q2 : b.Q, b.Qt, g.Bp, g.dp, g.bf16, st)) != KGE_OK) return rc;
@@ -410,14 +412,23 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         c.acc_part = b.acct; c.acc_part2 = nullptr; c.sum_part = b.sumt; c.stat_part = nullptr; c.own_pad = g.Np;
         if ((rc = launch_block(g, KGE_MODE_GRADT, cfg->loss, c, g.own_tiles_n, g.nsplit_t, g.dsplit_t, st)) != KGE_OK) return rc;
     }
-    if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, have_block ? g.nsplit_q : 0, b.gpos,
-                            g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, cfg->reg_l3, b.regv, st)) != KGE_OK) return rc;
-    if (N > 0) {
-        // with B == 0 there are no partials: nsplit 0 writes zero rows
-        rc = kge_run_tfinish(b.acct, b.sumt, have_block ? g.nsplit_t : 0, g.Np, g.N, g.dp, model->dim,
-                             have_block && g.kind == KGE_KIND_DIST && !g.l1, have_block ? b.T : nullptr, g.bf16, neg, g_ent + (size_t)2 * B * model->dim,
-                             g_ent_idx + 2 * B, model->ent, model->ent_ld, cfg->reg_l3, b.regv + (size_t)2 * g.Bp, st);
+    if (have_block) {
+        // chain rule of the queries and finish of the negatives' gradient rows in ONE launch
+        rc = kge_run_chain_tfinish(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, g.nsplit_q, b.gpos,
+                                   g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, cfg->reg_l3, b.regv,
+                                   b.acct, b.sumt, g.nsplit_t, g.Np, g.N, model->dim, g.kind == KGE_KIND_DIST && !g.l1, b.T, neg,
+                                   g_ent + (size_t)2 * B * model->dim, g_ent_idx + 2 * B, b.regv + (size_t)2 * g.Bp, st);
         if (rc != KGE_OK) return rc;
+    } else {
+        if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, 0, b.gpos,
+                                g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, cfg->reg_l3, b.regv, st)) != KGE_OK) return rc;
+        if (N > 0) {
+            // with B == 0 there are no partials: nsplit 0 writes zero rows (plus the regulariser of the rows, read from the table)
+            rc = kge_run_tfinish(b.acct, b.sumt, 0, g.Np, g.N, g.dp, model->dim, 0, nullptr, g.bf16, neg,
+                                 g_ent + (size_t)2 * B * model->dim, g_ent_idx + 2 * B, model->ent, model->ent_ld, cfg->reg_l3,
+                                 b.regv + (size_t)2 * g.Bp, st);
+            if (rc != KGE_OK) return rc;
+        }
     }
     if (cfg->reg_l3 > 0.f && B + N > 0) rc = kge_run_reg_add(b.regv, g.B, g.Bp, g.N, cfg->reg_l3, loss_out, st);
     return rc;

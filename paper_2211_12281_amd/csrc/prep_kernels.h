@@ -17,6 +17,10 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
                    float *pos_out, hipStream_t st);
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
                     hipStream_t st);
+// the two above as ONE launch (Bp > 0 and Np > 0; no positive scores out)
+int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
+                           int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
+                           const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st);
 // gather of the negatives and their transposed copy Tt [dp][Np] in one launch
 int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
                       hipStream_t st);
@@ -32,6 +36,14 @@ int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, cons
 int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N, int dp, int d,
                     int dist_kind, const void *T, bool bf16, const int32_t *neg, float *g_neg, int32_t *g_neg_idx,
                     const void *ent, int64_t ent_ld, float reg, float *regn, hipStream_t st);
+// kge_run_chain and kge_run_tfinish as ONE launch (B > 0 and N > 0; the rows of the negatives are read from T or,
+// with T == nullptr, from the model's entity table)
+int kge_run_chain_tfinish(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
+                          const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
+                          const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
+                          float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv,
+                          const float *accT_part, const float4 *sumT_part, int nsplit_t, int Np, int N, int d, int dist_kind,
+                          const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn, hipStream_t st);
 // loss_out += reg * (sum of regv over the 2B + N gathered slots), laid out [Bp heads][Bp tails][N negatives]
 int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st);
 

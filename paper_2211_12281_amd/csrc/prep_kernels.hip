@@ -42,12 +42,21 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 // ---------------------------------------------------------------------------------------------
 // gather + query build + positive score (one wave per triple; rows >= B are written as zeros)
 // ---------------------------------------------------------------------------------------------
+struct KgeQbuildArgs {
+    KgeModelDev m; const int32_t *h, *r, *t; int B, Bp, dp; void *Q, *W, *Q2; float *Q32, *W32; KgeRowInfo *rowinfo;
+    float *pos_ws, *pos_out;
+};
+struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; };
+
 template <bool BF16, int SC>
-__global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t,
-                                  int B, int Bp, int dp, void *Q, void *W, void *Q2, float *Q32, float *W32,
-                                  KgeRowInfo *rowinfo, float *pos_ws, float *pos_out) {
+__device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a) {
+    const KgeModelDev &m = a.m;
+    const int32_t *h = a.h, *r = a.r, *t = a.t;
+    const int B = a.B, Bp = a.Bp, dp = a.dp;
+    void *Q = a.Q, *W = a.W, *Q2 = a.Q2; float *Q32 = a.Q32, *W32 = a.W32;
+    KgeRowInfo *rowinfo = a.rowinfo; float *pos_ws = a.pos_ws, *pos_out = a.pos_out;
     const int lane = threadIdx.x & 63;
-    const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int b = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (b >= Bp) return;
     if (b >= B) {
         for (int j = lane; j < dp; j += 64) {
@@ -113,9 +122,10 @@ __global__ void kge_qbuild_kernel(KgeModelDev m, const int32_t *h, const int32_t
 // gather of the shared negatives: T[n] = ent[neg[n]], tn[n] = ||T[n]||^2 (zeros past N)
 // ---------------------------------------------------------------------------------------------
 template <bool BF16>
-__global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn) {
+__device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T,
+                                                 float *tn) {
     const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int n = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (n >= Np) return;
     float s = 0.f;
     const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
@@ -126,6 +136,19 @@ __global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int
     }
     s = kge_wave_sum(s);
     if (lane == 0) tn[n] = s;
+}
+template <bool BF16>
+__global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn) {
+    kge_tgather_body<BF16>(blockIdx.x, m, neg, N, Np, dp, T, tn);
+}
+template <bool BF16, int SC>
+__global__ void kge_qbuild_kernel(KgeQbuildArgs a) { kge_qbuild_body<BF16, SC>(blockIdx.x, a); }
+// query build and gather of the negatives in ONE launch (the first q_blocks workgroups build queries): the two are
+// independent, and a launch of their own each would cost the second one's start-up on the critical path
+template <bool BF16, int SC>
+__global__ void kge_qbuild_tgather_kernel(int q_blocks, KgeQbuildArgs a, KgeTgatherArgs g) {
+    if ((int)blockIdx.x < q_blocks) kge_qbuild_body<BF16, SC>(blockIdx.x, a);
+    else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn);
 }
 
 // gather of the shared negatives AND their transposed copy in one launch: a workgroup takes 32 negatives, every
@@ -251,15 +274,29 @@ __global__ void kge_loss_reduce_kernel(const float *lossb, int B, float scale, f
 // ---------------------------------------------------------------------------------------------
 // (the scorer is a template parameter: with a run-time switch every load of this kernel sat in its own branch
 // and was waited for on its own)
+struct KgeChainArgs {
+    KgeModelDev m; const int32_t *h, *r, *t; int B, Bp, dp; const float *acc_part, *acc_part2; const float4 *sum_part, *stat_part;
+    const KgeRowInfo *rowinfo; int nsplit; const float *gpos; float *g_ent, *g_rel, *g_relw; int32_t *g_ent_idx, *g_rel_idx;
+    float reg; float *regv;
+};
+struct KgeTfinishArgs {
+    const float *accT_part; const float4 *sumT_part; int nsplit, Np, N, dp, d, dist_kind; const void *T; const int32_t *neg;
+    float *g_neg; int32_t *g_neg_idx; const void *ent; int64_t ent_ld; float reg; float *regn;
+};
+
 template <bool BF16, int SC>
-__global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t *r, const int32_t *t, int B,
-                                 int Bp, int dp, const float *acc_part, const float *acc_part2,
-                                 const float4 *sum_part, const float4 *stat_part, const KgeRowInfo *rowinfo,
-                                 int nsplit, const float *gpos, float *g_ent,
-                                 float *g_rel, float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg,
-                                 float *regv) {
+__device__ __forceinline__ void kge_chain_body(int blk, const KgeChainArgs &a) {
+    const KgeModelDev &m = a.m;
+    const int32_t *h = a.h, *r = a.r, *t = a.t;
+    const int B = a.B, Bp = a.Bp, dp = a.dp, nsplit = a.nsplit;
+    const float *acc_part = a.acc_part, *acc_part2 = a.acc_part2, *gpos = a.gpos;
+    const float4 *sum_part = a.sum_part, *stat_part = a.stat_part;
+    const KgeRowInfo *rowinfo = a.rowinfo;
+    float *g_ent = a.g_ent, *g_rel = a.g_rel, *g_relw = a.g_relw, *regv = a.regv;
+    int32_t *g_ent_idx = a.g_ent_idx, *g_rel_idx = a.g_rel_idx;
+    const float reg = a.reg;
     const int lane = threadIdx.x & 63;
-    const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int b = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (b >= B) return;
     const int d = m.dim, c = d >> 1;
     KgeRowCtx<BF16> cx;
@@ -430,12 +467,14 @@ __global__ void kge_chain_kernel(KgeModelDev m, const int32_t *h, const int32_t 
 // gradient rows of the shared negatives: sum of the split partials minus colsum * t (distances), plus
 // the L3 regulariser of the row (read from the table itself, so it is there without a scored block)
 template <bool BF16>
-__global__ void kge_tfinish_kernel(const float *accT_part, const float4 *sumT_part, int nsplit, int Np, int N,
-                                   int dp, int d, int dist_kind, const void *T, const int32_t *neg,
-                                   float *g_neg, int32_t *g_neg_idx, const void *ent, int64_t ent_ld, float reg,
-                                   float *regn) {
+__device__ __forceinline__ void kge_tfinish_body(int blk, const KgeTfinishArgs &a) {
+    const float *accT_part = a.accT_part; const float4 *sumT_part = a.sumT_part;
+    const int nsplit = a.nsplit, Np = a.Np, N = a.N, dp = a.dp, d = a.d, dist_kind = a.dist_kind;
+    const void *T = a.T, *ent = a.ent; const int32_t *neg = a.neg;
+    float *g_neg = a.g_neg, *regn = a.regn; int32_t *g_neg_idx = a.g_neg_idx;
+    const int64_t ent_ld = a.ent_ld; const float reg = a.reg;
     const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int n = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (n >= N) return;
     float cs = 0.f;
     if (dist_kind)
@@ -470,6 +509,17 @@ __global__ void kge_tfinish_kernel(const float *accT_part, const float4 *sumT_pa
     }
     if (lane == 0) g_neg_idx[n] = neg[n];
 }
+template <bool BF16>
+__global__ void kge_tfinish_kernel(KgeTfinishArgs a) { kge_tfinish_body<BF16>(blockIdx.x, a); }
+template <bool BF16, int SC>
+__global__ void kge_chain_kernel(KgeChainArgs a) { kge_chain_body<BF16, SC>(blockIdx.x, a); }
+// both finishing kernels in ONE launch (the first chain_blocks workgroups run the chain rule of the queries): they
+// read different partials and write different gradient rows
+template <bool BF16, int SC>
+__global__ void kge_chain_tfinish_kernel(int chain_blocks, KgeChainArgs c, KgeTfinishArgs t) {
+    if ((int)blockIdx.x < chain_blocks) kge_chain_body<BF16, SC>(blockIdx.x, c);
+    else kge_tfinish_body<BF16>(blockIdx.x - chain_blocks, t);
+}
 
 // loss += reg * (sum of the L3 norms of the 2B + N gathered slots): one workgroup of 1024 threads, fixed
 // summation order (eight interleaved partial sums per thread keep the loads in flight, then a tree)
@@ -502,25 +552,39 @@ __global__ void kge_zero_rows_kernel(float *p, int64_t count) {
 // ---------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------
+#define KGE_SC_SWITCH(BF, LAUNCH)                          \
+    switch (m.scorer) {                                   \
+    case KGE_TRANSE: LAUNCH(BF, KGE_TRANSE); break;       \
+    case KGE_TRANSH: LAUNCH(BF, KGE_TRANSH); break;       \
+    case KGE_ROTATE: LAUNCH(BF, KGE_ROTATE); break;       \
+    case KGE_DISTMULT: LAUNCH(BF, KGE_DISTMULT); break;   \
+    case KGE_COMPLEX: LAUNCH(BF, KGE_COMPLEX); break;     \
+    default: return KGE_E_INVALID_ARG;                    \
+    }
+
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                    int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                    float *pos_out, hipStream_t st) {
     const int grid = (Bp + 3) / 4;
     if (grid == 0) return KGE_OK;
-#define KGE_QBUILD(BF, SC) hipLaunchKernelGGL((kge_qbuild_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, \
-                                              W32, rowinfo, pos_ws, pos_out)
-#define KGE_QBUILD_SC(BF)                                  \
-    switch (m.scorer) {                                    \
-    case KGE_TRANSE: KGE_QBUILD(BF, KGE_TRANSE); break;    \
-    case KGE_TRANSH: KGE_QBUILD(BF, KGE_TRANSH); break;    \
-    case KGE_ROTATE: KGE_QBUILD(BF, KGE_ROTATE); break;    \
-    case KGE_DISTMULT: KGE_QBUILD(BF, KGE_DISTMULT); break; \
-    case KGE_COMPLEX: KGE_QBUILD(BF, KGE_COMPLEX); break;  \
-    default: return KGE_E_INVALID_ARG;                     \
-    }
-    if (m.bf16) { KGE_QBUILD_SC(true) } else { KGE_QBUILD_SC(false) }
-#undef KGE_QBUILD_SC
+    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out};
+#define KGE_QBUILD(BF, SC) hipLaunchKernelGGL((kge_qbuild_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, a)
+    if (m.bf16) { KGE_SC_SWITCH(true, KGE_QBUILD) } else { KGE_SC_SWITCH(false, KGE_QBUILD) }
 #undef KGE_QBUILD
+    return kge_launch_status();
+}
+
+// kge_run_qbuild and kge_run_tgather as one launch (both Bp > 0 and Np > 0)
+int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
+                           int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
+                           const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st) {
+    const int qb = (Bp + 3) / 4, tb = (Np + 3) / 4;
+    if (qb == 0 || tb == 0) return KGE_E_INVALID_ARG;
+    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, nullptr};
+    const KgeTgatherArgs g{neg, N, Np, T, tn};
+#define KGE_QT(BF, SC) hipLaunchKernelGGL((kge_qbuild_tgather_kernel<BF, SC>), dim3(qb + tb), dim3(256), 0, st, qb, a, g)
+    if (m.bf16) { KGE_SC_SWITCH(true, KGE_QT) } else { KGE_SC_SWITCH(false, KGE_QT) }
+#undef KGE_QT
     return kge_launch_status();
 }
 
@@ -569,19 +633,10 @@ int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, cons
                   float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv, hipStream_t st) {
     if (B == 0) return KGE_OK;
     const int grid = (B + 3) / 4;
-#define KGE_CHAIN(BF, SC) hipLaunchKernelGGL((kge_chain_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, m, h, r, t, B, Bp, dp, acc_part, \
-                                             acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos, g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv)
-#define KGE_CHAIN_SC(BF)                                  \
-    switch (m.scorer) {                                   \
-    case KGE_TRANSE: KGE_CHAIN(BF, KGE_TRANSE); break;    \
-    case KGE_TRANSH: KGE_CHAIN(BF, KGE_TRANSH); break;    \
-    case KGE_ROTATE: KGE_CHAIN(BF, KGE_ROTATE); break;    \
-    case KGE_DISTMULT: KGE_CHAIN(BF, KGE_DISTMULT); break; \
-    case KGE_COMPLEX: KGE_CHAIN(BF, KGE_COMPLEX); break;  \
-    default: return KGE_E_INVALID_ARG;                    \
-    }
-    if (m.bf16) { KGE_CHAIN_SC(true) } else { KGE_CHAIN_SC(false) }
-#undef KGE_CHAIN_SC
+    const KgeChainArgs a{m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos,
+                         g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv};
+#define KGE_CHAIN(BF, SC) hipLaunchKernelGGL((kge_chain_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, a)
+    if (m.bf16) { KGE_SC_SWITCH(true, KGE_CHAIN) } else { KGE_SC_SWITCH(false, KGE_CHAIN) }
 #undef KGE_CHAIN
     return kge_launch_status();
 }
@@ -591,10 +646,30 @@ int kge_run_tfinish(const float *accT_part, const float4 *sumT_part, int nsplit,
                     const void *ent, int64_t ent_ld, float reg, float *regn, hipStream_t st) {
     if (N == 0) return KGE_OK;
     const int grid = (N + 3) / 4;
-    if (bf16) hipLaunchKernelGGL(kge_tfinish_kernel<true>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, ent, ent_ld, reg, regn);
-    else      hipLaunchKernelGGL(kge_tfinish_kernel<false>, dim3(grid), dim3(256), 0, st, accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, ent, ent_ld, reg, regn);
+    const KgeTfinishArgs a{accT_part, sumT_part, nsplit, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, ent, ent_ld, reg, regn};
+    if (bf16) hipLaunchKernelGGL(kge_tfinish_kernel<true>, dim3(grid), dim3(256), 0, st, a);
+    else      hipLaunchKernelGGL(kge_tfinish_kernel<false>, dim3(grid), dim3(256), 0, st, a);
     return kge_launch_status();
 }
+
+// kge_run_chain and kge_run_tfinish as one launch (B > 0 and N > 0)
+int kge_run_chain_tfinish(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
+                          const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
+                          const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
+                          float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv,
+                          const float *accT_part, const float4 *sumT_part, int nsplit_t, int Np, int N, int d, int dist_kind,
+                          const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn, hipStream_t st) {
+    if (B == 0 || N == 0) return KGE_E_INVALID_ARG;
+    const int cb = (B + 3) / 4, tb = (N + 3) / 4;
+    const KgeChainArgs a{m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos,
+                         g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv};
+    const KgeTfinishArgs f{accT_part, sumT_part, nsplit_t, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, m.ent, m.ent_ld, reg, regn};
+#define KGE_CT(BF, SC) hipLaunchKernelGGL((kge_chain_tfinish_kernel<BF, SC>), dim3(cb + tb), dim3(256), 0, st, cb, a, f)
+    if (m.bf16) { KGE_SC_SWITCH(true, KGE_CT) } else { KGE_SC_SWITCH(false, KGE_CT) }
+#undef KGE_CT
+    return kge_launch_status();
+}
+#undef KGE_SC_SWITCH
 
 int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st) {
     hipLaunchKernelGGL(kge_reg_add_kernel, dim3(1), dim3(1024), 0, st, regv, B, Bp, N, reg, loss_out);
