@@ -136,15 +136,32 @@ void topk_scan_kernel(const TopkArgs a) {
         ld_row[jj] = r;
         ld_col[jj] = (pos ^ (r & 7)) * 16;              // source chunk that belongs at this LDS position
     }
+    // source of copy jj for tile 0 and its advance per tile (lanes of the padding columns read the 16 zero bytes, advance 0):
+    // one multiply-add per copy in the loop; only the table's last, ragged tile takes the clamped path
+    const char *src0[IPW];
+    uint32_t src_step[IPW];
+#pragma unroll
+    for (int jj = 0; jj < IPW; ++jj) {
+        const bool real = ld_col[jj] < a.valid_bytes;
+        src0[jj] = real ? a.ent + (int64_t)ld_row[jj] * a.ent_stride + ld_col[jj] : (const char *)a.zeros;
+        src_step[jj] = real ? (uint32_t)(TK_ST * a.ent_stride) : 0u;
+    }
     auto issue = [&](int64_t tile, int slot) {
         tile = tile < t1 ? tile : t1 - 1;               // past the end: a harmless repeat keeps vmcnt uniform
         const int stage = slot % NSTAGE;
+        if (tile * TK_ST + TK_ST <= a.ncand) {
 #pragma unroll
-        for (int jj = 0; jj < IPW; ++jj) {
-            int64_t cand = tile * TK_ST + ld_row[jj];
-            cand = cand < a.ncand ? cand : a.ncand - 1; // rows past the end are masked in the epilogue
-            const char *gp = ld_col[jj] < a.valid_bytes ? a.ent + cand * a.ent_stride + ld_col[jj] : (const char *)a.zeros;
-            async_copy16(gp, __builtin_amdgcn_readfirstlane(lds0 + stage * TILE_BYTES + (wave * IPW + jj) * 1024));
+            for (int jj = 0; jj < IPW; ++jj)
+                async_copy16(src0[jj] + (uint64_t)tile * src_step[jj],
+                             __builtin_amdgcn_readfirstlane(lds0 + stage * TILE_BYTES + (wave * IPW + jj) * 1024));
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < IPW; ++jj) {
+                int64_t cand = tile * TK_ST + ld_row[jj];
+                cand = cand < a.ncand ? cand : a.ncand - 1; // rows past the end are masked in the epilogue
+                const char *gp = ld_col[jj] < a.valid_bytes ? a.ent + cand * a.ent_stride + ld_col[jj] : (const char *)a.zeros;
+                async_copy16(gp, __builtin_amdgcn_readfirstlane(lds0 + stage * TILE_BYTES + (wave * IPW + jj) * 1024));
+            }
         }
         async_copy4(a.tn + tile * TK_ST + lr,
                     __builtin_amdgcn_readfirstlane(lds0 + NSTAGE * TILE_BYTES + ((slot % SIDE_SLOTS) * 4 + wave) * 256));
@@ -898,6 +915,7 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
     md.ent_ld = model.ent_ld; md.rel_ld = model.rel_ld; md.relw_ld = model.relw_ld;
     const char *cand0 = (const char *)model.ent + lo * model.ent_ld * p.es;
     const int64_t stride = model.ent_ld * p.es;
+    if (stride * TK_ST >= (1ll << 32)) return KGE_E_UNSUPPORTED;     // the scan advances its sources by a 32-bit step per tile
     const int kind = (model.scorer == KGE_DISTMULT || model.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
 
     hipLaunchKernelGGL(topk_zero_kernel, dim3(1), dim3(64), 0, st, w.tmax, w.zeros);
