@@ -1,19 +1,19 @@
-// The row-owner pass of the block kernel (MODE_FWD of block_kernel.hpp: loss statistics of every query row and
-// the unnormalised gradient of the queries in one pass over the shared negatives) as a two-role kernel for the
-// hot configuration: bf16 operands, rows of 512 bytes (d <= 256), bilinear and distance scorers without the TransH
-// operands.
+// The two passes of a training call over the score block (MODE_FWD and MODE_GRADT of block_kernel.hpp: loss statistics
+// of every query row with the unnormalised gradient of the queries in one pass over the shared negatives, then the
+// gradient of the negatives from the finished row constants) as a two-role kernel for the hot configuration: bf16
+// operands, rows of 512 bytes (d <= 256), bilinear and distance scorers without the TransH operands.
 //
-// In the one-role kernel a wave owns 32 query rows, keeps 64 registers of own fragments AND 128 registers of
-// gradient accumulators, so only one wave fits per SIMD, and its contraction over d, its element-wise epilogue
-// (exponentials, sums, packing) and its contraction over the stream index run one after another.  Here the two
-// contractions belong to two waves that share a SIMD:
-//   wave A (waves 0-3)  tile t:    acc[32 stream x 32 own] = X_t . own^t, epilogue, coefficients -> LDS
-//   wave B (waves 4-7)  tile t-1:  out^t[d x 32 own] += Xt_{t-1}[d x 32 stream] . coef_{t-1}
-// so that the vector work of A runs under the matrix work of B and both hide each other's LDS latency.  The
-// coefficient tile of a pair (2 KB: the accumulator layout of A is the B-operand layout of B, lane for lane)
-// and the rare rescaling factor of the running reference exponent pass through a double-buffered LDS slot; the one
-// workgroup barrier per tile that the staging ring needs anyway orders the hand-over.  The ring holds four
-// tiles: A reads tile t, B reads tile t-1, tile t+1 has landed or is landing, tile t+2 is requested.
+// In the one-role kernel a wave owns 32 rows, keeps 64 registers of own fragments AND 128 registers of gradient
+// accumulators, so only one wave fits per SIMD, and its contraction over d, its element-wise epilogue (exponentials,
+// sums, packing) and its contraction over the stream index run one after another.  Here the two contractions belong
+// to two waves that share a SIMD:
+//   wave A (waves 0-3)  round t: MFMAs of tile t, acc[32 stream x 32 own] = X_t . own^t, and under them the epilogue
+//                       of tile t-1, whose coefficients go to the LDS
+//   wave B (waves 4-7)  round t: out^t[d x 32 own] += Xt_{t-2}[d x 32 stream] . coef_{t-2}
+// The coefficient tile of a pair (2 KB: the accumulator layout of A is the B-operand layout of B, lane for lane) and
+// the rare rescaling factor of the running reference exponent pass through a double-buffered LDS slot; the one
+// workgroup barrier per tile that the staging ring needs anyway orders the hand-over.  The ring holds five tiles: B
+// reads tile t-2, A reads tile t, tile t+1 has landed or is landing, tile t+2 is requested.
 //
 // Only the row-major tile X is staged.  Wave B needs it transposed (for a dimension, 8 consecutive stream entries
 // per lane) and gets that from the LDS transpose read of gfx950 (ds_read_b64_tr_b16): inside a group of 16 lanes,
@@ -21,9 +21,9 @@
 // l / 4, l / 4 + 4, l / 4 + 8, l / 4 + 12.  With source lane i at row K[i / 4], dimensions 4 (i % 4) .. + 3, lane l
 // receives dimension l of the rows K[0 .. 3]: one read transposes a 4 x 16 patch, two reads give the 8 entries of
 // an MFMA operand.  Wave A loads stream row pi(m) = (m & ~7) | ((m & 3) << 1) | ((m >> 2) & 1) as row m of its
-// contraction: the four rows K[.] of a read are then two apart, fall into four different 32-byte bank groups
-// under the tile's XOR swizzle, and A's own fragment reads stay conflict-free (pi permutes inside groups of 8).
-// Geometry (own tiles of 128 rows, splits over the negatives, placement on the dies), operand layouts, epilogue
+// contraction: the four rows K[.] of a read are then two apart, and the chunk swizzle pp_swz() below keeps both
+// waves' reads free of bank conflicts.
+// Geometry (own tiles of 128 rows, splits over the streamed rows, placement on the dies), operand layouts, epilogue
 // arithmetic and outputs are those of the one-role kernel, which stays the reference for every other
 // configuration.
 #include "block_kernel.hpp"
@@ -34,16 +34,12 @@ int kge_launch_gradt_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles
 namespace {
 
 constexpr int PP_RB = 512, PP_DP = 256, PP_KS = 16, PP_NB = 8, PP_ST = 32;
-constexpr int PP_X_BYTES = PP_ST * PP_RB;                   // 16 KB: [32 rows][512 bytes], chunk c of row r at c ^ (r & 7)
+constexpr int PP_X_BYTES = PP_ST * PP_RB;                   // 16 KB: [32 rows][512 bytes], chunk c of row r at c ^ pp_swz(r)
 constexpr int PP_STAGE = PP_X_BYTES;
-#ifndef PP_AHEAD
-#define PP_AHEAD 2
-#endif
-constexpr int PP_NSTAGE = PP_AHEAD + 3;                      // tiles t - 2 (wave B) .. t + PP_AHEAD (requested)
-#ifndef PP_VALU_PER_MFMA
-#define PP_VALU_PER_MFMA 8
-#endif
-constexpr int PP_SIDE_SLOTS = PP_AHEAD + 3;                            // side information of a tile's 32 stream rows, one copy per A wave
+constexpr int PP_AHEAD = 2;                                 // tiles requested ahead of wave A's (3 and 4 measured: no gain)
+constexpr int PP_NSTAGE = PP_AHEAD + 3;                     // tiles t - 2 (wave B) .. t + PP_AHEAD (requested)
+constexpr int PP_VALU_PER_MFMA = 8;                         // vector instructions scheduled after every MFMA of wave A (2 .. 16 measured: level)
+constexpr int PP_SIDE_SLOTS = PP_AHEAD + 3;                 // side information of a tile's 32 stream rows, one copy per A wave
 constexpr int PP_XCH = 2048 + 256;                          // coefficients (64 lanes x 32 bytes) + rescaling factors (64 x 4 bytes)
 constexpr int pp_lds(int mode) { return PP_NSTAGE * PP_STAGE + PP_SIDE_SLOTS * 4 * (mode == KGE_MODE_FWD ? 256 : 1024) + 4 * 2 * PP_XCH; }
 constexpr int PP_LPW_A = 3, PP_LPW_B = 2;                   // asynchronous copies per tile of an A / B wave
