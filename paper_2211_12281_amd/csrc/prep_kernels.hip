@@ -129,10 +129,27 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
     if (n >= Np) return;
     float s = 0.f;
     const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
-    for (int j = lane; j < dp; j += 64) {
-        float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
-        El<BF16>::st(T, (int64_t)n * dp + j, v);
-        s += v * v;
+    constexpr int ES = BF16 ? 2 : 4;
+    const int lpr = dp * ES / 16;                           // lanes that cover a row with 16 bytes each
+    if (m.dim == dp && lpr <= 64 && (m.ent_ld * ES) % 16 == 0 && ((uintptr_t)m.ent & 15) == 0) {
+        // unpadded, 16-byte aligned rows: ONE load per lane (the row's round trip to memory is paid once, not dp / 64 times)
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (n < N && lane < lpr) v = *(const uint4 *)((const char *)m.ent + off * ES + lane * 16);
+        if (lane < lpr) *(uint4 *)((char *)T + ((int64_t)n * dp) * ES + lane * 16) = v;
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if constexpr (BF16) {
+                const float a0 = __uint_as_float(w[k] << 16), a1 = __uint_as_float(w[k] & 0xffff0000u);
+                s += a0 * a0; s += a1 * a1;
+            } else { const float a0 = __uint_as_float(w[k]); s += a0 * a0; }
+        }
+    } else {
+        for (int j = lane; j < dp; j += 64) {
+            float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
+            El<BF16>::st(T, (int64_t)n * dp + j, v);
+            s += v * v;
+        }
     }
     s = kge_wave_sum(s);
     if (lane == 0) tn[n] = s;
