@@ -324,31 +324,42 @@ __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *
     const int nareas = nsplit * 2;                          // <= 2 * nseg <= 512
     if (threadIdx.x == 0) over = 0;
     __syncthreads();
-    // counts (clamped to the area size), then their exclusive prefix sums behind the kept list
-    for (int a2 = threadIdx.x; a2 < nareas; a2 += blockDim.x) {
-        int c = segcnt[(size_t)q * nseg * 2 + a2];
-        if (c > TK_HALF) { over = 1; c = TK_HALF; }
-        abase[a2 + 1] = c;
+    // counts (clamped to the area size), then their exclusive prefix sums behind the kept list: thread t takes the areas
+    // 2 t and 2 t + 1 (256 threads, at most 512 areas), a shuffle scan inside every wave, the waves' sums through the LDS
+    {
+        __shared__ int wsum[4];
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, a0 = 2 * threadIdx.x;
+        int c[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            c[j] = a0 + j < nareas ? segcnt[(size_t)q * nseg * 2 + a0 + j] : 0;
+            if (c[j] > TK_HALF) { over = 1; c[j] = TK_HALF; }
+        }
+        int incl = c[0] + c[1];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o); if (lane >= o) incl += v; }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        int start = kept + incl - (c[0] + c[1]);
+        for (int w = 0; w < wave; ++w) start += wsum[w];
+        if (a0 <= nareas) abase[a0] = start;
+        if (a0 + 1 <= nareas) abase[a0 + 1] = start + c[0];
+        if (a0 + 2 == nareas) abase[a0 + 2] = start + c[0] + c[1];
+        __syncthreads();
+        if (threadIdx.x == 0) total = abase[nareas];
     }
-    if (threadIdx.x == 0) abase[0] = kept;
-    __syncthreads();
-    if (threadIdx.x == 0) { for (int a2 = 0; a2 < nareas; ++a2) abase[a2 + 1] += abase[a2]; total = abase[nareas]; }
     __syncthreads();
     for (int i = threadIdx.x; i < kept; i += blockDim.x) { const uint2 e = keep[(size_t)q * KP + i]; s[i] = pack_value(e.x, e.y); }
-    // the areas are copied by 64 threads each, four at a time (the order does not matter: the sort below is total)
-    {
-        const int sub = threadIdx.x >> 6, li = threadIdx.x & 63;
-        for (int a0 = 0; a0 < nareas; a0 += 4) {
-            const int a2 = a0 + sub;
-            if (a2 < nareas) {
-                const int base = abase[a2], c = abase[a2 + 1] - base;
-                if (li < c) {
-                    if (base + c <= TK_SORTCAP) {
-                        const uint2 e = seg[((size_t)q * nseg * 2 + a2) * TK_HALF + li];
-                        s[base + li] = pack_value(e.x, e.y);
-                    } else over = 1;
-                }
-            }
+    // every thread copies whole areas (an area holds one or two entries as a rule, 64 at most): the loads of different
+    // threads are independent, so the memory latency is paid once or twice per thread, not once per area of the query
+    // (the order does not matter: the sort below is total)
+    for (int a2 = threadIdx.x; a2 < nareas; a2 += blockDim.x) {
+        const int base = abase[a2], c = abase[a2 + 1] - base;
+        if (c > 0) {
+            if (base + c <= TK_SORTCAP) {
+                const uint2 *src = seg + ((size_t)q * nseg * 2 + a2) * TK_HALF;
+                for (int li = 0; li < c; ++li) { const uint2 e = src[li]; s[base + li] = pack_value(e.x, e.y); }
+            } else over = 1;
         }
     }
     __syncthreads();
