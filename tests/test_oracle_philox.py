@@ -37,6 +37,18 @@ def test_single_round_hand_computed(orc):
     assert list(orc.philox_single_round([2, 5, 3, 7], [11, 13])) == [12, 0x68DBA805, 11, 0xA4A23EA6]
 
 
+def test_published_known_answers(orc):
+    """The generator's published known-answer vectors (tests/golden/philox4x32_10_kat.txt)."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for w in rows:
+        v = [int(x, 16) for x in w]
+        assert list(orc.philox4x32_10(v[0:4], v[4:6])) == v[6:10]
+        assert py_philox(v[0:4], v[4:6]) == v[6:10]
+
+
 def test_block_matches_bigint_implementation(orc):
     g = np.random.default_rng(5)
     cases = [([0, 0, 0, 0], [0, 0]), ([MASK] * 4, [MASK] * 2), ([1, 2, 3, 4], [5, 6])]

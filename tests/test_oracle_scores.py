@@ -132,6 +132,56 @@ def test_transh_properties(orc):
     assert abs(orc.score_one("transh", h, r, w, t) + np.linalg.norm(hp + r - tp)) < 1e-14
 
 
+def _table2():
+    import os
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "table2_relation_properties.txt"))
+            if l.strip() and not l.startswith("#")]
+    return {w[0]: dict(zip("S AS I C".split(), (int(x) for x in w[1:5]))) for w in rows}
+
+
+@pytest.mark.parametrize("scorer", ["transe", "transh", "rotate", "distmult", "complex"])
+def test_check_marks_of_table_2_have_witnesses(orc, scorer):
+    """Every check mark of Table 2 (tests/golden/table2_relation_properties.txt) is realised by the oracle's scorer with an
+    explicit relation: S - a non-zero r with f(h,r,t) = f(t,r,h) for all h, t; AS - an r with f(h,r,t) != f(t,r,h); I - an
+    r' with f(h,r,t) = f(t,r',h); C - r3 built from r1, r2 such that f(h,r1,m) = f(m,r2,t) = 0 implies f(h,r3,t) = 0.  Two
+    crosses are facts of the formulas and are checked too: TransE is symmetric for no r != 0, DistMult antisymmetric for none."""
+    marks = _table2()[scorer]
+    g = np.random.default_rng(11)
+    d, c = 12, 6
+    q = np.float32(1 / 64.0)
+    grid = lambda n: (np.round(_rand(g, n)[0] / q) * q).astype(np.float32)      # sums and differences exact in fp32
+    h, t = grid(d), grid(d)
+    w = _rand(g, d)[0] if scorer == "transh" else None
+    f = lambda hh, rr, tt: orc.score_one(scorer, hh, rr, w, tt)
+    k = c if scorer == "rotate" else d
+    generic = grid(k) + q                                                        # no zero entry, no multiple of pi
+    if marks["S"]:
+        r_sym = {"transh": np.zeros(d, F), "rotate": np.array([0, math.pi] * 3, F), "distmult": generic,
+                 "complex": np.r_[generic[:c], np.zeros(c, F)]}[scorer]
+        assert abs(f(h, r_sym, t) - f(t, r_sym, h)) < 1e-6 * max(1.0, abs(f(h, r_sym, t)))
+        if scorer != "transh":
+            assert np.any(r_sym != 0)
+    else:
+        assert scorer == "transe" and abs(f(h, generic, t) - f(t, generic, h)) > 1e-3
+    if marks["AS"]:
+        assert abs(f(h, generic, t) - f(t, generic, h)) > 1e-3
+    else:
+        assert scorer == "distmult" and f(h, generic, t) == f(t, generic, h)
+    if marks["I"]:
+        r_inv = {"transe": -generic, "rotate": -generic, "complex": np.r_[generic[:c], -generic[c:]]}[scorer]
+        assert abs(f(h, generic, t) - f(t, r_inv, h)) < 1e-6 * max(1.0, abs(f(h, generic, t)))
+    if marks["C"]:
+        r1, r2 = grid(k), grid(k)
+        if scorer == "transe":
+            m, t3 = h + r1, h + r1 + r2
+            assert f(h, r1, m) == 0.0 and f(m, r2, t3) == 0.0 and f(h, r1 + r2, t3) == 0.0
+        else:                                                                    # rotate: the phases add
+            rot = lambda x, ph: np.r_[x[:c] * np.cos(ph) - x[c:] * np.sin(ph), x[:c] * np.sin(ph) + x[c:] * np.cos(ph)].astype(np.float32)
+            m = rot(h.astype(np.float64), r1.astype(np.float64))
+            t3 = rot(m.astype(np.float64), r2.astype(np.float64))
+            assert abs(f(h, r1, m)) < 1e-6 and abs(f(m, r2, t3)) < 1e-6 and abs(f(h, r1 + r2, t3)) < 1e-6
+
+
 @pytest.mark.parametrize("scorer", ["transe", "transh", "rotate", "distmult", "complex"])
 def test_block_forms_equal_direct_loops(orc, scorer):
     """The shared-negative block as (query build) + (contraction against the negative rows),
