@@ -186,7 +186,9 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
  * with the matrix-core scores and may differ from the fp64 rank by the number of candidates whose
  * score lies within the rounding error of the true tail's score.
  * Scorers: DistMult, ComplEx, TransE, RotatE and TransH with p_norm = 2 (p_norm = 1, and TransH rows longer than
- * 512 bytes: KGE_E_UNSUPPORTED).
+ * 512 bytes: KGE_E_UNSUPPORTED).  The rows of the entity table must start 16-byte aligned (model->ent and
+ * ent_ld * sizeof(element) multiples of 16; else KGE_E_UNSUPPORTED): the scan copies them straight from the table.
+ * kge_score and kge_loss_bwd take any row stride >= dim.
  * RotatE's key passes through cos / sin of the phases in fp64: its last bit is the math library's.  TransH's key
  * is |q' - t + (u.t) u|^2 with u = w / max(|w|, 1e-12) and q' = (h - (u.h) u) + r made once per query in fp64
  * (wave-wide sums), then u.t and the squared distance by sequential fused multiply-adds over the columns; it

@@ -491,6 +491,8 @@ int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64
     if (model->scorer == KGE_TRANSH && (int64_t)model->dim * (model->dtype == KGE_BF16 ? 2 : 4) > 512) return KGE_E_UNSUPPORTED;
     if ((model->scorer == KGE_TRANSE || model->scorer == KGE_ROTATE || model->scorer == KGE_TRANSH) && model->p_norm != 2)
         return KGE_E_UNSUPPORTED;
+    // the scan copies candidate rows straight from the table in 16-byte pieces
+    if (((uintptr_t)model->ent & 15) != 0 || (model->ent_ld * (model->dtype == KGE_BF16 ? 2 : 4)) % 16 != 0) return KGE_E_UNSUPPORTED;
     if (Q == 0) return KGE_OK;
     if (!h || !r || !out_idx || !out_score) return KGE_E_INVALID_ARG;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
