@@ -48,7 +48,7 @@ typedef enum { KGE_OP_SCORE = 0, KGE_OP_LOSS_BWD = 1, KGE_OP_SPARSE_ADAM = 2, KG
 enum {
     KGE_OK = 0,
     KGE_E_INVALID_ARG = -1,         /* NULL where data is required, negative size, bad enum, bad dim */
-    KGE_E_UNSUPPORTED = -2,         /* valid request this build has no kernel for (e.g. TransH with p_norm = 1) */
+    KGE_E_UNSUPPORTED = -2,         /* valid request this build has no kernel for (e.g. kge_topk with p_norm = 1) */
     KGE_E_WORKSPACE_TOO_SMALL = -3,
     KGE_E_HIP = -4                  /* a HIP runtime call failed (launch error) */
 };
@@ -146,7 +146,9 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
  *   param_f32   float[n_rows, ld]   master weights (updated in place)
  *   param_bf16  bf16 [n_rows, ld]   optional shadow copy, rewritten as RNE(theta) for touched rows
  *   m, v        float[n_rows, ld]   Adam moments (updated in place)
- * dim must be a multiple of 4.  M = 0 is valid (no-op).  This is the only call that writes a table.
+ * dim and ld must be multiples of 4, param_f32, m, v and grads 16-byte aligned, param_bf16 8-byte aligned (the update
+ * moves four columns at a time; KGE_E_INVALID_ARG otherwise).  M = 0 is valid (no-op).  This is the only call that
+ * writes a table.
  */
 int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows,
                     int32_t dim, int64_t ld, const int32_t *idx, const float *grads, int64_t M,

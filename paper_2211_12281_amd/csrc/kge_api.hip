@@ -180,6 +180,12 @@ int launch_block(const Geometry &g, int mode, int loss, const KgeBlockArgs &a, i
     return kge_launch_block(g.bf16, g.rb, mode, g.transh, g.kind, loss, dsplit, a, own_tiles, nsplit, st);
 }
 
+// the update reads and writes four columns at a time: 16-byte aligned fp32 rows (ld % 4 == 0 is checked by the callers),
+// 8-byte aligned bf16 shadow rows
+bool adam_rows_aligned(const float *param_f32, const void *param_bf16, const float *m, const float *v, const float *grads) {
+    return (((uintptr_t)param_f32 | (uintptr_t)m | (uintptr_t)v | (uintptr_t)grads) & 15) == 0 && ((uintptr_t)param_bf16 & 7) == 0;
+}
+
 void *align_ws(void *ws, size_t &bytes) {
     uintptr_t p = (uintptr_t)ws, q = (p + 255) & ~(uintptr_t)255;
     bytes = bytes >= (q - p) ? bytes - (q - p) : 0;
@@ -444,6 +450,7 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
     if (M == 0) return KGE_OK;
     if (M >= (1ll << 31)) return KGE_E_INVALID_ARG;
     if (!param_f32 || !m || !v || !idx || !grads) return KGE_E_INVALID_ARG;
+    if (!adam_rows_aligned(param_f32, param_bf16, m, v, grads)) return KGE_E_INVALID_ARG;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
     ws = align_ws(ws, ws_bytes);
     if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
@@ -473,6 +480,7 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
     if (M == 0) return KGE_OK;
     if (M >= (1ll << 31)) return KGE_E_INVALID_ARG;
     if (!param_f32 || !m || !v || !grads) return KGE_E_INVALID_ARG;
+    if (!adam_rows_aligned(param_f32, param_bf16, m, v, grads)) return KGE_E_INVALID_ARG;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
     ws = align_ws(ws, ws_bytes);
     if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;

@@ -53,6 +53,29 @@ def test_host_only_entry_points(lib):
                          ctypes.c_size_t(0), None) == -1
 
 
+def test_alignment_rules_are_checked_on_the_host(lib):
+    """Misaligned table pointers are refused before anything is launched (fake addresses: nothing dereferences them)."""
+    import paper_2211_12281_amd.binding as b
+    cfg = b.KgeAdamCfgT(1e-3, 0.9, 0.999, 1e-8, 1)
+    p = ctypes.c_void_p
+    ok = 0x10000000
+    call = lambda th, sh, m, v, g: lib.kge_sparse_adam(p(th), p(sh), p(m), p(v), ctypes.c_int64(100), 8, ctypes.c_int64(8), p(ok),
+                                                      p(g), ctypes.c_int64(4), ctypes.byref(cfg), None, ctypes.c_size_t(0), None)
+    assert call(ok, ok, ok, ok, ok) == -3                       # everything aligned: gets as far as the missing workspace
+    for bad in [(ok + 4, ok, ok, ok, ok), (ok, ok + 2, ok, ok, ok), (ok, ok, ok + 8, ok, ok), (ok, ok, ok, ok + 4, ok),
+                (ok, ok, ok, ok, ok + 12)]:
+        assert call(*bad) == -1
+    # kge_topk: rows of the entity table must be 16-byte aligned
+    m = b.KgeModelT()
+    m.scorer, m.p_norm, m.dtype, m.dim, m.rel_dim = b.SCORERS["distmult"], 2, 1, 64, 64
+    m.n_ent, m.n_rel, m.ent, m.rel, m.ent_ld, m.rel_ld = 1000, 10, ok, ok, 67, 64
+    topk = lambda: lib.kge_topk(ctypes.byref(m), p(ok), p(ok), ctypes.c_int64(8), ctypes.c_int64(0), ctypes.c_int64(1000), 10,
+                                p(ok), p(ok), None, None, None, ctypes.c_size_t(0), None)
+    assert topk() == -2                                         # unsupported: row stride of 134 bytes
+    m.ent_ld = 72
+    assert topk() == -3                                         # aligned rows: gets as far as the missing workspace
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     import paper_2211_12281_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
