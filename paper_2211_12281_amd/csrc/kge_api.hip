@@ -1,6 +1,7 @@
 // extern "C" entry points: argument validation, workspace carving, kernel sequencing.
 #include "prep_kernels.h"
 #include <math.h>
+#include <stdlib.h>
 
 int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
                         const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
@@ -13,6 +14,9 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
 size_t kge_topk_ws(const kge_model_t &model, int64_t Q, int64_t ncand, int K);
+int kge_run_split3(const float *src, int64_t n, void *planes, hipStream_t st);
+int kge_launch_score3(int kind, int dp, const void *Qp, const void *Tp, const float *Q32, const float *T32,
+                      const KgeRowInfo *rowinfo, const float *tn, int B, int N, int Bp, int Np, float *S_out, hipStream_t st);
 int kge_run_partition(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int D, int64_t *offsets,
                       int64_t *order, void *ws, size_t ws_bytes, hipStream_t st);
 size_t kge_partition_ws(int64_t n, int D);
@@ -106,6 +110,13 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     return g;
 }
 
+// fp32 score blocks of the scorers with ONE contraction per pair go through three bf16 planes on the bf16 matrix pipe
+// (block_f32x3_score.hip); KGE_SCORE_F32_MFMA=1 in the environment keeps the fp32 matrix instructions (cross-check)
+bool score3_applies(const Geometry &g) {
+    static const bool off = [] { const char *e = getenv("KGE_SCORE_F32_MFMA"); return e && e[0] == '1'; }();
+    return !off && !g.bf16 && !g.transh && !g.l1 && (g.dp == 128 || g.dp == 256) && g.N > 0;
+}
+
 // bump allocator over the caller's workspace (256-byte granules); with base == nullptr it only sizes
 struct Carver {
     char *base; size_t off = 0;
@@ -125,6 +136,7 @@ struct Buffers {
     float *regv;                       // L3 norms of the gathered slots: [Bp heads][Bp tails][Np negatives]
     float *S, *Q32;                    // 1-norm scorers: the score block [Bp][Np], the queries unrounded [Bp][dp]
     float *W32, *A, *P;                // ... TransH: the unit normals unrounded, w^ . t and sign(x) . w^ per pair [Bp][Np]
+    void *Qp3, *Tp3;                   // score-only calls on fp32 tables: three bf16 planes of Q and of T
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -139,6 +151,8 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
     b.Q32 = g.l1 ? c.take<float>(rowsB) : nullptr;
     b.W32 = g.l1 && g.transh ? c.take<float>(rowsB) : nullptr;
     b.A = b.P = nullptr;
+    b.Qp3 = b.Tp3 = nullptr;
+    if (!bwd && score3_applies(g)) { b.Qp3 = c.take<char>(3 * rowsB * 2); b.Tp3 = c.take<char>(3 * rowsN * 2); }
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
     b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr;
     if (bwd) {
@@ -335,6 +349,12 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     if (g.l1 && g.transh)
         return kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, nullptr, nullptr, g.N, st);
     if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);
+    if (score3_applies(g)) {
+        if ((rc = kge_run_split3((const float *)b.Q, (int64_t)g.Bp * g.dp, b.Qp3, st)) != KGE_OK) return rc;
+        if ((rc = kge_run_split3((const float *)b.T, (int64_t)g.Np * g.dp, b.Tp3, st)) != KGE_OK) return rc;
+        return kge_launch_score3(g.kind, g.dp, b.Qp3, b.Tp3, (const float *)b.Q, (const float *)b.T, b.rowinfo, b.tn, g.B, g.N,
+                                 g.Bp, g.Np, neg_out, st);
+    }
     KgeBlockArgs a{};
     a.own = b.T; a.str = b.Q; a.str2 = b.W; a.rowinfo = b.rowinfo; a.tn = b.tn;
     a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_b; a.tiles_per_split = g.tps_s;
