@@ -1,6 +1,6 @@
 // The score block of kge_score (Table 2 against the shared negatives of eq. (negsamples)) for fp32 tables on the bf16
 // matrix pipe.  The fp32 MFMA of gfx950 runs at 1/16 of the bf16 rate, so every fp32 operand is split into three bf16
-// planes, x = x1 + x2 + x3 with x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2) (the three 8-bit significands
+// planes by the gather kernels, x = x1 + x2 + x3 with x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2) (the three 8-bit significands
 // cover the 24 bits of the float: the residual is below 2^-24 |x|), and q . t is accumulated in fp32 from the six
 // plane products of weight >= 2^-16: q1.t1 + q1.t2 + q2.t1 + q1.t3 + q2.t2 + q3.t1 (what is dropped is below
 // 3 x 2^-24 |q| |t|, the size of the rounding of an fp32 contraction).  Six bf16 MFMAs replace sixteen fp32-rate ones.
@@ -13,25 +13,12 @@
 // store -sqrt.
 #include "block_kernel.hpp"
 
-int kge_run_split3(const float *src, int64_t n, void *planes, hipStream_t st);
 int kge_launch_score3(int kind, int dp, const void *Qp, const void *Tp, const float *Q32, const float *T32,
                       const KgeRowInfo *rowinfo, const float *tn, int B, int N, int Bp, int Np, float *S_out, hipStream_t st);
 
 namespace {
 
 constexpr int S3_ST = 32, S3_NSTAGE = 3;
-
-// planes[p][i], p = 0 .. 2: the bf16 pieces of src[i]
-__global__ void split3_kernel(const float *src, int64_t n, __bf16 *planes) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const float x = src[i];
-    const __bf16 x1 = (__bf16)x;
-    const float r1 = x - (float)x1;                    // exact: both are multiples of the float's last place
-    const __bf16 x2 = (__bf16)r1;
-    const float r2 = r1 - (float)x2;
-    planes[i] = x1; planes[n + i] = x2; planes[2 * n + i] = (__bf16)r2;
-}
 
 struct Score3Args {
     const char *Qp, *Tp;                               // bf16 planes [3][Bp][DP], [3][Np][DP]
@@ -205,12 +192,6 @@ int launch3(const Score3Args &a, hipStream_t st) {
 }
 
 }  // namespace
-
-int kge_run_split3(const float *src, int64_t n, void *planes, hipStream_t st) {
-    if (n <= 0) return KGE_OK;
-    hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, n, (__bf16 *)planes);
-    return kge_launch_status();
-}
 
 int kge_launch_score3(int kind, int dp, const void *Qp, const void *Tp, const float *Q32, const float *T32,
                       const KgeRowInfo *rowinfo, const float *tn, int B, int N, int Bp, int Np, float *S_out, hipStream_t st) {

@@ -14,7 +14,6 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
 size_t kge_topk_ws(const kge_model_t &model, int64_t Q, int64_t ncand, int K);
-int kge_run_split3(const float *src, int64_t n, void *planes, hipStream_t st);
 int kge_launch_score3(int kind, int dp, const void *Qp, const void *Tp, const float *Q32, const float *T32,
                       const KgeRowInfo *rowinfo, const float *tn, int B, int N, int Bp, int Np, float *S_out, hipStream_t st);
 int kge_run_partition(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int D, int64_t *offsets,
@@ -342,16 +341,14 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     if (carve(g, false, nullptr, b) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     carve(g, false, ws, b);
     KgeModelDev md = dev_model(*model);
-    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st);
+    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st, b.Qp3);
     if (rc != KGE_OK || !block) return rc;
-    rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st);
+    rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st, b.Tp3);
     if (rc != KGE_OK) return rc;
     if (g.l1 && g.transh)
         return kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, nullptr, nullptr, g.N, st);
     if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);
     if (score3_applies(g)) {
-        if ((rc = kge_run_split3((const float *)b.Q, (int64_t)g.Bp * g.dp, b.Qp3, st)) != KGE_OK) return rc;
-        if ((rc = kge_run_split3((const float *)b.T, (int64_t)g.Np * g.dp, b.Tp3, st)) != KGE_OK) return rc;
         return kge_launch_score3(g.kind, g.dp, b.Qp3, b.Tp3, (const float *)b.Q, (const float *)b.T, b.rowinfo, b.tn, g.B, g.N,
                                  g.Bp, g.Np, neg_out, st);
     }

@@ -14,9 +14,10 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
                       int32_t *out, hipStream_t st);
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                    int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
-                   float *pos_out, hipStream_t st);
+                   float *pos_out, hipStream_t st, void *planes = nullptr);
+// planes (fp32 tables only, optional): also the three bf16 pieces of every element, [3][rows][dp]
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
-                    hipStream_t st);
+                    hipStream_t st, void *planes = nullptr);
 // the two above as ONE launch (Bp > 0 and Np > 0; no positive scores out)
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,

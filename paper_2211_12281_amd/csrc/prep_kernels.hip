@@ -45,8 +45,17 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 struct KgeQbuildArgs {
     KgeModelDev m; const int32_t *h, *r, *t; int B, Bp, dp; void *Q, *W, *Q2; float *Q32, *W32; KgeRowInfo *rowinfo;
     float *pos_ws, *pos_out;
+    __bf16 *planes;                    // optional: the three bf16 pieces of q, [3][Bp][dp] (fp32 score blocks on the bf16 pipe)
 };
 struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; };
+
+// x = x1 + x2 + x3 in bf16 (each piece the rounding of what the previous ones leave): plane p of element i at planes[p n + i]
+__device__ __forceinline__ void kge_store_planes(__bf16 *planes, int64_t n, int64_t i, float x) {
+    const __bf16 x1 = (__bf16)x;
+    const float r1 = x - (float)x1;
+    const __bf16 x2 = (__bf16)r1;
+    planes[i] = x1; planes[n + i] = x2; planes[2 * n + i] = (__bf16)(r1 - (float)x2);
+}
 
 template <bool BF16, int SC>
 __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a) {
@@ -65,6 +74,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
             if (Q2) El<BF16>::st(Q2, (int64_t)b * dp + j, 0.f);
             if (Q32) Q32[(int64_t)b * dp + j] = 0.f;
             if (W32) W32[(int64_t)b * dp + j] = 0.f;
+            if (a.planes) kge_store_planes(a.planes, (int64_t)Bp * dp, (int64_t)b * dp + j, 0.f);
         }
         if (lane == 0) { rowinfo[b] = KgeRowInfo{0.f, 0.f, 0.f, 0.f}; if (pos_ws) pos_ws[b] = 0.f; }
         return;
@@ -88,6 +98,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
             if (W) El<BF16>::st(W, (int64_t)b * dp + j, cx.w[k]);
             if (Q32) Q32[(int64_t)b * dp + j] = cx.q[k];      // unrounded copies for the 1-norm kernels
             if (W32) W32[(int64_t)b * dp + j] = cx.w[k];
+            if (a.planes) kge_store_planes(a.planes, (int64_t)Bp * dp, (int64_t)b * dp + j, cx.q[k]);
         }
     }
     qn = kge_wave_sum(qn);
@@ -123,7 +134,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
 // ---------------------------------------------------------------------------------------------
 template <bool BF16>
 __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T,
-                                                 float *tn) {
+                                                 float *tn, __bf16 *planes = nullptr) {
     const int lane = threadIdx.x & 63;
     const int n = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (n >= Np) return;
@@ -142,12 +153,16 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
             if constexpr (BF16) {
                 const float a0 = __uint_as_float(w[k] << 16), a1 = __uint_as_float(w[k] & 0xffff0000u);
                 s += a0 * a0; s += a1 * a1;
-            } else { const float a0 = __uint_as_float(w[k]); s += a0 * a0; }
+            } else {
+                const float a0 = __uint_as_float(w[k]); s += a0 * a0;
+                if (planes && lane < lpr) kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + lane * 4 + k, a0);
+            }
         }
     } else {
         for (int j = lane; j < dp; j += 64) {
             float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
             El<BF16>::st(T, (int64_t)n * dp + j, v);
+            if (!BF16 && planes) kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + j, v);
             s += v * v;
         }
     }
@@ -155,8 +170,8 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
     if (lane == 0) tn[n] = s;
 }
 template <bool BF16>
-__global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn) {
-    kge_tgather_body<BF16>(blockIdx.x, m, neg, N, Np, dp, T, tn);
+__global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, __bf16 *planes) {
+    kge_tgather_body<BF16>(blockIdx.x, m, neg, N, Np, dp, T, tn, planes);
 }
 template <bool BF16, int SC>
 __global__ void kge_qbuild_kernel(KgeQbuildArgs a) { kge_qbuild_body<BF16, SC>(blockIdx.x, a); }
@@ -581,10 +596,10 @@ __global__ void kge_zero_rows_kernel(float *p, int64_t count) {
 
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                    int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
-                   float *pos_out, hipStream_t st) {
+                   float *pos_out, hipStream_t st, void *planes) {
     const int grid = (Bp + 3) / 4;
     if (grid == 0) return KGE_OK;
-    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out};
+    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (__bf16 *)planes};
 #define KGE_QBUILD(BF, SC) hipLaunchKernelGGL((kge_qbuild_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, a)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QBUILD) } else { KGE_SC_SWITCH(false, KGE_QBUILD) }
 #undef KGE_QBUILD
@@ -597,7 +612,7 @@ int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st) {
     const int qb = (Bp + 3) / 4, tb = (Np + 3) / 4;
     if (qb == 0 || tb == 0) return KGE_E_INVALID_ARG;
-    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, nullptr};
+    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, nullptr, nullptr};
     const KgeTgatherArgs g{neg, N, Np, T, tn};
 #define KGE_QT(BF, SC) hipLaunchKernelGGL((kge_qbuild_tgather_kernel<BF, SC>), dim3(qb + tb), dim3(256), 0, st, qb, a, g)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QT) } else { KGE_SC_SWITCH(false, KGE_QT) }
@@ -605,11 +620,12 @@ int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t
     return kge_launch_status();
 }
 
-int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, hipStream_t st) {
+int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, hipStream_t st, void *planes) {
     const int grid = (Np + 3) / 4;
     if (grid == 0) return KGE_OK;
-    if (m.bf16) hipLaunchKernelGGL(kge_tgather_kernel<true>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn);
-    else        hipLaunchKernelGGL(kge_tgather_kernel<false>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn);
+    if (planes && m.bf16) return KGE_E_INVALID_ARG;
+    if (m.bf16) hipLaunchKernelGGL(kge_tgather_kernel<true>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn, (__bf16 *)nullptr);
+    else        hipLaunchKernelGGL(kge_tgather_kernel<false>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn, (__bf16 *)planes);
     return kge_launch_status();
 }
 
