@@ -415,7 +415,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         if ((rc = launch_block(g, KGE_MODE_FWD, cfg->loss, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
     }
     if ((rc = kge_run_rowfinish(b.stat_part, have_block ? (g.l1 ? 1 : g.nsplit_q) : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
-                                cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, loss_out, st)) != KGE_OK) return rc;
+                                cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, have_block ? nullptr : loss_out, st)) != KGE_OK) return rc;
     if (have_block && g.l1 && g.transh) {
         if ((rc = kge_run_l1h_grad(g.bf16, true, b.Q32, b.W32, b.T, b.S, b.A, b.P, g.Np, b.rowinfo, g.B, g.N, g.Bp, g.Np, g.dp,
                                    cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_q, b.accq, b.accq2, st)) != KGE_OK) return rc;
@@ -440,7 +440,8 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         rc = kge_run_chain_tfinish(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, g.nsplit_q, b.gpos,
                                    g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, cfg->reg_l3, b.regv,
                                    b.acct, b.sumt, g.nsplit_t, g.Np, g.N, model->dim, g.kind == KGE_KIND_DIST && !g.l1, b.T, neg,
-                                   g_ent + (size_t)2 * B * model->dim, g_ent_idx + 2 * B, b.regv + (size_t)2 * g.Bp, st);
+                                   g_ent + (size_t)2 * B * model->dim, g_ent_idx + 2 * B, b.regv + (size_t)2 * g.Bp,
+                                   b.lossb, scale, loss_out, st);
         if (rc != KGE_OK) return rc;
     } else {
         if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, 0, b.gpos,

@@ -28,7 +28,7 @@ int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, i
 int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipStream_t st);
 int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma,
                       float c_corr, float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb,
-                      float *gpos, float *loss_out, hipStream_t st);
+                      float *gpos, float *loss_out, hipStream_t st);     // loss_out null: the rows' losses are not summed here
 // m.p1: acc_part holds finished gradient rows (coefficients already normalised), sum_part / stat_part are not read
 int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
                   const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
@@ -44,7 +44,8 @@ int kge_run_chain_tfinish(const KgeModelDev &m, const int32_t *h, const int32_t 
                           const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
                           float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv,
                           const float *accT_part, const float4 *sumT_part, int nsplit_t, int Np, int N, int d, int dist_kind,
-                          const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn, hipStream_t st);
+                          const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn,
+                          const float *lossb, float scale, float *loss_out, hipStream_t st);   // also loss_out = scale * sum of lossb
 // loss_out += reg * (sum of regv over the 2B + N gathered slots), laid out [Bp heads][Bp tails][N negatives]
 int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st);
 

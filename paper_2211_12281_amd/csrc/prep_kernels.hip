@@ -288,7 +288,7 @@ __global__ void kge_rowfinish_kernel(const float4 *stat_part, int nsplit, int Bp
 }
 
 // loss_out = scale * sum_b lossb[b], one workgroup, fixed summation tree
-__global__ void kge_loss_reduce_kernel(const float *lossb, int B, float scale, float *loss_out) {
+__device__ __forceinline__ void kge_loss_reduce_body(const float *lossb, int B, float scale, float *loss_out) {
     __shared__ double sh[256];
     double s = 0.0;
     for (int b = threadIdx.x; b < B; b += 256) s += (double)lossb[b];
@@ -299,6 +299,9 @@ __global__ void kge_loss_reduce_kernel(const float *lossb, int B, float scale, f
         __syncthreads();
     }
     if (threadIdx.x == 0) *loss_out = (float)(sh[0] * (double)scale);
+}
+__global__ void kge_loss_reduce_kernel(const float *lossb, int B, float scale, float *loss_out) {
+    kge_loss_reduce_body(lossb, B, scale, loss_out);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -511,33 +514,53 @@ __device__ __forceinline__ void kge_tfinish_body(int blk, const KgeTfinishArgs &
     float cs = 0.f;
     if (dist_kind)
         for (int s = 0; s < nsplit; ++s) cs += sumT_part[(size_t)s * Np + n].x;
-    // the row is read once (from the gathered copy when there is one, else from the table) and kept in registers
-    float x[KGE_MAXJ], f = 0.f;
+    // A lane takes FOUR consecutive columns per step (d is a multiple of 4: a group lies inside the row or past its end),
+    // so that a partial row is one 16-byte load per lane.  The row itself is read once (from the gathered copy when
+    // there is one, else from the table) and kept in registers.
+    constexpr int NG = KGE_MAXJ / 4;                        // column groups per lane
+    static_assert(KGE_MAXJ % 4 == 0, "four columns per lane and step");
+    float x[NG][4], f = 0.f;
     const bool need_row = reg > 0.f || dist_kind;
     const int64_t rbase = T ? (int64_t)n * dp : (int64_t)neg[n] * ent_ld;
     const void *rsrc = T ? T : ent;
 #pragma unroll
-    for (int k = 0; k < KGE_MAXJ; ++k) {
-        const int j = lane + 64 * k;
-        x[k] = (need_row && j < d) ? El<BF16>::ld(rsrc, rbase + j) : 0.f;
+    for (int k = 0; k < NG; ++k) {
+        const int j = 4 * (lane + 64 * k);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[k][e] = (need_row && j < d) ? El<BF16>::ld(rsrc, rbase + j + e) : 0.f;
     }
     if (reg > 0.f) {
         float c3 = 0.f;
 #pragma unroll
-        for (int k = 0; k < KGE_MAXJ; ++k) c3 += fabsf(x[k]) * x[k] * x[k];
+        for (int k = 0; k < NG; ++k)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) c3 += fabsf(x[k][e]) * x[k][e] * x[k][e];
         const float nrm = cbrtf(kge_wave_sum(c3));
         f = nrm > 0.f ? reg / (nrm * nrm) : 0.f;
         if (lane == 0) regn[n] = nrm;
     }
+    const bool out16 = ((uintptr_t)g_neg & 15) == 0;        // (d is a multiple of 4: rows of an aligned base are aligned)
 #pragma unroll
-    for (int k = 0; k < KGE_MAXJ; ++k) {
-        const int j = lane + 64 * k;
+    for (int k = 0; k < NG; ++k) {
+        const int j = 4 * (lane + 64 * k);
         if (j >= d) continue;
-        float v = 0.f;
-        for (int s = 0; s < nsplit; ++s) v += accT_part[((size_t)s * Np + n) * dp + j];
-        if (dist_kind) v -= cs * x[k];
-        if (reg > 0.f) v += f * fabsf(x[k]) * x[k];
-        g_neg[(int64_t)n * d + j] = v;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        // two splits are requested together, then added in split order
+        for (int s0 = 0; s0 < nsplit; s0 += 2) {
+            const bool two = s0 + 1 < nsplit;
+            const float4 p0 = *(const float4 *)(accT_part + ((size_t)s0 * Np + n) * dp + j);
+            const float4 p1 = two ? *(const float4 *)(accT_part + ((size_t)(s0 + 1) * Np + n) * dp + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+            v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
+            if (two) { v[0] += p1.x; v[1] += p1.y; v[2] += p1.z; v[3] += p1.w; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (dist_kind) v[e] -= cs * x[k][e];
+            if (reg > 0.f) v[e] += f * fabsf(x[k][e]) * x[k][e];
+        }
+        float *dst = g_neg + (int64_t)n * d + j;
+        if (out16) *(float4 *)dst = make_float4(v[0], v[1], v[2], v[3]);
+        else { dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3]; }
     }
     if (lane == 0) g_neg_idx[n] = neg[n];
 }
@@ -548,9 +571,13 @@ __global__ void kge_chain_kernel(KgeChainArgs a) { kge_chain_body<BF16, SC>(bloc
 // both finishing kernels in ONE launch (the first chain_blocks workgroups run the chain rule of the queries): they
 // read different partials and write different gradient rows
 template <bool BF16, int SC>
-__global__ void kge_chain_tfinish_kernel(int chain_blocks, KgeChainArgs c, KgeTfinishArgs t) {
-    if ((int)blockIdx.x < chain_blocks) kge_chain_body<BF16, SC>(blockIdx.x, c);
-    else kge_tfinish_body<BF16>(blockIdx.x - chain_blocks, t);
+__global__ void kge_chain_tfinish_kernel(int chain_blocks, KgeChainArgs c, KgeTfinishArgs t, const float *lossb, float scale,
+                                         float *loss_out) {
+    // (workgroup 0: the loss of the batch from the rows' losses, the reduction that would otherwise be a launch
+    // of its own between the two passes)
+    if (blockIdx.x == 0) kge_loss_reduce_body(lossb, c.B, scale, loss_out);
+    else if ((int)blockIdx.x <= chain_blocks) kge_chain_body<BF16, SC>(blockIdx.x - 1, c);
+    else kge_tfinish_body<BF16>(blockIdx.x - 1 - chain_blocks, t);
 }
 
 // loss += reg * (sum of the L3 norms of the 2B + N gathered slots): one workgroup of 1024 threads, fixed
@@ -656,7 +683,7 @@ int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N,
     if (Bp > 0)
         hipLaunchKernelGGL(kge_rowfinish_kernel, dim3((Bp + 255) / 256), dim3(256), 0, st, stat_part, nsplit, Bp, B, N,
                            loss, gamma, c_corr, scale, pos, rowinfo, lossb, gpos);
-    hipLaunchKernelGGL(kge_loss_reduce_kernel, dim3(1), dim3(256), 0, st, lossb, B, scale, loss_out);
+    if (loss_out) hipLaunchKernelGGL(kge_loss_reduce_kernel, dim3(1), dim3(256), 0, st, lossb, B, scale, loss_out);
     return kge_launch_status();
 }
 
@@ -691,13 +718,14 @@ int kge_run_chain_tfinish(const KgeModelDev &m, const int32_t *h, const int32_t 
                           const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
                           float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv,
                           const float *accT_part, const float4 *sumT_part, int nsplit_t, int Np, int N, int d, int dist_kind,
-                          const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn, hipStream_t st) {
+                          const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn,
+                          const float *lossb, float scale, float *loss_out, hipStream_t st) {
     if (B == 0 || N == 0) return KGE_E_INVALID_ARG;
     const int cb = (B + 3) / 4, tb = (N + 3) / 4;
     const KgeChainArgs a{m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos,
                          g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv};
     const KgeTfinishArgs f{accT_part, sumT_part, nsplit_t, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, m.ent, m.ent_ld, reg, regn};
-#define KGE_CT(BF, SC) hipLaunchKernelGGL((kge_chain_tfinish_kernel<BF, SC>), dim3(cb + tb), dim3(256), 0, st, cb, a, f)
+#define KGE_CT(BF, SC) hipLaunchKernelGGL((kge_chain_tfinish_kernel<BF, SC>), dim3(1 + cb + tb), dim3(256), 0, st, cb, a, f, lossb, scale, loss_out)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_CT) } else { KGE_SC_SWITCH(false, KGE_CT) }
 #undef KGE_CT
     return kge_launch_status();
