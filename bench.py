@@ -512,8 +512,7 @@ def main():
                 # issues six bf16 matrix products per fp32 one (error about 3 ulp of fp32).  The line stays priced
                 # in ALGORITHMIC fp32 flops against the fp32 matrix peak, the dtype of the contract; the bf16 pipe
                 # does six times that work, against its own peak:
-                roof["issued_bf16"] = {"achieved": 6 * ach, "peak": PEAK_BF16_TFLOPS, "frac": 6 * ach / PEAK_BF16_TFLOPS,
-                                       "note": "upper bound: the two-contraction scorer stays on the fp32 pipe"}
+                roof["issued_bf16"] = {"achieved": 6 * ach, "peak": PEAK_BF16_TFLOPS, "frac": 6 * ach / PEAK_BF16_TFLOPS}
         else:
             roof = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": None, "traffic": None, "avg_us": avg_s * 1e6}

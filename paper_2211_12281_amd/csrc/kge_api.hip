@@ -14,7 +14,7 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
 size_t kge_topk_ws(const kge_model_t &model, int64_t Q, int64_t ncand, int K);
-int kge_launch_score3(int kind, int dp, const void *Qp, const void *Tp, const float *Q32, const float *T32,
+int kge_launch_score3(int kind, int dp, const void *Qp, const void *Tp, const float *Q32, const float *T32, const float *W32,
                       const KgeRowInfo *rowinfo, const float *tn, int B, int N, int Bp, int Np, float *S_out, hipStream_t st);
 int kge_run_partition(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int D, int64_t *offsets,
                       int64_t *order, void *ws, size_t ws_bytes, hipStream_t st);
@@ -109,11 +109,12 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     return g;
 }
 
-// fp32 score blocks of the scorers with ONE contraction per pair go through three bf16 planes on the bf16 matrix pipe
-// (block_f32x3_score.hip); KGE_SCORE_F32_MFMA=1 in the environment keeps the fp32 matrix instructions (cross-check)
+// fp32 score blocks go through three bf16 planes on the bf16 matrix pipe (block_f32x3_score.hip); KGE_SCORE_F32_MFMA=1
+// in the environment (read at every call) keeps the fp32 matrix instructions (cross-check)
 bool score3_applies(const Geometry &g) {
-    static const bool off = [] { const char *e = getenv("KGE_SCORE_F32_MFMA"); return e && e[0] == '1'; }();
-    return !off && !g.bf16 && !g.transh && !g.l1 && (g.dp == 128 || g.dp == 256) && g.N > 0;
+    const char *e = getenv("KGE_SCORE_F32_MFMA");
+    const bool off = e && e[0] == '1';
+    return !off && !g.bf16 && !g.l1 && (g.dp == 128 || g.dp == 256) && g.N > 0;
 }
 
 // bump allocator over the caller's workspace (256-byte granules); with base == nullptr it only sizes
@@ -135,7 +136,7 @@ struct Buffers {
     float *regv;                       // L3 norms of the gathered slots: [Bp heads][Bp tails][Np negatives]
     float *S, *Q32;                    // 1-norm scorers: the score block [Bp][Np], the queries unrounded [Bp][dp]
     float *W32, *A, *P;                // ... TransH: the unit normals unrounded, w^ . t and sign(x) . w^ per pair [Bp][Np]
-    void *Qp3, *Tp3;                   // score-only calls on fp32 tables: three bf16 planes of Q and of T
+    void *Qp3, *Tp3;                   // score-only calls on fp32 tables: three bf16 planes of Q (TransH: and of W) and of T
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -151,7 +152,7 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
     b.W32 = g.l1 && g.transh ? c.take<float>(rowsB) : nullptr;
     b.A = b.P = nullptr;
     b.Qp3 = b.Tp3 = nullptr;
-    if (!bwd && score3_applies(g)) { b.Qp3 = c.take<char>(3 * rowsB * 2); b.Tp3 = c.take<char>(3 * rowsN * 2); }
+    if (!bwd && score3_applies(g)) { b.Qp3 = c.take<char>((g.transh ? 6 : 3) * rowsB * 2); b.Tp3 = c.take<char>(3 * rowsN * 2); }
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
     b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr;
     if (bwd) {
@@ -349,7 +350,8 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
         return kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, nullptr, nullptr, g.N, st);
     if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);
     if (score3_applies(g)) {
-        return kge_launch_score3(g.kind, g.dp, b.Qp3, b.Tp3, (const float *)b.Q, (const float *)b.T, b.rowinfo, b.tn, g.B, g.N,
+        return kge_launch_score3(g.kind, g.dp, b.Qp3, b.Tp3, (const float *)b.Q, (const float *)b.T,
+                                 g.transh ? (const float *)b.W : nullptr, b.rowinfo, b.tn, g.B, g.N,
                                  g.Bp, g.Np, neg_out, st);
     }
     KgeBlockArgs a{};

@@ -45,7 +45,7 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 struct KgeQbuildArgs {
     KgeModelDev m; const int32_t *h, *r, *t; int B, Bp, dp; void *Q, *W, *Q2; float *Q32, *W32; KgeRowInfo *rowinfo;
     float *pos_ws, *pos_out;
-    __bf16 *planes;                    // optional: the three bf16 pieces of q, [3][Bp][dp] (fp32 score blocks on the bf16 pipe)
+    __bf16 *planes;                    // optional: the three bf16 pieces of q, [3][Bp][dp], with W three more for the unit normal
 };
 struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; };
 
@@ -75,6 +75,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
             if (Q32) Q32[(int64_t)b * dp + j] = 0.f;
             if (W32) W32[(int64_t)b * dp + j] = 0.f;
             if (a.planes) kge_store_planes(a.planes, (int64_t)Bp * dp, (int64_t)b * dp + j, 0.f);
+            if (a.planes && W) kge_store_planes(a.planes + 3 * (int64_t)Bp * dp, (int64_t)Bp * dp, (int64_t)b * dp + j, 0.f);
         }
         if (lane == 0) { rowinfo[b] = KgeRowInfo{0.f, 0.f, 0.f, 0.f}; if (pos_ws) pos_ws[b] = 0.f; }
         return;
@@ -99,6 +100,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
             if (Q32) Q32[(int64_t)b * dp + j] = cx.q[k];      // unrounded copies for the 1-norm kernels
             if (W32) W32[(int64_t)b * dp + j] = cx.w[k];
             if (a.planes) kge_store_planes(a.planes, (int64_t)Bp * dp, (int64_t)b * dp + j, cx.q[k]);
+            if (a.planes && W) kge_store_planes(a.planes + 3 * (int64_t)Bp * dp, (int64_t)Bp * dp, (int64_t)b * dp + j, cx.w[k]);
         }
     }
     qn = kge_wave_sum(qn);

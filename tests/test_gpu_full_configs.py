@@ -56,6 +56,29 @@ def test_c2_scoring_all_scorers_full_size(orc):
     _free()
 
 
+@pytest.mark.parametrize("scorer", ["transh", "rotate", "distmult"])
+def test_scoring_fp32_rows_of_128_dimensions_many_tiles_per_workgroup(orc, scorer):
+    """B = 2,048 queries against N = 4,096 negatives at d = 128 (the row size of c5): a workgroup of the score kernel
+    streams eight tiles of queries, more than its ring of stages holds; every score is compared."""
+    import paper_2211_12281_amd as kge
+    n_ent, n_rel, d, B, N = 100_000, 50, 128, 2048, 4096
+    ent = _fill(n_ent, d, torch.float32)
+    g = ks.rng(ks.BASE_SEED, ks.TAG_BATCH, 3)
+    h, r, t = ks.uniform_ids(g, 0, n_ent, B), ks.uniform_ids(g, 0, n_rel, B), ks.uniform_ids(g, 0, n_ent, B)
+    neg = kge.sample_negatives(ks.BASE_SEED, 3, ks.TAG_NEG, 0, n_ent, N)
+    neg_h = neg.cpu().numpy()
+    uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg_h)
+    rows = ks.uniform_rows(ks.BASE_SEED, ks.TAG_ENT, uniq, d, 0.1)
+    rel, relw = ks.relation_tables(scorer, n_rel, d)
+    model = kge.Model(scorer, ent, torch.from_numpy(rel).cuda(), None if relw is None else torch.from_numpy(relw).cuda())
+    pos, blk = kge.score(model, dev_idx(h), dev_idx(r), dev_idx(t), neg)
+    rp, rn = orc.score_batch(scorer, rows, rel, relw, ch, r, ct, cn)
+    assert norm_err(pos.cpu().numpy(), rp) <= RTOL_F32
+    assert norm_err(blk.cpu().numpy(), rn) <= RTOL_F32
+    del ent, model
+    _free()
+
+
 def test_c3_complex_training_step_full_size(orc):
     """10M entities, bf16 compute + fp32 master and moments, Zipf ids, B = 4096, N = 16384, sampled softmax."""
     import paper_2211_12281_amd as kge

@@ -34,6 +34,20 @@ def test_large_rows_fp32_1024_bytes(orc, scorer):
     assert norm_err(pos, rp) <= RTOL_F32 and norm_err(neg, rn) <= RTOL_F32
 
 
+@pytest.mark.parametrize("scorer", SCORERS)
+@pytest.mark.parametrize("dim", [128, 104, 200])
+def test_fp32_tables_on_the_bf16_pipe(orc, scorer, dim, monkeypatch):
+    """fp32 rows padded to 128 or 256 dimensions are contracted as three bf16 pieces per operand: against the oracle,
+    and against the kernel that uses the fp32 matrix instructions (selected through the environment)."""
+    G = make_case(scorer, 4000, 12, dim, 200, 333, False)
+    pos, neg, rp, rn = _run(orc, scorer, G, False)
+    assert norm_err(pos, rp) <= RTOL_F32 and norm_err(neg, rn) <= RTOL_F32
+    monkeypatch.setenv("KGE_SCORE_F32_MFMA", "1")
+    pos2, neg2, _, _ = _run(orc, scorer, G, False)
+    assert norm_err(neg2, rn) <= RTOL_F32
+    assert norm_err(neg, neg2) <= RTOL_F32 and np.array_equal(pos, pos2)
+
+
 @pytest.mark.parametrize("scorer", ["transe", "distmult"])
 def test_edge_shapes(orc, scorer):
     import paper_2211_12281_amd as kge
@@ -55,11 +69,12 @@ def test_edge_shapes(orc, scorer):
 
 
 @pytest.mark.parametrize("scorer", ["transe", "rotate", "transh"])
-@pytest.mark.parametrize("bf16", [False, True])
-def test_near_zero_distances_do_not_cancel(orc, scorer, bf16):
-    """Negatives that (almost) coincide with the query: the norm-expansion form would cancel."""
+@pytest.mark.parametrize("bf16,dim", [(False, 64), (True, 64), (False, 128), (False, 256)])
+def test_near_zero_distances_do_not_cancel(orc, scorer, bf16, dim):
+    """Negatives that (almost) coincide with the query: the norm-expansion form would cancel (fp32 rows of 128 and 256
+    dimensions take the kernels that contract three bf16 pieces per operand: their guard is the same)."""
     import kge_synth as ks
-    G = make_case(scorer, 2000, 5, 64, 40, 70, bf16)
+    G = make_case(scorer, 2000, 5, dim, 40, 70, bf16)
     E = G["ent"].astype(np.float64)
     R = G["rel"].astype(np.float64)
     for b, n in [(0, 0), (1, 5), (39, 69)]:
@@ -67,7 +82,7 @@ def test_near_zero_distances_do_not_cancel(orc, scorer, bf16):
         if scorer == "transe":
             q = h + r
         elif scorer == "rotate":
-            c = 32
+            c = dim // 2
             q = np.r_[h[:c] * np.cos(r) - h[c:] * np.sin(r), h[:c] * np.sin(r) + h[c:] * np.cos(r)]
         else:
             w = G["relw"][G["r"][b]].astype(np.float64); w /= np.linalg.norm(w)
