@@ -134,42 +134,80 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
 // ---------------------------------------------------------------------------------------------
 // gather of the shared negatives: T[n] = ent[neg[n]], tn[n] = ||T[n]||^2 (zeros past N)
 // ---------------------------------------------------------------------------------------------
+// rows of the gathered block that one wave takes: a row of dp elements is covered by dp * ES / 16 lanes with 16 bytes
+// each; 64 / (that, rounded up to a power of two) rows share a load instruction, and FOUR such loads are in flight per
+// lane (a random row costs a full memory round trip: the bytes in flight bound the rate of the gather)
+__host__ __device__ inline int kge_tgather_group_lanes(int dp, int es) {
+    const int lpr = dp * es / 16;
+    int gl = 1;
+    while (gl < lpr) gl <<= 1;
+    return gl < 64 ? gl : 64;
+}
+__host__ __device__ inline int kge_tgather_rows_per_wave(int dp, int es) { return 4 * (64 / kge_tgather_group_lanes(dp, es)); }
+
 template <bool BF16>
 __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T,
                                                  float *tn, __bf16 *planes = nullptr) {
     const int lane = threadIdx.x & 63;
-    const int n = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (n >= Np) return;
-    float s = 0.f;
-    const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
     constexpr int ES = BF16 ? 2 : 4;
     const int lpr = dp * ES / 16;                           // lanes that cover a row with 16 bytes each
+    const int gl = kge_tgather_group_lanes(dp, ES), rpl = 64 / gl, rpw = 4 * rpl;
+    const int nbase = (blk * (blockDim.x >> 6) + (threadIdx.x >> 6)) * rpw;
+    if (nbase >= Np) return;
     if (m.dim == dp && lpr <= 64 && (m.ent_ld * ES) % 16 == 0 && ((uintptr_t)m.ent & 15) == 0) {
-        // unpadded, 16-byte aligned rows: ONE load per lane (the row's round trip to memory is paid once, not dp / 64 times)
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (n < N && lane < lpr) v = *(const uint4 *)((const char *)m.ent + off * ES + lane * 16);
-        if (lane < lpr) *(uint4 *)((char *)T + ((int64_t)n * dp) * ES + lane * 16) = v;
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        // unpadded, 16-byte aligned rows: ONE load per lane and row, four rows (groups of rows) requested together
+        const int grp = lane / gl, lg = lane % gl;
+        uint4 v[4];
+        int64_t off[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if constexpr (BF16) {
-                const float a0 = __uint_as_float(w[k] << 16), a1 = __uint_as_float(w[k] & 0xffff0000u);
-                s += a0 * a0; s += a1 * a1;
-            } else {
-                const float a0 = __uint_as_float(w[k]); s += a0 * a0;
-                if (planes && lane < lpr) kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + lane * 4 + k, a0);
-            }
+        for (int u = 0; u < 4; ++u) {
+            const int n = nbase + u * rpl + grp;
+            off[u] = n < N ? (int64_t)neg[n] * m.ent_ld : -1;
         }
-    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            v[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (off[u] >= 0 && lg < lpr) v[u] = *(const uint4 *)((const char *)m.ent + off[u] * ES + lg * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int n = nbase + u * rpl + grp;
+            const bool live = n < Np && lg < lpr;
+            if (live) *(uint4 *)((char *)T + ((int64_t)n * dp) * ES + lg * 16) = v[u];
+            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if constexpr (BF16) {
+                    const float a0 = __uint_as_float(w[k] << 16), a1 = __uint_as_float(w[k] & 0xffff0000u);
+                    s += a0 * a0; s += a1 * a1;
+                } else {
+                    const float a0 = __uint_as_float(w[k]); s += a0 * a0;
+                    if (planes && live) kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + lg * 4 + k, a0);
+                }
+            }
+            // sum over the lanes of the row's group (fixed order)
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1)
+                if (o < gl) s += __shfl_xor(s, o);
+            if (lg == 0 && n < Np) tn[n] = s;
+        }
+        return;
+    }
+    for (int u = 0; u < rpw; ++u) {
+        const int n = nbase + u;
+        if (n >= Np) break;                                 // (wave-uniform)
+        const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
+        float s = 0.f;
         for (int j = lane; j < dp; j += 64) {
             float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
             El<BF16>::st(T, (int64_t)n * dp + j, v);
             if (!BF16 && planes) kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + j, v);
             s += v * v;
         }
+        s = kge_wave_sum(s);
+        if (lane == 0) tn[n] = s;
     }
-    s = kge_wave_sum(s);
-    if (lane == 0) tn[n] = s;
 }
 template <bool BF16>
 __global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, __bf16 *planes) {
@@ -639,7 +677,8 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st) {
-    const int qb = (Bp + 3) / 4, tb = (Np + 3) / 4;
+    const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
+    const int qb = (Bp + 3) / 4, tb = (Np + rows_wg - 1) / rows_wg;
     if (qb == 0 || tb == 0) return KGE_E_INVALID_ARG;
     const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, nullptr, nullptr};
     const KgeTgatherArgs g{neg, N, Np, T, tn};
@@ -650,7 +689,8 @@ int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t
 }
 
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, hipStream_t st, void *planes) {
-    const int grid = (Np + 3) / 4;
+    const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
+    const int grid = (Np + rows_wg - 1) / rows_wg;
     if (grid == 0) return KGE_OK;
     if (planes && m.bf16) return KGE_E_INVALID_ARG;
     if (m.bf16) hipLaunchKernelGGL(kge_tgather_kernel<true>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn, (__bf16 *)nullptr);
