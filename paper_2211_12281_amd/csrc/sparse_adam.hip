@@ -192,10 +192,11 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
 // The association order is a function of the sorted positions only: results are run-to-run identical.
 
 // A: one wave per sorted position.
-__global__ void adam_interior_kernel(const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads, int dim,
-                                     int64_t ld, float *param, uint16_t *shadow, float *mom, float *var, AdamConst c) {
+__device__ __forceinline__ void adam_interior_body(int64_t blk, const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads,
+                                                   int dim, int64_t ld, float *param, uint16_t *shadow, float *mom, float *var,
+                                                   const AdamConst &c) {
     const int lane = threadIdx.x & 63;
-    const int64_t i = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t i = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (i >= M) return;
     const uint32_t key = sk[i];
     if (i > 0 && sk[i - 1] == key) return;                 // not the first position of its segment
@@ -214,10 +215,10 @@ __global__ void adam_interior_kernel(const uint32_t *sk, const uint32_t *sp, int
 // B1: one wave per chunk; partial sums of its boundary-crossing pieces.
 //   part[2k]   : the run at the chunk start when it continues a segment from chunk k-1
 //   part[2k+1] : the run that reaches the chunk end and continues into chunk k+1, unless it is part[2k]
-__global__ void adam_piece_kernel(const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads, int dim,
-                                  float *part) {
+__device__ __forceinline__ void adam_piece_body(int64_t blk, const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads,
+                                                int dim, float *part) {
     const int lane = threadIdx.x & 63;
-    const int64_t k = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t k = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int64_t c0 = k * SEG_CHUNK;
     if (c0 >= M) return;
     const int64_t c1 = c0 + SEG_CHUNK < M ? c0 + SEG_CHUNK : M;
@@ -242,6 +243,14 @@ __global__ void adam_piece_kernel(const uint32_t *sk, const uint32_t *sp, int64_
         for (int col = lane * 4; col < dim; col += 256)
             *(float4 *)(part + (2 * k + 1) * (int64_t)dim + col) = reduce_rows(sp, c0 + start, c1, grads, dim, col);
     }
+}
+
+// A and B1 in ONE launch (they read the same sorted gradients and write different things: A the rows of the segments
+// inside a chunk, B1 the piece sums): the first piece_blocks workgroups run B1, whose few long runs then start first
+__global__ void adam_interior_kernel(int piece_blocks, const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads, int dim,
+                                     int64_t ld, float *param, uint16_t *shadow, float *mom, float *var, float *part, AdamConst c) {
+    if ((int)blockIdx.x < piece_blocks) adam_piece_body(blockIdx.x, sk, sp, M, grads, dim, part);
+    else adam_interior_body((int64_t)blockIdx.x - piece_blocks, sk, sp, M, grads, dim, ld, param, shadow, mom, var, c);
 }
 
 // B2: one wave per chunk; if a boundary-crossing segment STARTS in this chunk, add its pieces and update.
@@ -375,12 +384,11 @@ int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, in
     sort_carve(M, dim, ws, s);                              // the piece buffer lies behind the sort buffers
     KgeProfScope prof(KGE_PROF_ADAM, st);
     const int grid = (int)((M + 3) / 4);
-    hipLaunchKernelGGL(adam_interior_kernel, dim3(grid), dim3(256), 0, st, sk, sp, M, grads, dim, ld, param,
-                       (uint16_t *)shadow, m, v, c);
     const int64_t nchunk = (M + SEG_CHUNK - 1) / SEG_CHUNK;
+    const int gridc = nchunk > 1 ? (int)((nchunk + 3) / 4) : 0;
+    hipLaunchKernelGGL(adam_interior_kernel, dim3(gridc + grid), dim3(256), 0, st, gridc, sk, sp, M, grads, dim, ld, param,
+                       (uint16_t *)shadow, m, v, s.part, c);
     if (nchunk > 1) {
-        const int gridc = (int)((nchunk + 3) / 4);
-        hipLaunchKernelGGL(adam_piece_kernel, dim3(gridc), dim3(256), 0, st, sk, sp, M, grads, dim, s.part);
         hipLaunchKernelGGL(adam_boundary_kernel, dim3(gridc), dim3(256), 0, st, sk, M, dim, ld, s.part, param,
                            (uint16_t *)shadow, m, v, c);
     }
