@@ -334,8 +334,11 @@ size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t 
 
 /*
  * Optional instrumentation for benchmarks: while enabled, the library brackets the launches of its
- * dominant kernels with HIP events on the caller's stream.  kge_profile_collect() waits for the
- * recorded events of one slot, returns their summed duration and count, and forgets them.
+ * dominant kernels with HIP events on the caller's stream.  kge_profile_enable(on): 0 switches it off,
+ * a negative value instruments every slot, a positive value is a bit mask (bit s = slot s; two event
+ * records per instrumented launch cost host time, so a timed run may want the slot it reports only).
+ * kge_profile_collect() waits for the recorded events of one slot, returns their summed duration and
+ * count, and forgets them.
  * Host-side state shared by all callers of the process; not thread-safe; off by default.
  */
 enum { KGE_PROF_BLOCK_SCORE = 0, KGE_PROF_BLOCK_FWD = 1, KGE_PROF_BLOCK_GRADT = 2, KGE_PROF_ADAM = 3,

@@ -119,8 +119,10 @@ def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
-def _stream():
-    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+def _stream(stream=None):
+    """The HIP stream of a call: torch's current one, or the given torch.cuda.Stream (saves the lookup and the
+    stream context around the call)."""
+    return C.c_void_p((stream if stream is not None else torch.cuda.current_stream()).cuda_stream)
 
 
 def _i32(t):
@@ -177,10 +179,10 @@ def workspace_bytes(op: int, model: Model | None, B: int, N: int, K: int = 0) ->
     return int(load().kge_workspace_bytes(op, model.ref if model is not None else None, B, N, K))
 
 
-def sample_negatives(seed: int, step: int, tag: int, lo: int, hi: int, n: int, out=None):
+def sample_negatives(seed: int, step: int, tag: int, lo: int, hi: int, n: int, out=None, stream=None):
     if out is None:
         out = torch.empty(n, dtype=torch.int32, device="cuda")
-    _check(load().kge_sample_negatives(seed, step, tag, lo, hi, n, _ptr(out), _stream()), "kge_sample_negatives")
+    _check(load().kge_sample_negatives(seed, step, tag, lo, hi, n, _ptr(out), _stream(stream)), "kge_sample_negatives")
     return out
 
 
@@ -198,7 +200,7 @@ def score(model: Model, h, r, t, neg, want_neg: bool = True, ws: Workspace | Non
 
 def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp: float = 0.0,
              loss_scale: float = 0.0, n_ent_for_c: int = 0, ws: Workspace | None = None, out=None,
-             reg_l3: float = 0.0):
+             reg_l3: float = 0.0, stream=None):
     B, N, d = h.numel(), neg.numel(), model.dim
     k = model.rel.shape[1]
     if out is None:
@@ -216,7 +218,7 @@ def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp
     _check(load().kge_loss_bwd(model.ref, C.byref(cfg), _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B,
                                _ptr(_i32(neg)), N, _ptr(out["loss"]), _ptr(out["g_ent"]), _ptr(out["g_ent_idx"]),
                                _ptr(out["g_rel"]), _ptr(out["g_relw"]), _ptr(out["g_rel_idx"]), _ptr(buf),
-                               buf.numel(), _stream()), "kge_loss_bwd")
+                               buf.numel(), _stream(stream)), "kge_loss_bwd")
     return out
 
 
@@ -236,16 +238,16 @@ def sparse_adam(param, shadow, m, v, idx, grads, lr: float, beta1: float = 0.9, 
            "kge_sparse_adam")
 
 
-def sparse_adam_plan(n_rows: int, dim: int, idx, ws: Workspace):
+def sparse_adam_plan(n_rows: int, dim: int, idx, ws: Workspace, stream=None):
     """Sorts the row ids of a later sparse_adam_apply into `ws` (which must be kept for that call alone)."""
     M = idx.numel()
     buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, dim))
-    _check(load().kge_sparse_adam_plan(n_rows, dim, _ptr(_i32(idx)), M, _ptr(buf), buf.numel(), _stream()),
+    _check(load().kge_sparse_adam_plan(n_rows, dim, _ptr(_i32(idx)), M, _ptr(buf), buf.numel(), _stream(stream)),
            "kge_sparse_adam_plan")
 
 
 def sparse_adam_apply(param, shadow, m, v, grads, ws: Workspace, lr: float, beta1: float = 0.9, beta2: float = 0.999,
-                      eps: float = 1e-8, step: int = 1):
+                      eps: float = 1e-8, step: int = 1, stream=None):
     assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
     assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
     assert m.stride() == param.stride() and v.stride() == param.stride()
@@ -255,7 +257,7 @@ def sparse_adam_apply(param, shadow, m, v, grads, ws: Workspace, lr: float, beta
     cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step)
     buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, d))
     _check(load().kge_sparse_adam_apply(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
-                                        _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream()),
+                                        _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream(stream)),
            "kge_sparse_adam_apply")
 
 
@@ -282,8 +284,15 @@ def ensemble(lists, p: float, K_out: int = 10):
     return out_idx, out_score
 
 
-def profile_enable(on: bool):
-    _check(load().kge_profile_enable(1 if on else 0), "kge_profile_enable")
+def profile_enable(on):
+    """True / False: every instrumented kernel / none; a list of slot names: those only."""
+    if isinstance(on, (list, tuple, set)):
+        mask = 0
+        for s in on:
+            mask |= 1 << PROF_SLOTS[s]
+    else:
+        mask = -1 if on else 0
+    _check(load().kge_profile_enable(mask), "kge_profile_enable")
 
 
 def profile_collect(slot: str):

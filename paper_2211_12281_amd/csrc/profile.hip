@@ -4,7 +4,7 @@
 
 namespace {
 struct Rec { int slot; hipEvent_t a, b; };
-bool g_enabled = false;
+unsigned g_mask = 0;                     // bit s: slot s is instrumented
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 
@@ -17,7 +17,7 @@ hipEvent_t get_event() {
 }  // namespace
 
 KgeProfScope::KgeProfScope(int slot, hipStream_t st) : slot_(slot), st_(st), a_(nullptr), b_(nullptr) {
-    if (!g_enabled) return;
+    if (!((g_mask >> slot) & 1u)) return;
     a_ = get_event(); b_ = get_event();
     if (a_ && b_) (void)hipEventRecord((hipEvent_t)a_, st_);
 }
@@ -29,7 +29,7 @@ KgeProfScope::~KgeProfScope() {
 }
 
 extern "C" int kge_profile_enable(int on) {
-    g_enabled = on != 0;
+    g_mask = on < 0 ? ~0u : (unsigned)on;
     return KGE_OK;
 }
 
