@@ -342,10 +342,13 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     if (carve(g, false, nullptr, b) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     carve(g, false, ws, b);
     KgeModelDev md = dev_model(*model);
-    rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st, b.Qp3);
+    // (queries and negatives from one launch when there is a block to score)
+    if (block && g.Bp > 0)
+        rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, neg, g.N, g.Np,
+                                    b.T, b.tn, st, pos_out, b.Qp3, b.Tp3);
+    else
+        rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st, b.Qp3);
     if (rc != KGE_OK || !block) return rc;
-    rc = kge_run_tgather(md, neg, g.N, g.Np, g.dp, b.T, b.tn, st, b.Tp3);
-    if (rc != KGE_OK) return rc;
     if (g.l1 && g.transh)
         return kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, nullptr, nullptr, g.N, st);
     if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);

@@ -21,7 +21,8 @@ int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int
 // the two above as ONE launch (Bp > 0 and Np > 0; no positive scores out)
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
-                           const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st);
+                           const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out = nullptr,
+                           void *q_planes = nullptr, void *t_planes = nullptr);
 // gather of the negatives and their transposed copy Tt [dp][Np] in one launch
 int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
                       hipStream_t st);

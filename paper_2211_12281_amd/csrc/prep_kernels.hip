@@ -47,7 +47,7 @@ struct KgeQbuildArgs {
     float *pos_ws, *pos_out;
     __bf16 *planes;                    // optional: the three bf16 pieces of q, [3][Bp][dp], with W three more for the unit normal
 };
-struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; };
+struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; __bf16 *planes; };
 
 // x = x1 + x2 + x3 in bf16 (each piece the rounding of what the previous ones leave): plane p of element i at planes[p n + i]
 __device__ __forceinline__ void kge_store_planes(__bf16 *planes, int64_t n, int64_t i, float x) {
@@ -220,7 +220,7 @@ __global__ void kge_qbuild_kernel(KgeQbuildArgs a) { kge_qbuild_body<BF16, SC>(b
 template <bool BF16, int SC>
 __global__ void kge_qbuild_tgather_kernel(int q_blocks, KgeQbuildArgs a, KgeTgatherArgs g) {
     if ((int)blockIdx.x < q_blocks) kge_qbuild_body<BF16, SC>(blockIdx.x, a);
-    else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn);
+    else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn, g.planes);
 }
 
 // gather of the shared negatives AND their transposed copy in one launch: a workgroup takes 32 negatives, every
@@ -676,12 +676,13 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
 // kge_run_qbuild and kge_run_tgather as one launch (both Bp > 0 and Np > 0)
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
-                           const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st) {
+                           const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out,
+                           void *q_planes, void *t_planes) {
     const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
     const int qb = (Bp + 3) / 4, tb = (Np + rows_wg - 1) / rows_wg;
-    if (qb == 0 || tb == 0) return KGE_E_INVALID_ARG;
-    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, nullptr, nullptr};
-    const KgeTgatherArgs g{neg, N, Np, T, tn};
+    if (qb == 0 || tb == 0 || ((q_planes || t_planes) && m.bf16)) return KGE_E_INVALID_ARG;
+    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (__bf16 *)q_planes};
+    const KgeTgatherArgs g{neg, N, Np, T, tn, (__bf16 *)t_planes};
 #define KGE_QT(BF, SC) hipLaunchKernelGGL((kge_qbuild_tgather_kernel<BF, SC>), dim3(qb + tb), dim3(256), 0, st, qb, a, g)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QT) } else { KGE_SC_SWITCH(false, KGE_QT) }
 #undef KGE_QT
