@@ -53,6 +53,20 @@ def test_host_only_entry_points(lib):
                          ctypes.c_size_t(0), None) == -1
 
 
+def test_profile_slots_are_selected_by_mask(lib):
+    """kge_profile_enable: 0 off, negative every slot, positive a bit mask of slots; nothing is recorded without a GPU
+    call, so collecting returns zero launches."""
+    import paper_2211_12281_amd as kge
+    for on in (True, ["block_fwd"], ["adam", "sort"], False):
+        kge.profile_enable(on)
+    with pytest.raises(KeyError):
+        kge.profile_enable(["no_such_slot"])
+    kge.profile_enable(False)
+    ms, n = ctypes.c_double(1.0), ctypes.c_int64(7)
+    assert lib.kge_profile_collect(1, ctypes.byref(ms), ctypes.byref(n)) == 0 and n.value == 0 and ms.value == 0.0
+    assert lib.kge_profile_collect(99, ctypes.byref(ms), ctypes.byref(n)) == -1
+
+
 def test_alignment_rules_are_checked_on_the_host(lib):
     """Misaligned table pointers are refused before anything is launched (fake addresses: nothing dereferences them)."""
     import paper_2211_12281_amd.binding as b

@@ -148,3 +148,36 @@ def test_plan_on_a_side_stream_then_apply_is_bitwise_the_single_call():
     torch.cuda.synchronize()
     for a, b in zip(ref + [sh_ref], two + [sh_two]):
         assert bool((a == b).all())
+
+
+def test_streams_passed_as_arguments_give_the_same_bits():
+    """The binding takes the stream of a call as an argument (no stream context on the host): plan on a side stream,
+    apply on the main one, both named explicitly, against the single call on the current stream; with the kernels of
+    the update bracketed by the library's events on the given stream."""
+    import paper_2211_12281_amd as kge
+    n_rows, d, M = 30000, 128, 5000
+    g = np.random.default_rng(11)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    ws = kge.Workspace()
+    ref = [torch.from_numpy(x).cuda() for x in _state(n_rows, d, 3, True)]
+    two = [x.clone() for x in ref]
+    ev_ids, ev_plan = torch.cuda.Event(), torch.cuda.Event()
+    kge.profile_enable(["adam"])
+    for step in (1, 2):
+        idx = torch.from_numpy(ks.ZipfIds(n_rows, 1.1).draw(g, M)).cuda()
+        grads = torch.from_numpy((g.normal(size=(M, d)) * 1e-2).astype(F)).cuda()
+        kge.sparse_adam(ref[0], None, ref[1], ref[2], idx, grads, 1e-3, step=step)
+        ev_ids.record(main)
+        side.wait_event(ev_ids)
+        kge.sparse_adam_plan(n_rows, d, idx, ws, stream=side)
+        ev_plan.record(side)
+        main.wait_event(ev_plan)
+        kge.sparse_adam_apply(two[0], None, two[1], two[2], grads, ws, 1e-3, step=step, stream=main)
+    torch.cuda.synchronize()
+    kge.profile_enable(False)
+    ms, n = kge.profile_collect("adam")
+    assert n == 4 and ms > 0.0                 # two single calls + two applies; the plans belong to the slot "sort"
+    assert kge.profile_collect("sort")[1] == 0  # (not selected)
+    for a, b in zip(ref, two):
+        assert bool((a == b).all())
+
