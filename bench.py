@@ -438,6 +438,10 @@ class RankWorkload:
                 "sample": f"first {nq} of {self.Q} queries against all {self.n_ent} entities, top-{self.K} + rank"}
 
 
+def wl_bf16(wl):
+    return bool(getattr(wl, "bf16", False))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -581,6 +585,11 @@ def main():
                     roof["traffic"] = tr          # HBM bytes per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
             except (ValueError, OSError):
                 pass
+    # the same box's own figures beside the published peaks: a loop of independent bf16 matrix instructions and a plain
+    # 1 GiB streaming copy (after the timed region; a few milliseconds)
+    calib = {"mfma_bf16_loop_tflops": kge.calibrate_mfma(), "copy_gbs": kge.calibrate_copy(1 << 30)}
+    if roof is not None and roof.get("achieved") is not None and roof["bound"] == "mfma" and wl_bf16(wl):
+        roof["frac_of_measured_loop"] = roof["achieved"] / calib["mfma_bf16_loop_tflops"]
     pairs = wl.pairs_per_step()
     line = {
         "metric": "scored (query,candidate) pairs/s", "value": pairs / (ms * 1e-3), "unit": "pairs/s",
@@ -588,7 +597,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": P["dtype"], "data": "synthetic",
         "config": {"workload": a.workload, **{k: v for k, v in P.items() if k in
                                               ("n_ent", "n_rel", "dim", "B", "N", "Q", "K", "loss")}},
-        "roofline": roof, "cpu_baseline": cpu, "kernels": prof,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": prof, "calibration": calib,
     }
     line["host_enqueue_ms_per_step"] = dt_host * 1e3 / a.steps
     line.update(wl.extra(ms))

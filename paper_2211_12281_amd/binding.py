@@ -20,7 +20,8 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
            "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble", "kge_sparse_adam_plan",
            "kge_sparse_adam_apply",
-           "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect"]
+           "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
+           "kge_calibrate_mfma", "kge_calibrate_copy"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7}
 
@@ -77,6 +78,8 @@ def load():
                                                      C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         lib.kge_workspace_bytes.restype = C.c_size_t
         lib.kge_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
+        lib.kge_calibrate_mfma.argtypes = [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        lib.kge_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.kge_status_string.restype = C.c_char_p
         lib.kge_status_string.argtypes = [C.c_int]
         lib.kge_sample_negatives.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
@@ -300,6 +303,24 @@ def profile_collect(slot: str):
     ms, n = C.c_double(0.0), C.c_int64(0)
     _check(load().kge_profile_collect(PROF_SLOTS[slot], C.byref(ms), C.byref(n)), "kge_profile_collect")
     return ms.value, n.value
+
+
+def calibrate_mfma(iters: int = 4096) -> float:
+    """TFLOP/s of a loop of independent bf16 matrix instructions on this GPU (synchronises the stream)."""
+    sink = torch.empty(2048 * 512, dtype=torch.float32, device="cuda")
+    out = C.c_double(0.0)
+    _check(load().kge_calibrate_mfma(iters, _ptr(sink), sink.numel(), C.byref(out), _stream()), "kge_calibrate_mfma")
+    return out.value
+
+
+def calibrate_copy(nbytes: int = 1 << 30) -> float:
+    """GB/s (read + written) of a plain streaming copy of nbytes on this GPU (synchronises the stream)."""
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").zero_()
+    dst = torch.empty_like(src)
+    out = C.c_double(0.0)
+    _check(load().kge_calibrate_copy(_ptr(src), _ptr(dst), C.c_size_t(src.numel() * 4), C.byref(out), _stream()),
+           "kge_calibrate_copy")
+    return out.value
 
 
 def partition_triples(h, t, part_size: int, D: int, ws: Workspace | None = None):

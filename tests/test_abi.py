@@ -67,6 +67,15 @@ def test_profile_slots_are_selected_by_mask(lib):
     assert lib.kge_profile_collect(99, ctypes.byref(ms), ctypes.byref(n)) == -1
 
 
+def test_calibration_calls_validate_their_arguments(lib):
+    out = ctypes.c_double(0.0)
+    assert lib.kge_calibrate_mfma(0, None, ctypes.c_int64(0), ctypes.byref(out), None) == -1
+    assert lib.kge_calibrate_mfma(16, ctypes.c_void_p(4096), ctypes.c_int64(1000), ctypes.byref(out), None) == -1   # sink too small
+    assert lib.kge_calibrate_copy(None, None, ctypes.c_size_t(1 << 20), ctypes.byref(out), None) == -1
+    assert lib.kge_calibrate_copy(ctypes.c_void_p(4096), ctypes.c_void_p(8200), ctypes.c_size_t(1 << 20), ctypes.byref(out),
+                                  None) == -1                                                                      # unaligned
+
+
 def test_alignment_rules_are_checked_on_the_host(lib):
     """Misaligned table pointers are refused before anything is launched (fake addresses: nothing dereferences them)."""
     import paper_2211_12281_amd.binding as b
