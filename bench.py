@@ -588,6 +588,14 @@ def main():
     # the same box's own figures beside the published peaks: a loop of independent bf16 matrix instructions and a plain
     # 1 GiB streaming copy (after the timed region; a few milliseconds)
     calib = {"mfma_bf16_loop_tflops": kge.calibrate_mfma(), "copy_gbs": kge.calibrate_copy(1 << 30)}
+    # what two HIP events read when NOTHING lies between them: the share of a bracketed kernel's duration that is the
+    # bracket's own (the rocprofv3 trace of the same command shows the kernel without it)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tot = 0.0
+    for _ in range(20):
+        e0.record(); e1.record(); e1.synchronize()
+        tot += e0.elapsed_time(e1)
+    calib["empty_event_pair_us"] = tot / 20 * 1e3
     if roof is not None and roof.get("achieved") is not None and roof["bound"] == "mfma" and wl_bf16(wl):
         roof["frac_of_measured_loop"] = roof["achieved"] / calib["mfma_bf16_loop_tflops"]
     pairs = wl.pairs_per_step()
