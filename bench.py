@@ -445,7 +445,7 @@ def wl_bf16(wl):
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (see DESIGN.md, sharding)",
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are built: the path shards by entity partition, one worker per GPU)",
               file=sys.stderr)
         sys.exit(2)
     import torch
