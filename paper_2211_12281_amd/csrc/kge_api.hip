@@ -14,8 +14,9 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
 size_t kge_topk_ws(const kge_model_t &model, int64_t Q, int64_t ncand, int K);
-int kge_launch_score3(int kind, int dp, const void *Qp, const void *Tp, const float *Q32, const float *T32, const float *W32,
-                      const KgeRowInfo *rowinfo, const float *tn, int B, int N, int Bp, int Np, float *S_out, hipStream_t st);
+int kge_launch_score_h2(int kind, int dp, const void *Qp, const void *Tp, const float *t_inv, const float *Q32, const float *T32,
+                        const float *W32, const KgeRowInfo *rowinfo, const float *tn, int B, int N, int Bp, int Np, float *S_out,
+                        hipStream_t st);
 int kge_run_partition(const int32_t *h, const int32_t *t, int64_t n, int64_t part_size, int D, int64_t *offsets,
                       int64_t *order, void *ws, size_t ws_bytes, hipStream_t st);
 size_t kge_partition_ws(int64_t n, int D);
@@ -109,7 +110,7 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     return g;
 }
 
-// fp32 score blocks go through three bf16 planes on the bf16 matrix pipe (block_f32x3_score.hip); KGE_SCORE_F32_MFMA=1
+// fp32 score blocks go through two fp16 planes on the 16-bit matrix pipe (block_f32h2_score.hip); KGE_SCORE_F32_MFMA=1
 // in the environment (read at every call) keeps the fp32 matrix instructions (cross-check)
 bool score3_applies(const Geometry &g) {
     const char *e = getenv("KGE_SCORE_F32_MFMA");
@@ -136,7 +137,8 @@ struct Buffers {
     float *regv;                       // L3 norms of the gathered slots: [Bp heads][Bp tails][Np negatives]
     float *S, *Q32;                    // 1-norm scorers: the score block [Bp][Np], the queries unrounded [Bp][dp]
     float *W32, *A, *P;                // ... TransH: the unit normals unrounded, w^ . t and sign(x) . w^ per pair [Bp][Np]
-    void *Qp3, *Tp3;                   // score-only calls on fp32 tables: three bf16 planes of Q (TransH: and of W) and of T
+    void *Qp3, *Tp3;                   // score-only calls on fp32 tables: two fp16 planes of the scaled Q (TransH: and of W) and T
+    float *t_inv;                      // ... 1 / scale of the rows of T
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -151,8 +153,10 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
     b.Q32 = g.l1 ? c.take<float>(rowsB) : nullptr;
     b.W32 = g.l1 && g.transh ? c.take<float>(rowsB) : nullptr;
     b.A = b.P = nullptr;
-    b.Qp3 = b.Tp3 = nullptr;
-    if (!bwd && score3_applies(g)) { b.Qp3 = c.take<char>((g.transh ? 6 : 3) * rowsB * 2); b.Tp3 = c.take<char>(3 * rowsN * 2); }
+    b.Qp3 = b.Tp3 = nullptr; b.t_inv = nullptr;
+    if (!bwd && score3_applies(g)) {
+        b.Qp3 = c.take<char>((g.transh ? 4 : 2) * rowsB * 2); b.Tp3 = c.take<char>(2 * rowsN * 2); b.t_inv = c.take<float>(g.Np);
+    }
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
     b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr;
     if (bwd) {
@@ -345,7 +349,7 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     // (queries and negatives from one launch when there is a block to score)
     if (block && g.Bp > 0)
         rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, neg, g.N, g.Np,
-                                    b.T, b.tn, st, pos_out, b.Qp3, b.Tp3);
+                                    b.T, b.tn, st, pos_out, b.Qp3, b.Tp3, b.t_inv);
     else
         rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st, b.Qp3);
     if (rc != KGE_OK || !block) return rc;
@@ -353,7 +357,7 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
         return kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, nullptr, nullptr, g.N, st);
     if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);
     if (score3_applies(g)) {
-        return kge_launch_score3(g.kind, g.dp, b.Qp3, b.Tp3, (const float *)b.Q, (const float *)b.T,
+        return kge_launch_score_h2(g.kind, g.dp, b.Qp3, b.Tp3, b.t_inv, (const float *)b.Q, (const float *)b.T,
                                  g.transh ? (const float *)b.W : nullptr, b.rowinfo, b.tn, g.B, g.N,
                                  g.Bp, g.Np, neg_out, st);
     }

@@ -15,14 +15,16 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                    int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                    float *pos_out, hipStream_t st, void *planes = nullptr);
-// planes (fp32 tables only, optional): also the three bf16 pieces of every element, [3][rows][dp]
+// planes (fp32 tables only, optional): also the two fp16 pieces of every element of the rows scaled by a power of two,
+// [2][rows][dp], and 1 / scale of every row in inv_scale
+constexpr float KGE_PLANE_UNIT_SCALE = 1024.f;      // scale of the planes of TransH's unit normals (all rows)
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
-                    hipStream_t st, void *planes = nullptr);
+                    hipStream_t st, void *planes = nullptr, float *inv_scale = nullptr);
 // the two above as ONE launch (Bp > 0 and Np > 0; no positive scores out)
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out = nullptr,
-                           void *q_planes = nullptr, void *t_planes = nullptr);
+                           void *q_planes = nullptr, void *t_planes = nullptr, float *t_inv_scale = nullptr);
 // gather of the negatives and their transposed copy Tt [dp][Np] in one launch
 int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
                       hipStream_t st);

@@ -45,16 +45,26 @@ int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, in
 struct KgeQbuildArgs {
     KgeModelDev m; const int32_t *h, *r, *t; int B, Bp, dp; void *Q, *W, *Q2; float *Q32, *W32; KgeRowInfo *rowinfo;
     float *pos_ws, *pos_out;
-    __bf16 *planes;                    // optional: the three bf16 pieces of q, [3][Bp][dp], with W three more for the unit normal
+    _Float16 *planes;                  // optional: the two fp16 pieces of the scaled q, [2][Bp][dp], with W two more for the
+                                       // unit normal (scaled by KGE_PLANE_UNIT_SCALE); then rowinfo.K = 1 / scale of the row
 };
-struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; __bf16 *planes; };
+struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; _Float16 *planes; float *inv_scale; };
 
-// x = x1 + x2 + x3 in bf16 (each piece the rounding of what the previous ones leave): plane p of element i at planes[p n + i]
-__device__ __forceinline__ void kge_store_planes(__bf16 *planes, int64_t n, int64_t i, float x) {
-    const __bf16 x1 = (__bf16)x;
-    const float r1 = x - (float)x1;
-    const __bf16 x2 = (__bf16)r1;
-    planes[i] = x1; planes[n + i] = x2; planes[2 * n + i] = (__bf16)(r1 - (float)x2);
+// fp32 rows as TWO fp16 planes for the matrix cores: the row is scaled by a power of two s that brings its largest
+// magnitude into [2^10, 2^11) (well inside the fp16 range, with the second piece of every element that matters still
+// normal), then s x = x1 + x2 with x1 = fp16(s x), x2 = fp16(s x - x1): 22 significand bits, residual < 2^-22 s |x|.
+// Plane p of element i at planes[p n + i]; the contraction is multiplied by the two rows' 1 / s afterwards (exact).
+__device__ __forceinline__ float kge_plane_scale(float amax, float &inv) {
+    if (!(amax > 0.f)) { inv = 1.f; return 1.f; }
+    int e;
+    (void)frexpf(amax, &e);                                 // amax = f 2^e, f in [0.5, 1)
+    e = e < -100 ? -100 : (e > 100 ? 100 : e);
+    inv = ldexpf(1.f, e - 11);
+    return ldexpf(1.f, 11 - e);
+}
+__device__ __forceinline__ void kge_store_planes(_Float16 *planes, int64_t n, int64_t i, float xs) {
+    const _Float16 x1 = (_Float16)xs;
+    planes[i] = x1; planes[n + i] = (_Float16)(xs - (float)x1);
 }
 
 template <bool BF16, int SC>
@@ -75,9 +85,9 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
             if (Q32) Q32[(int64_t)b * dp + j] = 0.f;
             if (W32) W32[(int64_t)b * dp + j] = 0.f;
             if (a.planes) kge_store_planes(a.planes, (int64_t)Bp * dp, (int64_t)b * dp + j, 0.f);
-            if (a.planes && W) kge_store_planes(a.planes + 3 * (int64_t)Bp * dp, (int64_t)Bp * dp, (int64_t)b * dp + j, 0.f);
+            if (a.planes && W) kge_store_planes(a.planes + 2 * (int64_t)Bp * dp, (int64_t)Bp * dp, (int64_t)b * dp + j, 0.f);
         }
-        if (lane == 0) { rowinfo[b] = KgeRowInfo{0.f, 0.f, 0.f, 0.f}; if (pos_ws) pos_ws[b] = 0.f; }
+        if (lane == 0) { rowinfo[b] = KgeRowInfo{0.f, 0.f, a.planes ? 1.f : 0.f, 0.f}; if (pos_ws) pos_ws[b] = 0.f; }
         return;
     }
     KgeRowCtx<BF16> cx;
@@ -86,6 +96,13 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
     const int64_t toff = (int64_t)t[b] * m.ent_ld;
     float qn = 0.f, cq = 0.f, wn = 0.f, s_pos = 0.f, wt = 0.f;
     float tv[KGE_MAXJ];
+    float q_scale = 1.f, q_inv = 0.f;
+    if (a.planes) {
+        float amax = 0.f;
+#pragma unroll
+        for (int k = 0; k < KGE_MAXJ; ++k) amax = fmaxf(amax, fabsf(cx.q[k]));
+        q_scale = kge_plane_scale(kge_wave_max(amax), q_inv);
+    }
 #pragma unroll
     for (int k = 0; k < KGE_MAXJ; ++k) {
         const int j = lane + 64 * k;
@@ -99,8 +116,9 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
             if (W) El<BF16>::st(W, (int64_t)b * dp + j, cx.w[k]);
             if (Q32) Q32[(int64_t)b * dp + j] = cx.q[k];      // unrounded copies for the 1-norm kernels
             if (W32) W32[(int64_t)b * dp + j] = cx.w[k];
-            if (a.planes) kge_store_planes(a.planes, (int64_t)Bp * dp, (int64_t)b * dp + j, cx.q[k]);
-            if (a.planes && W) kge_store_planes(a.planes + 3 * (int64_t)Bp * dp, (int64_t)Bp * dp, (int64_t)b * dp + j, cx.w[k]);
+            if (a.planes) kge_store_planes(a.planes, (int64_t)Bp * dp, (int64_t)b * dp + j, q_scale * cx.q[k]);
+            if (a.planes && W)
+                kge_store_planes(a.planes + 2 * (int64_t)Bp * dp, (int64_t)Bp * dp, (int64_t)b * dp + j, KGE_PLANE_UNIT_SCALE * cx.w[k]);
         }
     }
     qn = kge_wave_sum(qn);
@@ -125,7 +143,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
     s_pos = kge_wave_sum(s_pos);
     if (!(SC == KGE_DISTMULT || SC == KGE_COMPLEX)) s_pos = m.p1 ? -s_pos : -sqrtf(s_pos);
     if (lane == 0) {
-        rowinfo[b] = KgeRowInfo{qn, cq, 0.f, SC == KGE_TRANSH ? wn : 1.f};
+        rowinfo[b] = KgeRowInfo{qn, cq, q_inv, SC == KGE_TRANSH ? wn : 1.f};     // (K: set by the row finish when training)
         if (pos_ws) pos_ws[b] = s_pos;
         if (pos_out) pos_out[b] = s_pos;
     }
@@ -147,7 +165,7 @@ __host__ __device__ inline int kge_tgather_rows_per_wave(int dp, int es) { retur
 
 template <bool BF16>
 __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T,
-                                                 float *tn, __bf16 *planes = nullptr) {
+                                                 float *tn, _Float16 *planes = nullptr, float *inv_scale = nullptr) {
     const int lane = threadIdx.x & 63;
     constexpr int ES = BF16 ? 2 : 4;
     const int lpr = dp * ES / 16;                           // lanes that cover a row with 16 bytes each
@@ -175,22 +193,31 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
             const bool live = n < Np && lg < lpr;
             if (live) *(uint4 *)((char *)T + ((int64_t)n * dp) * ES + lg * 16) = v[u];
             const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-            float s = 0.f;
+            float s = 0.f, amax = 0.f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if constexpr (BF16) {
                     const float a0 = __uint_as_float(w[k] << 16), a1 = __uint_as_float(w[k] & 0xffff0000u);
                     s += a0 * a0; s += a1 * a1;
-                } else {
-                    const float a0 = __uint_as_float(w[k]); s += a0 * a0;
-                    if (planes && live) kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + lg * 4 + k, a0);
-                }
+                } else { const float a0 = __uint_as_float(w[k]); s += a0 * a0; amax = fmaxf(amax, fabsf(a0)); }
             }
-            // sum over the lanes of the row's group (fixed order)
+            // sum (and largest magnitude) over the lanes of the row's group (fixed order)
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1)
-                if (o < gl) s += __shfl_xor(s, o);
+                if (o < gl) { s += __shfl_xor(s, o); amax = fmaxf(amax, __shfl_xor(amax, o)); }
             if (lg == 0 && n < Np) tn[n] = s;
+            if constexpr (!BF16) {
+                if (planes) {
+                    float inv;
+                    const float sc = kge_plane_scale(amax, inv);
+                    if (live) {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + lg * 4 + k, sc * __uint_as_float(w[k]));
+                    }
+                    if (lg == 0 && n < Np) inv_scale[n] = inv;
+                }
+            }
         }
         return;
     }
@@ -198,20 +225,29 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
         const int n = nbase + u;
         if (n >= Np) break;                                 // (wave-uniform)
         const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
-        float s = 0.f;
+        float s = 0.f, amax = 0.f;
         for (int j = lane; j < dp; j += 64) {
             float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
             El<BF16>::st(T, (int64_t)n * dp + j, v);
-            if (!BF16 && planes) kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + j, v);
-            s += v * v;
+            s += v * v; amax = fmaxf(amax, fabsf(v));
         }
         s = kge_wave_sum(s);
         if (lane == 0) tn[n] = s;
+        if (!BF16 && planes) {                              // (second walk over the row, now that its scale is known)
+            float inv;
+            const float sc = kge_plane_scale(kge_wave_max(amax), inv);
+            for (int j = lane; j < dp; j += 64) {
+                const float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
+                kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + j, sc * v);
+            }
+            if (lane == 0) inv_scale[n] = inv;
+        }
     }
 }
 template <bool BF16>
-__global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, __bf16 *planes) {
-    kge_tgather_body<BF16>(blockIdx.x, m, neg, N, Np, dp, T, tn, planes);
+__global__ void kge_tgather_kernel(KgeModelDev m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, _Float16 *planes,
+                                   float *inv_scale) {
+    kge_tgather_body<BF16>(blockIdx.x, m, neg, N, Np, dp, T, tn, planes, inv_scale);
 }
 template <bool BF16, int SC>
 __global__ void kge_qbuild_kernel(KgeQbuildArgs a) { kge_qbuild_body<BF16, SC>(blockIdx.x, a); }
@@ -220,7 +256,7 @@ __global__ void kge_qbuild_kernel(KgeQbuildArgs a) { kge_qbuild_body<BF16, SC>(b
 template <bool BF16, int SC>
 __global__ void kge_qbuild_tgather_kernel(int q_blocks, KgeQbuildArgs a, KgeTgatherArgs g) {
     if ((int)blockIdx.x < q_blocks) kge_qbuild_body<BF16, SC>(blockIdx.x, a);
-    else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn, g.planes);
+    else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn, g.planes, g.inv_scale);
 }
 
 // gather of the shared negatives AND their transposed copy in one launch: a workgroup takes 32 negatives, every
@@ -666,7 +702,7 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
                    float *pos_out, hipStream_t st, void *planes) {
     const int grid = (Bp + 3) / 4;
     if (grid == 0) return KGE_OK;
-    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (__bf16 *)planes};
+    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (_Float16 *)planes};
 #define KGE_QBUILD(BF, SC) hipLaunchKernelGGL((kge_qbuild_kernel<BF, SC>), dim3(grid), dim3(256), 0, st, a)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QBUILD) } else { KGE_SC_SWITCH(false, KGE_QBUILD) }
 #undef KGE_QBUILD
@@ -677,25 +713,26 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out,
-                           void *q_planes, void *t_planes) {
+                           void *q_planes, void *t_planes, float *t_inv_scale) {
     const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
     const int qb = (Bp + 3) / 4, tb = (Np + rows_wg - 1) / rows_wg;
-    if (qb == 0 || tb == 0 || ((q_planes || t_planes) && m.bf16)) return KGE_E_INVALID_ARG;
-    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (__bf16 *)q_planes};
-    const KgeTgatherArgs g{neg, N, Np, T, tn, (__bf16 *)t_planes};
+    if (qb == 0 || tb == 0 || ((q_planes || t_planes) && m.bf16) || (t_planes && !t_inv_scale)) return KGE_E_INVALID_ARG;
+    const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (_Float16 *)q_planes};
+    const KgeTgatherArgs g{neg, N, Np, T, tn, (_Float16 *)t_planes, t_inv_scale};
 #define KGE_QT(BF, SC) hipLaunchKernelGGL((kge_qbuild_tgather_kernel<BF, SC>), dim3(qb + tb), dim3(256), 0, st, qb, a, g)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QT) } else { KGE_SC_SWITCH(false, KGE_QT) }
 #undef KGE_QT
     return kge_launch_status();
 }
 
-int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, hipStream_t st, void *planes) {
+int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn, hipStream_t st, void *planes,
+                    float *inv_scale) {
     const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
     const int grid = (Np + rows_wg - 1) / rows_wg;
     if (grid == 0) return KGE_OK;
-    if (planes && m.bf16) return KGE_E_INVALID_ARG;
-    if (m.bf16) hipLaunchKernelGGL(kge_tgather_kernel<true>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn, (__bf16 *)nullptr);
-    else        hipLaunchKernelGGL(kge_tgather_kernel<false>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn, (__bf16 *)planes);
+    if (planes && (m.bf16 || !inv_scale)) return KGE_E_INVALID_ARG;
+    if (m.bf16) hipLaunchKernelGGL(kge_tgather_kernel<true>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn, (_Float16 *)nullptr, (float *)nullptr);
+    else        hipLaunchKernelGGL(kge_tgather_kernel<false>, dim3(grid), dim3(256), 0, st, m, neg, N, Np, dp, T, tn, (_Float16 *)planes, inv_scale);
     return kge_launch_status();
 }
 

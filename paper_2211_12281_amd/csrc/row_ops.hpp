@@ -24,6 +24,12 @@ __device__ __forceinline__ float kge_wave_sum(float v) {
     return v;
 }
 
+__device__ __forceinline__ float kge_wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
 constexpr int KGE_MAXJ = 8;   // dim <= 512 -> at most 8 columns per lane
 
 // The query of triple b (fp32, unrounded), spread over a wave: lane holds columns lane + 64*k.

@@ -37,7 +37,7 @@ def test_large_rows_fp32_1024_bytes(orc, scorer):
 @pytest.mark.parametrize("scorer", SCORERS)
 @pytest.mark.parametrize("dim", [128, 104, 200])
 def test_fp32_tables_on_the_bf16_pipe(orc, scorer, dim, monkeypatch):
-    """fp32 rows padded to 128 or 256 dimensions are contracted as three bf16 pieces per operand: against the oracle,
+    """fp32 rows padded to 128 or 256 dimensions are contracted as two fp16 pieces per operand: against the oracle,
     and against the kernel that uses the fp32 matrix instructions (selected through the environment)."""
     G = make_case(scorer, 4000, 12, dim, 200, 333, False)
     pos, neg, rp, rn = _run(orc, scorer, G, False)
@@ -46,6 +46,24 @@ def test_fp32_tables_on_the_bf16_pipe(orc, scorer, dim, monkeypatch):
     pos2, neg2, _, _ = _run(orc, scorer, G, False)
     assert norm_err(neg2, rn) <= RTOL_F32
     assert norm_err(neg, neg2) <= RTOL_F32 and np.array_equal(pos, pos2)
+
+
+@pytest.mark.parametrize("scorer", ["transe", "transh", "distmult", "rotate"])
+@pytest.mark.parametrize("scale", [1e-4, 3e3, None])
+def test_fp32_score_block_does_not_depend_on_the_scale_of_the_tables(orc, scorer, scale):
+    """The fp32 rows reach the matrix cores as two fp16 pieces of the row scaled by a power of two of its own: tables a
+    factor 1e-4 or 3e3 away from the usual magnitudes, and rows whose columns span four decades (scale None), stay
+    inside the fp32 tolerance."""
+    G = make_case(scorer, 4000, 12, 256, 200, 333, False)
+    if scale is None:
+        col = (10.0 ** (-4.0 * np.random.default_rng(3).random(256))).astype(np.float32)
+        G["ent"] = G["ent"] * col
+    else:
+        G["ent"] = (G["ent"] * scale).astype(np.float32)
+        if scorer != "rotate":
+            G["rel"] = (G["rel"] * scale).astype(np.float32)
+    pos, neg, rp, rn = _run(orc, scorer, G, False)
+    assert norm_err(pos, rp) <= RTOL_F32 and norm_err(neg, rn) <= RTOL_F32, norm_err(neg, rn)
 
 
 @pytest.mark.parametrize("scorer", ["transe", "distmult"])
@@ -72,7 +90,7 @@ def test_edge_shapes(orc, scorer):
 @pytest.mark.parametrize("bf16,dim", [(False, 64), (True, 64), (False, 128), (False, 256)])
 def test_near_zero_distances_do_not_cancel(orc, scorer, bf16, dim):
     """Negatives that (almost) coincide with the query: the norm-expansion form would cancel (fp32 rows of 128 and 256
-    dimensions take the kernels that contract three bf16 pieces per operand: their guard is the same)."""
+    dimensions take the kernels that contract two fp16 pieces per operand: their guard is the same)."""
     import kge_synth as ks
     G = make_case(scorer, 2000, 5, dim, 40, 70, bf16)
     E = G["ent"].astype(np.float64)
