@@ -112,7 +112,7 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
 
 // fp32 score blocks go through two fp16 planes on the 16-bit matrix pipe (block_f32h2_score.hip); KGE_SCORE_F32_MFMA=1
 // in the environment (read at every call) keeps the fp32 matrix instructions (cross-check)
-bool score3_applies(const Geometry &g) {
+bool score_h2_applies(const Geometry &g) {
     const char *e = getenv("KGE_SCORE_F32_MFMA");
     const bool off = e && e[0] == '1';
     return !off && !g.bf16 && !g.l1 && (g.dp == 128 || g.dp == 256) && g.N > 0;
@@ -137,7 +137,7 @@ struct Buffers {
     float *regv;                       // L3 norms of the gathered slots: [Bp heads][Bp tails][Np negatives]
     float *S, *Q32;                    // 1-norm scorers: the score block [Bp][Np], the queries unrounded [Bp][dp]
     float *W32, *A, *P;                // ... TransH: the unit normals unrounded, w^ . t and sign(x) . w^ per pair [Bp][Np]
-    void *Qp3, *Tp3;                   // score-only calls on fp32 tables: two fp16 planes of the scaled Q (TransH: and of W) and T
+    void *Qp2, *Tp2;                   // score-only calls on fp32 tables: two fp16 planes of the scaled Q (TransH: and of W) and T
     float *t_inv;                      // ... 1 / scale of the rows of T
 };
 
@@ -153,9 +153,9 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
     b.Q32 = g.l1 ? c.take<float>(rowsB) : nullptr;
     b.W32 = g.l1 && g.transh ? c.take<float>(rowsB) : nullptr;
     b.A = b.P = nullptr;
-    b.Qp3 = b.Tp3 = nullptr; b.t_inv = nullptr;
-    if (!bwd && score3_applies(g)) {
-        b.Qp3 = c.take<char>((g.transh ? 4 : 2) * rowsB * 2); b.Tp3 = c.take<char>(2 * rowsN * 2); b.t_inv = c.take<float>(g.Np);
+    b.Qp2 = b.Tp2 = nullptr; b.t_inv = nullptr;
+    if (!bwd && score_h2_applies(g)) {
+        b.Qp2 = c.take<char>((g.transh ? 4 : 2) * rowsB * 2); b.Tp2 = c.take<char>(2 * rowsN * 2); b.t_inv = c.take<float>(g.Np);
     }
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
     b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr;
@@ -349,15 +349,15 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     // (queries and negatives from one launch when there is a block to score)
     if (block && g.Bp > 0)
         rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, neg, g.N, g.Np,
-                                    b.T, b.tn, st, pos_out, b.Qp3, b.Tp3, b.t_inv);
+                                    b.T, b.tn, st, pos_out, b.Qp2, b.Tp2, b.t_inv);
     else
-        rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st, b.Qp3);
+        rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, nullptr, b.Q32, b.W32, b.rowinfo, b.pos, pos_out, st, b.Qp2);
     if (rc != KGE_OK || !block) return rc;
     if (g.l1 && g.transh)
         return kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, nullptr, nullptr, g.N, st);
     if (g.l1) return kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, neg_out, g.N, st);
-    if (score3_applies(g)) {
-        return kge_launch_score_h2(g.kind, g.dp, b.Qp3, b.Tp3, b.t_inv, (const float *)b.Q, (const float *)b.T,
+    if (score_h2_applies(g)) {
+        return kge_launch_score_h2(g.kind, g.dp, b.Qp2, b.Tp2, b.t_inv, (const float *)b.Q, (const float *)b.T,
                                  g.transh ? (const float *)b.W : nullptr, b.rowinfo, b.tn, g.B, g.N,
                                  g.Bp, g.Np, neg_out, st);
     }
