@@ -210,10 +210,16 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
                 if (planes) {
                     float inv;
                     const float sc = kge_plane_scale(amax, inv);
-                    if (live) {
+                    if (live) {                         // the lane's four elements: one 8-byte store per plane
+                        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                        h4 p1, p2;
 #pragma unroll
-                        for (int k = 0; k < 4; ++k)
-                            kge_store_planes(planes, (int64_t)Np * dp, (int64_t)n * dp + lg * 4 + k, sc * __uint_as_float(w[k]));
+                        for (int k = 0; k < 4; ++k) {
+                            const float xs = sc * __uint_as_float(w[k]);
+                            p1[k] = (_Float16)xs; p2[k] = (_Float16)(xs - (float)p1[k]);
+                        }
+                        _Float16 *dst = planes + (int64_t)n * dp + lg * 4;
+                        *(h4 *)dst = p1; *(h4 *)(dst + (int64_t)Np * dp) = p2;
                     }
                     if (lg == 0 && n < Np) inv_scale[n] = inv;
                 }
