@@ -23,6 +23,7 @@ int kge_launch_score_h2(int kind, int dp, const void *Qp, const void *Tp, const 
 namespace {
 
 constexpr int H2_ST = 32, H2_NSTAGE = 3;
+constexpr int H2_NSTAGE_ONE = 2;                     // one-contraction kernel: two workgroups share a compute unit, two stages each
 
 typedef _Float16 kge_f16x8 __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ kge_f32x16 h2_mma(kge_f32x16 acc, uint4 a, uint4 b) {
@@ -54,15 +55,16 @@ __device__ __forceinline__ bool h2_place(const ScoreH2Args &a, int &own_tile, in
 }
 
 template <int DP, int KIND>
-__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(1, 1)))
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
 void score_h2_kernel(const ScoreH2Args a) {
     constexpr int RB = DP * 2, KS = DP / 16;           // bytes of a plane row, k-steps of 16
     constexpr int PLANE = H2_ST * RB, STAGE = 2 * PLANE;
     constexpr int CPW = STAGE / 1024 / 4;              // 1 KB copies per wave and tile
     constexpr int LPW = CPW + 1;                       // plus the row information
+    constexpr int NSTAGE = H2_NSTAGE_ONE, AHEAD = NSTAGE - 1;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-    char *side_ring = lds + H2_NSTAGE * STAGE;         // [stage][wave][64 lanes x 16 bytes]
+    char *side_ring = lds + NSTAGE * STAGE;         // [stage][wave][64 lanes x 16 bytes]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
     int own_tile, t0, t1;
@@ -88,19 +90,20 @@ void score_h2_kernel(const ScoreH2Args a) {
     }
     auto issue = [&](int tile, int slot) {
         tile = tile < t1 ? tile : t1 - 1;               // past the end: a harmless repeat keeps vmcnt uniform
-        const uint32_t sbase = lds0 + (slot % H2_NSTAGE) * STAGE;
+        const uint32_t sbase = lds0 + (slot % NSTAGE) * STAGE;
         const char *src = a.Qp + (size_t)tile * H2_ST * RB;
 #pragma unroll
         for (int jj = 0; jj < CPW; ++jj)
             kge_async_copy16(src + x_off[jj], __builtin_amdgcn_readfirstlane(sbase + (wave * CPW + jj) * 1024));
         kge_async_copy16(a.rowinfo + tile * H2_ST + lr,
-                         __builtin_amdgcn_readfirstlane(lds0 + H2_NSTAGE * STAGE + ((slot % H2_NSTAGE) * 4 + wave) * 1024));
+                         __builtin_amdgcn_readfirstlane(lds0 + NSTAGE * STAGE + ((slot % NSTAGE) * 4 + wave) * 1024));
     };
     int frag_off[8];                                    // chunk 2 ks + g of row lr at position chunk ^ (lr & 15)
 #pragma unroll
     for (int b = 0; b < 8; ++b) frag_off[b] = lr * RB + 16 * ((2 * b + g) ^ (lr & 15));
 
-    issue(t0, 0); issue(t0 + 1, 1);
+#pragma unroll
+    for (int s2 = 0; s2 < AHEAD; ++s2) issue(t0 + s2, s2);
     // the own operand must have arrived before the loop (a wait inside it would drain the ring)
 #pragma unroll
     for (int p = 0; p < 2; ++p)
@@ -110,11 +113,11 @@ void score_h2_kernel(const ScoreH2Args a) {
 
     for (int t = t0; t < t1; ++t) {
         const int slot = t - t0;
-        kge_wait_vmcnt<LPW>();                          // tile t has landed (this wave's part); tile t + 1 may be in flight
+        kge_wait_vmcnt<(AHEAD - 1) * LPW>();            // tile t has landed (this wave's part); later tiles may be in flight
         __syncthreads();
-        issue(t + 2, slot + 2);                         // into the stage that tile t - 1 vacated
-        const char *stage = lds + (slot % H2_NSTAGE) * STAGE;
-        const char *side = side_ring + ((slot % H2_NSTAGE) * 4 + wave) * 1024;
+        issue(t + AHEAD, slot + AHEAD);                 // into the stage that tile t - 1 vacated
+        const char *stage = lds + (slot % NSTAGE) * STAGE;
+        const char *side = side_ring + ((slot % NSTAGE) * 4 + wave) * 1024;
         kge_f32x16 acc0, acc1;
 #pragma unroll
         for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
@@ -347,8 +350,8 @@ int launch_transh(const ScoreH2Args &a, hipStream_t st) {
 
 template <int DP, int KIND>
 int launch_one(const ScoreH2Args &a, hipStream_t st) {
-    constexpr int LDS = H2_NSTAGE * (2 * H2_ST * DP * 2) + H2_NSTAGE * 4 * 1024;
-    static_assert(LDS <= 160 * 1024, "LDS budget");
+    constexpr int LDS = H2_NSTAGE_ONE * (2 * H2_ST * DP * 2) + H2_NSTAGE_ONE * 4 * 1024;
+    static_assert(2 * LDS <= 160 * 1024, "LDS budget of two workgroups");
     static bool attr_set = false;
     return launch_h2(score_h2_kernel<DP, KIND>, LDS, attr_set, a, st);
 }
@@ -365,7 +368,8 @@ int kge_launch_score_h2(int kind, int dp, const void *Qp, const void *Tp, const 
     a.Qp = (const char *)Qp; a.Tp = (const char *)Tp; a.t_inv = t_inv; a.Q32 = Q32; a.T32 = T32; a.W32 = W32;
     a.rowinfo = rowinfo; a.tn = tn; a.B = B; a.N = N; a.Bp = Bp; a.Np = Np; a.S_out = S_out;
     a.own_tiles = Np / 128; a.str_tiles = Bp / H2_ST;
-    int want = (256 + a.own_tiles - 1) / a.own_tiles;           // about one workgroup per compute unit
+    const int wgs = W32 ? 256 : 512;                            // one workgroup per compute unit (TransH), or two
+    int want = (wgs + a.own_tiles - 1) / a.own_tiles;
     if (want > a.str_tiles) want = a.str_tiles;
     if (want < 1) want = 1;
     a.tiles_per_split = (a.str_tiles + want - 1) / want;
