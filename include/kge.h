@@ -108,8 +108,13 @@ int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int6
  *   pos_out[b]       = f(h_b, r_b, t_b)           b < B          (float[B], or NULL)
  *   neg_out[b*N + n] = f(h_b, r_b, neg_n)         n < N          (float[B*N] row-major, or NULL)
  * h, r, t: int32[B]; neg: int32[N] (may be NULL when N = 0).  B = 0 or N = 0 are valid.
- * Arithmetic: fp32 tables -> fp32 matrix cores; bf16 tables -> bf16 matrix cores with fp32
- * accumulation (queries are rounded to bf16 after the query build).
+ * Arithmetic: bf16 tables -> bf16 matrix cores with fp32 accumulation (queries are rounded to bf16
+ * after the query build).  fp32 tables -> the positive scores by direct fp32 sums; the block, for rows
+ * padded to 128 or 256 dimensions (dim <= 256), from TWO fp16 pieces of every operand row scaled by a
+ * power of two of its own (22 significand bits, three fp16 matrix products per fp32 one, fp32
+ * accumulation; the error of a contraction stays below 3 x 2^-22 |q| |t| whatever the magnitude of the
+ * tables), entries of a distance scorer whose norm expansion cancels being redone by direct fp32
+ * differences.  KGE_SCORE_F32_MFMA=1 in the environment selects the fp32 matrix instructions instead.
  */
 int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, const int32_t *t,
               int64_t B, const int32_t *neg, int64_t N, float *pos_out, float *neg_out, void *ws,
