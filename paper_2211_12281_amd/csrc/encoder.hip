@@ -334,17 +334,33 @@ __global__ __launch_bounds__(256) void enc_gather_t_kernel(EncRowArgs a, const v
     const int ldt = fd + 1;
     constexpr int EPV = BF16 ? 8 : 4;                      // elements per 16 bytes
     const int ppr = fd / EPV;                              // 16-byte pieces per row
-    for (int idx = threadIdx.x; idx < gr.count * ppr; idx += 256) {
-        const int r = idx / ppr, pc = idx % ppr;
-        const char *src = (const char *)feat + ((int64_t)enc_slot_entity(a, gr.slot0 + r) * feat_ld + pc * EPV) * (BF16 ? 2 : 4);
-        const enc_u32x4 v = *(const enc_u32x4 *)src;
-        float *dst = tile + r * ldt + pc * EPV;
-        if constexpr (BF16) {
+    // six pieces per thread are requested before the first is used (random rows: the bytes in flight bound the rate)
+    constexpr int U = 6;
+    const int total = gr.count * ppr;
+    for (int base = threadIdx.x; base < total; base += 256 * U) {
+        enc_u32x4 v[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { dst[2 * u] = __uint_as_float(v[u] << 16); dst[2 * u + 1] = __uint_as_float(v[u] & 0xffff0000u); }
-        } else {
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256;
+            if (idx < total) {
+                const int r = idx / ppr, pc = idx % ppr;
+                v[q] = *(const enc_u32x4 *)((const char *)feat +
+                                            ((int64_t)enc_slot_entity(a, gr.slot0 + r) * feat_ld + pc * EPV) * (BF16 ? 2 : 4));
+            }
+        }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) dst[u] = __uint_as_float(v[u]);
+        for (int q = 0; q < U; ++q) {
+            const int idx = base + q * 256;
+            if (idx >= total) continue;
+            const int r = idx / ppr, pc = idx % ppr;
+            float *dst = tile + r * ldt + pc * EPV;
+            if constexpr (BF16) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { dst[2 * u] = __uint_as_float(v[q][u] << 16); dst[2 * u + 1] = __uint_as_float(v[q][u] & 0xffff0000u); }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) dst[u] = __uint_as_float(v[q][u]);
+            }
         }
     }
     __syncthreads();
