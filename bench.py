@@ -597,6 +597,11 @@ def main():
         e0.record(); e1.record(); e1.synchronize()
         tot += e0.elapsed_time(e1)
     calib["empty_event_pair_us"] = tot / 20 * 1e3
+    if roof is not None and roof.get("achieved") and roof.get("avg_us", 0) > 2 * calib["empty_event_pair_us"]:
+        # the same figures with the bracket's own duration taken off (information; "frac" above keeps the raw duration)
+        net = roof["avg_us"] - calib["empty_event_pair_us"]
+        roof["avg_us_less_empty_pair"] = net
+        roof["frac_less_empty_pair"] = roof["frac"] * roof["avg_us"] / net
     if roof is not None and roof.get("achieved") is not None and roof["bound"] == "mfma" and wl_bf16(wl):
         roof["frac_of_measured_loop"] = roof["achieved"] / calib["mfma_bf16_loop_tflops"]
     pairs = wl.pairs_per_step()
