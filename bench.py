@@ -514,9 +514,9 @@ def main():
                               "avg_us": 1e3 * tot / n, "measured": f"{extra_steps} steps after the timed region"}
     roof = None
     if prof:
-        # the slots "adam" and "sort" bracket several kernels per call (3 and 6 launches): they compete with their
+        # the slots "adam" and "sort" bracket several kernels per call (2 and 6 launches): they compete with their
         # per-kernel share, the roofline below being that of ONE kernel
-        share = {"adam": 3.0, "sort": 6.0}
+        share = {"adam": 2.0, "sort": 6.0}
         dom = max(prof, key=lambda k: prof[k]["total_ms"] / share.get(k, 1.0))
         # The two passes of a training step (block_fwd over the queries, block_gradt over the negatives) are the same
         # kernel template and take the same time to within run-to-run noise: when they are within 5 % of each other the
