@@ -50,7 +50,8 @@ enum {
     KGE_E_INVALID_ARG = -1,         /* NULL where data is required, negative size, bad enum, bad dim */
     KGE_E_UNSUPPORTED = -2,         /* valid request this build has no kernel for (e.g. kge_topk with p_norm = 1) */
     KGE_E_WORKSPACE_TOO_SMALL = -3,
-    KGE_E_HIP = -4                  /* a HIP runtime call failed (launch error) */
+    KGE_E_HIP = -4,                 /* a HIP runtime call failed (launch error) */
+    KGE_E_STATIC_SCRATCH_TOO_SMALL = -5   /* kge_sparse_adam_static: the request needs more than the built-in scratch buffer */
 };
 
 /* A model = scorer + tables (Section 3.1: shallow entity / relation embeddings; TransH adds w_r). */
@@ -174,6 +175,23 @@ int kge_sparse_adam_plan(int64_t n_rows, int32_t dim, const int32_t *idx, int64_
 int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
                           int64_t ld, const float *grads, int64_t M, const kge_adam_cfg_t *cfg, void *ws,
                           size_t ws_bytes, void *hip_stream);
+
+/*
+ * kge_sparse_adam for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the workspace), same kernels
+ * and the same bits as kge_sparse_adam; the sort buffers and piece sums live in a buffer built into the library
+ * (static device memory, kge_sparse_adam_static_limit() bytes = 4 MiB, one copy per GPU, held until the process ends).
+ * The call allocates and frees nothing (the profiling hooks, off by default, create HIP events while they are on).
+ * Limit: kge_workspace_bytes(KGE_OP_SPARSE_ADAM, NULL, M, dim, 0) <= kge_sparse_adam_static_limit() -- e.g. M = 24,576
+ * rows of dim 256, or M = 65,536 of dim 64 -- else KGE_E_STATIC_SCRATCH_TOO_SMALL and nothing is launched.
+ * Every call on a GPU shares that GPU's buffer: calls that overlap on one GPU (two streams, two threads) race; order
+ * them on one stream or with events.  Nothing in the buffer needs clearing between calls (every word a call reads it
+ * has written itself), so calls of any sizes may follow each other.
+ */
+int kge_sparse_adam_static(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
+                           int64_t ld, const int32_t *idx, const float *grads, int64_t M,
+                           const kge_adam_cfg_t *cfg, void *hip_stream);
+size_t kge_sparse_adam_static_limit(void);
 
 /*
  * Link prediction (Section 3.2, "Inference"): for each query (h_q, r_q), q < Q, rank all

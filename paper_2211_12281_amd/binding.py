@@ -19,7 +19,7 @@ OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION, OP_SAMPLER_BUILD, 
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
            "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
            "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble", "kge_sparse_adam_plan",
-           "kge_sparse_adam_apply",
+           "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
            "kge_calibrate_mfma", "kge_calibrate_copy"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
@@ -90,6 +90,10 @@ def load():
             [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
         lib.kge_sparse_adam.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                                            C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kge_sparse_adam_static.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                                                  C.c_int64, C.c_void_p, C.c_void_p]
+        lib.kge_sparse_adam_static_limit.restype = C.c_size_t
+        lib.kge_sparse_adam_static_limit.argtypes = []
         lib.kge_sparse_adam_plan.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kge_sparse_adam_apply.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_int64,
                                                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -239,6 +243,24 @@ def sparse_adam(param, shadow, m, v, idx, grads, lr: float, beta1: float = 0.9, 
     _check(load().kge_sparse_adam(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
                                   _ptr(_i32(idx)), _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream()),
            "kge_sparse_adam")
+
+
+def sparse_adam_static_limit() -> int:
+    return int(load().kge_sparse_adam_static_limit())
+
+
+def sparse_adam_static(param, shadow, m, v, idx, grads, lr: float, beta1: float = 0.9, beta2: float = 0.999,
+                       eps: float = 1e-8, step: int = 1, stream=None):
+    """kge_sparse_adam_static: the update with the library's built-in scratch buffer (no workspace, no allocation)."""
+    assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
+    assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
+    assert m.stride() == param.stride() and v.stride() == param.stride()
+    if shadow is not None:
+        assert shadow.dtype == torch.bfloat16 and shadow.stride() == param.stride()
+    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step)
+    _check(load().kge_sparse_adam_static(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], param.shape[1],
+                                         param.stride(0), _ptr(_i32(idx)), _ptr(grads), idx.numel(), C.byref(cfg),
+                                         _stream(stream)), "kge_sparse_adam_static")
 
 
 def sparse_adam_plan(n_rows: int, dim: int, idx, ws: Workspace, stream=None):

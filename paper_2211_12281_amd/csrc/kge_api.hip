@@ -7,6 +7,8 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
                         const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
                         size_t ws_bytes, hipStream_t st);
 size_t kge_sparse_adam_ws(int64_t M, int dim);
+int kge_static_scratch(void **ptr, size_t *bytes);
+size_t kge_static_scratch_bytes();
 int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void *ws, hipStream_t st);
 int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
                               const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st);
@@ -221,6 +223,7 @@ const char *kge_status_string(int status) {
     case KGE_E_UNSUPPORTED: return "unsupported configuration";
     case KGE_E_WORKSPACE_TOO_SMALL: return "workspace too small";
     case KGE_E_HIP: return "HIP runtime error";
+    case KGE_E_STATIC_SCRATCH_TOO_SMALL: return "request exceeds the library's static scratch buffer";
     default: return "unknown status";
     }
 }
@@ -467,10 +470,11 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     return rc;
 }
 
-int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
-                    int64_t ld, const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t *cfg,
-                    void *ws, size_t ws_bytes, void *hip_stream) {
-    if (!cfg || M < 0 || n_rows <= 0 || n_rows >= (1ll << 31) || dim <= 0 || dim % 4 != 0 || ld < dim || ld % 4 != 0)
+// argument checks shared by kge_sparse_adam and kge_sparse_adam_static; KGE_OK with M == 0 means "nothing to do"
+static int validate_sparse_adam(const float *param_f32, const void *param_bf16, const float *m, const float *v, int64_t n_rows,
+                                int32_t dim, int64_t ld, const int32_t *idx, const float *grads, int64_t M,
+                                const kge_adam_cfg_t *cfg) {
+    if (!cfg || M < 0 || n_rows <= 0 || n_rows >= (1ll << 31) || dim <= 0 || dim % 4 != 0 || dim > 4096 || ld < dim || ld % 4 != 0)
         return KGE_E_INVALID_ARG;
     if (cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f))
         return KGE_E_INVALID_ARG;
@@ -478,9 +482,32 @@ int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int6
     if (M >= (1ll << 31)) return KGE_E_INVALID_ARG;
     if (!param_f32 || !m || !v || !idx || !grads) return KGE_E_INVALID_ARG;
     if (!adam_rows_aligned(param_f32, param_bf16, m, v, grads)) return KGE_E_INVALID_ARG;
+    return KGE_OK;
+}
+
+int kge_sparse_adam(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
+                    int64_t ld, const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t *cfg,
+                    void *ws, size_t ws_bytes, void *hip_stream) {
+    const int rc = validate_sparse_adam(param_f32, param_bf16, m, v, n_rows, dim, ld, idx, grads, M, cfg);
+    if (rc != KGE_OK || M == 0) return rc;
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
     ws = align_ws(ws, ws_bytes);
     if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    return kge_run_sparse_adam(param_f32, param_bf16, m, v, n_rows, dim, ld, idx, grads, M, *cfg, ws, ws_bytes,
+                               (hipStream_t)hip_stream);
+}
+
+size_t kge_sparse_adam_static_limit(void) { return kge_static_scratch_bytes(); }
+
+int kge_sparse_adam_static(float *param_f32, void *param_bf16, float *m, float *v, int64_t n_rows, int32_t dim,
+                           int64_t ld, const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t *cfg,
+                           void *hip_stream) {
+    const int rc = validate_sparse_adam(param_f32, param_bf16, m, v, n_rows, dim, ld, idx, grads, M, cfg);
+    if (rc != KGE_OK || M == 0) return rc;
+    if (kge_sparse_adam_ws(M, dim) > kge_static_scratch_bytes()) return KGE_E_STATIC_SCRATCH_TOO_SMALL;
+    void *ws = nullptr; size_t ws_bytes = 0;
+    const int rs = kge_static_scratch(&ws, &ws_bytes);
+    if (rs != KGE_OK) return rs;
     return kge_run_sparse_adam(param_f32, param_bf16, m, v, n_rows, dim, ld, idx, grads, M, *cfg, ws, ws_bytes,
                                (hipStream_t)hip_stream);
 }

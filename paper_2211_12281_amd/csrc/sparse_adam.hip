@@ -5,6 +5,13 @@
 // Only rows that occur in idx are read or written (arXiv 2211.12281, Section 1: sparse access).
 #include "kge_internal.h"
 #include <math.h>
+#include <mutex>
+
+// Scratch memory of kge_sparse_adam_static, the variant for callers that cannot allocate: one copy per GPU, held until
+// the process ends.  Host code never uses the array's name as an address; it asks the runtime for the device address
+// once per device (kge_static_scratch below) and hands that pointer to the kernels like any other workspace.
+constexpr size_t KGE_STATIC_SCRATCH_BYTES = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[KGE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -403,3 +410,24 @@ int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t 
     if (rc != KGE_OK) return rc;
     return kge_run_sparse_adam_apply(param, shadow, m, v, n_rows, dim, ld, grads, M, cfg, ws, st);
 }
+
+// Device address and size of the current device's copy of `scratch`.  The address is looked up on the first call on
+// each device, with that device current, and kept.
+int kge_static_scratch(void **ptr, size_t *bytes) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void *ptrs[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return KGE_E_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KGE_E_HIP;
+        ptrs[dev] = p;
+    }
+    *ptr = ptrs[dev];
+    *bytes = KGE_STATIC_SCRATCH_BYTES;
+    return KGE_OK;
+}
+
+size_t kge_static_scratch_bytes() { return KGE_STATIC_SCRATCH_BYTES; }
