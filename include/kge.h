@@ -115,7 +115,7 @@ int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int6
  * power of two of its own (22 significand bits, three fp16 matrix products per fp32 one, fp32
  * accumulation; the error of a contraction stays below 3 x 2^-22 |q| |t| whatever the magnitude of the
  * tables), entries of a distance scorer whose norm expansion cancels being redone by direct fp32
- * differences.  KGE_SCORE_F32_MFMA=1 in the environment selects the fp32 matrix instructions instead.
+ * differences.
  */
 int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, const int32_t *t,
               int64_t B, const int32_t *neg, int64_t N, float *pos_out, float *neg_out, void *ws,
@@ -381,6 +381,19 @@ int kge_profile_collect(int slot, double *total_ms, int64_t *launches);
  */
 int kge_calibrate_mfma(int32_t iters, float *sink, int64_t sink_elems, double *tflops_out, void *hip_stream);
 int kge_calibrate_copy(const void *src, void *dst, size_t bytes, double *gbs_out, void *hip_stream);
+
+/*
+ * For tests and benchmarks that compare two kernels of one job: every job has one kernel in the library's own dispatch;
+ * kge_debug_select(knob, 1) makes later calls of the whole process take the alternative, kge_debug_select(knob, 0)
+ * returns to the library's choice.  Not for production use: the alternatives are slower, and a workspace must be sized
+ * (kge_workspace_bytes) under the same setting as the call that uses it.
+ *   KGE_DEBUG_FWD_ONE_ROLE    the pass over the queries of kge_loss_bwd (bf16, rows <= 512 bytes) as the one-role kernel
+ *   KGE_DEBUG_GRADT_ONE_ROLE  the same for the pass over the negatives
+ *   KGE_DEBUG_SCORE_F32_MFMA  kge_score on fp32 tables with the fp32 matrix instructions instead of two fp16 planes
+ * Returns KGE_E_INVALID_ARG for an unknown knob or a value other than 0 / 1.
+ */
+enum { KGE_DEBUG_FWD_ONE_ROLE = 0, KGE_DEBUG_GRADT_ONE_ROLE = 1, KGE_DEBUG_SCORE_F32_MFMA = 2 };
+int kge_debug_select(int knob, int value);
 
 /* Static description of a status code. */
 const char *kge_status_string(int status);

@@ -202,6 +202,26 @@ def topk(scorer, ent, rel, relw, h, r, cand_lo, cand_hi, K, true_t=None):
     return out_idx, out_score, rank
 
 
+def topk_band(scorer, ent, rel, relw, h, r, cand_lo, cand_hi, K, true_t, band_eps):
+    """topk(...) plus, from the same pass, the number of candidates whose ranking key lies within band_eps[q] of the
+    held-out tail's key: (idx, score, rank, band)."""
+    ent, rel, relw = _f32(ent), _f32(rel), _f32(relw)
+    h, r, true_t = _i32(h), _i32(r), _i32(true_t)
+    eps = np.ascontiguousarray(band_eps, dtype=np.float64)
+    Q, d = h.shape[0], ent.shape[1]
+    assert eps.shape == (Q,)
+    out_idx = np.zeros((Q, K), dtype=np.int32)
+    out_score = np.zeros((Q, K), dtype=np.float64)
+    rank = np.zeros(Q, dtype=np.int64)
+    band = np.zeros(Q, dtype=np.int64)
+    lib().orc_topk_band(_sid(scorer), C.c_int(d), _p(ent, C.c_float), _p(rel, C.c_float),
+                        _p(relw, C.c_float), _p(h, C.c_int32), _p(r, C.c_int32), C.c_int64(Q),
+                        C.c_int64(cand_lo), C.c_int64(cand_hi), C.c_int32(K), _p(out_idx, C.c_int32),
+                        _p(out_score, C.c_double), _p(true_t, C.c_int32), _p(rank, C.c_int64),
+                        _p(eps, C.c_double), _p(band, C.c_int64))
+    return out_idx, out_score, rank, band
+
+
 def bucket_triples(h, t, part_size, D, want_order=True):
     h, t = _i32(h), _i32(t)
     n = h.shape[0]

@@ -607,10 +607,30 @@ static void orc_sift_up(orc_item *hp, int i)
  * rank(true) = 1 + #{t : key(t) < key(true)} + #{t < true : key(t) = key(true)}   (1-based),
  * counted over the same candidate range (the true tail need not lie inside it).
  */
+void orc_topk_band(int scorer, int d, const float *ent, const float *rel, const float *relw,
+                   const int32_t *h, const int32_t *r, int64_t Q, int64_t cand_lo, int64_t cand_hi,
+                   int32_t K, int32_t *out_idx, double *out_score, const int32_t *true_t,
+                   int64_t *out_rank, const double *band_eps, int64_t *out_band);
+
 void orc_topk(int scorer, int d, const float *ent, const float *rel, const float *relw,
               const int32_t *h, const int32_t *r, int64_t Q, int64_t cand_lo, int64_t cand_hi,
               int32_t K, int32_t *out_idx, double *out_score, const int32_t *true_t,
               int64_t *out_rank)
+{
+    orc_topk_band(scorer, d, ent, rel, relw, h, r, Q, cand_lo, cand_hi, K, out_idx, out_score, true_t,
+                  out_rank, NULL, NULL);
+}
+
+/*
+ * The same ranking, and in the same pass over the candidates (band_eps and out_band given, with a held-out
+ * tail): out_band[q] = #{t in the range : |key(t) - key(true_q)| <= band_eps[q]}, the number of candidates
+ * whose ranking key lies within band_eps[q] of the held-out tail's.  A ranking that compares approximate
+ * keys, each within eps/2 of the exact one, can misplace the held-out tail by at most that many positions.
+ */
+void orc_topk_band(int scorer, int d, const float *ent, const float *rel, const float *relw,
+                   const int32_t *h, const int32_t *r, int64_t Q, int64_t cand_lo, int64_t cand_hi,
+                   int32_t K, int32_t *out_idx, double *out_score, const int32_t *true_t,
+                   int64_t *out_rank, const double *band_eps, int64_t *out_band)
 {
     int k = orc_rel_dim(scorer, d);
 #pragma omp parallel for schedule(dynamic, 1)
@@ -621,7 +641,7 @@ void orc_topk(int scorer, int d, const float *ent, const float *rel, const float
         orc_item *hp = (orc_item *)malloc(sizeof(orc_item) * (size_t)(K > 0 ? K : 1));
         int cnt = 0;
         double true_key = 0.0;
-        int64_t above = 0;
+        int64_t above = 0, band = 0;
         if (true_t && out_rank)
             orc_score_one_ex(scorer, d, hq, rq, wq, ent + (int64_t)true_t[q] * d, &true_key);
         for (int64_t t = cand_lo; t < cand_hi; ++t) {
@@ -630,6 +650,7 @@ void orc_topk(int scorer, int d, const float *ent, const float *rel, const float
             orc_score_one_ex(scorer, d, hq, rq, wq, ent + t * d, &it.key);
             if (true_t && out_rank) {
                 if (it.key < true_key || (it.key == true_key && t < (int64_t)true_t[q])) ++above;
+                if (band_eps && fabs(it.key - true_key) <= band_eps[q]) ++band;
             }
             if (K <= 0) continue;
             if (cnt < K) {
@@ -642,6 +663,7 @@ void orc_topk(int scorer, int d, const float *ent, const float *rel, const float
             }
         }
         if (true_t && out_rank) out_rank[q] = 1 + above;
+        if (true_t && out_rank && band_eps && out_band) out_band[q] = band;
         /* pop worst-first into the back of the list */
         int kept = cnt;
         for (int i = kept - 1; i >= 0; --i) {

@@ -19,7 +19,7 @@ OP_SCORE, OP_LOSS_BWD, OP_SPARSE_ADAM, OP_TOPK, OP_PARTITION, OP_SAMPLER_BUILD, 
 EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam", "kge_topk",
            "kge_partition_triples", "kge_sampler_build", "kge_sample_triples", "kge_sample_negatives_sharded",
            "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble", "kge_sparse_adam_plan",
-           "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit",
+           "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit", "kge_debug_select",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
            "kge_calibrate_mfma", "kge_calibrate_copy"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
@@ -307,6 +307,14 @@ def ensemble(lists, p: float, K_out: int = 10):
     _check(load().kge_ensemble(_ptr(lists), M, Q, K, float(p), K_out, _ptr(out_idx), _ptr(out_score), _stream()),
            "kge_ensemble")
     return out_idx, out_score
+
+
+DEBUG_KNOBS = {"fwd_one_role": 0, "gradt_one_role": 1, "score_f32_mfma": 2}
+
+
+def debug_select(knob: str, value: bool):
+    """kge_debug_select: tests and benchmarks only - take the alternative kernel of a job (process-wide)."""
+    _check(load().kge_debug_select(DEBUG_KNOBS[knob], 1 if value else 0), "kge_debug_select")
 
 
 def profile_enable(on):

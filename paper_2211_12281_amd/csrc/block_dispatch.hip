@@ -1,15 +1,18 @@
 // Dispatch of the block-kernel instantiations.
 #include "kge_internal.h"
-#include <stdlib.h>
+#include <atomic>
 
 int kge_launch_fwd_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
 int kge_launch_gradt_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
 
-// The two-role row-owner kernel serves bf16 rows of 512 bytes without the TransH operands; the environment variable
-// KGE_FWD_ONE_ROLE=1 selects the one-role kernel instead (for comparisons).
-static bool kge_use_fwd_pp() {
-    static const bool on = [] { const char *e = getenv("KGE_FWD_ONE_ROLE"); return !(e && e[0] == '1'); }();
-    return on;
+// Every job has ONE kernel in the library's own dispatch.  Tests and benchmarks that compare two kernels of one job
+// override the choice through kge_debug_select (process-wide, off by default).
+static std::atomic<int> g_knobs[KGE_KNOBS];
+int kge_knob(int knob) { return g_knobs[knob].load(std::memory_order_relaxed); }
+extern "C" int kge_debug_select(int knob, int value) {
+    if (knob < 0 || knob >= KGE_KNOBS || value < 0 || value > 1) return KGE_E_INVALID_ARG;
+    g_knobs[knob].store(value, std::memory_order_relaxed);
+    return KGE_OK;
 }
 
 #define KGE_DECL(name) int kge_launch_block_##name(int, int, bool, int, int, int, const KgeBlockArgs &, int, int, hipStream_t);
@@ -18,14 +21,12 @@ KGE_DECL(bf16_score) KGE_DECL(bf16_fwd_ls) KGE_DECL(bf16_fwd_sm) KGE_DECL(bf16_g
 
 // whether the row-owner pass of this configuration runs the two-role kernel (which needs no transposed negatives)
 bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
-    return bf16 && rb == 512 && !transh && dsplit == 1 && kge_use_fwd_pp();
+    return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_FWD_ONE_ROLE);
 }
 
-// the same for the pass over the negatives (one own fragment per wave there; needs no transposed queries);
-// KGE_GRADT_ONE_ROLE=1 selects the one-role kernel
+// the same for the pass over the negatives (one own fragment per wave there; needs no transposed queries)
 bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
-    static const bool on = [] { const char *e = getenv("KGE_GRADT_ONE_ROLE"); return !(e && e[0] == '1'); }();
-    return bf16 && rb == 512 && !transh && dsplit == 1 && on;
+    return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_GRADT_ONE_ROLE);
 }
 
 int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,

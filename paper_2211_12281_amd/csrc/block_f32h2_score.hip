@@ -321,12 +321,8 @@ void score_h2_transh_kernel(const ScoreH2Args a) {
 }
 
 template <typename K>
-int launch_h2(K kern, int lds_bytes, bool &attr_set, const ScoreH2Args &a, hipStream_t st) {
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
-            return KGE_E_HIP;
-        attr_set = true;
-    }
+int launch_h2(K kern, int lds_bytes, KgeLdsLimit &lds_limit, const ScoreH2Args &a, hipStream_t st) {
+    if (lds_limit.set((const void *)kern, lds_bytes) != KGE_OK) return KGE_E_HIP;
     ScoreH2Args b = a;
     int groups;
     if (a.nsplit >= 8) { b.xcd_per = 1; groups = a.own_tiles * ((a.nsplit + 7) / 8); }
@@ -344,16 +340,16 @@ template <int DP>
 int launch_transh(const ScoreH2Args &a, hipStream_t st) {
     constexpr int LDS = H2_NSTAGE * (4 * H2_ST * 256) + H2_NSTAGE * 4 * 1024;
     static_assert(LDS <= 160 * 1024, "LDS budget");
-    static bool attr_set = false;
-    return launch_h2(score_h2_transh_kernel<DP>, LDS, attr_set, a, st);
+    static KgeLdsLimit lds_limit;
+    return launch_h2(score_h2_transh_kernel<DP>, LDS, lds_limit, a, st);
 }
 
 template <int DP, int KIND>
 int launch_one(const ScoreH2Args &a, hipStream_t st) {
     constexpr int LDS = H2_NSTAGE_ONE * (2 * H2_ST * DP * 2) + H2_NSTAGE_ONE * 4 * 1024;
     static_assert(2 * LDS <= 160 * 1024, "LDS budget of two workgroups");
-    static bool attr_set = false;
-    return launch_h2(score_h2_kernel<DP, KIND>, LDS, attr_set, a, st);
+    static KgeLdsLimit lds_limit;
+    return launch_h2(score_h2_kernel<DP, KIND>, LDS, lds_limit, a, st);
 }
 
 }  // namespace

@@ -394,11 +394,8 @@ template <int MODE, int KIND, int LOSS>
 int pp_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
     auto kern = kge_pp_kernel<MODE, KIND, LOSS>;
     constexpr int LDS = pp_lds(MODE);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess) return KGE_E_HIP;
-        attr_set = true;
-    }
+    static KgeLdsLimit lds_limit;
+    if (lds_limit.set((const void *)kern, LDS) != KGE_OK) return KGE_E_HIP;
     if ((int64_t)own_tiles * 128 != a.own_pad || a.dp != PP_DP) return KGE_E_INVALID_ARG;
     KgeBlockArgs b = a;
     b.own_tiles = own_tiles; b.nsplit = nsplit;

@@ -632,12 +632,8 @@ template <bool BF16, int RB, int MODE, bool TRANSH, int KIND, int LOSS, int DSPL
 int kge_block_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st) {
     using C = KgeBlockCfg<BF16, RB, MODE, TRANSH, KIND, DSPLIT>;
     auto kern = kge_block_kernel<BF16, RB, MODE, TRANSH, KIND, LOSS, DSPLIT>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
-            return KGE_E_HIP;
-        attr_set = true;
-    }
+    static KgeLdsLimit lds_limit;
+    if (lds_limit.set((const void *)kern, C::LDS_BYTES) != KGE_OK) return KGE_E_HIP;
     if ((int64_t)own_tiles * C::OWN_TILE != a.own_pad) return KGE_E_INVALID_ARG;   // the caller's geometry must match
     KgeBlockArgs b = a;
     b.own_tiles = own_tiles; b.nsplit = nsplit;

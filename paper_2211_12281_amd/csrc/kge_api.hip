@@ -1,7 +1,6 @@
 // extern "C" entry points: argument validation, workspace carving, kernel sequencing.
 #include "prep_kernels.h"
 #include <math.h>
-#include <stdlib.h>
 
 int kge_run_sparse_adam(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
                         const int32_t *idx, const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws,
@@ -112,12 +111,10 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     return g;
 }
 
-// fp32 score blocks go through two fp16 planes on the 16-bit matrix pipe (block_f32h2_score.hip); KGE_SCORE_F32_MFMA=1
-// in the environment (read at every call) keeps the fp32 matrix instructions (cross-check)
+// fp32 score blocks go through two fp16 planes on the 16-bit matrix pipe (block_f32h2_score.hip); other row sizes, and
+// the comparison that kge_debug_select(KGE_DEBUG_SCORE_F32_MFMA, 1) asks for, use the fp32 matrix instructions
 bool score_h2_applies(const Geometry &g) {
-    const char *e = getenv("KGE_SCORE_F32_MFMA");
-    const bool off = e && e[0] == '1';
-    return !off && !g.bf16 && !g.l1 && (g.dp == 128 || g.dp == 256) && g.N > 0;
+    return !kge_knob(KGE_KNOB_SCORE_F32_MFMA) && !g.bf16 && !g.l1 && (g.dp == 128 || g.dp == 256) && g.N > 0;
 }
 
 // bump allocator over the caller's workspace (256-byte granules); with base == nullptr it only sizes

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <mutex>
 #include "../../include/kge.h"
 
 #define KGE_HIP_TRY(expr)                                   \
@@ -21,6 +22,20 @@ struct KgeProfScope {
     ~KgeProfScope();
     int slot_; hipStream_t st_; void *a_, *b_;
 };
+
+// Raises a kernel's dynamic LDS limit once per process; safe when several threads make the first launch together.
+struct KgeLdsLimit {
+    std::once_flag once;
+    hipError_t err = hipSuccess;
+    int set(const void *kern, int bytes) {
+        std::call_once(once, [&] { err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+        return err == hipSuccess ? KGE_OK : KGE_E_HIP;
+    }
+};
+
+// Kernel choices that only tests and benchmarks override (kge_debug_select); 0 = the library's own choice.
+enum { KGE_KNOB_FWD_ONE_ROLE = 0, KGE_KNOB_GRADT_ONE_ROLE = 1, KGE_KNOB_SCORE_F32_MFMA = 2, KGE_KNOBS = 3 };
+int kge_knob(int knob);
 
 static inline int64_t kge_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 

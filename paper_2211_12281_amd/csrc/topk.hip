@@ -632,7 +632,11 @@ __global__ void topk_exact_kernel(KgeModelDev m, const int32_t *h, const int32_t
             if (kc <= tau) { const int s = atomicAdd(&count, 1); key[s] = kc; idx[s] = (int)c; }   // s < CAPX by the compaction below
         }
         __syncthreads();
-        if (count > CAPX - (int)blockDim.x) {                // next round could overflow: compact to the K best
+        // every thread reads the counter between two barriers, so that no wave can start the next round's appends before
+        // a slower one has taken the same decision
+        const bool compact = count > CAPX - (int)blockDim.x;   // next round could overflow: compact to the K best
+        __syncthreads();
+        if (compact) {
             bitonic_asc_pair(key, idx, CAPX);
             if (threadIdx.x == 0) { count = K; tau = key[K - 1]; }
             __syncthreads();
@@ -887,12 +891,8 @@ template <bool BF16, int RB, int KIND, int OB, bool TH = false>
 int launch_scan(const TopkArgs &a, int own_tiles, int nsplit, hipStream_t st) {
     constexpr int NSTAGE = RB == 512 ? 4 : 3;
     constexpr int LDS = NSTAGE * TK_ST * RB + (NSTAGE + 1) * 4 * 256;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)topk_scan_kernel<BF16, RB, KIND, OB, TH>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
-            return KGE_E_HIP;
-        attr_set = true;
-    }
+    static KgeLdsLimit lds_limit;
+    if (lds_limit.set((const void *)topk_scan_kernel<BF16, RB, KIND, OB, TH>, LDS) != KGE_OK) return KGE_E_HIP;
     hipLaunchKernelGGL((topk_scan_kernel<BF16, RB, KIND, OB, TH>), dim3(own_tiles * ((nsplit + 7) / 8 * 8)), dim3(256), LDS, st, a);
     return kge_launch_status();
 }

@@ -90,6 +90,31 @@ def test_all_indices_equal_and_empty(orc):
     _check(orc, 100, 8, 0, step=1, warm=True, shadow=False)
 
 
+@pytest.mark.parametrize("runs", [[(17, 6000)], [(3, 2500), (41, 2300)], [(0, 31), (9, 2049), (30, 33), (49, 2047)]])
+def test_long_runs_of_equal_ids(orc, runs):
+    """Runs of equal ids far longer than the 64 chunks x 32 positions that the wave of a run's first chunk probes per
+    round (the continuation of that search), alone and side by side, starting at positions that straddle chunk
+    boundaries; against the oracle, and bit-identical from call to call."""
+    import paper_2211_12281_amd as kge
+    theta, m, v = _state(50, 64, 3, True)
+    idx = np.concatenate([np.full(n, row, np.int32) for row, n in runs])
+    M = idx.size
+    grads = (np.random.default_rng(5).normal(size=(M, 64)) * 1e-2).astype(F)
+    outs = []
+    for _ in range(2):
+        dth, dm, dv = [torch.from_numpy(a.copy()).cuda() for a in (theta, m, v)]
+        kge.sparse_adam(dth, None, dm, dv, torch.from_numpy(idx).cuda(), torch.from_numpy(grads).cuda(), 1e-3, step=2)
+        outs.append((dth.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy()))
+    assert all(np.array_equal(a, b) for a, b in zip(*outs))
+    rth, rm, rv, touched = orc.sparse_adam(theta, m, v, idx, grads, float(F(1e-3)), float(F(0.9)), float(F(0.999)),
+                                           float(F(1e-8)), 2)
+    assert touched.sum() == len(runs)
+    gth, gm, gv = outs[0]
+    assert np.array_equal(gth[~touched], theta[~touched])
+    assert update_err_ok(gth[touched], theta[touched], rth[touched])
+    assert norm_err(gm[touched], rm[touched]) <= RTOL_F32 and norm_err(gv[touched], rv[touched]) <= RTOL_F32
+
+
 def test_padded_row_stride(orc):
     """Tables whose row stride exceeds dim (ld > dim): padding columns stay untouched."""
     import paper_2211_12281_amd as kge

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import kge_synth as ks
-from helpers import RTOL_BF16, RTOL_F32, dev_idx, norm_err
+from helpers import RTOL_BF16, RTOL_F32, dev_idx, l1_sign_flips_justified, norm_err, rank_band_eps, row_norm_err
 
 pytestmark = [pytest.mark.gpu, pytest.mark.full]
 F = np.float32
@@ -52,6 +52,7 @@ def test_c2_scoring_all_scorers_full_size(orc):
         rp, rn = orc.score_batch(s, rows, rel, relw, ch, r, ct, cn)
         assert norm_err(pos.cpu().numpy(), rp) <= RTOL_F32, s
         assert norm_err(blk.cpu().numpy(), rn) <= RTOL_F32, s
+        assert row_norm_err(blk.cpu().numpy(), rn) <= RTOL_F32, s          # every row against its own largest score
     del ent, model
     _free()
 
@@ -103,7 +104,9 @@ def test_c3_complex_training_step_full_size(orc):
     ge = out["g_ent"].cpu().numpy()
     for name, sl in (("heads", slice(0, B)), ("tails", slice(B, 2 * B)), ("negatives", slice(2 * B, 2 * B + N))):
         assert norm_err(ge[sl], ref["g_ent"][sl]) <= RTOL_BF16, name
+        assert row_norm_err(ge[sl], ref["g_ent"][sl]) <= RTOL_BF16, name   # every row against its own largest entry
     assert norm_err(out["g_rel"].cpu().numpy(), ref["g_rel"]) <= RTOL_BF16
+    assert row_norm_err(out["g_rel"].cpu().numpy(), ref["g_rel"]) <= RTOL_BF16
     assert np.array_equal(out["g_ent_idx"].cpu().numpy(), np.concatenate([h, t, neg_h]))
     # sparse Adam on the 10M-row tables with the GPU's own gradient rows as the common input
     m = torch.zeros_like(master); v = torch.zeros_like(master)
@@ -157,11 +160,13 @@ def test_c3_shapes_one_norm_full_size(orc, scorer):
              ("negatives", ge[2 * B:], ref["g_ent"][2 * B:]), ("relations", out["g_rel"].cpu().numpy(), ref["g_rel"])]
     if scorer == "transh":
         parts.append(("normals", out["g_relw"].cpu().numpy(), ref["g_relw"]))
-    flipped = total = 0
-    for name, x, rf in parts:
-        e = np.abs(x.astype(np.float64) - rf) / np.max(np.abs(rf))
-        flipped += int(np.sum(e > 2e-5)); total += e.size
-        assert e.max() < 0.05, name
+    got = {"g_ent": ge, "g_rel": out["g_rel"].cpu().numpy(), "g_relw": None if relw is None else out["g_relw"].cpu().numpy()}
+    # every outlying element must sit on a coordinate that the oracle finds within fp32 rounding of zero (checked for the
+    # 24 largest deviations and an even sample of 24 more per tensor: each check rebuilds the row's difference vectors)
+    flipped = l1_sign_flips_justified(orc, scorer, "sampled_softmax", rows, ks.round_to_bf16(rel),
+                                      None if relw is None else ks.round_to_bf16(relw), ch, r, ct, cn,
+                                      dict(n_ent_for_c=n_ent), got, ref, 2e-5, max_checked=48)
+    total = sum(v.size for v in got.values() if v is not None)
     assert flipped <= (64 if scorer == "transe" else 1e-3 * total), flipped
     del shadow, model
     _free()
@@ -193,10 +198,13 @@ def test_c4_link_prediction_full_size(orc, scorer):
     for q in range(0, Q, 41):
         pos = np.where(idx[q] == tt[q])[0]
         assert (len(pos) == 1 and rank[q] == pos[0] + 1) or (len(pos) == 0 and rank[q] > K)
-    # exact comparison on a subset
-    sub = np.r_[0:4, np.arange(100, 8192, 700)][:16]
+    # exact comparison on a subset: 128 queries for the two scorers the configuration names, 16 for the other three
+    nsub = 128 if scorer in ("distmult", "transe") else 16
+    sub = np.r_[0:4, np.arange(100, 8192, 8092 // (nsub - 4))][:nsub]
     host = ent.float().cpu().numpy()
-    ridx, rsc, rrank = orc.topk(scorer, host, rel, relw, h[sub], r[sub], 0, n_ent, K, tt[sub])
+    t_max = float(np.sqrt(np.max(np.einsum("ij,ij->i", host, host, dtype=np.float64))))
+    eps = rank_band_eps(scorer, host[h[sub]], rel[r[sub]], None if relw is None else relw[r[sub]], True, t_max)
+    ridx, rsc, rrank, band = orc.topk_band(scorer, host, rel, relw, h[sub], r[sub], 0, n_ent, K, tt[sub], eps)
     if scorer in ("rotate", "transh"):
         # cos / sin in fp64 differ in the last bit between math libraries (TransH: the summation order of the fp64
         # normalisation and dot products is the implementation's): candidates whose keys agree to 1e-12 may swap
@@ -209,9 +217,12 @@ def test_c4_link_prediction_full_size(orc, scorer):
     assert np.max(np.abs(sc[sub] - rsc)) <= RTOL_F32 * np.max(np.abs(rsc))
     inside = rrank <= K
     assert np.array_equal(rank[sub][inside], rrank[inside])
-    # beyond the list: counted with matrix-core values; the band of candidates within the rounding error of the
-    # true tail's score is a small fraction of the table
-    assert np.all(np.abs(rank[sub][~inside] - rrank[~inside]) <= 0.02 * n_ent)
+    # beyond the list the rank is counted with matrix-core values: off by at most the number of candidates whose exact
+    # key lies within the error band of those values around the true tail's key (counted by the oracle in its pass)
+    dev = np.abs(rank[sub][~inside] - rrank[~inside])
+    assert np.all(dev <= band[~inside]), (dev.max(), band[~inside].min())
+    print(f"c4 {scorer}: rank beyond K off by max {int(dev.max()) if dev.size else 0}, median "
+          f"{float(np.median(dev)) if dev.size else 0.0}; band max {int(band.max())} of {n_ent} candidates")
     del ent, host, model
     _free()
 
@@ -249,8 +260,11 @@ def test_c5_transh_partition_pair_step_full_size(orc):
     ge = out["g_ent"].cpu().numpy()
     for name, sl in (("heads", slice(0, B)), ("tails", slice(B, 2 * B)), ("negatives", slice(2 * B, 2 * B + N))):
         assert norm_err(ge[sl], ref["g_ent"][sl]) <= RTOL_F32, name
+        assert row_norm_err(ge[sl], ref["g_ent"][sl]) <= RTOL_F32, name
     assert norm_err(out["g_rel"].cpu().numpy(), ref["g_rel"]) <= RTOL_F32
     assert norm_err(out["g_relw"].cpu().numpy(), ref["g_relw"]) <= RTOL_F32
+    assert row_norm_err(out["g_rel"].cpu().numpy(), ref["g_rel"]) <= RTOL_F32
+    assert row_norm_err(out["g_relw"].cpu().numpy(), ref["g_relw"]) <= RTOL_F32
     lr, b1, b2, eps = float(F(1e-3)), float(F(0.9)), float(F(0.999)), float(F(1e-8))
     kge.sparse_adam(theta, None, m, v, out["g_ent_idx"], out["g_ent"], lr, b1, b2, eps, step=1)
     zr = np.zeros(rows.shape)

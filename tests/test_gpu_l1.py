@@ -2,13 +2,14 @@
 oracle.  The gradient of a 1-norm is discontinuous where a coordinate of h + r - t crosses zero, so the TransE
 cases put the tables on a binary grid on which every sum and difference is exact in fp32 and in bf16 (no sign can
 differ between the two implementations; with the relations on the same grid the micro-batch is full of exact ties,
-which must give the sub-gradient 0).  RotatE goes through sin / cos, where a sign may flip for a coordinate within
-rounding of zero: there a handful of outlying gradient elements is tolerated and counted."""
+which must give the sub-gradient 0).  RotatE goes through sin / cos and TransH through projections, where a sign may
+flip for a coordinate within fp32 rounding of zero: there every outlying gradient element must be explained from the
+oracle's side by such a coordinate (helpers.l1_sign_flips_justified)."""
 import numpy as np
 import pytest
 
 import kge_synth as ks
-from helpers import RTOL_BF16, RTOL_F32, dev_idx, norm_err, small_graph, to_dev
+from helpers import RTOL_BF16, RTOL_F32, dev_idx, l1_sign_flips_justified, norm_err, small_graph, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -35,7 +36,7 @@ def _outliers(x, ref, tol):
     return int(np.sum(e > tol)), float(e.max()) if e.size else 0.0
 
 
-def _compare(orc, scorer, loss, G, bf16, n_ent, kw, max_outliers=0):
+def _compare(orc, scorer, loss, G, bf16, n_ent, kw):
     import paper_2211_12281_amd as kge
     out = kge.loss_bwd(_model(scorer, G, bf16), loss, dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]), **kw)
     ref = orc.loss_bwd(scorer + "_l1", loss, G["ent"], G["rel"], None, G["h"], G["r"], G["t"], G["neg"], **kw)
@@ -50,7 +51,7 @@ def _compare(orc, scorer, loss, G, bf16, n_ent, kw, max_outliers=0):
             continue
         bad, worst = _outliers(x, r, tol)
         total += bad
-        assert bad <= max_outliers and worst < 0.5, (name, bad, worst)
+        assert bad == 0, (name, bad, worst)               # exact grids: no sign can differ
     assert np.array_equal(out["g_ent_idx"].cpu().numpy(), ref["g_ent_idx"])
     assert np.array_equal(out["g_rel_idx"].cpu().numpy(), ref["g_rel_idx"])
     return total
@@ -91,18 +92,15 @@ def test_rotate_loss_and_gradients(orc, loss, bf16):
     if bf16:
         G["ent"], G["rel"] = ks.round_to_bf16(G["ent"]), ks.round_to_bf16(G["rel"])
     kw = dict(n_ent_for_c=4000) if loss == "sampled_softmax" else dict(gamma=8.0, adv_temp=0.3)
-    # the arithmetic is fp32 for both table types: fp32 tolerance, at most a few sign flips in 4.3 M coordinates
-    G2 = dict(G)
+    # the arithmetic is fp32 for both table types: fp32 tolerance; a sign may differ only where the oracle finds a
+    # coordinate within rounding of zero
     import paper_2211_12281_amd as kge
     out = kge.loss_bwd(_model("rotate", G, bf16), loss, dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]), **kw)
     ref = orc.loss_bwd("rotate_l1", loss, G["ent"], G["rel"], None, G["h"], G["r"], G["t"], G["neg"], **kw)
     assert abs(out["loss"].item() - ref["loss"]) <= RTOL_F32 * abs(ref["loss"])
-    bad_total = 0
-    for x, r in ((out["g_ent"].cpu().numpy(), ref["g_ent"]), (out["g_rel"].cpu().numpy(), ref["g_rel"])):
-        bad, worst = _outliers(x, r, 2e-5)
-        bad_total += bad
-        assert worst < 0.5
-    assert bad_total <= 6, bad_total
+    got = {k2: out[k2].cpu().numpy() for k2 in ("g_ent", "g_rel")}
+    flips = l1_sign_flips_justified(orc, "rotate", loss, G["ent"], G["rel"], None, G["h"], G["r"], G["t"], G["neg"], kw, got, ref, 2e-5)
+    assert flips <= 1e-4 * (got["g_ent"].size + got["g_rel"].size)
 
 
 @pytest.mark.parametrize("dim,bf16", [(128, False), (256, True), (512, True), (32, False)])
@@ -157,7 +155,7 @@ def test_transh_scores_match_oracle(orc, bf16):
 @pytest.mark.parametrize("shape", [(200, 333, 64), (130, 70, 208), (1, 1, 32), (3, 0, 32), (65, 129, 128)])
 def test_transh_loss_and_gradients(orc, loss, bf16, shape):
     """TransH with the 1-norm: the normalisation of w and the projections make exact grids impossible, so a sign may
-    flip for a coordinate within rounding of zero: a handful of outlying gradient elements is tolerated and counted."""
+    flip for a coordinate within rounding of zero: every outlying gradient element must be explained by such a coordinate."""
     import paper_2211_12281_amd as kge
     B, N, dim = shape
     G = _transh_case(4000, 12, dim, B, N, bf16)
@@ -165,14 +163,9 @@ def test_transh_loss_and_gradients(orc, loss, bf16, shape):
     out = kge.loss_bwd(_transh_model(G, bf16), loss, dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"]), dev_idx(G["neg"]), **kw)
     ref = orc.loss_bwd("transh_l1", loss, G["ent"], G["rel"], G["relw"], G["h"], G["r"], G["t"], G["neg"], **kw)
     assert abs(out["loss"].item() - ref["loss"]) <= RTOL_F32 * abs(ref["loss"])
-    bad_total = 0
-    for name in ("g_ent", "g_rel", "g_relw"):
-        if ref[name].size == 0:
-            continue
-        bad, worst = _outliers(out[name].cpu().numpy(), ref[name], 2e-5)
-        bad_total += bad
-        assert worst < 0.5, (name, worst)
-    assert bad_total <= 8, bad_total
+    got = {k2: out[k2].cpu().numpy() for k2 in ("g_ent", "g_rel", "g_relw")}
+    flips = l1_sign_flips_justified(orc, "transh", loss, G["ent"], G["rel"], G["relw"], G["h"], G["r"], G["t"], G["neg"], kw, got, ref, 2e-5)
+    assert flips <= 1e-3 * sum(v.size for v in got.values()) + 8
     assert np.array_equal(out["g_ent_idx"].cpu().numpy(), ref["g_ent_idx"])
     assert np.array_equal(out["g_rel_idx"].cpu().numpy(), ref["g_rel_idx"])
 

@@ -36,14 +36,18 @@ def test_large_rows_fp32_1024_bytes(orc, scorer):
 
 @pytest.mark.parametrize("scorer", SCORERS)
 @pytest.mark.parametrize("dim", [128, 104, 200])
-def test_fp32_tables_on_the_bf16_pipe(orc, scorer, dim, monkeypatch):
+def test_fp32_tables_on_the_bf16_pipe(orc, scorer, dim):
     """fp32 rows padded to 128 or 256 dimensions are contracted as two fp16 pieces per operand: against the oracle,
-    and against the kernel that uses the fp32 matrix instructions (selected through the environment)."""
+    and against the kernel that uses the fp32 matrix instructions (selected through the library's debug call)."""
+    import paper_2211_12281_amd as kge
     G = make_case(scorer, 4000, 12, dim, 200, 333, False)
     pos, neg, rp, rn = _run(orc, scorer, G, False)
     assert norm_err(pos, rp) <= RTOL_F32 and norm_err(neg, rn) <= RTOL_F32
-    monkeypatch.setenv("KGE_SCORE_F32_MFMA", "1")
-    pos2, neg2, _, _ = _run(orc, scorer, G, False)
+    kge.debug_select("score_f32_mfma", True)
+    try:
+        pos2, neg2, _, _ = _run(orc, scorer, G, False)
+    finally:
+        kge.debug_select("score_f32_mfma", False)
     assert norm_err(neg2, rn) <= RTOL_F32
     assert norm_err(neg, neg2) <= RTOL_F32 and np.array_equal(pos, pos2)
 

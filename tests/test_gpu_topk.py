@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import kge_synth as ks
-from helpers import RTOL_BF16, RTOL_F32, dev_idx, gpu_model, make_case, norm_err, small_graph, to_dev
+from helpers import RTOL_BF16, RTOL_F32, dev_idx, gpu_model, make_case, norm_err, rank_band_eps, small_graph, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -36,15 +36,15 @@ def _check(orc, scorer, G, bf16, lo, hi, K, true_t=None):
         inside = rrank <= n
         assert np.array_equal(rank[inside], rrank[inside])          # exact whenever the tail is in the list
         assert np.all(rank[~inside] > n)
-        # beyond the list the rank is counted with matrix-core values: allowed to differ by the number of
-        # candidates whose exact score lies within the rounding band around the true tail's score
+        # beyond the list the rank is counted with matrix-core values: it may differ from the exact rank by at most the
+        # number of candidates whose exact key lies inside the error band of those values around the true tail's key,
+        # which the oracle counts in the same pass
         if (~inside).any() and hi > lo:
-            cand = np.arange(lo, hi, dtype=np.int32)
-            for q in np.where(~inside)[0][:16]:
-                one = slice(q, q + 1)
-                st, s = orc.score_batch(scorer, G["ent"], G["rel"], relw, G["h"][one], G["r"][one], true_t[one], cand)
-                band = (2e-2 if bf16 else 1e-5) * max(np.max(np.abs(s)), 1e-30)
-                assert abs(int(rank[q]) - int(rrank[q])) <= int(np.sum(np.abs(s[0] - st[0]) <= band)) + 1
+            t_max = float(np.max(np.linalg.norm(G["ent"][lo:hi].astype(np.float64), axis=1)))
+            eps = rank_band_eps(scorer, G["ent"][G["h"]], G["rel"][G["r"]], None if relw is None else relw[G["r"]], bf16, t_max)
+            _, _, rrank2, band = orc.topk_band(scorer, G["ent"], G["rel"], relw, G["h"], G["r"], lo, hi, K, true_t, eps)
+            assert np.array_equal(rrank2, rrank)
+            assert np.all(np.abs(rank[~inside] - rrank[~inside]) <= band[~inside])
 
 
 @pytest.mark.parametrize("scorer", ["distmult", "transe", "complex", "rotate", "transh"])

@@ -133,3 +133,35 @@ def test_topk_orders_by_the_one_norm(orc):
         assert np.array_equal(idx[q], order[:10])
         assert np.allclose(score[q], -key[order[:10]], rtol=0, atol=1e-12)
         assert rank[q] == 1 + int(np.where(order == [7, 9][q])[0][0])
+
+
+def test_sign_flip_justification_accepts_only_coordinates_near_zero(orc):
+    """The helper that the GPU tests use to accept a flipped sign: a deviation of 2 |dL/dS| at a column whose coordinate
+    lies within rounding of zero passes; the same deviation anywhere else, or a larger one at that column, fails."""
+    from helpers import l1_sign_flips_justified, small_graph
+    G = small_graph("transe", 300, 4, 16, 12, 20, amp=0.4)
+    b, n, j = 5, 7, 3
+    # put coordinate j of pair (b, n) a hair above zero: h + r - t = 1e-9-ish (well inside the band, not a tie)
+    G["ent"][G["neg"][n], j] = np.float32(G["ent"][G["h"][b], j] + G["rel"][G["r"][b], j]) - np.float32(2e-8)
+    kw = dict(n_ent_for_c=300)
+    args = (G["ent"], G["rel"], None, G["h"], G["r"], G["t"], G["neg"])
+    ref = orc.loss_bwd("transe_l1", "sampled_softmax", *args, **kw)
+    x = (np.float64(G["ent"][G["h"][b], j]) + np.float64(G["rel"][G["r"][b], j])) - np.float64(G["ent"][G["neg"][n], j])
+    assert 0 < abs(x) < 1e-7
+    # dL/dS(b, n) from the head's gradient: flipping sign(x) moves g_head[b, j] and g_neg[n, j] by 2 dL/dS each
+    pos, S = orc.score_batch("transe_l1", *args)
+    c = np.log(299 / 20)
+    z = np.concatenate([pos[:, None], S + c], axis=1); p = np.exp(z - z.max(axis=1, keepdims=True)); p /= p.sum(axis=1, keepdims=True)
+    gbn = p[b, 1 + n] / 12
+    same = lambda: {"g_ent": ref["g_ent"].copy(), "g_rel": ref["g_rel"].copy()}
+    assert l1_sign_flips_justified(orc, "transe", "sampled_softmax", *args, kw, same(), ref, 1e-5) == 0
+    got = same()
+    sgn = np.sign(x)
+    got["g_ent"][b, j] += 2 * sgn * gbn; got["g_rel"][b, j] += 2 * sgn * gbn; got["g_ent"][2 * 12 + n, j] -= 2 * sgn * gbn
+    assert l1_sign_flips_justified(orc, "transe", "sampled_softmax", *args, kw, got, ref, 1e-5) == 3
+    bad = same(); bad["g_ent"][b, j + 1] += 2 * gbn                       # right size, wrong column
+    with pytest.raises(AssertionError):
+        l1_sign_flips_justified(orc, "transe", "sampled_softmax", *args, kw, bad, ref, 1e-5)
+    bad = same(); bad["g_ent"][b, j] += 6 * sgn * gbn                     # right column, three times the allowance
+    with pytest.raises(AssertionError):
+        l1_sign_flips_justified(orc, "transe", "sampled_softmax", *args, kw, bad, ref, 1e-5)

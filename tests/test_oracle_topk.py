@@ -60,6 +60,32 @@ def test_ties_go_to_the_lower_index_and_sub_ranges(orc):
     assert rank[0] == rank[2] + 2 and rank[1] == rank[2] + 1
 
 
+@pytest.mark.parametrize("scorer", ["distmult", "transe", "rotate"])
+def test_band_count_equals_a_direct_count(orc, scorer):
+    """topk_band: the ranking is that of topk; the band is the number of candidates whose key (DistMult: -score; distance
+    scorers: squared distance) differs from the held-out tail's by at most eps - counted here from scores evaluated one
+    by one, with eps per query from zero (ties of the tail with itself and its copies only) to wider than every gap."""
+    G = small_graph(scorer, n_ent=400, n_rel=5, dim=16, B=8, N=0, normal=True)
+    G["ent"][333] = G["ent"][G["t"][1]]                          # an exact copy of query 1's held-out tail
+    lo, hi = 3, 390
+    cand = np.arange(lo, hi)
+    def key(q, c):
+        s = orc.score_one(scorer, G["ent"][G["h"][q]], G["rel"][G["r"][q]], None, G["ent"][c])
+        return -s if scorer == "distmult" else s * s
+    eps = np.array([0.0, 0.0, 1e-3, 1e-2, 5e-2, 0.3, 1e9, 2e-2])
+    idx, sc, rank, band = orc.topk_band(scorer, G["ent"], G["rel"], None, G["h"], G["r"], lo, hi, 20, G["t"], eps)
+    ridx, rsc, rrank = orc.topk(scorer, G["ent"], G["rel"], None, G["h"], G["r"], lo, hi, 20, G["t"])
+    assert np.array_equal(idx, ridx) and np.array_equal(sc, rsc) and np.array_equal(rank, rrank)
+    for q in range(8):
+        kt = key(q, G["t"][q])
+        keys = np.array([key(q, c) for c in cand])
+        # (the square of the rounded root is not the oracle's own key: leave out candidates within 1e-12 of the edge)
+        edge = np.abs(np.abs(keys - kt) - eps[q]) <= 1e-12 * max(abs(kt), 1.0)
+        lo_n, hi_n = int(np.sum((np.abs(keys - kt) <= eps[q]) & ~edge)), int(np.sum((np.abs(keys - kt) <= eps[q]) | edge))
+        assert lo_n <= band[q] <= hi_n, (q, band[q], lo_n, hi_n)
+    assert band[6] == hi - lo and band[1] >= (2 if lo <= G["t"][1] < hi else 1)
+
+
 def test_bucketing_matches_numpy(orc):
     g = ks.rng(1, ks.TAG_TRIPLE_H)
     n_ent, D, n = 1003, 4, 5000
