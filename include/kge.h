@@ -390,9 +390,11 @@ int kge_calibrate_copy(const void *src, void *dst, size_t bytes, double *gbs_out
  *   KGE_DEBUG_FWD_ONE_ROLE    the pass over the queries of kge_loss_bwd (bf16, rows <= 512 bytes) as the one-role kernel
  *   KGE_DEBUG_GRADT_ONE_ROLE  the same for the pass over the negatives
  *   KGE_DEBUG_SCORE_F32_MFMA  kge_score on fp32 tables with the fp32 matrix instructions instead of two fp16 planes
+ *   KGE_DEBUG_TWO_ROLE        both of those passes as the two-role kernels (the forward one is also what redoes a pass
+ *                             whose scores outgrow the delayed reference exponent of the default kernel)
  * Returns KGE_E_INVALID_ARG for an unknown knob or a value other than 0 / 1.
  */
-enum { KGE_DEBUG_FWD_ONE_ROLE = 0, KGE_DEBUG_GRADT_ONE_ROLE = 1, KGE_DEBUG_SCORE_F32_MFMA = 2 };
+enum { KGE_DEBUG_FWD_ONE_ROLE = 0, KGE_DEBUG_GRADT_ONE_ROLE = 1, KGE_DEBUG_SCORE_F32_MFMA = 2, KGE_DEBUG_TWO_ROLE = 3 };
 int kge_debug_select(int knob, int value);
 
 /* Static description of a status code. */

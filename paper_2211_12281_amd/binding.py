@@ -309,7 +309,7 @@ def ensemble(lists, p: float, K_out: int = 10):
     return out_idx, out_score
 
 
-DEBUG_KNOBS = {"fwd_one_role": 0, "gradt_one_role": 1, "score_f32_mfma": 2}
+DEBUG_KNOBS = {"fwd_one_role": 0, "gradt_one_role": 1, "score_f32_mfma": 2, "two_role": 3}
 
 
 def debug_select(knob: str, value: bool):

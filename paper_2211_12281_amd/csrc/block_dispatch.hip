@@ -4,6 +4,8 @@
 
 int kge_launch_fwd_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
 int kge_launch_gradt_pp(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
+int kge_launch_fwd_sym(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
+int kge_launch_gradt_sym(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
 
 // Every job has ONE kernel in the library's own dispatch.  Tests and benchmarks that compare two kernels of one job
 // override the choice through kge_debug_select (process-wide, off by default).
@@ -24,6 +26,18 @@ bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
     return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_FWD_ONE_ROLE);
 }
 
+// Bilinear scorers in these configurations run the kernel of block_sym.hip (64 own rows per pair of waves): the pass over
+// the negatives with both losses, the pass over the queries with the sampled softmax.  The two-role kernels serve the
+// distance scorers and the log-sigmoid forward pass, redo a forward pass whose scores outgrow the fixed reference of
+// the other kernel, and stand in for it in comparisons (KGE_KNOB_TWO_ROLE).
+bool kge_sym_applies(bool bf16, int rb, bool transh, int dsplit) {
+    return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_FWD_ONE_ROLE) && !kge_knob(KGE_KNOB_GRADT_ONE_ROLE) &&
+           !kge_knob(KGE_KNOB_TWO_ROLE);
+}
+static bool sym_serves(int mode, int kind, int loss) {
+    return kind == KGE_KIND_MULT && (mode == KGE_MODE_GRADT || loss == KGE_SAMPLED_SOFTMAX);
+}
+
 // the same for the pass over the negatives (one own fragment per wave there; needs no transposed queries)
 bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
     return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_GRADT_ONE_ROLE);
@@ -36,12 +50,20 @@ int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int los
                     : kge_launch_block_f32_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st);
     const bool ls = loss == KGE_LOGSIGMOID;
     if (mode == KGE_MODE_FWD) {
+        if (kge_sym_applies(bf16, rb, transh, dsplit) && sym_serves(mode, kind, loss)) {
+            const int rc = kge_launch_fwd_sym(kind, loss, a, own_tiles, nsplit, st);
+            if (rc != KGE_OK) return rc;
+            KgeBlockArgs b = a;                              // redone only if the first kernel raised the flag
+            b.gate = a.flag;
+            return kge_launch_fwd_pp(kind, loss, b, own_tiles, nsplit, st);
+        }
         if (kge_fwd_pp_applies(bf16, rb, transh, dsplit)) return kge_launch_fwd_pp(kind, loss, a, own_tiles, nsplit, st);
         if (bf16) return ls ? kge_launch_block_bf16_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
                             : kge_launch_block_bf16_fwd_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
         return ls ? kge_launch_block_f32_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
                   : kge_launch_block_f32_fwd_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);
     }
+    if (kge_sym_applies(bf16, rb, transh, dsplit) && sym_serves(mode, kind, loss)) return kge_launch_gradt_sym(kind, loss, a, own_tiles, nsplit, st);
     if (kge_gradt_pp_applies(bf16, rb, transh, dsplit)) return kge_launch_gradt_pp(kind, loss, a, own_tiles, nsplit, st);
     if (bf16) return ls ? kge_launch_block_bf16_gradt_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
                         : kge_launch_block_bf16_gradt_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);

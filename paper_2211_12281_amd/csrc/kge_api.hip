@@ -91,17 +91,19 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.own_tiles_n = g.Np / (128 * (kge_gradt_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_t) ? 1 : kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_GRADT, g.kind)));
     g.own_tiles_s = g.Np / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_SCORE, g.kind));
     g.str_tiles_b = g.Bp / KGE_STREAM_TILE; g.str_tiles_n = g.Np / KGE_STREAM_TILE;
-    auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps, int occ) {
+    // gran: stream tiles (of 32 rows) that a kernel consumes at a time; a split holds a multiple of it
+    auto split = [](int own_tiles, int str_tiles, int &nsplit, int &tps, int occ, int gran) {
         if (own_tiles == 0 || str_tiles == 0) { nsplit = 0; tps = 0; return; }
         int want = (TARGET_WGS * occ + own_tiles - 1) / own_tiles;
         if (want > str_tiles) want = str_tiles;
         if (want < 1) want = 1;
-        tps = (str_tiles + want - 1) / want;
+        tps = ((str_tiles + want - 1) / want + gran - 1) / gran * gran;
         nsplit = (str_tiles + tps - 1) / tps;
     };
-    split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_FWD));
-    split(g.own_tiles_n, g.str_tiles_b, g.nsplit_t, g.tps_t, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_GRADT));
-    split(g.own_tiles_s, g.str_tiles_b, g.nsplit_s, g.tps_s, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_SCORE));
+    const int gran = kge_sym_applies(g.bf16, g.rb, g.transh, g.dsplit_q) ? 2 : 1;
+    split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_FWD), gran);
+    split(g.own_tiles_n, g.str_tiles_b, g.nsplit_t, g.tps_t, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_GRADT), gran);
+    split(g.own_tiles_s, g.str_tiles_b, g.nsplit_s, g.tps_s, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_SCORE), 1);
     g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
     g.dsplit_t = (g.bf16 && g.rb == 1024) ? 2 : 1;
     if (g.l1) {
@@ -138,6 +140,8 @@ struct Buffers {
     float *W32, *A, *P;                // ... TransH: the unit normals unrounded, w^ . t and sign(x) . w^ per pair [Bp][Np]
     void *Qp2, *Tp2;                   // score-only calls on fp32 tables: two fp16 planes of the scaled Q (TransH: and of W) and T
     float *t_inv;                      // ... 1 / scale of the rows of T
+    int32_t *flag;                     // training calls: "redo the forward pass" flag of the block kernels
+    float *nbias;                      // ... 0 for each of the N negatives, -inf for the padding rows behind them
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -157,7 +161,7 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
         b.Qp2 = c.take<char>((g.transh ? 4 : 2) * rowsB * 2); b.Tp2 = c.take<char>(2 * rowsN * 2); b.t_inv = c.take<float>(g.Np);
     }
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
-    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr;
+    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr; b.flag = nullptr; b.nbias = nullptr;
     if (bwd) {
         b.Q2 = g.transh && !g.l1 ? c.take<char>(rowsB * es) : nullptr;
         if (!g.l1) {
@@ -177,6 +181,8 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
         b.acct = c.take<float>((size_t)g.nsplit_t * rowsN);
         b.sumt = c.take<float4>((size_t)g.nsplit_t * g.Np);
         b.regv = c.take<float>((size_t)2 * g.Bp + g.Np);
+        b.flag = c.take<int32_t>(1);
+        b.nbias = c.take<float>(g.Np);
     }
     return c.off + 256;
 }
@@ -399,7 +405,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     // (the kernels that need no transposed copy of the negatives get queries and negatives from ONE launch)
     const bool plain_gather = have_block && (g.l1 || kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q));
     if (plain_gather) rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos,
-                                                  neg, g.N, g.Np, b.T, b.tn, st);
+                                                  neg, g.N, g.Np, b.T, b.tn, st, nullptr, nullptr, nullptr, nullptr, b.flag, b.nbias);
     else rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos, nullptr, st);
     if (rc != KGE_OK) return rc;
     KgeBlockArgs a{};
@@ -421,6 +427,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_n; a.tiles_per_split = g.tps_q;
         a.kind = g.kind; a.loss = cfg->loss; a.gamma = cfg->gamma; a.adv_temp = cfg->adv_temp; a.c_corr = c_corr;
         a.stat_part = b.stat_part; a.acc_part = b.accq; a.acc_part2 = b.accq2; a.sum_part = b.sumq; a.own_pad = g.Bp;
+        a.flag = b.flag; a.str_bias = b.nbias;
         if ((rc = launch_block(g, KGE_MODE_FWD, cfg->loss, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
     }
     if ((rc = kge_run_rowfinish(b.stat_part, have_block ? (g.l1 ? 1 : g.nsplit_q) : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,

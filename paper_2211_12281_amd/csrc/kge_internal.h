@@ -34,7 +34,7 @@ struct KgeLdsLimit {
 };
 
 // Kernel choices that only tests and benchmarks override (kge_debug_select); 0 = the library's own choice.
-enum { KGE_KNOB_FWD_ONE_ROLE = 0, KGE_KNOB_GRADT_ONE_ROLE = 1, KGE_KNOB_SCORE_F32_MFMA = 2, KGE_KNOBS = 3 };
+enum { KGE_KNOB_FWD_ONE_ROLE = 0, KGE_KNOB_GRADT_ONE_ROLE = 1, KGE_KNOB_SCORE_F32_MFMA = 2, KGE_KNOB_TWO_ROLE = 3, KGE_KNOBS = 4 };
 int kge_knob(int knob);
 
 static inline int64_t kge_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
@@ -95,10 +95,15 @@ struct KgeBlockArgs {
     int32_t own_pad;
     int32_t own_tiles, nsplit;     // launch geometry (the grid is one-dimensional in (split, own tile))
     int32_t xcd_per;               // XCDs that share one split (1 when there are 8 or more splits)
+    const float *str_bias;         // FWD, kernel of block_sym.hip: [Np] 0 for a negative, -inf for a padding row (added to its scores)
+    int32_t *flag;                 // FWD, kernel of block_sym.hip: set to 1 when the pass has to be redone by the kernel below
+    const int32_t *gate;           // FWD, kernel of block_fwd_pp.hip: when given, the launch returns at once unless *gate != 0
 };
 
 bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit);
 bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit);
+// the kernel of block_sym.hip serves both passes of the same configurations; it walks the stream in tiles of 64 rows
+bool kge_sym_applies(bool bf16, int rb, bool transh, int dsplit);
 // launchers implemented in block_*.hip (one file per element type and pass to bound compile time)
 int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
                      int own_tiles, int nsplit, hipStream_t st);

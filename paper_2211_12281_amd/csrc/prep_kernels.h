@@ -24,7 +24,9 @@ int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out = nullptr,
-                           void *q_planes = nullptr, void *t_planes = nullptr, float *t_inv_scale = nullptr);
+                           void *q_planes = nullptr, void *t_planes = nullptr, float *t_inv_scale = nullptr,
+                           int32_t *flag = nullptr, float *bias = nullptr);   // flag: set to 0 by the launch (see KgeBlockArgs::flag);
+                                                                              // bias [Np]: 0 for the N negatives, -inf behind them
 // gather of the negatives and their transposed copy Tt [dp][Np] in one launch
 int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
                       hipStream_t st);

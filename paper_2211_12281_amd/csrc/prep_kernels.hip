@@ -48,7 +48,7 @@ struct KgeQbuildArgs {
     _Float16 *planes;                  // optional: the two fp16 pieces of the scaled q, [2][Bp][dp], with W two more for the
                                        // unit normal (scaled by KGE_PLANE_UNIT_SCALE); then rowinfo.K = 1 / scale of the row
 };
-struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; _Float16 *planes; float *inv_scale; };
+struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; _Float16 *planes; float *inv_scale; int32_t *flag; float *bias; };
 
 // fp32 rows as TWO fp16 planes for the matrix cores: the row is scaled by a power of two s that brings its largest
 // magnitude into [2^10, 2^11) (well inside the fp16 range, with the second piece of every element that matters still
@@ -261,6 +261,9 @@ __global__ void kge_qbuild_kernel(KgeQbuildArgs a) { kge_qbuild_body<BF16, SC>(b
 // independent, and a launch of their own each would cost the second one's start-up on the critical path
 template <bool BF16, int SC>
 __global__ void kge_qbuild_tgather_kernel(int q_blocks, KgeQbuildArgs a, KgeTgatherArgs g) {
+    if (blockIdx.x == 0 && threadIdx.x == 0 && g.flag) *g.flag = 0;     // the "redo the forward pass" flag of the block kernels
+    if (g.bias)                                                         // 0 for the negatives, -inf for the padding rows behind them
+        for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < g.Np; n += gridDim.x * blockDim.x) g.bias[n] = n < g.N ? 0.f : -INFINITY;
     if ((int)blockIdx.x < q_blocks) kge_qbuild_body<BF16, SC>(blockIdx.x, a);
     else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn, g.planes, g.inv_scale);
 }
@@ -719,12 +722,12 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out,
-                           void *q_planes, void *t_planes, float *t_inv_scale) {
+                           void *q_planes, void *t_planes, float *t_inv_scale, int32_t *flag, float *bias) {
     const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
     const int qb = (Bp + 3) / 4, tb = (Np + rows_wg - 1) / rows_wg;
     if (qb == 0 || tb == 0 || ((q_planes || t_planes) && m.bf16) || (t_planes && !t_inv_scale)) return KGE_E_INVALID_ARG;
     const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (_Float16 *)q_planes};
-    const KgeTgatherArgs g{neg, N, Np, T, tn, (_Float16 *)t_planes, t_inv_scale};
+    const KgeTgatherArgs g{neg, N, Np, T, tn, (_Float16 *)t_planes, t_inv_scale, flag, bias};
 #define KGE_QT(BF, SC) hipLaunchKernelGGL((kge_qbuild_tgather_kernel<BF, SC>), dim3(qb + tb), dim3(256), 0, st, qb, a, g)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QT) } else { KGE_SC_SWITCH(false, KGE_QT) }
 #undef KGE_QT
