@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--ensemble", type=int, default=0, metavar="MODELS",
                     help="c4: also time the power-rank ensemble of this many synthetic top-K lists per query (reported "
                          "beside the ranking numbers, outside the timed steps)")
+    ap.add_argument("--graph", action="store_true",
+                    help="training workloads: replay every step from a HIP graph (step number from a counter in device "
+                         "memory) instead of enqueueing it call by call; on ROCm 7.2 the replay is no faster")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy first (reference for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -119,8 +122,15 @@ class TrainWorkload:
             else:
                 r = ks.uniform_ids(g, 0, self.n_rel, self.B)
             self.host_batches.append((h, r, t, lo, hi))
-            self.batches.append(tuple(torch.from_numpy(x).to(dev) for x in (h, r, t)) + (lo, hi))
+            # the row ids of a step in gradient-row order, [h | t | negatives]: the negatives are drawn into the tail, so
+            # the sort for the sparse update reads the array as it stands (no concatenation)
+            ids = torch.empty(2 * self.B + self.N, dtype=torch.int32, device=dev)
+            ids[:self.B] = torch.from_numpy(h).to(dev)
+            ids[self.B:2 * self.B] = torch.from_numpy(t).to(dev)
+            self.batches.append((ids[:self.B], torch.from_numpy(r).to(dev), ids[self.B:2 * self.B], lo, hi, ids))
         self.neg = torch.empty(self.N, dtype=torch.int32, device=dev)
+        self.counter = torch.zeros(1, dtype=torch.int64, device=dev)      # the step number, on the device
+        self.graphs = None
         k = self.rel.shape[1]
         self.out = {
             "loss": torch.empty(1, dtype=torch.float32, device=dev),
@@ -138,9 +148,15 @@ class TrainWorkload:
         self.side = torch.cuda.Stream()
         self.main = torch.cuda.current_stream()
         self.ev_ids, self.ev_plan, self.ev_grad, self.ev_rel = (torch.cuda.Event() for _ in range(4))
-        self.ev_rel.record()
+        self.eager_now = False
+        self.prepared = -1
+        self.depth = 3                                   # sort buffers in flight: steps i, i + 1, i + 2
+        self.ev_plan2 = [torch.cuda.Event() for _ in range(self.depth)]
+        self.ev_done = [torch.cuda.Event() for _ in range(self.depth)]
+        for e in self.ev_done:
+            e.record()
+        self.ws_ent2, self.ws_rel2, self.ws_relw2 = ([kge.Workspace() for _ in range(self.depth)] for _ in range(3))
         self.ws_ent, self.ws_rel, self.ws_relw = kge.Workspace(), kge.Workspace(), kge.Workspace()
-        self.idx_all = torch.empty(2 * self.B + self.N, dtype=torch.int32, device=dev)
         self.enc = None
         if feat_dim > 0:
             # text features stand-ins: fixed U(-0.5, 0.5) rows; projections start at U(-0.05, 0.05)
@@ -189,7 +205,17 @@ class TrainWorkload:
             kge.sample_negatives_sharded(ks.BASE_SEED, i, ks.TAG_NEG, self.part, self.n_ent, self.D, self.N // self.D,
                                          out=self.neg)
         else:
-            h, r, t, lo, hi = self.batches[i % len(self.batches)]
+            if self.enc is None:
+                if self.graphs is None:
+                    self._step_call_by_call(i)
+                # (graphs: the step number of the negatives and of Adam is read from the device counter, which every step
+                # advances; argument i only selects the pre-drawn batch)
+                elif not self.eager_now:
+                    self.graphs[i % len(self.batches)].replay()
+                else:
+                    self._enqueue(i % len(self.batches), self.main, self.side)
+                return
+            h, r, t, lo, hi, _ = self.batches[i % len(self.batches)]
             kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=self.neg, stream=self.main)
         lr = self.P["lr"]
         if self.enc is not None:
@@ -203,39 +229,103 @@ class TrainWorkload:
             for q, gm in zip(self.mproj, (g_mh, g_mt)):
                 kge.sparse_adam(q["p"], q["sh"], q["m"], q["v"], self.rows_d, gm, lr, step=i + 1)
         else:
-            # The row ids of the step are known as soon as the negatives are drawn: the sorts that the sparse updates
-            # need run on a second stream beside the forward / backward kernels (kge_sparse_adam_plan), the updates
-            # themselves follow the gradients on the main stream (kge_sparse_adam_apply).
-            # (The library calls take their stream as an argument: no stream context is entered on the host.)
-            torch = self.torch
-            main, side = self.main, self.side
-            torch.cat((h, t, self.neg), out=self.idx_all)     # one small launch; the ids in gradient-row order
-            self.ev_ids.record(main)
-            side.wait_event(self.ev_ids)
-            kge.sparse_adam_plan(self.n_ent, self.d, self.idx_all, self.ws_ent, stream=side)
-            kge.sparse_adam_plan(self.n_rel, self.rel.shape[1], r, self.ws_rel, stream=side)
-            if self.relw is not None:
-                kge.sparse_adam_plan(self.n_rel, self.d, r, self.ws_relw, stream=side)
-            self.ev_plan.record(side)
-            main.wait_event(self.ev_rel)                  # the relation tables of the previous step are in place
-            kge.loss_bwd(self.model, self.P["loss"], h, r, t, self.neg, out=self.out, stream=main, **self.loss_kw)
-            self.ev_grad.record(main)
-            main.wait_event(self.ev_plan)
-            kge.sparse_adam_apply(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent, lr,
-                                  step=i + 1, stream=main)
-            side.wait_event(self.ev_grad)                 # the small relation tables are updated beside the entity table
-            kge.sparse_adam_apply(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel, lr,
-                                  step=i + 1, stream=side)
-            if self.relw is not None:
-                kge.sparse_adam_apply(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"],
-                                      self.ws_relw, lr, step=i + 1, stream=side)
-            self.ev_rel.record(side)
-            return
+            raise AssertionError("unreachable: the plain step is enqueued by _enqueue")
         kge.sparse_adam(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel_idx"], self.out["g_rel"], lr,
                         step=i + 1)
         if self.relw is not None:
             kge.sparse_adam(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_rel_idx"],
                             self.out["g_relw"], lr, step=i + 1)
+
+    def _prepare(self, i, side):
+        """What step i needs of its row ids alone, on the second stream: the shared negatives, drawn into the tail of the
+        step's id array [h | t | negatives], and the sorts of the sparse updates (kge_sparse_adam_plan)."""
+        kge, ks = self.kge, self.ks
+        h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
+        p = i % self.depth
+        side.wait_event(self.ev_done[p])                 # the update of step i - depth has read these sort buffers
+        kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=ids[2 * self.B:], stream=side)
+        kge.sparse_adam_plan(self.n_ent, self.d, ids, self.ws_ent2[p], stream=side)
+        kge.sparse_adam_plan(self.n_rel, self.rel.shape[1], r, self.ws_rel2[p], stream=side)
+        if self.relw is not None:
+            kge.sparse_adam_plan(self.n_rel, self.d, r, self.ws_relw2[p], stream=side)
+        self.ev_plan2[p].record(side)
+        self.prepared = i
+
+    def _step_call_by_call(self, i):
+        """One step, software-pipelined over two streams: everything that depends on the row ids alone (negatives, sorts)
+        is enqueued two steps ahead on the second stream (its small kernels find free compute units only between and at
+        the ends of the full-chip kernels, so one step ahead they still arrive late), so that the main stream holds only
+        the chain gather -> forward -> backward -> update, and the only event it waits for was recorded long before."""
+        kge = self.kge
+        main, side = self.main, self.side
+        if not i <= self.prepared < i + self.depth:      # first step, or a jump in the step numbers
+            self.prepared = i - 1
+        while self.prepared < i:
+            self._prepare(self.prepared + 1, side)
+        h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
+        p, lr = i % self.depth, self.P["lr"]
+        main.wait_event(self.ev_plan2[p])
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main, **self.loss_kw)
+        kge.sparse_adam_apply(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent2[p], lr,
+                              step=i + 1, stream=main)
+        kge.sparse_adam_apply(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel2[p], lr,
+                              step=i + 1, stream=main)
+        if self.relw is not None:
+            kge.sparse_adam_apply(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"],
+                                  self.ws_relw2[p], lr, step=i + 1, stream=main)
+        self.ev_done[p].record(main)
+        while self.prepared < i + self.depth - 1:
+            self._prepare(self.prepared + 1, side)
+
+    def _enqueue(self, k, main, side):
+        """One step on pre-drawn batch k, in a form that a HIP graph can record.  The row ids of the step are known as soon as the negatives are drawn: the sorts
+        that the sparse updates need run on a second stream beside the forward / backward kernels (kge_sparse_adam_plan),
+        the updates themselves follow the gradients (kge_sparse_adam_apply), the entity table on the main stream, the small
+        relation tables beside it; the second stream joins the main one before the step counter advances.  The library
+        calls take their stream as an argument (no stream context is entered on the host) and only launch kernels, so the
+        same function serves the call-by-call step and the capture of the graph."""
+        kge, ks = self.kge, self.ks
+        h, r, t, lo, hi, ids = self.batches[k]
+        lr, c = self.P["lr"], self.counter
+        neg = ids[2 * self.B:]
+        kge.sample_negatives_dev(ks.BASE_SEED, c, 0, ks.TAG_NEG, lo, hi, self.N, out=neg, stream=main)
+        self.ev_ids.record(main)
+        side.wait_event(self.ev_ids)
+        kge.sparse_adam_plan(self.n_ent, self.d, ids, self.ws_ent, stream=side)
+        kge.sparse_adam_plan(self.n_rel, self.rel.shape[1], r, self.ws_rel, stream=side)
+        if self.relw is not None:
+            kge.sparse_adam_plan(self.n_rel, self.d, r, self.ws_relw, stream=side)
+        self.ev_plan.record(side)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, neg, out=self.out, stream=main, **self.loss_kw)
+        self.ev_grad.record(main)
+        main.wait_event(self.ev_plan)
+        kge.sparse_adam_apply(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent, lr,
+                              step=1, stream=main, step_counter=c)
+        side.wait_event(self.ev_grad)
+        kge.sparse_adam_apply(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel, lr,
+                              step=1, stream=side, step_counter=c)
+        if self.relw is not None:
+            kge.sparse_adam_apply(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"],
+                                  self.ws_relw, lr, step=1, stream=side, step_counter=c)
+        self.ev_rel.record(side)
+        main.wait_event(self.ev_rel)
+        kge.step_counter_add(c, 1, stream=main)
+
+    def capture(self):
+        """Records the step of every pre-drawn batch into a HIP graph of its own (kernel nodes on two streams; the graphs
+        differ in the id arrays they read).  One call-by-call step first sizes the workspaces."""
+        torch = self.torch
+        if self.enc is not None or self.sampler is not None:
+            return
+        self._enqueue(0, self.main, self.side)
+        torch.cuda.synchronize()
+        self.graphs = []
+        for k in range(len(self.batches)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self._enqueue(k, torch.cuda.current_stream(), self.side)
+            self.graphs.append(g)
+        torch.cuda.synchronize()
 
     def pairs_per_step(self):
         return self.B * (self.N + 1)
@@ -466,6 +556,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    graphed = isinstance(wl, TrainWorkload) and a.graph
+    if graphed:
+        wl.capture()
+        graphed = wl.graphs is not None
     for i in range(a.warmup):
         wl.step(i)
     torch.cuda.synchronize()
@@ -477,12 +571,14 @@ def main():
                   ["block_score"] if isinstance(wl, ScoreWorkload) else ["topk_scan"]
     other_slots = [s_ for s_ in kge.binding.PROF_SLOTS if s_ not in timed_slots]
     # In a training step the bracket is set on every FOURTH step of the timed region (the average below is over
-    # those launches): the value then carries a quarter of the cost of its own instrumentation.
+    # those launches): the value then carries a quarter of the cost of its own instrumentation.  When the steps are
+    # replayed from HIP graphs, those bracketed steps are the ones enqueued call by call (a graph holds no events).
     every = 4 if isinstance(wl, TrainWorkload) else 1
     t0 = time.perf_counter()
     for i in range(a.warmup, a.warmup + a.steps):
         if every > 1:
             kge.profile_enable(timed_slots if (i - a.warmup) % every == 0 else False)
+            wl.eager_now = (i - a.warmup) % every == 0
         elif i == a.warmup:
             kge.profile_enable(timed_slots)
         wl.step(i)
@@ -503,6 +599,7 @@ def main():
     if isinstance(wl, TrainWorkload):
         extra_steps = min(a.steps, 20)
         kge.profile_enable(other_slots)
+        wl.eager_now = True
         for i in range(a.warmup + a.steps, a.warmup + a.steps + extra_steps):
             wl.step(i)
         torch.cuda.synchronize()
@@ -614,6 +711,9 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, "kernels": prof, "calibration": calib,
     }
     line["host_enqueue_ms_per_step"] = dt_host * 1e3 / a.steps
+    if isinstance(wl, TrainWorkload):
+        line["enqueue"] = ("HIP graph replay, one graph per pre-drawn batch; every 4th step call by call with the HIP-event bracket"
+                           if graphed else "call by call, two streams, id-only work one step ahead")
     line.update(wl.extra(ms))
     if enc_roof:
         line["encoder_roofline"] = enc_roof

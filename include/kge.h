@@ -15,7 +15,10 @@
  *    from the caller's workspace `ws` (size from kge_workspace_bytes(); 256-byte aligned).
  *  - Work is enqueued on `hip_stream` (a hipStream_t, may be NULL for the default stream) and the
  *    call returns without waiting for it.  Calls that share a workspace must be ordered on one
- *    stream.
+ *    stream.  The training calls (kge_sample_negatives*, kge_loss_bwd, kge_sparse_adam*) only launch
+ *    kernels: no allocation, no synchronisation, no memset or copy node, so a stream that is being
+ *    captured into a HIP graph may be passed; what changes from one replay to the next then comes
+ *    from a counter in device memory (kge_step_counter_add below).
  *  - Return value: KGE_OK (0) or a negative KGE_E_* code.  Arguments are validated on the host
  *    before anything is launched; on error nothing has been enqueued.
  *  - Index VALUES are not range-checked on the device: ids outside [0, n_ent) / [0, n_rel) are
@@ -90,6 +93,9 @@ typedef struct {
 typedef struct {
     float lr, beta1, beta2, eps;
     int64_t step;          /* global 1-based step used in the bias corrections */
+    const uint64_t *step_counter;   /* NULL, or a DEVICE counter (kge_step_counter_add): the kernels then use
+                                       step + *step_counter, read when they run, so that a captured update
+                                       can be replayed step after step */
 } kge_adam_cfg_t;
 
 /*
@@ -103,6 +109,19 @@ typedef struct {
  */
 int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int64_t lo, int64_t hi,
                          int64_t n, int32_t *out_idx, void *hip_stream);
+
+/*
+ * Steps replayed from a HIP graph.  A graph fixes every kernel argument when it is captured; of the training step
+ * (Section 4, "Training": sample, gather, score, update) two numbers change from one step to the next - the step word of
+ * the negatives' Philox counter and the step of Adam's bias corrections.  Both can be read from a uint64 in DEVICE
+ * memory instead: kge_sample_negatives_dev uses step_offset + *step_counter (same ids as kge_sample_negatives with that
+ * step; the caller keeps the sum below 2^32), kge_adam_cfg_t.step_counter does the same for the updates, and
+ * kge_step_counter_add enqueues *step_counter += inc (one thread; typically the last node of the captured step).
+ * The counter is the caller's memory; the caller sets its first value (e.g. with a copy before the first replay).
+ */
+int kge_step_counter_add(uint64_t *step_counter, uint64_t inc, void *hip_stream);
+int kge_sample_negatives_dev(uint64_t seed, const uint64_t *step_counter, uint64_t step_offset, uint32_t stream_tag,
+                             int64_t lo, int64_t hi, int64_t n, int32_t *out_idx, void *hip_stream);
 
 /*
  * Scores of a micro-batch (Table 2; negative sharing per eq. (negsamples)):

@@ -21,7 +21,7 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble", "kge_sparse_adam_plan",
            "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit", "kge_debug_select",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
-           "kge_calibrate_mfma", "kge_calibrate_copy"]
+           "kge_calibrate_mfma", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7}
 
@@ -47,7 +47,7 @@ class KgeLossCfgT(C.Structure):
 
 class KgeAdamCfgT(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("step", C.c_int64)]
+                ("step", C.c_int64), ("step_counter", C.c_void_p)]
 
 
 class KgeError(RuntimeError):
@@ -82,6 +82,9 @@ def load():
         lib.kge_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.kge_status_string.restype = C.c_char_p
         lib.kge_status_string.argtypes = [C.c_int]
+        lib.kge_step_counter_add.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
+        lib.kge_sample_negatives_dev.argtypes = [C.c_uint64, C.c_void_p, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
+                                                 C.c_void_p, C.c_void_p]
         lib.kge_sample_negatives.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
                                              C.c_void_p, C.c_void_p]
         lib.kge_score.argtypes = [C.c_void_p] + [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_int64] + \
@@ -186,6 +189,28 @@ def workspace_bytes(op: int, model: Model | None, B: int, N: int, K: int = 0) ->
     return int(load().kge_workspace_bytes(op, model.ref if model is not None else None, B, N, K))
 
 
+def _counter(t):
+    """Device pointer of a step counter: one int64 (read as uint64) on the GPU, or None."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.dtype == torch.int64 and t.numel() == 1
+    return t.data_ptr()
+
+
+def step_counter_add(counter, inc: int = 1, stream=None):
+    """kge_step_counter_add: enqueues counter += inc (for steps replayed from a HIP graph)."""
+    _check(load().kge_step_counter_add(_counter(counter), inc, _stream(stream)), "kge_step_counter_add")
+
+
+def sample_negatives_dev(seed: int, counter, step_offset: int, tag: int, lo: int, hi: int, n: int, out=None, stream=None):
+    """kge_sample_negatives_dev: the ids of step step_offset + counter[0], the counter being read on the device."""
+    if out is None:
+        out = torch.empty(n, dtype=torch.int32, device="cuda")
+    _check(load().kge_sample_negatives_dev(seed, _counter(counter), step_offset, tag, lo, hi, n, _ptr(out), _stream(stream)),
+           "kge_sample_negatives_dev")
+    return out
+
+
 def sample_negatives(seed: int, step: int, tag: int, lo: int, hi: int, n: int, out=None, stream=None):
     if out is None:
         out = torch.empty(n, dtype=torch.int32, device="cuda")
@@ -230,14 +255,14 @@ def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp
 
 
 def sparse_adam(param, shadow, m, v, idx, grads, lr: float, beta1: float = 0.9, beta2: float = 0.999,
-                eps: float = 1e-8, step: int = 1, ws: Workspace | None = None):
+                eps: float = 1e-8, step: int = 1, ws: Workspace | None = None, step_counter=None):
     assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
     assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
     assert m.stride() == param.stride() and v.stride() == param.stride()
     if shadow is not None:
         assert shadow.dtype == torch.bfloat16 and shadow.stride() == param.stride()
     M, d = idx.numel(), param.shape[1]
-    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step)
+    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step, _counter(step_counter))
     ws = ws or _default_ws
     buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, d))
     _check(load().kge_sparse_adam(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
@@ -250,14 +275,14 @@ def sparse_adam_static_limit() -> int:
 
 
 def sparse_adam_static(param, shadow, m, v, idx, grads, lr: float, beta1: float = 0.9, beta2: float = 0.999,
-                       eps: float = 1e-8, step: int = 1, stream=None):
+                       eps: float = 1e-8, step: int = 1, stream=None, step_counter=None):
     """kge_sparse_adam_static: the update with the library's built-in scratch buffer (no workspace, no allocation)."""
     assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
     assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
     assert m.stride() == param.stride() and v.stride() == param.stride()
     if shadow is not None:
         assert shadow.dtype == torch.bfloat16 and shadow.stride() == param.stride()
-    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step)
+    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step, _counter(step_counter))
     _check(load().kge_sparse_adam_static(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], param.shape[1],
                                          param.stride(0), _ptr(_i32(idx)), _ptr(grads), idx.numel(), C.byref(cfg),
                                          _stream(stream)), "kge_sparse_adam_static")
@@ -272,14 +297,14 @@ def sparse_adam_plan(n_rows: int, dim: int, idx, ws: Workspace, stream=None):
 
 
 def sparse_adam_apply(param, shadow, m, v, grads, ws: Workspace, lr: float, beta1: float = 0.9, beta2: float = 0.999,
-                      eps: float = 1e-8, step: int = 1, stream=None):
+                      eps: float = 1e-8, step: int = 1, stream=None, step_counter=None):
     assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
     assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
     assert m.stride() == param.stride() and v.stride() == param.stride()
     if shadow is not None:
         assert shadow.dtype == torch.bfloat16 and shadow.stride() == param.stride()
     M, d = grads.shape[0], param.shape[1]
-    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step)
+    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step, _counter(step_counter))
     buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, d))
     _check(load().kge_sparse_adam_apply(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
                                         _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream(stream)),

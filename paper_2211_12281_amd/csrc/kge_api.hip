@@ -256,7 +256,20 @@ int kge_sample_negatives(uint64_t seed, uint64_t step, uint32_t stream_tag, int6
     if (n < 0 || hi <= lo || lo < 0 || hi > (1ll << 31) || step >= (1ull << 32)) return KGE_E_INVALID_ARG;
     if (n == 0) return KGE_OK;
     if (!out_idx) return KGE_E_INVALID_ARG;
-    return kge_run_negatives(seed, step, stream_tag, lo, hi, n, out_idx, (hipStream_t)hip_stream);
+    return kge_run_negatives(seed, step, nullptr, stream_tag, lo, hi, n, out_idx, (hipStream_t)hip_stream);
+}
+
+int kge_sample_negatives_dev(uint64_t seed, const uint64_t *step_counter, uint64_t step_offset, uint32_t stream_tag, int64_t lo,
+                             int64_t hi, int64_t n, int32_t *out_idx, void *hip_stream) {
+    if (!step_counter || n < 0 || hi <= lo || lo < 0 || hi > (1ll << 31) || step_offset >= (1ull << 32)) return KGE_E_INVALID_ARG;
+    if (n == 0) return KGE_OK;
+    if (!out_idx) return KGE_E_INVALID_ARG;
+    return kge_run_negatives(seed, step_offset, step_counter, stream_tag, lo, hi, n, out_idx, (hipStream_t)hip_stream);
+}
+
+int kge_step_counter_add(uint64_t *step_counter, uint64_t inc, void *hip_stream) {
+    if (!step_counter) return KGE_E_INVALID_ARG;
+    return kge_run_step_counter_add(step_counter, inc, (hipStream_t)hip_stream);
 }
 
 size_t kge_encode_workspace_bytes(int op, const kge_encoder_t *enc, int64_t B, int64_t N) {

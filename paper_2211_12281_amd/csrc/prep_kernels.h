@@ -10,8 +10,9 @@ struct KgeModelDev {
     int64_t ent_ld, rel_ld, relw_ld;
 };
 
-int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, int64_t hi, int64_t n,
-                      int32_t *out, hipStream_t st);
+int kge_run_negatives(uint64_t seed, uint64_t step, const uint64_t *step_counter, uint32_t tag, int64_t lo, int64_t hi,
+                      int64_t n, int32_t *out, hipStream_t st);
+int kge_run_step_counter_add(uint64_t *counter, uint64_t inc, hipStream_t st);
 int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                    int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                    float *pos_out, hipStream_t st, void *planes = nullptr);

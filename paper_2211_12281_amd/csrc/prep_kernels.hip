@@ -13,11 +13,19 @@ __device__ __forceinline__ void kge_philox_round(uint32_t (&c)[4], uint32_t k0, 
     c[0] = n0; c[1] = lo1; c[2] = n2; c[3] = lo0;
 }
 
-__global__ void kge_negatives_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t step, uint32_t tag,
-                                     int64_t lo, uint64_t range, int64_t n, int32_t *out) {
+__global__ void kge_step_counter_add_kernel(uint64_t *counter, uint64_t inc) { *counter += inc; }
+
+int kge_run_step_counter_add(uint64_t *counter, uint64_t inc, hipStream_t st) {
+    hipLaunchKernelGGL(kge_step_counter_add_kernel, dim3(1), dim3(1), 0, st, counter, inc);
+    return kge_launch_status();
+}
+
+__global__ void kge_negatives_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t step, const uint64_t *step_counter,
+                                     uint32_t tag, int64_t lo, uint64_t range, int64_t n, int32_t *out) {
     // one thread per Philox block = two ids
     const int64_t blk = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (2 * blk >= n) return;
+    if (step_counter) step += (uint32_t)*step_counter;
     uint32_t c[4] = { (uint32_t)blk, (uint32_t)((uint64_t)blk >> 32), step, tag };
     uint32_t k0 = seed_lo, k1 = seed_hi;
 #pragma unroll
@@ -30,12 +38,12 @@ __global__ void kge_negatives_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_
     if (2 * blk + 1 < n) out[2 * blk + 1] = (int32_t)(lo + (int64_t)__umul64hi(x1, range));
 }
 
-int kge_run_negatives(uint64_t seed, uint64_t step, uint32_t tag, int64_t lo, int64_t hi, int64_t n,
-                      int32_t *out, hipStream_t st) {
+int kge_run_negatives(uint64_t seed, uint64_t step, const uint64_t *step_counter, uint32_t tag, int64_t lo, int64_t hi,
+                      int64_t n, int32_t *out, hipStream_t st) {
     const int64_t blocks = (n + 1) / 2;
     const int grid = (int)((blocks + 255) / 256);
     hipLaunchKernelGGL(kge_negatives_kernel, dim3(grid), dim3(256), 0, st, (uint32_t)seed,
-                       (uint32_t)(seed >> 32), (uint32_t)step, tag, lo, (uint64_t)(hi - lo), n, out);
+                       (uint32_t)(seed >> 32), (uint32_t)step, step_counter, tag, lo, (uint64_t)(hi - lo), n, out);
     return kge_launch_status();
 }
 

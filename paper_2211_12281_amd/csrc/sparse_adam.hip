@@ -149,7 +149,27 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
-struct AdamConst { float lr, b1, b2, eps, omb1, omb2, inv_bc1, inv_bc2; };
+struct AdamConst { float lr, b1, b2, eps, omb1, omb2, inv_bc1, inv_bc2; const uint64_t *step_counter; uint64_t step; };
+
+// 1 / (1 - beta^step) by binary powering in fp64: products only, so the host (plain calls) and the device (steps read
+// from a counter in device memory) arrive at the same bits.
+__host__ __device__ inline float adam_inv_bias(float beta, uint64_t step) {
+    double p = 1.0, b = (double)beta;
+    for (; step; step >>= 1) {
+        if (step & 1) p *= b;
+        b *= b;
+    }
+    return (float)(1.0 / (1.0 - p));
+}
+
+// With a device counter the corrections belong to step + *counter and are formed by the wave that is about to update.
+__device__ __forceinline__ void adam_resolve(AdamConst &c) {
+    if (c.step_counter) {
+        const uint64_t s = c.step + *c.step_counter;
+        c.inv_bc1 = adam_inv_bias(c.b1, s);
+        c.inv_bc2 = adam_inv_bias(c.b2, s);
+    }
+}
 
 constexpr int SEG_CHUNK = 32;     // sorted positions per chunk of the two-level reduction
 
@@ -201,7 +221,7 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
 // A: one wave per sorted position.
 __device__ __forceinline__ void adam_interior_body(int64_t blk, const uint32_t *sk, const uint32_t *sp, int64_t M, const float *grads,
                                                    int dim, int64_t ld, float *param, uint16_t *shadow, float *mom, float *var,
-                                                   const AdamConst &c) {
+                                                   AdamConst c) {
     const int lane = threadIdx.x & 63;
     const int64_t i = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (i >= M) return;
@@ -215,6 +235,7 @@ __device__ __forceinline__ void adam_interior_body(int64_t blk, const uint32_t *
     const int run = __builtin_ctzll(~mask);                // leading ones from lane 0
     const int64_t e = i + run;
     if (e == chunk_end && chunk_end < M && sk[chunk_end] == key) return;   // crosses the boundary: kernels B
+    adam_resolve(c);
     for (int col = lane * 4; col < dim; col += 256)
         adam_apply(key, col, reduce_rows(sp, i, e, grads, dim, col), ld, param, shadow, mom, var, c);
 }
@@ -284,6 +305,7 @@ __global__ void adam_boundary_kernel(const uint32_t *sk, int64_t M, int dim, int
         jend += run;
         if (run < 64) break;
     }
+    adam_resolve(c);
     for (int col = lane * 4; col < dim; col += 256) {
         float4 g = *(const float4 *)(part + (2 * k + 1) * (int64_t)dim + col);
         int64_t j = k + 1;
@@ -385,8 +407,9 @@ int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, in
     AdamConst c;
     c.lr = cfg.lr; c.b1 = cfg.beta1; c.b2 = cfg.beta2; c.eps = cfg.eps;
     c.omb1 = 1.f - cfg.beta1; c.omb2 = 1.f - cfg.beta2;
-    c.inv_bc1 = (float)(1.0 / (1.0 - pow((double)cfg.beta1, (double)cfg.step)));
-    c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)cfg.beta2, (double)cfg.step)));
+    c.inv_bc1 = adam_inv_bias(cfg.beta1, (uint64_t)cfg.step);
+    c.inv_bc2 = adam_inv_bias(cfg.beta2, (uint64_t)cfg.step);
+    c.step_counter = cfg.step_counter; c.step = (uint64_t)cfg.step;
     SortWs s;
     sort_carve(M, dim, ws, s);                              // the piece buffer lies behind the sort buffers
     KgeProfScope prof(KGE_PROF_ADAM, st);
