@@ -150,12 +150,11 @@ class TrainWorkload:
         self.ev_ids, self.ev_plan, self.ev_grad, self.ev_rel = (torch.cuda.Event() for _ in range(4))
         self.eager_now = False
         self.prepared = -1
-        self.depth = 3                                   # sort buffers in flight: steps i, i + 1, i + 2
-        self.ev_plan2 = [torch.cuda.Event() for _ in range(self.depth)]
-        self.ev_done = [torch.cuda.Event() for _ in range(self.depth)]
-        for e in self.ev_done:
-            e.record()
-        self.ws_ent2, self.ws_rel2, self.ws_relw2 = ([kge.Workspace() for _ in range(self.depth)] for _ in range(3))
+        self.ev_plan2 = [torch.cuda.Event() for _ in range(2)]
+        self.ev_neg = [torch.cuda.Event() for _ in range(2)]
+        self.ev_bwd, self.ev_done = torch.cuda.Event(), torch.cuda.Event()
+        self.ev_done.record()
+        self.ws_ent2, self.ws_rel2, self.ws_relw2 = ([kge.Workspace() for _ in range(2)] for _ in range(3))
         self.ws_ent, self.ws_rel, self.ws_relw = kge.Workspace(), kge.Workspace(), kge.Workspace()
         self.enc = None
         if feat_dim > 0:
@@ -241,9 +240,9 @@ class TrainWorkload:
         step's id array [h | t | negatives], and the sorts of the sparse updates (kge_sparse_adam_plan)."""
         kge, ks = self.kge, self.ks
         h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
-        p = i % self.depth
-        side.wait_event(self.ev_done[p])                 # the update of step i - depth has read these sort buffers
+        p = i % 2
         kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=ids[2 * self.B:], stream=side)
+        self.ev_neg[p].record(side)
         kge.sparse_adam_plan(self.n_ent, self.d, ids, self.ws_ent2[p], stream=side)
         kge.sparse_adam_plan(self.n_rel, self.rel.shape[1], r, self.ws_rel2[p], stream=side)
         if self.relw is not None:
@@ -252,30 +251,30 @@ class TrainWorkload:
         self.prepared = i
 
     def _step_call_by_call(self, i):
-        """One step, software-pipelined over two streams: everything that depends on the row ids alone (negatives, sorts)
-        is enqueued two steps ahead on the second stream (its small kernels find free compute units only between and at
-        the ends of the full-chip kernels, so one step ahead they still arrive late), so that the main stream holds only
-        the chain gather -> forward -> backward -> update, and the only event it waits for was recorded long before."""
+        """One step, software-pipelined over two streams.  The main stream holds the chain gather -> forward -> backward ->
+        update.  Everything that depends on the row ids alone (negatives, sorts) belongs to the NEXT step and runs on the
+        second stream while this step's update runs: the update is bound by memory traffic and leaves room for a few small
+        workgroups, whereas the forward and backward kernels need every compute unit at once and are held up by any
+        workgroup that sits on one.  The events the main stream waits for were recorded most of a step earlier."""
         kge = self.kge
         main, side = self.main, self.side
-        if not i <= self.prepared < i + self.depth:      # first step, or a jump in the step numbers
-            self.prepared = i - 1
-        while self.prepared < i:
-            self._prepare(self.prepared + 1, side)
+        if self.prepared != i:                           # first step, or a jump in the step numbers
+            side.wait_event(self.ev_done)
+            self._prepare(i, side)
         h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
-        p, lr = i % self.depth, self.P["lr"]
-        main.wait_event(self.ev_plan2[p])
+        p, lr = i % 2, self.P["lr"]
+        main.wait_event(self.ev_neg[p])
         kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main, **self.loss_kw)
-        kge.sparse_adam_apply(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent2[p], lr,
-                              step=i + 1, stream=main)
-        kge.sparse_adam_apply(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel2[p], lr,
-                              step=i + 1, stream=main)
+        self.ev_bwd.record(main)
+        main.wait_event(self.ev_plan2[p])
+        tables = [(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent2[p]),
+                  (self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel2[p])]
         if self.relw is not None:
-            kge.sparse_adam_apply(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"],
-                                  self.ws_relw2[p], lr, step=i + 1, stream=main)
-        self.ev_done[p].record(main)
-        while self.prepared < i + self.depth - 1:
-            self._prepare(self.prepared + 1, side)
+            tables.append((self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"], self.ws_relw2[p]))
+        kge.sparse_adam_apply_tables(tables, lr, step=i + 1, stream=main)     # every table of the step in two launches
+        self.ev_done.record(main)
+        side.wait_event(self.ev_bwd)                     # (the sort buffers of step i + 1 were last read by step i - 1)
+        self._prepare(i + 1, side)
 
     def _enqueue(self, k, main, side):
         """One step on pre-drawn batch k, in a form that a HIP graph can record.  The row ids of the step are known as soon as the negatives are drawn: the sorts
@@ -713,7 +712,7 @@ def main():
     line["host_enqueue_ms_per_step"] = dt_host * 1e3 / a.steps
     if isinstance(wl, TrainWorkload):
         line["enqueue"] = ("HIP graph replay, one graph per pre-drawn batch; every 4th step call by call with the HIP-event bracket"
-                           if graphed else "call by call, two streams, id-only work one step ahead")
+                           if graphed else "call by call; the next step's negatives and sorts on a second stream beside the update")
     line.update(wl.extra(ms))
     if enc_roof:
         line["encoder_roofline"] = enc_roof

@@ -196,6 +196,22 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
                           size_t ws_bytes, void *hip_stream);
 
 /*
+ * kge_sparse_adam_apply for several tables at once: a training step updates the entity table and one or two small
+ * relation tables (Section 3.1: relation embeddings, TransH's normals), and a small table alone costs two launches for
+ * a few microseconds of work.  Each table has been planned with kge_sparse_adam_plan into its own workspace; the
+ * result equals one kge_sparse_adam_apply per table, bit for bit, in two launches for all of them.  1 <= n_tables <= 4;
+ * the tables must not overlap; tables with M = 0 are skipped.
+ */
+typedef struct {
+    float *param_f32; void *param_bf16; float *m, *v;      /* as in kge_sparse_adam */
+    int64_t n_rows; int32_t dim; int64_t ld;
+    const float *grads; int64_t M;
+    void *ws; size_t ws_bytes;                             /* the workspace that kge_sparse_adam_plan filled */
+} kge_adam_table_t;
+int kge_sparse_adam_apply_tables(const kge_adam_table_t *tables, int32_t n_tables, const kge_adam_cfg_t *cfg,
+                                 void *hip_stream);
+
+/*
  * kge_sparse_adam for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the workspace), same kernels
  * and the same bits as kge_sparse_adam; the sort buffers and piece sums live in a buffer built into the library

@@ -21,7 +21,8 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble", "kge_sparse_adam_plan",
            "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit", "kge_debug_select",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
-           "kge_calibrate_mfma", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev"]
+           "kge_calibrate_mfma", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev",
+           "kge_sparse_adam_apply_tables"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7}
 
@@ -48,6 +49,12 @@ class KgeLossCfgT(C.Structure):
 class KgeAdamCfgT(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("step", C.c_int64), ("step_counter", C.c_void_p)]
+
+
+class KgeAdamTableT(C.Structure):
+    _fields_ = [("param_f32", C.c_void_p), ("param_bf16", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("n_rows", C.c_int64), ("dim", C.c_int32), ("ld", C.c_int64), ("grads", C.c_void_p), ("M", C.c_int64),
+                ("ws", C.c_void_p), ("ws_bytes", C.c_size_t)]
 
 
 class KgeError(RuntimeError):
@@ -82,6 +89,7 @@ def load():
         lib.kge_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.kge_status_string.restype = C.c_char_p
         lib.kge_status_string.argtypes = [C.c_int]
+        lib.kge_sparse_adam_apply_tables.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         lib.kge_step_counter_add.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
         lib.kge_sample_negatives_dev.argtypes = [C.c_uint64, C.c_void_p, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
                                                  C.c_void_p, C.c_void_p]
@@ -309,6 +317,24 @@ def sparse_adam_apply(param, shadow, m, v, grads, ws: Workspace, lr: float, beta
     _check(load().kge_sparse_adam_apply(_ptr(param), _ptr(shadow), _ptr(m), _ptr(v), param.shape[0], d, param.stride(0),
                                         _ptr(grads), M, C.byref(cfg), _ptr(buf), buf.numel(), _stream(stream)),
            "kge_sparse_adam_apply")
+
+
+def sparse_adam_apply_tables(tables, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, step: int = 1,
+                             stream=None, step_counter=None):
+    """kge_sparse_adam_apply_tables: tables = [(param, shadow, m, v, grads, ws), ...], each planned into its own ws."""
+    arr = (KgeAdamTableT * len(tables))()
+    for a, (param, shadow, m, v, grads, ws) in zip(arr, tables):
+        assert param.dtype == torch.float32 and m.dtype == torch.float32 and v.dtype == torch.float32
+        assert grads.dtype == torch.float32 and grads.is_contiguous() and param.stride(1) == 1
+        assert m.stride() == param.stride() and v.stride() == param.stride()
+        if shadow is not None:
+            assert shadow.dtype == torch.bfloat16 and shadow.stride() == param.stride()
+        M, d = grads.shape[0], param.shape[1]
+        buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, d))
+        a.param_f32, a.param_bf16, a.m, a.v = _ptr(param), _ptr(shadow), _ptr(m), _ptr(v)
+        a.n_rows, a.dim, a.ld, a.grads, a.M, a.ws, a.ws_bytes = param.shape[0], d, param.stride(0), _ptr(grads), M, _ptr(buf), buf.numel()
+    cfg = KgeAdamCfgT(lr, beta1, beta2, eps, step, _counter(step_counter))
+    _check(load().kge_sparse_adam_apply_tables(arr, len(tables), C.byref(cfg), _stream(stream)), "kge_sparse_adam_apply_tables")
 
 
 def topk(model: Model, h, r, cand_lo: int, cand_hi: int, K: int, true_t=None, ws: Workspace | None = None):

@@ -11,6 +11,7 @@ size_t kge_static_scratch_bytes();
 int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void *ws, hipStream_t st);
 int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
                               const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st);
+int kge_run_sparse_adam_apply_tables(const kge_adam_table_t *tb, int n, const kge_adam_cfg_t &cfg, hipStream_t st);
 int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, int64_t Q, int64_t lo, int64_t hi,
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
@@ -557,6 +558,32 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
     if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     return kge_run_sparse_adam_apply(param_f32, param_bf16, m, v, n_rows, dim, ld, grads, M, *cfg, ws,
                                      (hipStream_t)hip_stream);
+}
+
+int kge_sparse_adam_apply_tables(const kge_adam_table_t *tables, int32_t n_tables, const kge_adam_cfg_t *cfg, void *hip_stream) {
+    if (!tables || !cfg || n_tables < 1 || n_tables > 4) return KGE_E_INVALID_ARG;
+    if (cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f))
+        return KGE_E_INVALID_ARG;
+    kge_adam_table_t live[4];
+    int n = 0;
+    for (int k = 0; k < n_tables; ++k) {
+        const kge_adam_table_t &t = tables[k];
+        if (t.M < 0 || t.n_rows <= 0 || t.n_rows >= (1ll << 31) || t.dim <= 0 || t.dim % 4 != 0 || t.dim > 4096 || t.ld < t.dim ||
+            t.ld % 4 != 0 || t.M >= (1ll << 31))
+            return KGE_E_INVALID_ARG;
+        if (t.M == 0) continue;
+        if (!t.param_f32 || !t.m || !t.v || !t.grads) return KGE_E_INVALID_ARG;
+        if (!adam_rows_aligned(t.param_f32, t.param_bf16, t.m, t.v, t.grads)) return KGE_E_INVALID_ARG;
+        if (!t.ws) return KGE_E_WORKSPACE_TOO_SMALL;
+        size_t bytes = t.ws_bytes;
+        void *ws = t.ws;
+        ws = align_ws(ws, bytes);
+        if (kge_sparse_adam_ws(t.M, t.dim) - 256 > bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+        live[n] = t; live[n].ws = ws; live[n].ws_bytes = bytes;
+        ++n;
+    }
+    if (n == 0) return KGE_OK;
+    return kge_run_sparse_adam_apply_tables(live, n, *cfg, (hipStream_t)hip_stream);
 }
 
 int kge_topk(const kge_model_t *model, const int32_t *h, const int32_t *r, int64_t Q, int64_t cand_lo,

@@ -210,6 +210,187 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
     if (shadow) *(uint2 *)(shadow + o) = make_uint2(pack_bf16x2(tt[0], tt[1]), pack_bf16x2(tt[2], tt[3]));
 }
 
+// ---------------------------------------------------------------------------------------------
+// Up to SMALL_MAX row ids in ONE launch (the ids of a training step: 2B + N of them).  Only the grouping of equal ids and
+// the position order inside a group matter to the update, so the order is (id & 255, id >> 8, position): workgroup w owns
+// the ids whose low byte is w.  It reads ALL ids (a few tens of KB, from L2), counts those of lower workgroups (its place
+// in the output) and collects its own in position order; then it sorts its list by the remaining bits, stable, four bits
+// a pass, in LDS (in the output buffers when its list is longer than SMALL_CAP: one id repeated thousands of times).
+// No workgroup waits for another.
+// ---------------------------------------------------------------------------------------------
+constexpr int SMALL_MAX = 32768;
+constexpr int SMALL_CAP = 8192;
+__host__ __device__ constexpr int small_cnt_at(int f) { return f + (f >> 4); }     // one pad word per 16: strided reads spread over banks
+
+// exclusive scan of one value per thread over the 256 threads (in thread order); returns the total through `total`
+__device__ __forceinline__ uint32_t block_scan_256(uint32_t v, uint32_t *s_wave, uint32_t &total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t u = __shfl_up(inc, o);
+        if (lane >= o) inc += u;
+    }
+    __syncthreads();                                       // s_wave may still be read from an earlier scan
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int k = 0; k < wave; ++k) before += s_wave[k];
+    total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+    return before + inc - v;
+}
+
+// One stable counting pass over a list of n (key, position) pairs by the four key bits at `shift`; thread t owns the
+// contiguous piece [t c, (t + 1) c) of the list, c = ceil(n / 256), and moves through it eight entries at a time (eight
+// loads in flight: the list may lie in global memory).  dst_off is added to every destination index.
+__device__ __forceinline__ void small_pass(const uint32_t *sk, const uint32_t *sp, uint32_t *dk, uint32_t *dp, int n, int shift,
+                                           int dst_off, uint32_t *s_cnt, uint32_t *s_wave) {
+    const int tid = threadIdx.x;
+    const int c = (n + 255) >> 8, lo = tid * c, hi = lo + c < n ? lo + c : n;
+#pragma unroll
+    for (int d = 0; d < 16; ++d) s_cnt[small_cnt_at(d * 256 + tid)] = 0;
+    for (int e = lo; e < hi; e += 8) {
+        uint32_t k[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) k[u] = e + u < hi ? sk[e + u] : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (e + u < hi) s_cnt[small_cnt_at((int)((k[u] >> shift) & 15u) * 256 + tid)] += 1;      // own slots only
+    }
+    __syncthreads();
+    // counters in (digit, thread) order: thread t scans the 16 consecutive ones at 16 t
+    uint32_t v[16], sum = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { v[j] = s_cnt[small_cnt_at(tid * 16 + j)]; sum += v[j]; }
+    uint32_t total;
+    uint32_t run = block_scan_256(sum, s_wave, total);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { s_cnt[small_cnt_at(tid * 16 + j)] = run; run += v[j]; }
+    __syncthreads();
+    for (int e = lo; e < hi; e += 8) {
+        uint32_t k[8], q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { k[u] = e + u < hi ? sk[e + u] : 0u; q[u] = e + u < hi ? sp[e + u] : 0u; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (e + u < hi) {
+                const int slot = small_cnt_at((int)((k[u] >> shift) & 15u) * 256 + tid);
+                const uint32_t at = s_cnt[slot];
+                s_cnt[slot] = at + 1;
+                dk[dst_off + (int)at] = k[u]; dp[dst_off + (int)at] = q[u];
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// The same pass when every key of the list has the same four bits at `shift` (decided together; one id repeated through a
+// long list): the order stays, the list is copied.
+__device__ __forceinline__ bool small_pass_trivial(const uint32_t *sk, const uint32_t *sp, uint32_t *dk, uint32_t *dp, int n, int shift) {
+    const uint32_t d0 = (sk[0] >> shift) & 15u;
+    int same = 1;
+    for (int e = threadIdx.x; e < n; e += 256) same &= ((sk[e] >> shift) & 15u) == d0;
+    if (!__syncthreads_and(same)) return false;
+    for (int e = threadIdx.x; e < n; e += 256) { dk[e] = sk[e]; dp[e] = sp[e]; }
+    __syncthreads();
+    return true;
+}
+
+constexpr int SMALL_QUADS = SMALL_MAX / 1024;              // rounds of 256 threads x 4 consecutive ids
+
+__global__ __launch_bounds__(256) void sort_small_kernel(const int32_t *idx, int M, int passes, uint32_t *ka, uint32_t *kb,
+                                                         uint32_t *pa, uint32_t *pb) {
+    __shared__ uint32_t s_cnt[4096 + 256];
+    __shared__ uint32_t s_rc[SMALL_QUADS * 4];             // own ids of every (round, wave), then their offsets
+    __shared__ uint32_t s_key[2][SMALL_CAP], s_pos[2][SMALL_CAP];
+    __shared__ uint32_t s_wave[4];
+    const int w = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rounds = (M + 1023) >> 10;
+    const bool vec = ((uintptr_t)idx & 15) == 0;
+    // every id into registers, all loads in flight: thread t of round r holds ids 4 (256 r + t) .. + 3 (position order =
+    // round, thread, element); 0xFFFFFFFF past the end (no low byte matches: the comparison below is on 9 bits)
+    uint4 id[SMALL_QUADS];
+#pragma unroll
+    for (int r = 0; r < SMALL_QUADS; ++r) {
+        const int i = 4 * (r * 256 + tid);
+        id[r] = make_uint4(~0u, ~0u, ~0u, ~0u);
+        if (r < rounds) {
+            if (vec && i + 3 < M) id[r] = *(const uint4 *)(idx + i);
+            else {
+                if (i < M) id[r].x = (uint32_t)idx[i];
+                if (i + 1 < M) id[r].y = (uint32_t)idx[i + 1];
+                if (i + 2 < M) id[r].z = (uint32_t)idx[i + 2];
+                if (i + 3 < M) id[r].w = (uint32_t)idx[i + 3];
+            }
+        }
+    }
+    const uint64_t below = (1ull << lane) - 1ull;
+    uint32_t lower = 0;                                    // ids of lower workgroups seen by this thread
+#pragma unroll
+    for (int r = 0; r < SMALL_QUADS; ++r) {
+        if (r < rounds) {
+            const int i = 4 * (r * 256 + tid);
+            const uint32_t e[4] = { id[r].x, id[r].y, id[r].z, id[r].w };
+            uint32_t own = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool in = i + j < M;
+                lower += in && (int)(e[j] & 255u) < w;
+                own += (uint32_t)__builtin_popcountll(__ballot(in && (int)(e[j] & 255u) == w));
+            }
+            if (lane == 0) s_rc[r * 4 + wave] = own;
+        }
+    }
+    __syncthreads();
+    // offsets of the (round, wave) groups in the list
+    const int nrc = rounds * 4;
+    const uint32_t c0 = tid < nrc ? s_rc[tid] : 0;
+    uint32_t n_own, n_lower;
+    const uint32_t off = block_scan_256(c0, s_wave, n_own);
+    if (tid < nrc) s_rc[tid] = off;
+    (void)block_scan_256(lower, s_wave, n_lower);
+    __syncthreads();
+    const int n = (int)n_own, base = (int)n_lower;
+    if (n == 0) return;                                    // (uniform: every thread holds the same totals)
+    // the list starts where `passes` exchanges of buffers end in (ka, pa); in LDS the last pass writes (ka, pa) itself
+    const bool in_lds = n <= SMALL_CAP;
+    uint32_t *lk = in_lds ? (passes == 0 ? ka + base : s_key[0]) : ((passes & 1) ? kb : ka) + base;
+    uint32_t *lp = in_lds ? (passes == 0 ? pa + base : s_pos[0]) : ((passes & 1) ? pb : pa) + base;
+#pragma unroll
+    for (int r = 0; r < SMALL_QUADS; ++r) {
+        if (r < rounds) {
+            const int i = 4 * (r * 256 + tid);
+            const uint32_t e[4] = { id[r].x, id[r].y, id[r].z, id[r].w };
+            bool mine[4];
+            int before = 0;                                // own ids of lower lanes in this round
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                mine[j] = i + j < M && (int)(e[j] & 255u) == w;
+                before += __builtin_popcountll(__ballot(mine[j]) & below);
+            }
+            int at = (int)s_rc[r * 4 + wave] + before;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (mine[j]) { lk[at] = e[j]; lp[at] = (uint32_t)(i + j); ++at; }
+        }
+    }
+    __syncthreads();
+    if (in_lds) {
+        for (int p = 0; p < passes; ++p) {
+            const bool last = p == passes - 1;
+            small_pass(s_key[p & 1], s_pos[p & 1], last ? ka : s_key[(p + 1) & 1], last ? pa : s_pos[(p + 1) & 1], n, 8 + 4 * p,
+                       last ? base : 0, s_cnt, s_wave);
+        }
+    } else {
+        uint32_t *k0 = lk, *p0 = lp, *k1 = ((passes & 1) ? ka : kb) + base, *p1 = ((passes & 1) ? pa : pb) + base;
+        for (int p = 0; p < passes; ++p) {
+            if (!small_pass_trivial(k0, p0, k1, p1, n, 8 + 4 * p)) small_pass(k0, p0, k1, p1, n, 8 + 4 * p, 0, s_cnt, s_wave);
+            uint32_t *tk = k0; k0 = k1; k1 = tk;
+            tk = p0; p0 = p1; p1 = tk;
+        }
+    }
+}
+
 // Runs of equal rows ("segments") in the sorted order are reduced in two ways:
 //  - a segment that lies inside one aligned chunk of SEG_CHUNK positions is summed and updated by the
 //    wave of its first position (kernel A): full parallelism over the many short segments;
@@ -282,10 +463,10 @@ __global__ void adam_interior_kernel(int piece_blocks, const uint32_t *sk, const
 }
 
 // B2: one wave per chunk; if a boundary-crossing segment STARTS in this chunk, add its pieces and update.
-__global__ void adam_boundary_kernel(const uint32_t *sk, int64_t M, int dim, int64_t ld, const float *part,
-                                     float *param, uint16_t *shadow, float *mom, float *var, AdamConst c) {
+__device__ __forceinline__ void adam_boundary_body(int64_t blk, const uint32_t *sk, int64_t M, int dim, int64_t ld, const float *part,
+                                                   float *param, uint16_t *shadow, float *mom, float *var, AdamConst c) {
     const int lane = threadIdx.x & 63;
-    const int64_t k = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t k = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int64_t c0 = k * SEG_CHUNK;
     if (c0 >= M) return;
     const int64_t c1 = c0 + SEG_CHUNK < M ? c0 + SEG_CHUNK : M;
@@ -324,6 +505,50 @@ __global__ void adam_boundary_kernel(const uint32_t *sk, int64_t M, int dim, int
     }
 }
 
+// Several tables in one pair of launches (a training step updates the entity table and one or two small relation
+// tables: alone, each of the small ones costs two launches for a few microseconds of work).  Same bodies, so the same bits
+// as one call per table.  Workgroups: the piece sums of every table first, then the interior rows of every table.
+constexpr int ADAM_MAX_TABLES = 4;
+struct AdamTable {
+    const uint32_t *sk, *sp; int64_t M; const float *grads; int dim; int64_t ld; float *param; uint16_t *shadow; float *mom, *var;
+    float *part; int piece_blocks, interior_blocks;
+};
+struct AdamTables { AdamTable t[ADAM_MAX_TABLES]; };
+
+__global__ void adam_interior_tables_kernel(const AdamTables T, AdamConst c) {
+    int b = (int)blockIdx.x;
+#pragma unroll
+    for (int k = 0; k < ADAM_MAX_TABLES; ++k) {
+        const AdamTable &t = T.t[k];
+        if (b < t.piece_blocks) { adam_piece_body(b, t.sk, t.sp, t.M, t.grads, t.dim, t.part); return; }
+        b -= t.piece_blocks;
+    }
+#pragma unroll
+    for (int k = 0; k < ADAM_MAX_TABLES; ++k) {
+        const AdamTable &t = T.t[k];
+        if (b < t.interior_blocks) {
+            adam_interior_body(b, t.sk, t.sp, t.M, t.grads, t.dim, t.ld, t.param, t.shadow, t.mom, t.var, c);
+            return;
+        }
+        b -= t.interior_blocks;
+    }
+}
+
+__global__ void adam_boundary_tables_kernel(const AdamTables T, AdamConst c) {
+    int b = (int)blockIdx.x;
+#pragma unroll
+    for (int k = 0; k < ADAM_MAX_TABLES; ++k) {
+        const AdamTable &t = T.t[k];
+        if (b < t.piece_blocks) { adam_boundary_body(b, t.sk, t.M, t.dim, t.ld, t.part, t.param, t.shadow, t.mom, t.var, c); return; }
+        b -= t.piece_blocks;
+    }
+}
+
+__global__ void adam_boundary_kernel(const uint32_t *sk, int64_t M, int dim, int64_t ld, const float *part,
+                                     float *param, uint16_t *shadow, float *mom, float *var, AdamConst c) {
+    adam_boundary_body(blockIdx.x, sk, M, dim, ld, part, param, shadow, mom, var, c);
+}
+
 struct SortWs { uint32_t *ka, *kb, *pa, *pb, *hist; float *part; int nblk, rounds; };
 
 size_t sort_carve(int64_t M, int dim, void *ws, SortWs &s) {
@@ -351,6 +576,9 @@ size_t kge_sparse_adam_ws(int64_t M, int dim) {
 
 size_t kge_sort_ws(int64_t M) { return kge_sparse_adam_ws(M, 0); }
 
+// row ids of a step: the one-launch sort (grouped, not ascending: see sort_small_kernel); everything else the radix passes
+static bool sort_is_small(bool row_ids, int64_t M) { return row_ids && M <= SMALL_MAX; }
+
 // Sorts (key, position) pairs by key, stable; returns the buffers that hold the result.  Keys are
 // either the given row ids, or (when h and t are given) the partition-pair bucket of each triple, or
 // (with r as well) bucket * n_rel + relation.
@@ -361,6 +589,12 @@ int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64
     sort_carve(M, 0, ws, s);
     int bits = 1;
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
+    if (sort_is_small(idx != nullptr, M)) {
+        const int passes = bits > 8 ? (bits - 8 + 3) / 4 : 0;
+        hipLaunchKernelGGL(sort_small_kernel, dim3(256), dim3(256), 0, st, idx, (int)M, passes, s.ka, s.kb, s.pa, s.pb);
+        *sk = s.ka; *sp = s.pa;
+        return kge_launch_status();
+    }
     uint32_t *ki = s.ka, *ko = s.kb, *pi = s.pa, *po = s.pb;       // the first pass writes buffer B
     const bool own_scan = s.nblk <= 64;
     const int first = idx ? 1 : (r ? 3 : 2);
@@ -388,6 +622,7 @@ int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64
 static void sort_result(int64_t M, int64_t key_range, void *ws, const uint32_t **sk, const uint32_t **sp) {
     SortWs s;
     sort_carve(M, 0, ws, s);
+    if (sort_is_small(true, M)) { *sk = s.ka; *sp = s.pa; return; }
     int bits = 1;
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
     const int passes = (bits + 7) / 8;
@@ -400,16 +635,46 @@ int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void
     return kge_sort_pairs(idx, nullptr, nullptr, 1, 1, M, n_rows, ws, &sk, &sp, st, nullptr, 0);
 }
 
-int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
-                              const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st) {
-    const uint32_t *sk, *sp;
-    sort_result(M, n_rows, ws, &sk, &sp);
+static AdamConst adam_const(const kge_adam_cfg_t &cfg) {
     AdamConst c;
     c.lr = cfg.lr; c.b1 = cfg.beta1; c.b2 = cfg.beta2; c.eps = cfg.eps;
     c.omb1 = 1.f - cfg.beta1; c.omb2 = 1.f - cfg.beta2;
     c.inv_bc1 = adam_inv_bias(cfg.beta1, (uint64_t)cfg.step);
     c.inv_bc2 = adam_inv_bias(cfg.beta2, (uint64_t)cfg.step);
     c.step_counter = cfg.step_counter; c.step = (uint64_t)cfg.step;
+    return c;
+}
+
+// tables with M = 0 are skipped by the caller; n <= ADAM_MAX_TABLES
+int kge_run_sparse_adam_apply_tables(const kge_adam_table_t *tb, int n, const kge_adam_cfg_t &cfg, hipStream_t st) {
+    AdamTables T = {};
+    int pieces = 0, interior = 0;
+    for (int k = 0; k < n; ++k) {
+        AdamTable &t = T.t[k];
+        void *ws = tb[k].ws;
+        if (((uintptr_t)ws & 255) != 0) ws = (char *)ws + (256 - ((uintptr_t)ws & 255));
+        sort_result(tb[k].M, tb[k].n_rows, ws, &t.sk, &t.sp);
+        SortWs s;
+        sort_carve(tb[k].M, tb[k].dim, ws, s);
+        const int64_t nchunk = (tb[k].M + SEG_CHUNK - 1) / SEG_CHUNK;
+        t.M = tb[k].M; t.grads = tb[k].grads; t.dim = tb[k].dim; t.ld = tb[k].ld; t.param = tb[k].param_f32;
+        t.shadow = (uint16_t *)tb[k].param_bf16; t.mom = tb[k].m; t.var = tb[k].v; t.part = s.part;
+        t.piece_blocks = nchunk > 1 ? (int)((nchunk + 3) / 4) : 0;
+        t.interior_blocks = (int)((tb[k].M + 3) / 4);
+        pieces += t.piece_blocks; interior += t.interior_blocks;
+    }
+    const AdamConst c = adam_const(cfg);
+    KgeProfScope prof(KGE_PROF_ADAM, st);
+    hipLaunchKernelGGL(adam_interior_tables_kernel, dim3(pieces + interior), dim3(256), 0, st, T, c);
+    if (pieces > 0) hipLaunchKernelGGL(adam_boundary_tables_kernel, dim3(pieces), dim3(256), 0, st, T, c);
+    return kge_launch_status();
+}
+
+int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
+                              const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st) {
+    const uint32_t *sk, *sp;
+    sort_result(M, n_rows, ws, &sk, &sp);
+    const AdamConst c = adam_const(cfg);
     SortWs s;
     sort_carve(M, dim, ws, s);                              // the piece buffer lies behind the sort buffers
     KgeProfScope prof(KGE_PROF_ADAM, st);

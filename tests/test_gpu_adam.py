@@ -206,3 +206,37 @@ def test_streams_passed_as_arguments_give_the_same_bits():
     for a, b in zip(ref, two):
         assert bool((a == b).all())
 
+
+
+def test_several_tables_in_one_call_give_the_bits_of_one_call_per_table():
+    """kge_sparse_adam_apply_tables (the entity table and the small relation tables of a step in two launches) against
+    kge_sparse_adam_apply table by table; one table of the set is empty, one has a single row id repeated."""
+    import paper_2211_12281_amd as kge
+    shapes = [(50000, 256, 24576, True), (1000, 128, 4096, True), (1000, 256, 0, False), (7, 64, 300, False)]
+    dev = lambda a: torch.from_numpy(a.copy()).cuda()
+    sets = []
+    for k, (n_rows, d, M, shadow) in enumerate(shapes):
+        theta, m, v = _state(n_rows, d, 40 + k, True)
+        g = np.random.default_rng(140 + k)
+        idx = ks.ZipfIds(n_rows, 1.1).draw(g, M) if k != 3 else np.full(M, 5, np.int32)
+        grads = (g.normal(size=(M, d)) * 1e-2).astype(F)
+        one = {"idx": dev(idx), "grads": dev(grads)}
+        for tag in ("ref", "got"):
+            one[tag] = [dev(theta), dev(m), dev(v)]
+            one[tag + "_sh"] = torch.zeros((n_rows, d), dtype=torch.bfloat16, device="cuda") if shadow else None
+            one[tag + "_ws"] = kge.Workspace()
+        sets.append(one)
+    for s, (n_rows, d, M, _) in zip(sets, shapes):
+        if M:
+            kge.sparse_adam_plan(n_rows, d, s["idx"], s["ref_ws"])
+            kge.sparse_adam_apply(s["ref"][0], s["ref_sh"], s["ref"][1], s["ref"][2], s["grads"], s["ref_ws"], 2e-3, step=7)
+            kge.sparse_adam_plan(n_rows, d, s["idx"], s["got_ws"])
+    kge.sparse_adam_apply_tables([(s["got"][0], s["got_sh"], s["got"][1], s["got"][2], s["grads"], s["got_ws"]) for s in sets],
+                                 2e-3, step=7)
+    torch.cuda.synchronize()
+    for s in sets:
+        for a, c in zip(s["ref"], s["got"]):
+            assert bool((a == c).all())
+        if s["ref_sh"] is not None:
+            assert bool((s["ref_sh"].view(torch.int16) == s["got_sh"].view(torch.int16)).all())
+    assert not bool((sets[0]["got"][0] == dev(_state(50000, 256, 40, True)[0])).all())     # something was updated
