@@ -27,9 +27,11 @@
 // MODE_FWD weights a score x with exp2(x - ref), ref a reference exponent per own row.  The two waves of a pair see
 // different stream rows but feed the same accumulators, so they use the SAME reference: the exact maximum of the
 // workgroup's first tile over both waves (exchanged through the LDS once).  It is never raised: the weights of later
-// tiles may exceed 1, which costs nothing while they stay finite.  A score that exceeds the reference by more than
-// 2^SY_GUARD (69 in natural units) cannot be handled this way; the wave then sets *a.flag and the host side runs the pass
-// again with the kernel of block_fwd_pp.hip, which raises its reference as it goes.
+// tiles may exceed 1, which costs nothing while they stay finite.  A score that exceeds the reference by more than about
+// 2^SY_GUARD (69 in natural units) cannot be handled this way: when a lane's sum of weights ends above 2^SY_GUARD (or is
+// not a number), the wave sets *a.flag and the host side runs the pass again with the kernel of block_fwd_pp.hip, which
+// raises its reference as it goes.  (The check is on the sums at the end, not on every score: a weight that overflowed
+// leaves an infinite sum, and a sum below 2^SY_GUARD bounds every weight.)
 #include "block_kernel.hpp"
 
 int kge_launch_fwd_sym(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
@@ -240,7 +242,6 @@ void kge_sym_kernel(const KgeBlockArgs a) {
         const char *stage = lds + (slot % SY_NSTAGE) * SY_STAGE;
         const char *xs = lds + ((slot + SY_NSTAGE - 1) % SY_NSTAGE) * SY_STAGE;
         uint4 av[SY_KS], pp[2][2], trp[8];
-        float tm[2] = {-INFINITY, -INFINITY};
         uint32_t pk[4];
         uint4 pnew[2][2];
         // ---- requests of the round ----
@@ -269,7 +270,6 @@ void kge_sym_kernel(const KgeBlockArgs a) {
             const float s1 = accs[ob][i];
             const float x1 = FWD ? fmaf(s1, xscale, -ref[ob])            // (-inf for a padding row: its accumulator started there)
                                  : fmaf(s1, xscale, side_k[i]);
-            if constexpr (FWD) tm[ob] = fmaxf(tm[ob], x1);
             const float c1 = entry_coef(ob, s1, x1);
             if (i & 1) {
                 pk[(i >> 1) & 3] = kge_pack_bf16x2(cprev, c1);
@@ -328,9 +328,6 @@ void kge_sym_kernel(const KgeBlockArgs a) {
             entry(1, 2 * n);
             entry(1, 2 * n + 1);
             __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (FWD) {
-            if (__any(fmaxf(tm[0], tm[1]) > SY_GUARD)) guard = true;     // (wave-uniform)
         }
 #pragma unroll
         for (int ob = 0; ob < 2; ++ob)
@@ -405,7 +402,9 @@ void kge_sym_kernel(const KgeBlockArgs a) {
                 }
         }
         if constexpr (FWD) {
-            if (guard && lane == 0) atomicOr(a.flag, 1);    // a tile outgrew the fixed reference: the pass is redone
+            const float lim = __builtin_amdgcn_ldexpf(1.f, (int)SY_GUARD);
+            guard = __any(!(st_l[0] <= lim) || !(st_l[1] <= lim));
+            if (guard && lane == 0) atomicOr(a.flag, 1);    // a score outgrew the fixed reference: the pass is redone
         }
     }
 

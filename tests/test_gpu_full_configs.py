@@ -287,10 +287,10 @@ def test_c5_transh_partition_pair_step_full_size(orc):
 
 
 def test_c5_partition_bucketing_at_scale(orc):
-    """100M seeded triples into 16 x 16 buckets (the 600M-triple graph takes the same kernels; the
-    host-side generation of the index stream is what bounds this test)."""
+    """600M seeded triples (the triple count of the full-scale configuration; Table 1 lists 601M) into 16 x 16 buckets:
+    offsets against the oracle's count, the order by its properties."""
     import paper_2211_12281_amd as kge
-    n_ent, D, n = 90_000_000, 16, 100_000_000
+    n_ent, D, n = 90_000_000, 16, 600_000_000
     part = -(-n_ent // D)
     g = ks.rng(ks.BASE_SEED, ks.TAG_TRIPLE_H)
     h, t = ks.uniform_ids(g, 0, n_ent, n), ks.uniform_ids(g, 0, n_ent, n)
@@ -304,15 +304,16 @@ def test_c5_partition_bucketing_at_scale(orc):
     same = sb[1:] == sb[:-1]
     assert np.all(order[1:][same] > order[:-1][same])                  # input order kept inside a bucket
     assert np.array_equal(np.sort(order[:: 9973]), np.unique(order[:: 9973]))
+    del bkt, sb, same, order, h, t
     _free()
 
 
 def test_c5_relation_sampler_at_scale(orc):
-    """100M seeded triples, 1,400 Zipf(1.0) relations, 16 x 16 buckets: the index is checked by its
+    """600M seeded triples, 1,400 Zipf(1.0) relations, 16 x 16 buckets: the index is checked by its
     properties, the draws of one worker's micro-batch (8,192 triples, 512 per tail partition) against the
     oracle's sampler running on the index the library built."""
     import paper_2211_12281_amd as kge
-    n_ent, D, n, n_rel = 90_000_000, 16, 100_000_000, 1400
+    n_ent, D, n, n_rel = 90_000_000, 16, 600_000_000, 1400
     part = -(-n_ent // D)
     g = ks.rng(ks.BASE_SEED, ks.TAG_TRIPLE_H)
     h, t = ks.uniform_ids(g, 0, n_ent, n), ks.uniform_ids(g, 0, n_ent, n)
