@@ -39,6 +39,9 @@ def parse():
                     help="training workloads: draw every micro-batch on the GPU with the relation-aware sampler "
                          "(one worker's all-partition micro-batch and sharded negatives) from a synthetic list of "
                          "this many triples, instead of replaying pre-drawn index streams")
+    ap.add_argument("--pair-batches", action="store_true",
+                    help="c5: replay pre-drawn micro-batches of ONE partition pair per step instead of the default there, "
+                         "the sampler's all-partition micro-batch with sharded negatives (--sampled-batches 100000000)")
     ap.add_argument("--encoder", type=int, default=0, metavar="FEAT_DIM",
                     help="training workloads: entities are encoded as e_S + M e_F from synthetic text features of "
                          "this width (768 in the paper) with dropout 0.1, trained M_H and M_T; default: shallow only")
@@ -326,6 +329,26 @@ class TrainWorkload:
             self.graphs.append(g)
         torch.cuda.synchronize()
 
+    def hbm_bytes(self):
+        """Algorithmic HBM bytes per step of the memory-bound kernels (what the method must move, whatever the kernels do):
+        gather - the 2B + N entity rows and B relation rows read once, and the ids (a fused path writes nothing);
+        finish - the 2B + N + B gradient rows written once and the 3B rows the chain rule reads;
+        adam   - per DISTINCT touched row (counted on the batches in flight) parameter and both moments read and written,
+                 the bf16 shadow written, plus every gradient row and id read once."""
+        torch = self.torch
+        if self.enc is not None or self.sampler is not None:
+            return {}
+        e = 2 if self.bf16 else 4
+        B, N, d, k = self.B, self.N, self.d, self.rel.shape[1]
+        u_ent = sum(int(torch.unique(b[5]).numel()) for b in self.batches) / len(self.batches)
+        u_rel = sum(int(torch.unique(b[1]).numel()) for b in self.batches) / len(self.batches)
+        w = 1 if self.relw is None else 2
+        row = lambda dim: dim * (24 + (2 if self.bf16 else 0))
+        return {"gather": (2 * B + N) * d * e + w * B * k * e + (3 * B + N) * 4,
+                "finish": (2 * B + N) * d * 4 + w * B * k * 4 + 3 * B * d * e,
+                "adam": u_ent * row(d) + (2 * B + N) * (d * 4 + 4) + u_rel * (row(k) + (w - 1) * row(d)) + w * B * (k * 4 + 4),
+                "distinct_rows": {"entity": u_ent, "relation": u_rel}}
+
     def pairs_per_step(self):
         return self.B * (self.N + 1)
 
@@ -359,11 +382,11 @@ class TrainWorkload:
             per = {"block_score": 5.0, "block_fwd": 5.0, "block_gradt": 4.0}.get(slot, 5.0)
         return per * self.B * self.N * self.d
 
-    def cpu_baseline(self, orc):
+    def cpu_baseline(self, orc, shrink=1):
         """Oracle forward + backward + sparse Adam on the first rows of batch 0 against all negatives."""
         ks = self.ks
         h, r, t, lo, hi = self.host_batches[0]
-        bs = self.B
+        bs = max(1, self.B // shrink)
         h, r, t = h[:bs], r[:bs], t[:bs]
         neg = orc.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, lo, hi, self.N)
         uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg)
@@ -382,7 +405,7 @@ class TrainWorkload:
         dt = time.time() - t0
         return {"value": bs * (self.N + 1) / dt, "unit": "scored_pairs/s", "cores": orc.num_threads(),
                 "kind": "oracle", "seconds": round(dt, 2),
-                "sample": f"all {bs} triples of batch 0 against all {self.N} shared negatives: "
+                "sample": f"the first {bs} triples of batch 0 against all {self.N} shared negatives: "
                           f"forward + backward + sparse Adam of the entity table"}
 
 
@@ -429,9 +452,9 @@ class ScoreWorkload:
         g = sum(2 if s == "transh" else 1 for s in self.scorers) / len(self.scorers)
         return 2.0 * self.B * self.N * self.d * g
 
-    def cpu_baseline(self, orc):
+    def cpu_baseline(self, orc, shrink=1):
         ks = self.ks
-        bs = self.B
+        bs = max(1, self.B // shrink)
         neg = orc.sample_negatives(ks.BASE_SEED, 0, ks.TAG_NEG, 0, self.n_ent, self.N)
         h, r, t = self.h_host[:bs], self.r_host[:bs], self.t_host[:bs]
         uniq, (ch, ct, cn) = ks.compact_rows(h, t, neg)
@@ -443,7 +466,7 @@ class ScoreWorkload:
         dt = time.time() - t0
         return {"value": len(self.scorers) * bs * (self.N + 1) / dt, "unit": "scored_pairs/s",
                 "cores": orc.num_threads(), "kind": "oracle", "seconds": round(dt, 2),
-                "sample": f"all {bs} queries against all {self.N} negatives, {len(self.scorers)} scorers"}
+                "sample": f"the first {bs} queries against all {self.N} negatives, {len(self.scorers)} scorers"}
 
 
 class RankWorkload:
@@ -510,9 +533,9 @@ class RankWorkload:
         # summed over the chunk launches of one call (TransH: the second contraction, w^ . t, is part of the score)
         return 2.0 * self.Q * self.n_ent * self.d * (2 if self.scorers == ["transh"] else 1)
 
-    def cpu_baseline(self, orc):
+    def cpu_baseline(self, orc, shrink=1):
         ks = self.ks
-        nq = 8
+        nq = max(1, 8 // shrink)
         ent = self.ent.float().cpu().numpy()
         t0 = time.time()
         for s in self.scorers:
@@ -542,6 +565,8 @@ def main():
     import paper_2211_12281_amd as kge
     kge.load()
     P = ks.PRESETS[a.workload]
+    if a.workload == "c5" and not a.sampled_batches and not a.pair_batches:
+        a.sampled_batches = 100_000_000    # the paper's generator (eq. (microbatch), eq. (negsamples)) is the default at full scale
     if a.workload in ("c1", "c3", "c5"):
         wl = TrainWorkload(a.workload, P, a.scale, a.scorer, a.reg_l3, a.sampled_batches, a.encoder, a.p_norm)
     elif a.workload == "c2":
@@ -610,9 +635,9 @@ def main():
                               "avg_us": 1e3 * tot / n, "measured": f"{extra_steps} steps after the timed region"}
     roof = None
     if prof:
-        # the slots "adam" and "sort" bracket several kernels per call (2 and 6 launches): they compete with their
+        # the slots "adam" and "sort" bracket several kernels per call (2, and 1 to 6 launches): they compete with their
         # per-kernel share, the roofline below being that of ONE kernel
-        share = {"adam": 2.0, "sort": 6.0}
+        share = {"adam": 2.0, "sort": 2.0}
         dom = max(prof, key=lambda k: prof[k]["total_ms"] / share.get(k, 1.0))
         # The two passes of a training step (block_fwd over the queries, block_gradt over the negatives) are the same
         # kernel template and take the same time to within run-to-run noise: when they are within 5 % of each other the
@@ -661,17 +686,37 @@ def main():
 
     cpu = None
     if not a.no_cpu_baseline:
+        import ctypes
         import oracle
         oracle.build()
-        reps, secs, cpu = 0, 0.0, None
-        while secs < 10.0 and reps < 64:          # whole samples until about 10 s of CPU work
-            one = wl.cpu_baseline(oracle)
-            secs += one["seconds"]; reps += 1
-            cpu = one if cpu is None else cpu
-        work = cpu["value"] * cpu["seconds"]      # units of one sample
-        cpu["value"] = work * reps / secs
-        cpu["seconds"] = round(secs, 2)
-        cpu["sample"] += f" (x{reps})"
+
+        def timed(shrink, budget_s):
+            reps, secs, first = 0, 0.0, None
+            while secs < budget_s and reps < 64:   # whole samples until about budget_s of CPU work
+                one = wl.cpu_baseline(oracle, shrink)
+                secs += one["seconds"]; reps += 1
+                first = one if first is None else first
+            work = first["value"] * first["seconds"]    # units of one sample
+            first["value"] = work * reps / secs
+            first["seconds"] = round(secs, 2)
+            first["sample"] += f" (x{reps})"
+            return first
+
+        cpu = timed(1, 10.0)                       # every thread the OpenMP runtime gives the oracle
+        cpu["nproc"] = os.cpu_count()
+        try:
+            cpu["cpu_model"] = next(l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name"))
+        except (OSError, StopIteration):
+            cpu["cpu_model"] = None
+        try:                                        # the same oracle on ONE thread, on a sample a sixteenth the size
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            one = timed(16, 6.0)
+            gomp.omp_set_num_threads(cpu["cores"])
+            one["cores"] = 1
+            cpu["one_thread"] = {k: one[k] for k in ("value", "unit", "cores", "seconds", "sample")}
+        except OSError:
+            cpu["one_thread"] = None
 
     if roof is not None and roof["bound"] == "mfma":
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -680,6 +725,7 @@ def main():
                 tr = json.load(open(tpath)).get(a.workload, {}).get(roof["kernel"])
                 if tr is not None:
                     roof["traffic"] = tr          # HBM bytes per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+                    roof["traffic_source"] = "stored: profiles/traffic.json, read from a rocprofv3 --pmc run of this command (not measured in this run)"
             except (ValueError, OSError):
                 pass
     # the same box's own figures beside the published peaks: a loop of independent bf16 matrix instructions and a plain
@@ -700,6 +746,20 @@ def main():
         roof["frac_less_empty_pair"] = roof["frac"] * roof["avg_us"] / net
     if roof is not None and roof.get("achieved") is not None and roof["bound"] == "mfma" and wl_bf16(wl):
         roof["frac_of_measured_loop"] = roof["achieved"] / calib["mfma_bf16_loop_tflops"]
+    # the memory-bound kernels of a training step against the HBM peak and against this box's own streaming copy
+    hbm = None
+    if isinstance(wl, TrainWorkload):
+        per = wl.hbm_bytes()
+        hbm = {}
+        for slot in ("gather", "finish", "adam"):
+            if slot in prof and slot in per:
+                gbs = per[slot] / (prof[slot]["avg_us"] * 1e-6) / 1e9
+                hbm[slot] = {"bytes_algorithmic": int(per[slot]), "avg_us": prof[slot]["avg_us"], "GB/s": gbs,
+                             "frac_of_8TBs": gbs / PEAK_HBM_GBS, "frac_of_copy": gbs / calib["copy_gbs"]}
+        if hbm:
+            hbm["distinct_rows_per_step"] = per["distinct_rows"]
+            hbm["note"] = ("avg_us: HIP events around the launch(es) of the slot, 20 steps after the timed region "
+                           "(adam: both launches, all tables of the step)")
     pairs = wl.pairs_per_step()
     line = {
         "metric": "scored (query,candidate) pairs/s", "value": pairs / (ms * 1e-3), "unit": "pairs/s",
@@ -710,6 +770,8 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, "kernels": prof, "calibration": calib,
     }
     line["host_enqueue_ms_per_step"] = dt_host * 1e3 / a.steps
+    if hbm:
+        line["hbm_kernels"] = hbm
     if isinstance(wl, TrainWorkload):
         line["enqueue"] = ("HIP graph replay, one graph per pre-drawn batch; every 4th step call by call with the HIP-event bracket"
                            if graphed else "call by call; the next step's negatives and sorts on a second stream beside the update")

@@ -400,7 +400,10 @@ size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t 
  * Host-side state shared by all callers of the process; not thread-safe; off by default.
  */
 enum { KGE_PROF_BLOCK_SCORE = 0, KGE_PROF_BLOCK_FWD = 1, KGE_PROF_BLOCK_GRADT = 2, KGE_PROF_ADAM = 3,
-       KGE_PROF_SORT = 4, KGE_PROF_TOPK_SCAN = 5, KGE_PROF_ENC_FWD = 6, KGE_PROF_ENC_BWD = 7, KGE_PROF_SLOTS = 8 };
+       KGE_PROF_SORT = 4, KGE_PROF_TOPK_SCAN = 5, KGE_PROF_ENC_FWD = 6, KGE_PROF_ENC_BWD = 7,
+       KGE_PROF_GATHER = 8,   /* kge_loss_bwd: query build + gather of the negatives' rows (one launch) */
+       KGE_PROF_FINISH = 9,   /* kge_loss_bwd: chain rule of the queries + finish of the negatives' gradient rows (one launch) */
+       KGE_PROF_SLOTS = 10 };
 int kge_profile_enable(int on);
 int kge_profile_collect(int slot, double *total_ms, int64_t *launches);
 

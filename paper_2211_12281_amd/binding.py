@@ -24,7 +24,7 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_calibrate_mfma", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev",
            "kge_sparse_adam_apply_tables"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
-              "enc_fwd": 6, "enc_bwd": 7}
+              "enc_fwd": 6, "enc_bwd": 7, "gather": 8, "finish": 9}
 
 
 class KgeEncoderT(C.Structure):

@@ -43,20 +43,28 @@ bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
     return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_GRADT_ONE_ROLE);
 }
 
+// (The optional event bracket of a pass lies around its block kernel alone: the gated second launch of a forward pass,
+// which exits at once unless the first kernel asked for it, follows the bracket.)
 int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
                      int own_tiles, int nsplit, hipStream_t st) {
+    const int slot = mode == KGE_MODE_SCORE ? KGE_PROF_BLOCK_SCORE : mode == KGE_MODE_FWD ? KGE_PROF_BLOCK_FWD : KGE_PROF_BLOCK_GRADT;
+    if (mode == KGE_MODE_FWD && kge_sym_applies(bf16, rb, transh, dsplit) && sym_serves(mode, kind, loss)) {
+        int rc;
+        {
+            KgeProfScope prof(slot, st);
+            rc = kge_launch_fwd_sym(kind, loss, a, own_tiles, nsplit, st);
+        }
+        if (rc != KGE_OK) return rc;
+        KgeBlockArgs b = a;                                  // redone only if the first kernel raised the flag
+        b.gate = a.flag;
+        return kge_launch_fwd_pp(kind, loss, b, own_tiles, nsplit, st);
+    }
+    KgeProfScope prof(slot, st);
     if (mode == KGE_MODE_SCORE)
         return bf16 ? kge_launch_block_bf16_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st)
                     : kge_launch_block_f32_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st);
     const bool ls = loss == KGE_LOGSIGMOID;
     if (mode == KGE_MODE_FWD) {
-        if (kge_sym_applies(bf16, rb, transh, dsplit) && sym_serves(mode, kind, loss)) {
-            const int rc = kge_launch_fwd_sym(kind, loss, a, own_tiles, nsplit, st);
-            if (rc != KGE_OK) return rc;
-            KgeBlockArgs b = a;                              // redone only if the first kernel raised the flag
-            b.gate = a.flag;
-            return kge_launch_fwd_pp(kind, loss, b, own_tiles, nsplit, st);
-        }
         if (kge_fwd_pp_applies(bf16, rb, transh, dsplit)) return kge_launch_fwd_pp(kind, loss, a, own_tiles, nsplit, st);
         if (bf16) return ls ? kge_launch_block_bf16_fwd_ls(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st)
                             : kge_launch_block_bf16_fwd_sm(rb, mode, transh, kind, loss, dsplit, a, own_tiles, nsplit, st);

@@ -199,8 +199,6 @@ KgeModelDev dev_model(const kge_model_t &m) {
 
 int launch_block(const Geometry &g, int mode, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, int dsplit,
                  hipStream_t st) {
-    KgeProfScope prof(mode == KGE_MODE_SCORE ? KGE_PROF_BLOCK_SCORE : mode == KGE_MODE_FWD ? KGE_PROF_BLOCK_FWD
-                                                                                        : KGE_PROF_BLOCK_GRADT, st);
     return kge_launch_block(g.bf16, g.rb, mode, g.transh, g.kind, loss, dsplit, a, own_tiles, nsplit, st);
 }
 
@@ -418,8 +416,11 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
 
     // (the kernels that need no transposed copy of the negatives get queries and negatives from ONE launch)
     const bool plain_gather = have_block && (g.l1 || kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q));
-    if (plain_gather) rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos,
-                                                  neg, g.N, g.Np, b.T, b.tn, st, nullptr, nullptr, nullptr, nullptr, b.flag, b.nbias);
+    if (plain_gather) {
+        KgeProfScope prof(KGE_PROF_GATHER, st);
+        rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos,
+                                    neg, g.N, g.Np, b.T, b.tn, st, nullptr, nullptr, nullptr, nullptr, b.flag, b.nbias);
+    }
     else rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos, nullptr, st);
     if (rc != KGE_OK) return rc;
     KgeBlockArgs a{};
@@ -467,6 +468,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     }
     if (have_block) {
         // chain rule of the queries and finish of the negatives' gradient rows in ONE launch
+        KgeProfScope prof(KGE_PROF_FINISH, st);
         rc = kge_run_chain_tfinish(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, g.nsplit_q, b.gpos,
                                    g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, cfg->reg_l3, b.regv,
                                    b.acct, b.sumt, g.nsplit_t, g.Np, g.N, model->dim, g.kind == KGE_KIND_DIST && !g.l1, b.T, neg,
