@@ -151,8 +151,10 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
  *   g_rel         float[B * rel_dim] gradient of each triple's relation row
  *   g_relw        float[B * d]       TransH only (NULL otherwise)
  *   g_rel_idx     int32[B]           = r
- * The sub-gradient of a distance score at distance 0 is 0.  TransH requires d*sizeof(element)
- * <= 512 bytes in this call.
+ * The sub-gradient of a distance score at distance 0 is 0.  TransH rows of more than 512 bytes (Table 3 lists
+ * TransH at d = 256, 1,024 bytes in fp32) take the route of the 1-norm variants: the score block is written to the
+ * workspace (B*N floats, three of them) and both passes run on the vector pipe in fp32, about ten times slower than the
+ * matrix-core route of the narrower rows.
  */
 int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h,
                  const int32_t *r, const int32_t *t, int64_t B, const int32_t *neg, int64_t N,

@@ -45,7 +45,10 @@ int kge_run_ensemble(const int32_t *lists, int M, int64_t Q, int K, double p, in
 namespace {
 
 struct Geometry {
-    bool bf16, transh, l1;              // l1: distance scorer with the 1-norm (vector-pipe kernels, score block in memory)
+    bool bf16, transh, l1;              // l1: the vector-pipe kernels with the score block in memory - distance scorers with the
+                                        // 1-norm, and in training calls TransH rows over 512 bytes (2-norm; the matrix-core
+                                        // kernels have no registers for two operands of that width)
+    int pn;                             // ... the norm they compute
     int es, rb, dp, kind;
     int B, N, Bp, Np;
     int own_tiles_b, own_tiles_n, own_tiles_s;   // own tiles of the FWD pass (queries), the GRADT and the SCORE pass (negatives)
@@ -74,7 +77,7 @@ int validate_model(const kge_model_t *m) {
     return KGE_OK;
 }
 
-Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
+Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N, bool train = false) {
     Geometry g{};
     g.bf16 = m.dtype == KGE_BF16;
     g.transh = m.scorer == KGE_TRANSH;
@@ -82,7 +85,8 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N) {
     g.rb = m.dim * g.es <= 512 ? 512 : 1024;
     g.dp = g.rb / g.es;
     g.kind = (m.scorer == KGE_DISTMULT || m.scorer == KGE_COMPLEX) ? KGE_KIND_MULT : KGE_KIND_DIST;
-    g.l1 = g.kind == KGE_KIND_DIST && m.p_norm == 1;
+    g.l1 = g.kind == KGE_KIND_DIST && (m.p_norm == 1 || (train && g.transh && g.rb > 512));
+    g.pn = g.kind == KGE_KIND_DIST ? m.p_norm : 2;
     g.B = (int)B; g.N = (int)N;
     g.Bp = (int)kge_round_up(B, KGE_PAD); g.Np = (int)kge_round_up(N, KGE_PAD);
     g.own_tiles_b = g.Bp / (128 * kge_block_ow(g.bf16, g.rb, g.transh, KGE_MODE_FWD, g.kind));
@@ -192,6 +196,7 @@ KgeModelDev dev_model(const kge_model_t &m) {
     KgeModelDev d;
     d.scorer = m.scorer; d.bf16 = m.dtype == KGE_BF16; d.dim = m.dim; d.rel_dim = m.rel_dim;
     d.p1 = (m.scorer == KGE_TRANSE || m.scorer == KGE_TRANSH || m.scorer == KGE_ROTATE) && m.p_norm == 1;
+    d.vec = d.p1;
     d.ent = m.ent; d.rel = m.rel; d.relw = m.relw;
     d.ent_ld = m.ent_ld; d.rel_ld = m.rel_ld; d.relw_ld = m.relw_ld;
     return d;
@@ -236,7 +241,7 @@ size_t kge_workspace_bytes(int op, const kge_model_t *model, int64_t B, int64_t 
     case KGE_OP_SCORE:
     case KGE_OP_LOSS_BWD: {
         if (validate_model(model) != KGE_OK || B >= (1ll << 30) || N >= (1ll << 30)) return 0;
-        Geometry g = make_geometry(*model, B, N);
+        Geometry g = make_geometry(*model, B, N, op == KGE_OP_LOSS_BWD);
         Buffers b;
         return carve(g, op == KGE_OP_LOSS_BWD, nullptr, b);
     }
@@ -400,8 +405,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     if (B > 0 && (!h || !r || !t || !g_ent || !g_ent_idx || !g_rel || !g_rel_idx)) return KGE_E_INVALID_ARG;
     if (N > 0 && (!neg || !g_ent || !g_ent_idx)) return KGE_E_INVALID_ARG;
     if (model->scorer == KGE_TRANSH && B > 0 && !g_relw) return KGE_E_INVALID_ARG;
-    Geometry g = make_geometry(*model, B, N);
-    if (g.transh && !g.l1 && g.rb > 512) return KGE_E_UNSUPPORTED;
+    Geometry g = make_geometry(*model, B, N, true);
     if (!ws) return KGE_E_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)hip_stream;
     Buffers b;
@@ -409,6 +413,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     if (carve(g, true, nullptr, b) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     carve(g, true, ws, b);
     KgeModelDev md = dev_model(*model);
+    md.vec = g.l1;
     const float scale = cfg->loss_scale > 0.f ? cfg->loss_scale : (B > 0 ? 1.f / (float)B : 1.f);
     const float c_corr = (cfg->loss == KGE_SAMPLED_SOFTMAX && N > 0)
                              ? (float)log((double)(cfg->n_ent_for_c - 1) / (double)N) : 0.f;
@@ -426,7 +431,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     KgeBlockArgs a{};
     if (have_block && g.l1) {
         // 1-norm: the score block goes to memory, one row pass gives the loss statistics
-        rc = g.transh ? kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, b.A, b.P, g.Np, st)
+        rc = g.transh ? kge_run_l1h_score(g.bf16, b.Q32, b.W32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, b.A, b.P, g.Np, st, g.pn)
                       : kge_run_l1_score(g.bf16, b.Q32, b.T, g.B, g.N, g.Bp, g.Np, g.dp, b.S, g.Np, st);
         if (rc != KGE_OK) return rc;
         if ((rc = kge_run_l1_rowstat(b.S, g.Np, g.B, g.N, g.Bp, cfg->loss, cfg->gamma, cfg->adv_temp, b.stat_part, st)) != KGE_OK) return rc;
@@ -449,9 +454,9 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
                                 cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, have_block ? nullptr : loss_out, st)) != KGE_OK) return rc;
     if (have_block && g.l1 && g.transh) {
         if ((rc = kge_run_l1h_grad(g.bf16, true, b.Q32, b.W32, b.T, b.S, b.A, b.P, g.Np, b.rowinfo, g.B, g.N, g.Bp, g.Np, g.dp,
-                                   cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_q, b.accq, b.accq2, st)) != KGE_OK) return rc;
+                                   cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_q, b.accq, b.accq2, st, g.pn)) != KGE_OK) return rc;
         if ((rc = kge_run_l1h_grad(g.bf16, false, b.Q32, b.W32, b.T, b.S, b.A, b.P, g.Np, b.rowinfo, g.B, g.N, g.Np, g.Bp, g.dp,
-                                   cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_t, b.acct, nullptr, st)) != KGE_OK) return rc;
+                                   cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_t, b.acct, nullptr, st, g.pn)) != KGE_OK) return rc;
     } else if (have_block && g.l1) {
         // gradient rows of the queries and of the shared negatives from S and the finished row constants
         if ((rc = kge_run_l1_grad(g.bf16, true, b.Q32, b.T, b.S, g.Np, b.rowinfo, g.B, g.N, g.Bp, g.Np, g.dp, cfg->loss, cfg->gamma,

@@ -212,7 +212,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // unrounded fp32 rows.  Same tiling as above with 64 own rows per gradient workgroup (a 4 x 4 register tile; the
 // pass over the queries carries two accumulators, dq' and dw^).
 // ---------------------------------------------------------------------------------------------
-template <bool BF16>
+// PN = 2 runs the same three kernels for the 2-norm (rows too wide for the matrix-core TransH kernels): the distance sums
+// x_j^2, u = x / ||x|| (0 at distance 0), P = (x . w^) / ||x||; the gradient kernels fold 1 / ||x|| = -1 / S into the
+// weight of the pair and use x itself where the 1-norm has sign(x).
+template <bool BF16, int PN>
 __global__ __launch_bounds__(256) void l1h_score_kernel(const float *Q, const float *W, const void *T, int B, int N, int dp,
                                                         float *S, float *A, float *P, int64_t ldS) {
     __shared__ __attribute__((aligned(16))) float qs[L1_TILE * L1_PITCH], ws[L1_TILE * L1_PITCH], ts[L1_TILE * L1_PITCH];
@@ -265,8 +268,13 @@ __global__ __launch_bounds__(256) void l1h_score_kernel(const float *Q, const fl
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const float x = fmaf(a[i][k], w4[i][c], q4[i][c] - t4[k][c]);
-                        acc[i][k] += fabsf(x);
-                        pp[i][k] = fmaf(__builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f), w4[i][c], pp[i][k]);
+                        if constexpr (PN == 1) {
+                            acc[i][k] += fabsf(x);
+                            pp[i][k] = fmaf(__builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f), w4[i][c], pp[i][k]);
+                        } else {
+                            acc[i][k] = fmaf(x, x, acc[i][k]);
+                            pp[i][k] = fmaf(x, w4[i][c], pp[i][k]);
+                        }
                     }
         }
     }
@@ -277,8 +285,9 @@ __global__ __launch_bounds__(256) void l1h_score_kernel(const float *Q, const fl
         for (int k = 0; k < 4; ++k) {
             const int n = n0 + tx + 16 * k;
             if (b < B && n < N) {
-                S[(int64_t)b * ldS + n] = -acc[i][k];
-                if (A) { A[(int64_t)b * ldS + n] = a[i][k]; P[(int64_t)b * ldS + n] = pp[i][k]; }
+                const float dist = PN == 1 ? acc[i][k] : sqrtf(acc[i][k]);
+                S[(int64_t)b * ldS + n] = -dist;
+                if (A) { A[(int64_t)b * ldS + n] = a[i][k]; P[(int64_t)b * ldS + n] = PN == 1 ? pp[i][k] : (dist > 0.f ? pp[i][k] / dist : 0.f); }
             }
         }
     }
@@ -290,7 +299,7 @@ constexpr int L1H_GO = 64;             // own rows of a TransH gradient workgrou
 //        acc_part2 = dw^ = -sum_n (w P) t_n + (w A) u.
 // else:  own = 64 negatives, streamed = queries: acc_part = dt = sum_b w u - (w P) w^_b.
 // u = sign(x) = median(-1, x 2^100, 1) (a non-zero x of magnitude at least 2^-100 scales to at least 1).
-template <bool BF16, bool OWN_Q>
+template <bool BF16, bool OWN_Q, int PN>
 __global__ __launch_bounds__(256) void l1h_grad_kernel(const float *Q, const float *W, const void *T, const float *S,
                                                        const float *A, const float *P, int64_t ldS, const KgeRowInfo *rowinfo,
                                                        int B, int N, int own_pad, int dp, int chunks, int cps, int loss,
@@ -346,6 +355,7 @@ __global__ __launch_bounds__(256) void l1h_grad_kernel(const float *Q, const flo
                 if (loss == KGE_LOGSIGMOID) w *= l1_sigmoid(gamma + sc);
                 av = A[(int64_t)b * ldS + n];
                 pv = w * P[(int64_t)b * ldS + n];
+                if constexpr (PN == 2) w = sc < 0.f ? -w / sc : 0.f;    // u = x / ||x||: the pair's 1 / ||x|| rides on its weight
             }
             cw[sl * L1_PITCH + ol] = w; ca[sl * L1_PITCH + ol] = av; cp[sl * L1_PITCH + ol] = pv;
         }
@@ -363,7 +373,7 @@ __global__ __launch_bounds__(256) void l1h_grad_kernel(const float *Q, const flo
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const float x = fmaf(a4[i], o2[i][c], o1[i][c] - r1[c]);
-                        const float u = __builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f);
+                        const float u = PN == 1 ? __builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f) : x;
                         acc1[i][c] = fmaf(-w4[i], u, acc1[i][c]);
                         acc2[i][c] = fmaf(-p4[i], r1[c], fmaf(-wa, u, acc2[i][c]));
                     }
@@ -375,7 +385,7 @@ __global__ __launch_bounds__(256) void l1h_grad_kernel(const float *Q, const flo
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const float x = fmaf(a4[i], r2[c], r1[c] - o1[i][c]);
-                        const float u = __builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f);
+                        const float u = PN == 1 ? __builtin_amdgcn_fmed3f(x * L1_BIG, -1.f, 1.f) : x;
                         acc1[i][c] = fmaf(w4[i], u, fmaf(-p4[i], r2[c], acc1[i][c]));
                     }
             }
@@ -438,28 +448,32 @@ int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *s
 
 // TransH: scores (and, with A and P given, the two per-pair scalars that the gradient kernels need)
 int kge_run_l1h_score(bool bf16, const float *Q, const float *W, const void *T, int B, int N, int Bp, int Np, int dp, float *S,
-                      float *A, float *P, int64_t ldS, hipStream_t st) {
+                      float *A, float *P, int64_t ldS, hipStream_t st, int pn) {
     if (Bp % L1_TILE || Np % L1_TILE || dp % L1_TILE || (A == nullptr) != (P == nullptr)) return KGE_E_INVALID_ARG;
     if (Bp == 0 || Np == 0) return KGE_OK;
     if (Bp / L1_TILE > 65535) return KGE_E_UNSUPPORTED;
     KgeProfScope prof(KGE_PROF_BLOCK_SCORE, st);
     const dim3 grid(Np / L1_TILE, Bp / L1_TILE);
-    if (bf16) hipLaunchKernelGGL(l1h_score_kernel<true>, grid, dim3(256), 0, st, Q, W, T, B, N, dp, S, A, P, ldS);
-    else      hipLaunchKernelGGL(l1h_score_kernel<false>, grid, dim3(256), 0, st, Q, W, T, B, N, dp, S, A, P, ldS);
+#define L1H_SCORE(BF, PN) hipLaunchKernelGGL((l1h_score_kernel<BF, PN>), grid, dim3(256), 0, st, Q, W, T, B, N, dp, S, A, P, ldS)
+    if (bf16) { if (pn == 1) L1H_SCORE(true, 1); else L1H_SCORE(true, 2); }
+    else      { if (pn == 1) L1H_SCORE(false, 1); else L1H_SCORE(false, 2); }
+#undef L1H_SCORE
     return kge_launch_status();
 }
 
 int kge_run_l1h_grad(bool bf16, bool own_is_query, const float *Q, const float *W, const void *T, const float *S, const float *A,
                      const float *P, int64_t ldS, const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp,
-                     int loss, float gamma, float adv_temp, int nsplit, float *acc_part, float *acc_part2, hipStream_t st) {
+                     int loss, float gamma, float adv_temp, int nsplit, float *acc_part, float *acc_part2, hipStream_t st, int pn) {
     if (own_pad % L1H_GO || str_pad % L1_GS || dp % L1_GD) return KGE_E_INVALID_ARG;
     if (nsplit <= 0 || nsplit != kge_l1_nsplit(own_pad, str_pad, dp, true)) return KGE_E_INVALID_ARG;
     KgeProfScope prof(own_is_query ? KGE_PROF_BLOCK_FWD : KGE_PROF_BLOCK_GRADT, st);
     const int chunks = str_pad / L1_GS, cps = (chunks + nsplit - 1) / nsplit;
     const dim3 grid(own_pad / L1H_GO, dp / L1_GD, nsplit);
     if (grid.z > 65535 || grid.y > 65535) return KGE_E_UNSUPPORTED;
-#define L1H_GRAD(BF, OQ) hipLaunchKernelGGL((l1h_grad_kernel<BF, OQ>), grid, dim3(256), 0, st, Q, W, T, S, A, P, ldS, rowinfo, B, N, \
-                                            own_pad, dp, chunks, cps, loss, gamma, adv_temp, acc_part, acc_part2)
+#define L1H_GRAD(BF, OQ) do { if (pn == 1) hipLaunchKernelGGL((l1h_grad_kernel<BF, OQ, 1>), grid, dim3(256), 0, st, Q, W, T, S, A, P, ldS, rowinfo, B, N, \
+                                                                  own_pad, dp, chunks, cps, loss, gamma, adv_temp, acc_part, acc_part2); \
+                              else hipLaunchKernelGGL((l1h_grad_kernel<BF, OQ, 2>), grid, dim3(256), 0, st, Q, W, T, S, A, P, ldS, rowinfo, B, N, \
+                                                      own_pad, dp, chunks, cps, loss, gamma, adv_temp, acc_part, acc_part2); } while (0)
     if (bf16) { if (own_is_query) L1H_GRAD(true, true); else L1H_GRAD(true, false); }
     else      { if (own_is_query) L1H_GRAD(false, true); else L1H_GRAD(false, false); }
 #undef L1H_GRAD

@@ -6,6 +6,8 @@
 struct KgeModelDev {
     int32_t scorer, bf16, dim, rel_dim;
     int32_t p1;                    // distance scorers: 1 = the 1-norm variant (Table 2, p = 1)
+    int32_t vec;                   // the block passes ran on the vector pipe (1-norm; TransH rows over 512 bytes): their
+                                   // partials are finished gradient rows
     const void *ent, *rel, *relw;
     int64_t ent_ld, rel_ld, relw_ld;
 };
@@ -35,7 +37,7 @@ int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipSt
 int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma,
                       float c_corr, float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb,
                       float *gpos, float *loss_out, hipStream_t st);     // loss_out null: the rows' losses are not summed here
-// m.p1: acc_part holds finished gradient rows (coefficients already normalised), sum_part / stat_part are not read
+// m.vec: acc_part holds finished gradient rows (coefficients already normalised), sum_part / stat_part are not read
 int kge_run_chain(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp, int dp,
                   const float *acc_part, const float *acc_part2, const float4 *sum_part, const float4 *stat_part,
                   const KgeRowInfo *rowinfo, int nsplit, const float *gpos, float *g_ent, float *g_rel,
@@ -67,7 +69,8 @@ int kge_run_l1_grad(bool bf16, bool own_is_query, const void *own, const void *s
 // TransH under the 1-norm: Q, W = unrounded queries q' and unit normals [Bp][dp]; A = w^ . t and P = sign(x) . w^ per
 // pair beside S (both nullptr: scores only); the pass over the queries also fills acc_part2 with the gradient of w^
 int kge_run_l1h_score(bool bf16, const float *Q, const float *W, const void *T, int B, int N, int Bp, int Np, int dp, float *S,
-                      float *A, float *P, int64_t ldS, hipStream_t st);
+                      float *A, float *P, int64_t ldS, hipStream_t st, int pn = 1);   // pn: the norm (1, or 2 for wide TransH rows)
 int kge_run_l1h_grad(bool bf16, bool own_is_query, const float *Q, const float *W, const void *T, const float *S, const float *A,
                      const float *P, int64_t ldS, const KgeRowInfo *rowinfo, int B, int N, int own_pad, int str_pad, int dp,
-                     int loss, float gamma, float adv_temp, int nsplit, float *acc_part, float *acc_part2, hipStream_t st);
+                     int loss, float gamma, float adv_temp, int nsplit, float *acc_part, float *acc_part2, hipStream_t st,
+                     int pn = 1);

@@ -434,9 +434,9 @@ __device__ __forceinline__ void kge_chain_body(int blk, const KgeChainArgs &a) {
     // the row pass leaves, per split, sums of UNNORMALISED weights relative to that split's running
     // maximum m_s; exp2(m_s + K) turns them into gradient coefficients
     const float K2 = rowinfo[b].K;
-    // (the 1-norm kernels apply the finished coefficients themselves: their partials are summed as they are)
+    // (the vector-pipe kernels apply the finished coefficients themselves: their partials are summed as they are)
     auto kappa = [&](int s) {
-        if (m.p1) return 1.f;
+        if (m.vec) return 1.f;
         const float ms = stat_part[(size_t)s * Bp + b].x;
         return ms > -INFINITY ? exp2f(ms + K2) : 0.f;
     };
@@ -460,7 +460,7 @@ __device__ __forceinline__ void kge_chain_body(int blk, const KgeChainArgs &a) {
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u < nsplit ? s0 + u : nsplit - 1;      // past the end: the last split again, weight 0
             kap[u] = s0 + u < nsplit ? kappa(s) : 0.f;
-            p[u] = m.p1 ? make_float4(0.f, 0.f, 0.f, 0.f) : sum_part[(size_t)s * Bp + b];
+            p[u] = m.vec ? make_float4(0.f, 0.f, 0.f, 0.f) : sum_part[(size_t)s * Bp + b];
 #pragma unroll
             for (int k = 0; k < KGE_MAXJ; ++k) {
                 v1[u][k] = v2[u][k] = 0.f;
@@ -509,8 +509,8 @@ __device__ __forceinline__ void kge_chain_body(int blk, const KgeChainArgs &a) {
                 dq[k] -= s2 * cx.w[k];
                 dtp[k] = -(apu - aw * cx.w[k]);
                 // gradient with respect to the unit normal: negatives' part + positive's part
-                // (1-norm: a2 is the finished negatives' part, the sums s1..s3 are zero)
-                dwh[k] = (m.p1 ? 0.f : -cq * a1[k]) - s2 * cx.q[k] + a2[k] - s3 * cx.w[k] + aw * tv[k] + wt * apu;
+                // (vector-pipe kernels: a2 is the finished negatives' part, the sums s1..s3 are zero)
+                dwh[k] = (m.vec ? 0.f : -cq * a1[k]) - s2 * cx.q[k] + a2[k] - s3 * cx.w[k] + aw * tv[k] + wt * apu;
             }
         }
     }

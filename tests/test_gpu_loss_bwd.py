@@ -61,6 +61,16 @@ def test_other_row_sizes(orc, scorer, dim, bf16):
     _compare(orc, scorer, "logsigmoid", G, bf16, 3000)
 
 
+@pytest.mark.parametrize("dim,bf16,B,N", [(256, False, 150, 260), (512, True, 150, 260), (192, False, 700, 1500)])
+def test_transh_rows_wider_than_512_bytes(orc, dim, bf16, B, N):
+    """TransH at d = 256 in fp32 (one of the sizes of Table 3) and wider: 1,024-byte rows train on the vector-pipe route
+    with the 2-norm (score block in memory); several tiles and ragged tails in the third case."""
+    G = make_case("transh", 3000, 9, dim, B, N, bf16, amp=0.1, zipf=True)
+    _compare(orc, "transh", "sampled_softmax", G, bf16, 3000)
+    _compare(orc, "transh", "logsigmoid", G, bf16, 3000)
+    _compare(orc, "transh", "logsigmoid", G, bf16, 3000, kw=dict(gamma=3.0, adv_temp=0.0, reg_l3=1e-3))
+
+
 @pytest.mark.parametrize("scorer", ["transe", "complex"])
 def test_edge_shapes(orc, scorer):
     for (B, N) in [(1, 1), (3, 0), (130, 1), (1, 130)]:
