@@ -148,16 +148,8 @@ class TrainWorkload:
             self.loss_kw = dict(n_ent_for_c=self.n_ent)
         if reg_l3 > 0.0:
             self.loss_kw["reg_l3"] = reg_l3
-        self.side = torch.cuda.Stream()
         self.main = torch.cuda.current_stream()
-        self.ev_ids, self.ev_plan, self.ev_grad, self.ev_rel = (torch.cuda.Event() for _ in range(4))
         self.eager_now = False
-        self.prepared = -1
-        self.ev_plan2 = [torch.cuda.Event() for _ in range(2)]
-        self.ev_neg = [torch.cuda.Event() for _ in range(2)]
-        self.ev_bwd, self.ev_done = torch.cuda.Event(), torch.cuda.Event()
-        self.ev_done.record()
-        self.ws_ent2, self.ws_rel2, self.ws_relw2 = ([kge.Workspace() for _ in range(2)] for _ in range(3))
         self.ws_ent, self.ws_rel, self.ws_relw = kge.Workspace(), kge.Workspace(), kge.Workspace()
         self.enc = None
         if feat_dim > 0:
@@ -215,7 +207,7 @@ class TrainWorkload:
                 elif not self.eager_now:
                     self.graphs[i % len(self.batches)].replay()
                 else:
-                    self._enqueue(i % len(self.batches), self.main, self.side)
+                    self._enqueue(i % len(self.batches), self.main)
                 return
             h, r, t, lo, hi, _ = self.batches[i % len(self.batches)]
             kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=self.neg, stream=self.main)
@@ -238,79 +230,43 @@ class TrainWorkload:
             kge.sparse_adam(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_rel_idx"],
                             self.out["g_relw"], lr, step=i + 1)
 
-    def _prepare(self, i, side):
-        """What step i needs of its row ids alone, on the second stream: the shared negatives, drawn into the tail of the
-        step's id array [h | t | negatives], and the sorts of the sparse updates (kge_sparse_adam_plan)."""
-        kge, ks = self.kge, self.ks
-        h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
-        p = i % 2
-        kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=ids[2 * self.B:], stream=side)
-        self.ev_neg[p].record(side)
-        kge.sparse_adam_plan(self.n_ent, self.d, ids, self.ws_ent2[p], stream=side)
-        kge.sparse_adam_plan(self.n_rel, self.rel.shape[1], r, self.ws_rel2[p], stream=side)
+    def _tables(self):
+        """(plans, updates) of the step's tables for kge_sparse_adam_plan_tables / kge_sparse_adam_apply_tables."""
+        t = [(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent),
+             (self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel)]
         if self.relw is not None:
-            kge.sparse_adam_plan(self.n_rel, self.d, r, self.ws_relw2[p], stream=side)
-        self.ev_plan2[p].record(side)
-        self.prepared = i
+            t.append((self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"], self.ws_relw))
+        return t
 
     def _step_call_by_call(self, i):
-        """One step, software-pipelined over two streams.  The main stream holds the chain gather -> forward -> backward ->
-        update.  Everything that depends on the row ids alone (negatives, sorts) belongs to the NEXT step and runs on the
-        second stream while this step's update runs: the update is bound by memory traffic and leaves room for a few small
-        workgroups, whereas the forward and backward kernels need every compute unit at once and are held up by any
-        workgroup that sits on one.  The events the main stream waits for were recorded most of a step earlier."""
-        kge = self.kge
-        main, side = self.main, self.side
-        if self.prepared != i:                           # first step, or a jump in the step numbers
-            side.wait_event(self.ev_done)
-            self._prepare(i, side)
+        """One step on ONE stream: negatives -> the sorts of the step's row ids (every table in one launch) -> gather,
+        forward, backward -> the update of every table (two launches).  (A second stream for the sorts, which need the ids
+        alone, was measured and lost: each cross-stream wait costs the waiting stream about 10 us on this stack, and small
+        kernels that share the chip with the forward or backward kernel hold up a workgroup of theirs.)"""
+        kge, ks = self.kge, self.ks
+        main = self.main
         h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
-        p, lr = i % 2, self.P["lr"]
-        main.wait_event(self.ev_neg[p])
-        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main, **self.loss_kw)
-        self.ev_bwd.record(main)
-        main.wait_event(self.ev_plan2[p])
-        tables = [(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent2[p]),
-                  (self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel2[p])]
+        kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=ids[2 * self.B:], stream=main)
+        plans = [(self.n_ent, self.d, ids, self.ws_ent), (self.n_rel, self.rel.shape[1], r, self.ws_rel)]
         if self.relw is not None:
-            tables.append((self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"], self.ws_relw2[p]))
-        kge.sparse_adam_apply_tables(tables, lr, step=i + 1, stream=main)     # every table of the step in two launches
-        self.ev_done.record(main)
-        side.wait_event(self.ev_bwd)                     # (the sort buffers of step i + 1 were last read by step i - 1)
-        self._prepare(i + 1, side)
+            plans.append((self.n_rel, self.d, r, self.ws_relw))
+        kge.sparse_adam_plan_tables(plans, stream=main)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main, **self.loss_kw)
+        kge.sparse_adam_apply_tables(self._tables(), self.P["lr"], step=i + 1, stream=main)
 
-    def _enqueue(self, k, main, side):
-        """One step on pre-drawn batch k, in a form that a HIP graph can record.  The row ids of the step are known as soon as the negatives are drawn: the sorts
-        that the sparse updates need run on a second stream beside the forward / backward kernels (kge_sparse_adam_plan),
-        the updates themselves follow the gradients (kge_sparse_adam_apply), the entity table on the main stream, the small
-        relation tables beside it; the second stream joins the main one before the step counter advances.  The library
-        calls take their stream as an argument (no stream context is entered on the host) and only launch kernels, so the
-        same function serves the call-by-call step and the capture of the graph."""
+    def _enqueue(self, k, main):
+        """The same step on pre-drawn batch k in a form that a HIP graph can record: the step number of the negatives and
+        of Adam comes from the counter in device memory, which the last node advances."""
         kge, ks = self.kge, self.ks
         h, r, t, lo, hi, ids = self.batches[k]
-        lr, c = self.P["lr"], self.counter
-        neg = ids[2 * self.B:]
-        kge.sample_negatives_dev(ks.BASE_SEED, c, 0, ks.TAG_NEG, lo, hi, self.N, out=neg, stream=main)
-        self.ev_ids.record(main)
-        side.wait_event(self.ev_ids)
-        kge.sparse_adam_plan(self.n_ent, self.d, ids, self.ws_ent, stream=side)
-        kge.sparse_adam_plan(self.n_rel, self.rel.shape[1], r, self.ws_rel, stream=side)
+        c = self.counter
+        kge.sample_negatives_dev(ks.BASE_SEED, c, 0, ks.TAG_NEG, lo, hi, self.N, out=ids[2 * self.B:], stream=main)
+        plans = [(self.n_ent, self.d, ids, self.ws_ent), (self.n_rel, self.rel.shape[1], r, self.ws_rel)]
         if self.relw is not None:
-            kge.sparse_adam_plan(self.n_rel, self.d, r, self.ws_relw, stream=side)
-        self.ev_plan.record(side)
-        kge.loss_bwd(self.model, self.P["loss"], h, r, t, neg, out=self.out, stream=main, **self.loss_kw)
-        self.ev_grad.record(main)
-        main.wait_event(self.ev_plan)
-        kge.sparse_adam_apply(self.ent, self.ent_sh, self.ent_m, self.ent_v, self.out["g_ent"], self.ws_ent, lr,
-                              step=1, stream=main, step_counter=c)
-        side.wait_event(self.ev_grad)
-        kge.sparse_adam_apply(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel"], self.ws_rel, lr,
-                              step=1, stream=side, step_counter=c)
-        if self.relw is not None:
-            kge.sparse_adam_apply(self.relw, self.relw_sh, self.relw_m, self.relw_v, self.out["g_relw"],
-                                  self.ws_relw, lr, step=1, stream=side, step_counter=c)
-        self.ev_rel.record(side)
-        main.wait_event(self.ev_rel)
+            plans.append((self.n_rel, self.d, r, self.ws_relw))
+        kge.sparse_adam_plan_tables(plans, stream=main)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main, **self.loss_kw)
+        kge.sparse_adam_apply_tables(self._tables(), self.P["lr"], step=1, stream=main, step_counter=c)
         kge.step_counter_add(c, 1, stream=main)
 
     def capture(self):
@@ -319,13 +275,13 @@ class TrainWorkload:
         torch = self.torch
         if self.enc is not None or self.sampler is not None:
             return
-        self._enqueue(0, self.main, self.side)
+        self._enqueue(0, self.main)
         torch.cuda.synchronize()
         self.graphs = []
         for k in range(len(self.batches)):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
-                self._enqueue(k, torch.cuda.current_stream(), self.side)
+                self._enqueue(k, torch.cuda.current_stream())
             self.graphs.append(g)
         torch.cuda.synchronize()
 
@@ -774,7 +730,7 @@ def main():
         line["hbm_kernels"] = hbm
     if isinstance(wl, TrainWorkload):
         line["enqueue"] = ("HIP graph replay, one graph per pre-drawn batch; every 4th step call by call with the HIP-event bracket"
-                           if graphed else "call by call; the next step's negatives and sorts on a second stream beside the update")
+                           if graphed else "call by call, one stream, 9 launches per step")
     line.update(wl.extra(ms))
     if enc_roof:
         line["encoder_roofline"] = enc_roof

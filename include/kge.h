@@ -205,6 +205,14 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
  * the tables must not overlap; tables with M = 0 are skipped.
  */
 typedef struct {
+    int64_t n_rows; int32_t dim; const int32_t *idx; int64_t M;   /* as in kge_sparse_adam_plan */
+    void *ws; size_t ws_bytes;
+} kge_adam_plan_t;
+/* kge_sparse_adam_plan for several tables (1 <= n_tables <= 4), each into its own workspace; the sorts of up to 32,768 ids
+ * share one launch.  Same result in every workspace as one kge_sparse_adam_plan per table. */
+int kge_sparse_adam_plan_tables(const kge_adam_plan_t *plans, int32_t n_tables, void *hip_stream);
+
+typedef struct {
     float *param_f32; void *param_bf16; float *m, *v;      /* as in kge_sparse_adam */
     int64_t n_rows; int32_t dim; int64_t ld;
     const float *grads; int64_t M;
@@ -431,10 +439,13 @@ int kge_calibrate_copy(const void *src, void *dst, size_t bytes, double *gbs_out
  *   KGE_DEBUG_GRADT_ONE_ROLE  the same for the pass over the negatives
  *   KGE_DEBUG_SCORE_F32_MFMA  kge_score on fp32 tables with the fp32 matrix instructions instead of two fp16 planes
  *   KGE_DEBUG_TWO_ROLE        both of those passes as the two-role kernels (the forward one is also what redoes a pass
- *                             whose scores outgrow the delayed reference exponent of the default kernel)
+ *                             whose scores outgrow the fixed reference exponent of the default kernel)
+ *   KGE_DEBUG_GRADT_RECOMPUTE the pass over the negatives recomputes the scores also where the forward pass has kept its
+ *                             weights for it (sampled softmax, bilinear scorers, bf16 rows of 512 bytes)
  * Returns KGE_E_INVALID_ARG for an unknown knob or a value other than 0 / 1.
  */
-enum { KGE_DEBUG_FWD_ONE_ROLE = 0, KGE_DEBUG_GRADT_ONE_ROLE = 1, KGE_DEBUG_SCORE_F32_MFMA = 2, KGE_DEBUG_TWO_ROLE = 3 };
+enum { KGE_DEBUG_FWD_ONE_ROLE = 0, KGE_DEBUG_GRADT_ONE_ROLE = 1, KGE_DEBUG_SCORE_F32_MFMA = 2, KGE_DEBUG_TWO_ROLE = 3,
+       KGE_DEBUG_GRADT_RECOMPUTE = 4 };
 int kge_debug_select(int knob, int value);
 
 /* Static description of a status code. */

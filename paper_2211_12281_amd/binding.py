@@ -22,7 +22,7 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit", "kge_debug_select",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
            "kge_calibrate_mfma", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev",
-           "kge_sparse_adam_apply_tables"]
+           "kge_sparse_adam_apply_tables", "kge_sparse_adam_plan_tables"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7, "gather": 8, "finish": 9}
 
@@ -49,6 +49,11 @@ class KgeLossCfgT(C.Structure):
 class KgeAdamCfgT(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("step", C.c_int64), ("step_counter", C.c_void_p)]
+
+
+class KgeAdamPlanT(C.Structure):
+    _fields_ = [("n_rows", C.c_int64), ("dim", C.c_int32), ("idx", C.c_void_p), ("M", C.c_int64), ("ws", C.c_void_p),
+                ("ws_bytes", C.c_size_t)]
 
 
 class KgeAdamTableT(C.Structure):
@@ -89,6 +94,7 @@ def load():
         lib.kge_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.kge_status_string.restype = C.c_char_p
         lib.kge_status_string.argtypes = [C.c_int]
+        lib.kge_sparse_adam_plan_tables.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         lib.kge_sparse_adam_apply_tables.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         lib.kge_step_counter_add.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
         lib.kge_sample_negatives_dev.argtypes = [C.c_uint64, C.c_void_p, C.c_uint64, C.c_uint32, C.c_int64, C.c_int64, C.c_int64,
@@ -319,6 +325,16 @@ def sparse_adam_apply(param, shadow, m, v, grads, ws: Workspace, lr: float, beta
            "kge_sparse_adam_apply")
 
 
+def sparse_adam_plan_tables(plans, stream=None):
+    """kge_sparse_adam_plan_tables: plans = [(n_rows, dim, idx, ws), ...]; the sorts of up to 32,768 ids share one launch."""
+    arr = (KgeAdamPlanT * len(plans))()
+    for a, (n_rows, dim, idx, ws) in zip(arr, plans):
+        M = idx.numel()
+        buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, dim))
+        a.n_rows, a.dim, a.idx, a.M, a.ws, a.ws_bytes = n_rows, dim, _ptr(_i32(idx)), M, _ptr(buf), buf.numel()
+    _check(load().kge_sparse_adam_plan_tables(arr, len(plans), _stream(stream)), "kge_sparse_adam_plan_tables")
+
+
 def sparse_adam_apply_tables(tables, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, step: int = 1,
                              stream=None, step_counter=None):
     """kge_sparse_adam_apply_tables: tables = [(param, shadow, m, v, grads, ws), ...], each planned into its own ws."""
@@ -360,7 +376,7 @@ def ensemble(lists, p: float, K_out: int = 10):
     return out_idx, out_score
 
 
-DEBUG_KNOBS = {"fwd_one_role": 0, "gradt_one_role": 1, "score_f32_mfma": 2, "two_role": 3}
+DEBUG_KNOBS = {"fwd_one_role": 0, "gradt_one_role": 1, "score_f32_mfma": 2, "two_role": 3, "gradt_recompute": 4}
 
 
 def debug_select(knob: str, value: bool):

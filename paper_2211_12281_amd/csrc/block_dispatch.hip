@@ -27,12 +27,15 @@ bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
 }
 
 // Bilinear scorers in these configurations run the kernel of block_sym.hip (64 own rows per pair of waves): the pass over
-// the negatives with both losses, the pass over the queries with the sampled softmax.  The two-role kernels serve the
-// distance scorers and the log-sigmoid forward pass, redo a forward pass whose scores outgrow the fixed reference of
-// the other kernel, and stand in for it in comparisons (KGE_KNOB_TWO_ROLE).
+// the negatives with both losses, the pass over the queries with the sampled softmax (whose weights it keeps, so that the
+// pass over the negatives of that loss is the contraction of block_gradp.hip).  The two-role kernels serve the distance
+// scorers and the log-sigmoid forward pass, and stand in for the others in comparisons (KGE_KNOB_TWO_ROLE).
 bool kge_sym_applies(bool bf16, int rb, bool transh, int dsplit) {
     return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_FWD_ONE_ROLE) && !kge_knob(KGE_KNOB_GRADT_ONE_ROLE) &&
            !kge_knob(KGE_KNOB_TWO_ROLE);
+}
+bool kge_gradp_applies(bool bf16, int rb, bool transh, int dsplit, int kind) {
+    return kge_sym_applies(bf16, rb, transh, dsplit) && kind == KGE_KIND_MULT && !kge_knob(KGE_KNOB_GRADT_RECOMPUTE);
 }
 static bool sym_serves(int mode, int kind, int loss) {
     return kind == KGE_KIND_MULT && (mode == KGE_MODE_GRADT || loss == KGE_SAMPLED_SOFTMAX);
@@ -43,23 +46,18 @@ bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit) {
     return bf16 && rb == 512 && !transh && dsplit == 1 && !kge_knob(KGE_KNOB_GRADT_ONE_ROLE);
 }
 
-// (The optional event bracket of a pass lies around its block kernel alone: the gated second launch of a forward pass,
-// which exits at once unless the first kernel asked for it, follows the bracket.)
 int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
                      int own_tiles, int nsplit, hipStream_t st) {
     const int slot = mode == KGE_MODE_SCORE ? KGE_PROF_BLOCK_SCORE : mode == KGE_MODE_FWD ? KGE_PROF_BLOCK_FWD : KGE_PROF_BLOCK_GRADT;
-    if (mode == KGE_MODE_FWD && kge_sym_applies(bf16, rb, transh, dsplit) && sym_serves(mode, kind, loss)) {
-        int rc;
-        {
-            KgeProfScope prof(slot, st);
-            rc = kge_launch_fwd_sym(kind, loss, a, own_tiles, nsplit, st);
-        }
-        if (rc != KGE_OK) return rc;
-        KgeBlockArgs b = a;                                  // redone only if the first kernel raised the flag
-        b.gate = a.flag;
-        return kge_launch_fwd_pp(kind, loss, b, own_tiles, nsplit, st);
-    }
     KgeProfScope prof(slot, st);
+    if (mode == KGE_MODE_FWD && kge_sym_applies(bf16, rb, transh, dsplit) && sym_serves(mode, kind, loss))
+        return kge_launch_fwd_sym(kind, loss, a, own_tiles, nsplit, st);
+    if (mode == KGE_MODE_GRADT && loss == KGE_SAMPLED_SOFTMAX && a.pstore && kge_gradp_applies(bf16, rb, transh, dsplit, kind)) {
+        // the forward pass kept its weights: no scores are recomputed
+        KgeBlockArgs b = a;
+        b.str = a.str2; b.str2 = nullptr;                    // the queries scaled per forward split
+        return kge_launch_gradp(b, own_tiles, nsplit, st);
+    }
     if (mode == KGE_MODE_SCORE)
         return bf16 ? kge_launch_block_bf16_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st)
                     : kge_launch_block_f32_score(rb, mode, transh, kind, 0, dsplit, a, own_tiles, nsplit, st);

@@ -81,7 +81,6 @@ void kge_pp_kernel(const KgeBlockArgs a) {
     if (a.xcd_per == 1) { own_tile = kk % a.own_tiles; split = xcd + 8 * (kk / a.own_tiles); }
     else { split = xcd / a.xcd_per; own_tile = kk * a.xcd_per + xcd % a.xcd_per; }
     if (own_tile >= a.own_tiles || split >= a.nsplit) return;
-    if (a.gate && *a.gate == 0) return;                     // a guarded launch: only if the kernel before it asked for it
     const int oidx = own_tile * 128 + pair * 32 + lr;       // the pair's own row of this lane
     const int str_limit = FWD ? a.N : a.B;                  // valid stream rows
     const int t0 = split * a.tiles_per_split;

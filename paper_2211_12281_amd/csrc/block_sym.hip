@@ -29,9 +29,9 @@
 // workgroup's first tile over both waves (exchanged through the LDS once).  It is never raised: the weights of later
 // tiles may exceed 1, which costs nothing while they stay finite.  A score that exceeds the reference by more than about
 // 2^SY_GUARD (69 in natural units) cannot be handled this way: when a lane's sum of weights ends above 2^SY_GUARD (or is
-// not a number), the wave sets *a.flag and the host side runs the pass again with the kernel of block_fwd_pp.hip, which
-// raises its reference as it goes.  (The check is on the sums at the end, not on every score: a weight that overflowed
-// leaves an infinite sum, and a sum below 2^SY_GUARD bounds every weight.)
+// not a number), the workgroup does its pass a second time, the reference now being the exact maximum of every row over
+// the whole split (one more walk over the tiles finds it).  (The check is on the sums at the end, not on every score: a
+// weight that overflowed leaves an infinite sum, and a sum below 2^SY_GUARD bounds every weight.)
 #include "block_kernel.hpp"
 
 int kge_launch_fwd_sym(int kind, int loss, const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
@@ -151,7 +151,6 @@ void kge_sym_kernel(const KgeBlockArgs a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc2[blk][ob][i] = 0.f;
     float ref[2] = {-INFINITY, -INFINITY}, st_l[2] = {0.f, 0.f};
-    bool guard = false;                                     // FWD: a score outgrew what the fixed reference can carry
 
     // phase 1 fragments: row m of the contraction is row 32 sh + pi(m) of the tile
     int frag_off[8];
@@ -226,6 +225,25 @@ void kge_sym_kernel(const KgeBlockArgs a) {
     };
     using yes = std::true_type;
     using no = std::false_type;
+    // FWD: the coefficients of tile t (exp2 of the score's exponent less the reference, bf16) go to memory as the wave holds
+    // them, for the pass over the negatives: 4 KB per wave and tile.  They are stored at the START of the next round (from
+    // the registers that phase 2 still reads), so that the wait for the ring's copies at the top of a round finds the
+    // stores of the round before long finished.
+    auto store_coefs = [&](int t, const uint4 (&pc)[2][2]) {
+        if constexpr (FWD) {
+            if (a.pstore) {
+                char *dst = (char *)a.pstore + ((((size_t)own_tile * a.ps_nsplit + split) * a.ps_rounds + (t - t0)) * 4 + wave) * 4096 + lane * 16;
+#pragma unroll
+                for (int ob = 0; ob < 2; ++ob)
+#pragma unroll
+                    for (int f = 0; f < 2; ++f) {           // (read once, much later: no reason to keep it in the caches)
+                        typedef unsigned sy_u32x4 __attribute__((ext_vector_type(4)));
+                        const sy_u32x4 v = { pc[ob][f].x, pc[ob][f].y, pc[ob][f].z, pc[ob][f].w };
+                        __builtin_nontemporal_store(v, (sy_u32x4 *)(dst + ob * 2048 + f * 1024));
+                    }
+            }
+        }
+    };
 
     // One round.  Tile t (ring slot `slot`) gets its scores and its coefficients; tile t - 1 its phase 2.  The order
     // keeps the matrix pipe fed while everything else is in flight:
@@ -250,6 +268,7 @@ void kge_sym_kernel(const KgeBlockArgs a) {
         for (int k = 0; k < 8; ++k) av[k] = *(const uint4 *)(stage + frag_off[k]);
         if constexpr (!FWD) load_side(slot);
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (P2) store_coefs(t - 1, pown);
         // ---- A ----
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
@@ -335,35 +354,82 @@ void kge_sym_kernel(const KgeBlockArgs a) {
             for (int f = 0; f < 2; ++f) pown[ob][f] = pnew[ob][f];
     };
 
-    if (work) {
+    // FWD: a pass whose weights outgrow the first tile's reference (see the head of the file) is done a second time, with the
+    // exact row maxima of the whole split as reference - nothing can overflow then.  The decision is the workgroup's.
+    for (int attempt = 0; work && attempt < (FWD ? 2 : 1); ++attempt) {
         kge_f32x16 accs[2];
         uint4 trf[8], pown[2][2];
+        if constexpr (FWD) {
+            if (attempt == 1) {
+                // (rare, and written for brevity, not speed: one tile in flight at a time)
+                float tm[2] = {-INFINITY, -INFINITY};
+                for (int t = t0; t < t1; ++t) {
+                    __syncthreads();                        // everyone is done with stage 0
+                    issue(t, 0);
+                    kge_wait_vmcnt<0>();
+                    __syncthreads();
+                    load_side(0);
+#pragma unroll
+                    for (int ob = 0; ob < 2; ++ob) {
+                        kge_f32x16 acc;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[i] = side_k[i];
+#pragma unroll
+                        for (int k = 0; k < SY_KS; ++k)
+                            acc = kge_mma16<true>(acc, *(const uint4 *)(lds + frag_off[k & 7] + 256 * (k >> 3)), own[ob][k]);
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) tm[ob] = fmaxf(tm[ob], acc[i] * xscale);
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int ob = 0; ob < 2; ++ob) {
+                    tm[ob] = sy_max_halves(tm[ob]);
+                    *(float *)(post_base + wave * 256 + (32 * ob + lr) * 4) = tm[ob];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int ob = 0; ob < 2; ++ob) {
+                    ref[ob] = fmaxf(tm[ob], *(const float *)(post_base + partner * 256 + (32 * ob + lr) * 4));
+                    st_l[ob] = 0.f;
+                }
+#pragma unroll
+                for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+                    for (int ob = 0; ob < 2; ++ob)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc2[blk][ob][i] = 0.f;
+                __syncthreads();
+            }
+        }
         issue(t0, 0);
         kge_wait_vmcnt<0>();
         __syncthreads();                                    // tile t0 has landed
         if constexpr (FWD) {
-            // the reference starts as the exact maximum of the first tile over both waves of the pair
-            const char *stage = lds;
-            load_side(0);                                   // (0 / -inf of the tile's rows)
-            float tm[2];
+            if (attempt == 0) {
+                // the reference starts as the exact maximum of the first tile over both waves of the pair
+                const char *stage = lds;
+                load_side(0);                               // (0 / -inf of the tile's rows)
+                float tm[2];
 #pragma unroll
-            for (int ob = 0; ob < 2; ++ob) {
-                kge_f32x16 acc;
+                for (int ob = 0; ob < 2; ++ob) {
+                    kge_f32x16 acc;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = side_k[i];
+                    for (int i = 0; i < 16; ++i) acc[i] = side_k[i];
 #pragma unroll
-                for (int k = 0; k < SY_KS; ++k)
-                    acc = kge_mma16<true>(acc, *(const uint4 *)(stage + frag_off[k & 7] + 256 * (k >> 3)), own[ob][k]);
-                tm[ob] = -INFINITY;
+                    for (int k = 0; k < SY_KS; ++k)
+                        acc = kge_mma16<true>(acc, *(const uint4 *)(stage + frag_off[k & 7] + 256 * (k >> 3)), own[ob][k]);
+                    tm[ob] = -INFINITY;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) tm[ob] = fmaxf(tm[ob], acc[i] * xscale);
-                tm[ob] = sy_max_halves(tm[ob]);
-                *(float *)(post_base + wave * 256 + (32 * ob + lr) * 4) = tm[ob];
+                    for (int i = 0; i < 16; ++i) tm[ob] = fmaxf(tm[ob], acc[i] * xscale);
+                    tm[ob] = sy_max_halves(tm[ob]);
+                    *(float *)(post_base + wave * 256 + (32 * ob + lr) * 4) = tm[ob];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int ob = 0; ob < 2; ++ob)
+                    ref[ob] = fmaxf(tm[ob], *(const float *)(post_base + partner * 256 + (32 * ob + lr) * 4));
             }
-            __syncthreads();
-#pragma unroll
-            for (int ob = 0; ob < 2; ++ob)
-                ref[ob] = fmaxf(tm[ob], *(const float *)(post_base + partner * 256 + (32 * ob + lr) * 4));
         }
         round(no{}, t0, 0, accs, trf, pown);
         for (int t = t0 + 1; t < t1; ++t) {
@@ -382,6 +448,7 @@ void kge_sym_kernel(const KgeBlockArgs a) {
         kge_wait_vmcnt<0>();                                // no copy may be in flight when the LDS is released
         __syncthreads();
         // phase 2 of the last tile
+        store_coefs(t1 - 1, pown);
         {
             const int pslot = t1 - 1 - t0;
             const char *xs = lds + (pslot % SY_NSTAGE) * SY_STAGE;
@@ -403,8 +470,7 @@ void kge_sym_kernel(const KgeBlockArgs a) {
         }
         if constexpr (FWD) {
             const float lim = __builtin_amdgcn_ldexpf(1.f, (int)SY_GUARD);
-            guard = __any(!(st_l[0] <= lim) || !(st_l[1] <= lim));
-            if (guard && lane == 0) atomicOr(a.flag, 1);    // a score outgrew the fixed reference: the pass is redone
+            if (!__syncthreads_or(!(st_l[0] <= lim) || !(st_l[1] <= lim))) break;
         }
     }
 
@@ -443,7 +509,7 @@ int sym_launch(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st)
     if (lds_limit.set((const void *)kern, LDS) != KGE_OK) return KGE_E_HIP;
     // the caller's geometry must match: 128 own rows per workgroup, stream tiles counted in 32 rows, an even number per split
     if ((int64_t)own_tiles * 128 != a.own_pad || a.dp != SY_DP || (a.tiles_per_split & 1) || (a.str_tiles & 1)) return KGE_E_INVALID_ARG;
-    if (MODE == KGE_MODE_FWD && (!a.flag || !a.str_bias)) return KGE_E_INVALID_ARG;
+    if (MODE == KGE_MODE_FWD && !a.str_bias) return KGE_E_INVALID_ARG;
     KgeBlockArgs b = a;
     b.own_tiles = own_tiles; b.nsplit = nsplit;
     int groups;

@@ -12,6 +12,7 @@ int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void
 int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
                               const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st);
 int kge_run_sparse_adam_apply_tables(const kge_adam_table_t *tb, int n, const kge_adam_cfg_t &cfg, hipStream_t st);
+int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st);
 int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, int64_t Q, int64_t lo, int64_t hi,
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
@@ -106,7 +107,10 @@ Geometry make_geometry(const kge_model_t &m, int64_t B, int64_t N, bool train = 
         nsplit = (str_tiles + tps - 1) / tps;
     };
     const int gran = kge_sym_applies(g.bf16, g.rb, g.transh, g.dsplit_q) ? 2 : 1;
-    split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_FWD), gran);
+    // (where the forward pass keeps its weights for the pass over the negatives, a forward split holds whole own tiles of
+    // that pass: 128 negatives = four stream tiles)
+    split(g.own_tiles_b, g.str_tiles_n, g.nsplit_q, g.tps_q, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_FWD),
+          kge_gradp_applies(g.bf16, g.rb, g.transh, g.dsplit_q, g.kind) ? 4 : gran);
     split(g.own_tiles_n, g.str_tiles_b, g.nsplit_t, g.tps_t, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_GRADT), gran);
     split(g.own_tiles_s, g.str_tiles_b, g.nsplit_s, g.tps_s, kge_block_occ(g.bf16, g.rb, g.transh, KGE_MODE_SCORE), 1);
     g.dsplit_q = (g.bf16 && (g.rb == 1024 || g.transh)) ? 2 : 1;
@@ -145,8 +149,9 @@ struct Buffers {
     float *W32, *A, *P;                // ... TransH: the unit normals unrounded, w^ . t and sign(x) . w^ per pair [Bp][Np]
     void *Qp2, *Tp2;                   // score-only calls on fp32 tables: two fp16 planes of the scaled Q (TransH: and of W) and T
     float *t_inv;                      // ... 1 / scale of the rows of T
-    int32_t *flag;                     // training calls: "redo the forward pass" flag of the block kernels
-    float *nbias;                      // ... 0 for each of the N negatives, -inf for the padding rows behind them
+    void *pstore, *Qs;                 // sampled softmax on the kernels of block_sym.hip / block_gradp.hip: the weights of the
+                                       // forward pass [Bp x Np bf16, in records], the queries scaled per forward split [nsplit_q][Bp][dp]
+    float *nbias;                      // training calls: 0 for each of the N negatives, -inf for the padding rows behind them
 };
 
 size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
@@ -166,7 +171,7 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
         b.Qp2 = c.take<char>((g.transh ? 4 : 2) * rowsB * 2); b.Tp2 = c.take<char>(2 * rowsN * 2); b.t_inv = c.take<float>(g.Np);
     }
     b.Q2 = nullptr; b.Qt = b.Wt = b.Tt = nullptr; b.lossb = b.gpos = nullptr; b.stat_part = nullptr;
-    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr; b.flag = nullptr; b.nbias = nullptr;
+    b.accq = b.accq2 = b.acct = nullptr; b.sumq = b.sumt = nullptr; b.regv = nullptr; b.S = nullptr; b.nbias = nullptr;
     if (bwd) {
         b.Q2 = g.transh && !g.l1 ? c.take<char>(rowsB * es) : nullptr;
         if (!g.l1) {
@@ -186,8 +191,12 @@ size_t carve(const Geometry &g, bool bwd, void *ws, Buffers &b) {
         b.acct = c.take<float>((size_t)g.nsplit_t * rowsN);
         b.sumt = c.take<float4>((size_t)g.nsplit_t * g.Np);
         b.regv = c.take<float>((size_t)2 * g.Bp + g.Np);
-        b.flag = c.take<int32_t>(1);
         b.nbias = c.take<float>(g.Np);
+        b.pstore = b.Qs = nullptr;
+        if (g.B > 0 && g.N > 0 && !g.l1 && kge_gradp_applies(g.bf16, g.rb, g.transh, g.dsplit_q, g.kind)) {
+            b.pstore = c.take<char>((size_t)g.own_tiles_b * g.nsplit_q * (g.tps_q / 2) * 16384);
+            b.Qs = c.take<char>((size_t)g.nsplit_q * rowsB * es);
+        }
     }
     return c.off + 256;
 }
@@ -418,13 +427,16 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     const float c_corr = (cfg->loss == KGE_SAMPLED_SOFTMAX && N > 0)
                              ? (float)log((double)(cfg->n_ent_for_c - 1) / (double)N) : 0.f;
     const bool have_block = B > 0 && N > 0;
+    // sampled softmax, bilinear scorers on bf16 rows of 512 bytes: the forward pass keeps its weights, the pass over the
+    // negatives contracts them with the scaled queries instead of scoring every pair again
+    const bool keep_weights = have_block && !g.l1 && cfg->loss == KGE_SAMPLED_SOFTMAX && b.pstore != nullptr;
 
     // (the kernels that need no transposed copy of the negatives get queries and negatives from ONE launch)
     const bool plain_gather = have_block && (g.l1 || kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q));
     if (plain_gather) {
         KgeProfScope prof(KGE_PROF_GATHER, st);
         rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos,
-                                    neg, g.N, g.Np, b.T, b.tn, st, nullptr, nullptr, nullptr, nullptr, b.flag, b.nbias);
+                                    neg, g.N, g.Np, b.T, b.tn, st, nullptr, nullptr, nullptr, nullptr, b.nbias);
     }
     else rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos, nullptr, st);
     if (rc != KGE_OK) return rc;
@@ -447,11 +459,17 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         a.B = g.B; a.N = g.N; a.dp = g.dp; a.str_tiles = g.str_tiles_n; a.tiles_per_split = g.tps_q;
         a.kind = g.kind; a.loss = cfg->loss; a.gamma = cfg->gamma; a.adv_temp = cfg->adv_temp; a.c_corr = c_corr;
         a.stat_part = b.stat_part; a.acc_part = b.accq; a.acc_part2 = b.accq2; a.sum_part = b.sumq; a.own_pad = g.Bp;
-        a.flag = b.flag; a.str_bias = b.nbias;
+        a.str_bias = b.nbias;
+        if (keep_weights) { a.pstore = b.pstore; a.ps_nsplit = g.nsplit_q; a.ps_rounds = g.tps_q / 2; }
         if ((rc = launch_block(g, KGE_MODE_FWD, cfg->loss, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
     }
-    if ((rc = kge_run_rowfinish(b.stat_part, have_block ? (g.l1 ? 1 : g.nsplit_q) : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
-                                cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, have_block ? nullptr : loss_out, st)) != KGE_OK) return rc;
+    if (keep_weights)
+        rc = kge_run_rowfinish_qscale(b.stat_part, g.nsplit_q, g.Bp, g.B, g.N, cfg->loss, cfg->gamma, c_corr, scale, b.pos, b.rowinfo,
+                                      b.lossb, b.gpos, b.Q, b.Qs, st);
+    else
+        rc = kge_run_rowfinish(b.stat_part, have_block ? (g.l1 ? 1 : g.nsplit_q) : 0, g.Bp, g.B, have_block ? g.N : 0, cfg->loss,
+                               cfg->gamma, c_corr, scale, b.pos, b.rowinfo, b.lossb, b.gpos, have_block ? nullptr : loss_out, st);
+    if (rc != KGE_OK) return rc;
     if (have_block && g.l1 && g.transh) {
         if ((rc = kge_run_l1h_grad(g.bf16, true, b.Q32, b.W32, b.T, b.S, b.A, b.P, g.Np, b.rowinfo, g.B, g.N, g.Bp, g.Np, g.dp,
                                    cfg->loss, cfg->gamma, cfg->adv_temp, g.nsplit_q, b.accq, b.accq2, st, g.pn)) != KGE_OK) return rc;
@@ -469,6 +487,7 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
         c.own = b.T; c.own2 = nullptr; c.str = b.Q; c.str2 = b.W; c.strT = b.Qt; c.strT2 = b.Wt; c.strT_ld = g.Bp;
         c.str_tiles = g.str_tiles_b; c.tiles_per_split = g.tps_t;
         c.acc_part = b.acct; c.acc_part2 = nullptr; c.sum_part = b.sumt; c.stat_part = nullptr; c.own_pad = g.Np;
+        if (keep_weights) c.str2 = b.Qs; else c.pstore = nullptr;    // (str2: the scaled queries; the recomputing kernel behind streams the plain ones)
         if ((rc = launch_block(g, KGE_MODE_GRADT, cfg->loss, c, g.own_tiles_n, g.nsplit_t, g.dsplit_t, st)) != KGE_OK) return rc;
     }
     if (have_block) {
@@ -565,6 +584,23 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
     if (kge_sparse_adam_ws(M, dim) - 256 > ws_bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     return kge_run_sparse_adam_apply(param_f32, param_bf16, m, v, n_rows, dim, ld, grads, M, *cfg, ws,
                                      (hipStream_t)hip_stream);
+}
+
+int kge_sparse_adam_plan_tables(const kge_adam_plan_t *plans, int32_t n_tables, void *hip_stream) {
+    if (!plans || n_tables < 1 || n_tables > 4) return KGE_E_INVALID_ARG;
+    for (int k = 0; k < n_tables; ++k) {
+        const kge_adam_plan_t &t = plans[k];
+        if (t.M < 0 || t.n_rows <= 0 || t.n_rows >= (1ll << 31) || t.dim <= 0 || t.dim % 4 != 0 || t.dim > 4096 || t.M >= (1ll << 31))
+            return KGE_E_INVALID_ARG;
+        if (t.M == 0) continue;
+        if (!t.idx) return KGE_E_INVALID_ARG;
+        if (!t.ws) return KGE_E_WORKSPACE_TOO_SMALL;
+        size_t bytes = t.ws_bytes;
+        void *ws = t.ws;
+        ws = align_ws(ws, bytes);
+        if (kge_sparse_adam_ws(t.M, t.dim) - 256 > bytes) return KGE_E_WORKSPACE_TOO_SMALL;
+    }
+    return kge_run_sparse_adam_plan_tables(plans, n_tables, (hipStream_t)hip_stream);
 }
 
 int kge_sparse_adam_apply_tables(const kge_adam_table_t *tables, int32_t n_tables, const kge_adam_cfg_t *cfg, void *hip_stream) {

@@ -34,7 +34,8 @@ struct KgeLdsLimit {
 };
 
 // Kernel choices that only tests and benchmarks override (kge_debug_select); 0 = the library's own choice.
-enum { KGE_KNOB_FWD_ONE_ROLE = 0, KGE_KNOB_GRADT_ONE_ROLE = 1, KGE_KNOB_SCORE_F32_MFMA = 2, KGE_KNOB_TWO_ROLE = 3, KGE_KNOBS = 4 };
+enum { KGE_KNOB_FWD_ONE_ROLE = 0, KGE_KNOB_GRADT_ONE_ROLE = 1, KGE_KNOB_SCORE_F32_MFMA = 2, KGE_KNOB_TWO_ROLE = 3,
+       KGE_KNOB_GRADT_RECOMPUTE = 4, KGE_KNOBS = 5 };
 int kge_knob(int knob);
 
 static inline int64_t kge_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
@@ -96,14 +97,20 @@ struct KgeBlockArgs {
     int32_t own_tiles, nsplit;     // launch geometry (the grid is one-dimensional in (split, own tile))
     int32_t xcd_per;               // XCDs that share one split (1 when there are 8 or more splits)
     const float *str_bias;         // FWD, kernel of block_sym.hip: [Np] 0 for a negative, -inf for a padding row (added to its scores)
-    int32_t *flag;                 // FWD, kernel of block_sym.hip: set to 1 when the pass has to be redone by the kernel below
-    const int32_t *gate;           // FWD, kernel of block_fwd_pp.hip: when given, the launch returns at once unless *gate != 0
+    // the coefficients of the forward pass, kept for the pass over the negatives (block_sym.hip writes, block_gradp.hip reads):
+    // one 4 KB record per (own tile of 128 queries, split, round of 64 negatives, wave), in the writer's register layout
+    void *pstore;
+    int32_t ps_nsplit, ps_rounds;  // splits and rounds per split of the forward pass that wrote them
 };
 
 bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit);
 bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit);
 // the kernel of block_sym.hip serves both passes of the same configurations; it walks the stream in tiles of 64 rows
 bool kge_sym_applies(bool bf16, int rb, bool transh, int dsplit);
+// sampled softmax, bilinear scorers: the pass over the negatives without recomputing the scores (block_gradp.hip);
+// kge_gradp_applies: the configurations whose forward pass keeps its weights for it
+bool kge_gradp_applies(bool bf16, int rb, bool transh, int dsplit, int kind);
+int kge_launch_gradp(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream_t st);
 // launchers implemented in block_*.hip (one file per element type and pass to bound compile time)
 int kge_launch_block(bool bf16, int rb, int mode, bool transh, int kind, int loss, int dsplit, const KgeBlockArgs &a,
                      int own_tiles, int nsplit, hipStream_t st);

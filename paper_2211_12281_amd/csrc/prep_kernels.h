@@ -28,12 +28,15 @@ int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out = nullptr,
                            void *q_planes = nullptr, void *t_planes = nullptr, float *t_inv_scale = nullptr,
-                           int32_t *flag = nullptr, float *bias = nullptr);   // flag: set to 0 by the launch (see KgeBlockArgs::flag);
-                                                                              // bias [Np]: 0 for the N negatives, -inf behind them
+                           float *bias = nullptr);            // bias [Np]: 0 for the N negatives, -inf behind them
 // gather of the negatives and their transposed copy Tt [dp][Np] in one launch
 int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
                       hipStream_t st);
 int kge_run_transpose(const void *src, void *dst, int R, int C, bool bf16, hipStream_t st);
+// bf16 rows of 256 elements: the finish plus the query rows scaled for every forward split, Qs [nsplit][Bp][256] (block_gradp.hip)
+int kge_run_rowfinish_qscale(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma, float c_corr,
+                              float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb, float *gpos, const void *Q,
+                              void *Qs, hipStream_t st);
 int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma,
                       float c_corr, float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb,
                       float *gpos, float *loss_out, hipStream_t st);     // loss_out null: the rows' losses are not summed here

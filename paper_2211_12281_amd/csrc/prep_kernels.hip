@@ -56,7 +56,7 @@ struct KgeQbuildArgs {
     _Float16 *planes;                  // optional: the two fp16 pieces of the scaled q, [2][Bp][dp], with W two more for the
                                        // unit normal (scaled by KGE_PLANE_UNIT_SCALE); then rowinfo.K = 1 / scale of the row
 };
-struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; _Float16 *planes; float *inv_scale; int32_t *flag; float *bias; };
+struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; _Float16 *planes; float *inv_scale; float *bias; };
 
 // fp32 rows as TWO fp16 planes for the matrix cores: the row is scaled by a power of two s that brings its largest
 // magnitude into [2^10, 2^11) (well inside the fp16 range, with the second piece of every element that matters still
@@ -269,7 +269,6 @@ __global__ void kge_qbuild_kernel(KgeQbuildArgs a) { kge_qbuild_body<BF16, SC>(b
 // independent, and a launch of their own each would cost the second one's start-up on the critical path
 template <bool BF16, int SC>
 __global__ void kge_qbuild_tgather_kernel(int q_blocks, KgeQbuildArgs a, KgeTgatherArgs g) {
-    if (blockIdx.x == 0 && threadIdx.x == 0 && g.flag) *g.flag = 0;     // the "redo the forward pass" flag of the block kernels
     if (g.bias)                                                         // 0 for the negatives, -inf for the padding rows behind them
         for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < g.Np; n += gridDim.x * blockDim.x) g.bias[n] = n < g.N ? 0.f : -INFINITY;
     if ((int)blockIdx.x < q_blocks) kge_qbuild_body<BF16, SC>(blockIdx.x, a);
@@ -343,13 +342,10 @@ __global__ void kge_transpose_kernel(const T *src, T *dst, int R, int C) {
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float kge_softplus_f(float y) { return fmaxf(y, 0.f) + log1pf(expf(-fabsf(y))); }
 
-__global__ void kge_rowfinish_kernel(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss,
-                                     float gamma, float c_corr, float scale, const float *pos,
-                                     KgeRowInfo *rowinfo, float *lossb, float *gpos) {
+struct KgeRowFinish { float L, gp, K; };
+__device__ __forceinline__ KgeRowFinish kge_rowfinish_row(const float4 *stat_part, int nsplit, int Bp, int b, int N, int loss,
+                                                          float gamma, float c_corr, float scale, float fp) {
     const float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= Bp) return;
-    if (b >= B) { lossb[b] = 0.f; gpos[b] = 0.f; rowinfo[b].K = -INFINITY; return; }
     // merge the splits: m is the running maximum of x * log2(e) (x = a*s or s), l the sum of
     // exp(x - max), ac the sum of exp(x - max) * softplus(gamma + s)
     float m = -INFINITY, l = 0.f, ac = 0.f;
@@ -360,24 +356,71 @@ __global__ void kge_rowfinish_kernel(const float4 *stat_part, int nsplit, int Bp
         const float r0 = exp2f(m - mn), r1 = exp2f(p.x - mn);
         l = l * r0 + p.y * r1; ac = ac * r0 + p.z * r1; m = mn;
     }
-    const float fp = pos[b];
-    float L, gp, K;
+    KgeRowFinish o;
     if (loss == KGE_LOGSIGMOID) {
-        L = kge_softplus_f(-(gamma + fp));
+        o.L = kge_softplus_f(-(gamma + fp));
         const float e = expf(-fabsf(gamma + fp));           // sigma(-(gamma+fp)), stable
-        gp = -((gamma + fp) >= 0.f ? e / (1.f + e) : 1.f / (1.f + e)) * scale;
-        if (N > 0 && l > 0.f) { L += ac / l; K = -m - log2f(l) + log2f(scale); } else K = -INFINITY;
+        o.gp = -((gamma + fp) >= 0.f ? e / (1.f + e) : 1.f / (1.f + e)) * scale;
+        if (N > 0 && l > 0.f) { o.L += ac / l; o.K = -m - log2f(l) + log2f(scale); } else o.K = -INFINITY;
     } else {
         if (N > 0 && l > 0.f) {
             const float A = c_corr + logf(l) + m * LN2;     // log of the negatives' share of the partition sum
             const float M = fmaxf(A, fp);
             const float lse = M + logf(expf(A - M) + expf(fp - M));
-            L = lse - fp;
-            gp = (expf(fp - lse) - 1.f) * scale;
-            K = (c_corr - lse + logf(scale)) * LOG2E;
-        } else { L = 0.f; gp = 0.f; K = -INFINITY; }
+            o.L = lse - fp;
+            o.gp = (expf(fp - lse) - 1.f) * scale;
+            o.K = (c_corr - lse + logf(scale)) * LOG2E;
+        } else { o.L = 0.f; o.gp = 0.f; o.K = -INFINITY; }
     }
-    lossb[b] = L; gpos[b] = gp; rowinfo[b].K = K;
+    return o;
+}
+
+__global__ void kge_rowfinish_kernel(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss,
+                                     float gamma, float c_corr, float scale, const float *pos,
+                                     KgeRowInfo *rowinfo, float *lossb, float *gpos) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= Bp) return;
+    if (b >= B) { lossb[b] = 0.f; gpos[b] = 0.f; rowinfo[b].K = -INFINITY; return; }
+    const KgeRowFinish o = kge_rowfinish_row(stat_part, nsplit, Bp, b, N, loss, gamma, c_corr, scale, pos[b]);
+    lossb[b] = o.L; gpos[b] = o.gp; rowinfo[b].K = o.K;
+}
+
+// The same finish, one wave per row, which also leaves the bf16 query row (256 elements) scaled for every forward split s:
+// qs[s][b] = bf16(exp2(ref_s[b] + K[b]) q[b]), ref_s the reference exponent that split s weighted the row's scores
+// against (stat_part[s][b].x) - the factor that turns a stored weight of the forward pass into the pair's gradient
+// coefficient (block_gradp.hip).  Rows b >= B and splits that saw no negative get zeros.
+__global__ void kge_rowfinish_qscale_kernel(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss,
+                                            float gamma, float c_corr, float scale, const float *pos,
+                                            KgeRowInfo *rowinfo, float *lossb, float *gpos, const uint16_t *Q, uint16_t *Qs) {
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (b >= Bp) return;
+    float K = -INFINITY;
+    if (b < B) {
+        const KgeRowFinish o = kge_rowfinish_row(stat_part, nsplit, Bp, b, N, loss, gamma, c_corr, scale, pos[b]);
+        K = o.K;
+        if (lane == 0) { lossb[b] = o.L; gpos[b] = o.gp; rowinfo[b].K = o.K; }
+    } else if (lane == 0) { lossb[b] = 0.f; gpos[b] = 0.f; rowinfo[b].K = -INFINITY; }
+    const uint2 raw = *(const uint2 *)(Q + (size_t)b * 256 + 4 * lane);
+    const float q[4] = { __uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                         __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u) };
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+      float refs[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) refs[u] = s0 + u < nsplit ? stat_part[(size_t)(s0 + u) * Bp + b].x : -INFINITY;   // eight loads in flight
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int s = s0 + u;
+        if (s >= nsplit) break;
+        const float ref = refs[u];
+        const float f = (b < B && ref > -INFINITY && K > -INFINITY) ? exp2f(ref + K) : 0.f;
+        uint16_t o[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[c] = __builtin_bit_cast(uint16_t, (__bf16)(f * q[c]));
+        *(uint2 *)(Qs + ((size_t)s * Bp + b) * 256 + 4 * lane) =
+            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+      }
+    }
 }
 
 // loss_out = scale * sum_b lossb[b], one workgroup, fixed summation tree
@@ -730,12 +773,12 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out,
-                           void *q_planes, void *t_planes, float *t_inv_scale, int32_t *flag, float *bias) {
+                           void *q_planes, void *t_planes, float *t_inv_scale, float *bias) {
     const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
     const int qb = (Bp + 3) / 4, tb = (Np + rows_wg - 1) / rows_wg;
     if (qb == 0 || tb == 0 || ((q_planes || t_planes) && m.bf16) || (t_planes && !t_inv_scale)) return KGE_E_INVALID_ARG;
     const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (_Float16 *)q_planes};
-    const KgeTgatherArgs g{neg, N, Np, T, tn, (_Float16 *)t_planes, t_inv_scale, flag, bias};
+    const KgeTgatherArgs g{neg, N, Np, T, tn, (_Float16 *)t_planes, t_inv_scale, bias};
 #define KGE_QT(BF, SC) hipLaunchKernelGGL((kge_qbuild_tgather_kernel<BF, SC>), dim3(qb + tb), dim3(256), 0, st, qb, a, g)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QT) } else { KGE_SC_SWITCH(false, KGE_QT) }
 #undef KGE_QT
@@ -781,6 +824,15 @@ int kge_run_rowfinish(const float4 *stat_part, int nsplit, int Bp, int B, int N,
         hipLaunchKernelGGL(kge_rowfinish_kernel, dim3((Bp + 255) / 256), dim3(256), 0, st, stat_part, nsplit, Bp, B, N,
                            loss, gamma, c_corr, scale, pos, rowinfo, lossb, gpos);
     if (loss_out) hipLaunchKernelGGL(kge_loss_reduce_kernel, dim3(1), dim3(256), 0, st, lossb, B, scale, loss_out);
+    return kge_launch_status();
+}
+
+int kge_run_rowfinish_qscale(const float4 *stat_part, int nsplit, int Bp, int B, int N, int loss, float gamma, float c_corr,
+                              float scale, const float *pos, KgeRowInfo *rowinfo, float *lossb, float *gpos, const void *Q,
+                              void *Qs, hipStream_t st) {
+    if (Bp > 0)
+        hipLaunchKernelGGL(kge_rowfinish_qscale_kernel, dim3((Bp + 3) / 4), dim3(256), 0, st, stat_part, nsplit, Bp, B, N, loss,
+                           gamma, c_corr, scale, pos, rowinfo, lossb, gpos, (const uint16_t *)Q, (uint16_t *)Qs);
     return kge_launch_status();
 }
 

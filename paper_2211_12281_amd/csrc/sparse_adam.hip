@@ -214,16 +214,24 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
 // Up to SMALL_MAX row ids in ONE launch (the ids of a training step: 2B + N of them).  Only the grouping of equal ids and
 // the position order inside a group matter to the update, so the order is (id & 255, id >> 8, position): workgroup w owns
 // the ids whose low byte is w.  It reads ALL ids (a few tens of KB, from L2), counts those of lower workgroups (its place
-// in the output) and collects its own in position order; then it sorts its list by the remaining bits, stable, four bits
-// a pass, in LDS (in the output buffers when its list is longer than SMALL_CAP: one id repeated thousands of times).
-// No workgroup waits for another.
+// in the output) and collects its own in position order; then it orders its list by the remaining bits, stable: a list
+// of up to 256 entries by counting, for every entry, the entries that come before it (one entry per thread); a longer
+// one (one id repeated thousands of times) by counting passes of four bits, in LDS, or in the output buffers when it is
+// longer than SMALL_CAP.  No workgroup waits for another; several tables go into one launch (256 workgroups each).
 // ---------------------------------------------------------------------------------------------
 constexpr int SMALL_MAX = 32768;
-constexpr int SMALL_CAP = 8192;
+constexpr int SMALL_CAP = 4096;
+constexpr int SMALL_NT = 1024;                              // threads of a workgroup
+constexpr int SMALL_ROUNDS = SMALL_MAX / (4 * SMALL_NT);    // rounds of SMALL_NT threads x 4 consecutive ids
+constexpr int SMALL_DIRECT = 256;                           // longest list that is ordered by counting predecessors
+constexpr int SMALL_TABLES = 4;
 __host__ __device__ constexpr int small_cnt_at(int f) { return f + (f >> 4); }     // one pad word per 16: strided reads spread over banks
 
-// exclusive scan of one value per thread over the 256 threads (in thread order); returns the total through `total`
-__device__ __forceinline__ uint32_t block_scan_256(uint32_t v, uint32_t *s_wave, uint32_t &total) {
+struct SmallSort { const int32_t *idx; int M, passes; uint32_t *ka, *kb, *pa, *pb; };
+struct SmallSorts { SmallSort t[SMALL_TABLES]; };
+
+// exclusive scan of one value per thread over the workgroup (in thread order); returns the total through `total`
+__device__ __forceinline__ uint32_t small_block_scan(uint32_t v, uint32_t *s_wave, uint32_t &total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t inc = v;
 #pragma unroll
@@ -234,28 +242,29 @@ __device__ __forceinline__ uint32_t block_scan_256(uint32_t v, uint32_t *s_wave,
     __syncthreads();                                       // s_wave may still be read from an earlier scan
     if (lane == 63) s_wave[wave] = inc;
     __syncthreads();
-    uint32_t before = 0;
-    for (int k = 0; k < wave; ++k) before += s_wave[k];
-    total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int k = 0; k < SMALL_NT / 64; ++k) { const uint32_t x = s_wave[k]; before += k < wave ? x : 0u; all += x; }
+    total = all;
     return before + inc - v;
 }
 
-// One stable counting pass over a list of n (key, position) pairs by the four key bits at `shift`; thread t owns the
-// contiguous piece [t c, (t + 1) c) of the list, c = ceil(n / 256), and moves through it eight entries at a time (eight
-// loads in flight: the list may lie in global memory).  dst_off is added to every destination index.
+// One stable counting pass over a list of n (key, position) pairs by the four key bits at `shift`: thread t owns the
+// contiguous piece [t c, (t + 1) c) of the list, c = ceil(n / SMALL_NT), and moves through it eight entries at a time
+// (eight loads in flight: the list may lie in global memory).  dst_off is added to every destination index.
 __device__ __forceinline__ void small_pass(const uint32_t *sk, const uint32_t *sp, uint32_t *dk, uint32_t *dp, int n, int shift,
                                            int dst_off, uint32_t *s_cnt, uint32_t *s_wave) {
     const int tid = threadIdx.x;
-    const int c = (n + 255) >> 8, lo = tid * c, hi = lo + c < n ? lo + c : n;
+    const int c = (n + SMALL_NT - 1) / SMALL_NT, lo = tid * c < n ? tid * c : n, hi = lo + c < n ? lo + c : n;
 #pragma unroll
-    for (int d = 0; d < 16; ++d) s_cnt[small_cnt_at(d * 256 + tid)] = 0;
+    for (int d = 0; d < 16; ++d) s_cnt[small_cnt_at(d * SMALL_NT + tid)] = 0;
     for (int e = lo; e < hi; e += 8) {
         uint32_t k[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) k[u] = e + u < hi ? sk[e + u] : 0u;
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            if (e + u < hi) s_cnt[small_cnt_at((int)((k[u] >> shift) & 15u) * 256 + tid)] += 1;      // own slots only
+            if (e + u < hi) s_cnt[small_cnt_at((int)((k[u] >> shift) & 15u) * SMALL_NT + tid)] += 1;      // own slots only
     }
     __syncthreads();
     // counters in (digit, thread) order: thread t scans the 16 consecutive ones at 16 t
@@ -263,7 +272,7 @@ __device__ __forceinline__ void small_pass(const uint32_t *sk, const uint32_t *s
 #pragma unroll
     for (int j = 0; j < 16; ++j) { v[j] = s_cnt[small_cnt_at(tid * 16 + j)]; sum += v[j]; }
     uint32_t total;
-    uint32_t run = block_scan_256(sum, s_wave, total);
+    uint32_t run = small_block_scan(sum, s_wave, total);
 #pragma unroll
     for (int j = 0; j < 16; ++j) { s_cnt[small_cnt_at(tid * 16 + j)] = run; run += v[j]; }
     __syncthreads();
@@ -274,7 +283,7 @@ __device__ __forceinline__ void small_pass(const uint32_t *sk, const uint32_t *s
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             if (e + u < hi) {
-                const int slot = small_cnt_at((int)((k[u] >> shift) & 15u) * 256 + tid);
+                const int slot = small_cnt_at((int)((k[u] >> shift) & 15u) * SMALL_NT + tid);
                 const uint32_t at = s_cnt[slot];
                 s_cnt[slot] = at + 1;
                 dk[dst_off + (int)at] = k[u]; dp[dst_off + (int)at] = q[u];
@@ -289,31 +298,33 @@ __device__ __forceinline__ void small_pass(const uint32_t *sk, const uint32_t *s
 __device__ __forceinline__ bool small_pass_trivial(const uint32_t *sk, const uint32_t *sp, uint32_t *dk, uint32_t *dp, int n, int shift) {
     const uint32_t d0 = (sk[0] >> shift) & 15u;
     int same = 1;
-    for (int e = threadIdx.x; e < n; e += 256) same &= ((sk[e] >> shift) & 15u) == d0;
+    for (int e = threadIdx.x; e < n; e += SMALL_NT) same &= ((sk[e] >> shift) & 15u) == d0;
     if (!__syncthreads_and(same)) return false;
-    for (int e = threadIdx.x; e < n; e += 256) { dk[e] = sk[e]; dp[e] = sp[e]; }
+    for (int e = threadIdx.x; e < n; e += SMALL_NT) { dk[e] = sk[e]; dp[e] = sp[e]; }
     __syncthreads();
     return true;
 }
 
-constexpr int SMALL_QUADS = SMALL_MAX / 1024;              // rounds of 256 threads x 4 consecutive ids
-
-__global__ __launch_bounds__(256) void sort_small_kernel(const int32_t *idx, int M, int passes, uint32_t *ka, uint32_t *kb,
-                                                         uint32_t *pa, uint32_t *pb) {
-    __shared__ uint32_t s_cnt[4096 + 256];
-    __shared__ uint32_t s_rc[SMALL_QUADS * 4];             // own ids of every (round, wave), then their offsets
-    __shared__ uint32_t s_key[2][SMALL_CAP], s_pos[2][SMALL_CAP];
-    __shared__ uint32_t s_wave[4];
-    const int w = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rounds = (M + 1023) >> 10;
+__global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T) {
+    __shared__ uint32_t s_cnt[16 * SMALL_NT + SMALL_NT];
+    __shared__ uint32_t s_rc[SMALL_ROUNDS * (SMALL_NT / 64)];   // own ids of every (round, wave), then their offsets
+    __shared__ __attribute__((aligned(16))) uint32_t s_key[2][SMALL_CAP];
+    __shared__ uint32_t s_pos[2][SMALL_CAP];
+    __shared__ uint32_t s_wave[SMALL_NT / 64];
+    const SmallSort &S = T.t[blockIdx.x >> 8];
+    const int32_t *idx = S.idx;
+    const int M = S.M, passes = S.passes;
+    uint32_t *ka = S.ka, *kb = S.kb, *pa = S.pa, *pb = S.pb;
+    const int w = blockIdx.x & 255, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rounds = (M + 4 * SMALL_NT - 1) / (4 * SMALL_NT);
     const bool vec = ((uintptr_t)idx & 15) == 0;
-    // every id into registers, all loads in flight: thread t of round r holds ids 4 (256 r + t) .. + 3 (position order =
-    // round, thread, element); 0xFFFFFFFF past the end (no low byte matches: the comparison below is on 9 bits)
-    uint4 id[SMALL_QUADS];
+    // every id into registers, all loads in flight: thread t of round r holds ids 4 (SMALL_NT r + t) .. + 3 (position order
+    // = round, thread, element)
+    uint4 id[SMALL_ROUNDS];
 #pragma unroll
-    for (int r = 0; r < SMALL_QUADS; ++r) {
-        const int i = 4 * (r * 256 + tid);
-        id[r] = make_uint4(~0u, ~0u, ~0u, ~0u);
+    for (int r = 0; r < SMALL_ROUNDS; ++r) {
+        const int i = 4 * (r * SMALL_NT + tid);
+        id[r] = make_uint4(0u, 0u, 0u, 0u);
         if (r < rounds) {
             if (vec && i + 3 < M) id[r] = *(const uint4 *)(idx + i);
             else {
@@ -327,9 +338,9 @@ __global__ __launch_bounds__(256) void sort_small_kernel(const int32_t *idx, int
     const uint64_t below = (1ull << lane) - 1ull;
     uint32_t lower = 0;                                    // ids of lower workgroups seen by this thread
 #pragma unroll
-    for (int r = 0; r < SMALL_QUADS; ++r) {
+    for (int r = 0; r < SMALL_ROUNDS; ++r) {
         if (r < rounds) {
-            const int i = 4 * (r * 256 + tid);
+            const int i = 4 * (r * SMALL_NT + tid);
             const uint32_t e[4] = { id[r].x, id[r].y, id[r].z, id[r].w };
             uint32_t own = 0;
 #pragma unroll
@@ -338,28 +349,28 @@ __global__ __launch_bounds__(256) void sort_small_kernel(const int32_t *idx, int
                 lower += in && (int)(e[j] & 255u) < w;
                 own += (uint32_t)__builtin_popcountll(__ballot(in && (int)(e[j] & 255u) == w));
             }
-            if (lane == 0) s_rc[r * 4 + wave] = own;
+            if (lane == 0) s_rc[r * (SMALL_NT / 64) + wave] = own;
         }
     }
     __syncthreads();
     // offsets of the (round, wave) groups in the list
-    const int nrc = rounds * 4;
+    const int nrc = rounds * (SMALL_NT / 64);
     const uint32_t c0 = tid < nrc ? s_rc[tid] : 0;
     uint32_t n_own, n_lower;
-    const uint32_t off = block_scan_256(c0, s_wave, n_own);
+    const uint32_t off = small_block_scan(c0, s_wave, n_own);
     if (tid < nrc) s_rc[tid] = off;
-    (void)block_scan_256(lower, s_wave, n_lower);
+    (void)small_block_scan(lower, s_wave, n_lower);
     __syncthreads();
     const int n = (int)n_own, base = (int)n_lower;
     if (n == 0) return;                                    // (uniform: every thread holds the same totals)
-    // the list starts where `passes` exchanges of buffers end in (ka, pa); in LDS the last pass writes (ka, pa) itself
+    // the list starts where `passes` exchanges of buffers end in (ka, pa); in LDS the last step writes (ka, pa) itself
     const bool in_lds = n <= SMALL_CAP;
     uint32_t *lk = in_lds ? (passes == 0 ? ka + base : s_key[0]) : ((passes & 1) ? kb : ka) + base;
     uint32_t *lp = in_lds ? (passes == 0 ? pa + base : s_pos[0]) : ((passes & 1) ? pb : pa) + base;
 #pragma unroll
-    for (int r = 0; r < SMALL_QUADS; ++r) {
+    for (int r = 0; r < SMALL_ROUNDS; ++r) {
         if (r < rounds) {
-            const int i = 4 * (r * 256 + tid);
+            const int i = 4 * (r * SMALL_NT + tid);
             const uint32_t e[4] = { id[r].x, id[r].y, id[r].z, id[r].w };
             bool mine[4];
             int before = 0;                                // own ids of lower lanes in this round
@@ -368,14 +379,29 @@ __global__ __launch_bounds__(256) void sort_small_kernel(const int32_t *idx, int
                 mine[j] = i + j < M && (int)(e[j] & 255u) == w;
                 before += __builtin_popcountll(__ballot(mine[j]) & below);
             }
-            int at = (int)s_rc[r * 4 + wave] + before;
+            int at = (int)s_rc[r * (SMALL_NT / 64) + wave] + before;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 if (mine[j]) { lk[at] = e[j]; lp[at] = (uint32_t)(i + j); ++at; }
         }
     }
     __syncthreads();
-    if (in_lds) {
+    if (passes == 0) return;
+    if (n <= SMALL_DIRECT) {
+        // the place of entry e: the entries with a smaller id, and those with the same id that come before it
+        if (tid < n) {
+            const uint32_t key = s_key[0][tid];
+            int rank = 0;
+            const int n4 = n & ~3;
+            for (int j = 0; j < n4; j += 4) {
+                const uint4 k4 = *(const uint4 *)&s_key[0][j];              // (the same address in every lane: a broadcast)
+                rank += (k4.x < key || (k4.x == key && j < tid)) + (k4.y < key || (k4.y == key && j + 1 < tid)) +
+                        (k4.z < key || (k4.z == key && j + 2 < tid)) + (k4.w < key || (k4.w == key && j + 3 < tid));
+            }
+            for (int j = n4; j < n; ++j) { const uint32_t kj = s_key[0][j]; rank += kj < key || (kj == key && j < tid); }
+            ka[base + rank] = key; pa[base + rank] = s_pos[0][tid];
+        }
+    } else if (in_lds) {
         for (int p = 0; p < passes; ++p) {
             const bool last = p == passes - 1;
             small_pass(s_key[p & 1], s_pos[p & 1], last ? ka : s_key[(p + 1) & 1], last ? pa : s_pos[(p + 1) & 1], n, 8 + 4 * p,
@@ -590,8 +616,9 @@ int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64
     int bits = 1;
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
     if (sort_is_small(idx != nullptr, M)) {
-        const int passes = bits > 8 ? (bits - 8 + 3) / 4 : 0;
-        hipLaunchKernelGGL(sort_small_kernel, dim3(256), dim3(256), 0, st, idx, (int)M, passes, s.ka, s.kb, s.pa, s.pb);
+        SmallSorts T = {};
+        T.t[0] = SmallSort{idx, (int)M, bits > 8 ? (bits - 8 + 3) / 4 : 0, s.ka, s.kb, s.pa, s.pb};
+        hipLaunchKernelGGL(sort_small_kernel, dim3(256), dim3(SMALL_NT), 0, st, T);
         *sk = s.ka; *sp = s.pa;
         return kge_launch_status();
     }
@@ -627,6 +654,31 @@ static void sort_result(int64_t M, int64_t key_range, void *ws, const uint32_t *
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
     const int passes = (bits + 7) / 8;
     *sk = (passes & 1) ? s.kb : s.ka; *sp = (passes & 1) ? s.pb : s.pa;
+}
+
+// Several tables: those of up to SMALL_MAX ids share one launch (256 workgroups each), longer ones take the radix passes.
+int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st) {
+    KgeProfScope prof(KGE_PROF_SORT, st);
+    SmallSorts T = {};
+    int small = 0;
+    for (int k = 0; k < n; ++k) {
+        if (pl[k].M == 0) continue;
+        void *ws = pl[k].ws;
+        if (((uintptr_t)ws & 255) != 0) ws = (char *)ws + (256 - ((uintptr_t)ws & 255));
+        if (sort_is_small(true, pl[k].M)) {
+            SortWs s;
+            sort_carve(pl[k].M, 0, ws, s);
+            int bits = 1;
+            while (bits < 32 && (1ll << bits) < pl[k].n_rows) ++bits;
+            T.t[small++] = SmallSort{pl[k].idx, (int)pl[k].M, bits > 8 ? (bits - 8 + 3) / 4 : 0, s.ka, s.kb, s.pa, s.pb};
+        } else {
+            const uint32_t *sk, *sp;
+            const int rc = kge_sort_pairs(pl[k].idx, nullptr, nullptr, 1, 1, pl[k].M, pl[k].n_rows, ws, &sk, &sp, st, nullptr, 0);
+            if (rc != KGE_OK) return rc;
+        }
+    }
+    if (small > 0) hipLaunchKernelGGL(sort_small_kernel, dim3(256 * small), dim3(SMALL_NT), 0, st, T);
+    return kge_launch_status();
 }
 
 int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void *ws, hipStream_t st) {

@@ -240,3 +240,37 @@ def test_several_tables_in_one_call_give_the_bits_of_one_call_per_table():
         if s["ref_sh"] is not None:
             assert bool((s["ref_sh"].view(torch.int16) == s["got_sh"].view(torch.int16)).all())
     assert not bool((sets[0]["got"][0] == dev(_state(50000, 256, 40, True)[0])).all())     # something was updated
+
+
+def test_plans_of_several_tables_in_one_call_equal_one_call_per_table():
+    """kge_sparse_adam_plan_tables against kge_sparse_adam_plan table by table, through the updates that read the plans:
+    a long Zipf list, a list of one repeated id (longer than the list a workgroup orders in one step), a short list over
+    few rows (no bits left to order by), an empty one."""
+    import paper_2211_12281_amd as kge
+    shapes = [(10_000_000, 64, 24576, "zipf"), (1000, 64, 9000, "same"), (200, 64, 4096, "zipf"), (77, 64, 0, "zipf")]
+    dev = lambda a: torch.from_numpy(a.copy()).cuda()
+    sets = []
+    for k, (n_rows, d, M, kind) in enumerate(shapes):
+        g = np.random.default_rng(240 + k)
+        idx = ks.ZipfIds(n_rows, 1.1).draw(g, M) if kind == "zipf" else np.full(M, 777, np.int32)
+        touched = np.unique(idx)
+        rows = min(n_rows, 70000)                          # (the big table: only ids below 70,000 are kept)
+        idx = idx[idx < rows] if n_rows > rows else idx
+        M = idx.size
+        theta, m, v = _state(rows, d, 340 + k, True)
+        grads = (g.normal(size=(M, d)) * 1e-2).astype(F)
+        one = {"idx": dev(idx), "grads": dev(grads), "n_rows": n_rows, "d": d}
+        for tag in ("ref", "got"):
+            one[tag] = [dev(theta), dev(m), dev(v)]
+            one[tag + "_ws"] = kge.Workspace()
+        sets.append(one)
+    for s in sets:
+        if s["idx"].numel():
+            kge.sparse_adam_plan(s["n_rows"], s["d"], s["idx"], s["ref_ws"])
+            kge.sparse_adam_apply(s["ref"][0], None, s["ref"][1], s["ref"][2], s["grads"], s["ref_ws"], 2e-3, step=3)
+    kge.sparse_adam_plan_tables([(s["n_rows"], s["d"], s["idx"], s["got_ws"]) for s in sets])
+    kge.sparse_adam_apply_tables([(s["got"][0], None, s["got"][1], s["got"][2], s["grads"], s["got_ws"]) for s in sets], 2e-3, step=3)
+    torch.cuda.synchronize()
+    for s in sets:
+        for a, c in zip(s["ref"], s["got"]):
+            assert bool((a == c).all())
