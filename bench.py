@@ -702,6 +702,11 @@ def main():
         roof["frac_less_empty_pair"] = roof["frac"] * roof["avg_us"] / net
     if roof is not None and roof.get("achieved") is not None and roof["bound"] == "mfma" and wl_bf16(wl):
         roof["frac_of_measured_loop"] = roof["achieved"] / calib["mfma_bf16_loop_tflops"]
+    if roof is not None and isinstance(wl, TrainWorkload) and "block_fwd" in prof and "block_gradt" in prof and roof["bound"] == "mfma":
+        # both passes together: the credited flops of the step (scores, dQ, dT: 3 contractions) over the two kernels' time
+        us = prof["block_fwd"]["avg_us"] + prof["block_gradt"]["avg_us"]
+        fl = wl.mfma_flops("block_fwd") + wl.mfma_flops("block_gradt")
+        roof["both_passes"] = {"avg_us": us, "achieved": fl / (us * 1e-6) / 1e12, "frac": fl / (us * 1e-6) / 1e12 / roof["peak"]}
     # the memory-bound kernels of a training step against the HBM peak and against this box's own streaming copy
     hbm = None
     if isinstance(wl, TrainWorkload):

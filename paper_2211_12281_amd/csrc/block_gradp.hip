@@ -58,12 +58,13 @@ void kge_gradp_kernel(const KgeBlockArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, g = lane >> 5;
     const int oh = wave >> 1, sh = wave & 1;
-    // placement: workgroups that stream the same queries share a die
+    // placement: the own tiles whose negatives one forward split scored stream the same scaled queries (q'_fs) - they go
+    // to ONE die (workgroups are dealt to the eight dies in turn), so that a die's L2 holds one q'_fs instead of all
     const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
-    int own_tile, split;
-    if (a.xcd_per == 1) { own_tile = kk % a.own_tiles; split = xcd + 8 * (kk / a.own_tiles); }
-    else { split = xcd / a.xcd_per; own_tile = kk * a.xcd_per + xcd % a.xcd_per; }
-    if (own_tile >= a.own_tiles || split >= a.nsplit) return;
+    const int tpf = a.ps_rounds >> 1, per_group = tpf * a.nsplit;          // own tiles per forward split; work items per group
+    const int group = xcd + 8 * (kk / per_group), within = kk % per_group;
+    const int own_tile = group * tpf + within / a.nsplit, split = within % a.nsplit;
+    if (own_tile >= a.own_tiles) return;
     // rounds of 64 queries; only rounds that hold a valid query are visited
     const int tps = a.tiles_per_split >> 1;
     const int tiles = min(a.str_tiles >> 1, (a.B + GP_ST - 1) / GP_ST);
@@ -211,14 +212,8 @@ int kge_launch_gradp(const KgeBlockArgs &a, int own_tiles, int nsplit, hipStream
     if ((int64_t)a.ps_nsplit * a.ps_rounds < 2 * (int64_t)own_tiles) return KGE_E_INVALID_ARG;
     KgeBlockArgs b = a;
     b.own_tiles = own_tiles; b.nsplit = nsplit;
-    int groups;
-    if (nsplit >= 8) { b.xcd_per = 1; groups = own_tiles * ((nsplit + 7) / 8); }
-    else {
-        int s2 = 1;
-        while (s2 < nsplit) s2 <<= 1;
-        b.xcd_per = 8 / s2;
-        groups = (own_tiles + b.xcd_per - 1) / b.xcd_per;
-    }
-    hipLaunchKernelGGL(kern, dim3(8 * groups), dim3(256), gp_lds(), st, b);
+    const int tpf = a.ps_rounds / 2, ngroups = (own_tiles + tpf - 1) / tpf;         // see the placement in the kernel
+    const int per_die = (ngroups + 7) / 8 * tpf * nsplit;
+    hipLaunchKernelGGL(kern, dim3(8 * per_die), dim3(256), gp_lds(), st, b);
     return kge_launch_status();
 }
