@@ -213,11 +213,11 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
 // ---------------------------------------------------------------------------------------------
 // Up to SMALL_MAX row ids in ONE launch (the ids of a training step: 2B + N of them).  Only the grouping of equal ids and
 // the position order inside a group matter to the update, so the order is (id & 255, id >> 8, position): workgroup w owns
-// the ids whose low byte is w.  It reads ALL ids (a few tens of KB, from L2), counts those of lower workgroups (its place
+// the ids whose low byte is w (low five bits, 32 workgroups, for a table of at most SMALL_FEW ids).  It reads ALL ids (a few tens of KB, from L2), counts those of lower workgroups (its place
 // in the output) and collects its own in position order; then it orders its list by the remaining bits, stable: a list
 // of up to 256 entries by counting, for every entry, the entries that come before it (one entry per thread); a longer
 // one (one id repeated thousands of times) by counting passes of four bits, in LDS, or in the output buffers when it is
-// longer than SMALL_CAP.  No workgroup waits for another; several tables go into one launch (256 workgroups each).
+// longer than SMALL_CAP.  No workgroup waits for another; several tables go into one launch (workgroup ranges).
 // ---------------------------------------------------------------------------------------------
 constexpr int SMALL_MAX = 32768;
 constexpr int SMALL_CAP = 4096;
@@ -225,9 +225,10 @@ constexpr int SMALL_NT = 1024;                              // threads of a work
 constexpr int SMALL_ROUNDS = SMALL_MAX / (4 * SMALL_NT);    // rounds of SMALL_NT threads x 4 consecutive ids
 constexpr int SMALL_DIRECT = 256;                           // longest list that is ordered by counting predecessors
 constexpr int SMALL_TABLES = 4;
+constexpr int SMALL_FEW = 8192;                            // a table of at most this many ids is cut into 32 parts, not 256
 __host__ __device__ constexpr int small_cnt_at(int f) { return f + (f >> 4); }     // one pad word per 16: strided reads spread over banks
 
-struct SmallSort { const int32_t *idx; int M, passes; uint32_t *ka, *kb, *pa, *pb; };
+struct SmallSort { const int32_t *idx; int M, bits; uint32_t *ka, *kb, *pa, *pb; };   // bits: of the largest id
 struct SmallSorts { SmallSort t[SMALL_TABLES]; };
 
 // exclusive scan of one value per thread over the workgroup (in thread order); returns the total through `total`
@@ -311,11 +312,23 @@ __global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T
     __shared__ __attribute__((aligned(16))) uint32_t s_key[2][SMALL_CAP];
     __shared__ uint32_t s_pos[2][SMALL_CAP];
     __shared__ uint32_t s_wave[SMALL_NT / 64];
-    const SmallSort &S = T.t[blockIdx.x >> 8];
+    // workgroups 0 .. nb0 - 1 take the first table, the next nb1 the second, ...: a table of up to SMALL_FEW ids is cut into
+    // 32 parts (by the low five bits), a longer one into 256
+    int first = 0, ti = 0;
+#pragma unroll
+    for (int k = 0; k < SMALL_TABLES - 1; ++k) {
+        const int nbk = T.t[k].M <= SMALL_FEW ? 32 : 256;
+        if (T.t[k].idx && (int)blockIdx.x >= first + nbk) { first += nbk; ti = k + 1; }
+    }
+    const SmallSort &S = T.t[ti];
     const int32_t *idx = S.idx;
-    const int M = S.M, passes = S.passes;
+    const int M = S.M;
+    const int lb = M <= SMALL_FEW ? 5 : 8;                 // bits of the id that select the workgroup
+    const int passes = S.bits > lb ? (S.bits - lb + 3) / 4 : 0;
+    const uint32_t lmask = (1u << lb) - 1u;
     uint32_t *ka = S.ka, *kb = S.kb, *pa = S.pa, *pb = S.pb;
-    const int w = blockIdx.x & 255, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int w = (int)blockIdx.x - first;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rounds = (M + 4 * SMALL_NT - 1) / (4 * SMALL_NT);
     const bool vec = ((uintptr_t)idx & 15) == 0;
     // every id into registers, all loads in flight: thread t of round r holds ids 4 (SMALL_NT r + t) .. + 3 (position order
@@ -346,8 +359,8 @@ __global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const bool in = i + j < M;
-                lower += in && (int)(e[j] & 255u) < w;
-                own += (uint32_t)__builtin_popcountll(__ballot(in && (int)(e[j] & 255u) == w));
+                lower += in && (int)(e[j] & lmask) < w;
+                own += (uint32_t)__builtin_popcountll(__ballot(in && (int)(e[j] & lmask) == w));
             }
             if (lane == 0) s_rc[r * (SMALL_NT / 64) + wave] = own;
         }
@@ -376,7 +389,7 @@ __global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T
             int before = 0;                                // own ids of lower lanes in this round
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                mine[j] = i + j < M && (int)(e[j] & 255u) == w;
+                mine[j] = i + j < M && (int)(e[j] & lmask) == w;
                 before += __builtin_popcountll(__ballot(mine[j]) & below);
             }
             int at = (int)s_rc[r * (SMALL_NT / 64) + wave] + before;
@@ -402,15 +415,60 @@ __global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T
             ka[base + rank] = key; pa[base + rank] = s_pos[0][tid];
         }
     } else if (in_lds) {
+        // A long list is usually ONE id repeated (Zipf's hottest rows): the entries with that id keep their order as one
+        // group, and only the others are ordered - by counting predecessors among themselves - and placed before or
+        // behind the group.  (Which id is taken only decides how fast this is.)
+        // the most frequent id among the list's first 64 entries (ties: the earliest), found by every wave for itself
+        const uint32_t mine = s_key[0][lane];
+        int votes = 0;
+        for (int j = 0; j < 64; ++j) votes += mine == (uint32_t)__builtin_amdgcn_readlane((int)mine, j);
+        int best = (votes << 6) | (63 - lane);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) { const int other = __shfl_xor(best, o); best = other > best ? other : best; }
+        const uint32_t hot = (uint32_t)__builtin_amdgcn_readlane((int)mine, 63 - (best & 63));
+        constexpr int PER = SMALL_CAP / SMALL_NT;          // list entries per thread, in list order: thread t has t PER .. + PER - 1
+        uint32_t mk[PER], mp[PER];
+        int cold = 0, less = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = tid * PER + u;
+            mk[u] = e < n ? s_key[0][e] : hot; mp[u] = e < n ? s_pos[0][e] : 0u;
+            cold += mk[u] != hot; less += mk[u] < hot;
+        }
+        uint32_t n_cold, n_less;
+        const uint32_t cold_at = small_block_scan((uint32_t)cold, s_wave, n_cold);
+        (void)small_block_scan((uint32_t)less, s_wave, n_less);
+        if ((int)n_cold <= SMALL_DIRECT) {                 // (uniform)
+            const int hot_at = tid * PER - (int)cold_at;   // entries of the group before this thread's
+            int ci = (int)cold_at, hi = 0;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int e = tid * PER + u;
+                if (e < n) {
+                    if (mk[u] != hot) { s_key[1][ci] = mk[u]; s_pos[1][ci] = mp[u]; ++ci; }
+                    else { const int at = base + (int)n_less + hot_at + hi; ka[at] = hot; pa[at] = mp[u]; ++hi; }
+                }
+            }
+            __syncthreads();
+            const int nc = (int)n_cold, n_hot = n - nc;
+            if (tid < nc) {
+                const uint32_t key = s_key[1][tid];
+                int rank = 0;
+                for (int j = 0; j < nc; ++j) { const uint32_t kj = s_key[1][j]; rank += kj < key || (kj == key && j < tid); }
+                const int at = base + rank + (key > hot ? n_hot : 0);
+                ka[at] = key; pa[at] = s_pos[1][tid];
+            }
+            return;
+        }
         for (int p = 0; p < passes; ++p) {
             const bool last = p == passes - 1;
-            small_pass(s_key[p & 1], s_pos[p & 1], last ? ka : s_key[(p + 1) & 1], last ? pa : s_pos[(p + 1) & 1], n, 8 + 4 * p,
+            small_pass(s_key[p & 1], s_pos[p & 1], last ? ka : s_key[(p + 1) & 1], last ? pa : s_pos[(p + 1) & 1], n, lb + 4 * p,
                        last ? base : 0, s_cnt, s_wave);
         }
     } else {
         uint32_t *k0 = lk, *p0 = lp, *k1 = ((passes & 1) ? ka : kb) + base, *p1 = ((passes & 1) ? pa : pb) + base;
         for (int p = 0; p < passes; ++p) {
-            if (!small_pass_trivial(k0, p0, k1, p1, n, 8 + 4 * p)) small_pass(k0, p0, k1, p1, n, 8 + 4 * p, 0, s_cnt, s_wave);
+            if (!small_pass_trivial(k0, p0, k1, p1, n, lb + 4 * p)) small_pass(k0, p0, k1, p1, n, lb + 4 * p, 0, s_cnt, s_wave);
             uint32_t *tk = k0; k0 = k1; k1 = tk;
             tk = p0; p0 = p1; p1 = tk;
         }
@@ -617,8 +675,8 @@ int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
     if (sort_is_small(idx != nullptr, M)) {
         SmallSorts T = {};
-        T.t[0] = SmallSort{idx, (int)M, bits > 8 ? (bits - 8 + 3) / 4 : 0, s.ka, s.kb, s.pa, s.pb};
-        hipLaunchKernelGGL(sort_small_kernel, dim3(256), dim3(SMALL_NT), 0, st, T);
+        T.t[0] = SmallSort{idx, (int)M, bits, s.ka, s.kb, s.pa, s.pb};
+        hipLaunchKernelGGL(sort_small_kernel, dim3(M <= SMALL_FEW ? 32 : 256), dim3(SMALL_NT), 0, st, T);
         *sk = s.ka; *sp = s.pa;
         return kge_launch_status();
     }
@@ -660,7 +718,7 @@ static void sort_result(int64_t M, int64_t key_range, void *ws, const uint32_t *
 int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st) {
     KgeProfScope prof(KGE_PROF_SORT, st);
     SmallSorts T = {};
-    int small = 0;
+    int small = 0, nwg = 0;
     for (int k = 0; k < n; ++k) {
         if (pl[k].M == 0) continue;
         void *ws = pl[k].ws;
@@ -670,14 +728,15 @@ int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_
             sort_carve(pl[k].M, 0, ws, s);
             int bits = 1;
             while (bits < 32 && (1ll << bits) < pl[k].n_rows) ++bits;
-            T.t[small++] = SmallSort{pl[k].idx, (int)pl[k].M, bits > 8 ? (bits - 8 + 3) / 4 : 0, s.ka, s.kb, s.pa, s.pb};
+            T.t[small++] = SmallSort{pl[k].idx, (int)pl[k].M, bits, s.ka, s.kb, s.pa, s.pb};
+            nwg += pl[k].M <= SMALL_FEW ? 32 : 256;
         } else {
             const uint32_t *sk, *sp;
             const int rc = kge_sort_pairs(pl[k].idx, nullptr, nullptr, 1, 1, pl[k].M, pl[k].n_rows, ws, &sk, &sp, st, nullptr, 0);
             if (rc != KGE_OK) return rc;
         }
     }
-    if (small > 0) hipLaunchKernelGGL(sort_small_kernel, dim3(256 * small), dim3(SMALL_NT), 0, st, T);
+    if (small > 0) hipLaunchKernelGGL(sort_small_kernel, dim3(nwg), dim3(SMALL_NT), 0, st, T);
     return kge_launch_status();
 }
 
