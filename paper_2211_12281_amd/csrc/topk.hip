@@ -47,6 +47,7 @@ struct TopkArgs {
 // Asynchronous global -> LDS copies (gfx950): lane l of a wave-wide instruction writes its 16 (or 4)
 // bytes to LDS byte address m0 + l*16 (l*4); the data never passes through registers, completion is
 // tracked by vmcnt.  The compiler does not see these loads, so the waits are explicit.
+__device__ __forceinline__ int tk_swz(int r) { return (((r >> 1) & 3) << 2) | (((r >> 3) & 1) << 1) | (r & 1); }
 __device__ __forceinline__ void async_copy16(const void *g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
 }
@@ -65,8 +66,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 //
 // Candidate tiles (32 rows) stream through an LDS ring of NSTAGE stages filled by asynchronous copies,
 // so several tiles are in flight per compute unit.  A row of RB bytes is stored unpadded with its
-// 16-byte chunks XOR-swizzled by (row & 7): the MFMA A-fragment reads of 8 consecutive rows then fall
-// into 8 different bank groups.  The MFMAs of tile t+1 are issued before the epilogue of tile t, so the
+// 16-byte chunks XOR-swizzled by a bit permutation of (row mod 16) (tk_swz): the MFMA A-fragment reads of 16
+// consecutive rows at one chunk index then fall into 16 different bank groups (an XOR with row mod 8 reaches half the
+// LDS's rate: half of the LDS's active cycles were bank conflicts).  The MFMAs of tile t+1 are issued before the epilogue of tile t, so the
 // matrix pipe works while the vector ALU filters.
 template <bool BF16, int RB, int KIND, int OB, bool TH = false>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
@@ -134,7 +136,7 @@ void topk_scan_kernel(const TopkArgs a) {
         const int byte = (wave * IPW + jj) * 1024 + lane * 16;
         const int r = byte / RB, pos = (byte % RB) / 16;
         ld_row[jj] = r;
-        ld_col[jj] = (pos ^ (r & 7)) * 16;              // source chunk that belongs at this LDS position
+        ld_col[jj] = (pos ^ tk_swz(r)) * 16;            // source chunk that belongs at this LDS position
     }
     // source of copy jj for tile 0 and its advance per tile (lanes of the padding columns read the 16 zero bytes, advance 0):
     // one multiply-add per copy in the loop; only the table's last, ragged tile takes the clamped path
@@ -166,15 +168,15 @@ void topk_scan_kernel(const TopkArgs a) {
         async_copy4(a.tn + tile * TK_ST + lr,
                     __builtin_amdgcn_readfirstlane(lds0 + NSTAGE * TILE_BYTES + ((slot % SIDE_SLOTS) * 4 + wave) * 256));
     };
-    // ---- A-fragment addresses: chunk (2 ks + g) of row lr sits at position chunk ^ (lr & 7) -----------
-    int frag_off[4];
+    // ---- A-fragment addresses: chunk (2 ks + g) of row lr sits at position chunk ^ tk_swz(lr) ----------
+    int frag_off[8];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) frag_off[b] = lr * RB + 16 * (((2 * b) ^ (lr & 6)) | (g ^ (lr & 1)));
+    for (int b = 0; b < 8; ++b) frag_off[b] = lr * RB + 16 * ((2 * b + g) ^ tk_swz(lr));
     auto mma_tile = [&](int slot, kge_f32x16 (&acc)[OB]) {
         const char *base = lds + (slot % NSTAGE) * TILE_BYTES;
         uint4 av[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) av[ks] = *(const uint4 *)(base + frag_off[ks & 3] + 128 * (ks >> 2));
+        for (int ks = 0; ks < KS; ++ks) av[ks] = *(const uint4 *)(base + frag_off[ks & 7] + 256 * (ks >> 3));
         if constexpr (KIND == KGE_KIND_DIST) {
             // TransE: the accumulators start at -|t|^2 of their candidate row and the queries are stored
             // doubled, so the contraction itself yields 2 q.t - |t|^2
