@@ -161,7 +161,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
 // gather of the shared negatives: T[n] = ent[neg[n]], tn[n] = ||T[n]||^2 (zeros past N)
 // ---------------------------------------------------------------------------------------------
 // rows of the gathered block that one wave takes: a row of dp elements is covered by dp * ES / 16 lanes with 16 bytes
-// each; 64 / (that, rounded up to a power of two) rows share a load instruction, and FOUR such loads are in flight per
+// each; 64 / (that, rounded up to a power of two) rows share a load instruction, and EIGHT such loads are in flight per
 // lane (a random row costs a full memory round trip: the bytes in flight bound the rate of the gather)
 __host__ __device__ inline int kge_tgather_group_lanes(int dp, int es) {
     const int lpr = dp * es / 16;
@@ -169,7 +169,8 @@ __host__ __device__ inline int kge_tgather_group_lanes(int dp, int es) {
     while (gl < lpr) gl <<= 1;
     return gl < 64 ? gl : 64;
 }
-__host__ __device__ inline int kge_tgather_rows_per_wave(int dp, int es) { return 4 * (64 / kge_tgather_group_lanes(dp, es)); }
+constexpr int KGE_TG_INFLIGHT = 8;                          // row loads in flight per lane
+__host__ __device__ inline int kge_tgather_rows_per_wave(int dp, int es) { return KGE_TG_INFLIGHT * (64 / kge_tgather_group_lanes(dp, es)); }
 
 template <bool BF16>
 __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T,
@@ -177,26 +178,26 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
     const int lane = threadIdx.x & 63;
     constexpr int ES = BF16 ? 2 : 4;
     const int lpr = dp * ES / 16;                           // lanes that cover a row with 16 bytes each
-    const int gl = kge_tgather_group_lanes(dp, ES), rpl = 64 / gl, rpw = 4 * rpl;
+    const int gl = kge_tgather_group_lanes(dp, ES), rpl = 64 / gl, rpw = KGE_TG_INFLIGHT * rpl;
     const int nbase = (blk * (blockDim.x >> 6) + (threadIdx.x >> 6)) * rpw;
     if (nbase >= Np) return;
     if (m.dim == dp && lpr <= 64 && (m.ent_ld * ES) % 16 == 0 && ((uintptr_t)m.ent & 15) == 0) {
-        // unpadded, 16-byte aligned rows: ONE load per lane and row, four rows (groups of rows) requested together
+        // unpadded, 16-byte aligned rows: ONE load per lane and row, eight rows (groups of rows) requested together
         const int grp = lane / gl, lg = lane % gl;
-        uint4 v[4];
-        int64_t off[4];
+        uint4 v[KGE_TG_INFLIGHT];
+        int64_t off[KGE_TG_INFLIGHT];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < KGE_TG_INFLIGHT; ++u) {
             const int n = nbase + u * rpl + grp;
             off[u] = n < N ? (int64_t)neg[n] * m.ent_ld : -1;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < KGE_TG_INFLIGHT; ++u) {
             v[u] = make_uint4(0u, 0u, 0u, 0u);
             if (off[u] >= 0 && lg < lpr) v[u] = *(const uint4 *)((const char *)m.ent + off[u] * ES + lg * 16);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < KGE_TG_INFLIGHT; ++u) {
             const int n = nbase + u * rpl + grp;
             const bool live = n < Np && lg < lpr;
             if (live) *(uint4 *)((char *)T + ((int64_t)n * dp) * ES + lg * 16) = v[u];
@@ -349,12 +350,18 @@ __device__ __forceinline__ KgeRowFinish kge_rowfinish_row(const float4 *stat_par
     // merge the splits: m is the running maximum of x * log2(e) (x = a*s or s), l the sum of
     // exp(x - max), ac the sum of exp(x - max) * softplus(gamma + s)
     float m = -INFINITY, l = 0.f, ac = 0.f;
-    for (int s = 0; s < nsplit; ++s) {                      // fixed order
-        const float4 p = stat_part[(size_t)s * Bp + b];
-        if (p.x == -INFINITY) continue;
-        const float mn = fmaxf(m, p.x);
-        const float r0 = exp2f(m - mn), r1 = exp2f(p.x - mn);
-        l = l * r0 + p.y * r1; ac = ac * r0 + p.z * r1; m = mn;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {                // fixed order; eight loads in flight
+        float4 pv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) pv[u] = stat_part[(size_t)(s0 + u < nsplit ? s0 + u : nsplit - 1) * Bp + b];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float4 p = pv[u];
+            if (s0 + u >= nsplit || p.x == -INFINITY) continue;
+            const float mn = fmaxf(m, p.x);
+            const float r0 = exp2f(m - mn), r1 = exp2f(p.x - mn);
+            l = l * r0 + p.y * r1; ac = ac * r0 + p.z * r1; m = mn;
+        }
     }
     KgeRowFinish o;
     if (loss == KGE_LOGSIGMOID) {

@@ -314,11 +314,15 @@ __global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T
     __shared__ uint32_t s_wave[SMALL_NT / 64];
     // workgroups 0 .. nb0 - 1 take the first table, the next nb1 the second, ...: a table of up to SMALL_FEW ids is cut into
     // 32 parts (by the low five bits), a longer one into 256
-    int first = 0, ti = 0;
+    int first = 0, ti = SMALL_TABLES - 1;
+    bool found = false;
 #pragma unroll
-    for (int k = 0; k < SMALL_TABLES - 1; ++k) {
+    for (int k = 0; k < SMALL_TABLES - 1; ++k) {           // (the tables of a launch are packed from slot 0 on)
         const int nbk = T.t[k].M <= SMALL_FEW ? 32 : 256;
-        if (T.t[k].idx && (int)blockIdx.x >= first + nbk) { first += nbk; ti = k + 1; }
+        if (!found) {
+            if ((int)blockIdx.x < first + nbk) { ti = k; found = true; }
+            else first += nbk;
+        }
     }
     const SmallSort &S = T.t[ti];
     const int32_t *idx = S.idx;

@@ -242,12 +242,16 @@ def test_several_tables_in_one_call_give_the_bits_of_one_call_per_table():
     assert not bool((sets[0]["got"][0] == dev(_state(50000, 256, 40, True)[0])).all())     # something was updated
 
 
-def test_plans_of_several_tables_in_one_call_equal_one_call_per_table():
+@pytest.mark.parametrize("shapes", [
+    [(10_000_000, 64, 24576, "zipf"), (1000, 64, 9000, "same"), (200, 64, 4096, "zipf"), (77, 64, 0, "zipf")],
+    [(10_000_000, 64, 24576, "zipf"), (1000, 64, 4096, "zipf")],          # entities and relations of a training step
+    [(200, 64, 4096, "zipf"), (10_000_000, 64, 24576, "zipf"), (1000, 64, 100, "zipf"), (5000, 64, 8193, "zipf")],
+], ids=["long-same-short-empty", "entities-relations", "short-long-short-long"])
+def test_plans_of_several_tables_in_one_call_equal_one_call_per_table(shapes):
     """kge_sparse_adam_plan_tables against kge_sparse_adam_plan table by table, through the updates that read the plans:
     a long Zipf list, a list of one repeated id (longer than the list a workgroup orders in one step), a short list over
-    few rows (no bits left to order by), an empty one."""
+    few rows (no bits left to order by), an empty one; short and long lists in either order."""
     import paper_2211_12281_amd as kge
-    shapes = [(10_000_000, 64, 24576, "zipf"), (1000, 64, 9000, "same"), (200, 64, 4096, "zipf"), (77, 64, 0, "zipf")]
     dev = lambda a: torch.from_numpy(a.copy()).cuda()
     sets = []
     for k, (n_rows, d, M, kind) in enumerate(shapes):
@@ -265,6 +269,9 @@ def test_plans_of_several_tables_in_one_call_equal_one_call_per_table():
             one[tag + "_ws"] = kge.Workspace()
         sets.append(one)
     for s in sets:
+        # (the workspaces start cleared, so that nothing a call leaves unsorted can pass for sorted: position 0 everywhere)
+        for tag in ("ref_ws", "got_ws"):
+            s[tag].get(kge.workspace_bytes(kge.binding.OP_SPARSE_ADAM, None, max(1, s["idx"].numel()), s["d"])).zero_()
         if s["idx"].numel():
             kge.sparse_adam_plan(s["n_rows"], s["d"], s["idx"], s["ref_ws"])
             kge.sparse_adam_apply(s["ref"][0], None, s["ref"][1], s["ref"][2], s["grads"], s["ref_ws"], 2e-3, step=3)
