@@ -686,7 +686,11 @@ def main():
                 pass
     # the same box's own figures beside the published peaks: a loop of independent bf16 matrix instructions and a plain
     # 1 GiB streaming copy (after the timed region; a few milliseconds)
-    calib = {"mfma_bf16_loop_tflops": kge.calibrate_mfma(), "copy_gbs": kge.calibrate_copy(1 << 30)}
+    # (the loop also on operands whose signs and mantissas differ from element to element, as a table's do: the chip
+    # holds a lower clock the more bits toggle, so this, not the published peak, is what a kernel fed from real rows
+    # could reach if it did nothing but matrix instructions)
+    calib = {"mfma_bf16_loop_tflops": kge.calibrate_mfma(), "mfma_bf16_loop_tflops_varied_operands": kge.calibrate_mfma(varied=True),
+             "copy_gbs": kge.calibrate_copy(1 << 30)}
     # what two HIP events read when NOTHING lies between them: the share of a bracketed kernel's duration that is the
     # bracket's own (the rocprofv3 trace of the same command shows the kernel without it)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -702,6 +706,7 @@ def main():
         roof["frac_less_empty_pair"] = roof["frac"] * roof["avg_us"] / net
     if roof is not None and roof.get("achieved") is not None and roof["bound"] == "mfma" and wl_bf16(wl):
         roof["frac_of_measured_loop"] = roof["achieved"] / calib["mfma_bf16_loop_tflops"]
+        roof["frac_of_measured_loop_varied_operands"] = roof["achieved"] / calib["mfma_bf16_loop_tflops_varied_operands"]
     if roof is not None and isinstance(wl, TrainWorkload) and "block_fwd" in prof and "block_gradt" in prof and roof["bound"] == "mfma":
         # both passes together: the credited flops of the step (scores, dQ, dT: 3 contractions) over the two kernels' time
         us = prof["block_fwd"]["avg_us"] + prof["block_gradt"]["avg_us"]

@@ -418,16 +418,19 @@ int kge_profile_enable(int on);
 int kge_profile_collect(int slot, double *total_ms, int64_t *launches);
 
 /*
- * Two measured figures of the GPU for benchmarks that quote rooflines (not part of the method; both run their kernel
- * twice on the given stream, time the second run with HIP events and SYNCHRONISE the stream before they return):
+ * Measured figures of the GPU for benchmarks that quote rooflines (not part of the method; each runs its kernel
+ * twice on the given stream, times the second run with HIP events and SYNCHRONISES the stream before it returns):
  * kge_calibrate_mfma: the rate, in TFLOP/s, of 2,048 workgroups of 8 waves that each issue 4 x iters independent
  *   bf16 matrix instructions (32 x 32 x 16) on constant operands; sink: device memory of at least 2,048 x 512 floats
  *   (sink_elems says how many) that takes one value per lane; iters in [1, 2^20].
+ * kge_calibrate_mfma_varied: the same loop on operands whose signs and mantissas differ from element to element, as
+ *   those of embedding tables do (the chip lowers its clock with the number of bits that toggle; the sums stay finite).
  * kge_calibrate_copy: the rate, in GB/s read + written, of a plain 16-byte-per-lane copy of `bytes` bytes from src to dst
  *   (device memory, 16-byte aligned, bytes a multiple of 16, ranges must not overlap).
  * Errors: KGE_E_INVALID_ARG (nothing is launched), KGE_E_HIP.
  */
 int kge_calibrate_mfma(int32_t iters, float *sink, int64_t sink_elems, double *tflops_out, void *hip_stream);
+int kge_calibrate_mfma_varied(int32_t iters, float *sink, int64_t sink_elems, double *tflops_out, void *hip_stream);
 int kge_calibrate_copy(const void *src, void *dst, size_t bytes, double *gbs_out, void *hip_stream);
 
 /*

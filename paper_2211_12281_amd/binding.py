@@ -21,7 +21,7 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_encode", "kge_encode_bwd", "kge_encode_workspace_bytes", "kge_ensemble", "kge_sparse_adam_plan",
            "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit", "kge_debug_select",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
-           "kge_calibrate_mfma", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev",
+           "kge_calibrate_mfma", "kge_calibrate_mfma_varied", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev",
            "kge_sparse_adam_apply_tables", "kge_sparse_adam_plan_tables"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7, "gather": 8, "finish": 9}
@@ -91,6 +91,7 @@ def load():
         lib.kge_workspace_bytes.restype = C.c_size_t
         lib.kge_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
         lib.kge_calibrate_mfma.argtypes = [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        lib.kge_calibrate_mfma_varied.argtypes = [C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         lib.kge_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.kge_status_string.restype = C.c_char_p
         lib.kge_status_string.argtypes = [C.c_int]
@@ -402,11 +403,13 @@ def profile_collect(slot: str):
     return ms.value, n.value
 
 
-def calibrate_mfma(iters: int = 4096) -> float:
-    """TFLOP/s of a loop of independent bf16 matrix instructions on this GPU (synchronises the stream)."""
+def calibrate_mfma(iters: int = 4096, varied: bool = False) -> float:
+    """TFLOP/s of a loop of independent bf16 matrix instructions on this GPU (synchronises the stream); varied: on
+    operands whose signs and mantissas differ from element to element instead of constant ones."""
     sink = torch.empty(2048 * 512, dtype=torch.float32, device="cuda")
     out = C.c_double(0.0)
-    _check(load().kge_calibrate_mfma(iters, _ptr(sink), sink.numel(), C.byref(out), _stream()), "kge_calibrate_mfma")
+    fn = load().kge_calibrate_mfma_varied if varied else load().kge_calibrate_mfma
+    _check(fn(iters, _ptr(sink), sink.numel(), C.byref(out), _stream()), "kge_calibrate_mfma")
     return out.value
 
 

@@ -71,6 +71,8 @@ def test_calibration_calls_validate_their_arguments(lib):
     out = ctypes.c_double(0.0)
     assert lib.kge_calibrate_mfma(0, None, ctypes.c_int64(0), ctypes.byref(out), None) == -1
     assert lib.kge_calibrate_mfma(16, ctypes.c_void_p(4096), ctypes.c_int64(1000), ctypes.byref(out), None) == -1   # sink too small
+    assert lib.kge_calibrate_mfma_varied(0, None, ctypes.c_int64(0), ctypes.byref(out), None) == -1
+    assert lib.kge_calibrate_mfma_varied(16, ctypes.c_void_p(4096), ctypes.c_int64(1000), ctypes.byref(out), None) == -1
     assert lib.kge_calibrate_copy(None, None, ctypes.c_size_t(1 << 20), ctypes.byref(out), None) == -1
     assert lib.kge_calibrate_copy(ctypes.c_void_p(4096), ctypes.c_void_p(8200), ctypes.c_size_t(1 << 20), ctypes.byref(out),
                                   None) == -1                                                                      # unaligned
