@@ -161,7 +161,7 @@ __device__ __forceinline__ void kge_qbuild_body(int blk, const KgeQbuildArgs &a)
 // gather of the shared negatives: T[n] = ent[neg[n]], tn[n] = ||T[n]||^2 (zeros past N)
 // ---------------------------------------------------------------------------------------------
 // rows of the gathered block that one wave takes: a row of dp elements is covered by dp * ES / 16 lanes with 16 bytes
-// each; 64 / (that, rounded up to a power of two) rows share a load instruction, and EIGHT such loads are in flight per
+// each; 64 / (that, rounded up to a power of two) rows share a load instruction, and FOUR such loads are in flight per
 // lane (a random row costs a full memory round trip: the bytes in flight bound the rate of the gather)
 __host__ __device__ inline int kge_tgather_group_lanes(int dp, int es) {
     const int lpr = dp * es / 16;
@@ -169,7 +169,7 @@ __host__ __device__ inline int kge_tgather_group_lanes(int dp, int es) {
     while (gl < lpr) gl <<= 1;
     return gl < 64 ? gl : 64;
 }
-constexpr int KGE_TG_INFLIGHT = 8;                          // row loads in flight per lane
+constexpr int KGE_TG_INFLIGHT = 4;                          // row loads in flight per lane
 __host__ __device__ inline int kge_tgather_rows_per_wave(int dp, int es) { return KGE_TG_INFLIGHT * (64 / kge_tgather_group_lanes(dp, es)); }
 
 template <bool BF16>
@@ -182,7 +182,7 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
     const int nbase = (blk * (blockDim.x >> 6) + (threadIdx.x >> 6)) * rpw;
     if (nbase >= Np) return;
     if (m.dim == dp && lpr <= 64 && (m.ent_ld * ES) % 16 == 0 && ((uintptr_t)m.ent & 15) == 0) {
-        // unpadded, 16-byte aligned rows: ONE load per lane and row, eight rows (groups of rows) requested together
+        // unpadded, 16-byte aligned rows: ONE load per lane and row, four rows (groups of rows) requested together
         const int grp = lane / gl, lg = lane % gl;
         uint4 v[KGE_TG_INFLIGHT];
         int64_t off[KGE_TG_INFLIGHT];
