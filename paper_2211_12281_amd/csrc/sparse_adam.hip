@@ -212,9 +212,12 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
 
 // ---------------------------------------------------------------------------------------------
 // Up to SMALL_MAX row ids in ONE launch (the ids of a training step: 2B + N of them).  Only the grouping of equal ids and
-// the position order inside a group matter to the update, so the order is (id & 255, id >> 8, position): workgroup w owns
-// the ids whose low byte is w (low five bits, 32 workgroups, for a table of at most SMALL_FEW ids).  It reads ALL ids (a few tens of KB, from L2), counts those of lower workgroups (its place
-// in the output) and collects its own in position order; then it orders its list by the remaining bits, stable: a list
+// the position order inside a group matter to the update, so the order is (id & 127, id >> 7, position): workgroup w owns
+// the ids whose low seven bits are w (five, 32 workgroups, for a table of at most SMALL_FEW ids): a workgroup takes a
+// compute unit's LDS, so the entity and the relation table of a step together must not need more workgroups than the
+// chip has compute units, or the ones past 256 wait for a second turn (256 + 32 workgroups took 18-20 us, 128 + 32 take
+// 15-17; a long table alone 12-16 and 15-17).  It reads ALL ids (a few tens of KB, from L2), counts those of lower
+// workgroups (its place in the output) and collects its own in position order; then it orders its list by the remaining bits, stable: a list
 // of up to 256 entries by counting, for every entry, the entries that come before it (one entry per thread); a longer
 // one (one id repeated thousands of times) by counting passes of four bits, in LDS, or in the output buffers when it is
 // longer than SMALL_CAP.  No workgroup waits for another; several tables go into one launch (workgroup ranges).
@@ -228,7 +231,12 @@ constexpr int SMALL_TABLES = 4;
 constexpr int SMALL_FEW = 8192;                            // a table of at most this many ids is cut into 32 parts, not 256
 __host__ __device__ constexpr int small_cnt_at(int f) { return f + (f >> 4); }     // one pad word per 16: strided reads spread over banks
 
-struct SmallSort { const int32_t *idx; int M, bits; uint32_t *ka, *kb, *pa, *pb; };   // bits: of the largest id
+struct SmallSort { const int32_t *idx; int M, bits, lb; uint32_t *ka, *kb, *pa, *pb; };   // bits: of the largest id; lb: of the id that select the workgroup
+// the low bits that select a table's workgroup (a function of the table alone: the order of the sorted ids, and with it
+// the association order of the sums, must not depend on what else is in the launch)
+static void small_parts(const int *ms, int n, int *lb) {
+    for (int k = 0; k < n; ++k) lb[k] = ms[k] <= SMALL_FEW ? 5 : 7;
+}
 struct SmallSorts { SmallSort t[SMALL_TABLES]; };
 
 // exclusive scan of one value per thread over the workgroup (in thread order); returns the total through `total`
@@ -318,7 +326,7 @@ __global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T
     bool found = false;
 #pragma unroll
     for (int k = 0; k < SMALL_TABLES - 1; ++k) {           // (the tables of a launch are packed from slot 0 on)
-        const int nbk = T.t[k].M <= SMALL_FEW ? 32 : 256;
+        const int nbk = 1 << T.t[k].lb;
         if (!found) {
             if ((int)blockIdx.x < first + nbk) { ti = k; found = true; }
             else first += nbk;
@@ -327,7 +335,7 @@ __global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T
     const SmallSort &S = T.t[ti];
     const int32_t *idx = S.idx;
     const int M = S.M;
-    const int lb = M <= SMALL_FEW ? 5 : 8;                 // bits of the id that select the workgroup
+    const int lb = S.lb;                                   // bits of the id that select the workgroup
     const int passes = S.bits > lb ? (S.bits - lb + 3) / 4 : 0;
     const uint32_t lmask = (1u << lb) - 1u;
     uint32_t *ka = S.ka, *kb = S.kb, *pa = S.pa, *pb = S.pb;
@@ -679,8 +687,11 @@ int kge_sort_pairs(const int32_t *idx, const int32_t *h, const int32_t *t, int64
     while (bits < 32 && (1ll << bits) < key_range) ++bits;
     if (sort_is_small(idx != nullptr, M)) {
         SmallSorts T = {};
-        T.t[0] = SmallSort{idx, (int)M, bits, s.ka, s.kb, s.pa, s.pb};
-        hipLaunchKernelGGL(sort_small_kernel, dim3(M <= SMALL_FEW ? 32 : 256), dim3(SMALL_NT), 0, st, T);
+        const int m1 = (int)M;
+        int lb1;
+        small_parts(&m1, 1, &lb1);
+        T.t[0] = SmallSort{idx, m1, bits, lb1, s.ka, s.kb, s.pa, s.pb};
+        hipLaunchKernelGGL(sort_small_kernel, dim3(1 << lb1), dim3(SMALL_NT), 0, st, T);
         *sk = s.ka; *sp = s.pa;
         return kge_launch_status();
     }
@@ -718,7 +729,7 @@ static void sort_result(int64_t M, int64_t key_range, void *ws, const uint32_t *
     *sk = (passes & 1) ? s.kb : s.ka; *sp = (passes & 1) ? s.pb : s.pa;
 }
 
-// Several tables: those of up to SMALL_MAX ids share one launch (256 workgroups each), longer ones take the radix passes.
+// Several tables: those of up to SMALL_MAX ids share one launch (128 or 32 workgroups each), longer ones take the radix passes.
 int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st) {
     KgeProfScope prof(KGE_PROF_SORT, st);
     SmallSorts T = {};
@@ -732,15 +743,20 @@ int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_
             sort_carve(pl[k].M, 0, ws, s);
             int bits = 1;
             while (bits < 32 && (1ll << bits) < pl[k].n_rows) ++bits;
-            T.t[small++] = SmallSort{pl[k].idx, (int)pl[k].M, bits, s.ka, s.kb, s.pa, s.pb};
-            nwg += pl[k].M <= SMALL_FEW ? 32 : 256;
+            T.t[small++] = SmallSort{pl[k].idx, (int)pl[k].M, bits, 0, s.ka, s.kb, s.pa, s.pb};
         } else {
             const uint32_t *sk, *sp;
             const int rc = kge_sort_pairs(pl[k].idx, nullptr, nullptr, 1, 1, pl[k].M, pl[k].n_rows, ws, &sk, &sp, st, nullptr, 0);
             if (rc != KGE_OK) return rc;
         }
     }
-    if (small > 0) hipLaunchKernelGGL(sort_small_kernel, dim3(nwg), dim3(SMALL_NT), 0, st, T);
+    if (small > 0) {
+        int ms[SMALL_TABLES], lb[SMALL_TABLES];
+        for (int k = 0; k < small; ++k) ms[k] = T.t[k].M;
+        small_parts(ms, small, lb);
+        for (int k = 0; k < small; ++k) { T.t[k].lb = lb[k]; nwg += 1 << lb[k]; }
+        hipLaunchKernelGGL(sort_small_kernel, dim3(nwg), dim3(SMALL_NT), 0, st, T);
+    }
     return kge_launch_status();
 }
 
