@@ -212,21 +212,23 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
 
 // ---------------------------------------------------------------------------------------------
 // Up to SMALL_MAX row ids in ONE launch (the ids of a training step: 2B + N of them).  Only the grouping of equal ids and
-// the position order inside a group matter to the update, so the order is (id & 127, id >> 7, position): workgroup w owns
-// the ids whose low seven bits are w (five, 32 workgroups, for a table of at most SMALL_FEW ids): a workgroup takes a
-// compute unit's LDS, so the entity and the relation table of a step together must not need more workgroups than the
-// chip has compute units, or the ones past 256 wait for a second turn (256 + 32 workgroups took 18-20 us, 128 + 32 take
-// 15-17; a long table alone 12-16 and 15-17).  It reads ALL ids (a few tens of KB, from L2), counts those of lower
-// workgroups (its place in the output) and collects its own in position order; then it orders its list by the remaining bits, stable: a list
+// the position order inside a group matter to the update, so the order is (id & 255, id >> 8, position): workgroup w owns
+// the ids whose low byte is w (low five bits, 32 workgroups, for a table of at most SMALL_FEW ids).  Two workgroups share
+// a compute unit (66 KB of LDS, 64 registers), so that the 256 + 32 workgroups of a step's entity and relation table run
+// in one turn (with the LDS of a whole compute unit each, the 32 past the 256th waited for a second turn: 18-20 us
+// instead of 14-18).  It reads ALL ids (a few tens of KB, from L2), counts those of lower workgroups (its place in the
+// output) and collects its own in position order; then it orders its list by the remaining bits, stable: a list
 // of up to 256 entries by counting, for every entry, the entries that come before it (one entry per thread); a longer
 // one (one id repeated thousands of times) by counting passes of four bits, in LDS, or in the output buffers when it is
 // longer than SMALL_CAP.  No workgroup waits for another; several tables go into one launch (workgroup ranges).
 // ---------------------------------------------------------------------------------------------
 constexpr int SMALL_MAX = 32768;
-constexpr int SMALL_CAP = 4096;
+constexpr int SMALL_CAP = 3072;                             // longest list that is ordered in LDS
 constexpr int SMALL_NT = 1024;                              // threads of a workgroup
 constexpr int SMALL_ROUNDS = SMALL_MAX / (4 * SMALL_NT);    // rounds of SMALL_NT threads x 4 consecutive ids
 constexpr int SMALL_DIRECT = 256;                           // longest list that is ordered by counting predecessors
+constexpr int SMALL_PT = 256;                               // threads that take part in a counting pass (a rare path: its
+                                                            // counters are kept small so that two workgroups share a compute unit)
 constexpr int SMALL_TABLES = 4;
 constexpr int SMALL_FEW = 8192;                            // a table of at most this many ids is cut into 32 parts, not 256
 __host__ __device__ constexpr int small_cnt_at(int f) { return f + (f >> 4); }     // one pad word per 16: strided reads spread over banks
@@ -235,7 +237,7 @@ struct SmallSort { const int32_t *idx; int M, bits, lb; uint32_t *ka, *kb, *pa, 
 // the low bits that select a table's workgroup (a function of the table alone: the order of the sorted ids, and with it
 // the association order of the sums, must not depend on what else is in the launch)
 static void small_parts(const int *ms, int n, int *lb) {
-    for (int k = 0; k < n; ++k) lb[k] = ms[k] <= SMALL_FEW ? 5 : 7;
+    for (int k = 0; k < n; ++k) lb[k] = ms[k] <= SMALL_FEW ? 5 : 8;
 }
 struct SmallSorts { SmallSort t[SMALL_TABLES]; };
 
@@ -259,31 +261,36 @@ __device__ __forceinline__ uint32_t small_block_scan(uint32_t v, uint32_t *s_wav
 }
 
 // One stable counting pass over a list of n (key, position) pairs by the four key bits at `shift`: thread t owns the
-// contiguous piece [t c, (t + 1) c) of the list, c = ceil(n / SMALL_NT), and moves through it eight entries at a time
+// contiguous piece [t c, (t + 1) c) of the list, c = ceil(n / SMALL_PT), t < SMALL_PT, and moves through it eight entries at a time
 // (eight loads in flight: the list may lie in global memory).  dst_off is added to every destination index.
 __device__ __forceinline__ void small_pass(const uint32_t *sk, const uint32_t *sp, uint32_t *dk, uint32_t *dp, int n, int shift,
                                            int dst_off, uint32_t *s_cnt, uint32_t *s_wave) {
     const int tid = threadIdx.x;
-    const int c = (n + SMALL_NT - 1) / SMALL_NT, lo = tid * c < n ? tid * c : n, hi = lo + c < n ? lo + c : n;
+    const bool part = tid < SMALL_PT;                      // (the other threads only help with the scan and the barriers)
+    const int c = (n + SMALL_PT - 1) / SMALL_PT, lo = !part ? n : (tid * c < n ? tid * c : n), hi = lo + c < n ? lo + c : n;
+    if (part) {
 #pragma unroll
-    for (int d = 0; d < 16; ++d) s_cnt[small_cnt_at(d * SMALL_NT + tid)] = 0;
+        for (int d = 0; d < 16; ++d) s_cnt[small_cnt_at(d * SMALL_PT + tid)] = 0;
+    }
     for (int e = lo; e < hi; e += 8) {
         uint32_t k[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) k[u] = e + u < hi ? sk[e + u] : 0u;
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            if (e + u < hi) s_cnt[small_cnt_at((int)((k[u] >> shift) & 15u) * SMALL_NT + tid)] += 1;      // own slots only
+            if (e + u < hi) s_cnt[small_cnt_at((int)((k[u] >> shift) & 15u) * SMALL_PT + tid)] += 1;      // own slots only
     }
     __syncthreads();
     // counters in (digit, thread) order: thread t scans the 16 consecutive ones at 16 t
     uint32_t v[16], sum = 0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) { v[j] = s_cnt[small_cnt_at(tid * 16 + j)]; sum += v[j]; }
+    for (int j = 0; j < 16; ++j) { v[j] = part ? s_cnt[small_cnt_at(tid * 16 + j)] : 0u; sum += v[j]; }
     uint32_t total;
     uint32_t run = small_block_scan(sum, s_wave, total);
+    if (part) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) { s_cnt[small_cnt_at(tid * 16 + j)] = run; run += v[j]; }
+        for (int j = 0; j < 16; ++j) { s_cnt[small_cnt_at(tid * 16 + j)] = run; run += v[j]; }
+    }
     __syncthreads();
     for (int e = lo; e < hi; e += 8) {
         uint32_t k[8], q[8];
@@ -292,7 +299,7 @@ __device__ __forceinline__ void small_pass(const uint32_t *sk, const uint32_t *s
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             if (e + u < hi) {
-                const int slot = small_cnt_at((int)((k[u] >> shift) & 15u) * SMALL_NT + tid);
+                const int slot = small_cnt_at((int)((k[u] >> shift) & 15u) * SMALL_PT + tid);
                 const uint32_t at = s_cnt[slot];
                 s_cnt[slot] = at + 1;
                 dk[dst_off + (int)at] = k[u]; dp[dst_off + (int)at] = q[u];
@@ -314,8 +321,8 @@ __device__ __forceinline__ bool small_pass_trivial(const uint32_t *sk, const uin
     return true;
 }
 
-__global__ __launch_bounds__(SMALL_NT) void sort_small_kernel(const SmallSorts T) {
-    __shared__ uint32_t s_cnt[16 * SMALL_NT + SMALL_NT];
+__global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgpu_waves_per_eu(8, 8))) void sort_small_kernel(const SmallSorts T) {
+    __shared__ uint32_t s_cnt[16 * SMALL_PT + SMALL_PT];
     __shared__ uint32_t s_rc[SMALL_ROUNDS * (SMALL_NT / 64)];   // own ids of every (round, wave), then their offsets
     __shared__ __attribute__((aligned(16))) uint32_t s_key[2][SMALL_CAP];
     __shared__ uint32_t s_pos[2][SMALL_CAP];
@@ -729,7 +736,7 @@ static void sort_result(int64_t M, int64_t key_range, void *ws, const uint32_t *
     *sk = (passes & 1) ? s.kb : s.ka; *sp = (passes & 1) ? s.pb : s.pa;
 }
 
-// Several tables: those of up to SMALL_MAX ids share one launch (128 or 32 workgroups each), longer ones take the radix passes.
+// Several tables: those of up to SMALL_MAX ids share one launch (256 or 32 workgroups each), longer ones take the radix passes.
 int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st) {
     KgeProfScope prof(KGE_PROF_SORT, st);
     SmallSorts T = {};
