@@ -428,13 +428,10 @@ EncGemm enc_gemm_desc(const void *A, int64_t lda_b, bool gather, const int32_t *
 
 int enc_launch_pair(bool bf16, const EncGemm &g0, const EncGemm &g1, hipStream_t st) {
     // the ring of stages is larger than the default dynamic limit
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)enc_gemm_nt_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, ENC_LDS_BYTES) != hipSuccess ||
-            hipFuncSetAttribute((const void *)enc_gemm_nt_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, ENC_LDS_BYTES) != hipSuccess)
-            return KGE_E_HIP;
-        attr_done = true;
-    }
+    static KgeLdsLimit lim_bf16, lim_f32;
+    if (lim_bf16.set((const void *)enc_gemm_nt_kernel<true>, ENC_LDS_BYTES) != KGE_OK ||
+        lim_f32.set((const void *)enc_gemm_nt_kernel<false>, ENC_LDS_BYTES) != KGE_OK)
+        return KGE_E_HIP;
     EncGemmPair pr{};
     pr.g[0] = g0; pr.g[1] = g1;
     pr.wgs0 = g0.tiles_m * g0.tiles_n * g0.nsplit;
@@ -524,15 +521,14 @@ int kge_run_encode_bwd(const kge_encoder_t &e, const int32_t *h, const int32_t *
         }
     }
     // the row kernels stage 32 rows in the LDS: more than the default dynamic limit for long rows
-    static bool attr_done = false;
-    if (!attr_done) {
+    static KgeLdsLimit lim_rows_bf16, lim_rows_f32, lim_gt_bf16, lim_gt_f32;
+    {
         const int big = 32 * (1024 + 1) * 4;
-        if (hipFuncSetAttribute((const void *)enc_bwd_rows_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, big) != hipSuccess ||
-            hipFuncSetAttribute((const void *)enc_bwd_rows_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, big) != hipSuccess ||
-            hipFuncSetAttribute((const void *)enc_gather_t_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, big) != hipSuccess ||
-            hipFuncSetAttribute((const void *)enc_gather_t_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, big) != hipSuccess)
+        if (lim_rows_bf16.set((const void *)enc_bwd_rows_kernel<true>, big) != KGE_OK ||
+            lim_rows_f32.set((const void *)enc_bwd_rows_kernel<false>, big) != KGE_OK ||
+            lim_gt_bf16.set((const void *)enc_gather_t_kernel<true>, big) != KGE_OK ||
+            lim_gt_f32.set((const void *)enc_gather_t_kernel<false>, big) != KGE_OK)
             return KGE_E_HIP;
-        attr_done = true;
     }
     const EncRowArgs a = enc_row_args(e, h, t, B, neg, N, seed, step);
     if (p.n > 0) {

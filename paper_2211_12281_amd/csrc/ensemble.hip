@@ -115,12 +115,8 @@ int kge_run_ensemble(const int32_t *lists, int M, int64_t Q, int K, double p, in
     int n2 = 256;
     while (n2 < M * K) n2 <<= 1;
     const int lds = n2 * 16;
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)ens_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ENS_MAX_ENTRIES * 16) != hipSuccess)
-            return KGE_E_HIP;
-        attr_done = true;
-    }
+    static KgeLdsLimit lds_limit;
+    if (lds_limit.set((const void *)ens_kernel, ENS_MAX_ENTRIES * 16) != KGE_OK) return KGE_E_HIP;
     hipLaunchKernelGGL(ens_kernel, dim3((unsigned)Q), dim3(256), lds, st, lists, M, Q, K, n2, tm, K_out, out_idx, out_score);
     return kge_launch_status();
 }

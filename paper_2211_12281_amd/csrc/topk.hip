@@ -957,12 +957,8 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
     // spread over nsplit x 2 private areas of TK_HALF entries.
     int64_t seen = 0;
     const int compact_lds = TK_SORTCAP * 8;
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void *)topk_compact_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, compact_lds) != hipSuccess)
-            return KGE_E_HIP;
-        attr_done = true;
-    }
+    static KgeLdsLimit compact_limit;
+    if (compact_limit.set((const void *)topk_compact_kernel, compact_lds) != KGE_OK) return KGE_E_HIP;
     while (seen < total_tiles) {
         int64_t tiles = seen == 0 ? (p.nseg * (TK_HALF / TK_ST) < 128 ? p.nseg * (TK_HALF / TK_ST) : 128) : 3 * seen;
         if (tiles > total_tiles - seen) tiles = total_tiles - seen;
