@@ -223,7 +223,14 @@ class TrainWorkload:
             for q, gm in zip(self.mproj, (g_mh, g_mt)):
                 kge.sparse_adam(q["p"], q["sh"], q["m"], q["v"], self.rows_d, gm, lr, step=i + 1)
         else:
-            raise AssertionError("unreachable: the plain step is enqueued by _enqueue")
+            # batches drawn by the sampler: the ids that the update sorts are the ones kge_loss_bwd lists beside its gradient rows
+            kge.loss_bwd(self.model, self.P["loss"], h, r, t, self.neg, out=self.out, stream=self.main, **self.loss_kw)
+            plans = [(self.n_ent, self.d, self.out["g_ent_idx"], self.ws_ent), (self.n_rel, self.rel.shape[1], r, self.ws_rel)]
+            if self.relw is not None:
+                plans.append((self.n_rel, self.d, r, self.ws_relw))
+            kge.sparse_adam_plan_tables(plans, stream=self.main)
+            kge.sparse_adam_apply_tables(self._tables(), lr, step=i + 1, stream=self.main)
+            return
         kge.sparse_adam(self.rel, self.rel_sh, self.rel_m, self.rel_v, self.out["g_rel_idx"], self.out["g_rel"], lr,
                         step=i + 1)
         if self.relw is not None:
