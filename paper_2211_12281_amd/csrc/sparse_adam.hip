@@ -219,8 +219,9 @@ __device__ __forceinline__ void adam_apply(uint32_t key, int col, float4 g, int6
 // instead of 14-18).  It reads ALL ids (a few tens of KB, from L2), counts those of lower workgroups (its place in the
 // output) and collects its own in position order; then it orders its list by the remaining bits, stable: a list
 // of up to 256 entries by counting, for every entry, the entries that come before it (one entry per thread); a longer
-// one (one id repeated thousands of times) by counting passes of four bits, in LDS, or in the output buffers when it is
-// longer than SMALL_CAP.  No workgroup waits for another; several tables go into one launch (workgroup ranges).
+// one (one id repeated thousands of times) after its dominant id has been split off, or, if what remains is still longer,
+// by counting passes of four bits; the list lies in LDS, or in the second pair of output buffers when it is longer than
+// SMALL_CAP.  No workgroup waits for another; several tables go into one launch (workgroup ranges).
 // ---------------------------------------------------------------------------------------------
 constexpr int SMALL_MAX = 32768;
 constexpr int SMALL_CAP = 3072;                             // longest list that is ordered in LDS
@@ -397,8 +398,9 @@ __global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgp
     if (n == 0) return;                                    // (uniform: every thread holds the same totals)
     // the list starts where `passes` exchanges of buffers end in (ka, pa); in LDS the last step writes (ka, pa) itself
     const bool in_lds = n <= SMALL_CAP;
-    uint32_t *lk = in_lds ? (passes == 0 ? ka + base : s_key[0]) : ((passes & 1) ? kb : ka) + base;
-    uint32_t *lp = in_lds ? (passes == 0 ? pa + base : s_pos[0]) : ((passes & 1) ? pb : pa) + base;
+    // the list is collected in LDS, or, when it is longer than SMALL_CAP, in the second pair of output buffers
+    uint32_t *lk = in_lds ? (passes == 0 ? ka + base : s_key[0]) : kb + base;
+    uint32_t *lp = in_lds ? (passes == 0 ? pa + base : s_pos[0]) : pb + base;
 #pragma unroll
     for (int r = 0; r < SMALL_ROUNDS; ++r) {
         if (r < rounds) {
@@ -433,63 +435,95 @@ __global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgp
             for (int j = n4; j < n; ++j) { const uint32_t kj = s_key[0][j]; rank += kj < key || (kj == key && j < tid); }
             ka[base + rank] = key; pa[base + rank] = s_pos[0][tid];
         }
-    } else if (in_lds) {
+    } else {
         // A long list is usually ONE id repeated (Zipf's hottest rows): the entries with that id keep their order as one
         // group, and only the others are ordered - by counting predecessors among themselves - and placed before or
         // behind the group.  (Which id is taken only decides how fast this is.)
         // the most frequent id among the list's first 64 entries (ties: the earliest), found by every wave for itself
-        const uint32_t mine = s_key[0][lane];
+        const uint32_t mine = lk[lane];
         int votes = 0;
         for (int j = 0; j < 64; ++j) votes += mine == (uint32_t)__builtin_amdgcn_readlane((int)mine, j);
         int best = (votes << 6) | (63 - lane);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) { const int other = __shfl_xor(best, o); best = other > best ? other : best; }
         const uint32_t hot = (uint32_t)__builtin_amdgcn_readlane((int)mine, 63 - (best & 63));
-        constexpr int PER = SMALL_CAP / SMALL_NT;          // list entries per thread, in list order: thread t has t PER .. + PER - 1
-        uint32_t mk[PER], mp[PER];
-        int cold = 0, less = 0;
+        // wave v takes the contiguous piece [v cw, (v + 1) cw) of the list, 64 consecutive entries per step (coalesced: the
+        // list may lie in global memory), twice: to count, then to place; ranks inside a step come from ballots
+        constexpr int NW = SMALL_NT / 64;
+        const int cw = ((n + NW - 1) / NW + 63) & ~63, wlo = wave * cw < n ? wave * cw : n, whi = wlo + cw < n ? wlo + cw : n;
+        int cold = 0, less = 0;                            // of the wave (the same in every lane)
+        for (int e0 = wlo; e0 < whi; e0 += 512) {
+            uint32_t k[8];
 #pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int e = tid * PER + u;
-            mk[u] = e < n ? s_key[0][e] : hot; mp[u] = e < n ? s_pos[0][e] : 0u;
-            cold += mk[u] != hot; less += mk[u] < hot;
+            for (int u = 0; u < 8; ++u) { const int e = e0 + 64 * u + lane; k[u] = e < whi ? lk[e] : hot; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                cold += __builtin_popcountll(__ballot(k[u] != hot));
+                less += __builtin_popcountll(__ballot(k[u] < hot));
+            }
         }
-        uint32_t n_cold, n_less;
-        const uint32_t cold_at = small_block_scan((uint32_t)cold, s_wave, n_cold);
-        (void)small_block_scan((uint32_t)less, s_wave, n_less);
-        if ((int)n_cold <= SMALL_DIRECT) {                 // (uniform)
-            const int hot_at = tid * PER - (int)cold_at;   // entries of the group before this thread's
-            int ci = (int)cold_at, hi = 0;
+        __syncthreads();                                   // (s_rc is free: the list has been collected)
+        if (lane == 0) { s_rc[wave] = (uint32_t)cold; s_rc[NW + wave] = (uint32_t)less; }
+        __syncthreads();
+        int cold_at = 0, n_cold = 0, n_less = 0;           // cold entries of lower waves; totals
 #pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                const int e = tid * PER + u;
-                if (e < n) {
-                    if (mk[u] != hot) { s_key[1][ci] = mk[u]; s_pos[1][ci] = mp[u]; ++ci; }
-                    else { const int at = base + (int)n_less + hot_at + hi; ka[at] = hot; pa[at] = mp[u]; ++hi; }
+        for (int v = 0; v < NW; ++v) {
+            const int cv = (int)s_rc[v];
+            cold_at += v < wave ? cv : 0; n_cold += cv; n_less += (int)s_rc[NW + v];
+        }
+        if (n_cold <= SMALL_DIRECT) {                      // (uniform)
+            int ci = cold_at;                              // cold entries before the step
+            for (int e0 = wlo; e0 < whi; e0 += 512) {
+                uint32_t k[8], q[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + 64 * u + lane;
+                    k[u] = e < whi ? lk[e] : hot; q[u] = e < whi ? lp[e] : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + 64 * u + lane;
+                    const bool is_cold = k[u] != hot;
+                    const uint64_t mc = __ballot(is_cold);
+                    const int mine_at = ci + __builtin_popcountll(mc & below);          // cold entries before this one
+                    if (e < whi) {
+                        if (is_cold) { s_key[1][mine_at] = k[u]; s_pos[1][mine_at] = q[u]; }
+                        else { const int at = base + n_less + e - mine_at; ka[at] = hot; pa[at] = q[u]; }
+                    }
+                    ci += __builtin_popcountll(mc);
                 }
             }
             __syncthreads();
-            const int nc = (int)n_cold, n_hot = n - nc;
+            const int nc = n_cold, n_hot = n - nc;
             if (tid < nc) {
                 const uint32_t key = s_key[1][tid];
                 int rank = 0;
                 for (int j = 0; j < nc; ++j) { const uint32_t kj = s_key[1][j]; rank += kj < key || (kj == key && j < tid); }
-                const int at = base + rank + (key > hot ? n_hot : 0);
-                ka[at] = key; pa[at] = s_pos[1][tid];
+                const int to = base + rank + (key > hot ? n_hot : 0);
+                ka[to] = key; pa[to] = s_pos[1][tid];
             }
             return;
         }
-        for (int p = 0; p < passes; ++p) {
-            const bool last = p == passes - 1;
-            small_pass(s_key[p & 1], s_pos[p & 1], last ? ka : s_key[(p + 1) & 1], last ? pa : s_pos[(p + 1) & 1], n, lb + 4 * p,
-                       last ? base : 0, s_cnt, s_wave);
-        }
-    } else {
-        uint32_t *k0 = lk, *p0 = lp, *k1 = ((passes & 1) ? ka : kb) + base, *p1 = ((passes & 1) ? pa : pb) + base;
-        for (int p = 0; p < passes; ++p) {
-            if (!small_pass_trivial(k0, p0, k1, p1, n, lb + 4 * p)) small_pass(k0, p0, k1, p1, n, lb + 4 * p, 0, s_cnt, s_wave);
-            uint32_t *tk = k0; k0 = k1; k1 = tk;
-            tk = p0; p0 = p1; p1 = tk;
+        if (in_lds) {
+            for (int p = 0; p < passes; ++p) {
+                const bool last = p == passes - 1;
+                small_pass(s_key[p & 1], s_pos[p & 1], last ? ka : s_key[(p + 1) & 1], last ? pa : s_pos[(p + 1) & 1], n, lb + 4 * p,
+                           last ? base : 0, s_cnt, s_wave);
+            }
+        } else {
+            // between the two pairs of output buffers, ending in (ka, pa): an even number of passes starts there (one copy)
+            uint32_t *k0 = lk, *p0 = lp, *k1 = ka + base, *p1 = pa + base;
+            if (!(passes & 1)) {
+                for (int e = tid; e < n; e += SMALL_NT) { k1[e] = k0[e]; p1[e] = p0[e]; }
+                __syncthreads();
+                uint32_t *tk = k0; k0 = k1; k1 = tk;
+                tk = p0; p0 = p1; p1 = tk;
+            }
+            for (int p = 0; p < passes; ++p) {
+                if (!small_pass_trivial(k0, p0, k1, p1, n, lb + 4 * p)) small_pass(k0, p0, k1, p1, n, lb + 4 * p, 0, s_cnt, s_wave);
+                uint32_t *tk = k0; k0 = k1; k1 = tk;
+                tk = p0; p0 = p1; p1 = tk;
+            }
         }
     }
 }
