@@ -115,6 +115,29 @@ def test_long_runs_of_equal_ids(orc, runs):
     assert norm_err(gm[touched], rm[touched]) <= RTOL_F32 and norm_err(gv[touched], rv[touched]) <= RTOL_F32
 
 
+@pytest.mark.parametrize("n_rows", [4096, 65536, 1 << 21])
+def test_one_list_of_several_long_runs(orc, n_rows):
+    """Ids that all fall into ONE list of the one-launch sort (the same low byte), longer than the list kept in LDS, with
+    two long runs and hundreds of other ids - no single id to split off leaves a short remainder, so the list is ordered
+    by counting passes over the output buffers (an odd and an even number of them, by the width of the ids)."""
+    import paper_2211_12281_amd as kge
+    g = np.random.default_rng(77)
+    same_byte = 5 + 256 * np.arange(n_rows // 256)
+    others = g.choice(same_byte[2:], 700)
+    idx = np.concatenate([np.full(1900, same_byte[0]), others[:350], np.full(2100, same_byte[1]), others[350:]]).astype(np.int32)
+    idx = idx[g.permutation(idx.size)]
+    d = 32
+    theta, m, v = _state(n_rows, d, 5, True)
+    grads = (g.normal(size=(idx.size, d)) * 1e-2).astype(F)
+    dth, dm, dv = [torch.from_numpy(a.copy()).cuda() for a in (theta, m, v)]
+    kge.sparse_adam(dth, None, dm, dv, torch.from_numpy(idx).cuda(), torch.from_numpy(grads).cuda(), 1e-3, step=3)
+    rth, rm, rv, touched = orc.sparse_adam(theta, m, v, idx, grads, float(F(1e-3)), float(F(0.9)), float(F(0.999)), float(F(1e-8)), 3)
+    gth, gm, gv = dth.cpu().numpy(), dm.cpu().numpy(), dv.cpu().numpy()
+    assert np.array_equal(gth[~touched], theta[~touched])
+    assert update_err_ok(gth[touched], theta[touched], rth[touched])
+    assert norm_err(gm[touched], rm[touched]) <= RTOL_F32 and norm_err(gv[touched], rv[touched]) <= RTOL_F32
+
+
 def test_padded_row_stride(orc):
     """Tables whose row stride exceeds dim (ld > dim): padding columns stay untouched."""
     import paper_2211_12281_amd as kge
