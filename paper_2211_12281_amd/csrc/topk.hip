@@ -239,8 +239,12 @@ void topk_scan_kernel(const TopkArgs a) {
 #pragma unroll
         for (int ob = 0; ob < NQ; ++ob) {
             if (a.true_t) {
+                // v > vt exactly when vt - v is negative: the sign bits are shifted into one word (one subtraction and
+                // one funnel shift per entry, no compare results through scalar registers) and counted at the end
+                uint32_t signs = 0;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) above[ob] += vv[ob][i] > vt[ob] ? 1u : 0u;
+                for (int i = 0; i < 16; ++i) signs = __builtin_amdgcn_alignbit(signs, __float_as_uint(vt[ob] - vv[ob][i]), 31);
+                above[ob] += (uint32_t)__builtin_popcount(signs);
             }
             float mx = vv[ob][0];
 #pragma unroll
