@@ -641,6 +641,10 @@ def main():
                 # says that the path is not on the fp32 pipe); the 16-bit pipe does three times that work, against
                 # its own peak:
                 roof["issued_f16"] = {"achieved": 3 * ach, "peak": PEAK_BF16_TFLOPS, "frac": 3 * ach / PEAK_BF16_TFLOPS}
+            if dom in ("block_fwd", "block_gradt") and not wl.bf16 and (wl.d * 4 <= 512 or dom == "block_gradt"):
+                # fp32 training passes: every operand value as three bf16 pieces, six bf16 matrix products per fp32 one
+                # (all terms down to 2^-26 of |a| |b|); priced like the fp32 score block above
+                roof["issued_bf16"] = {"achieved": 6 * ach, "peak": PEAK_BF16_TFLOPS, "frac": 6 * ach / PEAK_BF16_TFLOPS}
         else:
             roof = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": None, "traffic": None, "avg_us": avg_s * 1e6}

@@ -69,6 +69,47 @@ __device__ __forceinline__ uint32_t kge_pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// fp32 operands on the bf16 matrix pipe.  The fp32 MFMA of gfx950 runs at 1/16 of the bf16 rate, so the fp32 passes
+// whose registers allow it (KgeBlockCfg::X3) split every operand value into THREE bf16 pieces, x = x0 + x1 + x2 with x0 = bf16(x), x1 = bf16(x - x0),
+// x2 = bf16(x - x0 - x1) (round to nearest; 8 significand bits each, |x1| <= 2^-9 |x|, |x2| <= 2^-18 |x|; the bf16
+// exponent range is that of fp32, so no scaling is needed), and accumulate the six products of total order <= 2 in
+// fp32: a.b = a0 b0 + a0 b1 + a1 b0 + a1 b1 + a0 b2 + a2 b0 + O(2^-26 |a| |b|).  Six 32x32x16 bf16 MFMAs (192 cycles)
+// replace the eight 32x32x2 fp32 ones (512 cycles) of sixteen k-steps.
+// Eight values of a lane (two 16-byte fragments: slot j of lane half g of both operands is one contraction index,
+// whatever its number) become three bf16 fragments.
+struct KgeP3 { uint4 p[3]; };
+__device__ __forceinline__ KgeP3 kge_split3(uint4 a, uint4 b) {
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    uint32_t q[3][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float x0 = __uint_as_float(w[2 * i]), x1 = __uint_as_float(w[2 * i + 1]);
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) {
+            const uint32_t pk = kge_pack_bf16x2(x0, x1);
+            q[pl][i] = pk;
+            if (pl < 2) { x0 -= __uint_as_float(pk << 16); x1 -= __uint_as_float(pk & 0xffff0000u); }
+        }
+    }
+    KgeP3 r;
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) r.p[pl] = make_uint4(q[pl][0], q[pl][1], q[pl][2], q[pl][3]);
+    return r;
+}
+// acc += A . B over the sixteen contraction indices of two fragment pairs (smallest terms first)
+__device__ __forceinline__ kge_f32x16 kge_mma3(kge_f32x16 acc, const KgeP3 &A, const KgeP3 &B) {
+    auto mm = [](kge_f32x16 c, uint4 x, uint4 y) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(kge_bf16x8, x), __builtin_bit_cast(kge_bf16x8, y), c, 0, 0, 0);
+    };
+    acc = mm(acc, A.p[0], B.p[2]);
+    acc = mm(acc, A.p[2], B.p[0]);
+    acc = mm(acc, A.p[1], B.p[1]);
+    acc = mm(acc, A.p[0], B.p[1]);
+    acc = mm(acc, A.p[1], B.p[0]);
+    acc = mm(acc, A.p[0], B.p[0]);
+    return acc;
+}
+
 // Asynchronous global -> LDS copies: lane l of a wave-wide instruction writes its 16 (4) bytes to LDS
 // byte address m0 + 16 l (4 l).  Completion is tracked by vmcnt; the compiler does not see these
 // loads, so the waits are explicit.
@@ -127,6 +168,12 @@ struct KgeBlockCfg {
     static constexpr int SIDE_SLOT = OWN_ROW ? 4 * 256 : 4 * 1024;   // per-wave copies of the tile's side info
     // Workgroups per compute unit (= waves per SIMD): two where a workgroup's registers fit in 256, so that
     // the MFMA, LDS and vector phases of one workgroup run under those of the other.
+    // fp32 training passes that contract bf16 pieces (kge_split3 / kge_mma3): the own operand's pieces take 1.5 times the
+    // registers of its fp32 fragments, which the pass over the queries has only for rows of up to 512 bytes (measured, rows
+    // of 1,024 bytes: pass over the negatives 550 -> 461 us, pass over the queries 589 -> 727 us with 170-320 bytes of
+    // scratch).  The score block of this kernel stays on the fp32 instructions: kge_score on fp32 tables runs
+    // block_f32h2_score.hip, and this one is what that is compared with.
+    static constexpr bool X3 = !BF16 && ((MODE == KGE_MODE_FWD && RB <= 512) || MODE == KGE_MODE_GRADT);
     static constexpr int OCC = kge_block_occ(BF16, RB, TRANSH, MODE);
     static constexpr int LDS_MAX = 160 * 1024 / OCC;
     static constexpr int NSTAGE_RAW = (LDS_MAX - SIDE_SLOT) / (STAGE_BYTES + SIDE_SLOT);   // n stages + (n+1) side slots fit
@@ -288,6 +335,20 @@ void kge_block_kernel(const KgeBlockArgs a) {
         asm volatile("" : "+v"(o_qn[h]), "+v"(o_c[h]), "+v"(o_wn[h]), "+v"(o_tn[h]));
     }
 
+    // the own operand as bf16 pieces, two k-steps per entry (the fp32 fragments are not used again)
+    constexpr bool X3 = C::X3;
+    KgeP3 ownp[X3 ? OW : 1][X3 ? C::KS / 2 : 1], ownwp[(X3 && TRANSH && OWN_ROW) ? C::KS / 2 : 1];
+    if constexpr (X3) {
+#pragma unroll
+        for (int h = 0; h < OW; ++h)
+#pragma unroll
+            for (int k2 = 0; k2 < C::KS / 2; ++k2) ownp[h][k2] = kge_split3(own[h][2 * k2], own[h][2 * k2 + 1]);
+        if constexpr (TRANSH && OWN_ROW) {
+#pragma unroll
+            for (int k2 = 0; k2 < C::KS / 2; ++k2) ownwp[k2] = kge_split3(ownw[2 * k2], ownw[2 * k2 + 1]);
+        }
+    }
+
     // ---- state of the tile in work (set by the loops below, used by the pieces) -------------------
     int tile = t0;
     const char *base = lds, *side = side_ring;
@@ -304,7 +365,8 @@ void kge_block_kernel(const KgeBlockArgs a) {
     };
     kge_f32x16 acc[OW], accw;                              // phase-1 accumulators: [stream, own]
     uint4 bf[OW][2], bf2[2];                               // bf16 B-operands of phase 2
-    float coefs[BF16 ? 1 : 16], coefs2[BF16 ? 1 : 16];     // fp32 B-operands of phase 2 (OW == 1)
+    float coefs[(BF16 || X3) ? 1 : 16], coefs2[(BF16 || X3) ? 1 : 16];   // fp32 B-operands of phase 2 (OW == 1) ...
+    KgeP3 coefp[2], coefp2[2];                             // ... or their bf16 pieces
 
     // ---- phase 1: acc[h][stream, own] = X_tile . own^t; a fragment read from the LDS feeds all own fragments
     constexpr bool HASW = TRANSH && !OWN_ROW;
@@ -327,10 +389,18 @@ void kge_block_kernel(const KgeBlockArgs a) {
 #pragma unroll
         for (int k = 0; k < G1; ++k) {
             const int ks = grp * G1 + k;
+            if constexpr (!X3) {
 #pragma unroll
-            for (int h = 0; h < OW; ++h) acc[h] = kge_mma16<BF16>(acc[h], av[ks], own[h][ks]);
-            if constexpr (TRANSH && OWN_ROW) accw = kge_mma16<BF16>(accw, av[ks], ownw[ks]);
-            if constexpr (HASW) accw = kge_mma16<BF16>(accw, aw[ks], own[0][ks]);
+                for (int h = 0; h < OW; ++h) acc[h] = kge_mma16<BF16>(acc[h], av[ks], own[h][ks]);
+                if constexpr (TRANSH && OWN_ROW) accw = kge_mma16<BF16>(accw, av[ks], ownw[ks]);
+                if constexpr (HASW) accw = kge_mma16<BF16>(accw, aw[ks], own[0][ks]);
+            } else if ((k & 1) == 0) {                      // bf16 pieces: two k-steps at a time (G1 is even)
+                const KgeP3 x = kge_split3(av[ks], av[ks + 1]);
+#pragma unroll
+                for (int h = 0; h < OW; ++h) acc[h] = kge_mma3(acc[h], x, ownp[h][ks >> 1]);
+                if constexpr (TRANSH && OWN_ROW) accw = kge_mma3(accw, x, ownwp[ks >> 1]);
+                if constexpr (HASW) accw = kge_mma3(accw, kge_split3(aw[ks], aw[ks + 1]), ownp[0][ks >> 1]);
+            }
         }
     };
     // ---- phase 2: out^t[d, own] += Xt_tile[d, stream] . coef[stream, own] ---------------------------
@@ -373,7 +443,7 @@ void kge_block_kernel(const KgeBlockArgs a) {
                     if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma16<true>(acc2b[blk], av2[blk][s2], bf2[s2]);
                     if constexpr (HASW) acc2[0][blk] = kge_mma16<true>(acc2[0][blk], aw2[blk][s2], bf2[s2]);
                 }
-            } else {
+            } else if constexpr (!X3) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const kge_f32x4 fa = __builtin_bit_cast(kge_f32x4, av2[blk][j]);
@@ -387,6 +457,15 @@ void kge_block_kernel(const KgeBlockArgs a) {
                         if constexpr (HASW)
                             acc2[0][blk] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[r], coefs2[4 * j + r], acc2[0][blk], 0, 0, 0);
                     }
+                }
+            } else {
+#pragma unroll
+                for (int j2 = 0; j2 < 2; ++j2) {            // stream entries 16 j2 .. + 15: fragments 2 j2 and 2 j2 + 1
+                    const KgeP3 x = kge_split3(av2[blk][2 * j2], av2[blk][2 * j2 + 1]);
+                    acc2[0][blk] = kge_mma3(acc2[0][blk], x, coefp[j2]);
+                    if constexpr (TRANSH && OWN_ROW) acc2b[blk] = kge_mma3(acc2b[blk], x, coefp2[j2]);
+                    if constexpr (HASW)
+                        acc2[0][blk] = kge_mma3(acc2[0][blk], kge_split3(aw2[blk][2 * j2], aw2[blk][2 * j2 + 1]), coefp2[j2]);
                 }
             }
         }
@@ -525,9 +604,16 @@ void kge_block_kernel(const KgeBlockArgs a) {
                                              kge_pack_bf16x2(coef2[8 * s2 + 4], coef2[8 * s2 + 5]),
                                              kge_pack_bf16x2(coef2[8 * s2 + 6], coef2[8 * s2 + 7]));
                 }
-            } else {
+            } else if constexpr (!X3) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { coefs[i] = coef[i]; if constexpr (TRANSH) coefs2[i] = coef2[i]; }
+            } else {
+                auto four = [](const float *c) { return make_uint4(__float_as_uint(c[0]), __float_as_uint(c[1]), __float_as_uint(c[2]), __float_as_uint(c[3])); };
+#pragma unroll
+                for (int j2 = 0; j2 < 2; ++j2) {
+                    coefp[j2] = kge_split3(four(coef + 8 * j2), four(coef + 8 * j2 + 4));
+                    if constexpr (TRANSH) coefp2[j2] = kge_split3(four(coef2 + 8 * j2), four(coef2 + 8 * j2 + 4));
+                }
             }
         }
     };
