@@ -155,6 +155,11 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
  * TransH at d = 256, 1,024 bytes in fp32) take the route of the 1-norm variants: the score block is written to the
  * workspace (B*N floats, three of them) and both passes run on the vector pipe in fp32, about ten times slower than the
  * matrix-core route of the narrower rows.
+ * Arithmetic of the two contractions per pass (scores; gradient rows): bf16 tables -> bf16 matrix cores with fp32
+ * accumulation.  fp32 tables -> every operand value as three bf16 pieces x0 + x1 + x2 (round to nearest at each step:
+ * 24 significand bits, the exponent range of fp32, nothing scaled) and the six piece products of total order <= 2 on
+ * the bf16 matrix cores with fp32 accumulation (what is dropped is below 2^-26 |a| |b| per product); the pass over the
+ * queries with rows of 1,024 bytes uses the fp32 matrix instructions.
  */
 int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h,
                  const int32_t *r, const int32_t *t, int64_t B, const int32_t *neg, int64_t N,
