@@ -248,19 +248,19 @@ class TrainWorkload:
         return t
 
     def _step_call_by_call(self, i):
-        """One step on ONE stream: negatives -> the sorts of the step's row ids (every table in one launch) -> gather,
-        forward, backward -> the update of every table (two launches).  (A second stream for the sorts, which need the ids
-        alone, was measured and lost: each cross-stream wait costs the waiting stream about 10 us on this stack, and small
-        kernels that share the chip with the forward or backward kernel hold up a workgroup of theirs.)"""
+        """One step on ONE stream: gather (which draws the step's negatives), forward, backward -> the sorts of the step's row
+        ids (every table in one launch) -> the update of every table (two launches).  (A second stream for the sorts,
+        which need the ids alone, was measured and lost: each cross-stream wait costs the waiting stream about 10 us on this
+        stack, and small kernels that share the chip with the forward or backward kernel hold up a workgroup of theirs.)"""
         kge, ks = self.kge, self.ks
         main = self.main
         h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
-        kge.sample_negatives(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi, self.N, out=ids[2 * self.B:], stream=main)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main,
+                     draw=(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi), **self.loss_kw)
         plans = [(self.n_ent, self.d, ids, self.ws_ent), (self.n_rel, self.rel.shape[1], r, self.ws_rel)]
         if self.relw is not None:
             plans.append((self.n_rel, self.d, r, self.ws_relw))
         kge.sparse_adam_plan_tables(plans, stream=main)
-        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main, **self.loss_kw)
         kge.sparse_adam_apply_tables(self._tables(), self.P["lr"], step=i + 1, stream=main)
 
     def _enqueue(self, k, main):
@@ -269,12 +269,12 @@ class TrainWorkload:
         kge, ks = self.kge, self.ks
         h, r, t, lo, hi, ids = self.batches[k]
         c = self.counter
-        kge.sample_negatives_dev(ks.BASE_SEED, c, 0, ks.TAG_NEG, lo, hi, self.N, out=ids[2 * self.B:], stream=main)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main,
+                     draw=(ks.BASE_SEED, 0, ks.TAG_NEG, lo, hi, c), **self.loss_kw)
         plans = [(self.n_ent, self.d, ids, self.ws_ent), (self.n_rel, self.rel.shape[1], r, self.ws_rel)]
         if self.relw is not None:
             plans.append((self.n_rel, self.d, r, self.ws_relw))
         kge.sparse_adam_plan_tables(plans, stream=main)
-        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main, **self.loss_kw)
         kge.sparse_adam_apply_tables(self._tables(), self.P["lr"], step=1, stream=main, step_counter=c)
         kge.step_counter_add(c, 1, stream=main)
 
@@ -761,7 +761,7 @@ def main():
         line["hbm_kernels"] = hbm
     if isinstance(wl, TrainWorkload):
         line["enqueue"] = ("HIP graph replay, one graph per pre-drawn batch; every 4th step call by call with the HIP-event bracket"
-                           if graphed else "call by call, one stream, 9 launches per step")
+                           if graphed else "call by call, one stream, 8 launches per step")
     line.update(wl.extra(ms))
     if enc_roof:
         line["encoder_roofline"] = enc_roof

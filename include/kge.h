@@ -167,6 +167,27 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
                  int32_t *g_rel_idx, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * kge_loss_bwd that draws its shared negatives itself (Section 4, "Training": sample, gather, score, update; the draw of
+ * eq. (negsamples) joins the gather of the rows it selects: one launch less per step, and the gather does not wait for
+ * ids from memory).  The ids are those of kge_sample_negatives(seed, step, stream_tag, lo, hi, N) - with step_counter
+ * set, those of kge_sample_negatives_dev(seed, step_counter, step, ...) - bit for bit.  They are written to neg_out
+ * (device int32[N], required when N > 0) and are complete when the call's work is: a kge_sparse_adam_plan* that sorts
+ * them comes after this call on the stream.  Everything else as kge_loss_bwd with neg = neg_out.
+ */
+typedef struct {
+    uint64_t seed;
+    uint64_t step;                    /* < 2^32 (with step_counter: step + *step_counter < 2^32) */
+    const uint64_t *step_counter;     /* NULL, or a DEVICE counter as in kge_sample_negatives_dev */
+    uint32_t stream_tag;
+    uint32_t reserved;                /* 0 */
+    int64_t lo, hi;                   /* ids in [lo, hi), 0 <= lo < hi <= 2^31 */
+} kge_neg_draw_t;
+int kge_loss_bwd_sampled(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h,
+                         const int32_t *r, const int32_t *t, int64_t B, const kge_neg_draw_t *draw, int32_t *neg_out,
+                         int64_t N, float *loss_out, float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw,
+                         int32_t *g_rel_idx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Duplicate-aware scatter-add + lazy sparse Adam on the touched rows only (Section 1: only the
  * rows of the mini-batch are accessed and updated; optimiser state lives beside the rows,
  * Section 4.1).  grads[i*dim .. ] (float, i < M) targets table row idx[i]; rows with equal idx

@@ -22,7 +22,7 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit", "kge_debug_select",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
            "kge_calibrate_mfma", "kge_calibrate_mfma_varied", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev",
-           "kge_sparse_adam_apply_tables", "kge_sparse_adam_plan_tables"]
+           "kge_sparse_adam_apply_tables", "kge_sparse_adam_plan_tables", "kge_loss_bwd_sampled"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7, "gather": 8, "finish": 9}
 
@@ -49,6 +49,11 @@ class KgeLossCfgT(C.Structure):
 class KgeAdamCfgT(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("step", C.c_int64), ("step_counter", C.c_void_p)]
+
+
+class KgeNegDrawT(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("step", C.c_uint64), ("step_counter", C.c_void_p), ("stream_tag", C.c_uint32),
+                ("reserved", C.c_uint32), ("lo", C.c_int64), ("hi", C.c_int64)]
 
 
 class KgeAdamPlanT(C.Structure):
@@ -105,6 +110,8 @@ def load():
         lib.kge_score.argtypes = [C.c_void_p] + [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_int64] + \
             [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]
         lib.kge_loss_bwd.argtypes = [C.c_void_p, C.c_void_p] + [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_int64] + \
+            [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
+        lib.kge_loss_bwd_sampled.argtypes = [C.c_void_p, C.c_void_p] + [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64] + \
             [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
         lib.kge_sparse_adam.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                                            C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -247,7 +254,9 @@ def score(model: Model, h, r, t, neg, want_neg: bool = True, ws: Workspace | Non
 
 def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp: float = 0.0,
              loss_scale: float = 0.0, n_ent_for_c: int = 0, ws: Workspace | None = None, out=None,
-             reg_l3: float = 0.0, stream=None):
+             reg_l3: float = 0.0, stream=None, draw=None):
+    """kge_loss_bwd; with draw = (seed, step, stream_tag, lo, hi[, step_counter]) kge_loss_bwd_sampled, which draws the
+    negatives itself and writes their ids to `neg` (an int32 tensor of N entries)."""
     B, N, d = h.numel(), neg.numel(), model.dim
     k = model.rel.shape[1]
     if out is None:
@@ -262,6 +271,15 @@ def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp
     cfg = KgeLossCfgT(LOSSES[loss], gamma, adv_temp, loss_scale, n_ent_for_c, reg_l3, 0)
     ws = ws or _default_ws
     buf = ws.get(workspace_bytes(OP_LOSS_BWD, model, B, N))
+    if draw is not None:
+        assert neg.is_cuda and neg.dtype == torch.int32 and neg.is_contiguous()
+        dr = KgeNegDrawT(draw[0], draw[1], _counter(draw[5]) if len(draw) > 5 else None, draw[2], 0, draw[3], draw[4])
+        _check(load().kge_loss_bwd_sampled(model.ref, C.byref(cfg), _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B,
+                                           C.byref(dr), _ptr(neg), N, _ptr(out["loss"]), _ptr(out["g_ent"]),
+                                           _ptr(out["g_ent_idx"]), _ptr(out["g_rel"]), _ptr(out["g_relw"]),
+                                           _ptr(out["g_rel_idx"]), _ptr(buf), buf.numel(), _stream(stream)),
+               "kge_loss_bwd_sampled")
+        return out
     _check(load().kge_loss_bwd(model.ref, C.byref(cfg), _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B,
                                _ptr(_i32(neg)), N, _ptr(out["loss"]), _ptr(out["g_ent"]), _ptr(out["g_ent_idx"]),
                                _ptr(out["g_rel"]), _ptr(out["g_relw"]), _ptr(out["g_rel_idx"]), _ptr(buf),

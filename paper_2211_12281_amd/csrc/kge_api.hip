@@ -400,10 +400,12 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
     return launch_block(g, KGE_MODE_SCORE, 0, a, g.own_tiles_s, g.nsplit_s, 1, st);
 }
 
-int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
-                 const int32_t *t, int64_t B, const int32_t *neg, int64_t N, float *loss_out, float *g_ent,
-                 int32_t *g_ent_idx, float *g_rel, float *g_relw, int32_t *g_rel_idx, void *ws, size_t ws_bytes,
-                 void *hip_stream) {
+// kge_loss_bwd and kge_loss_bwd_sampled (gen: the draw of the negatives, gen->out their ids' place; else neg holds them)
+static int loss_bwd_impl(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
+                         const int32_t *t, int64_t B, const int32_t *neg, const KgeNegGen *gen, int64_t N, float *loss_out,
+                         float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw, int32_t *g_rel_idx, void *ws,
+                         size_t ws_bytes, void *hip_stream) {
+    if (gen) neg = gen->out;
     int rc = validate_model(model);
     if (rc != KGE_OK) return rc;
     if (!cfg || (cfg->loss != KGE_LOGSIGMOID && cfg->loss != KGE_SAMPLED_SOFTMAX)) return KGE_E_INVALID_ARG;
@@ -433,10 +435,16 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
 
     // (the kernels that need no transposed copy of the negatives get queries and negatives from ONE launch)
     const bool plain_gather = have_block && (g.l1 || kge_fwd_pp_applies(g.bf16, g.rb, g.transh, g.dsplit_q));
+    // (negatives that the call draws itself: in that launch; where the rows are gathered otherwise, in a launch of their own)
+    if (gen && N > 0 && !plain_gather) {
+        rc = kge_run_negatives(((uint64_t)gen->seed_hi << 32) | gen->seed_lo, gen->step, gen->step_counter, gen->tag, gen->lo,
+                               gen->lo + (int64_t)gen->range, N, gen->out, st);
+        if (rc != KGE_OK) return rc;
+    }
     if (plain_gather) {
         KgeProfScope prof(KGE_PROF_GATHER, st);
         rc = kge_run_qbuild_tgather(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos,
-                                    neg, g.N, g.Np, b.T, b.tn, st, nullptr, nullptr, nullptr, nullptr, b.nbias);
+                                    neg, g.N, g.Np, b.T, b.tn, st, nullptr, nullptr, nullptr, nullptr, b.nbias, gen);
     }
     else rc = kge_run_qbuild(md, h, r, t, g.B, g.Bp, g.dp, b.Q, b.W, b.Q2, b.Q32, b.W32, b.rowinfo, b.pos, nullptr, st);
     if (rc != KGE_OK) return rc;
@@ -512,6 +520,27 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
     }
     if (cfg->reg_l3 > 0.f && B + N > 0) rc = kge_run_reg_add(b.regv, g.B, g.Bp, g.N, cfg->reg_l3, loss_out, st);
     return rc;
+}
+
+int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
+                 const int32_t *t, int64_t B, const int32_t *neg, int64_t N, float *loss_out, float *g_ent,
+                 int32_t *g_ent_idx, float *g_rel, float *g_relw, int32_t *g_rel_idx, void *ws, size_t ws_bytes,
+                 void *hip_stream) {
+    return loss_bwd_impl(model, cfg, h, r, t, B, neg, nullptr, N, loss_out, g_ent, g_ent_idx, g_rel, g_relw, g_rel_idx, ws,
+                         ws_bytes, hip_stream);
+}
+
+int kge_loss_bwd_sampled(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
+                         const int32_t *t, int64_t B, const kge_neg_draw_t *draw, int32_t *neg_out, int64_t N,
+                         float *loss_out, float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw,
+                         int32_t *g_rel_idx, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (!draw || draw->hi <= draw->lo || draw->lo < 0 || draw->hi > (1ll << 31) || draw->step >= (1ull << 32) || draw->reserved != 0)
+        return KGE_E_INVALID_ARG;
+    if (N > 0 && !neg_out) return KGE_E_INVALID_ARG;
+    const KgeNegGen gen{neg_out, (uint32_t)draw->seed, (uint32_t)(draw->seed >> 32), (uint32_t)draw->step, draw->stream_tag,
+                        draw->step_counter, draw->lo, (uint64_t)(draw->hi - draw->lo)};
+    return loss_bwd_impl(model, cfg, h, r, t, B, nullptr, &gen, N, loss_out, g_ent, g_ent_idx, g_rel, g_relw, g_rel_idx, ws,
+                         ws_bytes, hip_stream);
 }
 
 // argument checks shared by kge_sparse_adam and kge_sparse_adam_static; KGE_OK with M == 0 means "nothing to do"

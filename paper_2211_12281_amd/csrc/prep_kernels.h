@@ -23,12 +23,16 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
 constexpr float KGE_PLANE_UNIT_SCALE = 1024.f;      // scale of the planes of TransH's unit normals (all rows)
 int kge_run_tgather(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, float *tn,
                     hipStream_t st, void *planes = nullptr, float *inv_scale = nullptr);
+// The draw of kge_run_negatives for a gather that makes it itself: id n of (seed, step [+ *step_counter], tag) in
+// [lo, lo + range), written to out[n] as it is used.  out == nullptr: the gather reads its ids.
+struct KgeNegGen { int32_t *out; uint32_t seed_lo, seed_hi, step, tag; const uint64_t *step_counter; int64_t lo; uint64_t range; };
 // the two above as ONE launch (Bp > 0 and Np > 0; no positive scores out)
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out = nullptr,
                            void *q_planes = nullptr, void *t_planes = nullptr, float *t_inv_scale = nullptr,
-                           float *bias = nullptr);            // bias [Np]: 0 for the N negatives, -inf behind them
+                           float *bias = nullptr,             // bias [Np]: 0 for the N negatives, -inf behind them
+                           const KgeNegGen *gen = nullptr);   // gen->out set: neg is ignored, the ids are drawn and written there
 // gather of the negatives and their transposed copy Tt [dp][Np] in one launch
 int kge_run_tgather_t(const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T, void *Tt, float *tn,
                       hipStream_t st);

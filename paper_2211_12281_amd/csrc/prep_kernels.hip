@@ -47,6 +47,20 @@ int kge_run_negatives(uint64_t seed, uint64_t step, const uint64_t *step_counter
     return kge_launch_status();
 }
 
+// id n of the draw that kge_negatives_kernel makes with these arguments (for the gather that draws its own ids)
+__device__ __forceinline__ int32_t kge_negative_id(const KgeNegGen &q, uint32_t step, int64_t n) {
+    const int64_t blk = n >> 1;
+    uint32_t c[4] = { (uint32_t)blk, (uint32_t)((uint64_t)blk >> 32), step, q.tag };
+    uint32_t k0 = q.seed_lo, k1 = q.seed_hi;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        kge_philox_round(c, k0, k1);
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    const uint64_t x = (n & 1) ? (((uint64_t)c[3] << 32) | c[2]) : (((uint64_t)c[1] << 32) | c[0]);
+    return (int32_t)(q.lo + (int64_t)__umul64hi(x, q.range));
+}
+
 // ---------------------------------------------------------------------------------------------
 // gather + query build + positive score (one wave per triple; rows >= B are written as zeros)
 // ---------------------------------------------------------------------------------------------
@@ -56,7 +70,10 @@ struct KgeQbuildArgs {
     _Float16 *planes;                  // optional: the two fp16 pieces of the scaled q, [2][Bp][dp], with W two more for the
                                        // unit normal (scaled by KGE_PLANE_UNIT_SCALE); then rowinfo.K = 1 / scale of the row
 };
-struct KgeTgatherArgs { const int32_t *neg; int N, Np; void *T; float *tn; _Float16 *planes; float *inv_scale; float *bias; };
+struct KgeTgatherArgs {
+    const int32_t *neg; int N, Np; void *T; float *tn; _Float16 *planes; float *inv_scale; float *bias;
+    KgeNegGen gen;                     // gen.out set: the ids are drawn here (and written to gen.out) instead of read from neg
+};
 
 // fp32 rows as TWO fp16 planes for the matrix cores: the row is scaled by a power of two s that brings its largest
 // magnitude into [2^10, 2^11) (well inside the fp16 range, with the second piece of every element that matters still
@@ -174,8 +191,12 @@ __host__ __device__ inline int kge_tgather_rows_per_wave(int dp, int es) { retur
 
 template <bool BF16>
 __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, const int32_t *neg, int N, int Np, int dp, void *T,
-                                                 float *tn, _Float16 *planes = nullptr, float *inv_scale = nullptr) {
+                                                 float *tn, _Float16 *planes = nullptr, float *inv_scale = nullptr,
+                                                 const KgeNegGen *gen = nullptr) {
     const int lane = threadIdx.x & 63;
+    const bool draw = gen && gen->out;
+    uint32_t step = 0;
+    if (draw) { step = gen->step; if (gen->step_counter) step += (uint32_t)*gen->step_counter; }
     constexpr int ES = BF16 ? 2 : 4;
     const int lpr = dp * ES / 16;                           // lanes that cover a row with 16 bytes each
     const int gl = kge_tgather_group_lanes(dp, ES), rpl = 64 / gl, rpw = KGE_TG_INFLIGHT * rpl;
@@ -186,10 +207,21 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
         const int grp = lane / gl, lg = lane % gl;
         uint4 v[KGE_TG_INFLIGHT];
         int64_t off[KGE_TG_INFLIGHT];
+        // ids drawn here: lane l draws the id of row nbase + l % rpw (one Philox block per lane instead of one per row and
+        // lane), the first rpw lanes write them out, and every lane fetches its rows' ids from the lanes that hold them
+        int32_t mine = 0;
+        if (draw) {
+            const int n = nbase + lane % rpw;
+            if (n < N) mine = kge_negative_id(*gen, step, n);
+            if (lane < rpw && n < N) gen->out[n] = mine;
+        }
 #pragma unroll
         for (int u = 0; u < KGE_TG_INFLIGHT; ++u) {
             const int n = nbase + u * rpl + grp;
-            off[u] = n < N ? (int64_t)neg[n] * m.ent_ld : -1;
+            int32_t id = 0;
+            if (draw) id = __shfl(mine, u * rpl + grp);     // (every lane takes part)
+            else if (n < N) id = neg[n];
+            off[u] = n < N ? (int64_t)id * m.ent_ld : -1;
         }
 #pragma unroll
         for (int u = 0; u < KGE_TG_INFLIGHT; ++u) {
@@ -239,7 +271,12 @@ __device__ __forceinline__ void kge_tgather_body(int blk, const KgeModelDev &m, 
     for (int u = 0; u < rpw; ++u) {
         const int n = nbase + u;
         if (n >= Np) break;                                 // (wave-uniform)
-        const int64_t off = n < N ? (int64_t)neg[n] * m.ent_ld : 0;
+        int64_t off = 0;
+        if (n < N) {
+            const int32_t id = draw ? kge_negative_id(*gen, step, n) : neg[n];
+            if (draw && lane == 0) gen->out[n] = id;
+            off = (int64_t)id * m.ent_ld;
+        }
         float s = 0.f, amax = 0.f;
         for (int j = lane; j < dp; j += 64) {
             float v = (n < N && j < m.dim) ? El<BF16>::ld(m.ent, off + j) : 0.f;
@@ -273,7 +310,7 @@ __global__ void kge_qbuild_tgather_kernel(int q_blocks, KgeQbuildArgs a, KgeTgat
     if (g.bias)                                                         // 0 for the negatives, -inf for the padding rows behind them
         for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < g.Np; n += gridDim.x * blockDim.x) g.bias[n] = n < g.N ? 0.f : -INFINITY;
     if ((int)blockIdx.x < q_blocks) kge_qbuild_body<BF16, SC>(blockIdx.x, a);
-    else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn, g.planes, g.inv_scale);
+    else kge_tgather_body<BF16>(blockIdx.x - q_blocks, a.m, g.neg, g.N, g.Np, a.dp, g.T, g.tn, g.planes, g.inv_scale, &g.gen);
 }
 
 // gather of the shared negatives AND their transposed copy in one launch: a workgroup takes 32 negatives, every
@@ -780,12 +817,12 @@ int kge_run_qbuild(const KgeModelDev &m, const int32_t *h, const int32_t *r, con
 int kge_run_qbuild_tgather(const KgeModelDev &m, const int32_t *h, const int32_t *r, const int32_t *t, int B, int Bp,
                            int dp, void *Q, void *W, void *Q2, float *Q32, float *W32, KgeRowInfo *rowinfo, float *pos_ws,
                            const int32_t *neg, int N, int Np, void *T, float *tn, hipStream_t st, float *pos_out,
-                           void *q_planes, void *t_planes, float *t_inv_scale, float *bias) {
+                           void *q_planes, void *t_planes, float *t_inv_scale, float *bias, const KgeNegGen *gen) {
     const int rows_wg = 4 * kge_tgather_rows_per_wave(dp, m.bf16 ? 2 : 4);
     const int qb = (Bp + 3) / 4, tb = (Np + rows_wg - 1) / rows_wg;
     if (qb == 0 || tb == 0 || ((q_planes || t_planes) && m.bf16) || (t_planes && !t_inv_scale)) return KGE_E_INVALID_ARG;
     const KgeQbuildArgs a{m, h, r, t, B, Bp, dp, Q, W, Q2, Q32, W32, rowinfo, pos_ws, pos_out, (_Float16 *)q_planes};
-    const KgeTgatherArgs g{neg, N, Np, T, tn, (_Float16 *)t_planes, t_inv_scale, bias};
+    const KgeTgatherArgs g{neg, N, Np, T, tn, (_Float16 *)t_planes, t_inv_scale, bias, gen ? *gen : KgeNegGen{}};
 #define KGE_QT(BF, SC) hipLaunchKernelGGL((kge_qbuild_tgather_kernel<BF, SC>), dim3(qb + tb), dim3(256), 0, st, qb, a, g)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_QT) } else { KGE_SC_SWITCH(false, KGE_QT) }
 #undef KGE_QT

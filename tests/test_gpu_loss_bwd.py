@@ -224,3 +224,48 @@ def test_scores_that_outgrow_the_first_tile(orc, scorer):
     print(scorer, "second pass vs two-role kernel:", errs, "vs oracle:", norm_err(ge[:B], ref["g_ent"][:B]))
     assert max(errs.values()) <= RTOL_BF16, errs
 
+
+
+@pytest.mark.parametrize("scorer,dim,bf16,loss,B,N", [
+    ("complex", 256, True, "sampled_softmax", 300, 701),     # hot path: the gather of the negatives draws the ids
+    ("transe", 256, True, "logsigmoid", 130, 260),           # two-role kernels, same gather
+    ("distmult", 64, False, "sampled_softmax", 200, 333),    # fp32 tables: the draw is a launch of its own inside the call
+    ("transh", 128, False, "logsigmoid", 64, 97),
+    ("transe", 256, True, "logsigmoid", 0, 50),              # no queries: zero rows and the ids
+    ("complex", 256, True, "sampled_softmax", 40, 0),        # no negatives: nothing is drawn
+])
+def test_negatives_drawn_inside_the_call_equal_the_two_calls(scorer, dim, bf16, loss, B, N):
+    """kge_loss_bwd_sampled: the ids of kge_sample_negatives bit for bit, and every output of kge_loss_bwd on them
+    bit for bit (same kernels on the same ids); a sub-range of the entities, and the step read from a device counter."""
+    import kge_synth as ks
+    import paper_2211_12281_amd as kge
+    n_ent = 4000
+    G = make_case(scorer, n_ent, 12, dim, max(B, 1), max(N, 1), bf16, amp=0.3, zipf=True)
+    model = gpu_model(scorer, G, bf16)
+    h, r, t = dev_idx(G["h"][:B]), dev_idx(G["r"][:B]), dev_idx(G["t"][:B])
+    kw = _kw(scorer, loss, n_ent)
+    for lo, hi, step, counter in ((0, n_ent, 5, None), (1000, 1777, 0, None), (0, n_ent, 3, 4)):
+        ref_neg = kge.sample_negatives(ks.BASE_SEED, step + (counter or 0), ks.TAG_NEG, lo, hi, N)
+        ref = kge.loss_bwd(model, loss, h, r, t, ref_neg, **kw)
+        ref = {k: v.clone() for k, v in ref.items() if v is not None}
+        neg = torch.full((N,), -1, dtype=torch.int32, device="cuda")
+        draw = (ks.BASE_SEED, step, ks.TAG_NEG, lo, hi)
+        if counter is not None:
+            draw = draw + (torch.tensor([counter], dtype=torch.int64, device="cuda"),)
+        out = kge.loss_bwd(model, loss, h, r, t, neg, draw=draw, **kw)
+        assert torch.equal(neg, ref_neg), (lo, hi, step, counter)
+        for k in ref:
+            assert torch.equal(out[k], ref[k]), (k, lo, hi, step, counter)
+
+
+def test_negatives_drawn_inside_the_call_argument_checks():
+    import kge_synth as ks
+    import paper_2211_12281_amd as kge
+    G = make_case("complex", 500, 4, 256, 8, 8, True)
+    model = gpu_model("complex", G, True)
+    h, r, t = dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"])
+    neg = torch.zeros(8, dtype=torch.int32, device="cuda")
+    for draw in ((ks.BASE_SEED, 0, ks.TAG_NEG, 10, 10), (ks.BASE_SEED, 0, ks.TAG_NEG, -1, 10), (ks.BASE_SEED, 1 << 32, ks.TAG_NEG, 0, 10),
+                 (ks.BASE_SEED, 0, ks.TAG_NEG, 0, (1 << 31) + 1)):
+        with pytest.raises(kge.KgeError):
+            kge.loss_bwd(model, "sampled_softmax", h, r, t, neg, draw=draw, n_ent_for_c=500)
