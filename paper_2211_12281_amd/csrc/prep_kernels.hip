@@ -747,11 +747,11 @@ __device__ __forceinline__ void kge_tfinish_body(int blk, const KgeTfinishArgs &
 template <bool BF16>
 __global__ void kge_tfinish_kernel(KgeTfinishArgs a) { kge_tfinish_body<BF16>(blockIdx.x, a); }
 template <bool BF16, int SC>
-__global__ void kge_chain_kernel(KgeChainArgs a) { kge_chain_body<BF16, SC>(blockIdx.x, a); }
+__global__ __launch_bounds__(256) void kge_chain_kernel(KgeChainArgs a) { kge_chain_body<BF16, SC>(blockIdx.x, a); }
 // both finishing kernels in ONE launch (the first chain_blocks workgroups run the chain rule of the queries): they
 // read different partials and write different gradient rows
 template <bool BF16, int SC>
-__global__ void kge_chain_tfinish_kernel(int chain_blocks, KgeChainArgs c, KgeTfinishArgs t, const float *lossb, float scale,
+__global__ __launch_bounds__(256) void kge_chain_tfinish_kernel(int chain_blocks, KgeChainArgs c, KgeTfinishArgs t, const float *lossb, float scale,
                                          float *loss_out) {
     // (workgroup 0: the loss of the batch from the rows' losses, the reduction that would otherwise be a launch
     // of its own between the two passes)
