@@ -26,8 +26,9 @@ def _model(kge, scorer, T, bf16):
     return kge.Model(scorer, tbl(T["ent"]), tbl(T["rel"]))
 
 
+@pytest.mark.parametrize("fused", [False, True])     # the negatives from a call of their own / drawn inside kge_loss_bwd_sampled
 @pytest.mark.parametrize("scorer,d,bf16,loss", [("complex", 256, True, "sampled_softmax"), ("distmult", 64, False, "logsigmoid")])
-def test_replays_of_a_captured_step_match_the_step_run_call_by_call(scorer, d, bf16, loss):
+def test_replays_of_a_captured_step_match_the_step_run_call_by_call(scorer, d, bf16, loss, fused):
     import paper_2211_12281_amd as kge
     n_ent, n_rel, B, N, steps = 6000, 12, 512, 1024, 4
     G = make_case(scorer, n_ent, n_rel, d, B, N, bf16, amp=0.3)
@@ -66,8 +67,11 @@ def test_replays_of_a_captured_step_match_the_step_run_call_by_call(scorer, d, b
     ws = [kge.Workspace() for _ in range(3)]
 
     def one_step():
-        kge.sample_negatives_dev(ks.BASE_SEED, counter, 5, ks.TAG_NEG, 0, n_ent, N, out=negg)
-        kge.loss_bwd(mg, loss, h, r, t, negg, out=og, ws=ws[0], **kw)
+        if fused:
+            kge.loss_bwd(mg, loss, h, r, t, negg, out=og, ws=ws[0], draw=(ks.BASE_SEED, 5, ks.TAG_NEG, 0, n_ent, counter), **kw)
+        else:
+            kge.sample_negatives_dev(ks.BASE_SEED, counter, 5, ks.TAG_NEG, 0, n_ent, N, out=negg)
+            kge.loss_bwd(mg, loss, h, r, t, negg, out=og, ws=ws[0], **kw)
         for j, (name, gi, gg) in enumerate((("ent", "g_ent_idx", "g_ent"), ("rel", "g_rel_idx", "g_rel"))):
             q = Tg[name]
             kge.sparse_adam(q["p"], q["sh"], q["m"], q["v"], og[gi], og[gg], lr, step=1, ws=ws[1 + j], step_counter=counter)
