@@ -316,15 +316,21 @@ __device__ void bitonic_asc_pair(double *key, int *idx, int P) {
         }
 }
 
-// per query: merge the kept list with the fresh append areas, keep the KP best, refresh the threshold
+// per query: merge the kept list with the fresh append areas, keep the KP best, refresh the threshold.
+// Two launches per chunk.  After the first chunk a query's list is a few KP long, and a workgroup whose LDS holds
+// TK_SORTCAP_SMALL entries leaves room for eight on a compute unit instead of two (the reads of a query's scattered
+// entries and the sort's chain of barriers are all latency: what a compute unit needs is more workgroups): the first launch (cap = TK_SORTCAP_SMALL, redo written) takes the queries whose lists
+// fit and marks the others, the second (cap = TK_SORTCAP, redo read) takes the marked ones.
 constexpr int TK_SORTCAP = 8192;        // entries one workgroup can sort in LDS
+constexpr int TK_SORTCAP_SMALL = 2048;
 __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *seg, const int32_t *segcnt, int nseg,
-                                    int nsplit, int KP, float *thr, int32_t *flag, int Q) {
+                                    int nsplit, int KP, float *thr, int32_t *flag, int Q, int cap, int32_t *redo, int second) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     uint64_t *s = (uint64_t *)lds;
     __shared__ int total, over;
     const int q = blockIdx.x;
     if (q >= Q) return;
+    if (second && !redo[q]) return;
     const int kept = keepcnt[q];
     __shared__ int abase[512 + 1];                          // start of every area's entries in the sort buffer
     const int nareas = nsplit * 2;                          // <= 2 * nseg <= 512
@@ -355,6 +361,11 @@ __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *
         if (threadIdx.x == 0) total = abase[nareas];
     }
     __syncthreads();
+    if (!second) {                                          // (the same for every thread)
+        const bool fits = total <= cap;
+        if (threadIdx.x == 0) redo[q] = fits ? 0 : 1;
+        if (!fits) return;
+    }
     for (int i = threadIdx.x; i < kept; i += blockDim.x) { const uint2 e = keep[(size_t)q * KP + i]; s[i] = pack_value(e.x, e.y); }
     // every thread copies whole areas (an area holds one or two entries as a rule, 64 at most): the loads of different
     // threads are independent, so the memory latency is paid once or twice per thread, not once per area of the query
@@ -362,7 +373,7 @@ __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *
     for (int a2 = threadIdx.x; a2 < nareas; a2 += blockDim.x) {
         const int base = abase[a2], c = abase[a2 + 1] - base;
         if (c > 0) {
-            if (base + c <= TK_SORTCAP) {
+            if (base + c <= cap) {
                 const uint2 *src = seg + ((size_t)q * nseg * 2 + a2) * TK_HALF;
                 for (int li = 0; li < c; ++li) { const uint2 e = src[li]; s[base + li] = pack_value(e.x, e.y); }
             } else over = 1;
@@ -370,8 +381,8 @@ __global__ void topk_compact_kernel(uint2 *keep, int32_t *keepcnt, const uint2 *
     }
     __syncthreads();
     if (over) { if (threadIdx.x == 0) flag[q] = 1; }         // entries were dropped: exhaustive re-rank later
-    int n = total < TK_SORTCAP ? total : TK_SORTCAP;
-    if (over && total > TK_SORTCAP) n = kept;                // partially filled: keep the old list
+    int n = total < cap ? total : cap;
+    if (over && total > cap) n = kept;                       // partially filled: keep the old list
     int P = 2;
     while (P < n) P <<= 1;
     for (int i = n + threadIdx.x; i < P; i += blockDim.x) s[i] = 0;   // padding sorts last
@@ -868,7 +879,7 @@ TopkPlan make_plan(const kge_model_t &m, int64_t Q, int64_t ncand, int K) {
 }
 
 struct TopkWs {
-    void *Qm; float *vt, *thr, *tn; QInfo *qinfo; int32_t *cnt, *flag; uint32_t *rankcnt, *tmax; uint2 *keep, *seg; int32_t *segcnt; double *keyd; uint32_t *zeros;
+    void *Qm; float *vt, *thr, *tn; QInfo *qinfo; int32_t *cnt, *flag, *redo; uint32_t *rankcnt, *tmax; uint2 *keep, *seg; int32_t *segcnt; double *keyd; uint32_t *zeros;
     void *Wm; float *cq; double *qx;                    // TransH only
 };
 
@@ -879,6 +890,7 @@ size_t topk_carve(const TopkPlan &p, void *ws, TopkWs &w) {
     w.vt = (float *)take((size_t)p.Qp * 4); w.thr = (float *)take((size_t)p.Qp * 4);
     w.qinfo = (QInfo *)take((size_t)p.Qp * sizeof(QInfo));
     w.cnt = (int32_t *)take((size_t)p.Qp * 4); w.flag = (int32_t *)take((size_t)p.Qp * 4);
+    w.redo = (int32_t *)take((size_t)p.Qp * 4);
     w.rankcnt = (uint32_t *)take((size_t)p.Qp * 4); w.tmax = (uint32_t *)take(256); w.zeros = (uint32_t *)take(256);
     w.tn = (float *)take((size_t)p.npad * 4);
     w.keep = (uint2 *)take((size_t)p.Qp * p.KP * 8);
@@ -984,8 +996,11 @@ int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, i
         }
         if (rc != KGE_OK) return rc;
         seen += tiles;
+        const int areas_of = (nsplit + 7) / 8 * 8 < p.nseg ? (nsplit + 7) / 8 * 8 : p.nseg;
+        hipLaunchKernelGGL(topk_compact_kernel, dim3((unsigned)Q), dim3(256), TK_SORTCAP_SMALL * 8, st, w.keep, w.cnt, w.seg, w.segcnt,
+                           p.nseg, areas_of, p.KP, w.thr, w.flag, (int)Q, TK_SORTCAP_SMALL, w.redo, 0);
         hipLaunchKernelGGL(topk_compact_kernel, dim3((unsigned)Q), dim3(256), compact_lds, st, w.keep, w.cnt, w.seg, w.segcnt,
-                           p.nseg, (nsplit + 7) / 8 * 8 < p.nseg ? (nsplit + 7) / 8 * 8 : p.nseg, p.KP, w.thr, w.flag, (int)Q);
+                           p.nseg, areas_of, p.KP, w.thr, w.flag, (int)Q, TK_SORTCAP, w.redo, 1);
     }
     const int64_t nres = Q * p.KP;
     const int final_lds = p.KPP * 12;
