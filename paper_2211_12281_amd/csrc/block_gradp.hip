@@ -188,6 +188,25 @@ void kge_gradp_kernel(const KgeBlockArgs a) {
     for (int nb = 0; nb < 2; ++nb) {
         const int oidx = own_tile * 128 + 64 * oh + 32 * nb + nrow;
         if (sh == 0 && g == 0) a.sum_part[(size_t)split * a.own_pad + oidx] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (a.part_bf16) {
+            // bf16 partials in column order.  A lane holds columns 8 q4 + 4 g .. + 3 of every 32-column block; the halves of
+            // the wave exchange the odd q4 of the lower with the even q4 of the upper, so that a lane writes eight
+            // consecutive columns (16 bytes): the lower half those of the even q4, the upper half those of the odd.
+            uint16_t *pr = (uint16_t *)a.acc_part + ((size_t)split * a.own_pad + oidx) * GP_DP + 128 * sh + 8 * g;
+#pragma unroll
+            for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+                for (int q2 = 0; q2 < 2; ++q2) {
+                    const int e = 8 * q2;                    // first accumulator of q4 = 2 q2
+                    const uint32_t x0 = kge_pack_bf16x2(acc2[blk][nb][e], acc2[blk][nb][e + 1]), x1 = kge_pack_bf16x2(acc2[blk][nb][e + 2], acc2[blk][nb][e + 3]);
+                    const uint32_t y0 = kge_pack_bf16x2(acc2[blk][nb][e + 4], acc2[blk][nb][e + 5]), y1 = kge_pack_bf16x2(acc2[blk][nb][e + 6], acc2[blk][nb][e + 7]);
+                    // (upper half of x <-> lower half of y)
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+                    *(uint4 *)(pr + blk * 32 + 16 * q2) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                }
+            continue;
+        }
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk)
 #pragma unroll

@@ -490,6 +490,20 @@ void kge_sym_kernel(const KgeBlockArgs a) {
             a.sum_part[(size_t)split * a.own_pad + oidx] = make_float4(0.f, 0.f, 0.f, 0.f);     // (distance scorers' sums: none here)
             if constexpr (FWD) a.stat_part[(size_t)split * a.own_pad + oidx] = make_float4(ref[ob], st_l[ob] + fin[partner * 64 + 32 * ob + lr], 0.f, 0.f);
         }
+        if (a.part_bf16) {
+            // bf16 partials: a lane holds columns c .. c + 3 (blk) and c + 64 .. c + 67 (blk + 2): four words of the row
+            uint32_t *pw = (uint32_t *)a.acc_part + ((size_t)split * a.own_pad + oidx) * (SY_DP / 2) + 64 * sh + 4 * g;
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *(uint4 *)(pw + blk * 32 + 8 * q4) =
+                        make_uint4(kge_pack_bf16x2(acc2[blk][ob][4 * q4], acc2[blk + 2][ob][4 * q4]),
+                                   kge_pack_bf16x2(acc2[blk][ob][4 * q4 + 1], acc2[blk + 2][ob][4 * q4 + 1]),
+                                   kge_pack_bf16x2(acc2[blk][ob][4 * q4 + 2], acc2[blk + 2][ob][4 * q4 + 2]),
+                                   kge_pack_bf16x2(acc2[blk][ob][4 * q4 + 3], acc2[blk + 2][ob][4 * q4 + 3]));
+            continue;
+        }
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk)
 #pragma unroll

@@ -468,7 +468,7 @@ static int loss_bwd_impl(const kge_model_t *model, const kge_loss_cfg_t *cfg, co
         a.kind = g.kind; a.loss = cfg->loss; a.gamma = cfg->gamma; a.adv_temp = cfg->adv_temp; a.c_corr = c_corr;
         a.stat_part = b.stat_part; a.acc_part = b.accq; a.acc_part2 = b.accq2; a.sum_part = b.sumq; a.own_pad = g.Bp;
         a.str_bias = b.nbias;
-        if (keep_weights) { a.pstore = b.pstore; a.ps_nsplit = g.nsplit_q; a.ps_rounds = g.tps_q / 2; }
+        if (keep_weights) { a.pstore = b.pstore; a.ps_nsplit = g.nsplit_q; a.ps_rounds = g.tps_q / 2; a.part_bf16 = 1; }
         if ((rc = launch_block(g, KGE_MODE_FWD, cfg->loss, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
     }
     if (keep_weights)
@@ -505,7 +505,7 @@ static int loss_bwd_impl(const kge_model_t *model, const kge_loss_cfg_t *cfg, co
                                    g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, cfg->reg_l3, b.regv,
                                    b.acct, b.sumt, g.nsplit_t, g.Np, g.N, model->dim, g.kind == KGE_KIND_DIST && !g.l1, b.T, neg,
                                    g_ent + (size_t)2 * B * model->dim, g_ent_idx + 2 * B, b.regv + (size_t)2 * g.Bp,
-                                   b.lossb, scale, loss_out, st);
+                                   b.lossb, scale, loss_out, st, keep_weights);
         if (rc != KGE_OK) return rc;
     } else {
         if ((rc = kge_run_chain(md, h, r, t, g.B, g.Bp, g.dp, b.accq, b.accq2, b.sumq, b.stat_part, b.rowinfo, 0, b.gpos,

@@ -101,6 +101,12 @@ struct KgeBlockArgs {
     // one 4 KB record per (own tile of 128 queries, split, round of 64 negatives, wave), in the writer's register layout
     void *pstore;
     int32_t ps_nsplit, ps_rounds;  // splits and rounds per split of the forward pass that wrote them
+    // block_sym.hip (forward pass that keeps its weights) and block_gradp.hip: the split partials of the gradient rows are
+    // written as bf16 (round to nearest even), half the bytes that the finishing launch reads back.  acc_part then holds
+    // [nsplit][own_pad][dp] bf16: the pass over the negatives in column order; the pass over the queries as dp/2 32-bit
+    // words per row, word 64 (c / 128) + c % 64 = columns c (low half) and c + 64 (high half) for c % 128 < 64 - the
+    // pairs that one lane of the chain-rule kernel holds.
+    int32_t part_bf16;
 };
 
 bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit);

@@ -60,7 +60,7 @@ int kge_run_chain_tfinish(const KgeModelDev &m, const int32_t *h, const int32_t 
                           float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv,
                           const float *accT_part, const float4 *sumT_part, int nsplit_t, int Np, int N, int d, int dist_kind,
                           const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn,
-                          const float *lossb, float scale, float *loss_out, hipStream_t st);   // also loss_out = scale * sum of lossb
+                          const float *lossb, float scale, float *loss_out, hipStream_t st, bool part_bf16 = false);   // also loss_out = scale * sum of lossb
 // loss_out += reg * (sum of regv over the 2B + N gathered slots), laid out [Bp heads][Bp tails][N negatives]
 int kge_run_reg_add(const float *regv, int B, int Bp, int N, float reg, float *loss_out, hipStream_t st);
 

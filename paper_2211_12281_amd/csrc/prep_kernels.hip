@@ -499,7 +499,9 @@ struct KgeTfinishArgs {
     float *g_neg; int32_t *g_neg_idx; const void *ent; int64_t ent_ld; float reg; float *regn;
 };
 
-template <bool BF16, int SC>
+// PB: the partials of the queries' gradient rows are bf16 in the paired-column words that the forward pass of
+// block_sym.hip writes (word lane + 64 kk of a row: columns lane + 128 kk and lane + 64 + 128 kk; rows of 256 columns)
+template <bool BF16, int SC, bool PB = false>
 __device__ __forceinline__ void kge_chain_body(int blk, const KgeChainArgs &a) {
     const KgeModelDev &m = a.m;
     const int32_t *h = a.h, *r = a.r, *t = a.t;
@@ -551,9 +553,17 @@ __device__ __forceinline__ void kge_chain_body(int blk, const KgeChainArgs &a) {
 #pragma unroll
             for (int k = 0; k < KGE_MAXJ; ++k) {
                 v1[u][k] = v2[u][k] = 0.f;
+                if constexpr (PB) continue;
                 if (64 * k >= dp) continue;                // wave-uniform: the partial rows are dp columns long
                 v1[u][k] = acc_part[((size_t)s * Bp + b) * dp + lane + 64 * k];
                 if (SC == KGE_TRANSH) v2[u][k] = acc_part2[((size_t)s * Bp + b) * dp + lane + 64 * k];
+            }
+            if constexpr (PB) {
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const uint32_t w = ((const uint32_t *)acc_part)[((size_t)s * Bp + b) * 128 + lane + 64 * kk];
+                    v1[u][2 * kk] = __uint_as_float(w << 16); v1[u][2 * kk + 1] = __uint_as_float(w & 0xFFFF0000u);
+                }
             }
         }
 #pragma unroll
@@ -681,7 +691,8 @@ __device__ __forceinline__ void kge_chain_body(int blk, const KgeChainArgs &a) {
 
 // gradient rows of the shared negatives: sum of the split partials minus colsum * t (distances), plus
 // the L3 regulariser of the row (read from the table itself, so it is there without a scored block)
-template <bool BF16>
+// PB: the split partials are bf16 rows in column order (block_gradp.hip)
+template <bool BF16, bool PB = false>
 __device__ __forceinline__ void kge_tfinish_body(int blk, const KgeTfinishArgs &a) {
     const float *accT_part = a.accT_part; const float4 *sumT_part = a.sumT_part;
     const int nsplit = a.nsplit, Np = a.Np, N = a.N, dp = a.dp, d = a.d, dist_kind = a.dist_kind;
@@ -728,8 +739,17 @@ __device__ __forceinline__ void kge_tfinish_body(int blk, const KgeTfinishArgs &
         // two splits are requested together, then added in split order
         for (int s0 = 0; s0 < nsplit; s0 += 2) {
             const bool two = s0 + 1 < nsplit;
-            const float4 p0 = *(const float4 *)(accT_part + ((size_t)s0 * Np + n) * dp + j);
-            const float4 p1 = two ? *(const float4 *)(accT_part + ((size_t)(s0 + 1) * Np + n) * dp + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 p0, p1 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if constexpr (PB) {
+                const uint16_t *pb = (const uint16_t *)accT_part;
+                const uint2 w0 = *(const uint2 *)(pb + ((size_t)s0 * Np + n) * dp + j);
+                const uint2 w1 = two ? *(const uint2 *)(pb + ((size_t)(s0 + 1) * Np + n) * dp + j) : make_uint2(0u, 0u);
+                p0 = make_float4(__uint_as_float(w0.x << 16), __uint_as_float(w0.x & 0xFFFF0000u), __uint_as_float(w0.y << 16), __uint_as_float(w0.y & 0xFFFF0000u));
+                p1 = make_float4(__uint_as_float(w1.x << 16), __uint_as_float(w1.x & 0xFFFF0000u), __uint_as_float(w1.y << 16), __uint_as_float(w1.y & 0xFFFF0000u));
+            } else {
+                p0 = *(const float4 *)(accT_part + ((size_t)s0 * Np + n) * dp + j);
+                if (two) p1 = *(const float4 *)(accT_part + ((size_t)(s0 + 1) * Np + n) * dp + j);
+            }
             v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
             if (two) { v[0] += p1.x; v[1] += p1.y; v[2] += p1.z; v[3] += p1.w; }
         }
@@ -750,14 +770,14 @@ template <bool BF16, int SC>
 __global__ __launch_bounds__(256) void kge_chain_kernel(KgeChainArgs a) { kge_chain_body<BF16, SC>(blockIdx.x, a); }
 // both finishing kernels in ONE launch (the first chain_blocks workgroups run the chain rule of the queries): they
 // read different partials and write different gradient rows
-template <bool BF16, int SC>
+template <bool BF16, int SC, bool PB = false>
 __global__ __launch_bounds__(256) void kge_chain_tfinish_kernel(int chain_blocks, KgeChainArgs c, KgeTfinishArgs t, const float *lossb, float scale,
                                          float *loss_out) {
     // (workgroup 0: the loss of the batch from the rows' losses, the reduction that would otherwise be a launch
     // of its own between the two passes)
     if (blockIdx.x == 0) kge_loss_reduce_body(lossb, c.B, scale, loss_out);
-    else if ((int)blockIdx.x <= chain_blocks) kge_chain_body<BF16, SC>(blockIdx.x - 1, c);
-    else kge_tfinish_body<BF16>(blockIdx.x - 1 - chain_blocks, t);
+    else if ((int)blockIdx.x <= chain_blocks) kge_chain_body<BF16, SC, PB>(blockIdx.x - 1, c);
+    else kge_tfinish_body<BF16, PB>(blockIdx.x - 1 - chain_blocks, t);
 }
 
 // loss += reg * (sum of the L3 norms of the 2B + N gathered slots): one workgroup of 1024 threads, fixed
@@ -912,12 +932,21 @@ int kge_run_chain_tfinish(const KgeModelDev &m, const int32_t *h, const int32_t 
                           float *g_relw, int32_t *g_ent_idx, int32_t *g_rel_idx, float reg, float *regv,
                           const float *accT_part, const float4 *sumT_part, int nsplit_t, int Np, int N, int d, int dist_kind,
                           const void *T, const int32_t *neg, float *g_neg, int32_t *g_neg_idx, float *regn,
-                          const float *lossb, float scale, float *loss_out, hipStream_t st) {
+                          const float *lossb, float scale, float *loss_out, hipStream_t st, bool part_bf16) {
     if (B == 0 || N == 0) return KGE_E_INVALID_ARG;
     const int cb = (B + 3) / 4, tb = (N + 3) / 4;
     const KgeChainArgs a{m, h, r, t, B, Bp, dp, acc_part, acc_part2, sum_part, stat_part, rowinfo, nsplit, gpos,
                          g_ent, g_rel, g_relw, g_ent_idx, g_rel_idx, reg, regv};
     const KgeTfinishArgs f{accT_part, sumT_part, nsplit_t, Np, N, dp, d, dist_kind, T, neg, g_neg, g_neg_idx, m.ent, m.ent_ld, reg, regn};
+    if (part_bf16) {
+        // (written by the bilinear kernels on bf16 rows of 512 bytes only)
+        if (!m.bf16 || dp != 256 || m.vec || (m.scorer != KGE_DISTMULT && m.scorer != KGE_COMPLEX)) return KGE_E_INVALID_ARG;
+        if (m.scorer == KGE_DISTMULT)
+            hipLaunchKernelGGL((kge_chain_tfinish_kernel<true, KGE_DISTMULT, true>), dim3(1 + cb + tb), dim3(256), 0, st, cb, a, f, lossb, scale, loss_out);
+        else
+            hipLaunchKernelGGL((kge_chain_tfinish_kernel<true, KGE_COMPLEX, true>), dim3(1 + cb + tb), dim3(256), 0, st, cb, a, f, lossb, scale, loss_out);
+        return kge_launch_status();
+    }
 #define KGE_CT(BF, SC) hipLaunchKernelGGL((kge_chain_tfinish_kernel<BF, SC>), dim3(1 + cb + tb), dim3(256), 0, st, cb, a, f, lossb, scale, loss_out)
     if (m.bf16) { KGE_SC_SWITCH(true, KGE_CT) } else { KGE_SC_SWITCH(false, KGE_CT) }
 #undef KGE_CT
