@@ -255,12 +255,11 @@ class TrainWorkload:
         kge, ks = self.kge, self.ks
         main = self.main
         h, r, t, lo, hi, ids = self.batches[i % len(self.batches)]
-        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main,
-                     draw=(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi), **self.loss_kw)
         plans = [(self.n_ent, self.d, ids, self.ws_ent), (self.n_rel, self.rel.shape[1], r, self.ws_rel)]
         if self.relw is not None:
             plans.append((self.n_rel, self.d, r, self.ws_relw))
-        kge.sparse_adam_plan_tables(plans, stream=main)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main,
+                     draw=(ks.BASE_SEED, i, ks.TAG_NEG, lo, hi), plans=plans, **self.loss_kw)
         kge.sparse_adam_apply_tables(self._tables(), self.P["lr"], step=i + 1, stream=main)
 
     def _enqueue(self, k, main):
@@ -269,12 +268,11 @@ class TrainWorkload:
         kge, ks = self.kge, self.ks
         h, r, t, lo, hi, ids = self.batches[k]
         c = self.counter
-        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main,
-                     draw=(ks.BASE_SEED, 0, ks.TAG_NEG, lo, hi, c), **self.loss_kw)
         plans = [(self.n_ent, self.d, ids, self.ws_ent), (self.n_rel, self.rel.shape[1], r, self.ws_rel)]
         if self.relw is not None:
             plans.append((self.n_rel, self.d, r, self.ws_relw))
-        kge.sparse_adam_plan_tables(plans, stream=main)
+        kge.loss_bwd(self.model, self.P["loss"], h, r, t, ids[2 * self.B:], out=self.out, stream=main,
+                     draw=(ks.BASE_SEED, 0, ks.TAG_NEG, lo, hi, c), plans=plans, **self.loss_kw)
         kge.sparse_adam_apply_tables(self._tables(), self.P["lr"], step=1, stream=main, step_counter=c)
         kge.step_counter_add(c, 1, stream=main)
 

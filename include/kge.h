@@ -238,6 +238,22 @@ typedef struct {
  * share one launch.  Same result in every workspace as one kge_sparse_adam_plan per table. */
 int kge_sparse_adam_plan_tables(const kge_adam_plan_t *plans, int32_t n_tables, void *hip_stream);
 
+/*
+ * kge_loss_bwd_sampled and kge_sparse_adam_plan_tables in one call (Section 4, "Training": one step = sample, gather, score,
+ * update).  The sorts of a step's row ids need the ids alone, so the call puts them where they cost least: with the sampled
+ * softmax on bilinear bf16 rows of 512 bytes they share the launch that finishes the rows' losses between the two block
+ * passes (one launch less per step, and the finish passes under the sorts); in every other configuration they follow the
+ * call's other work.  Results - losses, gradients, ids, and every plan in its workspace - equal those of the two calls, bit
+ * for bit.  plans[k].idx must be complete when the call starts, or be neg_out, or an array that ends in neg_out (e.g. one
+ * buffer [h | t | neg_out]); g_ent_idx and g_rel_idx, which the call writes last, are rejected (KGE_E_INVALID_ARG).
+ * Other errors as the two calls.
+ */
+int kge_loss_bwd_sampled_planned(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h,
+                                 const int32_t *r, const int32_t *t, int64_t B, const kge_neg_draw_t *draw,
+                                 int32_t *neg_out, int64_t N, float *loss_out, float *g_ent, int32_t *g_ent_idx,
+                                 float *g_rel, float *g_relw, int32_t *g_rel_idx, void *ws, size_t ws_bytes,
+                                 const kge_adam_plan_t *plans, int32_t n_tables, void *hip_stream);
+
 typedef struct {
     float *param_f32; void *param_bf16; float *m, *v;      /* as in kge_sparse_adam */
     int64_t n_rows; int32_t dim; int64_t ld;

@@ -22,7 +22,8 @@ EXPORTS = ["kge_sample_negatives", "kge_score", "kge_loss_bwd", "kge_sparse_adam
            "kge_sparse_adam_apply", "kge_sparse_adam_static", "kge_sparse_adam_static_limit", "kge_debug_select",
            "kge_workspace_bytes", "kge_status_string", "kge_profile_enable", "kge_profile_collect",
            "kge_calibrate_mfma", "kge_calibrate_mfma_varied", "kge_calibrate_copy", "kge_step_counter_add", "kge_sample_negatives_dev",
-           "kge_sparse_adam_apply_tables", "kge_sparse_adam_plan_tables", "kge_loss_bwd_sampled"]
+           "kge_sparse_adam_apply_tables", "kge_sparse_adam_plan_tables", "kge_loss_bwd_sampled",
+           "kge_loss_bwd_sampled_planned"]
 PROF_SLOTS = {"block_score": 0, "block_fwd": 1, "block_gradt": 2, "adam": 3, "sort": 4, "topk_scan": 5,
               "enc_fwd": 6, "enc_bwd": 7, "gather": 8, "finish": 9}
 
@@ -113,6 +114,8 @@ def load():
             [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
         lib.kge_loss_bwd_sampled.argtypes = [C.c_void_p, C.c_void_p] + [C.c_void_p] * 3 + [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64] + \
             [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
+        lib.kge_loss_bwd_sampled_planned.argtypes = [C.c_void_p, C.c_void_p] + [C.c_void_p] * 3 + \
+            [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64] + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p, C.c_int32, C.c_void_p]
         lib.kge_sparse_adam.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                                            C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kge_sparse_adam_static.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
@@ -254,9 +257,10 @@ def score(model: Model, h, r, t, neg, want_neg: bool = True, ws: Workspace | Non
 
 def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp: float = 0.0,
              loss_scale: float = 0.0, n_ent_for_c: int = 0, ws: Workspace | None = None, out=None,
-             reg_l3: float = 0.0, stream=None, draw=None):
+             reg_l3: float = 0.0, stream=None, draw=None, plans=None):
     """kge_loss_bwd; with draw = (seed, step, stream_tag, lo, hi[, step_counter]) kge_loss_bwd_sampled, which draws the
-    negatives itself and writes their ids to `neg` (an int32 tensor of N entries)."""
+    negatives itself and writes their ids to `neg` (an int32 tensor of N entries); with plans = [(n_rows, dim, idx, ws),
+    ...] as well kge_loss_bwd_sampled_planned, which also plans the sparse update of those tables."""
     B, N, d = h.numel(), neg.numel(), model.dim
     k = model.rel.shape[1]
     if out is None:
@@ -274,6 +278,14 @@ def loss_bwd(model: Model, loss: str, h, r, t, neg, gamma: float = 0.0, adv_temp
     if draw is not None:
         assert neg.is_cuda and neg.dtype == torch.int32 and neg.is_contiguous()
         dr = KgeNegDrawT(draw[0], draw[1], _counter(draw[5]) if len(draw) > 5 else None, draw[2], 0, draw[3], draw[4])
+        if plans is not None:
+            arr = _plan_array(plans)
+            _check(load().kge_loss_bwd_sampled_planned(model.ref, C.byref(cfg), _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B,
+                                                       C.byref(dr), _ptr(neg), N, _ptr(out["loss"]), _ptr(out["g_ent"]),
+                                                       _ptr(out["g_ent_idx"]), _ptr(out["g_rel"]), _ptr(out["g_relw"]),
+                                                       _ptr(out["g_rel_idx"]), _ptr(buf), buf.numel(), arr, len(plans),
+                                                       _stream(stream)), "kge_loss_bwd_sampled_planned")
+            return out
         _check(load().kge_loss_bwd_sampled(model.ref, C.byref(cfg), _ptr(_i32(h)), _ptr(_i32(r)), _ptr(_i32(t)), B,
                                            C.byref(dr), _ptr(neg), N, _ptr(out["loss"]), _ptr(out["g_ent"]),
                                            _ptr(out["g_ent_idx"]), _ptr(out["g_rel"]), _ptr(out["g_relw"]),
@@ -346,12 +358,16 @@ def sparse_adam_apply(param, shadow, m, v, grads, ws: Workspace, lr: float, beta
 
 def sparse_adam_plan_tables(plans, stream=None):
     """kge_sparse_adam_plan_tables: plans = [(n_rows, dim, idx, ws), ...]; the sorts of up to 32,768 ids share one launch."""
+    _check(load().kge_sparse_adam_plan_tables(_plan_array(plans), len(plans), _stream(stream)), "kge_sparse_adam_plan_tables")
+
+
+def _plan_array(plans):
     arr = (KgeAdamPlanT * len(plans))()
     for a, (n_rows, dim, idx, ws) in zip(arr, plans):
         M = idx.numel()
         buf = ws.get(workspace_bytes(OP_SPARSE_ADAM, None, M, dim))
         a.n_rows, a.dim, a.idx, a.M, a.ws, a.ws_bytes = n_rows, dim, _ptr(_i32(idx)), M, _ptr(buf), buf.numel()
-    _check(load().kge_sparse_adam_plan_tables(arr, len(plans), _stream(stream)), "kge_sparse_adam_plan_tables")
+    return arr
 
 
 def sparse_adam_apply_tables(tables, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, step: int = 1,

@@ -12,7 +12,7 @@ int kge_run_sparse_adam_plan(int64_t n_rows, const int32_t *idx, int64_t M, void
 int kge_run_sparse_adam_apply(float *param, void *shadow, float *m, float *v, int64_t n_rows, int dim, int64_t ld,
                               const float *grads, int64_t M, const kge_adam_cfg_t &cfg, void *ws, hipStream_t st);
 int kge_run_sparse_adam_apply_tables(const kge_adam_table_t *tb, int n, const kge_adam_cfg_t &cfg, hipStream_t st);
-int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st);
+int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st, const KgeRowFinishQArgs *rf = nullptr);
 int kge_run_topk(const kge_model_t &model, const int32_t *h, const int32_t *r, int64_t Q, int64_t lo, int64_t hi,
                  int K, int32_t *out_idx, float *out_score, const int32_t *true_t, int64_t *out_rank, void *ws,
                  size_t ws_bytes, hipStream_t st);
@@ -404,7 +404,7 @@ int kge_score(const kge_model_t *model, const int32_t *h, const int32_t *r, cons
 static int loss_bwd_impl(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
                          const int32_t *t, int64_t B, const int32_t *neg, const KgeNegGen *gen, int64_t N, float *loss_out,
                          float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw, int32_t *g_rel_idx, void *ws,
-                         size_t ws_bytes, void *hip_stream) {
+                         size_t ws_bytes, void *hip_stream, const kge_adam_plan_t *plans = nullptr, int n_plans = 0) {
     if (gen) neg = gen->out;
     int rc = validate_model(model);
     if (rc != KGE_OK) return rc;
@@ -471,7 +471,15 @@ static int loss_bwd_impl(const kge_model_t *model, const kge_loss_cfg_t *cfg, co
         if (keep_weights) { a.pstore = b.pstore; a.ps_nsplit = g.nsplit_q; a.ps_rounds = g.tps_q / 2; a.part_bf16 = 1; }
         if ((rc = launch_block(g, KGE_MODE_FWD, cfg->loss, a, g.own_tiles_b, g.nsplit_q, g.dsplit_q, st)) != KGE_OK) return rc;
     }
-    if (keep_weights)
+    // (the plans of the sparse update that the caller asked for: their sorts need the ids alone and share the launch of the
+    // rows' finish where there is one of that kind; otherwise they follow at the end)
+    bool planned = false;
+    if (keep_weights && plans) {
+        const KgeRowFinishQArgs rf{b.stat_part, g.nsplit_q, g.Bp, g.B, g.N, cfg->loss, cfg->gamma, c_corr, scale, b.pos, b.rowinfo,
+                                   b.lossb, b.gpos, (const uint16_t *)b.Q, (uint16_t *)b.Qs};
+        rc = kge_run_sparse_adam_plan_tables(plans, n_plans, st, &rf);
+        planned = true;
+    } else if (keep_weights)
         rc = kge_run_rowfinish_qscale(b.stat_part, g.nsplit_q, g.Bp, g.B, g.N, cfg->loss, cfg->gamma, c_corr, scale, b.pos, b.rowinfo,
                                       b.lossb, b.gpos, b.Q, b.Qs, st);
     else
@@ -519,6 +527,7 @@ static int loss_bwd_impl(const kge_model_t *model, const kge_loss_cfg_t *cfg, co
         }
     }
     if (cfg->reg_l3 > 0.f && B + N > 0) rc = kge_run_reg_add(b.regv, g.B, g.Bp, g.N, cfg->reg_l3, loss_out, st);
+    if (rc == KGE_OK && plans && !planned) rc = kge_run_sparse_adam_plan_tables(plans, n_plans, st);
     return rc;
 }
 
@@ -530,17 +539,26 @@ int kge_loss_bwd(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int3
                          ws_bytes, hip_stream);
 }
 
-int kge_loss_bwd_sampled(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
-                         const int32_t *t, int64_t B, const kge_neg_draw_t *draw, int32_t *neg_out, int64_t N,
-                         float *loss_out, float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw,
-                         int32_t *g_rel_idx, void *ws, size_t ws_bytes, void *hip_stream) {
+static int loss_bwd_sampled_impl(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
+                                 const int32_t *t, int64_t B, const kge_neg_draw_t *draw, int32_t *neg_out, int64_t N,
+                                 float *loss_out, float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw,
+                                 int32_t *g_rel_idx, void *ws, size_t ws_bytes, const kge_adam_plan_t *plans, int32_t n_tables,
+                                 void *hip_stream) {
     if (!draw || draw->hi <= draw->lo || draw->lo < 0 || draw->hi > (1ll << 31) || draw->step >= (1ull << 32) || draw->reserved != 0)
         return KGE_E_INVALID_ARG;
     if (N > 0 && !neg_out) return KGE_E_INVALID_ARG;
     const KgeNegGen gen{neg_out, (uint32_t)draw->seed, (uint32_t)(draw->seed >> 32), (uint32_t)draw->step, draw->stream_tag,
                         draw->step_counter, draw->lo, (uint64_t)(draw->hi - draw->lo)};
     return loss_bwd_impl(model, cfg, h, r, t, B, nullptr, &gen, N, loss_out, g_ent, g_ent_idx, g_rel, g_relw, g_rel_idx, ws,
-                         ws_bytes, hip_stream);
+                         ws_bytes, hip_stream, plans, n_tables);
+}
+
+int kge_loss_bwd_sampled(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
+                         const int32_t *t, int64_t B, const kge_neg_draw_t *draw, int32_t *neg_out, int64_t N,
+                         float *loss_out, float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw,
+                         int32_t *g_rel_idx, void *ws, size_t ws_bytes, void *hip_stream) {
+    return loss_bwd_sampled_impl(model, cfg, h, r, t, B, draw, neg_out, N, loss_out, g_ent, g_ent_idx, g_rel, g_relw, g_rel_idx,
+                                 ws, ws_bytes, nullptr, 0, hip_stream);
 }
 
 // argument checks shared by kge_sparse_adam and kge_sparse_adam_static; KGE_OK with M == 0 means "nothing to do"
@@ -615,7 +633,7 @@ int kge_sparse_adam_apply(float *param_f32, void *param_bf16, float *m, float *v
                                      (hipStream_t)hip_stream);
 }
 
-int kge_sparse_adam_plan_tables(const kge_adam_plan_t *plans, int32_t n_tables, void *hip_stream) {
+static int validate_plans(const kge_adam_plan_t *plans, int32_t n_tables) {
     if (!plans || n_tables < 1 || n_tables > 4) return KGE_E_INVALID_ARG;
     for (int k = 0; k < n_tables; ++k) {
         const kge_adam_plan_t &t = plans[k];
@@ -629,7 +647,26 @@ int kge_sparse_adam_plan_tables(const kge_adam_plan_t *plans, int32_t n_tables, 
         ws = align_ws(ws, bytes);
         if (kge_sparse_adam_ws(t.M, t.dim) - 256 > bytes) return KGE_E_WORKSPACE_TOO_SMALL;
     }
+    return KGE_OK;
+}
+
+int kge_sparse_adam_plan_tables(const kge_adam_plan_t *plans, int32_t n_tables, void *hip_stream) {
+    const int rc = validate_plans(plans, n_tables);
+    if (rc != KGE_OK) return rc;
     return kge_run_sparse_adam_plan_tables(plans, n_tables, (hipStream_t)hip_stream);
+}
+
+int kge_loss_bwd_sampled_planned(const kge_model_t *model, const kge_loss_cfg_t *cfg, const int32_t *h, const int32_t *r,
+                                 const int32_t *t, int64_t B, const kge_neg_draw_t *draw, int32_t *neg_out, int64_t N,
+                                 float *loss_out, float *g_ent, int32_t *g_ent_idx, float *g_rel, float *g_relw,
+                                 int32_t *g_rel_idx, void *ws, size_t ws_bytes, const kge_adam_plan_t *plans,
+                                 int32_t n_tables, void *hip_stream) {
+    const int rc = validate_plans(plans, n_tables);
+    if (rc != KGE_OK) return rc;
+    for (int k = 0; k < n_tables; ++k)                      // (the sorts may run before these arrays are written)
+        if (plans[k].M > 0 && (plans[k].idx == g_ent_idx || plans[k].idx == g_rel_idx)) return KGE_E_INVALID_ARG;
+    return loss_bwd_sampled_impl(model, cfg, h, r, t, B, draw, neg_out, N, loss_out, g_ent, g_ent_idx, g_rel, g_relw, g_rel_idx,
+                                 ws, ws_bytes, plans, n_tables, hip_stream);
 }
 
 int kge_sparse_adam_apply_tables(const kge_adam_table_t *tables, int32_t n_tables, const kge_adam_cfg_t *cfg, void *hip_stream) {

@@ -109,6 +109,12 @@ struct KgeBlockArgs {
     int32_t part_bf16;
 };
 
+// arguments of the rows' finish that also scales the query rows per forward split (row_finish.hpp)
+struct KgeRowFinishQArgs {
+    const float4 *stat_part; int nsplit, Bp, B, N, loss; float gamma, c_corr, scale; const float *pos;
+    KgeRowInfo *rowinfo; float *lossb, *gpos; const uint16_t *Q; uint16_t *Qs;
+};
+
 bool kge_fwd_pp_applies(bool bf16, int rb, bool transh, int dsplit);
 bool kge_gradt_pp_applies(bool bf16, int rb, bool transh, int dsplit);
 // the kernel of block_sym.hip serves both passes of the same configurations; it walks the stream in tiles of 64 rows

@@ -4,6 +4,7 @@
 //   3. one Adam step on each distinct row, fp32 master weights + moments, optional bf16 shadow
 // Only rows that occur in idx are read or written (arXiv 2211.12281, Section 1: sparse access).
 #include "kge_internal.h"
+#include "row_finish.hpp"
 #include <math.h>
 #include <mutex>
 
@@ -322,7 +323,7 @@ __device__ __forceinline__ bool small_pass_trivial(const uint32_t *sk, const uin
     return true;
 }
 
-__global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgpu_waves_per_eu(8, 8))) void sort_small_kernel(const SmallSorts T) {
+__device__ __forceinline__ void sort_small_body(const SmallSorts &T, const int wg) {
     __shared__ uint32_t s_cnt[16 * SMALL_PT + SMALL_PT];
     __shared__ uint32_t s_rc[SMALL_ROUNDS * (SMALL_NT / 64)];   // own ids of every (round, wave), then their offsets
     __shared__ __attribute__((aligned(16))) uint32_t s_key[2][SMALL_CAP];
@@ -336,7 +337,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgp
     for (int k = 0; k < SMALL_TABLES - 1; ++k) {           // (the tables of a launch are packed from slot 0 on)
         const int nbk = 1 << T.t[k].lb;
         if (!found) {
-            if ((int)blockIdx.x < first + nbk) { ti = k; found = true; }
+            if (wg < first + nbk) { ti = k; found = true; }
             else first += nbk;
         }
     }
@@ -347,7 +348,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgp
     const int passes = S.bits > lb ? (S.bits - lb + 3) / 4 : 0;
     const uint32_t lmask = (1u << lb) - 1u;
     uint32_t *ka = S.ka, *kb = S.kb, *pa = S.pa, *pb = S.pb;
-    const int w = (int)blockIdx.x - first;
+    const int w = wg - first;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rounds = (M + 4 * SMALL_NT - 1) / (4 * SMALL_NT);
     const bool vec = ((uintptr_t)idx & 15) == 0;
@@ -526,6 +527,18 @@ __global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgp
             }
         }
     }
+}
+
+__global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgpu_waves_per_eu(8, 8))) void sort_small_kernel(const SmallSorts T) {
+    sort_small_body(T, (int)blockIdx.x);
+}
+// The sorts of a training step's row ids need the ids alone, the finish of the rows' losses (row_finish.hpp) the forward
+// pass alone: they share a launch between the two block kernels, the sorts' workgroups first (two fit a compute unit, and a
+// workgroup of the finish, sixteen rows, beside one of them), so that the few microseconds of the finish pass under the sorts.
+__global__ __attribute__((amdgpu_flat_work_group_size(SMALL_NT, SMALL_NT), amdgpu_waves_per_eu(8, 8)))
+void sort_small_rowfinish_kernel(const SmallSorts T, const int sort_blocks, const KgeRowFinishQArgs q) {
+    if ((int)blockIdx.x < sort_blocks) sort_small_body(T, (int)blockIdx.x);
+    else kge_rowfinish_qscale_body((int)blockIdx.x - sort_blocks, q);
 }
 
 // Runs of equal rows ("segments") in the sorted order are reduced in two ways:
@@ -771,7 +784,8 @@ static void sort_result(int64_t M, int64_t key_range, void *ws, const uint32_t *
 }
 
 // Several tables: those of up to SMALL_MAX ids share one launch (256 or 32 workgroups each), longer ones take the radix passes.
-int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st) {
+// rf: the finish of the rows' losses joins the launch of the small sorts (or gets a launch of the same kernel to itself).
+int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_t st, const KgeRowFinishQArgs *rf) {
     KgeProfScope prof(KGE_PROF_SORT, st);
     SmallSorts T = {};
     int small = 0, nwg = 0;
@@ -796,8 +810,12 @@ int kge_run_sparse_adam_plan_tables(const kge_adam_plan_t *pl, int n, hipStream_
         for (int k = 0; k < small; ++k) ms[k] = T.t[k].M;
         small_parts(ms, small, lb);
         for (int k = 0; k < small; ++k) { T.t[k].lb = lb[k]; nwg += 1 << lb[k]; }
-        hipLaunchKernelGGL(sort_small_kernel, dim3(nwg), dim3(SMALL_NT), 0, st, T);
+        if (!rf) hipLaunchKernelGGL(sort_small_kernel, dim3(nwg), dim3(SMALL_NT), 0, st, T);
     }
+    if (rf && rf->Bp > 0) {
+        const int rows_wg = SMALL_NT / 64;
+        hipLaunchKernelGGL(sort_small_rowfinish_kernel, dim3(nwg + (rf->Bp + rows_wg - 1) / rows_wg), dim3(SMALL_NT), 0, st, T, nwg, *rf);
+    } else if (rf && small > 0) hipLaunchKernelGGL(sort_small_kernel, dim3(nwg), dim3(SMALL_NT), 0, st, T);
     return kge_launch_status();
 }
 

@@ -269,3 +269,68 @@ def test_negatives_drawn_inside_the_call_argument_checks():
                  (ks.BASE_SEED, 0, ks.TAG_NEG, 0, (1 << 31) + 1)):
         with pytest.raises(kge.KgeError):
             kge.loss_bwd(model, "sampled_softmax", h, r, t, neg, draw=draw, n_ent_for_c=500)
+
+
+@pytest.mark.parametrize("scorer,dim,bf16,loss,B,N", [
+    ("complex", 256, True, "sampled_softmax", 700, 3000),    # the sorts share the launch of the rows' finish
+    ("distmult", 256, True, "sampled_softmax", 4096, 16384), # the same at the size of a full step (288 + 256 workgroups)
+    ("distmult", 256, True, "logsigmoid", 300, 900),         # every other configuration: the sorts follow the call's work
+    ("complex", 64, False, "sampled_softmax", 200, 333),
+    ("transh", 128, False, "logsigmoid", 64, 97),
+    ("complex", 256, True, "sampled_softmax", 40, 0),        # no negatives
+    ("distmult", 256, True, "sampled_softmax", 0, 50),       # no queries: the relations' plan is empty
+])
+def test_planned_call_equals_the_sampled_call_followed_by_the_plans(scorer, dim, bf16, loss, B, N):
+    """kge_loss_bwd_sampled_planned against kge_loss_bwd_sampled + kge_sparse_adam_plan_tables: every output bit for bit,
+    and the plans through the updates that read them (entity rows by [h | t | drawn negatives], relation rows by r)."""
+    import kge_synth as ks
+    import paper_2211_12281_amd as kge
+    n_ent, n_rel = 4000, 12
+    G = make_case(scorer, n_ent, n_rel, dim, max(B, 1), max(N, 1), bf16, amp=0.3, zipf=True)
+    model = gpu_model(scorer, G, bf16)
+    h, r, t = dev_idx(G["h"][:B]), dev_idx(G["r"][:B]), dev_idx(G["t"][:B])
+    kw = _kw(scorer, loss, n_ent)
+    draw = (ks.BASE_SEED, 7, ks.TAG_NEG, 0, n_ent)
+    k_rel = G["rel"].shape[1]
+    res = {}
+    for tag in ("two_calls", "planned"):
+        ids = torch.full((2 * B + N,), -1, dtype=torch.int32, device="cuda")
+        ids[:B] = h; ids[B:2 * B] = t
+        ws_e, ws_r = kge.Workspace(), kge.Workspace()
+        for w, M, d in ((ws_e, 2 * B + N, dim), (ws_r, B, k_rel)):
+            w.get(kge.workspace_bytes(kge.binding.OP_SPARSE_ADAM, None, max(1, M), d)).zero_()
+        plans = [(n_ent, dim, ids, ws_e), (n_rel, k_rel, r, ws_r)]
+        if tag == "planned":
+            out = kge.loss_bwd(model, loss, h, r, t, ids[2 * B:], draw=draw, plans=plans, **kw)
+        else:
+            out = kge.loss_bwd(model, loss, h, r, t, ids[2 * B:], draw=draw, **kw)
+            kge.sparse_adam_plan_tables(plans)
+        out = {k: v.clone() for k, v in out.items() if v is not None}
+        g = torch.Generator(device="cpu").manual_seed(5)
+        te = torch.randn((n_ent, dim), generator=g).cuda(); tr = torch.randn((n_rel, k_rel), generator=g).cuda()
+        st = [te, torch.zeros_like(te), torch.zeros_like(te), tr, torch.zeros_like(tr), torch.zeros_like(tr)]
+        kge.sparse_adam_apply_tables([(st[0], None, st[1], st[2], out["g_ent"], ws_e), (st[3], None, st[4], st[5], out["g_rel"], ws_r)],
+                                     1e-2, step=2)
+        torch.cuda.synchronize()
+        res[tag] = (out, ids.clone(), st)
+    a, b = res["two_calls"], res["planned"]
+    assert torch.equal(a[1], b[1])
+    for k in a[0]:
+        assert torch.equal(a[0][k], b[0][k]), k
+    for x, y in zip(a[2], b[2]):
+        assert torch.equal(x, y)
+    if B > 0 and N > 0:                                    # (no block: zero gradients, nothing moves)
+        assert not torch.equal(a[2][0], torch.randn((n_ent, dim), generator=torch.Generator(device="cpu").manual_seed(5)).cuda())
+
+
+def test_planned_call_rejects_the_id_arrays_it_writes_last():
+    import kge_synth as ks
+    import paper_2211_12281_amd as kge
+    G = make_case("complex", 500, 4, 256, 8, 8, True)
+    model = gpu_model("complex", G, True)
+    h, r, t = dev_idx(G["h"]), dev_idx(G["r"]), dev_idx(G["t"])
+    neg = torch.zeros(8, dtype=torch.int32, device="cuda")
+    out = kge.loss_bwd(model, "sampled_softmax", h, r, t, neg, draw=(ks.BASE_SEED, 0, ks.TAG_NEG, 0, 500), n_ent_for_c=500)
+    with pytest.raises(kge.KgeError):
+        kge.loss_bwd(model, "sampled_softmax", h, r, t, neg, draw=(ks.BASE_SEED, 0, ks.TAG_NEG, 0, 500), n_ent_for_c=500, out=out,
+                     plans=[(500, 256, out["g_ent_idx"], kge.Workspace())])
