@@ -29,7 +29,7 @@ struct TopkArgs {
     int32_t valid_bytes;                // d * sizeof(element)
     int64_t ncand;
     int64_t cand_lo;                    // entity id of candidate 0
-    const float *tn;                    // [ncand rounded up to a tile] squared norms of the candidates
+    const float *tn;                    // [ncand rounded up to a tile] MINUS the squared norms of the candidates
     const float *thr;                   // [Qp] current threshold (local value units)
     const float *vt;                    // [Qp] value of the held-out tail (local units), +inf when absent
     const int32_t *true_t;              // [Q] entity ids, or nullptr
@@ -107,13 +107,11 @@ void topk_scan_kernel(const TopkArgs a) {
     uint4 own[OB][KS];
     float thr[NQ], vt[NQ];
     int qid[NQ], myc[NQ];
-    uint2 *segp[NQ];
     uint32_t above[NQ];
 #pragma unroll
     for (int ob = 0; ob < NQ; ++ob) {
         qid[ob] = own_base + (wave * NQ + ob) * 32 + lr;
         myc[ob] = 0;
-        segp[ob] = a.seg + (((size_t)qid[ob] * a.nseg + split) * 2 + g) * TK_HALF;
         const char *p = (const char *)a.Qmat + (size_t)qid[ob] * RB + g * 16;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) own[ob][ks] = *(const uint4 *)(p + ks * 32);
@@ -130,43 +128,40 @@ void topk_scan_kernel(const TopkArgs a) {
     }
 
     // ---- loader geometry of this lane: instruction jj covers LDS bytes [(wave*IPW+jj) KB, +1 KB) ----
-    int ld_row[IPW], ld_col[IPW];
+    // A copy takes a wave-uniform base (the tile's first row, scalar registers) and ONE 32-bit offset per lane that does not
+    // change from tile to tile (row in the tile x stride + source chunk), and its LDS address is scalar arithmetic on the
+    // wave's number: no vector instruction per copy in the loop.  Rows shorter than RB (padding columns, which read the 16
+    // zero bytes) and the table's last, ragged tile take per-lane 64-bit addresses, computed where they are needed.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto ld_row_of = [&](int jj) { return ((wave_u * IPW + jj) * 1024 + lane * 16) / RB; };
+    auto ld_col_of = [&](int jj) {
+        const int byte = (wave_u * IPW + jj) * 1024 + lane * 16, r = byte / RB, pos = (byte % RB) / 16;
+        return (pos ^ tk_swz(r)) * 16;                  // source chunk that belongs at this LDS position
+    };
+    uint32_t ld_off[IPW];
 #pragma unroll
-    for (int jj = 0; jj < IPW; ++jj) {
-        const int byte = (wave * IPW + jj) * 1024 + lane * 16;
-        const int r = byte / RB, pos = (byte % RB) / 16;
-        ld_row[jj] = r;
-        ld_col[jj] = (pos ^ tk_swz(r)) * 16;            // source chunk that belongs at this LDS position
-    }
-    // source of copy jj for tile 0 and its advance per tile (lanes of the padding columns read the 16 zero bytes, advance 0):
-    // one multiply-add per copy in the loop; only the table's last, ragged tile takes the clamped path
-    const char *src0[IPW];
-    uint32_t src_step[IPW];
-#pragma unroll
-    for (int jj = 0; jj < IPW; ++jj) {
-        const bool real = ld_col[jj] < a.valid_bytes;
-        src0[jj] = real ? a.ent + (int64_t)ld_row[jj] * a.ent_stride + ld_col[jj] : (const char *)a.zeros;
-        src_step[jj] = real ? (uint32_t)(TK_ST * a.ent_stride) : 0u;
-    }
+    for (int jj = 0; jj < IPW; ++jj) ld_off[jj] = (uint32_t)(ld_row_of(jj) * a.ent_stride + ld_col_of(jj));
+    const bool unpadded = a.valid_bytes == RB && a.ent_stride < (1ll << 26);     // (uniform; 32 rows x stride fits the offset)
     auto issue = [&](int64_t tile, int slot) {
         tile = tile < t1 ? tile : t1 - 1;               // past the end: a harmless repeat keeps vmcnt uniform
         const int stage = slot % NSTAGE;
-        if (tile * TK_ST + TK_ST <= a.ncand) {
+        const uint32_t lbase = lds0 + stage * TILE_BYTES + wave_u * (IPW * 1024);
+        if (unpadded && tile * TK_ST + TK_ST <= a.ncand) {
+            const char *tb = a.ent + tile * TK_ST * a.ent_stride;
 #pragma unroll
             for (int jj = 0; jj < IPW; ++jj)
-                async_copy16(src0[jj] + (uint64_t)tile * src_step[jj],
-                             __builtin_amdgcn_readfirstlane(lds0 + stage * TILE_BYTES + (wave * IPW + jj) * 1024));
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lbase + jj * 1024), "v"(ld_off[jj]), "s"(tb) : "memory");
         } else {
 #pragma unroll
             for (int jj = 0; jj < IPW; ++jj) {
-                int64_t cand = tile * TK_ST + ld_row[jj];
+                int64_t cand = tile * TK_ST + ld_row_of(jj);
                 cand = cand < a.ncand ? cand : a.ncand - 1; // rows past the end are masked in the epilogue
-                const char *gp = ld_col[jj] < a.valid_bytes ? a.ent + cand * a.ent_stride + ld_col[jj] : (const char *)a.zeros;
-                async_copy16(gp, __builtin_amdgcn_readfirstlane(lds0 + stage * TILE_BYTES + (wave * IPW + jj) * 1024));
+                const int col = ld_col_of(jj);
+                const char *gp = col < a.valid_bytes ? a.ent + cand * a.ent_stride + col : (const char *)a.zeros;
+                async_copy16(gp, lbase + jj * 1024);
             }
         }
-        async_copy4(a.tn + tile * TK_ST + lr,
-                    __builtin_amdgcn_readfirstlane(lds0 + NSTAGE * TILE_BYTES + ((slot % SIDE_SLOTS) * 4 + wave) * 256));
+        async_copy4(a.tn + tile * TK_ST + lr, lds0 + NSTAGE * TILE_BYTES + ((slot % SIDE_SLOTS) * 4 + wave_u) * 256);
     };
     // ---- A-fragment addresses: chunk (2 ks + g) of row lr sits at position chunk ^ tk_swz(lr) ----------
     int frag_off[8];
@@ -174,20 +169,26 @@ void topk_scan_kernel(const TopkArgs a) {
     for (int b = 0; b < 8; ++b) frag_off[b] = lr * RB + 16 * ((2 * b + g) ^ tk_swz(lr));
     auto mma_tile = [&](int slot, kge_f32x16 (&acc)[OB]) {
         const char *base = lds + (slot % NSTAGE) * TILE_BYTES;
-        uint4 av[KS];
+        // Rows of 512 bytes: the fragment of step ks + AH is requested before the MFMAs of step ks are issued, and the
+        // scheduler is held to that order (left to itself the compiler reads each fragment right before its two MFMAs and
+        // waits for it).  The kernels of 1,024-byte rows have no registers for fragments in flight: held to this order they
+        // spill operands inside the loop, so they keep the compiler's.
+        constexpr int AH = RB == 512 ? (TH ? 2 : 3) : 0;
+        uint4 av[AH > 0 ? AH + 1 : KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) av[ks] = *(const uint4 *)(base + frag_off[ks & 7] + 256 * (ks >> 3));
+        for (int ks = 0; ks < (AH > 0 ? AH : KS); ++ks) av[ks] = *(const uint4 *)(base + frag_off[ks & 7] + 256 * (ks >> 3));
         if constexpr (KIND == KGE_KIND_DIST) {
             // TransE: the accumulators start at -|t|^2 of their candidate row and the queries are stored
             // doubled, so the contraction itself yields 2 q.t - |t|^2
-            const char *tside = side_base + ((slot % SIDE_SLOTS) * 4 + wave) * 256;
+            const char *tside = side_base + ((slot % SIDE_SLOTS) * 4 + wave_u) * 256;
             // (rows 8 j + 4 g .. + 3 of the tile are registers 4 j .. 4 j + 3: one 16-byte read per j)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                // (the side array holds -|t|^2: the accumulators are loaded, not computed)
                 const kge_f32x4 tn4 = *(const kge_f32x4 *)(tside + (8 * j + 4 * g) * 4);
 #pragma unroll
                 for (int ob = 0; ob < NQ; ++ob)
-                    for (int u = 0; u < 4; ++u) acc[ob][4 * j + u] = -tn4[u];
+                    for (int u = 0; u < 4; ++u) acc[ob][4 * j + u] = tn4[u];
             }
             if constexpr (TH) for (int i = 0; i < 16; ++i) acc[1][i] = 0.f;
         } else {
@@ -196,8 +197,16 @@ void topk_scan_kernel(const TopkArgs a) {
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
+            if constexpr (AH == 0) {
 #pragma unroll
-            for (int ob = 0; ob < OB; ++ob) acc[ob] = kge_mma16<BF16>(acc[ob], av[ks], own[ob][ks]);
+                for (int ob = 0; ob < OB; ++ob) acc[ob] = kge_mma16<BF16>(acc[ob], av[ks], own[ob][ks]);
+            } else {
+                if (ks + AH < KS) av[(ks + AH) % (AH + 1)] = *(const uint4 *)(base + frag_off[(ks + AH) & 7] + 256 * ((ks + AH) >> 3));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ob = 0; ob < OB; ++ob) acc[ob] = kge_mma16<BF16>(acc[ob], av[ks % (AH + 1)], own[ob][ks]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
 
@@ -254,7 +263,9 @@ void topk_scan_kernel(const TopkArgs a) {
                 for (int i = 0; i < 16; ++i) {
                     if (vv[ob][i] > thr[ob]) {
                         const int64_t cand = tile * TK_ST + 8 * (i >> 2) + 4 * g + (i & 3);
-                        if (myc[ob] < TK_HALF) segp[ob][myc[ob]] = make_uint2(__float_as_uint(vv[ob][i]), (uint32_t)cand);
+                        // (the area's address is formed here, on the rarely taken path, instead of living in registers)
+                        if (myc[ob] < TK_HALF)
+                            a.seg[(((size_t)qid[ob] * a.nseg + split) * 2 + g) * TK_HALF + myc[ob]] = make_uint2(__float_as_uint(vv[ob][i]), (uint32_t)cand);
                         ++myc[ob];                      // counts past TK_HALF mark the overflow for the compaction
                     }
                 }
@@ -800,7 +811,8 @@ __global__ void topk_prep_th_kernel(KgeModelDev m, const int32_t *h, const int32
     }
 }
 
-// squared norms of the candidate rows and their maximum, one atomic per wave.  Fast path (rows of 16-byte
+// squared norms of the candidate rows (stored negated: the scan starts its accumulators from them) and their maximum, one
+// atomic per wave.  Fast path (rows of 16-byte
 // aligned power-of-two length): a lane reads 16 bytes, a wave 64 / LPR rows per step, four steps in flight.
 template <bool BF16>
 __global__ void topk_tnorm_kernel(const char *ent, int64_t stride, int d, int64_t ncand, int64_t npad, float *tn,
@@ -834,7 +846,7 @@ __global__ void topk_tnorm_kernel(const char *ent, int64_t stride, int d, int64_
                 }
                 for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o);
                 const int64_t c = c0 + u * rpw + sub;
-                if (li == 0 && c < npad) tn[c] = s;
+                if (li == 0 && c < npad) tn[c] = -s;
                 mx = fmaxf(mx, s);
             }
         }
@@ -843,7 +855,7 @@ __global__ void topk_tnorm_kernel(const char *ent, int64_t stride, int d, int64_
             float s = 0.f;
             if (c < ncand) for (int j = lane; j < d; j += 64) { const float v = El<BF16>::ld(ent + c * stride, j); s += v * v; }
             s = kge_wave_sum(s);
-            if (lane == 0) tn[c] = s;
+            if (lane == 0) tn[c] = -s;
             mx = fmaxf(mx, s);
         }
     }
