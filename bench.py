@@ -759,7 +759,7 @@ def main():
         line["hbm_kernels"] = hbm
     if isinstance(wl, TrainWorkload):
         line["enqueue"] = ("HIP graph replay, one graph per pre-drawn batch; every 4th step call by call with the HIP-event bracket"
-                           if graphed else "call by call, one stream, 8 launches per step")
+                           if graphed else "call by call, one stream (c3: 7 launches per step in two library calls)")
     line.update(wl.extra(ms))
     if enc_roof:
         line["encoder_roofline"] = enc_roof
