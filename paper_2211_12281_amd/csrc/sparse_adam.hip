@@ -499,7 +499,13 @@ __device__ __forceinline__ void sort_small_body(const SmallSorts &T, const int w
             if (tid < nc) {
                 const uint32_t key = s_key[1][tid];
                 int rank = 0;
-                for (int j = 0; j < nc; ++j) { const uint32_t kj = s_key[1][j]; rank += kj < key || (kj == key && j < tid); }
+                const int nc4 = nc & ~3;
+                for (int j = 0; j < nc4; j += 4) {
+                    const uint4 k4 = *(const uint4 *)&s_key[1][j];          // (the same address in every lane: a broadcast)
+                    rank += (k4.x < key || (k4.x == key && j < tid)) + (k4.y < key || (k4.y == key && j + 1 < tid)) +
+                            (k4.z < key || (k4.z == key && j + 2 < tid)) + (k4.w < key || (k4.w == key && j + 3 < tid));
+                }
+                for (int j = nc4; j < nc; ++j) { const uint32_t kj = s_key[1][j]; rank += kj < key || (kj == key && j < tid); }
                 const int to = base + rank + (key > hot ? n_hot : 0);
                 ka[to] = key; pa[to] = s_pos[1][tid];
             }
